@@ -1,0 +1,159 @@
+/*
+ * csr.h - C ABI of the MI355X (gfx950) implementation of the CSR sparse-representation
+ * hot path (arXiv 2412.11741, "CSR: Achieving 1 Bit Key-Value Cache via Sparse
+ * Representation").
+ *
+ * Two operations:
+ *   csr_encode       greedy Matching Pursuit of dense per-head key/value vectors into s
+ *                    (atom index, coefficient) pairs against a per-head dictionary
+ *                    (Section "Sparse representation", Eq.2-4; Section "KV Decomposition and
+ *                    Sparse Storage").
+ *   csr_decode_attn  attention of one query token per sequence over the cached codes.  It
+ *                    returns what ordinary softmax attention over the de-sparsified cache
+ *                    X~ = D r (Eq.12, Section "De-Sparse to restore") returns, but never
+ *                    builds X~: q.(D r) = (D^T q).r and sum_t p_t D r_t = D (sum_t p_t r_t).
+ *
+ * General rules
+ *   - Every data pointer is DEVICE memory owned by the caller.  The library allocates
+ *     nothing, frees nothing and keeps no pointer after a call returns.
+ *   - Descriptors are plain host structs, read during the call only.
+ *   - Calls enqueue work on the given HIP stream (a hipStream_t passed as void*; NULL is the
+ *     default stream) and return without waiting for it.
+ *   - No exception or abort crosses this boundary.  Argument problems are found on the host
+ *     before anything is launched and reported as a status; csr_last_error() gives a message.
+ *   - A dictionary is atom-major: D[h][n][k], n < N atoms, k < d contiguous.  Atoms must be
+ *     unit L2 norm (up to storage rounding); this is not checked and nothing is renormalised.
+ *   - Codes are two separate streams, idx[..][T][s] and coef[..][T][s], pair g of a vector being
+ *     the atom and signed projection picked at iteration g.  The same atom may appear twice in
+ *     one code; its coefficients then add (D r is the sum over the list).
+ *   - 16-bit indices are unsigned (N <= 65536).
+ */
+#ifndef CSR_H
+#define CSR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CSR_VERSION 100 /* major*10000 + minor*100 + patch */
+
+typedef enum {
+    CSR_OK = 0,
+    CSR_ERR_INVALID_ARG = 1, /* null pointer, negative size, inconsistent descriptor      */
+    CSR_ERR_UNSUPPORTED = 2, /* well-formed request this build has no kernel for           */
+    CSR_ERR_WORKSPACE = 3,   /* workspace missing, misaligned or smaller than the query says */
+    CSR_ERR_DEVICE = 4       /* the HIP runtime reported an error while enqueuing          */
+} csr_status;
+
+typedef enum { CSR_F32 = 0, CSR_F16 = 1 } csr_dtype; /* vectors, dictionaries, coefficients */
+typedef enum { CSR_I32 = 0, CSR_I16 = 1 } csr_itype; /* atom indices; I16 is unsigned        */
+
+/* Which encoder kernel runs.  AUTO picks MFMA when the shape allows it, else VALU. */
+typedef enum {
+    CSR_ENCODE_AUTO = 0,
+    CSR_ENCODE_VALU = 1, /* fp32 vector-ALU correlation, any supported shape               */
+    CSR_ENCODE_MFMA = 2  /* fp16 matrix-core screening pass + exact fp32 selection          */
+} csr_encode_algo;
+
+/*
+ * Matching Pursuit encode (Eq.2-4), H independent dictionaries with T vectors each.
+ * For every vector x: R_1 = x; for g = 1..s: i_g = argmax_n |R_g . d_n| (lowest n on ties),
+ * c_g = R_g . d_{i_g} (signed), R_{g+1} = R_g - c_g d_{i_g}.  The residual is kept in fp32 and
+ * is updated with the unrounded c_g; rounding to coef_dtype happens on store only.  A zero
+ * residual emits (0, 0).
+ */
+typedef struct {
+    int32_t H;          /* dictionaries (e.g. KV heads x {K,V}); >= 0                      */
+    int64_t T;          /* vectors per dictionary; >= 0 (0 is a no-op)                     */
+    int32_t d;          /* vector length; supported: 128 (MFMA), multiples of 64 <= 256 (VALU) */
+    int32_t N;          /* atoms per dictionary, 1..65536 (I16) or 1..2^24 (I32)            */
+    int32_t s;          /* iterations = pairs per vector, 1..32                             */
+    int32_t x_dtype;    /* csr_dtype of X                                                   */
+    int32_t dict_dtype; /* csr_dtype of D; must equal x_dtype                               */
+    int32_t coef_dtype; /* csr_dtype of coef                                                */
+    int32_t idx_dtype;  /* csr_itype of idx                                                 */
+    int64_t x_stride_h; /* elements between dictionaries' vector blocks; 0 = T*d            */
+    int64_t x_stride_t; /* elements between consecutive vectors; 0 = d                      */
+    int32_t algo;       /* csr_encode_algo                                                  */
+    uint32_t flags;     /* must be 0                                                        */
+} csr_encode_desc;
+
+/* Bytes of device scratch csr_encode needs for this descriptor (may be 0); (size_t)-1 if the
+ * descriptor is invalid. */
+size_t csr_encode_workspace_bytes(const csr_encode_desc *desc);
+
+/*
+ *   X    [H][T][d]  (strides as given)   in
+ *   D    [H][N][d]                       in
+ *   idx  [H][T][s]  idx_dtype            out
+ *   coef [H][T][s]  coef_dtype           out
+ *   workspace: device memory, 256-byte aligned, >= csr_encode_workspace_bytes(); may be NULL
+ *   when that is 0.  Contents are undefined before and after.
+ */
+csr_status csr_encode(const csr_encode_desc *desc, const void *X, const void *D, void *idx,
+                      void *coef, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Decode attention on codes.  For every sequence b and query head hq (KV head h = hq / (Hq/Hkv)):
+ *   score_t = scale * sum_j coefK[b][h][t][j] * (q[b][hq] . DK[h][idxK[b][h][t][j]])
+ *   p       = softmax over the valid tokens t < len_b
+ *   out     = DV[h]^T applied to hist, hist[n] = sum_{t,j : idxV = n} p_t * coefV[b][h][t][j]
+ * which equals softmax attention over K~ = D_K r_K, V~ = D_V r_V of Eq.12.  No mask beyond the
+ * sequence length, no position embedding (the paper's Section "KV cache in attention" sets it
+ * aside).  A sequence with len_b = 0 yields zeros.  Accumulation is fp32; the V-side histogram
+ * uses LDS float atomics, so results are reproducible to rounding, not bit for bit.
+ */
+typedef struct {
+    int32_t B;          /* sequences; >= 0                                                  */
+    int32_t Hq;         /* query heads; multiple of Hkv, Hq/Hkv <= 8                        */
+    int32_t Hkv;        /* KV heads                                                         */
+    int64_t T;          /* code rows allocated per (b, h); >= 0                             */
+    int32_t d;          /* head dimension; supported: 128                                   */
+    int32_t N;          /* atoms per dictionary                                             */
+    int32_t sK, sV;     /* pairs per key / value code, 1..32                                */
+    float scale;        /* score scale; 0 means 1/sqrt(d)                                   */
+    int32_t q_dtype;    /* csr_dtype of q                                                   */
+    int32_t dict_dtype; /* csr_dtype of DK and DV                                           */
+    int32_t coef_dtype; /* csr_dtype of coefK and coefV                                     */
+    int32_t idx_dtype;  /* csr_itype of idxK and idxV                                       */
+    int32_t out_dtype;  /* csr_dtype of out                                                 */
+    uint32_t flags;     /* must be 0                                                        */
+} csr_decode_desc;
+
+/* Bytes of device scratch csr_decode_attn needs; (size_t)-1 if the descriptor is invalid. */
+size_t csr_decode_workspace_bytes(const csr_decode_desc *desc);
+
+/*
+ *   q        [B][Hq][d]        in
+ *   DK, DV   [Hkv][N][d]       in, shared by all sequences
+ *   idxK, coefK [B][Hkv][T][sK]   in;   idxV, coefV [B][Hkv][T][sV]   in
+ *   seq_lens [B] int32 device pointer, or NULL for len_b = T.  Values must lie in [0, T];
+ *            larger values are clamped to T, negative ones to 0.
+ *   out      [B][Hq][d]        out
+ *   workspace: device memory, 256-byte aligned, >= csr_decode_workspace_bytes().
+ * Indices are not range-checked on the device: an index >= N reads outside the score table.
+ */
+csr_status csr_decode_attn(const csr_decode_desc *desc, const void *q, const void *DK,
+                           const void *idxK, const void *coefK, const void *DV, const void *idxV,
+                           const void *coefV, const int32_t *seq_lens, void *out, void *workspace,
+                           size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Storage accounting of Section "Analysis for CSR": bytes kept per head vector,
+ * s * s_n * (index bytes + coefficient bytes).  Returns 0 on bad arguments.
+ */
+size_t csr_code_bytes(int32_t s, int32_t s_n, int32_t idx_dtype, int32_t coef_dtype);
+
+/* Message for the last non-OK status returned on this thread ("" if none).  Static storage. */
+const char *csr_last_error(void);
+
+/* CSR_VERSION of the built library. */
+int csr_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CSR_H */

@@ -1,0 +1,152 @@
+"""ctypes front end of the CPU oracle (oracle/csr_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's cpu_baseline leg, never by the product package.  Every array is
+converted to float64 / int32 before the call; fp16 and fp32 inputs upcast
+exactly, so the oracle sees the same input bits the GPU saw.
+
+Functions and the passages they follow:
+  mp_encode        Matching Pursuit, Eq.2-4, s iterations ("Sparse representation",
+                   "KV Decomposition and Sparse Storage")
+  reconstruct      X~ = D r, Eq.12
+  decode_attn      softmax attention of one query per sequence over K~, V~
+                   ("De-Sparse to restore", last paragraph)
+  equivalent_bits, compression_ratio, code_bytes
+                   storage accounting of "Analysis for CSR"
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        path = _build.build()
+        lib = ctypes.CDLL(path)
+        i64, i32, p = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
+        lib.csr_oracle_max_threads.restype = ctypes.c_int
+        lib.csr_oracle_mp_encode.restype = ctypes.c_int
+        lib.csr_oracle_mp_encode.argtypes = [p, p, i64, i32, i32, i32, p, p, p, p, p, i32]
+        lib.csr_oracle_reconstruct.restype = ctypes.c_int
+        lib.csr_oracle_reconstruct.argtypes = [p, p, p, i64, i32, i32, i32, p]
+        lib.csr_oracle_decode_attn.restype = ctypes.c_int
+        lib.csr_oracle_decode_attn.argtypes = [p, p, p, p, p, p, p, i32, i32, i32, i64, i32, i32,
+                                               i32, i32, ctypes.c_double, p, p, i32]
+        _lib = lib
+    return _lib
+
+
+def max_threads() -> int:
+    return int(_load().csr_oracle_max_threads())
+
+
+def _f64(a):
+    return np.ascontiguousarray(np.asarray(a), dtype=np.float64)
+
+
+def _i32(a):
+    a = np.asarray(a)
+    if a.dtype == np.int16:          # 16-bit indices are stored unsigned
+        a = a.view(np.uint16)
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def mp_encode(X, D, s, nthreads=0, diagnostics=False):
+    """Matching Pursuit of X[T, d] against atoms D[N, d] for s iterations.
+
+    Returns (idx int32 [T, s], coef float64 [T, s]) and, with diagnostics=True, a
+    third dict with best_abs / second_abs [T, s] (|correlation| of the picked atom
+    and of the runner-up) and res_norm2 [T, s+1] (squared residual norms).
+    """
+    X, D = _f64(X), _f64(D)
+    assert X.ndim == 2 and D.ndim == 2 and X.shape[1] == D.shape[1]
+    T, d = X.shape
+    N = D.shape[0]
+    idx = np.zeros((T, s), dtype=np.int32)
+    coef = np.zeros((T, s), dtype=np.float64)
+    best = second = rn = None
+    if diagnostics:
+        best = np.zeros((T, s))
+        second = np.zeros((T, s))
+        rn = np.zeros((T, s + 1))
+    rc = _load().csr_oracle_mp_encode(_ptr(X), _ptr(D), T, d, N, s, _ptr(idx), _ptr(coef),
+                                      _ptr(best), _ptr(second), _ptr(rn), nthreads)
+    if rc != 0:
+        raise RuntimeError(f"csr_oracle_mp_encode failed: {rc}")
+    if diagnostics:
+        return idx, coef, {"best_abs": best, "second_abs": second, "res_norm2": rn}
+    return idx, coef
+
+
+def mp_encode_heads(X, D, s, nthreads=0, diagnostics=False):
+    """mp_encode applied per dictionary: X[H, T, d], D[H, N, d]."""
+    outs = [mp_encode(X[h], D[h], s, nthreads, diagnostics) for h in range(len(X))]
+    idx = np.stack([o[0] for o in outs])
+    coef = np.stack([o[1] for o in outs])
+    if diagnostics:
+        diag = {k: np.stack([o[2][k] for o in outs]) for k in outs[0][2]}
+        return idx, coef, diag
+    return idx, coef
+
+
+def reconstruct(idx, coef, D):
+    """Eq.12 for one dictionary: idx/coef [T, s], D [N, d] -> X~ [T, d] (float64)."""
+    idx, coef, D = _i32(idx), _f64(coef), _f64(D)
+    T, s = idx.shape
+    N, d = D.shape
+    out = np.zeros((T, d))
+    rc = _load().csr_oracle_reconstruct(_ptr(idx), _ptr(coef), _ptr(D), T, d, N, s, _ptr(out))
+    if rc != 0:
+        raise RuntimeError(f"csr_oracle_reconstruct failed: {rc}")
+    return out
+
+
+def decode_attn(q, DK, idxK, coefK, DV, idxV, coefV, scale=None, seq_lens=None, nthreads=0):
+    """Attention of q[B, Hq, d] over codes [B, Hkv, T, s*]; dictionaries [Hkv, N, d].
+
+    scale defaults to 1/sqrt(d).  Returns out [B, Hq, d] float64.
+    """
+    q, DK, DV = _f64(q), _f64(DK), _f64(DV)
+    idxK, idxV, coefK, coefV = _i32(idxK), _i32(idxV), _f64(coefK), _f64(coefV)
+    B, Hq, d = q.shape
+    Hkv, N, _ = DK.shape
+    T, sK = idxK.shape[2], idxK.shape[3]
+    sV = idxV.shape[3]
+    assert DV.shape == DK.shape and idxK.shape[:2] == (B, Hkv) and idxV.shape[:3] == (B, Hkv, T)
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    sl = None if seq_lens is None else np.ascontiguousarray(seq_lens, dtype=np.int32)
+    out = np.zeros((B, Hq, d))
+    rc = _load().csr_oracle_decode_attn(_ptr(q), _ptr(DK), _ptr(idxK), _ptr(coefK), _ptr(DV),
+                                        _ptr(idxV), _ptr(coefV), B, Hq, Hkv, T, d, N, sK, sV,
+                                        float(scale), _ptr(sl), _ptr(out), nthreads)
+    if rc != 0:
+        raise RuntimeError(f"csr_oracle_decode_attn failed: {rc}")
+    return out
+
+
+# --- storage accounting, "Analysis for CSR" ---------------------------------------------------
+
+def code_bytes(s, s_n=1, idx_bytes=2, coef_bytes=2):
+    """Bytes stored per head vector: s*s_n coefficients and as many indices."""
+    return s * s_n * (idx_bytes + coef_bytes)
+
+
+def compression_ratio(d_h, s, s_n=1):
+    """fp16 vector bits over code bits: 16 d_h / (16 s s_n + 16 s s_n)."""
+    return (16.0 * d_h) / (16.0 * s * s_n + 16.0 * s * s_n)
+
+
+def equivalent_bits(d_h, s, s_n=1):
+    """Bits per channel of the equivalent quantiser: 16 / compression ratio."""
+    return 16.0 / compression_ratio(d_h, s, s_n)
