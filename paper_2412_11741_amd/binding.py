@@ -1,0 +1,188 @@
+"""Thin ctypes binding of libcsr_hip.so (the C ABI of include/csr.h).
+
+Argument marshalling only: every step of the hot path runs in the HIP kernels.  PyTorch is
+used for device memory and the current stream.  There is no CPU fallback: if the library is
+missing, or a tensor is not on the GPU, the call raises.
+"""
+import ctypes
+import os
+
+import torch  # must precede loading the library: it brings the HIP runtime the library binds to
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcsr_hip.so")
+
+CSR_OK, CSR_ERR_INVALID_ARG, CSR_ERR_UNSUPPORTED, CSR_ERR_WORKSPACE, CSR_ERR_DEVICE = range(5)
+CSR_F32, CSR_F16 = 0, 1
+CSR_I32, CSR_I16 = 0, 1
+CSR_ENCODE_AUTO, CSR_ENCODE_VALU, CSR_ENCODE_MFMA = 0, 1, 2
+
+EXPORTS = ("csr_version", "csr_last_error", "csr_code_bytes", "csr_encode_workspace_bytes",
+           "csr_encode", "csr_decode_workspace_bytes", "csr_decode_attn")
+
+
+class EncodeDesc(ctypes.Structure):
+    _fields_ = [("H", ctypes.c_int32), ("T", ctypes.c_int64), ("d", ctypes.c_int32),
+                ("N", ctypes.c_int32), ("s", ctypes.c_int32), ("x_dtype", ctypes.c_int32),
+                ("dict_dtype", ctypes.c_int32), ("coef_dtype", ctypes.c_int32),
+                ("idx_dtype", ctypes.c_int32), ("x_stride_h", ctypes.c_int64),
+                ("x_stride_t", ctypes.c_int64), ("algo", ctypes.c_int32), ("flags", ctypes.c_uint32)]
+
+
+class DecodeDesc(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+                ("T", ctypes.c_int64), ("d", ctypes.c_int32), ("N", ctypes.c_int32),
+                ("sK", ctypes.c_int32), ("sV", ctypes.c_int32), ("scale", ctypes.c_float),
+                ("q_dtype", ctypes.c_int32), ("dict_dtype", ctypes.c_int32),
+                ("coef_dtype", ctypes.c_int32), ("idx_dtype", ctypes.c_int32),
+                ("out_dtype", ctypes.c_int32), ("flags", ctypes.c_uint32)]
+
+
+class CsrError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"csr status {status}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built (python -m paper_2412_11741_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+                               "`python -m paper_2412_11741_amd.build` (there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz = ctypes.c_void_p, ctypes.c_size_t
+        L.csr_version.restype = ctypes.c_int
+        L.csr_last_error.restype = ctypes.c_char_p
+        L.csr_code_bytes.restype = sz
+        L.csr_code_bytes.argtypes = [ctypes.c_int32] * 4
+        L.csr_encode_workspace_bytes.restype = sz
+        L.csr_encode_workspace_bytes.argtypes = [ctypes.POINTER(EncodeDesc)]
+        L.csr_encode.restype = ctypes.c_int
+        L.csr_encode.argtypes = [ctypes.POINTER(EncodeDesc), vp, vp, vp, vp, vp, sz, vp]
+        L.csr_decode_workspace_bytes.restype = sz
+        L.csr_decode_workspace_bytes.argtypes = [ctypes.POINTER(DecodeDesc)]
+        L.csr_decode_attn.restype = ctypes.c_int
+        L.csr_decode_attn.argtypes = [ctypes.POINTER(DecodeDesc)] + [vp] * 10 + [sz, vp]
+        _lib = L
+    return _lib
+
+
+def last_error():
+    return lib().csr_last_error().decode()
+
+
+def _check(status):
+    if status != CSR_OK:
+        raise CsrError(status, last_error())
+
+
+_DT = {torch.float32: CSR_F32, torch.float16: CSR_F16}
+_IT = {torch.int32: CSR_I32, torch.int16: CSR_I16}
+
+
+def _dev(t, name):
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise ValueError(f"{name} must be a GPU tensor (no CPU path exists)")
+    return t
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def csr_code_bytes(s, s_n=1, idx_dtype=torch.int16, coef_dtype=torch.float16):
+    return int(lib().csr_code_bytes(s, s_n, _IT[idx_dtype], _DT[coef_dtype]))
+
+
+def encode_desc(X, D, s, coef_dtype, idx_dtype, algo=CSR_ENCODE_AUTO):
+    H, T, d = X.shape
+    if X.stride(2) != 1:
+        raise ValueError("X must be contiguous along d")
+    return EncodeDesc(H=H, T=T, d=d, N=D.shape[1], s=s, x_dtype=_DT[X.dtype], dict_dtype=_DT[D.dtype],
+                      coef_dtype=_DT[coef_dtype], idx_dtype=_IT[idx_dtype],
+                      x_stride_h=X.stride(0) if H > 1 and T > 0 else 0,
+                      x_stride_t=X.stride(1) if T > 1 else 0, algo=algo, flags=0)
+
+
+def csr_encode_workspace_bytes(desc):
+    n = lib().csr_encode_workspace_bytes(ctypes.byref(desc))
+    if n == ctypes.c_size_t(-1).value:
+        raise CsrError(CSR_ERR_INVALID_ARG, last_error())
+    return int(n)
+
+
+def csr_encode(X, D, s, coef_dtype=None, idx_dtype=None, algo=CSR_ENCODE_AUTO, idx=None, coef=None,
+               workspace=None):
+    """Matching Pursuit encode.  X [H, T, d], D [H, N, d] on the GPU -> (idx, coef) [H, T, s]."""
+    _dev(X, "X"); _dev(D, "D")
+    if X.dim() != 3 or D.dim() != 3 or D.shape[0] != X.shape[0] or D.shape[2] != X.shape[2]:
+        raise ValueError("expected X [H, T, d] and D [H, N, d]")
+    D = D.contiguous()
+    coef_dtype = coef_dtype or X.dtype
+    idx_dtype = idx_dtype or (torch.int16 if X.dtype == torch.float16 else torch.int32)
+    desc = encode_desc(X, D, s, coef_dtype, idx_dtype, algo)
+    H, T, _ = X.shape
+    if idx is None:
+        idx = torch.empty((H, T, s), dtype=idx_dtype, device=X.device)
+    if coef is None:
+        coef = torch.empty((H, T, s), dtype=coef_dtype, device=X.device)
+    need = csr_encode_workspace_bytes(desc)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+    wsb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().csr_encode(ctypes.byref(desc), _ptr(X), _ptr(D), _ptr(idx), _ptr(coef),
+                            _ptr(workspace), wsb, _stream()))
+    return idx, coef
+
+
+def decode_desc(q, DK, idxK, coefK, idxV, sV=None, scale=0.0, out_dtype=None):
+    B, Hq, d = q.shape
+    Hkv, N, _ = DK.shape
+    T, sK = idxK.shape[2], idxK.shape[3]
+    return DecodeDesc(B=B, Hq=Hq, Hkv=Hkv, T=T, d=d, N=N, sK=sK, sV=idxV.shape[3], scale=float(scale),
+                      q_dtype=_DT[q.dtype], dict_dtype=_DT[DK.dtype], coef_dtype=_DT[coefK.dtype],
+                      idx_dtype=_IT[idxK.dtype], out_dtype=_DT[out_dtype or q.dtype], flags=0)
+
+
+def csr_decode_workspace_bytes(desc):
+    n = lib().csr_decode_workspace_bytes(ctypes.byref(desc))
+    if n == ctypes.c_size_t(-1).value:
+        raise CsrError(CSR_ERR_INVALID_ARG, last_error())
+    return int(n)
+
+
+def csr_decode_attn(q, DK, idxK, coefK, DV, idxV, coefV, scale=0.0, seq_lens=None, out=None,
+                    out_dtype=None, workspace=None):
+    """Decode attention on codes.  q [B, Hq, d]; DK/DV [Hkv, N, d]; codes [B, Hkv, T, s*] -> out [B, Hq, d]."""
+    for name, t in (("q", q), ("DK", DK), ("idxK", idxK), ("coefK", coefK), ("DV", DV), ("idxV", idxV),
+                    ("coefV", coefV)):
+        _dev(t, name)
+        if not t.is_contiguous():
+            raise ValueError(f"{name} must be contiguous")
+    if DV.shape != DK.shape or DV.dtype != DK.dtype or coefV.dtype != coefK.dtype or idxV.dtype != idxK.dtype:
+        raise ValueError("key and value dictionaries / codes must share shapes' leading dims and dtypes")
+    if idxV.shape[:3] != idxK.shape[:3] or coefK.shape != idxK.shape or coefV.shape != idxV.shape:
+        raise ValueError("code tensors disagree in shape")
+    desc = decode_desc(q, DK, idxK, coefK, idxV, scale=scale, out_dtype=out_dtype)
+    if out is None:
+        out = torch.empty(q.shape, dtype=out_dtype or q.dtype, device=q.device)
+    need = csr_decode_workspace_bytes(desc)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    if seq_lens is not None:
+        _dev(seq_lens, "seq_lens")
+        if seq_lens.dtype != torch.int32 or seq_lens.numel() != q.shape[0]:
+            raise ValueError("seq_lens must be int32 [B]")
+    _check(lib().csr_decode_attn(ctypes.byref(desc), _ptr(q), _ptr(DK), _ptr(idxK), _ptr(coefK), _ptr(DV),
+                                 _ptr(idxV), _ptr(coefV), _ptr(seq_lens), _ptr(out), _ptr(workspace),
+                                 workspace.numel() * workspace.element_size(), _stream()))
+    return out

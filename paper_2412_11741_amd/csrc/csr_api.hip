@@ -1,0 +1,193 @@
+// Host side of the C ABI declared in include/csr.h: argument validation, kernel choice,
+// workspace layout.  Nothing here allocates device memory or waits for the GPU.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "csr_internal.h"
+
+namespace {
+
+thread_local char g_err[384] = "";
+
+csr_status fail(csr_status st, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+bool valid_dtype(int32_t v) { return v == CSR_F32 || v == CSR_F16; }
+bool valid_itype(int32_t v) { return v == CSR_I32 || v == CSR_I16; }
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+size_t round256(size_t v) { return (v + 255) & ~size_t(255); }
+
+// Checks everything about an encode descriptor that does not need the pointers.
+csr_status check_encode_desc(const csr_encode_desc *d, bool *use_mfma)
+{
+    if (!d) return fail(CSR_ERR_INVALID_ARG, "csr_encode: descriptor is NULL");
+    if (d->H < 0 || d->T < 0) return fail(CSR_ERR_INVALID_ARG, "csr_encode: H=%d T=%lld must be >= 0", d->H, (long long)d->T);
+    if (d->flags != 0) return fail(CSR_ERR_INVALID_ARG, "csr_encode: flags must be 0");
+    if (!valid_dtype(d->x_dtype) || !valid_dtype(d->dict_dtype) || !valid_dtype(d->coef_dtype) || !valid_itype(d->idx_dtype))
+        return fail(CSR_ERR_INVALID_ARG, "csr_encode: unknown dtype / index type");
+    if (d->algo != CSR_ENCODE_AUTO && d->algo != CSR_ENCODE_VALU && d->algo != CSR_ENCODE_MFMA)
+        return fail(CSR_ERR_INVALID_ARG, "csr_encode: unknown algo %d", d->algo);
+    if (d->s < 1 || d->s > 32) return fail(CSR_ERR_INVALID_ARG, "csr_encode: s=%d outside 1..32", d->s);
+    if (d->N < 1) return fail(CSR_ERR_INVALID_ARG, "csr_encode: N=%d must be >= 1", d->N);
+    if (d->d < 1) return fail(CSR_ERR_INVALID_ARG, "csr_encode: d=%d must be >= 1", d->d);
+    if (d->idx_dtype == CSR_I16 && d->N > 65536)
+        return fail(CSR_ERR_INVALID_ARG, "csr_encode: N=%d does not fit unsigned 16-bit indices", d->N);
+    if (d->N > (1 << 24)) return fail(CSR_ERR_UNSUPPORTED, "csr_encode: N=%d above 2^24", d->N);
+    if (d->x_dtype != d->dict_dtype)
+        return fail(CSR_ERR_UNSUPPORTED, "csr_encode: vectors and dictionary must share one dtype");
+    if (d->d != 32 && d->d != 64 && d->d != 128)
+        return fail(CSR_ERR_UNSUPPORTED, "csr_encode: d=%d not supported (32, 64, 128)", d->d);
+    const int64_t st = d->x_stride_t ? d->x_stride_t : d->d;
+    const int64_t sh = d->x_stride_h ? d->x_stride_h : d->T * st;
+    const int64_t vec = d->x_dtype == CSR_F16 ? 8 : 4;  // elements per 16-byte load
+    if (st < d->d || st % vec != 0 || sh % vec != 0 || sh < 0)
+        return fail(CSR_ERR_INVALID_ARG, "csr_encode: strides (h=%lld, t=%lld) must be >= d and multiples of 16 bytes",
+                    (long long)sh, (long long)st);
+    if (d->T > 0 && d->H > 1 && sh < (d->T - 1) * st + d->d)
+        return fail(CSR_ERR_INVALID_ARG, "csr_encode: x_stride_h=%lld makes dictionaries' vector blocks overlap", (long long)sh);
+    if ((d->T + 63) / 64 * (int64_t)d->H > 0x7fffffffLL)
+        return fail(CSR_ERR_UNSUPPORTED, "csr_encode: H*T too large for one launch");
+    csr::EncodeArgs probe{};
+    probe.H = d->H; probe.T = d->T; probe.d = d->d; probe.N = d->N; probe.s = d->s;
+    probe.f16 = d->x_dtype == CSR_F16;
+    const bool mfma_ok = csr::encode_mfma_supported(probe);
+    if (d->algo == CSR_ENCODE_MFMA && !mfma_ok)
+        return fail(CSR_ERR_UNSUPPORTED, "csr_encode: the MFMA encoder needs fp16 inputs, d=128 and N a multiple of 32 (got d=%d N=%d %s)",
+                    d->d, d->N, probe.f16 ? "f16" : "f32");
+    *use_mfma = (d->algo == CSR_ENCODE_MFMA) || (d->algo == CSR_ENCODE_AUTO && mfma_ok);
+    return CSR_OK;
+}
+
+csr_status check_decode_desc(const csr_decode_desc *d, csr::DecodePlan *plan)
+{
+    if (!d) return fail(CSR_ERR_INVALID_ARG, "csr_decode_attn: descriptor is NULL");
+    if (d->B < 0 || d->T < 0) return fail(CSR_ERR_INVALID_ARG, "csr_decode_attn: B=%d T=%lld must be >= 0", d->B, (long long)d->T);
+    if (d->flags != 0) return fail(CSR_ERR_INVALID_ARG, "csr_decode_attn: flags must be 0");
+    if (d->Hq < 1 || d->Hkv < 1 || d->Hq % d->Hkv != 0)
+        return fail(CSR_ERR_INVALID_ARG, "csr_decode_attn: Hq=%d must be a positive multiple of Hkv=%d", d->Hq, d->Hkv);
+    if (!valid_dtype(d->q_dtype) || !valid_dtype(d->dict_dtype) || !valid_dtype(d->coef_dtype) ||
+        !valid_dtype(d->out_dtype) || !valid_itype(d->idx_dtype))
+        return fail(CSR_ERR_INVALID_ARG, "csr_decode_attn: unknown dtype / index type");
+    if (d->sK < 1 || d->sK > 32 || d->sV < 1 || d->sV > 32)
+        return fail(CSR_ERR_INVALID_ARG, "csr_decode_attn: sK=%d sV=%d outside 1..32", d->sK, d->sV);
+    if (d->N < 1) return fail(CSR_ERR_INVALID_ARG, "csr_decode_attn: N=%d must be >= 1", d->N);
+    if (d->idx_dtype == CSR_I16 && d->N > 65536)
+        return fail(CSR_ERR_INVALID_ARG, "csr_decode_attn: N=%d does not fit unsigned 16-bit indices", d->N);
+    if (!(d->scale >= 0.0f) || std::isinf(d->scale))
+        return fail(CSR_ERR_INVALID_ARG, "csr_decode_attn: scale must be finite and >= 0 (0 selects 1/sqrt(d))");
+    if (d->d != 128) return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: d=%d not supported (128)", d->d);
+    if (d->Hq / d->Hkv > 8) return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: group size %d above 8", d->Hq / d->Hkv);
+    if (d->Hkv > 65535 || d->B > 65535) return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: B or Hkv above 65535");
+    if (d->T > (int64_t)1 << 30) return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: T above 2^30");
+    if (!csr::plan_decode(d->B, d->Hq, d->Hkv, d->T, d->d, d->N, plan))
+        return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: N=%d atoms do not fit the LDS-resident score and histogram tables", d->N);
+    return CSR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int csr_version(void) { return CSR_VERSION; }
+
+const char *csr_last_error(void) { return g_err; }
+
+size_t csr_code_bytes(int32_t s, int32_t s_n, int32_t idx_dtype, int32_t coef_dtype)
+{
+    if (s < 1 || s_n < 1 || !valid_itype(idx_dtype) || !valid_dtype(coef_dtype)) return 0;
+    const size_t ib = idx_dtype == CSR_I16 ? 2 : 4, cb = coef_dtype == CSR_F16 ? 2 : 4;
+    return (size_t)s * (size_t)s_n * (ib + cb);
+}
+
+size_t csr_encode_workspace_bytes(const csr_encode_desc *desc)
+{
+    bool mfma = false;
+    if (check_encode_desc(desc, &mfma) != CSR_OK) return (size_t)-1;
+    if (!mfma || desc->H == 0 || desc->T == 0) return 0;
+    return csr::encode_mfma_workspace_bytes(desc->H, desc->T, desc->N, desc->s);
+}
+
+csr_status csr_encode(const csr_encode_desc *desc, const void *X, const void *D, void *idx,
+                      void *coef, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    bool mfma = false;
+    csr_status st = check_encode_desc(desc, &mfma);
+    if (st != CSR_OK) return st;
+    if (desc->H == 0 || desc->T == 0) return CSR_OK;
+    if (!X || !D || !idx || !coef) return fail(CSR_ERR_INVALID_ARG, "csr_encode: NULL data pointer");
+    if (!aligned(X, 16) || !aligned(D, 16)) return fail(CSR_ERR_INVALID_ARG, "csr_encode: X and D must be 16-byte aligned");
+    if (!aligned(idx, 4) || !aligned(coef, 4)) return fail(CSR_ERR_INVALID_ARG, "csr_encode: idx and coef must be 4-byte aligned");
+    const size_t need = mfma ? csr::encode_mfma_workspace_bytes(desc->H, desc->T, desc->N, desc->s) : 0;
+    if (need) {
+        if (!workspace || workspace_bytes < need || !aligned(workspace, 256))
+            return fail(CSR_ERR_WORKSPACE, "csr_encode: workspace of %zu bytes (256-byte aligned) required, got %zu", need, workspace ? workspace_bytes : (size_t)0);
+    }
+    csr::EncodeArgs a{};
+    a.X = X; a.D = D; a.idx = idx; a.coef = coef;
+    a.H = desc->H; a.T = desc->T; a.d = desc->d; a.N = desc->N; a.s = desc->s;
+    a.x_stride_t = desc->x_stride_t ? desc->x_stride_t : desc->d;
+    a.x_stride_h = desc->x_stride_h ? desc->x_stride_h : desc->T * a.x_stride_t;
+    a.f16 = desc->x_dtype == CSR_F16;
+    a.coef16 = desc->coef_dtype == CSR_F16;
+    a.idx16 = desc->idx_dtype == CSR_I16;
+    a.workspace = workspace;
+    a.stream = static_cast<hipStream_t>(hip_stream);
+    const hipError_t e = mfma ? csr::launch_encode_mfma(a) : csr::launch_encode_valu(a);
+    if (e != hipSuccess) return fail(CSR_ERR_DEVICE, "csr_encode: %s", hipGetErrorString(e));
+    return CSR_OK;
+}
+
+size_t csr_decode_workspace_bytes(const csr_decode_desc *desc)
+{
+    csr::DecodePlan p{};
+    if (check_decode_desc(desc, &p) != CSR_OK) return (size_t)-1;
+    return p.total_bytes;
+}
+
+csr_status csr_decode_attn(const csr_decode_desc *desc, const void *q, const void *DK,
+                           const void *idxK, const void *coefK, const void *DV, const void *idxV,
+                           const void *coefV, const int32_t *seq_lens, void *out, void *workspace,
+                           size_t workspace_bytes, void *hip_stream)
+{
+    csr::DecodePlan p{};
+    csr_status st = check_decode_desc(desc, &p);
+    if (st != CSR_OK) return st;
+    if (desc->B == 0) return CSR_OK;
+    if (!q || !out || !DK || !DV) return fail(CSR_ERR_INVALID_ARG, "csr_decode_attn: NULL data pointer");
+    if (desc->T > 0 && (!idxK || !coefK || !idxV || !coefV))
+        return fail(CSR_ERR_INVALID_ARG, "csr_decode_attn: NULL code pointer with T > 0");
+    if (!aligned(q, 16) || !aligned(DK, 16) || !aligned(DV, 16) || !aligned(out, 16))
+        return fail(CSR_ERR_INVALID_ARG, "csr_decode_attn: q, DK, DV and out must be 16-byte aligned");
+    if (!aligned(idxK, 16) || !aligned(coefK, 16) || !aligned(idxV, 16) || !aligned(coefV, 16))
+        return fail(CSR_ERR_INVALID_ARG, "csr_decode_attn: code streams must be 16-byte aligned");
+    if (seq_lens && !aligned(seq_lens, 4)) return fail(CSR_ERR_INVALID_ARG, "csr_decode_attn: seq_lens misaligned");
+    if (!workspace || workspace_bytes < p.total_bytes || !aligned(workspace, 256))
+        return fail(CSR_ERR_WORKSPACE, "csr_decode_attn: workspace of %zu bytes (256-byte aligned) required, got %zu",
+                    p.total_bytes, workspace ? workspace_bytes : (size_t)0);
+    csr::DecodeArgs a{};
+    a.q = q; a.DK = DK; a.idxK = idxK; a.coefK = coefK; a.DV = DV; a.idxV = idxV; a.coefV = coefV;
+    a.seq_lens = seq_lens; a.out = out;
+    a.B = desc->B; a.Hq = desc->Hq; a.Hkv = desc->Hkv; a.G = desc->Hq / desc->Hkv;
+    a.T = desc->T; a.d = desc->d; a.N = desc->N; a.sK = desc->sK; a.sV = desc->sV;
+    a.scale = desc->scale > 0.0f ? desc->scale : 1.0f / std::sqrt((float)desc->d);
+    a.q16 = desc->q_dtype == CSR_F16;
+    a.dict16 = desc->dict_dtype == CSR_F16;
+    a.coef16 = desc->coef_dtype == CSR_F16;
+    a.idx16 = desc->idx_dtype == CSR_I16;
+    a.out16 = desc->out_dtype == CSR_F16;
+    a.workspace = workspace;
+    a.stream = static_cast<hipStream_t>(hip_stream);
+    const hipError_t e = csr::launch_decode(a, p);
+    if (e != hipSuccess) return fail(CSR_ERR_DEVICE, "csr_decode_attn: %s", hipGetErrorString(e));
+    return CSR_OK;
+}
+
+}  // extern "C"

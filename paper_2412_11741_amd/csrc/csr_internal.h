@@ -1,0 +1,67 @@
+// Internal declarations shared by the host dispatch layer and the gfx950 kernels.
+// Not part of the public ABI (that is include/csr.h).
+#pragma once
+
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "csr.h"
+
+namespace csr {
+
+constexpr int kWave = 64;  // CDNA wavefront width
+
+// ---- encode ---------------------------------------------------------------------------------
+struct EncodeArgs {
+    const void *X;
+    const void *D;
+    void *idx;
+    void *coef;
+    int32_t H;
+    int64_t T;
+    int32_t d, N, s;
+    int64_t x_stride_h, x_stride_t;  // elements, already defaulted
+    bool f16;                        // X and D are fp16 (else fp32)
+    bool coef16, idx16;
+    void *workspace;
+    hipStream_t stream;
+};
+
+// fp32 vector-ALU encoder: any N, d in {32, 64, 128}.
+hipError_t launch_encode_valu(const EncodeArgs &a);
+
+// fp16 matrix-core encoder: d == 128, fp16 inputs.
+bool encode_mfma_supported(const EncodeArgs &a);
+size_t encode_mfma_workspace_bytes(int32_t H, int64_t T, int32_t N, int32_t s);
+hipError_t launch_encode_mfma(const EncodeArgs &a);
+
+// ---- decode ---------------------------------------------------------------------------------
+struct DecodePlan {
+    int32_t GB;           // query heads of one KV head handled together by a block (1, 2 or 4)
+    int32_t ngs;          // group slices per KV head = G / GB
+    int32_t nchunks;      // split of the token axis
+    int64_t chunk_tokens; // tokens per chunk (multiple of the block's token step)
+    size_t off_qd, off_hist, off_ml, off_acc, total_bytes;
+    size_t lds_bytes;     // dynamic LDS of the streaming kernel
+};
+
+struct DecodeArgs {
+    const void *q, *DK, *idxK, *coefK, *DV, *idxV, *coefV;
+    const int32_t *seq_lens;
+    void *out;
+    int32_t B, Hq, Hkv, G;
+    int64_t T;
+    int32_t d, N, sK, sV;
+    float scale;
+    bool q16, dict16, coef16, idx16, out16;
+    void *workspace;
+    hipStream_t stream;
+};
+
+// Fills the plan; returns false if no kernel configuration fits (e.g. N too large for LDS).
+bool plan_decode(int32_t B, int32_t Hq, int32_t Hkv, int64_t T, int32_t d, int32_t N, DecodePlan *p);
+hipError_t launch_decode(const DecodeArgs &a, const DecodePlan &p);
+
+}  // namespace csr

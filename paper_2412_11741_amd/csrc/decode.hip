@@ -1,0 +1,562 @@
+// Decode attention computed directly on (index, coefficient) codes.
+//
+// The paper rebuilds X~ = D r (Eq.12) and runs ordinary attention on it.  Because the rebuild is
+// linear, the same numbers come out of the code domain:
+//     score_t = q . (D_K r_t)      = sum_j coefK[t][j] * (q . d^K_{idxK[t][j]})
+//     out     = sum_t p_t D_V r_t  = D_V^T hist,   hist[n] = sum_{t,j: idxV[t][j]=n} p_t coefV[t][j]
+// so per cached token only its 2s-odd code pairs are read from HBM instead of 2d values.
+//
+// Four launches on the caller's stream:
+//   qd_kernel        qd[b][h][n][g] = scale * q[b][hg] . d^K_n   (also clears the output accumulator)
+//   stream_kernel    one workgroup per (token chunk, KV head x group slice, sequence):
+//                    score table qd and histogram hist live in LDS as [N][GB]; the K and V code
+//                    streams are read once, coalesced; softmax is kept online per workgroup (running
+//                    max, the histogram is rescaled when the max moves, which gets rare quickly);
+//                    the chunk's histogram, max and sum go to scratch
+//   out_kernel       combines chunk histograms with exp(m_c - M) weights and multiplies by a slice of
+//                    D_V, adding into an fp32 accumulator
+//   finalize_kernel  divides by the softmax denominator and stores in the output type
+#include <cmath>
+
+#include "csr_internal.h"
+
+namespace csr {
+namespace {
+
+constexpr int kStreamThreads = 1024;  // 16 waves: enough loads in flight with one workgroup per CU
+constexpr int kStreamWaves = kStreamThreads / 64;
+constexpr int kOutAtoms = 64;         // atoms of D_V per out_kernel workgroup
+constexpr int kQdAtoms = 64;          // atoms of D_K per qd_kernel workgroup
+constexpr int kQTile = 32;            // queries staged in LDS at a time by qd_kernel
+constexpr int kMaxChunks = 64;
+constexpr size_t kLdsBudget = 150 * 1024;
+
+__device__ __forceinline__ float h2f(__half v) { return __half2float(v); }
+
+template <typename T> __device__ __forceinline__ void load8(const T *p, float (&o)[8]);
+template <> __device__ __forceinline__ void load8<__half>(const __half *p, float (&o)[8])
+{
+    const uint4 raw = *reinterpret_cast<const uint4 *>(p);
+    const __half2 *h2 = reinterpret_cast<const __half2 *>(&raw);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float2 f = __half22float2(h2[j]);
+        o[2 * j] = f.x;
+        o[2 * j + 1] = f.y;
+    }
+}
+template <> __device__ __forceinline__ void load8<float>(const float *p, float (&o)[8])
+{
+    const float4 a = *reinterpret_cast<const float4 *>(p);
+    const float4 b = *reinterpret_cast<const float4 *>(p + 4);
+    o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w;
+    o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+}
+
+// ---------------------------------------------------------------------------------------------
+// qd[b][h][gs][n][gg] = scale * q[b][h*G + gs*GB + gg] . DK[h][n]
+// 16 lanes share one atom row (8 consecutive k each), so a wave reads 4 rows = 1 KiB per load.
+template <typename TQ, typename TD>
+__global__ __launch_bounds__(256) void qd_kernel(const TQ *__restrict__ q, const TD *__restrict__ DK,
+                                                 float *__restrict__ qd, float *__restrict__ out_acc,
+                                                 int32_t B, int32_t Hq, int32_t Hkv, int32_t G,
+                                                 int32_t GB, int32_t N, float scale)
+{
+    __shared__ float q_s[kQTile][128];
+    const int h = blockIdx.y;
+    const int tid = threadIdx.x;
+    const int sub = tid & 15, arow = tid >> 4;
+    const int n_base = blockIdx.x * kQdAtoms;
+    const int ngs = G / GB;
+
+    // clear the fp32 output accumulator (whole grid, strided)
+    {
+        const int64_t total = (int64_t)B * Hq * 128;
+        const int64_t stride = (int64_t)gridDim.x * gridDim.y * blockDim.x;
+        for (int64_t i = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * blockDim.x + tid; i < total; i += stride)
+            out_acc[i] = 0.0f;
+    }
+
+    float a[4][8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int n = n_base + arow + 16 * i;
+        if (n < N) load8<TD>(DK + ((int64_t)h * N + n) * 128 + sub * 8, a[i]);
+        else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) a[i][j] = 0.0f;
+        }
+    }
+
+    const int BG = B * G;
+    for (int q0 = 0; q0 < BG; q0 += kQTile) {
+        const int nq = min(kQTile, BG - q0);
+        __syncthreads();
+        for (int e = tid; e < nq * 128; e += 256) {
+            const int qi = q0 + e / 128, k = e % 128;
+            const int b = qi / G, g = qi % G;
+            q_s[e / 128][k] = (float)q[((int64_t)b * Hq + h * G + g) * 128 + k];
+        }
+        __syncthreads();
+        for (int ql = 0; ql < nq; ++ql) {
+            float qv[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) qv[j] = q_s[ql][sub * 8 + j];
+            float dot[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float acc = 0.0f;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc = fmaf(a[i][j], qv[j], acc);
+                dot[i] = acc;
+            }
+#pragma unroll
+            for (int m = 8; m >= 1; m >>= 1) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) dot[i] += __shfl_xor(dot[i], m, 64);
+            }
+            if (sub == 0) {
+                const int qi = q0 + ql;
+                const int b = qi / G, g = qi % G;
+                const int gs = g / GB, gg = g % GB;
+                float *dst = qd + (((int64_t)b * Hkv + h) * ngs + gs) * (int64_t)N * GB;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int n = n_base + arow + 16 * i;
+                    if (n < N) dst[(int64_t)n * GB + gg] = scale * dot[i];
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Code-stream loads: PV pairs of one token at a time, widened to int / float registers.
+template <typename TI, int PV> struct IdxLoad;
+template <> struct IdxLoad<uint16_t, 8> {
+    static __device__ __forceinline__ void ld(const uint16_t *p, int (&o)[8]) {
+        const uint4 r = *reinterpret_cast<const uint4 *>(p);
+        o[0] = r.x & 0xffff; o[1] = r.x >> 16; o[2] = r.y & 0xffff; o[3] = r.y >> 16;
+        o[4] = r.z & 0xffff; o[5] = r.z >> 16; o[6] = r.w & 0xffff; o[7] = r.w >> 16;
+    }
+};
+template <> struct IdxLoad<uint16_t, 4> {
+    static __device__ __forceinline__ void ld(const uint16_t *p, int (&o)[4]) {
+        const uint2 r = *reinterpret_cast<const uint2 *>(p);
+        o[0] = r.x & 0xffff; o[1] = r.x >> 16; o[2] = r.y & 0xffff; o[3] = r.y >> 16;
+    }
+};
+template <> struct IdxLoad<uint16_t, 1> {
+    static __device__ __forceinline__ void ld(const uint16_t *p, int (&o)[1]) { o[0] = p[0]; }
+};
+template <> struct IdxLoad<int32_t, 8> {
+    static __device__ __forceinline__ void ld(const int32_t *p, int (&o)[8]) {
+        const int4 a = *reinterpret_cast<const int4 *>(p);
+        const int4 b = *reinterpret_cast<const int4 *>(p + 4);
+        o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w; o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+    }
+};
+template <> struct IdxLoad<int32_t, 4> {
+    static __device__ __forceinline__ void ld(const int32_t *p, int (&o)[4]) {
+        const int4 a = *reinterpret_cast<const int4 *>(p);
+        o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w;
+    }
+};
+template <> struct IdxLoad<int32_t, 1> {
+    static __device__ __forceinline__ void ld(const int32_t *p, int (&o)[1]) { o[0] = p[0]; }
+};
+
+template <typename TC, int PV> struct CoefLoad;
+template <> struct CoefLoad<__half, 8> {
+    static __device__ __forceinline__ void ld(const __half *p, float (&o)[8]) { load8<__half>(p, o); }
+};
+template <> struct CoefLoad<__half, 4> {
+    static __device__ __forceinline__ void ld(const __half *p, float (&o)[4]) {
+        const uint2 raw = *reinterpret_cast<const uint2 *>(p);
+        const __half2 *h2 = reinterpret_cast<const __half2 *>(&raw);
+        const float2 f0 = __half22float2(h2[0]), f1 = __half22float2(h2[1]);
+        o[0] = f0.x; o[1] = f0.y; o[2] = f1.x; o[3] = f1.y;
+    }
+};
+template <> struct CoefLoad<__half, 1> {
+    static __device__ __forceinline__ void ld(const __half *p, float (&o)[1]) { o[0] = h2f(p[0]); }
+};
+template <> struct CoefLoad<float, 8> {
+    static __device__ __forceinline__ void ld(const float *p, float (&o)[8]) { load8<float>(p, o); }
+};
+template <> struct CoefLoad<float, 4> {
+    static __device__ __forceinline__ void ld(const float *p, float (&o)[4]) {
+        const float4 a = *reinterpret_cast<const float4 *>(p);
+        o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w;
+    }
+};
+template <> struct CoefLoad<float, 1> {
+    static __device__ __forceinline__ void ld(const float *p, float (&o)[1]) { o[0] = p[0]; }
+};
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+    return v;
+}
+
+// One workgroup: chunk c of the tokens of (sequence b, KV head h, group slice gs).
+// LDS: qd_s[N*GB] | hist[N*GB] | red[2][waves][GB]
+template <int GB, typename TI, typename TC, int PV>
+__global__ __launch_bounds__(kStreamThreads) void stream_kernel(
+    const float *__restrict__ qd, const TI *__restrict__ idxK, const TC *__restrict__ coefK,
+    const TI *__restrict__ idxV, const TC *__restrict__ coefV, const int32_t *__restrict__ seq_lens,
+    float *__restrict__ part_hist, float *__restrict__ part_ml, int32_t Hkv, int32_t ngs, int64_t T,
+    int32_t N, int32_t sK, int32_t sV, int64_t chunk_tokens, int32_t nchunks)
+{
+    extern __shared__ float smem[];
+    float *qd_s = smem;
+    float *hist = smem + (size_t)N * GB;
+    float *red = hist + (size_t)N * GB;  // [2][kStreamWaves][GB]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int c = blockIdx.x;
+    const int h = blockIdx.y / ngs, gs = blockIdx.y % ngs;
+    const int b = blockIdx.z;
+
+    int64_t len = T;
+    if (seq_lens) {
+        const int32_t l = seq_lens[b];
+        len = l < 0 ? 0 : (l > T ? T : l);
+    }
+    const int64_t t0 = (int64_t)c * chunk_tokens;
+    const int64_t t_end = min(t0 + chunk_tokens, len);
+    const int64_t slot = (((int64_t)b * Hkv + h) * ngs + gs) * nchunks + c;
+    float *ml = part_ml + slot * (2 * GB);
+
+    if (t_end <= t0) {  // nothing cached in this chunk: weight zero, histogram never read
+        if (tid < GB) { ml[2 * tid] = -INFINITY; ml[2 * tid + 1] = 0.0f; }
+        return;
+    }
+
+    const int table = N * GB;
+    {
+        const float *src = qd + (((int64_t)b * Hkv + h) * ngs + gs) * (int64_t)table;
+        for (int e = tid; e < table; e += kStreamThreads) { qd_s[e] = src[e]; hist[e] = 0.0f; }
+    }
+    __syncthreads();
+
+    const int64_t code_row = ((int64_t)b * Hkv + h) * T;
+    float m_run[GB], l_thr[GB];
+#pragma unroll
+    for (int g = 0; g < GB; ++g) { m_run[g] = -INFINITY; l_thr[g] = 0.0f; }
+
+    int it = 0;
+    for (int64_t tb = t0; tb < t_end; tb += kStreamThreads, ++it) {
+        const int64_t t = tb + tid;
+        const bool valid = t < t_end;
+        float sc[GB];
+#pragma unroll
+        for (int g = 0; g < GB; ++g) sc[g] = 0.0f;
+        if (valid) {
+            const TI *ip = idxK + (code_row + t) * sK;
+            const TC *cp = coefK + (code_row + t) * sK;
+            for (int j0 = 0; j0 < sK; j0 += PV) {
+                int id[PV];
+                float cf[PV];
+                IdxLoad<TI, PV>::ld(ip + j0, id);
+                CoefLoad<TC, PV>::ld(cp + j0, cf);
+#pragma unroll
+                for (int j = 0; j < PV; ++j) {
+#pragma unroll
+                    for (int g = 0; g < GB; ++g) sc[g] = fmaf(cf[j], qd_s[id[j] * GB + g], sc[g]);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int g = 0; g < GB; ++g) sc[g] = -INFINITY;
+        }
+        float *rbuf = red + (it & 1) * (kStreamWaves * GB);
+#pragma unroll
+        for (int g = 0; g < GB; ++g) {
+            const float wm = wave_max(sc[g]);
+            if (lane == 0) rbuf[wave * GB + g] = wm;
+        }
+        __syncthreads();
+        bool moved = false;
+        float fac[GB];
+#pragma unroll
+        for (int g = 0; g < GB; ++g) {
+            float mx = rbuf[g];
+#pragma unroll
+            for (int w = 1; w < kStreamWaves; ++w) mx = fmaxf(mx, rbuf[w * GB + g]);
+            fac[g] = 1.0f;
+            if (mx > m_run[g]) {
+                if (m_run[g] > -INFINITY) { fac[g] = __expf(m_run[g] - mx); moved = true; }
+                m_run[g] = mx;
+            }
+        }
+        if (moved) {  // uniform over the workgroup: every thread saw the same maxima
+            for (int e = tid; e < N; e += kStreamThreads) {
+#pragma unroll
+                for (int g = 0; g < GB; ++g) hist[e * GB + g] *= fac[g];
+            }
+#pragma unroll
+            for (int g = 0; g < GB; ++g) l_thr[g] *= fac[g];
+            __syncthreads();
+        }
+        if (valid) {
+            float p[GB];
+#pragma unroll
+            for (int g = 0; g < GB; ++g) { p[g] = __expf(sc[g] - m_run[g]); l_thr[g] += p[g]; }
+            const TI *ip = idxV + (code_row + t) * sV;
+            const TC *cp = coefV + (code_row + t) * sV;
+            for (int j0 = 0; j0 < sV; j0 += PV) {
+                int id[PV];
+                float cf[PV];
+                IdxLoad<TI, PV>::ld(ip + j0, id);
+                CoefLoad<TC, PV>::ld(cp + j0, cf);
+#pragma unroll
+                for (int j = 0; j < PV; ++j) {
+#pragma unroll
+                    for (int g = 0; g < GB; ++g) atomicAdd(&hist[id[j] * GB + g], p[g] * cf[j]);
+                }
+            }
+        }
+    }
+    __syncthreads();  // all atomics landed; `red` is free again
+
+#pragma unroll
+    for (int g = 0; g < GB; ++g) {
+        const float ws = wave_sum(l_thr[g]);
+        if (lane == 0) red[wave * GB + g] = ws;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int g = 0; g < GB; ++g) {
+        if (tid == g) {
+            float l = 0.0f;
+            for (int w = 0; w < kStreamWaves; ++w) l += red[w * GB + g];
+            ml[2 * g] = m_run[g];
+            ml[2 * g + 1] = l;
+        }
+    }
+    float *dst = part_hist + slot * (int64_t)table;
+    for (int e = tid; e < table; e += kStreamThreads) dst[e] = hist[e];
+}
+
+// ---------------------------------------------------------------------------------------------
+// out_acc[b][hq][k] += sum_{n in slice} (sum_c w_c hist_c[n][g]) * DV[h][n][k]
+template <typename TD>
+__global__ __launch_bounds__(128) void out_kernel(const TD *__restrict__ DV, const float *__restrict__ part_hist,
+                                                  const float *__restrict__ part_ml, float *__restrict__ out_acc,
+                                                  int32_t Hq, int32_t Hkv, int32_t G, int32_t GB, int32_t N,
+                                                  int32_t nchunks)
+{
+    __shared__ float dv_s[kOutAtoms][128];
+    __shared__ float hist_s[8][kOutAtoms];
+    __shared__ float w_s[8][kMaxChunks];
+    const int tid = threadIdx.x;
+    const int n0 = blockIdx.x * kOutAtoms;
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int ngs = G / GB;
+
+    for (int e = tid; e < kOutAtoms * 16; e += 128) {
+        const int r = e >> 4, cch = e & 15;
+        float v[8];
+        if (n0 + r < N) load8<TD>(DV + ((int64_t)h * N + n0 + r) * 128 + cch * 8, v);
+        else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = 0.0f;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) dv_s[r][cch * 8 + j] = v[j];
+    }
+    if (tid < G) {
+        const int gs = tid / GB, gg = tid % GB;
+        const float *ml = part_ml + ((((int64_t)b * Hkv + h) * ngs + gs) * nchunks) * (2 * GB);
+        float M = -INFINITY;
+        for (int c = 0; c < nchunks; ++c) M = fmaxf(M, ml[c * 2 * GB + 2 * gg]);
+        for (int c = 0; c < nchunks; ++c) {
+            const float m = ml[c * 2 * GB + 2 * gg];
+            w_s[tid][c] = (m > -INFINITY) ? __expf(m - M) : 0.0f;
+        }
+    }
+    __syncthreads();
+    for (int e = tid; e < G * kOutAtoms; e += 128) {
+        const int g = e / kOutAtoms, nn = e % kOutAtoms;
+        const int gs = g / GB, gg = g % GB;
+        float acc = 0.0f;
+        if (n0 + nn < N) {
+            const float *ph = part_hist + ((((int64_t)b * Hkv + h) * ngs + gs) * nchunks) * (int64_t)N * GB +
+                              (int64_t)(n0 + nn) * GB + gg;
+            for (int c = 0; c < nchunks; ++c) {
+                const float w = w_s[g][c];
+                if (w > 0.0f) acc = fmaf(w, ph[(int64_t)c * N * GB], acc);
+            }
+        }
+        hist_s[g][nn] = acc;
+    }
+    __syncthreads();
+    for (int g = 0; g < G; ++g) {
+        float acc = 0.0f;
+#pragma unroll 16
+        for (int nn = 0; nn < kOutAtoms; ++nn) acc = fmaf(hist_s[g][nn], dv_s[nn][tid], acc);
+        atomicAdd(&out_acc[((int64_t)b * Hq + h * G + g) * 128 + tid], acc);
+    }
+}
+
+template <typename TO>
+__global__ __launch_bounds__(128) void finalize_kernel(const float *__restrict__ out_acc,
+                                                       const float *__restrict__ part_ml, TO *__restrict__ out,
+                                                       int32_t Hq, int32_t Hkv, int32_t G, int32_t GB,
+                                                       int32_t nchunks)
+{
+    const int hq = blockIdx.x % Hq, b = blockIdx.x / Hq;
+    const int h = hq / G, g = hq % G;
+    const int ngs = G / GB, gs = g / GB, gg = g % GB;
+    const float *ml = part_ml + ((((int64_t)b * Hkv + h) * ngs + gs) * nchunks) * (2 * GB);
+    float M = -INFINITY;
+    for (int c = 0; c < nchunks; ++c) M = fmaxf(M, ml[c * 2 * GB + 2 * gg]);
+    float L = 0.0f;
+    for (int c = 0; c < nchunks; ++c) {
+        const float m = ml[c * 2 * GB + 2 * gg];
+        if (m > -INFINITY) L = fmaf(__expf(m - M), ml[c * 2 * GB + 2 * gg + 1], L);
+    }
+    const int64_t o = ((int64_t)b * Hq + hq) * 128 + threadIdx.x;
+    const float v = L > 0.0f ? out_acc[o] / L : 0.0f;
+    out[o] = (TO)v;
+}
+
+template <int GB, typename TI, typename TC, int PV>
+hipError_t launch_stream_t(const DecodeArgs &a, const DecodePlan &p, float *qd, float *hist, float *ml)
+{
+    auto kern = stream_kernel<GB, TI, TC, PV>;
+    static bool attr_set = false;  // raising the dynamic-LDS limit is needed once per kernel
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const dim3 grid((unsigned)p.nchunks, (unsigned)(a.Hkv * p.ngs), (unsigned)a.B);
+    hipLaunchKernelGGL(kern, grid, dim3(kStreamThreads), p.lds_bytes, a.stream, qd, (const TI *)a.idxK,
+                       (const TC *)a.coefK, (const TI *)a.idxV, (const TC *)a.coefV, a.seq_lens, hist, ml,
+                       a.Hkv, p.ngs, a.T, a.N, a.sK, a.sV, p.chunk_tokens, p.nchunks);
+    return hipGetLastError();
+}
+
+template <int GB, typename TI, typename TC>
+hipError_t launch_stream_pv(const DecodeArgs &a, const DecodePlan &p, float *qd, float *hist, float *ml)
+{
+    if (a.sK % 8 == 0 && a.sV % 8 == 0) return launch_stream_t<GB, TI, TC, 8>(a, p, qd, hist, ml);
+    if (a.sK % 4 == 0 && a.sV % 4 == 0) return launch_stream_t<GB, TI, TC, 4>(a, p, qd, hist, ml);
+    return launch_stream_t<GB, TI, TC, 1>(a, p, qd, hist, ml);
+}
+
+template <int GB>
+hipError_t launch_stream_gb(const DecodeArgs &a, const DecodePlan &p, float *qd, float *hist, float *ml)
+{
+    if (a.idx16) {
+        if (a.coef16) return launch_stream_pv<GB, uint16_t, __half>(a, p, qd, hist, ml);
+        return launch_stream_pv<GB, uint16_t, float>(a, p, qd, hist, ml);
+    }
+    if (a.coef16) return launch_stream_pv<GB, int32_t, __half>(a, p, qd, hist, ml);
+    return launch_stream_pv<GB, int32_t, float>(a, p, qd, hist, ml);
+}
+
+}  // namespace
+
+bool plan_decode(int32_t B, int32_t Hq, int32_t Hkv, int64_t T, int32_t d, int32_t N, DecodePlan *p)
+{
+    (void)d;
+    const int G = Hq / Hkv;
+    int GB = 0;
+    for (int cand : {4, 2, 1}) {
+        if (G % cand != 0) continue;
+        const size_t lds = (size_t)2 * N * cand * sizeof(float) + (size_t)2 * kStreamWaves * cand * sizeof(float);
+        if (lds <= kLdsBudget) { GB = cand; p->lds_bytes = lds; break; }
+    }
+    if (!GB) return false;
+    p->GB = GB;
+    p->ngs = G / GB;
+    // Split the token axis until the launch has a couple of workgroups per CU; every extra chunk
+    // costs one histogram round trip through scratch, so no more than that.
+    const int64_t groups = (int64_t)(B > 0 ? B : 1) * Hkv * p->ngs;
+    int64_t want = (512 + groups - 1) / groups;
+    const int64_t most = T > 0 ? (T + kStreamThreads - 1) / kStreamThreads : 1;
+    if (want > most) want = most;
+    if (want > kMaxChunks) want = kMaxChunks;
+    if (want < 1) want = 1;
+    int64_t ct = T > 0 ? (T + want - 1) / want : kStreamThreads;
+    ct = (ct + kStreamThreads - 1) / kStreamThreads * kStreamThreads;
+    p->chunk_tokens = ct;
+    p->nchunks = T > 0 ? (int32_t)((T + ct - 1) / ct) : 1;
+    auto r256 = [](size_t v) { return (v + 255) & ~size_t(255); };
+    const size_t BHq = (size_t)(B > 0 ? B : 1) * Hq;
+    size_t off = 0;
+    p->off_qd = off;   off += r256(BHq * N * sizeof(float));
+    p->off_hist = off; off += r256(BHq * N * sizeof(float) * p->nchunks);
+    p->off_ml = off;   off += r256(BHq * 2 * sizeof(float) * p->nchunks);
+    p->off_acc = off;  off += r256(BHq * 128 * sizeof(float));
+    p->total_bytes = off;
+    return true;
+}
+
+hipError_t launch_decode(const DecodeArgs &a, const DecodePlan &p)
+{
+    char *ws = static_cast<char *>(a.workspace);
+    float *qd = reinterpret_cast<float *>(ws + p.off_qd);
+    float *hist = reinterpret_cast<float *>(ws + p.off_hist);
+    float *ml = reinterpret_cast<float *>(ws + p.off_ml);
+    float *acc = reinterpret_cast<float *>(ws + p.off_acc);
+
+    {
+        const dim3 grid((unsigned)((a.N + kQdAtoms - 1) / kQdAtoms), (unsigned)a.Hkv);
+#define CSR_QD(TQ, TD)                                                                              \
+    hipLaunchKernelGGL((qd_kernel<TQ, TD>), grid, dim3(256), 0, a.stream, (const TQ *)a.q,          \
+                       (const TD *)a.DK, qd, acc, a.B, a.Hq, a.Hkv, a.G, p.GB, a.N, a.scale)
+        if (a.q16 && a.dict16) CSR_QD(__half, __half);
+        else if (a.q16) CSR_QD(__half, float);
+        else if (a.dict16) CSR_QD(float, __half);
+        else CSR_QD(float, float);
+#undef CSR_QD
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    {
+        hipError_t e;
+        switch (p.GB) {
+            case 4: e = launch_stream_gb<4>(a, p, qd, hist, ml); break;
+            case 2: e = launch_stream_gb<2>(a, p, qd, hist, ml); break;
+            default: e = launch_stream_gb<1>(a, p, qd, hist, ml); break;
+        }
+        if (e != hipSuccess) return e;
+    }
+    {
+        const dim3 grid((unsigned)((a.N + kOutAtoms - 1) / kOutAtoms), (unsigned)a.Hkv, (unsigned)a.B);
+        if (a.dict16)
+            hipLaunchKernelGGL((out_kernel<__half>), grid, dim3(128), 0, a.stream, (const __half *)a.DV, hist, ml,
+                               acc, a.Hq, a.Hkv, a.G, p.GB, a.N, p.nchunks);
+        else
+            hipLaunchKernelGGL((out_kernel<float>), grid, dim3(128), 0, a.stream, (const float *)a.DV, hist, ml,
+                               acc, a.Hq, a.Hkv, a.G, p.GB, a.N, p.nchunks);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    {
+        const dim3 grid((unsigned)(a.B * a.Hq));
+        if (a.out16)
+            hipLaunchKernelGGL((finalize_kernel<__half>), grid, dim3(128), 0, a.stream, acc, ml, (__half *)a.out,
+                               a.Hq, a.Hkv, a.G, p.GB, p.nchunks);
+        else
+            hipLaunchKernelGGL((finalize_kernel<float>), grid, dim3(128), 0, a.stream, acc, ml, (float *)a.out,
+                               a.Hq, a.Hkv, a.G, p.GB, p.nchunks);
+        return hipGetLastError();
+    }
+}
+
+}  // namespace csr

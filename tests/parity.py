@@ -1,0 +1,111 @@
+"""Comparison rules between a candidate encoder / decoder output and the CPU oracle.
+
+Encode (per vector, walking the iterations in order):
+  * same atom index as the oracle  -> the coefficient must agree within `coef_tol`, relative to
+    max(|c|, 1e-6 |x|);
+  * different index -> accepted only if, at that step, the oracle's best and runner-up
+    |correlation| differ by at most tie_rel * best (a tie: either atom is a correct greedy pick).
+    From there on the two paths legitimately differ, so the remaining steps of that vector are
+    checked for greedy validity instead: each pick must reach the largest |R . d_n| of the residual
+    built (in float64) from the candidate's own earlier picks, within tie_rel, and its coefficient
+    must be that projection within coef_tol.
+Decode: relative L2 error per (sequence, query head).
+"""
+from dataclasses import dataclass, field
+
+import numpy as np
+
+TIE_REL = 1e-6
+
+
+@dataclass
+class EncodeReport:
+    vectors: int = 0
+    steps: int = 0
+    exact_steps: int = 0
+    tie_vectors: int = 0
+    failures: list = field(default_factory=list)
+    max_coef_err: float = 0.0
+
+    @property
+    def ok(self):
+        return not self.failures
+
+    def summary(self):
+        return (f"{self.vectors} vectors, {self.exact_steps}/{self.steps} steps index-identical, "
+                f"{self.tie_vectors} vectors diverged at an accepted tie, "
+                f"{len(self.failures)} failures, max rel coef err {self.max_coef_err:.3e}")
+
+
+def _as_index(a):
+    a = np.asarray(a)
+    if a.dtype == np.int16:
+        a = a.view(np.uint16)
+    return a.astype(np.int64)
+
+
+def check_encode(X, D, idx_c, coef_c, idx_o, coef_o, diag, coef_tol, tie_rel=TIE_REL, max_report=10):
+    """X [T, d], D [N, d] (the exact input bits, any float dtype); candidate and oracle codes [T, s];
+    diag = the oracle's diagnostics dict for these vectors."""
+    X = np.asarray(X, dtype=np.float64)
+    D = np.asarray(D, dtype=np.float64)
+    idx_c, idx_o = _as_index(idx_c), _as_index(idx_o)
+    coef_c = np.asarray(coef_c, dtype=np.float64)
+    coef_o = np.asarray(coef_o, dtype=np.float64)
+    T, s = idx_o.shape
+    rep = EncodeReport(vectors=T, steps=T * s)
+    xnorm = np.linalg.norm(X, axis=1)
+    same = idx_c == idx_o
+    # number of leading steps that agree, per vector
+    lead = np.where(same.all(axis=1), s, np.argmin(same, axis=1))
+    rep.exact_steps = int(same.sum())
+    floor = 1e-6 * xnorm[:, None]
+    denom = np.maximum(np.abs(coef_o), floor)
+    rel = np.abs(coef_c - coef_o) / np.where(denom > 0, denom, 1.0)
+    for t in range(T):
+        L = int(lead[t])
+        if L:
+            e = float(rel[t, :L].max())
+            rep.max_coef_err = max(rep.max_coef_err, e)
+            if e > coef_tol and len(rep.failures) < max_report:
+                g = int(np.argmax(rel[t, :L]))
+                rep.failures.append(f"vector {t} step {g}: coef {coef_c[t, g]!r} vs oracle {coef_o[t, g]!r}")
+        if L == s:
+            continue
+        best, second = diag["best_abs"][t, L], diag["second_abs"][t, L]
+        if best - second > tie_rel * best:
+            if len(rep.failures) < max_report:
+                rep.failures.append(f"vector {t} step {L}: index {idx_c[t, L]} vs oracle {idx_o[t, L]} "
+                                    f"(best {best!r}, runner-up {second!r}: not a tie)")
+            continue
+        rep.tie_vectors += 1
+        # greedy validity of the candidate's own path from step L on
+        R = X[t].copy()
+        for g in range(L):
+            R -= coef_o[t, g] * D[idx_o[t, g]]
+        for g in range(L, s):
+            C = D @ R
+            a = np.abs(C)
+            n = int(idx_c[t, g])
+            if a[n] < a.max() * (1.0 - tie_rel) - 1e-300:
+                if len(rep.failures) < max_report:
+                    rep.failures.append(f"vector {t} step {g} (after tie at {L}): index {n} is not a greedy pick")
+                break
+            e = abs(coef_c[t, g] - C[n]) / max(abs(C[n]), 1e-6 * xnorm[t], 1e-300)
+            rep.max_coef_err = max(rep.max_coef_err, float(e))
+            if e > coef_tol:
+                if len(rep.failures) < max_report:
+                    rep.failures.append(f"vector {t} step {g} (after tie at {L}): coef {coef_c[t, g]!r} vs {C[n]!r}")
+                break
+            R -= C[n] * D[n]
+    return rep
+
+
+def decode_errors(out_c, out_o):
+    """Relative L2 error per (b, hq) and the largest absolute error."""
+    out_c = np.asarray(out_c, dtype=np.float64)
+    out_o = np.asarray(out_o, dtype=np.float64)
+    num = np.linalg.norm(out_c - out_o, axis=-1)
+    den = np.linalg.norm(out_o, axis=-1)
+    rel = np.where(den > 0, num / np.where(den > 0, den, 1.0), num)
+    return rel, float(np.abs(out_c - out_o).max()) if out_o.size else 0.0

@@ -1,0 +1,121 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad descriptors before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2412_11741_amd as csr
+from paper_2412_11741_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "csr.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return set(re.findall(r"\b(csr_[a-z_]+)\s*\(", text))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = csr.lib()
+    names = _declared_functions()
+    assert names == set(B.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert lib.csr_version() == 100
+
+
+def test_code_bytes_follow_the_papers_accounting():
+    # s * s_n * (index bytes + coefficient bytes); fp16 + int16 -> 4 bytes a pair
+    import torch
+    assert csr.csr_code_bytes(8) == 32 and csr.csr_code_bytes(4, 2) == 32 and csr.csr_code_bytes(16) == 64
+    assert csr.csr_code_bytes(8, 1, torch.int32, torch.float32) == 64
+    assert csr.lib().csr_code_bytes(0, 1, 1, 1) == 0
+
+
+def _enc(**kw):
+    base = dict(H=2, T=100, d=128, N=256, s=8, x_dtype=B.CSR_F16, dict_dtype=B.CSR_F16,
+                coef_dtype=B.CSR_F16, idx_dtype=B.CSR_I16, x_stride_h=0, x_stride_t=0, algo=0, flags=0)
+    base.update(kw)
+    return B.EncodeDesc(**base)
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(H=-1), B.CSR_ERR_INVALID_ARG), (dict(T=-5), B.CSR_ERR_INVALID_ARG),
+    (dict(s=0), B.CSR_ERR_INVALID_ARG), (dict(s=33), B.CSR_ERR_INVALID_ARG),
+    (dict(N=0), B.CSR_ERR_INVALID_ARG), (dict(N=70000), B.CSR_ERR_INVALID_ARG),
+    (dict(x_dtype=7), B.CSR_ERR_INVALID_ARG), (dict(idx_dtype=3), B.CSR_ERR_INVALID_ARG),
+    (dict(flags=1), B.CSR_ERR_INVALID_ARG), (dict(algo=9), B.CSR_ERR_INVALID_ARG),
+    (dict(x_stride_t=100), B.CSR_ERR_INVALID_ARG), (dict(x_stride_t=132), B.CSR_ERR_INVALID_ARG),
+    (dict(x_stride_t=256, x_stride_h=128), B.CSR_ERR_INVALID_ARG),
+    (dict(d=100), B.CSR_ERR_UNSUPPORTED), (dict(dict_dtype=B.CSR_F32), B.CSR_ERR_UNSUPPORTED),
+    (dict(d=64, algo=B.CSR_ENCODE_MFMA), B.CSR_ERR_UNSUPPORTED),
+    (dict(x_dtype=B.CSR_F32, dict_dtype=B.CSR_F32, algo=B.CSR_ENCODE_MFMA), B.CSR_ERR_UNSUPPORTED),
+])
+def test_encode_rejects_bad_descriptors_before_launch(kw, status):
+    lib = csr.lib()
+    d = _enc(**kw)
+    fake = ctypes.c_void_p(0x1000)          # never dereferenced: validation fails first
+    assert lib.csr_encode(ctypes.byref(d), fake, fake, fake, fake, None, 0, None) == status
+    assert csr.last_error() != ""
+    assert lib.csr_encode_workspace_bytes(ctypes.byref(d)) == ctypes.c_size_t(-1).value
+
+
+def test_encode_null_and_misaligned_pointers_and_noop_sizes():
+    lib = csr.lib()
+    d = _enc()
+    ok = ctypes.c_void_p(0x1000)
+    assert lib.csr_encode(None, ok, ok, ok, ok, None, 0, None) == B.CSR_ERR_INVALID_ARG
+    assert lib.csr_encode(ctypes.byref(d), None, ok, ok, ok, None, 0, None) == B.CSR_ERR_INVALID_ARG
+    assert lib.csr_encode(ctypes.byref(d), ctypes.c_void_p(0x1004), ok, ok, ok, None, 0, None) == B.CSR_ERR_INVALID_ARG
+    # empty problems are a no-op and touch nothing, even with NULL pointers
+    assert lib.csr_encode(ctypes.byref(_enc(T=0)), None, None, None, None, None, 0, None) == B.CSR_OK
+    assert lib.csr_encode(ctypes.byref(_enc(H=0)), None, None, None, None, None, 0, None) == B.CSR_OK
+
+
+def _dec(**kw):
+    base = dict(B=2, Hq=8, Hkv=2, T=1000, d=128, N=4096, sK=8, sV=8, scale=0.0, q_dtype=B.CSR_F16,
+                dict_dtype=B.CSR_F16, coef_dtype=B.CSR_F16, idx_dtype=B.CSR_I16, out_dtype=B.CSR_F16, flags=0)
+    base.update(kw)
+    return B.DecodeDesc(**base)
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(B=-1), B.CSR_ERR_INVALID_ARG), (dict(T=-1), B.CSR_ERR_INVALID_ARG),
+    (dict(Hq=7), B.CSR_ERR_INVALID_ARG), (dict(Hkv=0), B.CSR_ERR_INVALID_ARG),
+    (dict(sK=0), B.CSR_ERR_INVALID_ARG), (dict(sV=40), B.CSR_ERR_INVALID_ARG),
+    (dict(N=0), B.CSR_ERR_INVALID_ARG), (dict(N=65537), B.CSR_ERR_INVALID_ARG),
+    (dict(scale=-1.0), B.CSR_ERR_INVALID_ARG), (dict(scale=float("nan")), B.CSR_ERR_INVALID_ARG),
+    (dict(out_dtype=5), B.CSR_ERR_INVALID_ARG), (dict(flags=2), B.CSR_ERR_INVALID_ARG),
+    (dict(d=64), B.CSR_ERR_UNSUPPORTED), (dict(Hq=32, Hkv=2), B.CSR_ERR_UNSUPPORTED),
+    (dict(N=60000, Hq=2), B.CSR_ERR_UNSUPPORTED),
+])
+def test_decode_rejects_bad_descriptors_before_launch(kw, status):
+    lib = csr.lib()
+    d = _dec(**kw)
+    p = ctypes.c_void_p(0x1000)
+    assert lib.csr_decode_attn(ctypes.byref(d), p, p, p, p, p, p, p, None, p, p, 1 << 40, None) == status
+    assert lib.csr_decode_workspace_bytes(ctypes.byref(d)) == ctypes.c_size_t(-1).value
+
+
+def test_decode_workspace_is_required_and_checked():
+    lib = csr.lib()
+    d = _dec()
+    need = lib.csr_decode_workspace_bytes(ctypes.byref(d))
+    assert 0 < need < 1 << 32
+    p = ctypes.c_void_p(0x1000)
+    assert lib.csr_decode_attn(ctypes.byref(d), p, p, p, p, p, p, p, None, p, None, 0, None) == B.CSR_ERR_WORKSPACE
+    assert lib.csr_decode_attn(ctypes.byref(d), p, p, p, p, p, p, p, None, p, p, need - 1, None) == B.CSR_ERR_WORKSPACE
+    assert lib.csr_decode_attn(ctypes.byref(d), p, p, p, p, p, p, p, None, p, ctypes.c_void_p(0x1010), need, None) == B.CSR_ERR_WORKSPACE
+    assert lib.csr_decode_attn(ctypes.byref(d), None, p, p, p, p, p, p, None, p, p, need, None) == B.CSR_ERR_INVALID_ARG
+    assert lib.csr_decode_attn(ctypes.byref(_dec(B=0)), None, None, None, None, None, None, None, None, None, None, 0, None) == B.CSR_OK
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    X = torch.zeros(1, 4, 128, dtype=torch.float16)
+    D = torch.zeros(1, 32, 128, dtype=torch.float16)
+    with pytest.raises(ValueError, match="GPU tensor"):
+        csr.csr_encode(X, D, 4)

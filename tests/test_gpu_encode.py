@@ -1,0 +1,188 @@
+"""GPU parity: csr_encode (through the C ABI) against the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2412_11741_amd as csr
+from paper_2412_11741_amd import synth
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+# Coefficient tolerances: relative to max(|c|, 1e-6 |x|).  fp32 storage: fp32 dot products of 128
+# terms against fp64 (well under 1e-5, bound 1e-3 as the target states).  fp16 storage adds one
+# rounding to 11 bits (2^-11 = 4.9e-4); the oracle value is rounded the same way before comparing,
+# and 1e-3 covers a one-ulp flip at a rounding boundary.
+TOL = 1e-3
+
+ALGOS = {"valu": csr.CSR_ENCODE_VALU, "mfma": csr.CSR_ENCODE_MFMA}
+
+
+def _gpu_encode(X, D, s, algo, coef_dtype=None, idx_dtype=None):
+    Xg, Dg = torch.from_numpy(X).cuda(), torch.from_numpy(D).cuda()
+    idx, coef = csr.csr_encode(Xg, Dg, s, coef_dtype=coef_dtype, idx_dtype=idx_dtype, algo=algo)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), coef.cpu().numpy()
+
+
+def _compare(X, D, s, idx_g, coef_g, heads=None, rows=None):
+    """Oracle on (a subset of) the vectors; returns the merged report."""
+    H = X.shape[0]
+    reports = []
+    for h in (range(H) if heads is None else heads):
+        r = slice(None) if rows is None else rows
+        Xh = X[h][r]
+        idx_o, coef_o, diag = oracle.mp_encode(Xh, D[h], s, diagnostics=True)
+        coef_o_st = coef_o.astype(coef_g.dtype).astype(np.float64)      # storage rounding, RNE
+        rep = parity.check_encode(Xh, D[h], idx_g[h][r], coef_g[h][r], idx_o, coef_o_st, diag, TOL)
+        reports.append(rep)
+    return reports
+
+
+def _assert_ok(reports):
+    for rep in reports:
+        assert rep.ok, rep.summary() + "\n" + "\n".join(rep.failures)
+    total = sum(r.steps for r in reports)
+    exact = sum(r.exact_steps for r in reports)
+    ties = sum(r.tie_vectors for r in reports)
+    print(f"[encode parity] {sum(r.vectors for r in reports)} vectors, {exact}/{total} steps identical, "
+          f"{ties} tie-diverged vectors, max coef err {max(r.max_coef_err for r in reports):.2e}")
+    # ties within 1e-6 are rare events: if more than a handful of vectors diverge, something is off
+    assert ties <= max(2, total // 20000)
+
+
+def test_tiny_config_fp32_full():
+    w = synth.WORKLOADS["tiny"]
+    D = synth.dictionary(0, "dict_k", 1, w.n_atoms, w.d, "f32")
+    X = synth.vectors(0, "keys", 1, w.tokens, w.d, "f32", outliers=w.key_outliers)
+    idx, coef = _gpu_encode(X, D, w.s, csr.CSR_ENCODE_VALU)
+    assert idx.dtype == np.int32 and coef.dtype == np.float32 and idx.shape == (1, 4096, 8)
+    _assert_ok(_compare(X, D, w.s, idx, coef))
+
+
+@pytest.mark.parametrize("algo", ["valu", "mfma"])
+def test_fp16_ragged_tail_several_heads(algo):
+    H, T, N, d, s = 3, 777, 1024, 128, 8
+    D = synth.dictionary(1, "dict_k", H, N, d, "f16")
+    X = synth.vectors(1, "keys", H, T, d, "f16", outliers=8)
+    idx, coef = _gpu_encode(X, D, s, ALGOS[algo])
+    assert idx.dtype == np.int16 and coef.dtype == np.float16
+    _assert_ok(_compare(X, D, s, idx, coef))
+
+
+def test_valu_atom_count_not_a_multiple_of_anything():
+    H, T, N, d, s = 2, 130, 1000 + 3, 128, 6
+    D = synth.dictionary(2, "dict_v", H, N, d, "f16")
+    X = synth.vectors(2, "values", H, T, d, "f16")
+    idx, coef = _gpu_encode(X, D, s, csr.CSR_ENCODE_VALU)
+    _assert_ok(_compare(X, D, s, idx, coef))
+
+
+@pytest.mark.parametrize("d", [32, 64])
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_valu_smaller_head_chunks(d, dtype):
+    H, T, N, s = 2, 200, 256, 4
+    D = synth.dictionary(3, "dict_v", H, N, d, dtype)
+    X = synth.vectors(3, "values", H, T, d, dtype)
+    idx, coef = _gpu_encode(X, D, s, csr.CSR_ENCODE_VALU)
+    _assert_ok(_compare(X, D, s, idx, coef))
+
+
+@pytest.mark.parametrize("algo", ["valu", "mfma"])
+@pytest.mark.parametrize("s", [1, 16, 32])
+def test_iteration_counts(algo, s):
+    H, T, N, d = 1, 192, 512, 128
+    D = synth.dictionary(4, "dict_k", H, N, d, "f16")
+    X = synth.vectors(4, "keys", H, T, d, "f16", outliers=8)
+    idx, coef = _gpu_encode(X, D, s, ALGOS[algo])
+    _assert_ok(_compare(X, D, s, idx, coef))
+
+
+@pytest.mark.parametrize("algo", ["valu", "mfma"])
+def test_orthonormal_dictionary_recovers_top_s_coordinates(algo):
+    # Identity atoms (padded with a second, rotated orthonormal basis so N is a multiple of 32 x 8):
+    # with the identity alone the codes are the s largest |x_k| in order.
+    d, s, T = 128, 8, 256
+    D = np.eye(d, dtype=np.float16)[None]
+    X = synth.vectors(5, "keys", 1, T, d, "f16", outliers=4)
+    # make magnitudes distinct so the order is unique
+    X = (X.astype(np.float32) + np.linspace(0, 0.01, d, dtype=np.float32)).astype(np.float16)
+    idx, coef = _gpu_encode(X, D, s, ALGOS[algo])
+    order = np.argsort(-np.abs(X[0].astype(np.float64)), axis=1, kind="stable")[:, :s]
+    assert np.array_equal(idx[0].view(np.uint16).astype(np.int64), order)
+    assert np.array_equal(coef[0], np.take_along_axis(X[0], order, axis=1))
+
+
+@pytest.mark.parametrize("algo", ["valu", "mfma"])
+def test_degenerate_inputs_zero_vectors_scaled_atoms_single_vector(algo):
+    H, N, d, s = 1, 256, 128, 4
+    D = synth.dictionary(6, "dict_k", H, N, d, "f16")
+    X = np.zeros((1, 3, d), dtype=np.float16)
+    X[0, 1] = D[0, 77] * np.float16(2.0)
+    X[0, 2] = -D[0, 5]
+    idx, coef = _gpu_encode(X, D, s, ALGOS[algo])
+    assert np.all(idx[0, 0] == 0) and np.all(coef[0, 0] == 0) and not np.any(np.isnan(coef.astype(np.float32)))
+    assert idx[0, 1, 0] == 77 and abs(float(coef[0, 1, 0]) - 2.0) < 4e-3
+    assert idx[0, 2, 0] == 5 and abs(float(coef[0, 2, 0]) + 1.0) < 2e-3
+    _assert_ok(_compare(X, D, s, idx, coef))
+    # T = 1
+    idx1, coef1 = _gpu_encode(X[:, 1:2], D, s, ALGOS[algo])
+    assert np.array_equal(idx1[0, 0], idx[0, 1]) and np.array_equal(coef1[0, 0], coef[0, 1])
+
+
+def test_empty_problem_is_a_noop():
+    D = torch.zeros(2, 64, 128, dtype=torch.float16, device="cuda")
+    X = torch.zeros(2, 0, 128, dtype=torch.float16, device="cuda")
+    idx, coef = csr.csr_encode(X, D, 4)
+    assert idx.shape == (2, 0, 4) and coef.shape == (2, 0, 4)
+
+
+@pytest.mark.parametrize("algo", ["valu", "mfma"])
+def test_strided_input_and_storage_types_do_not_change_indices(algo):
+    H, T, N, d, s = 2, 100, 512, 128, 8
+    D = synth.dictionary(7, "dict_k", H, N, d, "f16")
+    X = synth.vectors(7, "keys", H, T, d, "f16", outliers=8)
+    Dg = torch.from_numpy(D).cuda()
+    wide = torch.zeros(H, T, 2 * d, dtype=torch.float16, device="cuda")   # e.g. K and V interleaved
+    wide[:, :, :d] = torch.from_numpy(X).cuda()
+    i16, c16 = csr.csr_encode(wide[:, :, :d], Dg, s, algo=ALGOS[algo])
+    i32, c32 = csr.csr_encode(torch.from_numpy(X).cuda(), Dg, s, coef_dtype=torch.float32,
+                              idx_dtype=torch.int32, algo=ALGOS[algo])
+    torch.cuda.synchronize()
+    # open loop: the residual uses the unrounded coefficient, so storage precision cannot move indices
+    assert np.array_equal(i16.cpu().numpy().view(np.uint16).astype(np.int32), i32.cpu().numpy())
+    assert np.array_equal(c16.cpu().numpy(), c32.cpu().numpy().astype(np.float16))
+    _assert_ok(_compare(X, D, s, i32.cpu().numpy(), c32.cpu().numpy()))
+
+
+@pytest.mark.parametrize("algo", ["valu", "mfma"])
+def test_llama7b_layer_shape_subset(algo):
+    # 4 of the 64 dictionaries (2 key heads with outlier channels, 2 value heads), 512 tokens each.
+    w = synth.WORKLOADS["llama7b_layer"]
+    T = 512
+    DK = synth.dictionary(0, "dict_k", 2, w.n_atoms, w.d, "f16")
+    DV = synth.dictionary(0, "dict_v", 2, w.n_atoms, w.d, "f16")
+    XK = synth.vectors(0, "keys", 2, T, w.d, "f16", outliers=w.key_outliers)
+    XV = synth.vectors(0, "values", 2, T, w.d, "f16")
+    D, X = np.concatenate([DK, DV]), np.concatenate([XK, XV])
+    idx, coef = _gpu_encode(X, D, w.s, ALGOS[algo])
+    _assert_ok(_compare(X, D, w.s, idx, coef))
+
+
+@pytest.mark.parametrize("algo", ["valu", "mfma"])
+def test_llama7b_layer_full_size_sampled(algo):
+    # The benchmark's launch: 64 dictionaries x 4096 vectors in one call; the oracle checks a sample
+    # of 24 vectors from every dictionary (ragged positions, first and last rows included).
+    w = synth.WORKLOADS["llama7b_layer"]
+    DK = synth.dictionary(0, "dict_k", w.hkv, w.n_atoms, w.d, "f16")
+    DV = synth.dictionary(0, "dict_v", w.hkv, w.n_atoms, w.d, "f16")
+    XK = synth.vectors(0, "keys", w.hkv, w.tokens, w.d, "f16", outliers=w.key_outliers)
+    XV = synth.vectors(0, "values", w.hkv, w.tokens, w.d, "f16")
+    D, X = np.concatenate([DK, DV]), np.concatenate([XK, XV])
+    idx, coef = _gpu_encode(X, D, w.s, ALGOS[algo])
+    rows = np.unique(np.concatenate([[0, 63, 64, w.tokens - 1],
+                                     synth.stream(0, "misc", 1).integers(0, w.tokens, 20)]))
+    _assert_ok(_compare(X, D, w.s, idx, coef, rows=rows))
+    # every index in range
+    assert int(idx.view(np.uint16).max()) < w.n_atoms
