@@ -1,0 +1,190 @@
+"""Benchmark of the CSR hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input, inputs resident in HBM:
+  1. Matching Pursuit encode of one layer's keys and values (csr_encode, 64 dictionaries x 4096
+     vectors at the Llama-7B-shaped workload), producing (index, coefficient) codes;
+  2. decode attention of one query token per head on those codes (csr_decode_attn).
+Prints ONE JSON line.  `value` is encoded KV vectors per second over the whole step; the decode
+rate (context tokens per second) and both rooflines are reported beside it, together with the CPU
+oracle timed on this machine's host cores on a bounded sample.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama7b_layer] [--algo auto]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_F16_TFLOPS = 2500.0   # MI355X dense fp16 matrix peak
+PEAK_VALU_F32_TFLOPS = 157.3    # MI355X fp32 vector peak
+PEAK_HBM_GBS = 8000.0           # MI355X HBM3E peak
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama7b_layer")
+    ap.add_argument("--algo", default="auto", choices=["auto", "valu", "mfma"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cold-copies", type=int, default=16,
+                    help="distinct input copies rotated through for the cache-cold decode figure")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is a single-GPU kernel path; run it with --gpus 1 "
+              "(there is no sharded or multi-rank mode to measure)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2412_11741_amd as csr
+    from paper_2412_11741_amd import synth
+
+    w = synth.WORKLOADS[args.workload]
+    if w.layers != 1:
+        print("bench.py: only single-layer workloads are benchmark lines", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    algo = {"auto": csr.CSR_ENCODE_AUTO, "valu": csr.CSR_ENCODE_VALU, "mfma": csr.CSR_ENCODE_MFMA}[args.algo]
+    tdt = torch.float16 if w.dtype == "f16" else torch.float32
+    tit = torch.int16 if w.itype == "i16" else torch.int32
+
+    # ---- synthetic inputs (host-generated, then resident on the GPU) ---------------------------
+    B, Hkv, Hq, T, N, d, s = w.batch, w.hkv, w.hq, w.tokens, w.n_atoms, w.d, w.s
+    DK = synth.dictionary(0, "dict_k", Hkv, N, d, w.dtype)
+    DV = synth.dictionary(0, "dict_v", Hkv, N, d, w.dtype)
+    q_h = synth.queries(0, B, Hq, d, w.dtype)
+    # vectors of sequence b, KV head h live at row b*Hkv + h; keys first, then values
+    XK = np.concatenate([synth.vectors(0, "keys", Hkv, T, d, w.dtype, outliers=w.key_outliers, token0=b)
+                         for b in range(B)])
+    XV = np.concatenate([synth.vectors(0, "values", Hkv, T, d, w.dtype, token0=b) for b in range(B)])
+    X_h = np.concatenate([XK, XV])
+    D_h = np.concatenate([np.tile(DK, (B, 1, 1)), np.tile(DV, (B, 1, 1))])
+    X, D = torch.from_numpy(X_h).to(dev), torch.from_numpy(D_h).to(dev)
+    DKg, DVg, q = torch.from_numpy(DK).to(dev), torch.from_numpy(DV).to(dev), torch.from_numpy(q_h).to(dev)
+    H = X.shape[0]
+    n_vec = H * T
+    idx = torch.empty((H, T, s), dtype=tit, device=dev)
+    coef = torch.empty((H, T, s), dtype=tdt, device=dev)
+    out = torch.empty((B, Hq, d), dtype=tdt, device=dev)
+    edesc = csr.encode_desc(X, D, s, tdt, tit, algo)
+    ews = csr.csr_encode_workspace_bytes(edesc)
+    enc_ws = torch.empty(max(ews, 256), dtype=torch.uint8, device=dev)
+    nkv = B * Hkv
+    idxK, coefK = idx[:nkv].view(B, Hkv, T, s), coef[:nkv].view(B, Hkv, T, s)
+    idxV, coefV = idx[nkv:].view(B, Hkv, T, s), coef[nkv:].view(B, Hkv, T, s)
+    ddesc = csr.decode_desc(q, DKg, idxK, coefK, idxV)
+    dec_ws = torch.empty(max(csr.csr_decode_workspace_bytes(ddesc), 256), dtype=torch.uint8, device=dev)
+
+    def encode():
+        csr.csr_encode(X, D, s, tdt, tit, algo, idx=idx, coef=coef, workspace=enc_ws if ews else None)
+
+    def decode(qq=q, dk=DKg, dv=DVg, ik=idxK, ck=coefK, iv=idxV, cv=coefV, o=out):
+        csr.csr_decode_attn(qq, dk, ik, ck, dv, iv, cv, out=o, workspace=dec_ws)
+
+    for _ in range(args.warmup):
+        encode(); decode()
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly `steps` passes ---------------------------------------------------
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ev[i][0].record()
+        encode()
+        ev[i][1].record()
+        decode()
+        ev[i][2].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_step = wall * 1e3 / args.steps
+    enc_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
+    dec_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
+
+    # ---- cache-cold decode: rotate distinct copies so nothing is served from the Infinity Cache --
+    code_b = csr.csr_code_bytes(s, 1, tit, tdt)
+    dict_b = 2 if w.dtype == "f16" else 4
+    dec_bytes = B * Hkv * T * 2 * code_b + Hkv * 2 * N * d * dict_b + B * Hq * d * 2 * dict_b
+    copies = max(1, args.cold_copies)
+    while copies > 1 and copies * dec_bytes > 24e9:
+        copies //= 2
+    sets = []
+    for c in range(copies):
+        sets.append(dict(qq=q.clone(), dk=DKg.clone(), dv=DVg.clone(), ik=idxK.clone(), ck=coefK.clone(),
+                         iv=idxV.clone(), cv=coefV.clone(), o=torch.empty_like(out)))
+    for c in range(copies):
+        decode(**sets[c])
+    torch.cuda.synchronize()
+    reps = max(copies, 2 * copies if dec_bytes * copies < 4e9 else copies)
+    cev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for r in range(reps):
+        cev[r][0].record()
+        decode(**sets[r % copies])
+        cev[r][1].record()
+    torch.cuda.synchronize()
+    dec_cold_ms = sum(a.elapsed_time(b) for a, b in cev) / reps
+    del sets
+
+    enc_flop = 2.0 * d * N * s * n_vec
+    enc_tflops = enc_flop / (enc_ms * 1e-3) / 1e12
+    uses_mfma = args.algo != "valu" and ews > 0
+    roofline = {"kernel": "csr_encode (%s)" % ("mfma" if uses_mfma else "valu"),
+                "bound": "mfma", "achieved": round(enc_tflops, 3), "peak": PEAK_MFMA_F16_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(enc_tflops / PEAK_MFMA_F16_TFLOPS, 5), "traffic": None,
+                "flop_per_vector": 2.0 * d * N * s, "avg_launch_ms": round(enc_ms, 4)}
+    dec_gbs = dec_bytes / (dec_cold_ms * 1e-3) / 1e9
+    roofline_decode = {"kernel": "csr_decode_attn (4 launches), cache-cold", "bound": "hbm",
+                       "achieved": round(dec_gbs, 2), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                       "frac": round(dec_gbs / PEAK_HBM_GBS, 5), "traffic": None,
+                       "bytes_per_call": dec_bytes, "avg_call_ms": round(dec_cold_ms, 5),
+                       "warm_call_ms": round(dec_ms, 5), "copies_rotated": copies}
+
+    result = {
+        "metric": "MP-encoded KV vectors/sec over the whole step (encode K+V, then decode attention on the codes)",
+        "value": round(n_vec / (ms_step * 1e-3), 1), "unit": "vectors/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16" if uses_mfma else "f32", "data": "synthetic",
+        "config": {"workload": w.name, "kv_heads": Hkv, "query_heads": Hq, "head_dim": d, "atoms": N,
+                   "tokens_per_head": T, "s": s, "decode_batch": B, "vectors_per_step": n_vec,
+                   "storage": f"{w.dtype}+{w.itype}", "encode_algo": args.algo},
+        "encode_vectors_per_s": round(n_vec / (enc_ms * 1e-3), 1), "encode_ms": round(enc_ms, 4),
+        "decode_ctx_tokens_per_s": round(B * T / (dec_cold_ms * 1e-3), 1),
+        "decode_ctx_tokens_per_s_warm": round(B * T / (dec_ms * 1e-3), 1),
+        "decode_ms_cold": round(dec_cold_ms, 5), "decode_ms_warm": round(dec_ms, 5),
+        "roofline": roofline, "roofline_decode": roofline_decode,
+    }
+
+    # ---- CPU oracle on a bounded sample of the same workload ---------------------------------------
+    if not args.no_cpu_baseline:
+        import oracle
+        per_dict = max(1, 131072 // H)   # ~10-15 s of oracle work on 16 host threads
+        t1 = time.perf_counter()
+        for h in range(H):
+            oracle.mp_encode(X_h[h, :per_dict], D_h[h], s)
+        cpu_enc = time.perf_counter() - t1
+        ik_h, ck_h = idxK.cpu().numpy(), coefK.cpu().numpy()
+        iv_h, cv_h = idxV.cpu().numpy(), coefV.cpu().numpy()
+        t1 = time.perf_counter()
+        oracle.decode_attn(q_h[:1], DK, ik_h[:1], ck_h[:1], DV, iv_h[:1], cv_h[:1])
+        cpu_dec = time.perf_counter() - t1
+        result["cpu_baseline"] = {
+            "value": round(H * per_dict / cpu_enc, 1), "unit": "vectors/s", "cores": oracle.max_threads(),
+            "kind": "oracle",
+            "sample": f"encode: first {per_dict} vectors of each of the {H} dictionaries "
+                      f"({H * per_dict} vectors, {cpu_enc:.1f} s); decode: sequence 0, all {Hq} heads "
+                      f"({T} tokens, {cpu_dec:.2f} s)",
+            "decode_ctx_tokens_per_s": round(T / cpu_dec, 1)}
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
