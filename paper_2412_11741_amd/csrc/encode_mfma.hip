@@ -11,36 +11,41 @@
 //            Every vector is first multiplied by a power of two that brings its largest |x_k| into
 //            [2^11, 2^12): Matching Pursuit commutes exactly with such a scaling (the coefficient is
 //            scaled back on store), nothing can leave the fp16 range (|R_k| <= |R| <= |x| < 2^15.5)
-//            and lo never lands in the fp16 subnormals.
+//            and lo stays clear of the fp16 subnormals.
 //   screen   c^[n] = hi . d_n, one v_mfma_f32_32x32x16_f16 sweep over the dictionary.
-//            |c^[n] - R . d_n| <= |lo| |d_n| + accumulation error, so the atom of largest true
-//            |correlation| lies within `delta` of the largest screened value.  The epilogue keeps,
-//            per lane, the three largest GROUP maxima of the sweep (a group = the 16 atoms one lane
-//            holds of one 32x32 output tile), with the tile number packed into the low mantissa bits
-//            so that one integer max/med3/min chain tracks value and position together.
-//   select   the (at most three) groups within delta of the best are re-scored exactly: products of
-//            fp16 pairs are exact in fp32 (v_dot2_f32_f16), hi and lo parts summed separately, the
-//            two lanes that share a token each doing half of the 128 dimensions.  The exact arg-max
-//            (lowest index on ties) and its signed projection are the iteration's pair.
-//   update   R -= c d in fp32 (Eq.4), new hi / lo split, new delta.
-//   overflow if more groups than tracked could matter (degenerate dictionaries, atoms far from unit
-//            norm) the token is flagged and re-encoded afterwards by an exact fp32 kernel, one
-//            workgroup per flagged token.  On Gaussian-like data that is about 1e-3 of the vectors.
+//            |c^[n] - R . d_n| <= |lo| |d_n| + accumulation error =: delta / 2, so the atom of
+//            largest true |correlation| lies within delta of the largest screened value.  The
+//            epilogue keeps, per lane, the four largest GROUP maxima of the sweep (a group = the 16
+//            atoms one lane holds of one 32x32 output tile), with the tile number packed into the
+//            low mantissa bits so that one integer max/med3 chain tracks value and position.
+//   select   the best group is re-scored on the vector ALU (v_dot2_f32_f16 on hi, the two lanes
+//            that share a token each doing half of the 128 dimensions).  If its best atom leads
+//            every other atom of the group by more than delta and no other tracked group comes
+//            within delta of it, that atom is the iteration's pick (about 97 % of the steps on
+//            Gaussian-like data).  Otherwise the wave resolves the token together: the residual
+//            goes through LDS to all 64 lanes, which evaluate hi . d + lo . d (products of fp16
+//            pairs are exact in fp32) for every atom of every candidate group and take the largest,
+//            lowest index on ties.  Should even the fourth tracked group of a lane be a candidate
+//            (about 1e-5 of the steps), untracked groups could matter too, and the wave evaluates
+//            all N atoms that way.
+//   update   c = (hi + lo) . d exactly, R -= c d in fp32 (Eq.4), new hi / lo split, new delta.
 //
 // Orientation: atoms are the M rows of the MFMA (A operand = dictionary tile from LDS), tokens the
 // N columns (B operand = hi, held in registers for the whole sweep).  Each lane therefore owns one
-// token column and 16 atom rows per tile, and the running maxima never leave its registers.
-// A wave owns 2 x 32 tokens so that every A fragment read from LDS feeds two MFMAs.  Dictionary
-// stages go from global memory straight into LDS (global_load_lds_dwordx4), XOR-swizzled so that the
-// 16-byte fragment reads are bank-conflict free.  Two 4-wave workgroups share a CU (two waves per
-// SIMD), so one workgroup's select/update phase overlaps the other's MFMA sweep.
+// token column and 16 atom rows per tile, and the running maxima never leave its registers.  The
+// contraction index is permuted so that lane half 0 holds dimensions 0..63 and half 1 holds 64..127
+// (any order is valid as long as both operands use it): vector and atom rows are then read as 128
+// contiguous bytes per lane.  A wave owns 2 x 32 tokens so that every A fragment read from LDS feeds
+// two MFMAs.  Dictionary stages (128 atoms, 32 KiB) go from global memory straight into LDS
+// (global_load_lds_dwordx4), double-buffered, 16-byte chunks XOR-swizzled by the row number so that
+// 16 consecutive rows read at the same logical chunk cover all LDS banks.  Two 4-wave workgroups
+// share a CU (two waves per SIMD), so one workgroup's select / update phase (vector ALU, gathers)
+// overlaps the other's sweep (matrix cores).
 #include <cstdio>
 #include <cstdlib>
+#include <type_traits>
 
 #include "csr_internal.h"
-#ifndef CSR_DBG
-#define CSR_DBG 0
-#endif
 
 namespace csr {
 namespace {
@@ -55,17 +60,29 @@ constexpr int kWavesPerWG = 4;
 constexpr int kThreads = 64 * kWavesPerWG;            // 256
 constexpr int kTokPerWave = 32 * kBlocks;             // 64
 constexpr int kTokPerWG = kWavesPerWG * kTokPerWave;  // 256
-constexpr int kStageAtoms = 64;                       // atoms per LDS stage (two 32-row tiles)
-constexpr int kStageBytes = kStageAtoms * kD * 2;     // 16 KiB, rows unpadded, chunks XOR-swizzled
+constexpr int kStageTiles = 4;                        // 32-atom tiles per LDS stage
+constexpr int kStageAtoms = 32 * kStageTiles;         // 128
+constexpr int kStageBytes = kStageAtoms * kD * 2;     // 32 KiB, rows unpadded, chunks XOR-swizzled
+constexpr int kScratchPerWave = 1024;                 // LDS a wave uses to share one token's state
+constexpr int kLdsBytes = 2 * kStageBytes + kWavesPerWG * kScratchPerWave;
+constexpr int kTrack = 4;                             // group maxima tracked per lane and sweep
 constexpr int kNormSlices = 8;                        // workgroups per dictionary in the norm pre-pass
-constexpr float kGammaAcc = 7.7e-6f;  // fp32 accumulation error of a 128-term MFMA dot, relative to |hi||d|
-constexpr float kNormSafe = 6.0e4f;   // a residual norm beyond this could leave the fp16 range
-constexpr int kFallbackGrid = 1024;
+// fp32 accumulation error of a 128-term dot product of exact fp16 products, relative to |hi||d|:
+// 129 roundings of at most 2^-23 each (this also covers accumulators that truncate).
+constexpr float kGammaAcc = 1.6e-5f;
 
 __device__ __forceinline__ uint32_t umed3(uint32_t a, uint32_t b, uint32_t c)
 {
     return max(min(a, b), min(max(a, b), c));
 }
+
+// value of the other lane of the pair (lane ^ 32)
+__device__ __forceinline__ uint32_t xchg32(uint32_t v, int hf)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return hf ? r[0] : r[1];
+}
+__device__ __forceinline__ float xchg32f(float v, int hf) { return __uint_as_float(xchg32(__float_as_uint(v), hf)); }
 
 __device__ __forceinline__ void unpack8(const uint4 &raw, float (&f)[8])
 {
@@ -80,46 +97,47 @@ __device__ __forceinline__ void unpack8(const uint4 &raw, float (&f)[8])
 
 __device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-// One dictionary stage (64 atoms x 256 B) from global memory into an LDS buffer, no registers in
-// between.  Each wave instruction fills 1 KiB = 4 rows; lane l lands at byte 16 l of that KiB, i.e.
-// row l/16, chunk position l%16, and fetches source chunk position ^ (row & 7).
-__device__ __forceinline__ void issue_stage(const __half *__restrict__ Dh, int stage, unsigned char *buf,
-                                            int wave, int lane)
+// LDS traffic inside one wave needs no barrier (the LDS executes a wave's instructions in order),
+// only that the compiler keeps the order and waits for the data.
+__device__ __forceinline__ void wave_lds_fence()
 {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int blk = i * kWavesPerWG + wave;            // which KiB of the stage
-        const int row = blk * 4 + (lane >> 4);
-        const int ch = (lane & 15) ^ (row & 7);
-        const __half *src = Dh + ((int64_t)stage * kStageAtoms + row) * kD + ch * 8;
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                         (__attribute__((address_space(3))) void *)(buf + blk * 1024), 16, 0, 0);
-    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
 }
 
-// Exact partial correlation over this lane's half of the dimensions (k = 16 j + 8 hf + e) of the
-// residual hi + lo with one atom row.
-__device__ __forceinline__ float half_dot(const __half *__restrict__ row, int hf, const half8 (&hi)[8],
-                                          const half8 (&lo)[8])
+// 8 dimensions of a dot product: a (fp16 x 8) . d (fp16 x 8), two fp32 accumulators
+__device__ __forceinline__ void dot8(const half8 &a, const half8 &d, float &s0, float &s1)
 {
-    float a0 = 0.0f, a1 = 0.0f, b0 = 0.0f, b1 = 0.0f;
+    s0 = __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 0, 1), __builtin_shufflevector(d, d, 0, 1), s0, false);
+    s1 = __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 2, 3), __builtin_shufflevector(d, d, 2, 3), s1, false);
+    s0 = __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 4, 5), __builtin_shufflevector(d, d, 4, 5), s0, false);
+    s1 = __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 6, 7), __builtin_shufflevector(d, d, 6, 7), s1, false);
+}
+
+// One dictionary stage (128 atoms x 256 B) from global memory into an LDS buffer, no registers in
+// between.  Each wave instruction fills 1 KiB = 4 rows; lane l lands at byte 16 l of that KiB, i.e.
+// row l/16, chunk position l%16, and fetches source chunk position ^ (row & 15).  A wave's
+// instructions are 16 rows apart, so that XOR term is the same for all of them and the source is
+// (uniform stage base + 4 KiB steps) + one per-lane offset, `lane_off` = stage_lane_offset().
+// Rows past the dictionary's end are not fetched; the sweep never reads those tiles.
+__device__ __forceinline__ uint32_t stage_lane_offset(int wave, int lane)
+{
+    const int row0 = wave * 4 + (lane >> 4);
+    return (uint32_t)(row0 * kD * 2 + (((lane & 15) ^ (row0 & 15)) << 4));
+}
+
+__device__ __forceinline__ void issue_stage(const __half *__restrict__ Dh, int stage, int32_t N, unsigned char *buf,
+                                            int wave, int lane, uint32_t lane_off)
+{
+    const unsigned char *sbase = reinterpret_cast<const unsigned char *>(Dh) + (int64_t)stage * kStageBytes;
+    const int rows_left = N - stage * kStageAtoms - (wave * 4 + (lane >> 4));  // > 0 for the rows that exist
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const uint4 raw = *reinterpret_cast<const uint4 *>(row + 16 * j + 8 * hf);
-        const half8 dv = *reinterpret_cast<const half8 *>(&raw);
-        const half2v d0 = __builtin_shufflevector(dv, dv, 0, 1), d1 = __builtin_shufflevector(dv, dv, 2, 3),
-                     d2 = __builtin_shufflevector(dv, dv, 4, 5), d3 = __builtin_shufflevector(dv, dv, 6, 7);
-        const half8 h = hi[j], l = lo[j];
-        a0 = __builtin_amdgcn_fdot2(__builtin_shufflevector(h, h, 0, 1), d0, a0, false);
-        a1 = __builtin_amdgcn_fdot2(__builtin_shufflevector(h, h, 2, 3), d1, a1, false);
-        a0 = __builtin_amdgcn_fdot2(__builtin_shufflevector(h, h, 4, 5), d2, a0, false);
-        a1 = __builtin_amdgcn_fdot2(__builtin_shufflevector(h, h, 6, 7), d3, a1, false);
-        b0 = __builtin_amdgcn_fdot2(__builtin_shufflevector(l, l, 0, 1), d0, b0, false);
-        b1 = __builtin_amdgcn_fdot2(__builtin_shufflevector(l, l, 2, 3), d1, b1, false);
-        b0 = __builtin_amdgcn_fdot2(__builtin_shufflevector(l, l, 4, 5), d2, b0, false);
-        b1 = __builtin_amdgcn_fdot2(__builtin_shufflevector(l, l, 6, 7), d3, b1, false);
+    for (int i = 0; i < kStageAtoms / (4 * kWavesPerWG); ++i) {
+        if (16 * i < rows_left)
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void *)(sbase + i * 4096 + lane_off),
+                (__attribute__((address_space(3))) void *)(buf + (i * kWavesPerWG + wave) * 1024), 16, 0, 0);
     }
-    return (a0 + a1) + (b0 + b1);
 }
 
 // dnorm[h][slice] = max over the slice's atoms of |d_n|_2: the screening bound scales with it.
@@ -148,21 +166,98 @@ __global__ __launch_bounds__(256) void dict_norm_kernel(const __half *__restrict
     if (tid == 0) dnorm[h * kNormSlices + sl] = sqrtf(fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3])));
 }
 
+// The whole wave resolves ONE token whose pick the fast path could not decide.  `scr` holds that
+// token's state, written by its two owner lanes:
+//   [0, 256)    hi, dimensions in order        [256, 512)  lo
+//   [512, 544)  tracked group values, lane half 0 then half 1
+//   [544, 552)  threshold bits, overflow flag
+// Lane (a = lane / 4, q = lane % 4) evaluates atom a of a 16-atom group over dimensions 32 q .. 32 q + 31.
+// Returns the arg-max of |hi . d + lo . d| (lowest index on ties) over the candidate groups, or over
+// all atoms when the overflow flag is set.
+__device__ __forceinline__ int resolve_token(const __half *__restrict__ Dh, int32_t N, int ntiles, uint32_t code_mask,
+                                             const unsigned char *scr, int lane)
+{
+    const int a = lane >> 2, q = lane & 3;
+    half8 th[4], tl[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        th[j] = *reinterpret_cast<const half8 *>(scr + q * 64 + j * 16);
+        tl[j] = *reinterpret_cast<const half8 *>(scr + 256 + q * 64 + j * 16);
+    }
+    const uint2 tf = *reinterpret_cast<const uint2 *>(scr + 544);
+    const uint32_t thr_bits = __builtin_amdgcn_readfirstlane(tf.x);
+    const bool ovf = __builtin_amdgcn_readfirstlane(tf.y) != 0;
+
+    float ba = -1.0f;
+    int bn = 0;
+    // `batch` atoms at a time: all their rows are requested before the first product waits
+    auto eval = [&](const int (&n)[2], int batch) {
+        uint4 raw[2][4];
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            if (b < batch) {
+                const __half *row = Dh + (int64_t)n[b] * kD + q * 32;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) raw[b][j] = *reinterpret_cast<const uint4 *>(row + 8 * j);
+            }
+        }
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            if (b < batch) {
+                float s0 = 0.0f, s1 = 0.0f, l0 = 0.0f, l1 = 0.0f;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const half8 dv = *reinterpret_cast<const half8 *>(&raw[b][j]);
+                    dot8(th[j], dv, s0, s1);
+                    dot8(tl[j], dv, l0, l1);
+                }
+                float c = (s0 + s1) + (l0 + l1);
+                c += __shfl_xor(c, 1, 64);
+                c += __shfl_xor(c, 2, 64);
+                const float ab = fabsf(c);
+                if (ab > ba || (ab == ba && n[b] < bn)) { ba = ab; bn = n[b]; }
+            }
+        }
+    };
+    if (!ovf) {
+#pragma unroll 1
+        for (int e = 0; e < 2 * kTrack; ++e) {
+            const uint32_t u = __builtin_amdgcn_readfirstlane(*reinterpret_cast<const uint32_t *>(scr + 512 + 4 * e));
+            if (u < thr_bits) continue;
+            const int tile = ntiles - 1 - (int)(u & code_mask);
+            const int n[2] = {tile * 32 + 4 * (e / kTrack) + 8 * (a >> 2) + (a & 3), 0};
+            eval(n, 1);
+        }
+    } else {
+        int n0 = 0;
+#pragma unroll 1
+        for (; n0 < N; n0 += 32) {
+            const int n[2] = {n0 + a, n0 + 16 + a};
+            eval(n, 2);
+        }
+    }
+#pragma unroll
+    for (int m = 4; m <= 32; m <<= 1) {
+        const float oa = __shfl_xor(ba, m, 64);
+        const int on = __shfl_xor(bn, m, 64);
+        if (oa > ba || (oa == ba && on < bn)) { ba = oa; bn = on; }
+    }
+    return __builtin_amdgcn_readfirstlane(bn);
+}
+
 __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
     const __half *__restrict__ X, const __half *__restrict__ Dict, void *__restrict__ idx_out,
-    void *__restrict__ coef_out, const float *__restrict__ dnorm, unsigned long long *__restrict__ flags,
-    int64_t T, int32_t N, int32_t s, int64_t x_stride_h, int64_t x_stride_t, int32_t tiles_per_h,
-    int32_t n_groups, int32_t idx16, int32_t coef16, uint32_t code_mask, int32_t stagger_cus)
+    void *__restrict__ coef_out, const float *__restrict__ dnorm, int64_t T, int32_t N, int32_t s,
+    int64_t x_stride_h, int64_t x_stride_t, int32_t tiles_per_h, int32_t n_groups, int32_t idx16, int32_t coef16,
+    uint32_t code_mask, int32_t first_round)
 {
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * kStageBytes];
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, hf = lane >> 5;
-#if CSR_DBG == 3
-    const unsigned long long dbg_t0 = __builtin_readcyclecounter();
-#endif
+    unsigned char *scr = lds + 2 * kStageBytes + wave * kScratchPerWave;
 
     // Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous run of work so
     // that workgroups sharing a dictionary share an L2.
@@ -172,24 +267,33 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
     const int tile_wg = work - h * tiles_per_h;
     const __half *Dh = Dict + (int64_t)h * N * kD;
     const int ntiles = N >> 5;
-    const int nstages = N / kStageAtoms;
+    const int nstages = (N + kStageAtoms - 1) / kStageAtoms;
 
-    issue_stage(Dh, 0, lds, wave, lane);  // in flight while the vectors are loaded
+    const uint32_t lane_off = stage_lane_offset(wave, lane);
+    issue_stage(Dh, 0, N, lds, wave, lane, lane_off);  // in flight while the vectors are loaded
+    // LDS byte offset, inside a 32-row tile, of this lane's A fragment j (row = col, chunk 8 hf + j)
+    uint32_t frag_off[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) frag_off[j] = (uint32_t)(col * kD * 2 + (((hf * 8 + j) ^ (col & 15)) << 4));
 
     // Two workgroups share a CU.  Started together they would sweep together and select together;
-    // holding back every second wave of workgroups by about half an iteration makes one's select
-    // phase (vector ALU, gathers) fall into the other's sweep (matrix cores).
-    bool hold = false;
-    if (stagger_cus > 0) hold = (blockIdx.x / stagger_cus) & 1;
-    else if (stagger_cus == -2) hold = (blockIdx.x >> 3) & 1;
-    else if (stagger_cus == -3) hold = ((blockIdx.x >> 3) / 32) & 1;
-    if (hold) {
-        for (int i = 0; i < nstages; ++i) __builtin_amdgcn_s_sleep(32);
+    // holding back the one in the odd wave slot by about half a sweep makes one's select phase
+    // (vector ALU, gathers) fall into the other's sweep (matrix cores).  Only the workgroups that
+    // start with the kernel need this; later ones start whenever a slot frees up.
+    if ((int)blockIdx.x < first_round) {
+        // HW_ID bits 3:0 = this wave's slot on its SIMD; a workgroup waits for its slowest wave anyway
+        if (__builtin_amdgcn_s_getreg(0xF804) & 1) {
+            for (int i = 0; i < nstages; ++i) __builtin_amdgcn_s_sleep(32);
+        }
     }
 
     float dmax = 0.0f;
 #pragma unroll
     for (int i = 0; i < kNormSlices; ++i) dmax = fmaxf(dmax, dnorm[h * kNormSlices + i]);
+    // ~code_mask in a vector register, so that packing value and tile code is one instruction with
+    // the code as its only scalar operand
+    uint32_t keep_mask;
+    asm volatile("v_mov_b32 %0, %1" : "=v"(keep_mask) : "s"(~code_mask));
     // relative slack of a packed value: its low mantissa bits were replaced by the tile code
     const float pack_q = (float)(code_mask + 1) * 1.1920929e-7f;
 
@@ -204,17 +308,17 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
         tok[bi] = (int64_t)tile_wg * kTokPerWG + wave * kTokPerWave + bi * 32 + col;
         valid[bi] = tok[bi] < T;
         const int64_t tc = valid[bi] ? tok[bi] : T - 1;
-        const __half *xr = X + (int64_t)h * x_stride_h + tc * x_stride_t;
+        const __half *xr = X + (int64_t)h * x_stride_h + tc * x_stride_t + hf * 64;
         float xv[8][8];
         float amax = 0.0f;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const uint4 raw = *reinterpret_cast<const uint4 *>(xr + 16 * j + 8 * hf);
+            const uint4 raw = *reinterpret_cast<const uint4 *>(xr + 8 * j);
             unpack8(raw, xv[j]);
 #pragma unroll
             for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(xv[j][e]));
         }
-        amax = fmaxf(amax, __shfl_xor(amax, 32, 64));
+        amax = fmaxf(amax, xchg32f(amax, hf));
         int ex = 0;
         if (amax > 0.0f && amax < INFINITY) {
             (void)frexpf(amax, &ex);  // amax = f 2^ex, f in [0.5, 1)
@@ -238,257 +342,231 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
             hi[bi][j] = hv;
             lo[bi][j] = lv;
         }
-        r2 += __shfl_xor(r2, 32, 64);
-        lo2 += __shfl_xor(lo2, 32, 64);
+        r2 += xchg32f(r2, hf);
+        lo2 += xchg32f(lo2, hf);
         rn2[bi] = r2;
         delta[bi] = 2.0f * dmax * (sqrtf(lo2) + kGammaAcc * sqrtf(r2));
     }
 
-    unsigned long long flag_acc = 0ull;  // wave-uniform: bit (32 bi + col) = token needs the exact kernel
-
     for (int g = 0; g < s; ++g) {
         // ---- screen: one MFMA sweep over the dictionary ------------------------------------
-        uint32_t u1[kBlocks], u2[kBlocks], u3[kBlocks];
+        uint32_t u[kBlocks][kTrack];
 #pragma unroll
-        for (int bi = 0; bi < kBlocks; ++bi) u1[bi] = u2[bi] = u3[bi] = 0u;
+        for (int bi = 0; bi < kBlocks; ++bi)
+#pragma unroll
+            for (int k = 0; k < kTrack; ++k) u[bi][k] = 0u;
 
         wait_vmem();
         __syncthreads();  // stage 0 is in buffer 0
 
-#if CSR_DBG == 2
-        for (int st = 0; st < 1; ++st) {
-#else
-        for (int st = 0; st < nstages; ++st) {
-#endif
-            const unsigned char *buf = lds + (st & 1) * kStageBytes;
-            if (st + 1 < nstages) issue_stage(Dh, st + 1, lds + ((st + 1) & 1) * kStageBytes, wave, lane);
+        // one stage: fetch the next one into the other buffer, sweep this one's tiles, meet the others
+        auto do_stage = [&](int st, auto buf_c) {
+            constexpr int kBuf = decltype(buf_c)::value;
+            if (st + 1 < nstages) issue_stage(Dh, st + 1, N, lds + (1 - kBuf) * kStageBytes, wave, lane, lane_off);
+            const int tiles_here = min(kStageTiles, ntiles - st * kStageTiles);
 #pragma unroll
-            for (int rt = 0; rt < 2; ++rt) {
-                floatx16 acc[kBlocks];
-#pragma unroll
-                for (int bi = 0; bi < kBlocks; ++bi)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[bi][r] = 0.0f;
-                const unsigned char *rowp = buf + (rt * 32 + col) * (kD * 2);
-                half8 a[8];  // all fragments of the row tile requested before the first MFMA waits
-#pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    a[j] = *reinterpret_cast<const half8 *>(rowp + (((2 * j + hf) ^ (col & 7)) << 4));
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
+            for (int rt = 0; rt < kStageTiles; ++rt) {
+                if (rt < tiles_here) {
+                    floatx16 acc[kBlocks];
 #pragma unroll
                     for (int bi = 0; bi < kBlocks; ++bi)
-                        acc[bi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[j], hi[bi][j], acc[bi], 0, 0, 0);
-                }
-                const uint32_t code = (uint32_t)(ntiles - 1 - (st * 2 + rt));  // earlier tile = larger code
 #pragma unroll
-                for (int bi = 0; bi < kBlocks; ++bi) {
-                    float m = fmaxf(fmaxf(fabsf(acc[bi][0]), fabsf(acc[bi][1])), fabsf(acc[bi][2]));
+                        for (int r = 0; r < 16; ++r) acc[bi][r] = 0.0f;
+                    half8 a[8];  // all fragments of the row tile requested before the first MFMA waits
 #pragma unroll
-                    for (int r = 3; r < 15; r += 2) m = fmaxf(fmaxf(m, fabsf(acc[bi][r])), fabsf(acc[bi][r + 1]));
-                    m = fmaxf(m, fabsf(acc[bi][15]));
-                    const uint32_t u = (__float_as_uint(m) & ~code_mask) | code;
-                    const uint32_t n3 = max(u3[bi], min(u2[bi], u));
-                    const uint32_t n2 = umed3(u1[bi], u2[bi], u);
-                    u1[bi] = max(u1[bi], u);
-                    u2[bi] = n2;
-                    u3[bi] = n3;
+                    for (int j = 0; j < 8; ++j)
+                        a[j] = *reinterpret_cast<const half8 *>(lds + kBuf * kStageBytes + rt * 32 * kD * 2 + frag_off[j]);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+#pragma unroll
+                        for (int bi = 0; bi < kBlocks; ++bi)
+                            acc[bi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[j], hi[bi][j], acc[bi], 0, 0, 0);
+                    }
+                    const uint32_t code = (uint32_t)(ntiles - 1 - (st * kStageTiles + rt));  // earlier tile = larger code
+#pragma unroll
+                    for (int bi = 0; bi < kBlocks; ++bi) {
+                        float m = 0.0f;  // eight v_max3_f32 with |.| operand modifiers
+#pragma unroll
+                        for (int r = 0; r < 16; r += 2) m = fmaxf(fmaxf(m, fabsf(acc[bi][r])), fabsf(acc[bi][r + 1]));
+                        const uint32_t v = (__float_as_uint(m) & keep_mask) | code;  // one v_and_or_b32
+                        const uint32_t n3 = umed3(u[bi][2], u[bi][3], v);
+                        const uint32_t n2 = umed3(u[bi][1], u[bi][2], v);
+                        const uint32_t n1 = umed3(u[bi][0], u[bi][1], v);
+                        u[bi][0] = max(u[bi][0], v);
+                        u[bi][1] = n1;
+                        u[bi][2] = n2;
+                        u[bi][3] = n3;
+                    }
                 }
             }
             wait_vmem();
             __syncthreads();
+        };
+        for (int st = 0; st < nstages; st += 2) {
+            do_stage(st, std::integral_constant<int, 0>{});
+            if (st + 1 < nstages) do_stage(st + 1, std::integral_constant<int, 1>{});
         }
         // both buffers are free now: fetch stage 0 for the next sweep behind the select phase
-        if (g + 1 < s) issue_stage(Dh, 0, lds, wave, lane);
+        if (g + 1 < s) issue_stage(Dh, 0, N, lds, wave, lane, lane_off);
 
         // ---- select + update, one 32-token block at a time ----------------------------------
 #pragma unroll
         for (int bi = 0; bi < kBlocks; ++bi) {
-            const uint32_t p1 = __shfl_xor(u1[bi], 32, 64), p2 = __shfl_xor(u2[bi], 32, 64),
-                           p3 = __shfl_xor(u3[bi], 32, 64);
-            // L = triple of lane-half 0, Hh = triple of lane-half 1: both lanes of a pair see the same
-            const uint32_t L1 = hf ? p1 : u1[bi], L2 = hf ? p2 : u2[bi], L3 = hf ? p3 : u3[bi];
-            const uint32_t H1 = hf ? u1[bi] : p1, H2 = hf ? u2[bi] : p2, H3 = hf ? u3[bi] : p3;
-            // merged top three with the owning half (ties: half 0 first)
-            uint32_t tv0, tv1, tv2;
-            int to0, to1, to2;
-            {
-                uint32_t a1 = L1, a2 = L2, a3 = L3, b1 = H1, b2 = H2, b3 = H3;
-                bool x = a1 >= b1;
-                tv0 = x ? a1 : b1; to0 = x ? 0 : 1;
-                if (x) { a1 = a2; a2 = a3; } else { b1 = b2; b2 = b3; }
-                x = a1 >= b1;
-                tv1 = x ? a1 : b1; to1 = x ? 0 : 1;
-                if (x) { a1 = a2; } else { b1 = b2; }
-                x = a1 >= b1;
-                tv2 = x ? a1 : b1; to2 = x ? 0 : 1;
-                (void)a3; (void)b3;
-            }
-            const float A = __uint_as_float(tv0 & ~code_mask);
+            uint32_t pu[kTrack];
+#pragma unroll
+            for (int k = 0; k < kTrack; ++k) pu[k] = xchg32(u[bi][k], hf);
+            // best group of the token: own or the partner lane's (equal values: lane half 0 first)
+            const bool own_best = hf == 0 ? u[bi][0] >= pu[0] : u[bi][0] > pu[0];
+            const uint32_t best_u = own_best ? u[bi][0] : pu[0];
+            const int best_half = own_best ? hf : 1 - hf;
+            const float A = __uint_as_float(best_u & ~code_mask);
             const float thr = (A - delta[bi]) * (1.0f - 2.0f * pack_q);
-            const bool zero = rn2[bi] == 0.0f;
-            auto cand = [&](uint32_t u) { return __uint_as_float(u & ~code_mask) >= thr; };
-            const int ncand = (int)cand(L1) + (int)cand(L2) + (int)cand(L3) + (int)cand(H1) + (int)cand(H2) + (int)cand(H3);
-            bool overflow = cand(L3) || cand(H3) || ncand > 3 || !(rn2[bi] < kNormSafe * kNormSafe);
-            overflow = overflow && !zero && valid[bi];
+            const uint32_t thr_bits = thr > 0.0f ? (__float_as_uint(thr) & ~code_mask) : 0u;
+            const bool zero = !(rn2[bi] > 0.0f);
+            int ncand = 0;
+#pragma unroll
+            for (int k = 0; k < kTrack; ++k) ncand += (int)(u[bi][k] >= thr_bits) + (int)(pu[k] >= thr_bits);
+            const bool overflow = u[bi][kTrack - 1] >= thr_bits || pu[kTrack - 1] >= thr_bits;
 
-            float best_a = -1.0f, best_c = 0.0f;
-            int best_n = 0;
-            auto rescore = [&](uint32_t tv, int to, bool need) {
-                const int tile = ntiles - 1 - (int)(tv & code_mask);
-                const int base = tile * 32 + 4 * to;
-#pragma unroll 4
-                for (int k = 0; k < 16; ++k) {
-                    const int n = base + 8 * (k >> 2) + (k & 3);
-                    float c = half_dot(Dh + (int64_t)n * kD, hf, hi[bi], lo[bi]);
-                    c += __shfl_xor(c, 32, 64);
-                    const float a = fabsf(c);
-                    if (need && (a > best_a || (a == best_a && n < best_n))) { best_a = a; best_c = c; best_n = n; }
+            // re-score the best group on hi: 16 atoms, this lane's 64 dimensions of each
+            const int tile0 = ntiles - 1 - (int)(best_u & code_mask);
+            const int base = tile0 * 32 + 4 * best_half;
+            float p[16];
+#pragma unroll
+            for (int k = 0; k < 16; k += 2) {
+                uint4 raw[2][8];
+#pragma unroll
+                for (int kk2 = 0; kk2 < 2; ++kk2) {
+                    const __half *row = Dh + (int64_t)(base + 8 * ((k + kk2) >> 2) + ((k + kk2) & 3)) * kD + hf * 64;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) raw[kk2][j] = *reinterpret_cast<const uint4 *>(row + 8 * j);
                 }
-            };
-#if CSR_DBG == 1
-            best_n = (ntiles - 1 - (int)(tv0 & code_mask)) * 32 + 4 * to0; best_c = 1e-3f;
-#else
-            rescore(tv0, to0, true);
-#endif
-#if CSR_DBG != 1
-            {
-                const bool need1 = cand(tv1);
-                if (__ballot(need1) != 0ull) rescore(tv1, to1, need1);
-                const bool need2 = cand(tv2);
-                if (__ballot(need2) != 0ull) rescore(tv2, to2, need2);
+#pragma unroll
+                for (int kk2 = 0; kk2 < 2; ++kk2) {
+                    float s0 = 0.0f, s1 = 0.0f;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) dot8(hi[bi][j], *reinterpret_cast<const half8 *>(&raw[kk2][j]), s0, s1);
+                    p[k + kk2] = s0 + s1;
+                }
+                __builtin_amdgcn_sched_barrier(0);  // keep at most two atoms' rows in registers
             }
-#endif
-            if (zero) { best_c = 0.0f; best_n = 0; }
+            // pair sum: afterwards lane half 0 holds the full products of atoms 0..7 of the group,
+            // half 1 those of atoms 8..15
+            float ba = -1.0f, sa = -1.0f;  // largest and second largest magnitude seen by this lane
+            int bk = 0;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(p[k]), __float_as_uint(p[k + 8]), false, false);
+                const float v = fabsf(__uint_as_float(r[0]) + __uint_as_float(r[1]));
+                if (v > ba) { sa = ba; ba = v; bk = k; }
+                else sa = fmaxf(sa, v);
+            }
+            const float oba = xchg32f(ba, hf), osa = xchg32f(sa, hf);
+            const int obk = (int)xchg32((uint32_t)bk, hf);
+            const bool mine = hf == 0 ? ba >= oba : ba > oba;  // equal: the lower atom index (half 0) wins
+            const float top = mine ? ba : oba;
+            const float second = fmaxf(mine ? oba : ba, fmaxf(sa, osa));
+            const int kk = mine ? bk + 8 * hf : obk + 8 * (1 - hf);
+            int best_n = base + 8 * (kk >> 2) + (kk & 3);
+            const bool unsure = !zero && (ncand > 1 || overflow || !(second < top - delta[bi]));
 
-            // Eq.4 on the full-precision residual, then the new hi / lo split and screening bound
+            // the rare tokens, one at a time, by the whole wave (both lanes of a pair agree on `unsure`)
+            uint32_t todo = (uint32_t)__ballot(unsure);
+            while (todo) {
+                const int t = __ffs((int)todo) - 1;
+                todo &= todo - 1;
+                if (col == t) {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        *reinterpret_cast<half8 *>(scr + hf * 128 + j * 16) = hi[bi][j];
+                        *reinterpret_cast<half8 *>(scr + 256 + hf * 128 + j * 16) = lo[bi][j];
+                    }
+                    *reinterpret_cast<uint4 *>(scr + 512 + hf * 16) = make_uint4(u[bi][0], u[bi][1], u[bi][2], u[bi][3]);
+                    if (hf == 0) *reinterpret_cast<uint2 *>(scr + 544) = make_uint2(thr_bits, overflow ? 1u : 0u);
+                }
+                wave_lds_fence();
+                const int n_res = resolve_token(Dh, N, ntiles, code_mask, scr, lane);
+                wave_lds_fence();
+                if (col == t) best_n = n_res;
+            }
+            if (zero) best_n = 0;
+
+            // c = (hi + lo) . d exactly, Eq.4 on the full-precision residual, new hi / lo split and bound
             {
-                const __half *row = Dh + (int64_t)best_n * kD;
-                float lo2 = 0.0f, r2 = 0.0f;
+                const __half *row = Dh + (int64_t)best_n * kD + hf * 64;
+                uint4 raw[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) raw[j] = *reinterpret_cast<const uint4 *>(row + 8 * j);
+                float s0 = 0.0f, s1 = 0.0f, l0 = 0.0f, l1 = 0.0f;
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    const uint4 raw = *reinterpret_cast<const uint4 *>(row + 16 * j + 8 * hf);
+                    const half8 dv = *reinterpret_cast<const half8 *>(&raw[j]);
+                    dot8(hi[bi][j], dv, s0, s1);
+                    dot8(lo[bi][j], dv, l0, l1);
+                }
+                float best_c = (s0 + s1) + (l0 + l1);
+                best_c += xchg32f(best_c, hf);
+                if (zero) best_c = 0.0f;
+                float v[8][8];
+                float r2 = 0.0f;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
                     float f[8];
-                    unpack8(raw, f);
-                    half8 hv, lv;
+                    unpack8(raw[j], f);
                     const half8 ho = hi[bi][j], lo_o = lo[bi][j];
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
                         const float r = (float)ho[e] + (float)lo_o[e];  // exact: 22 significant bits
-                        const float v = fmaf(-best_c, f[e], r);
-                        const _Float16 hh = (_Float16)v;
-                        const float l = v - (float)hh;
+                        v[j][e] = fmaf(-best_c, f[e], r);
+                        r2 = fmaf(v[j][e], v[j][e], r2);
+                    }
+                }
+                r2 += xchg32f(r2, hf);
+                const int sexp_used = sexp[bi];
+                // A residual that has shrunk a lot (a vector that is nearly a multiple of an atom) is
+                // scaled up again before the split, or lo would sink into the fp16 subnormals.
+                const bool shrunk = r2 < 65536.0f && r2 > 0.0f;
+                if (__ballot(shrunk) != 0ull) {
+                    int e2 = 0;
+                    (void)frexpf(r2, &e2);                       // |R| in [2^((e2-1)/2), 2^(e2/2))
+                    const int k = shrunk ? 14 - (e2 + 1) / 2 : 0;  // brings |R| into [2^12.5, 2^14.5)
+                    const float sc = ldexpf(1.0f, k);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) v[j][e] *= sc;
+                    r2 *= sc * sc;
+                    sexp[bi] += k;
+                }
+                float lo2 = 0.0f;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    half8 hv, lv;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const _Float16 hh = (_Float16)v[j][e];
+                        const float l = v[j][e] - (float)hh;
                         hv[e] = hh;
                         lv[e] = (_Float16)l;
                         lo2 = fmaf(l, l, lo2);
-                        r2 = fmaf(v, v, r2);
                     }
                     hi[bi][j] = hv;
                     lo[bi][j] = lv;
                 }
-                lo2 += __shfl_xor(lo2, 32, 64);
-                r2 += __shfl_xor(r2, 32, 64);
+                lo2 += xchg32f(lo2, hf);
                 rn2[bi] = r2;
                 delta[bi] = 2.0f * dmax * (sqrtf(lo2) + kGammaAcc * sqrtf(r2));
-            }
-            if (valid[bi] && hf == 0) {
-                const int64_t o = ((int64_t)h * T + tok[bi]) * s + g;
-                const float c_out = ldexpf(best_c, -sexp[bi]);
-                if (idx16) reinterpret_cast<uint16_t *>(idx_out)[o] = (uint16_t)best_n;
-                else reinterpret_cast<int32_t *>(idx_out)[o] = best_n;
-                if (coef16) reinterpret_cast<__half *>(coef_out)[o] = __float2half_rn(c_out);
-                else reinterpret_cast<float *>(coef_out)[o] = c_out;
-            }
-            const unsigned long long bal = __ballot(overflow && hf == 0);  // bits 0..31 = this block's tokens
-            flag_acc |= (bal & 0xffffffffull) << (32 * bi);
-        }
-    }
-    // every wave writes its word, flagged or not: the flag array needs no clearing beforehand
-#if CSR_DBG == 3
-    if (tid == 0) {
-        unsigned long long *rec = flags + (int64_t)blockIdx.x * kWavesPerWG;
-        rec[0] = dbg_t0;
-        rec[1] = __builtin_readcyclecounter();
-        rec[2] = __builtin_amdgcn_s_getreg(0xF804);
-        rec[3] = __builtin_amdgcn_s_getreg(0xF814);
-    }
-    (void)flag_acc;
-#else
-    if (lane == 0) flags[((int64_t)h * tiles_per_h + tile_wg) * kWavesPerWG + wave] = flag_acc;
-#endif
-}
-
-// Exact fp32 Matching Pursuit for the flagged tokens, one workgroup per token.  16 lanes share an
-// atom row (coalesced 256 B), each holding its 8 residual values in registers; the residual lives
-// in LDS between iterations.  Overwrites the codes the screening kernel left for these tokens.
-__global__ __launch_bounds__(256) void encode_exact_token_kernel(
-    const __half *__restrict__ X, const __half *__restrict__ Dict, void *__restrict__ idx_out,
-    void *__restrict__ coef_out, const unsigned long long *__restrict__ flags, int64_t T, int32_t N,
-    int32_t s, int64_t x_stride_h, int64_t x_stride_t, int32_t tiles_per_h, int64_t n_words,
-    int32_t idx16, int32_t coef16)
-{
-    __shared__ __attribute__((aligned(16))) float R_s[kD];
-    __shared__ float w_a[4], w_c[4];
-    __shared__ int w_n[4];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int sub = tid & 15, grp = tid >> 4;
-
-    for (int64_t w = blockIdx.x; w < n_words; w += gridDim.x) {
-        unsigned long long word = flags[w];  // same for every thread of the workgroup
-        while (word) {
-            const int b = __ffsll((long long)word) - 1;
-            word &= word - 1;
-            const int64_t wg = w / kWavesPerWG;
-            const int wv = (int)(w - wg * kWavesPerWG);
-            const int h = (int)(wg / tiles_per_h);
-            const int64_t t = (wg - (int64_t)h * tiles_per_h) * kTokPerWG + wv * kTokPerWave + b;
-            if (t >= T) continue;
-            const __half *Dh = Dict + (int64_t)h * N * kD;
-            __syncthreads();
-            if (tid < kD) R_s[tid] = __half2float(X[(int64_t)h * x_stride_h + t * x_stride_t + tid]);
-            __syncthreads();
-            for (int g = 0; g < s; ++g) {
-                float rv[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) rv[e] = R_s[sub * 8 + e];
-                float ba = -1.0f, bc = 0.0f;
-                int bn = 0;
-                for (int n = grp; n < N; n += 16) {
-                    const uint4 raw = *reinterpret_cast<const uint4 *>(Dh + (int64_t)n * kD + sub * 8);
-                    float f[8];
-                    unpack8(raw, f);
-                    float c0 = 0.0f, c1 = 0.0f;
-#pragma unroll
-                    for (int e = 0; e < 8; e += 2) { c0 = fmaf(rv[e], f[e], c0); c1 = fmaf(rv[e + 1], f[e + 1], c1); }
-                    float c = c0 + c1;
-#pragma unroll
-                    for (int m = 8; m >= 1; m >>= 1) c += __shfl_xor(c, m, 64);
-                    const float a = fabsf(c);
-                    if (a > ba) { ba = a; bc = c; bn = n; }  // ascending n: the lowest index is kept on ties
+                if (valid[bi]) {
+                    const int64_t o = ((int64_t)h * T + tok[bi]) * s + g;
+                    if (hf == 0) {
+                        if (idx16) reinterpret_cast<uint16_t *>(idx_out)[o] = (uint16_t)best_n;
+                        else reinterpret_cast<int32_t *>(idx_out)[o] = best_n;
+                    } else {
+                        const float c_out = ldexpf(best_c, -sexp_used);
+                        if (coef16) reinterpret_cast<__half *>(coef_out)[o] = __float2half_rn(c_out);
+                        else reinterpret_cast<float *>(coef_out)[o] = c_out;
+                    }
                 }
-                // lowest index among equal magnitudes, across the wave then across the 4 waves
-#pragma unroll
-                for (int m = 32; m >= 16; m >>= 1) {
-                    const float oa = __shfl_xor(ba, m, 64), oc = __shfl_xor(bc, m, 64);
-                    const int on = __shfl_xor(bn, m, 64);
-                    if (oa > ba || (oa == ba && on < bn)) { ba = oa; bc = oc; bn = on; }
-                }
-                if (lane == 0) { w_a[wave] = ba; w_c[wave] = bc; w_n[wave] = bn; }
-                __syncthreads();
-                ba = w_a[0]; bc = w_c[0]; bn = w_n[0];
-#pragma unroll
-                for (int k = 1; k < 4; ++k) {
-                    if (w_a[k] > ba || (w_a[k] == ba && w_n[k] < bn)) { ba = w_a[k]; bc = w_c[k]; bn = w_n[k]; }
-                }
-                if (tid < kD) R_s[tid] = fmaf(-bc, __half2float(Dh[(int64_t)bn * kD + tid]), R_s[tid]);
-                if (tid == 0) {
-                    const int64_t o = ((int64_t)h * T + t) * s + g;
-                    if (idx16) reinterpret_cast<uint16_t *>(idx_out)[o] = (uint16_t)bn;
-                    else reinterpret_cast<int32_t *>(idx_out)[o] = bn;
-                    if (coef16) reinterpret_cast<__half *>(coef_out)[o] = __float2half_rn(bc);
-                    else reinterpret_cast<float *>(coef_out)[o] = bc;
-                }
-                __syncthreads();
             }
         }
     }
@@ -500,15 +578,13 @@ size_t r256(size_t v) { return (v + 255) & ~size_t(255); }
 
 bool encode_mfma_supported(const EncodeArgs &a)
 {
-    return a.f16 && a.d == kD && a.N >= 128 && a.N % kStageAtoms == 0 && a.N <= 65536;
+    return a.f16 && a.d == kD && a.N >= 32 && a.N % 32 == 0 && a.N <= 65536;
 }
 
 size_t encode_mfma_workspace_bytes(int32_t H, int64_t T, int32_t N, int32_t s)
 {
-    (void)N; (void)s;
-    const int64_t tiles = (T + kTokPerWG - 1) / kTokPerWG;
-    return r256((size_t)H * kNormSlices * sizeof(float)) +
-           r256((size_t)H * tiles * kWavesPerWG * sizeof(unsigned long long));
+    (void)T; (void)N; (void)s;
+    return r256((size_t)H * kNormSlices * sizeof(float));
 }
 
 hipError_t launch_encode_mfma(const EncodeArgs &a)
@@ -516,44 +592,38 @@ hipError_t launch_encode_mfma(const EncodeArgs &a)
     const int64_t tiles = (a.T + kTokPerWG - 1) / kTokPerWG;
     const int64_t groups = tiles * a.H;
     if (groups > 0x7fffffffLL) return hipErrorInvalidValue;
-    char *ws = static_cast<char *>(a.workspace);
-    float *dnorm = reinterpret_cast<float *>(ws);
-    unsigned long long *flags =
-        reinterpret_cast<unsigned long long *>(ws + r256((size_t)a.H * kNormSlices * sizeof(float)));
+    float *dnorm = reinterpret_cast<float *>(a.workspace);
     const int ntiles = a.N / 32;
     int bits = 0;
     while ((1 << bits) < ntiles) ++bits;
     const uint32_t code_mask = (1u << bits) - 1u;
 
-    static int n_cus = -1;  // CU count of the current device, asked once
-    if (n_cus < 0) {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) v = 0;
-        n_cus = v;
+    // per device, once: the kernel's LDS need is above the default limit, and the number of
+    // workgroups that start together (two per CU) decides which ones are held back at the start
+    static int n_cus[64] = {0};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (n_cus[dev] == 0) {
+        int v = 0;
+        e = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(encode_mfma_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        if (e != hipSuccess) return e;
+        n_cus[dev] = v > 0 ? v : 1;
     }
-    int32_t stagger = (getenv("CSR_NO_STAGGER") || groups <= n_cus) ? 0 : n_cus;
-    if (getenv("CSR_STAGGER_MODE")) stagger = -atoi(getenv("CSR_STAGGER_MODE"));
+    const int32_t first_round = groups > n_cus[dev] ? 2 * n_cus[dev] : 0;
 
-    if (getenv("CSR_DBG_OCC")) {
-        int nb = -1;
-        hipError_t oe = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, encode_mfma_kernel, kThreads, 0);
-        fprintf(stderr, "[csr] occupancy: %d workgroups/CU (err %d), CUs %d\n", nb, (int)oe, n_cus);
-    }
     hipLaunchKernelGGL(dict_norm_kernel, dim3((unsigned)a.H, kNormSlices), dim3(256), 0, a.stream,
                        (const __half *)a.D, dnorm, a.N);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(encode_mfma_kernel, dim3((unsigned)groups), dim3(kThreads), 0, a.stream, (const __half *)a.X,
-                       (const __half *)a.D, a.idx, a.coef, dnorm, flags, a.T, a.N, a.s, a.x_stride_h, a.x_stride_t,
-                       (int32_t)tiles, (int32_t)groups, (int32_t)a.idx16, (int32_t)a.coef16, code_mask, stagger);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (getenv("CSR_DBG_SKIP_FB")) return hipSuccess;
-    const int64_t n_words = groups * kWavesPerWG;
-    const unsigned fb_grid = (unsigned)(n_words < kFallbackGrid ? n_words : kFallbackGrid);
-    hipLaunchKernelGGL(encode_exact_token_kernel, dim3(fb_grid), dim3(256), 0, a.stream, (const __half *)a.X,
-                       (const __half *)a.D, a.idx, a.coef, flags, a.T, a.N, a.s, a.x_stride_h, a.x_stride_t,
-                       (int32_t)tiles, n_words, (int32_t)a.idx16, (int32_t)a.coef16);
+    hipLaunchKernelGGL(encode_mfma_kernel, dim3((unsigned)groups), dim3(kThreads), kLdsBytes, a.stream,
+                       (const __half *)a.X, (const __half *)a.D, a.idx, a.coef, dnorm, a.T, a.N, a.s, a.x_stride_h,
+                       a.x_stride_t, (int32_t)tiles, (int32_t)groups, (int32_t)a.idx16, (int32_t)a.coef16, code_mask,
+                       first_round);
     return hipGetLastError();
 }
 
