@@ -18,11 +18,13 @@
 //            epilogue keeps, per lane, the four largest GROUP maxima of the sweep (a group = the 16
 //            atoms one lane holds of one 32x32 output tile), with the tile number packed into the
 //            low mantissa bits so that one integer max/med3 chain tracks value and position.
-//   select   the best group is re-scored on the vector ALU (v_dot2_f32_f16 on hi, the two lanes
-//            that share a token each doing half of the 128 dimensions).  If its best atom leads
-//            every other atom of the group by more than delta and no other tracked group comes
-//            within delta of it, that atom is the iteration's pick (about 97 % of the steps on
-//            Gaussian-like data).  Otherwise the wave resolves the token together: the residual
+//            Whenever a group becomes a lane's new best, its 16 screened magnitudes are parked in
+//            LDS as fp16, so that after the sweep the best group's values are at hand.
+//   select   if the best group's largest parked value leads the other 15 by more than delta (plus the
+//            fp16 rounding of the parked values) and no other tracked group comes within delta of
+//            it, that atom is the iteration's pick (about 97 % of the steps on Gaussian-like
+//            data): no memory access beyond one LDS read.  Otherwise the wave resolves the token
+//            together: the residual
 //            goes through LDS to all 64 lanes, which evaluate hi . d + lo . d (products of fp16
 //            pairs are exact in fp32) for every atom of every candidate group and take the largest,
 //            lowest index on ties.  Should even the fourth tracked group of a lane be a candidate
@@ -36,9 +38,10 @@
 // contraction index is permuted so that lane half 0 holds dimensions 0..63 and half 1 holds 64..127
 // (any order is valid as long as both operands use it): vector and atom rows are then read as 128
 // contiguous bytes per lane.  A wave owns 2 x 32 tokens so that every A fragment read from LDS feeds
-// two MFMAs.  Dictionary stages (128 atoms, 32 KiB) go from global memory straight into LDS
-// (global_load_lds_dwordx4), double-buffered, 16-byte chunks XOR-swizzled by the row number so that
-// 16 consecutive rows read at the same logical chunk cover all LDS banks.  Two 4-wave workgroups
+// two MFMAs.  Dictionary stages (64 atoms, 16 KiB) go from global memory straight into LDS
+// (global_load_lds_dwordx4) through a ring of three buffers, fetched two stages ahead, 16-byte
+// chunks XOR-swizzled by the row number so that 16 consecutive rows read at the same logical chunk
+// cover all LDS banks.  Two 4-wave workgroups
 // share a CU (two waves per SIMD), so one workgroup's select / update phase (vector ALU, gathers)
 // overlaps the other's sweep (matrix cores).
 #include <cstdio>
@@ -60,11 +63,16 @@ constexpr int kWavesPerWG = 4;
 constexpr int kThreads = 64 * kWavesPerWG;            // 256
 constexpr int kTokPerWave = 32 * kBlocks;             // 64
 constexpr int kTokPerWG = kWavesPerWG * kTokPerWave;  // 256
-constexpr int kStageTiles = 4;                        // 32-atom tiles per LDS stage
-constexpr int kStageAtoms = 32 * kStageTiles;         // 128
-constexpr int kStageBytes = kStageAtoms * kD * 2;     // 32 KiB, rows unpadded, chunks XOR-swizzled
+constexpr int kStageTiles = 2;                        // 32-atom tiles per LDS stage
+constexpr int kStageAtoms = 32 * kStageTiles;         // 64
+constexpr int kStageBytes = kStageAtoms * kD * 2;     // 16 KiB, rows unpadded, chunks XOR-swizzled
+constexpr int kRing = 3;                              // stage buffers; stage st lives in buffer st % 3
+constexpr int kStageLoads = kStageAtoms / (4 * kWavesPerWG);  // load instructions per lane and stage
+constexpr int kParkPerBlock = 64 * 32;                // 16 fp16 magnitudes for each of 64 lanes
+constexpr int kParkOff = kRing * kStageBytes;
 constexpr int kScratchPerWave = 1024;                 // LDS a wave uses to share one token's state
-constexpr int kLdsBytes = 2 * kStageBytes + kWavesPerWG * kScratchPerWave;
+constexpr int kScratchOff = kParkOff + kWavesPerWG * kBlocks * kParkPerBlock;
+constexpr int kLdsBytes = kScratchOff + kWavesPerWG * kScratchPerWave;  // 68 KiB: two workgroups per CU
 constexpr int kTrack = 4;                             // group maxima tracked per lane and sweep
 constexpr int kNormSlices = 8;                        // workgroups per dictionary in the norm pre-pass
 // fp32 accumulation error of a 128-term dot product of exact fp16 products, relative to |hi||d|:
@@ -96,6 +104,9 @@ __device__ __forceinline__ void unpack8(const uint4 &raw, float (&f)[8])
 }
 
 __device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// waits until at most `n` of this wave's vector memory operations are still in flight
+template <int N_LEFT>
+__device__ __forceinline__ void wait_vmem_but() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N_LEFT) : "memory"); }
 
 // LDS traffic inside one wave needs no barrier (the LDS executes a wave's instructions in order),
 // only that the compiler keeps the order and waits for the data.
@@ -114,7 +125,7 @@ __device__ __forceinline__ void dot8(const half8 &a, const half8 &d, float &s0, 
     s1 = __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 6, 7), __builtin_shufflevector(d, d, 6, 7), s1, false);
 }
 
-// One dictionary stage (128 atoms x 256 B) from global memory into an LDS buffer, no registers in
+// One dictionary stage (64 atoms x 256 B) from global memory into an LDS buffer, no registers in
 // between.  Each wave instruction fills 1 KiB = 4 rows; lane l lands at byte 16 l of that KiB, i.e.
 // row l/16, chunk position l%16, and fetches source chunk position ^ (row & 15).  A wave's
 // instructions are 16 rows apart, so that XOR term is the same for all of them and the source is
@@ -132,7 +143,7 @@ __device__ __forceinline__ void issue_stage(const __half *__restrict__ Dh, int s
     const unsigned char *sbase = reinterpret_cast<const unsigned char *>(Dh) + (int64_t)stage * kStageBytes;
     const int rows_left = N - stage * kStageAtoms - (wave * 4 + (lane >> 4));  // > 0 for the rows that exist
 #pragma unroll
-    for (int i = 0; i < kStageAtoms / (4 * kWavesPerWG); ++i) {
+    for (int i = 0; i < kStageLoads; ++i) {
         if (16 * i < rows_left)
             __builtin_amdgcn_global_load_lds(
                 (const __attribute__((address_space(1))) void *)(sbase + i * 4096 + lane_off),
@@ -257,7 +268,8 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, hf = lane >> 5;
-    unsigned char *scr = lds + 2 * kStageBytes + wave * kScratchPerWave;
+    unsigned char *scr = lds + kScratchOff + wave * kScratchPerWave;
+    unsigned char *park = lds + kParkOff + wave * kBlocks * kParkPerBlock + lane * 16;  // + bi * kParkPerBlock + {0, 1024}
 
     // Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous run of work so
     // that workgroups sharing a dictionary share an L2.
@@ -271,6 +283,7 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
 
     const uint32_t lane_off = stage_lane_offset(wave, lane);
     issue_stage(Dh, 0, N, lds, wave, lane, lane_off);  // in flight while the vectors are loaded
+    if (nstages > 1) issue_stage(Dh, 1, N, lds + kStageBytes, wave, lane, lane_off);
     // LDS byte offset, inside a 32-row tile, of this lane's A fragment j (row = col, chunk 8 hf + j)
     uint32_t frag_off[8];
 #pragma unroll
@@ -283,7 +296,7 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
     if ((int)blockIdx.x < first_round) {
         // HW_ID bits 3:0 = this wave's slot on its SIMD; a workgroup waits for its slowest wave anyway
         if (__builtin_amdgcn_s_getreg(0xF804) & 1) {
-            for (int i = 0; i < nstages; ++i) __builtin_amdgcn_s_sleep(32);
+            for (int i = 0; i < nstages; ++i) __builtin_amdgcn_s_sleep(16);
         }
     }
 
@@ -356,13 +369,16 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
 #pragma unroll
             for (int k = 0; k < kTrack; ++k) u[bi][k] = 0u;
 
+        // stages 0 and 1 were requested before (at kernel start or behind the previous select phase)
         wait_vmem();
-        __syncthreads();  // stage 0 is in buffer 0
+        __syncthreads();  // stages 0 and 1 are in buffers 0 and 1
 
-        // one stage: fetch the next one into the other buffer, sweep this one's tiles, meet the others
+        // one stage: fetch the one after next into the free buffer, sweep this one's tiles, then wait
+        // for the next one (the most recent request may stay in flight) and meet the other waves
         auto do_stage = [&](int st, auto buf_c) {
             constexpr int kBuf = decltype(buf_c)::value;
-            if (st + 1 < nstages) issue_stage(Dh, st + 1, N, lds + (1 - kBuf) * kStageBytes, wave, lane, lane_off);
+            const bool more = st + 2 < nstages;
+            if (more) issue_stage(Dh, st + 2, N, lds + ((kBuf + 2) % kRing) * kStageBytes, wave, lane, lane_off);
             const int tiles_here = min(kStageTiles, ntiles - st * kStageTiles);
 #pragma unroll
             for (int rt = 0; rt < kStageTiles; ++rt) {
@@ -389,6 +405,19 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
 #pragma unroll
                         for (int r = 0; r < 16; r += 2) m = fmaxf(fmaxf(m, fabsf(acc[bi][r])), fabsf(acc[bi][r + 1]));
                         const uint32_t v = (__float_as_uint(m) & keep_mask) | code;  // one v_and_or_b32
+                        const bool new_best = v > u[bi][0];
+                        if (__ballot(new_best) != 0ull) {
+                            if (new_best) {  // park this group's magnitudes (fp16, rounded toward zero)
+                                uint32_t w[8];
+#pragma unroll
+                                for (int r = 0; r < 8; ++r) {
+                                    const auto pk = __builtin_amdgcn_cvt_pkrtz(fabsf(acc[bi][2 * r]), fabsf(acc[bi][2 * r + 1]));
+                                    w[r] = *reinterpret_cast<const uint32_t *>(&pk);
+                                }
+                                *reinterpret_cast<uint4 *>(park + bi * kParkPerBlock) = make_uint4(w[0], w[1], w[2], w[3]);
+                                *reinterpret_cast<uint4 *>(park + bi * kParkPerBlock + 1024) = make_uint4(w[4], w[5], w[6], w[7]);
+                            }
+                        }
                         const uint32_t n3 = umed3(u[bi][2], u[bi][3], v);
                         const uint32_t n2 = umed3(u[bi][1], u[bi][2], v);
                         const uint32_t n1 = umed3(u[bi][0], u[bi][1], v);
@@ -399,17 +428,22 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
                     }
                 }
             }
-            wait_vmem();
+            if (more) wait_vmem_but<kStageLoads>(); else wait_vmem();
             __syncthreads();
         };
-        for (int st = 0; st < nstages; st += 2) {
+        for (int st = 0; st < nstages; st += kRing) {
             do_stage(st, std::integral_constant<int, 0>{});
             if (st + 1 < nstages) do_stage(st + 1, std::integral_constant<int, 1>{});
+            if (st + 2 < nstages) do_stage(st + 2, std::integral_constant<int, 2>{});
         }
-        // both buffers are free now: fetch stage 0 for the next sweep behind the select phase
-        if (g + 1 < s) issue_stage(Dh, 0, N, lds, wave, lane, lane_off);
+        // all buffers are free now: fetch stages 0 and 1 for the next sweep behind the select phase
+        if (g + 1 < s) {
+            issue_stage(Dh, 0, N, lds, wave, lane, lane_off);
+            if (nstages > 1) issue_stage(Dh, 1, N, lds + kStageBytes, wave, lane, lane_off);
+        }
 
-        // ---- select + update, one 32-token block at a time ----------------------------------
+        // ---- select: the iteration's atom for every token, one 32-token block at a time -------
+        int best_n[kBlocks];
 #pragma unroll
         for (int bi = 0; bi < kBlocks; ++bi) {
             uint32_t pu[kTrack];
@@ -428,49 +462,32 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
             for (int k = 0; k < kTrack; ++k) ncand += (int)(u[bi][k] >= thr_bits) + (int)(pu[k] >= thr_bits);
             const bool overflow = u[bi][kTrack - 1] >= thr_bits || pu[kTrack - 1] >= thr_bits;
 
-            // re-score the best group on hi: 16 atoms, this lane's 64 dimensions of each
-            const int tile0 = ntiles - 1 - (int)(best_u & code_mask);
-            const int base = tile0 * 32 + 4 * best_half;
-            float p[16];
-#pragma unroll
-            for (int k = 0; k < 16; k += 2) {
-                uint4 raw[2][8];
-#pragma unroll
-                for (int kk2 = 0; kk2 < 2; ++kk2) {
-                    const __half *row = Dh + (int64_t)(base + 8 * ((k + kk2) >> 2) + ((k + kk2) & 3)) * kD + hf * 64;
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) raw[kk2][j] = *reinterpret_cast<const uint4 *>(row + 8 * j);
-                }
-#pragma unroll
-                for (int kk2 = 0; kk2 < 2; ++kk2) {
-                    float s0 = 0.0f, s1 = 0.0f;
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) dot8(hi[bi][j], *reinterpret_cast<const half8 *>(&raw[kk2][j]), s0, s1);
-                    p[k + kk2] = s0 + s1;
-                }
-                __builtin_amdgcn_sched_barrier(0);  // keep at most two atoms' rows in registers
-            }
-            // pair sum: afterwards lane half 0 holds the full products of atoms 0..7 of the group,
-            // half 1 those of atoms 8..15
-            float ba = -1.0f, sa = -1.0f;  // largest and second largest magnitude seen by this lane
+            // this lane's best group as parked during the sweep: largest value, its position, runner-up
+            float ba = -1.0f, sa = -1.0f;
             int bk = 0;
+            {
+                const uint4 w0 = *reinterpret_cast<const uint4 *>(park + bi * kParkPerBlock);
+                const uint4 w1 = *reinterpret_cast<const uint4 *>(park + bi * kParkPerBlock + 1024);
+                const uint32_t w[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(p[k]), __float_as_uint(p[k + 8]), false, false);
-                const float v = fabsf(__uint_as_float(r[0]) + __uint_as_float(r[1]));
-                if (v > ba) { sa = ba; ba = v; bk = k; }
-                else sa = fmaxf(sa, v);
+                for (int r = 0; r < 8; ++r) {
+                    const float2 f = __half22float2(*reinterpret_cast<const __half2 *>(&w[r]));
+                    if (f.x > ba) { sa = ba; ba = f.x; bk = 2 * r; } else sa = fmaxf(sa, f.x);
+                    if (f.y > ba) { sa = ba; ba = f.y; bk = 2 * r + 1; } else sa = fmaxf(sa, f.y);
+                }
             }
-            const float oba = xchg32f(ba, hf), osa = xchg32f(sa, hf);
-            const int obk = (int)xchg32((uint32_t)bk, hf);
-            const bool mine = hf == 0 ? ba >= oba : ba > oba;  // equal: the lower atom index (half 0) wins
-            const float top = mine ? ba : oba;
-            const float second = fmaxf(mine ? oba : ba, fmaxf(sa, osa));
-            const int kk = mine ? bk + 8 * hf : obk + 8 * (1 - hf);
-            int best_n = base + 8 * (kk >> 2) + (kk & 3);
-            const bool unsure = !zero && (ncand > 1 || overflow || !(second < top - delta[bi]));
+            // parked values were rounded toward zero to 11 bits: two of them are told apart only
+            // beyond delta + 2^-10 of the larger
+            const bool close_own = !(sa < ba - delta[bi] - ba * 9.765625e-4f);
+            const uint32_t mine = (uint32_t)bk | (close_own ? 16u : 0u);
+            const uint32_t theirs = xchg32(mine, hf);
+            const uint32_t pick = own_best ? mine : theirs;
+            const int kk = (int)(pick & 15u);
+            const int tile0 = ntiles - 1 - (int)(best_u & code_mask);
+            best_n[bi] = tile0 * 32 + 4 * best_half + 8 * (kk >> 2) + (kk & 3);
+            const bool unsure = !zero && (ncand > 1 || overflow || (pick & 16u) != 0u);
 
-            // the rare tokens, one at a time, by the whole wave (both lanes of a pair agree on `unsure`)
+            // the undecided tokens, one at a time, by the whole wave (both lanes of a pair agree on `unsure`)
             uint32_t todo = (uint32_t)__ballot(unsure);
             while (todo) {
                 const int t = __ffs((int)todo) - 1;
@@ -487,85 +504,89 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
                 wave_lds_fence();
                 const int n_res = resolve_token(Dh, N, ntiles, code_mask, scr, lane);
                 wave_lds_fence();
-                if (col == t) best_n = n_res;
+                if (col == t) best_n[bi] = n_res;
             }
-            if (zero) best_n = 0;
+            if (zero) best_n[bi] = 0;
+        }
 
-            // c = (hi + lo) . d exactly, Eq.4 on the full-precision residual, new hi / lo split and bound
-            {
-                const __half *row = Dh + (int64_t)best_n * kD + hf * 64;
-                uint4 raw[8];
+        // ---- update: c = (hi + lo) . d exactly, Eq.4 on the full-precision residual, new split ----
+        uint4 raw[kBlocks][8];  // both blocks' atom rows are requested before either is used
 #pragma unroll
-                for (int j = 0; j < 8; ++j) raw[j] = *reinterpret_cast<const uint4 *>(row + 8 * j);
-                float s0 = 0.0f, s1 = 0.0f, l0 = 0.0f, l1 = 0.0f;
+        for (int bi = 0; bi < kBlocks; ++bi) {
+            const __half *row = Dh + (int64_t)best_n[bi] * kD + hf * 64;
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const half8 dv = *reinterpret_cast<const half8 *>(&raw[j]);
-                    dot8(hi[bi][j], dv, s0, s1);
-                    dot8(lo[bi][j], dv, l0, l1);
+            for (int j = 0; j < 8; ++j) raw[bi][j] = *reinterpret_cast<const uint4 *>(row + 8 * j);
+        }
+#pragma unroll
+        for (int bi = 0; bi < kBlocks; ++bi) {
+            float s0 = 0.0f, s1 = 0.0f, l0 = 0.0f, l1 = 0.0f;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const half8 dv = *reinterpret_cast<const half8 *>(&raw[bi][j]);
+                dot8(hi[bi][j], dv, s0, s1);
+                dot8(lo[bi][j], dv, l0, l1);
+            }
+            float best_c = (s0 + s1) + (l0 + l1);
+            best_c += xchg32f(best_c, hf);
+            if (!(rn2[bi] > 0.0f)) best_c = 0.0f;
+            float v[8][8];
+            float r2 = 0.0f;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                float f[8];
+                unpack8(raw[bi][j], f);
+                const half8 ho = hi[bi][j], lo_o = lo[bi][j];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float r = (float)ho[e] + (float)lo_o[e];  // exact: 22 significant bits
+                    v[j][e] = fmaf(-best_c, f[e], r);
+                    r2 = fmaf(v[j][e], v[j][e], r2);
                 }
-                float best_c = (s0 + s1) + (l0 + l1);
-                best_c += xchg32f(best_c, hf);
-                if (zero) best_c = 0.0f;
-                float v[8][8];
-                float r2 = 0.0f;
+            }
+            r2 += xchg32f(r2, hf);
+            const int sexp_used = sexp[bi];
+            // A residual that has shrunk a lot (a vector that is nearly a multiple of an atom) is
+            // scaled up again before the split, or lo would sink into the fp16 subnormals.
+            const bool shrunk = r2 < 65536.0f && r2 > 0.0f;
+            if (__ballot(shrunk) != 0ull) {
+                int e2 = 0;
+                (void)frexpf(r2, &e2);                       // |R| in [2^((e2-1)/2), 2^(e2/2))
+                const int k = shrunk ? 14 - (e2 + 1) / 2 : 0;  // brings |R| into [2^12.5, 2^14.5)
+                const float sc = ldexpf(1.0f, k);
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    float f[8];
-                    unpack8(raw[j], f);
-                    const half8 ho = hi[bi][j], lo_o = lo[bi][j];
+                for (int j = 0; j < 8; ++j)
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const float r = (float)ho[e] + (float)lo_o[e];  // exact: 22 significant bits
-                        v[j][e] = fmaf(-best_c, f[e], r);
-                        r2 = fmaf(v[j][e], v[j][e], r2);
-                    }
+                    for (int e = 0; e < 8; ++e) v[j][e] *= sc;
+                r2 *= sc * sc;
+                sexp[bi] += k;
+            }
+            float lo2 = 0.0f;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                half8 hv, lv;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const _Float16 hh = (_Float16)v[j][e];
+                    const float l = v[j][e] - (float)hh;
+                    hv[e] = hh;
+                    lv[e] = (_Float16)l;
+                    lo2 = fmaf(l, l, lo2);
                 }
-                r2 += xchg32f(r2, hf);
-                const int sexp_used = sexp[bi];
-                // A residual that has shrunk a lot (a vector that is nearly a multiple of an atom) is
-                // scaled up again before the split, or lo would sink into the fp16 subnormals.
-                const bool shrunk = r2 < 65536.0f && r2 > 0.0f;
-                if (__ballot(shrunk) != 0ull) {
-                    int e2 = 0;
-                    (void)frexpf(r2, &e2);                       // |R| in [2^((e2-1)/2), 2^(e2/2))
-                    const int k = shrunk ? 14 - (e2 + 1) / 2 : 0;  // brings |R| into [2^12.5, 2^14.5)
-                    const float sc = ldexpf(1.0f, k);
-#pragma unroll
-                    for (int j = 0; j < 8; ++j)
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) v[j][e] *= sc;
-                    r2 *= sc * sc;
-                    sexp[bi] += k;
-                }
-                float lo2 = 0.0f;
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    half8 hv, lv;
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const _Float16 hh = (_Float16)v[j][e];
-                        const float l = v[j][e] - (float)hh;
-                        hv[e] = hh;
-                        lv[e] = (_Float16)l;
-                        lo2 = fmaf(l, l, lo2);
-                    }
-                    hi[bi][j] = hv;
-                    lo[bi][j] = lv;
-                }
-                lo2 += xchg32f(lo2, hf);
-                rn2[bi] = r2;
-                delta[bi] = 2.0f * dmax * (sqrtf(lo2) + kGammaAcc * sqrtf(r2));
-                if (valid[bi]) {
-                    const int64_t o = ((int64_t)h * T + tok[bi]) * s + g;
-                    if (hf == 0) {
-                        if (idx16) reinterpret_cast<uint16_t *>(idx_out)[o] = (uint16_t)best_n;
-                        else reinterpret_cast<int32_t *>(idx_out)[o] = best_n;
-                    } else {
-                        const float c_out = ldexpf(best_c, -sexp_used);
-                        if (coef16) reinterpret_cast<__half *>(coef_out)[o] = __float2half_rn(c_out);
-                        else reinterpret_cast<float *>(coef_out)[o] = c_out;
-                    }
+                hi[bi][j] = hv;
+                lo[bi][j] = lv;
+            }
+            lo2 += xchg32f(lo2, hf);
+            rn2[bi] = r2;
+            delta[bi] = 2.0f * dmax * (sqrtf(lo2) + kGammaAcc * sqrtf(r2));
+            if (valid[bi]) {
+                const int64_t o = ((int64_t)h * T + tok[bi]) * s + g;
+                if (hf == 0) {
+                    if (idx16) reinterpret_cast<uint16_t *>(idx_out)[o] = (uint16_t)best_n[bi];
+                    else reinterpret_cast<int32_t *>(idx_out)[o] = best_n[bi];
+                } else {
+                    const float c_out = ldexpf(best_c, -sexp_used);
+                    if (coef16) reinterpret_cast<__half *>(coef_out)[o] = __float2half_rn(c_out);
+                    else reinterpret_cast<float *>(coef_out)[o] = c_out;
                 }
             }
         }
