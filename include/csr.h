@@ -103,14 +103,15 @@ csr_status csr_encode(const csr_encode_desc *desc, const void *X, const void *D,
  *   out     = DV[h]^T applied to hist, hist[n] = sum_{t,j : idxV = n} p_t * coefV[b][h][t][j]
  * which equals softmax attention over K~ = D_K r_K, V~ = D_V r_V of Eq.12.  No mask beyond the
  * sequence length, no position embedding (the paper's Section "KV cache in attention" sets it
- * aside).  A sequence with len_b = 0 yields zeros.  Accumulation is fp32; the V-side histogram
- * uses LDS float atomics, so results are reproducible to rounding, not bit for bit.
+ * aside).  A sequence with len_b = 0 yields zeros.  Accumulation is fp32, except the V-side histogram,
+ * which is summed exactly in 64-bit fixed point (units of 2^-32); the last stage adds partial outputs
+ * with float atomics, so results are reproducible to rounding, not bit for bit.
  */
 typedef struct {
     int32_t B;          /* sequences; >= 0                                                  */
     int32_t Hq;         /* query heads; multiple of Hkv, Hq/Hkv <= 8                        */
     int32_t Hkv;        /* KV heads                                                         */
-    int64_t T;          /* code rows allocated per (b, h); >= 0                             */
+    int64_t T;          /* code rows allocated per (b, h); 0 .. 2^20                        */
     int32_t d;          /* head dimension; supported: 128                                   */
     int32_t N;          /* atoms per dictionary                                             */
     int32_t sK, sV;     /* pairs per key / value code, 1..32                                */

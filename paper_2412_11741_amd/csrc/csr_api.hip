@@ -86,7 +86,7 @@ csr_status check_decode_desc(const csr_decode_desc *d, csr::DecodePlan *plan)
     if (d->d != 128) return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: d=%d not supported (128)", d->d);
     if (d->Hq / d->Hkv > 8) return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: group size %d above 8", d->Hq / d->Hkv);
     if (d->Hkv > 65535 || d->B > 65535) return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: B or Hkv above 65535");
-    if (d->T > (int64_t)1 << 30) return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: T above 2^30");
+    if (d->T > (int64_t)1 << 20) return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: T above 2^20");
     if (!csr::plan_decode(d->B, d->Hq, d->Hkv, d->T, d->d, d->N, plan))
         return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: N=%d atoms do not fit the LDS-resident score and histogram tables", d->N);
     return CSR_OK;

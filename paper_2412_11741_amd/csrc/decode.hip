@@ -8,13 +8,19 @@
 //
 // Four launches on the caller's stream:
 //   qd_kernel        qd[b][h][n][g] = scale * q[b][hg] . d^K_n   (also clears the output accumulator)
-//   stream_kernel    one workgroup per (token chunk, KV head x group slice, sequence):
-//                    score table qd and histogram hist live in LDS as [N][GB]; the K and V code
-//                    streams are read once, coalesced; softmax is kept online per workgroup (running
-//                    max, the histogram is rescaled when the max moves, which gets rare quickly);
-//                    the chunk's histogram, max and sum go to scratch
+//   stream_kernel    one workgroup per (token chunk, KV head x group slice, sequence), two passes over
+//                    its tokens.  Pass 1: the score table qd sits in LDS as [N][GB]; the K code stream
+//                    is read once, coalesced, and every thread keeps the scores of its tokens in
+//                    registers; one reduction gives the chunk's maximum.  Pass 2: the same LDS now
+//                    holds the histogram; p = exp(score - max) and the V code stream is scattered
+//                    into it.  The histogram is 64-bit fixed point (2^-32 units, integer LDS atomics):
+//                    on this chip the LDS float atomic add is serialised lane by lane and runs about
+//                    thirty times slower than the integer one, and integer sums are exact, so the
+//                    result does not depend on the order of the adds.  The chunk's histogram (as
+//                    fp32), maximum and sum go to scratch.
 //   out_kernel       combines chunk histograms with exp(m_c - M) weights and multiplies by a slice of
-//                    D_V, adding into an fp32 accumulator
+//                    D_V for all sequences and query heads of a KV head at once, adding into an fp32
+//                    accumulator
 //   finalize_kernel  divides by the softmax denominator and stores in the output type
 #include <cmath>
 
@@ -25,10 +31,12 @@ namespace {
 
 constexpr int kStreamThreads = 1024;  // 16 waves: enough loads in flight with one workgroup per CU
 constexpr int kStreamWaves = kStreamThreads / 64;
+constexpr int kMaxTPT = 16;           // tokens per thread and chunk: their scores stay in registers
 constexpr int kOutAtoms = 64;         // atoms of D_V per out_kernel workgroup
 constexpr int kQdAtoms = 64;          // atoms of D_K per qd_kernel workgroup
 constexpr int kQTile = 32;            // queries staged in LDS at a time by qd_kernel
 constexpr int kMaxChunks = 64;
+constexpr int kMaxBG = 32;            // sequences x query heads per KV head that out_kernel handles per pass
 constexpr size_t kLdsBudget = 150 * 1024;
 
 __device__ __forceinline__ float h2f(__half v) { return __half2float(v); }
@@ -207,8 +215,22 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
+// p * c as a 64-bit fixed-point number in units of 2^-32 (two's complement).  |x| < 2^31 is given:
+// p <= 1 and |c| is an fp16 or a sane fp32 coefficient.  x - floor(x) is exact in fp32.
+__device__ __forceinline__ unsigned long long to_fixed(float x)
+{
+    const float fl = floorf(x);
+    const int hi = (int)fl;
+    const unsigned lo = (unsigned)((x - fl) * 4294967296.0f);
+    return ((unsigned long long)(unsigned)hi << 32) | lo;
+}
+__device__ __forceinline__ float from_fixed(unsigned long long v)
+{
+    return (float)(int)(unsigned)(v >> 32) + (float)(unsigned)(v & 0xffffffffull) * 2.3283064365386963e-10f;
+}
+
 // One workgroup: chunk c of the tokens of (sequence b, KV head h, group slice gs).
-// LDS: qd_s[N*GB] | hist[N*GB] | red[2][waves][GB]
+// LDS: table[N*GB] as fp32 scores q.d (pass 1), then as 64-bit histogram (pass 2) | red[waves][GB]
 template <int GB, typename TI, typename TC, int PV>
 __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
     const float *__restrict__ qd, const TI *__restrict__ idxK, const TC *__restrict__ coefK,
@@ -216,10 +238,10 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
     float *__restrict__ part_hist, float *__restrict__ part_ml, int32_t Hkv, int32_t ngs, int64_t T,
     int32_t N, int32_t sK, int32_t sV, int64_t chunk_tokens, int32_t nchunks)
 {
-    extern __shared__ float smem[];
-    float *qd_s = smem;
-    float *hist = smem + (size_t)N * GB;
-    float *red = hist + (size_t)N * GB;  // [2][kStreamWaves][GB]
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    float *qd_s = reinterpret_cast<float *>(smem_raw);
+    unsigned long long *hist = reinterpret_cast<unsigned long long *>(smem_raw);
+    float *red = reinterpret_cast<float *>(smem_raw + (size_t)N * GB * 8);  // [kStreamWaves][GB]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -245,84 +267,90 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
     const int table = N * GB;
     {
         const float *src = qd + (((int64_t)b * Hkv + h) * ngs + gs) * (int64_t)table;
-        for (int e = tid; e < table; e += kStreamThreads) { qd_s[e] = src[e]; hist[e] = 0.0f; }
+        for (int e = tid * 4; e < table; e += kStreamThreads * 4) {
+            if (e + 4 <= table) *reinterpret_cast<float4 *>(qd_s + e) = *reinterpret_cast<const float4 *>(src + e);
+            else for (int r = e; r < table; ++r) qd_s[r] = src[r];
+        }
     }
     __syncthreads();
 
     const int64_t code_row = ((int64_t)b * Hkv + h) * T;
-    float m_run[GB], l_thr[GB];
-#pragma unroll
-    for (int g = 0; g < GB; ++g) { m_run[g] = -INFINITY; l_thr[g] = 0.0f; }
+    const int n_mine = (int)((t_end - t0 + kStreamThreads - 1) / kStreamThreads);  // rounds of 1024 tokens
 
-    int it = 0;
-    for (int64_t tb = t0; tb < t_end; tb += kStreamThreads, ++it) {
-        const int64_t t = tb + tid;
-        const bool valid = t < t_end;
-        float sc[GB];
+    // ---- pass 1: scores of this thread's tokens (token t0 + i * 1024 + tid in round i) --------
+    float sc[kMaxTPT][GB];
+    float mx[GB];
 #pragma unroll
-        for (int g = 0; g < GB; ++g) sc[g] = 0.0f;
-        if (valid) {
-            const TI *ip = idxK + (code_row + t) * sK;
-            const TC *cp = coefK + (code_row + t) * sK;
-            for (int j0 = 0; j0 < sK; j0 += PV) {
-                int id[PV];
-                float cf[PV];
-                IdxLoad<TI, PV>::ld(ip + j0, id);
-                CoefLoad<TC, PV>::ld(cp + j0, cf);
+    for (int g = 0; g < GB; ++g) mx[g] = -INFINITY;
 #pragma unroll
-                for (int j = 0; j < PV; ++j) {
+    for (int i = 0; i < kMaxTPT; ++i) {
 #pragma unroll
-                    for (int g = 0; g < GB; ++g) sc[g] = fmaf(cf[j], qd_s[id[j] * GB + g], sc[g]);
+        for (int g = 0; g < GB; ++g) sc[i][g] = -INFINITY;
+        if (i < n_mine) {
+            const int64_t t = t0 + (int64_t)i * kStreamThreads + tid;
+            if (t < t_end) {
+                float acc[GB];
+#pragma unroll
+                for (int g = 0; g < GB; ++g) acc[g] = 0.0f;
+                const TI *ip = idxK + (code_row + t) * sK;
+                const TC *cp = coefK + (code_row + t) * sK;
+                for (int j0 = 0; j0 < sK; j0 += PV) {
+                    int id[PV];
+                    float cf[PV];
+                    IdxLoad<TI, PV>::ld(ip + j0, id);
+                    CoefLoad<TC, PV>::ld(cp + j0, cf);
+#pragma unroll
+                    for (int j = 0; j < PV; ++j) {
+#pragma unroll
+                        for (int g = 0; g < GB; ++g) acc[g] = fmaf(cf[j], qd_s[id[j] * GB + g], acc[g]);
+                    }
                 }
-            }
-        } else {
 #pragma unroll
-            for (int g = 0; g < GB; ++g) sc[g] = -INFINITY;
-        }
-        float *rbuf = red + (it & 1) * (kStreamWaves * GB);
-#pragma unroll
-        for (int g = 0; g < GB; ++g) {
-            const float wm = wave_max(sc[g]);
-            if (lane == 0) rbuf[wave * GB + g] = wm;
-        }
-        __syncthreads();
-        bool moved = false;
-        float fac[GB];
-#pragma unroll
-        for (int g = 0; g < GB; ++g) {
-            float mx = rbuf[g];
-#pragma unroll
-            for (int w = 1; w < kStreamWaves; ++w) mx = fmaxf(mx, rbuf[w * GB + g]);
-            fac[g] = 1.0f;
-            if (mx > m_run[g]) {
-                if (m_run[g] > -INFINITY) { fac[g] = __expf(m_run[g] - mx); moved = true; }
-                m_run[g] = mx;
+                for (int g = 0; g < GB; ++g) { sc[i][g] = acc[g]; mx[g] = fmaxf(mx[g], acc[g]); }
             }
         }
-        if (moved) {  // uniform over the workgroup: every thread saw the same maxima
-            for (int e = tid; e < N; e += kStreamThreads) {
+    }
 #pragma unroll
-                for (int g = 0; g < GB; ++g) hist[e * GB + g] *= fac[g];
-            }
+    for (int g = 0; g < GB; ++g) {
+        const float wm = wave_max(mx[g]);
+        if (lane == 0) red[wave * GB + g] = wm;
+    }
+    __syncthreads();  // every score is computed: the table is free
+    float m_c[GB];
 #pragma unroll
-            for (int g = 0; g < GB; ++g) l_thr[g] *= fac[g];
-            __syncthreads();
-        }
-        if (valid) {
-            float p[GB];
+    for (int g = 0; g < GB; ++g) {
+        float v = red[g];
 #pragma unroll
-            for (int g = 0; g < GB; ++g) { p[g] = __expf(sc[g] - m_run[g]); l_thr[g] += p[g]; }
-            const TI *ip = idxV + (code_row + t) * sV;
-            const TC *cp = coefV + (code_row + t) * sV;
-            for (int j0 = 0; j0 < sV; j0 += PV) {
-                int id[PV];
-                float cf[PV];
-                IdxLoad<TI, PV>::ld(ip + j0, id);
-                CoefLoad<TC, PV>::ld(cp + j0, cf);
+        for (int w = 1; w < kStreamWaves; ++w) v = fmaxf(v, red[w * GB + g]);
+        m_c[g] = v;
+    }
+    for (int e = tid; e < table; e += kStreamThreads) hist[e] = 0ull;
+    __syncthreads();
+
+    // ---- pass 2: p = exp(score - max), scatter p * c of the V codes into the histogram -----------
+    float l_thr[GB];
 #pragma unroll
-                for (int j = 0; j < PV; ++j) {
+    for (int g = 0; g < GB; ++g) l_thr[g] = 0.0f;
 #pragma unroll
-                    for (int g = 0; g < GB; ++g) atomicAdd(&hist[id[j] * GB + g], p[g] * cf[j]);
+    for (int i = 0; i < kMaxTPT; ++i) {
+        if (i < n_mine) {
+            const int64_t t = t0 + (int64_t)i * kStreamThreads + tid;
+            if (t < t_end) {
+                float p[GB];
+#pragma unroll
+                for (int g = 0; g < GB; ++g) { p[g] = __expf(sc[i][g] - m_c[g]); l_thr[g] += p[g]; }
+                const TI *ip = idxV + (code_row + t) * sV;
+                const TC *cp = coefV + (code_row + t) * sV;
+                for (int j0 = 0; j0 < sV; j0 += PV) {
+                    int id[PV];
+                    float cf[PV];
+                    IdxLoad<TI, PV>::ld(ip + j0, id);
+                    CoefLoad<TC, PV>::ld(cp + j0, cf);
+#pragma unroll
+                    for (int j = 0; j < PV; ++j) {
+#pragma unroll
+                        for (int g = 0; g < GB; ++g) atomicAdd(&hist[id[j] * GB + g], to_fixed(p[g] * cf[j]));
+                    }
                 }
             }
         }
@@ -340,72 +368,90 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
         if (tid == g) {
             float l = 0.0f;
             for (int w = 0; w < kStreamWaves; ++w) l += red[w * GB + g];
-            ml[2 * g] = m_run[g];
+            ml[2 * g] = m_c[g];
             ml[2 * g + 1] = l;
         }
     }
     float *dst = part_hist + slot * (int64_t)table;
-    for (int e = tid; e < table; e += kStreamThreads) dst[e] = hist[e];
+    for (int e = tid; e < table; e += kStreamThreads) dst[e] = from_fixed(hist[e]);
 }
 
 // ---------------------------------------------------------------------------------------------
-// out_acc[b][hq][k] += sum_{n in slice} (sum_c w_c hist_c[n][g]) * DV[h][n][k]
+// out_acc[b][hq][k] += sum_{n in slice} (sum_c w_c hist_c[n][g]) * DV[h][n][k] for every sequence b and
+// query head g of KV head h: the slice of D_V is read once for all of them.  Thread (half, k) owns output
+// dimension k over half of the slice's atoms.
 template <typename TD>
-__global__ __launch_bounds__(128) void out_kernel(const TD *__restrict__ DV, const float *__restrict__ part_hist,
+__global__ __launch_bounds__(256) void out_kernel(const TD *__restrict__ DV, const float *__restrict__ part_hist,
                                                   const float *__restrict__ part_ml, float *__restrict__ out_acc,
-                                                  int32_t Hq, int32_t Hkv, int32_t G, int32_t GB, int32_t N,
+                                                  int32_t B, int32_t Hq, int32_t Hkv, int32_t G, int32_t GB, int32_t N,
                                                   int32_t nchunks)
 {
-    __shared__ float dv_s[kOutAtoms][128];
-    __shared__ float hist_s[8][kOutAtoms];
-    __shared__ float w_s[8][kMaxChunks];
+    __shared__ __attribute__((aligned(16))) TD dv_s[kOutAtoms][128];
+    __shared__ float hist_s[kMaxBG][kOutAtoms];
+    __shared__ float w_s[kMaxBG][kMaxChunks];
     const int tid = threadIdx.x;
     const int n0 = blockIdx.x * kOutAtoms;
-    const int h = blockIdx.y, b = blockIdx.z;
+    const int h = blockIdx.y;
     const int ngs = G / GB;
+    constexpr int kVec = 16 / sizeof(TD);  // elements per 16-byte load
 
-    for (int e = tid; e < kOutAtoms * 16; e += 128) {
-        const int r = e >> 4, cch = e & 15;
-        float v[8];
-        if (n0 + r < N) load8<TD>(DV + ((int64_t)h * N + n0 + r) * 128 + cch * 8, v);
-        else {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) v[j] = 0.0f;
-        }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) dv_s[r][cch * 8 + j] = v[j];
+    for (int e = tid; e < kOutAtoms * (128 / kVec); e += 256) {
+        const int r = e / (128 / kVec), cch = e % (128 / kVec);
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (n0 + r < N) v = *reinterpret_cast<const uint4 *>(DV + ((int64_t)h * N + n0 + r) * 128 + cch * kVec);
+        *reinterpret_cast<uint4 *>(&dv_s[r][cch * kVec]) = v;
     }
-    if (tid < G) {
-        const int gs = tid / GB, gg = tid % GB;
-        const float *ml = part_ml + ((((int64_t)b * Hkv + h) * ngs + gs) * nchunks) * (2 * GB);
-        float M = -INFINITY;
-        for (int c = 0; c < nchunks; ++c) M = fmaxf(M, ml[c * 2 * GB + 2 * gg]);
-        for (int c = 0; c < nchunks; ++c) {
-            const float m = ml[c * 2 * GB + 2 * gg];
-            w_s[tid][c] = (m > -INFINITY) ? __expf(m - M) : 0.0f;
-        }
-    }
-    __syncthreads();
-    for (int e = tid; e < G * kOutAtoms; e += 128) {
-        const int g = e / kOutAtoms, nn = e % kOutAtoms;
-        const int gs = g / GB, gg = g % GB;
-        float acc = 0.0f;
-        if (n0 + nn < N) {
-            const float *ph = part_hist + ((((int64_t)b * Hkv + h) * ngs + gs) * nchunks) * (int64_t)N * GB +
-                              (int64_t)(n0 + nn) * GB + gg;
+    const int BG = B * G;
+    for (int bg0 = 0; bg0 < BG; bg0 += kMaxBG) {
+        const int nbg = min(kMaxBG, BG - bg0);
+        __syncthreads();  // dv_s is loaded; hist_s / w_s of the previous pass are no longer read
+        if (tid < nbg) {
+            const int b = (bg0 + tid) / G, g = (bg0 + tid) % G;
+            const int gs = g / GB, gg = g % GB;
+            const float *ml = part_ml + ((((int64_t)b * Hkv + h) * ngs + gs) * nchunks) * (2 * GB);
+            float M = -INFINITY;
+            for (int c = 0; c < nchunks; ++c) M = fmaxf(M, ml[c * 2 * GB + 2 * gg]);
             for (int c = 0; c < nchunks; ++c) {
-                const float w = w_s[g][c];
-                if (w > 0.0f) acc = fmaf(w, ph[(int64_t)c * N * GB], acc);
+                const float m = ml[c * 2 * GB + 2 * gg];
+                w_s[tid][c] = (m > -INFINITY) ? __expf(m - M) : 0.0f;
             }
         }
-        hist_s[g][nn] = acc;
-    }
-    __syncthreads();
-    for (int g = 0; g < G; ++g) {
-        float acc = 0.0f;
-#pragma unroll 16
-        for (int nn = 0; nn < kOutAtoms; ++nn) acc = fmaf(hist_s[g][nn], dv_s[nn][tid], acc);
-        atomicAdd(&out_acc[((int64_t)b * Hq + h * G + g) * 128 + tid], acc);
+        __syncthreads();
+        for (int e = tid; e < nbg * kOutAtoms; e += 256) {
+            const int bgl = e / kOutAtoms, nn = e % kOutAtoms;
+            const int b = (bg0 + bgl) / G, g = (bg0 + bgl) % G;
+            const int gs = g / GB, gg = g % GB;
+            float acc = 0.0f;
+            if (n0 + nn < N) {
+                const float *ph = part_hist + ((((int64_t)b * Hkv + h) * ngs + gs) * nchunks) * (int64_t)N * GB +
+                                  (int64_t)(n0 + nn) * GB + gg;
+                for (int c = 0; c < nchunks; ++c) {
+                    const float w = w_s[bgl][c];
+                    if (w > 0.0f) acc = fmaf(w, ph[(int64_t)c * N * GB], acc);
+                }
+            }
+            hist_s[bgl][nn] = acc;
+        }
+        __syncthreads();
+        const int k = tid & 127, half = tid >> 7;
+        for (int q0 = 0; q0 < nbg; q0 += 8) {
+            float acc[8];
+#pragma unroll
+            for (int r = 0; r < 8; ++r) acc[r] = 0.0f;
+#pragma unroll 8
+            for (int nn = half * (kOutAtoms / 2); nn < (half + 1) * (kOutAtoms / 2); ++nn) {
+                const float dv = (float)dv_s[nn][k];
+#pragma unroll
+                for (int r = 0; r < 8; ++r) acc[r] = fmaf(hist_s[min(q0 + r, nbg - 1)][nn], dv, acc[r]);
+            }
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                if (q0 + r < nbg) {
+                    const int b = (bg0 + q0 + r) / G, g = (bg0 + q0 + r) % G;
+                    atomicAdd(&out_acc[((int64_t)b * Hq + h * G + g) * 128 + k], acc[r]);
+                }
+            }
+        }
     }
 }
 
@@ -477,19 +523,23 @@ bool plan_decode(int32_t B, int32_t Hq, int32_t Hkv, int64_t T, int32_t d, int32
     int GB = 0;
     for (int cand : {4, 2, 1}) {
         if (G % cand != 0) continue;
-        const size_t lds = (size_t)2 * N * cand * sizeof(float) + (size_t)2 * kStreamWaves * cand * sizeof(float);
+        // score table (fp32) and histogram (64-bit) share the space: the larger one counts
+        const size_t lds = (size_t)N * cand * 8 + (size_t)kStreamWaves * cand * sizeof(float);
         if (lds <= kLdsBudget) { GB = cand; p->lds_bytes = lds; break; }
     }
     if (!GB) return false;
     p->GB = GB;
     p->ngs = G / GB;
-    // Split the token axis until the launch has a couple of workgroups per CU; every extra chunk
-    // costs one histogram round trip through scratch, so no more than that.
+    // Split the token axis until every CU has a workgroup; every extra chunk costs one histogram
+    // round trip through scratch, so no more than that, except that a chunk holds at most
+    // kMaxTPT x 1024 tokens (a thread keeps its tokens' scores in registers).
     const int64_t groups = (int64_t)(B > 0 ? B : 1) * Hkv * p->ngs;
-    int64_t want = (512 + groups - 1) / groups;
+    int64_t want = (256 + groups - 1) / groups;
     const int64_t most = T > 0 ? (T + kStreamThreads - 1) / kStreamThreads : 1;
+    const int64_t least = T > 0 ? (T + (int64_t)kMaxTPT * kStreamThreads - 1) / ((int64_t)kMaxTPT * kStreamThreads) : 1;
     if (want > most) want = most;
-    if (want > kMaxChunks) want = kMaxChunks;
+    if (want < least) want = least;
+    if (want > kMaxChunks) return false;
     if (want < 1) want = 1;
     int64_t ct = T > 0 ? (T + want - 1) / want : kStreamThreads;
     ct = (ct + kStreamThreads - 1) / kStreamThreads * kStreamThreads;
@@ -537,13 +587,13 @@ hipError_t launch_decode(const DecodeArgs &a, const DecodePlan &p)
         if (e != hipSuccess) return e;
     }
     {
-        const dim3 grid((unsigned)((a.N + kOutAtoms - 1) / kOutAtoms), (unsigned)a.Hkv, (unsigned)a.B);
+        const dim3 grid((unsigned)((a.N + kOutAtoms - 1) / kOutAtoms), (unsigned)a.Hkv);
         if (a.dict16)
-            hipLaunchKernelGGL((out_kernel<__half>), grid, dim3(128), 0, a.stream, (const __half *)a.DV, hist, ml,
-                               acc, a.Hq, a.Hkv, a.G, p.GB, a.N, p.nchunks);
+            hipLaunchKernelGGL((out_kernel<__half>), grid, dim3(256), 0, a.stream, (const __half *)a.DV, hist, ml,
+                               acc, a.B, a.Hq, a.Hkv, a.G, p.GB, a.N, p.nchunks);
         else
-            hipLaunchKernelGGL((out_kernel<float>), grid, dim3(128), 0, a.stream, (const float *)a.DV, hist, ml,
-                               acc, a.Hq, a.Hkv, a.G, p.GB, a.N, p.nchunks);
+            hipLaunchKernelGGL((out_kernel<float>), grid, dim3(256), 0, a.stream, (const float *)a.DV, hist, ml,
+                               acc, a.B, a.Hq, a.Hkv, a.G, p.GB, a.N, p.nchunks);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
