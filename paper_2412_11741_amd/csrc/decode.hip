@@ -7,7 +7,7 @@
 // so per cached token only its 2s-odd code pairs are read from HBM instead of 2d values.
 //
 // Four launches on the caller's stream:
-//   qd_kernel        qd[b][h][n][g] = scale * q[b][hg] . d^K_n   (also clears the output accumulator)
+//   qd_kernel        qd[b][h][n][g] = scale * q[b][hg] . d^K_n  (matrix cores when both are fp16)
 //   stream_kernel    one workgroup per (token chunk, KV head x group slice, sequence), two passes over
 //                    its tokens.  Pass 1: the score table qd sits in LDS as [N][GB]; the K code stream
 //                    is read once, coalesced, and every thread keeps the scores of its tokens in
@@ -19,9 +19,12 @@
 //                    result does not depend on the order of the adds.  The chunk's histogram (as
 //                    fp32), maximum and sum go to scratch.
 //   out_kernel       combines chunk histograms with exp(m_c - M) weights and multiplies by a slice of
-//                    D_V for all sequences and query heads of a KV head at once, adding into an fp32
-//                    accumulator
-//   finalize_kernel  divides by the softmax denominator and stores in the output type
+//                    D_V for all sequences and query heads of a KV head at once; one partial output
+//                    per slice goes to scratch (no float atomics anywhere: the result is the same
+//                    bits on every run)
+//   finalize_kernel  adds the slices' partial outputs, divides by the softmax denominator and
+//                    stores in the output type.  (Folding this into out_kernel's last workgroup per
+//                    head was tried: the device-scope fences it needs cost more than the launch.)
 #include <cmath>
 
 #include "csr_internal.h"
@@ -32,7 +35,8 @@ namespace {
 constexpr int kStreamThreads = 1024;  // 16 waves: enough loads in flight with one workgroup per CU
 constexpr int kStreamWaves = kStreamThreads / 64;
 constexpr int kMaxTPT = 16;           // tokens per thread and chunk: their scores stay in registers
-constexpr int kOutAtoms = 64;         // atoms of D_V per out_kernel workgroup
+constexpr int kOutAtomsF16 = 128;     // atoms of D_V per out_kernel workgroup, fp16 dictionary
+constexpr int kOutAtomsF32 = 64;      // same, fp32 dictionary (the slice sits in LDS in its own type)
 constexpr int kQdAtoms = 64;          // atoms of D_K per qd_kernel workgroup
 constexpr int kQTile = 32;            // queries staged in LDS at a time by qd_kernel
 constexpr int kMaxChunks = 64;
@@ -66,7 +70,7 @@ template <> __device__ __forceinline__ void load8<float>(const float *p, float (
 // 16 lanes share one atom row (8 consecutive k each), so a wave reads 4 rows = 1 KiB per load.
 template <typename TQ, typename TD>
 __global__ __launch_bounds__(256) void qd_kernel(const TQ *__restrict__ q, const TD *__restrict__ DK,
-                                                 float *__restrict__ qd, float *__restrict__ out_acc,
+                                                 float *__restrict__ qd,
                                                  int32_t B, int32_t Hq, int32_t Hkv, int32_t G,
                                                  int32_t GB, int32_t N, float scale)
 {
@@ -76,14 +80,6 @@ __global__ __launch_bounds__(256) void qd_kernel(const TQ *__restrict__ q, const
     const int sub = tid & 15, arow = tid >> 4;
     const int n_base = blockIdx.x * kQdAtoms;
     const int ngs = G / GB;
-
-    // clear the fp32 output accumulator (whole grid, strided)
-    {
-        const int64_t total = (int64_t)B * Hq * 128;
-        const int64_t stride = (int64_t)gridDim.x * gridDim.y * blockDim.x;
-        for (int64_t i = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * blockDim.x + tid; i < total; i += stride)
-            out_acc[i] = 0.0f;
-    }
 
     float a[4][8];
 #pragma unroll
@@ -132,6 +128,74 @@ __global__ __launch_bounds__(256) void qd_kernel(const TQ *__restrict__ q, const
                 for (int i = 0; i < 4; ++i) {
                     const int n = n_base + arow + 16 * i;
                     if (n < N) dst[(int64_t)n * GB + gg] = scale * dot[i];
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same product on the matrix cores, fp16 queries and dictionary (fp16 products are exact, fp32
+// accumulation).  One wave per 32-atom tile: queries are the M rows of v_mfma_f32_32x32x16_f16, atoms
+// the N columns, so a lane ends up with one atom and, per group of four accumulators, four
+// consecutive queries - the [n][gg] order of the table.  The contraction index is permuted as in the
+// encoder: lane half 0 holds dimensions 0..63, half 1 holds 64..127, i.e. 128 contiguous bytes of
+// its atom row.
+typedef _Float16 qd_half8 __attribute__((ext_vector_type(8)));
+typedef float qd_floatx16 __attribute__((ext_vector_type(16)));
+
+__global__ __launch_bounds__(256) void qd_mfma_kernel(const __half *__restrict__ q, const __half *__restrict__ DK,
+                                                      float *__restrict__ qd, int32_t B, int32_t Hq, int32_t Hkv,
+                                                      int32_t G, int32_t GB, int32_t N, float scale)
+{
+    const int h = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = lane & 31, hf = lane >> 5;
+    const int n_tile = (blockIdx.x * 4 + wave) * 32;
+    if (n_tile >= N) return;
+    const int n = n_tile + col;
+    const int ngs = G / GB;
+    const int BG = B * G;
+
+    qd_half8 bfrag[8];
+    {
+        const __half *row = DK + ((int64_t)h * N + min(n, N - 1)) * 128 + hf * 64;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint4 raw = *reinterpret_cast<const uint4 *>(row + 8 * j);
+            bfrag[j] = *reinterpret_cast<const qd_half8 *>(&raw);
+        }
+    }
+    for (int q0 = 0; q0 < BG; q0 += 32) {
+        qd_floatx16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+        const int bgq = q0 + col;  // this lane's query row of the A operand
+        const bool have = bgq < BG;
+        const __half *qrow = q + ((int64_t)(have ? bgq / G : 0) * Hq + h * G + (have ? bgq % G : 0)) * 128 + hf * 64;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            uint4 raw = make_uint4(0u, 0u, 0u, 0u);
+            if (have) raw = *reinterpret_cast<const uint4 *>(qrow + 8 * j);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(*reinterpret_cast<const qd_half8 *>(&raw), bfrag[j], acc, 0, 0, 0);
+        }
+        if (n < N) {
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                const int bg = q0 + 8 * r4 + 4 * hf;  // first of four consecutive queries
+                if (GB == 4 && bg + 3 < BG) {          // G is a multiple of 4: same sequence, same group slice
+                    const int b = bg / G, g = bg % G;
+                    float *dst = qd + ((((int64_t)b * Hkv + h) * ngs + g / 4) * (int64_t)N + n) * 4;
+                    *reinterpret_cast<float4 *>(dst) = make_float4(scale * acc[4 * r4], scale * acc[4 * r4 + 1],
+                                                                   scale * acc[4 * r4 + 2], scale * acc[4 * r4 + 3]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (bg + e < BG) {
+                            const int b = (bg + e) / G, g = (bg + e) % G;
+                            qd[((((int64_t)b * Hkv + h) * ngs + g / GB) * (int64_t)N + n) * GB + g % GB] = scale * acc[4 * r4 + e];
+                        }
+                    }
                 }
             }
         }
@@ -377,34 +441,41 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// out_acc[b][hq][k] += sum_{n in slice} (sum_c w_c hist_c[n][g]) * DV[h][n][k] for every sequence b and
-// query head g of KV head h: the slice of D_V is read once for all of them.  Thread (half, k) owns output
-// dimension k over half of the slice's atoms.
-template <typename TD>
+// part_out[h][slice][b*G+g][k] = sum_{n in slice} (sum_c w_c hist_c[n][g]) * DV[h][n][k] for every
+// sequence b and query head g of KV head h: the slice of D_V is read once for all of them (its loads
+// are in flight while the chunk weights and histograms are combined).  Thread (half, k) owns output
+// dimension k over half of the slice's atoms; the halves meet in LDS.
+template <typename TD, int ATOMS>
 __global__ __launch_bounds__(256) void out_kernel(const TD *__restrict__ DV, const float *__restrict__ part_hist,
-                                                  const float *__restrict__ part_ml, float *__restrict__ out_acc,
-                                                  int32_t B, int32_t Hq, int32_t Hkv, int32_t G, int32_t GB, int32_t N,
+                                                  const float *__restrict__ part_ml, float *__restrict__ part_out,
+                                                  int32_t B, int32_t Hkv, int32_t G, int32_t GB, int32_t N,
                                                   int32_t nchunks)
 {
-    __shared__ __attribute__((aligned(16))) TD dv_s[kOutAtoms][128];
-    __shared__ float hist_s[kMaxBG][kOutAtoms];
+    __shared__ __attribute__((aligned(16))) TD dv_s[ATOMS][128];
+    __shared__ float hist_s[kMaxBG][ATOMS];
     __shared__ float w_s[kMaxBG][kMaxChunks];
+    __shared__ float half_s[8][128];
     const int tid = threadIdx.x;
-    const int n0 = blockIdx.x * kOutAtoms;
+    const int n0 = blockIdx.x * ATOMS;
     const int h = blockIdx.y;
     const int ngs = G / GB;
-    constexpr int kVec = 16 / sizeof(TD);  // elements per 16-byte load
+    const int nslices = gridDim.x;
+    constexpr int kVec = 16 / sizeof(TD);               // elements per 16-byte load
+    constexpr int kLoads = ATOMS * (128 / kVec) / 256;  // 16-byte loads per thread
 
-    for (int e = tid; e < kOutAtoms * (128 / kVec); e += 256) {
+    uint4 dv_r[kLoads];
+#pragma unroll
+    for (int i = 0; i < kLoads; ++i) {
+        const int e = i * 256 + tid;
         const int r = e / (128 / kVec), cch = e % (128 / kVec);
-        uint4 v = make_uint4(0u, 0u, 0u, 0u);
-        if (n0 + r < N) v = *reinterpret_cast<const uint4 *>(DV + ((int64_t)h * N + n0 + r) * 128 + cch * kVec);
-        *reinterpret_cast<uint4 *>(&dv_s[r][cch * kVec]) = v;
+        dv_r[i] = make_uint4(0u, 0u, 0u, 0u);
+        if (n0 + r < N) dv_r[i] = *reinterpret_cast<const uint4 *>(DV + ((int64_t)h * N + n0 + r) * 128 + cch * kVec);
     }
     const int BG = B * G;
+    float *dst = part_out + ((int64_t)h * nslices + blockIdx.x) * BG * 128;
     for (int bg0 = 0; bg0 < BG; bg0 += kMaxBG) {
         const int nbg = min(kMaxBG, BG - bg0);
-        __syncthreads();  // dv_s is loaded; hist_s / w_s of the previous pass are no longer read
+        __syncthreads();  // hist_s / w_s of the previous pass are no longer read
         if (tid < nbg) {
             const int b = (bg0 + tid) / G, g = (bg0 + tid) % G;
             const int gs = g / GB, gg = g % GB;
@@ -417,8 +488,8 @@ __global__ __launch_bounds__(256) void out_kernel(const TD *__restrict__ DV, con
             }
         }
         __syncthreads();
-        for (int e = tid; e < nbg * kOutAtoms; e += 256) {
-            const int bgl = e / kOutAtoms, nn = e % kOutAtoms;
+        for (int e = tid; e < nbg * ATOMS; e += 256) {
+            const int bgl = e / ATOMS, nn = e % ATOMS;
             const int b = (bg0 + bgl) / G, g = (bg0 + bgl) % G;
             const int gs = g / GB, gg = g % GB;
             float acc = 0.0f;
@@ -432,6 +503,13 @@ __global__ __launch_bounds__(256) void out_kernel(const TD *__restrict__ DV, con
             }
             hist_s[bgl][nn] = acc;
         }
+        if (bg0 == 0) {
+#pragma unroll
+            for (int i = 0; i < kLoads; ++i) {
+                const int e = i * 256 + tid;
+                *reinterpret_cast<uint4 *>(&dv_s[e / (128 / kVec)][(e % (128 / kVec)) * kVec]) = dv_r[i];
+            }
+        }
         __syncthreads();
         const int k = tid & 127, half = tid >> 7;
         for (int q0 = 0; q0 < nbg; q0 += 8) {
@@ -439,27 +517,32 @@ __global__ __launch_bounds__(256) void out_kernel(const TD *__restrict__ DV, con
 #pragma unroll
             for (int r = 0; r < 8; ++r) acc[r] = 0.0f;
 #pragma unroll 8
-            for (int nn = half * (kOutAtoms / 2); nn < (half + 1) * (kOutAtoms / 2); ++nn) {
+            for (int nn = half * (ATOMS / 2); nn < (half + 1) * (ATOMS / 2); ++nn) {
                 const float dv = (float)dv_s[nn][k];
 #pragma unroll
                 for (int r = 0; r < 8; ++r) acc[r] = fmaf(hist_s[min(q0 + r, nbg - 1)][nn], dv, acc[r]);
             }
+            if (half == 1) {
 #pragma unroll
-            for (int r = 0; r < 8; ++r) {
-                if (q0 + r < nbg) {
-                    const int b = (bg0 + q0 + r) / G, g = (bg0 + q0 + r) % G;
-                    atomicAdd(&out_acc[((int64_t)b * Hq + h * G + g) * 128 + k], acc[r]);
-                }
+                for (int r = 0; r < 8; ++r) half_s[r][k] = acc[r];
             }
+            __syncthreads();
+            if (half == 0) {
+#pragma unroll
+                for (int r = 0; r < 8; ++r)
+                    if (q0 + r < nbg) dst[(int64_t)(bg0 + q0 + r) * 128 + k] = acc[r] + half_s[r][k];
+            }
+            __syncthreads();
         }
     }
 }
 
+// out[b][hq][k] = (sum over slices of part_out) / softmax denominator
 template <typename TO>
-__global__ __launch_bounds__(128) void finalize_kernel(const float *__restrict__ out_acc,
+__global__ __launch_bounds__(128) void finalize_kernel(const float *__restrict__ part_out,
                                                        const float *__restrict__ part_ml, TO *__restrict__ out,
-                                                       int32_t Hq, int32_t Hkv, int32_t G, int32_t GB,
-                                                       int32_t nchunks)
+                                                       int32_t B, int32_t Hq, int32_t Hkv, int32_t G, int32_t GB,
+                                                       int32_t nchunks, int32_t nslices)
 {
     const int hq = blockIdx.x % Hq, b = blockIdx.x / Hq;
     const int h = hq / G, g = hq % G;
@@ -472,9 +555,19 @@ __global__ __launch_bounds__(128) void finalize_kernel(const float *__restrict__
         const float m = ml[c * 2 * GB + 2 * gg];
         if (m > -INFINITY) L = fmaf(__expf(m - M), ml[c * 2 * GB + 2 * gg + 1], L);
     }
-    const int64_t o = ((int64_t)b * Hq + hq) * 128 + threadIdx.x;
-    const float v = L > 0.0f ? out_acc[o] / L : 0.0f;
-    out[o] = (TO)v;
+    const int BG = B * G;
+    const float *src = part_out + ((int64_t)h * nslices * BG + (b * G + g)) * 128 + threadIdx.x;
+    float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+    int sl = 0;
+    for (; sl + 4 <= nslices; sl += 4) {
+        a0 += src[(int64_t)(sl + 0) * BG * 128];
+        a1 += src[(int64_t)(sl + 1) * BG * 128];
+        a2 += src[(int64_t)(sl + 2) * BG * 128];
+        a3 += src[(int64_t)(sl + 3) * BG * 128];
+    }
+    for (; sl < nslices; ++sl) a0 += src[(int64_t)sl * BG * 128];
+    const float v = L > 0.0f ? ((a0 + a1) + (a2 + a3)) / L : 0.0f;
+    out[((int64_t)b * Hq + hq) * 128 + threadIdx.x] = (TO)v;
 }
 
 template <int GB, typename TI, typename TC, int PV>
@@ -551,7 +644,7 @@ bool plan_decode(int32_t B, int32_t Hq, int32_t Hkv, int64_t T, int32_t d, int32
     p->off_qd = off;   off += r256(BHq * N * sizeof(float));
     p->off_hist = off; off += r256(BHq * N * sizeof(float) * p->nchunks);
     p->off_ml = off;   off += r256(BHq * 2 * sizeof(float) * p->nchunks);
-    p->off_acc = off;  off += r256(BHq * 128 * sizeof(float));
+    p->off_acc = off;  off += r256(BHq * 128 * sizeof(float) * (size_t)((N + kOutAtomsF32 - 1) / kOutAtomsF32));
     p->total_bytes = off;
     return true;
 }
@@ -568,9 +661,12 @@ hipError_t launch_decode(const DecodeArgs &a, const DecodePlan &p)
         const dim3 grid((unsigned)((a.N + kQdAtoms - 1) / kQdAtoms), (unsigned)a.Hkv);
 #define CSR_QD(TQ, TD)                                                                              \
     hipLaunchKernelGGL((qd_kernel<TQ, TD>), grid, dim3(256), 0, a.stream, (const TQ *)a.q,          \
-                       (const TD *)a.DK, qd, acc, a.B, a.Hq, a.Hkv, a.G, p.GB, a.N, a.scale)
-        if (a.q16 && a.dict16) CSR_QD(__half, __half);
-        else if (a.q16) CSR_QD(__half, float);
+                       (const TD *)a.DK, qd, a.B, a.Hq, a.Hkv, a.G, p.GB, a.N, a.scale)
+        if (a.q16 && a.dict16) {
+            const dim3 mgrid((unsigned)((a.N + 127) / 128), (unsigned)a.Hkv);
+            hipLaunchKernelGGL(qd_mfma_kernel, mgrid, dim3(256), 0, a.stream, (const __half *)a.q,
+                               (const __half *)a.DK, qd, a.B, a.Hq, a.Hkv, a.G, p.GB, a.N, a.scale);
+        } else if (a.q16) CSR_QD(__half, float);
         else if (a.dict16) CSR_QD(float, __half);
         else CSR_QD(float, float);
 #undef CSR_QD
@@ -586,14 +682,16 @@ hipError_t launch_decode(const DecodeArgs &a, const DecodePlan &p)
         }
         if (e != hipSuccess) return e;
     }
+    const int out_atoms = a.dict16 ? kOutAtomsF16 : kOutAtomsF32;
+    const int nslices = (a.N + out_atoms - 1) / out_atoms;
     {
-        const dim3 grid((unsigned)((a.N + kOutAtoms - 1) / kOutAtoms), (unsigned)a.Hkv);
+        const dim3 grid((unsigned)nslices, (unsigned)a.Hkv);
         if (a.dict16)
-            hipLaunchKernelGGL((out_kernel<__half>), grid, dim3(256), 0, a.stream, (const __half *)a.DV, hist, ml,
-                               acc, a.B, a.Hq, a.Hkv, a.G, p.GB, a.N, p.nchunks);
+            hipLaunchKernelGGL((out_kernel<__half, kOutAtomsF16>), grid, dim3(256), 0, a.stream, (const __half *)a.DV,
+                               hist, ml, acc, a.B, a.Hkv, a.G, p.GB, a.N, p.nchunks);
         else
-            hipLaunchKernelGGL((out_kernel<float>), grid, dim3(256), 0, a.stream, (const float *)a.DV, hist, ml,
-                               acc, a.B, a.Hq, a.Hkv, a.G, p.GB, a.N, p.nchunks);
+            hipLaunchKernelGGL((out_kernel<float, kOutAtomsF32>), grid, dim3(256), 0, a.stream, (const float *)a.DV,
+                               hist, ml, acc, a.B, a.Hkv, a.G, p.GB, a.N, p.nchunks);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -601,10 +699,10 @@ hipError_t launch_decode(const DecodeArgs &a, const DecodePlan &p)
         const dim3 grid((unsigned)(a.B * a.Hq));
         if (a.out16)
             hipLaunchKernelGGL((finalize_kernel<__half>), grid, dim3(128), 0, a.stream, acc, ml, (__half *)a.out,
-                               a.Hq, a.Hkv, a.G, p.GB, p.nchunks);
+                               a.B, a.Hq, a.Hkv, a.G, p.GB, p.nchunks, nslices);
         else
             hipLaunchKernelGGL((finalize_kernel<float>), grid, dim3(128), 0, a.stream, acc, ml, (float *)a.out,
-                               a.Hq, a.Hkv, a.G, p.GB, p.nchunks);
+                               a.B, a.Hq, a.Hkv, a.G, p.GB, p.nchunks, nslices);
         return hipGetLastError();
     }
 }
