@@ -19,7 +19,7 @@
 //                    result does not depend on the order of the adds.  The chunk's histogram (as
 //                    fp32), maximum and sum go to scratch.
 //   out_kernel       combines chunk histograms with exp(m_c - M) weights and multiplies by a slice of
-//                    D_V for all sequences and query heads of a KV head at once; one partial output
+//                    D_V for up to eight (sequence, query head) pairs of a KV head at once; one partial output
 //                    per slice goes to scratch (no float atomics anywhere: the result is the same
 //                    bits on every run)
 //   finalize_kernel  adds the slices' partial outputs, divides by the softmax denominator and
@@ -40,7 +40,7 @@ constexpr int kOutAtomsF32 = 64;      // same, fp32 dictionary (the slice sits i
 constexpr int kQdAtoms = 64;          // atoms of D_K per qd_kernel workgroup
 constexpr int kQTile = 32;            // queries staged in LDS at a time by qd_kernel
 constexpr int kMaxChunks = 64;
-constexpr int kMaxBG = 32;            // sequences x query heads per KV head that out_kernel handles per pass
+constexpr int kOutQ = 8;               // (sequence, query head) pairs of a KV head per out_kernel workgroup
 constexpr size_t kLdsBudget = 150 * 1024;
 
 __device__ __forceinline__ float h2f(__half v) { return __half2float(v); }
@@ -294,7 +294,8 @@ __device__ __forceinline__ float from_fixed(unsigned long long v)
 }
 
 // One workgroup: chunk c of the tokens of (sequence b, KV head h, group slice gs).
-// LDS: table[N*GB] as fp32 scores q.d (pass 1), then as 64-bit histogram (pass 2) | red[waves][GB]
+// LDS: table as fp32 scores q.d, [N][GB] (pass 1), then as 64-bit histogram, [GB][N] (pass 2: one table
+// per query head, so that the scatter of one head spreads over all banks) | red[waves][GB]
 template <int GB, typename TI, typename TC, int PV>
 __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
     const float *__restrict__ qd, const TI *__restrict__ idxK, const TC *__restrict__ coefK,
@@ -413,7 +414,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
 #pragma unroll
                     for (int j = 0; j < PV; ++j) {
 #pragma unroll
-                        for (int g = 0; g < GB; ++g) atomicAdd(&hist[id[j] * GB + g], to_fixed(p[g] * cf[j]));
+                        for (int g = 0; g < GB; ++g) atomicAdd(&hist[g * N + id[j]], to_fixed(p[g] * cf[j]));
                     }
                 }
             }
@@ -441,10 +442,11 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// part_out[h][slice][b*G+g][k] = sum_{n in slice} (sum_c w_c hist_c[n][g]) * DV[h][n][k] for every
-// sequence b and query head g of KV head h: the slice of D_V is read once for all of them (its loads
-// are in flight while the chunk weights and histograms are combined).  Thread (half, k) owns output
-// dimension k over half of the slice's atoms; the halves meet in LDS.
+// part_out[h][slice][b*G+g][k] = sum_{n in slice} (sum_c w_c hist_c[n][g]) * DV[h][n][k].
+// One workgroup: a slice of D_V (ATOMS atoms) times the histograms of up to kOutQ (sequence, query head)
+// pairs of KV head h.  All global loads - the slice, the chunk maxima, the chunk histograms - are issued
+// at once; the weights are applied when they have arrived.  Thread (half, k) owns output dimension k
+// over half of the slice's atoms; the halves meet in LDS.
 template <typename TD, int ATOMS>
 __global__ __launch_bounds__(256) void out_kernel(const TD *__restrict__ DV, const float *__restrict__ part_hist,
                                                   const float *__restrict__ part_ml, float *__restrict__ part_out,
@@ -452,16 +454,21 @@ __global__ __launch_bounds__(256) void out_kernel(const TD *__restrict__ DV, con
                                                   int32_t nchunks)
 {
     __shared__ __attribute__((aligned(16))) TD dv_s[ATOMS][128];
-    __shared__ float hist_s[kMaxBG][ATOMS];
-    __shared__ float w_s[kMaxBG][kMaxChunks];
-    __shared__ float half_s[8][128];
+    __shared__ __attribute__((aligned(16))) float hist_s[kOutQ][ATOMS];
+    __shared__ float w_s[kOutQ][kMaxChunks];
+    __shared__ float half_s[kOutQ][128];
     const int tid = threadIdx.x;
     const int n0 = blockIdx.x * ATOMS;
     const int h = blockIdx.y;
     const int ngs = G / GB;
     const int nslices = gridDim.x;
+    const int BG = B * G;
+    const int bg0 = blockIdx.z * kOutQ;
+    const int nbg = min(kOutQ, BG - bg0);
     constexpr int kVec = 16 / sizeof(TD);               // elements per 16-byte load
     constexpr int kLoads = ATOMS * (128 / kVec) / 256;  // 16-byte loads per thread
+    constexpr int kElems = kOutQ * ATOMS / 256;         // (query, atom) histogram entries per thread
+    constexpr int kEarly = 4;                           // chunks whose histograms are requested up front
 
     uint4 dv_r[kLoads];
 #pragma unroll
@@ -471,69 +478,85 @@ __global__ __launch_bounds__(256) void out_kernel(const TD *__restrict__ DV, con
         dv_r[i] = make_uint4(0u, 0u, 0u, 0u);
         if (n0 + r < N) dv_r[i] = *reinterpret_cast<const uint4 *>(DV + ((int64_t)h * N + n0 + r) * 128 + cch * kVec);
     }
-    const int BG = B * G;
-    float *dst = part_out + ((int64_t)h * nslices + blockIdx.x) * BG * 128;
-    for (int bg0 = 0; bg0 < BG; bg0 += kMaxBG) {
-        const int nbg = min(kMaxBG, BG - bg0);
-        __syncthreads();  // hist_s / w_s of the previous pass are no longer read
-        if (tid < nbg) {
-            const int b = (bg0 + tid) / G, g = (bg0 + tid) % G;
-            const int gs = g / GB, gg = g % GB;
-            const float *ml = part_ml + ((((int64_t)b * Hkv + h) * ngs + gs) * nchunks) * (2 * GB);
-            float M = -INFINITY;
-            for (int c = 0; c < nchunks; ++c) M = fmaxf(M, ml[c * 2 * GB + 2 * gg]);
-            for (int c = 0; c < nchunks; ++c) {
-                const float m = ml[c * 2 * GB + 2 * gg];
-                w_s[tid][c] = (m > -INFINITY) ? __expf(m - M) : 0.0f;
-            }
-        }
-        __syncthreads();
-        for (int e = tid; e < nbg * ATOMS; e += 256) {
-            const int bgl = e / ATOMS, nn = e % ATOMS;
+    // entry i of this thread: query bgl = e / ATOMS, atom nn = e % ATOMS with e = i * 256 + tid
+    const float *ph[kElems];
+    float early[kElems][kEarly];
+#pragma unroll
+    for (int i = 0; i < kElems; ++i) {
+        const int e = i * 256 + tid;
+        const int bgl = e / ATOMS, nn = e % ATOMS;
+        ph[i] = nullptr;
+        if (bgl < nbg && n0 + nn < N) {
             const int b = (bg0 + bgl) / G, g = (bg0 + bgl) % G;
-            const int gs = g / GB, gg = g % GB;
-            float acc = 0.0f;
-            if (n0 + nn < N) {
-                const float *ph = part_hist + ((((int64_t)b * Hkv + h) * ngs + gs) * nchunks) * (int64_t)N * GB +
-                                  (int64_t)(n0 + nn) * GB + gg;
-                for (int c = 0; c < nchunks; ++c) {
-                    const float w = w_s[bgl][c];
-                    if (w > 0.0f) acc = fmaf(w, ph[(int64_t)c * N * GB], acc);
-                }
-            }
-            hist_s[bgl][nn] = acc;
+            ph[i] = part_hist + ((((int64_t)b * Hkv + h) * ngs + g / GB) * nchunks) * (int64_t)N * GB +
+                    (int64_t)(g % GB) * N + (n0 + nn);
         }
-        if (bg0 == 0) {
 #pragma unroll
-            for (int i = 0; i < kLoads; ++i) {
-                const int e = i * 256 + tid;
-                *reinterpret_cast<uint4 *>(&dv_s[e / (128 / kVec)][(e % (128 / kVec)) * kVec]) = dv_r[i];
+        for (int c = 0; c < kEarly; ++c)
+            early[i][c] = (ph[i] && c < nchunks) ? ph[i][(int64_t)c * N * GB] : 0.0f;
+    }
+    if (tid < nbg) {
+        const int b = (bg0 + tid) / G, g = (bg0 + tid) % G;
+        const int gs = g / GB, gg = g % GB;
+        const float *ml = part_ml + ((((int64_t)b * Hkv + h) * ngs + gs) * nchunks) * (2 * GB);
+        float M = -INFINITY;
+        for (int c = 0; c < nchunks; ++c) M = fmaxf(M, ml[c * 2 * GB + 2 * gg]);
+        for (int c = 0; c < nchunks; ++c) {
+            const float m = ml[c * 2 * GB + 2 * gg];
+            w_s[tid][c] = (m > -INFINITY) ? __expf(m - M) : 0.0f;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < kLoads; ++i) {
+        const int e = i * 256 + tid;
+        *reinterpret_cast<uint4 *>(&dv_s[e / (128 / kVec)][(e % (128 / kVec)) * kVec]) = dv_r[i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kElems; ++i) {
+        const int e = i * 256 + tid;
+        const int bgl = e / ATOMS, nn = e % ATOMS;
+        float acc = 0.0f;
+        if (ph[i]) {
+            // a chunk without tokens has weight 0 and a histogram that was never written: skip, not multiply
+#pragma unroll
+            for (int c = 0; c < kEarly; ++c) {
+                const float w = c < nchunks ? w_s[bgl][c] : 0.0f;
+                if (w > 0.0f) acc = fmaf(w, early[i][c], acc);
+            }
+            for (int c = kEarly; c < nchunks; ++c) {
+                const float w = w_s[bgl][c];
+                if (w > 0.0f) acc = fmaf(w, ph[i][(int64_t)c * N * GB], acc);
             }
         }
-        __syncthreads();
-        const int k = tid & 127, half = tid >> 7;
-        for (int q0 = 0; q0 < nbg; q0 += 8) {
-            float acc[8];
+        hist_s[bgl][nn] = acc;
+    }
+    __syncthreads();
+    const int k = tid & 127, half = tid >> 7;
+    float acc[kOutQ];
 #pragma unroll
-            for (int r = 0; r < 8; ++r) acc[r] = 0.0f;
-#pragma unroll 8
-            for (int nn = half * (ATOMS / 2); nn < (half + 1) * (ATOMS / 2); ++nn) {
-                const float dv = (float)dv_s[nn][k];
+    for (int r = 0; r < kOutQ; ++r) acc[r] = 0.0f;
+    // four atoms at a time: four reads of this thread's column, one 16-byte broadcast read per query
+#pragma unroll 2
+    for (int nn = half * (ATOMS / 2); nn < (half + 1) * (ATOMS / 2); nn += 4) {
+        const float d0 = (float)dv_s[nn][k], d1 = (float)dv_s[nn + 1][k], d2 = (float)dv_s[nn + 2][k],
+                    d3 = (float)dv_s[nn + 3][k];
 #pragma unroll
-                for (int r = 0; r < 8; ++r) acc[r] = fmaf(hist_s[min(q0 + r, nbg - 1)][nn], dv, acc[r]);
-            }
-            if (half == 1) {
-#pragma unroll
-                for (int r = 0; r < 8; ++r) half_s[r][k] = acc[r];
-            }
-            __syncthreads();
-            if (half == 0) {
-#pragma unroll
-                for (int r = 0; r < 8; ++r)
-                    if (q0 + r < nbg) dst[(int64_t)(bg0 + q0 + r) * 128 + k] = acc[r] + half_s[r][k];
-            }
-            __syncthreads();
+        for (int r = 0; r < kOutQ; ++r) {
+            const float4 hv = *reinterpret_cast<const float4 *>(&hist_s[r][nn]);
+            acc[r] = fmaf(hv.x, d0, fmaf(hv.y, d1, fmaf(hv.z, d2, fmaf(hv.w, d3, acc[r]))));
         }
+    }
+    if (half == 1) {
+#pragma unroll
+        for (int r = 0; r < kOutQ; ++r) half_s[r][k] = acc[r];
+    }
+    __syncthreads();
+    if (half == 0) {
+        float *dst = part_out + (((int64_t)h * nslices + blockIdx.x) * BG + bg0) * 128;
+#pragma unroll
+        for (int r = 0; r < kOutQ; ++r)
+            if (r < nbg) dst[(int64_t)r * 128 + k] = acc[r] + half_s[r][k];
     }
 }
 
@@ -685,7 +708,7 @@ hipError_t launch_decode(const DecodeArgs &a, const DecodePlan &p)
     const int out_atoms = a.dict16 ? kOutAtomsF16 : kOutAtomsF32;
     const int nslices = (a.N + out_atoms - 1) / out_atoms;
     {
-        const dim3 grid((unsigned)nslices, (unsigned)a.Hkv);
+        const dim3 grid((unsigned)nslices, (unsigned)a.Hkv, (unsigned)((a.B * a.G + kOutQ - 1) / kOutQ));
         if (a.dict16)
             hipLaunchKernelGGL((out_kernel<__half, kOutAtomsF16>), grid, dim3(256), 0, a.stream, (const __half *)a.DV,
                                hist, ml, acc, a.B, a.Hkv, a.G, p.GB, a.N, p.nchunks);
