@@ -6,7 +6,12 @@ A step is one pass of the whole path over one batch of synthetic input, inputs r
   2. decode attention of one query token per head on those codes (csr_decode_attn).
 Prints ONE JSON line.  `value` is encoded KV vectors per second over the whole step; the decode
 rate (context tokens per second) and both rooflines are reported beside it, together with the CPU
-oracle timed on this machine's host cores on a bounded sample.
+oracle timed on this machine's host cores on a bounded sample.  `decode_rooflines` adds the decode
+call alone at the long-context and GQA shapes (random codes drawn on the GPU, cache-cold), where
+the code streams rather than the dictionaries dominate the traffic.
+
+All kernels run on PyTorch's current stream, and the HIP events that time them (torch.cuda.Event)
+are recorded on that same stream.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama7b_layer] [--algo auto]
 """
@@ -25,6 +30,54 @@ PEAK_VALU_F32_TFLOPS = 157.3    # MI355X fp32 vector peak
 PEAK_HBM_GBS = 8000.0           # MI355X HBM3E peak
 
 
+def decode_only(csr, w, dev):
+    """csr_decode_attn alone on workload `w`: uniformly random atom indices, N(0, 3) coefficients, unit-norm
+    Gaussian dictionaries, all drawn on the GPU with a fixed seed.  Distinct input copies are rotated
+    so that more than 1 GB is touched between reuses (the Infinity Cache holds 256 MB)."""
+    import torch
+    B, Hkv, Hq, T, N, d, s = w.batch, w.hkv, w.hq, w.tokens, w.n_atoms, w.d, w.s
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(0)
+
+    def unit(*shape):
+        a = torch.randn(*shape, device=dev, generator=gen)
+        return (a / a.norm(dim=-1, keepdim=True)).half()
+
+    def make():
+        idx = lambda: torch.randint(0, N, (B, Hkv, T, s), device=dev, generator=gen, dtype=torch.int32).to(torch.int16)
+        coef = lambda: (torch.randn(B, Hkv, T, s, device=dev, generator=gen) * 3).half()
+        return dict(q=torch.randn(B, Hq, d, device=dev, generator=gen).half(), DK=unit(Hkv, N, d), ik=idx(),
+                    ck=coef(), DV=unit(Hkv, N, d), iv=idx(), cv=coef(),
+                    out=torch.empty(B, Hq, d, device=dev, dtype=torch.float16))
+
+    nbytes = B * Hkv * T * 2 * s * 4 + Hkv * 2 * N * d * 2 + B * Hq * d * 4
+    copies = max(2, min(16, int(1.2e9 // nbytes) + 1))
+    sets = [make() for _ in range(copies)]
+    desc = csr.decode_desc(sets[0]["q"], sets[0]["DK"], sets[0]["ik"], sets[0]["ck"], sets[0]["iv"])
+    ws = torch.empty(max(csr.csr_decode_workspace_bytes(desc), 256), dtype=torch.uint8, device=dev)
+
+    def run(S):
+        csr.csr_decode_attn(S["q"], S["DK"], S["ik"], S["ck"], S["DV"], S["iv"], S["cv"], out=S["out"], workspace=ws)
+
+    for S in sets:
+        run(S)
+    torch.cuda.synchronize()
+    reps = max(2 * copies, 10)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for r in range(reps):
+        ev[r][0].record()
+        run(sets[r % copies])
+        ev[r][1].record()
+    torch.cuda.synchronize()
+    ms = sum(a.elapsed_time(b) for a, b in ev) / reps
+    gbs = nbytes / (ms * 1e-3) / 1e9
+    return {"workload": w.name, "kernel": "csr_decode_attn (4 launches), cache-cold", "bound": "hbm",
+            "achieved": round(gbs, 2), "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 5),
+            "traffic": None, "bytes_per_call": nbytes, "avg_call_ms": round(ms, 5),
+            "decode_ctx_tokens_per_s": round(B * T / (ms * 1e-3), 1), "copies_rotated": copies,
+            "config": {"kv_heads": Hkv, "query_heads": Hq, "atoms": N, "tokens_per_head": T, "s": s, "decode_batch": B}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -33,6 +86,8 @@ def main():
     ap.add_argument("--workload", default="llama7b_layer")
     ap.add_argument("--algo", default="auto", choices=["auto", "valu", "mfma"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra-decode", action="store_true",
+                    help="skip the decode-only lines at the long-context and GQA shapes")
     ap.add_argument("--cold-copies", type=int, default=16,
                     help="distinct input copies rotated through for the cache-cold decode figure")
     args = ap.parse_args()
@@ -162,6 +217,11 @@ def main():
         "decode_ms_cold": round(dec_cold_ms, 5), "decode_ms_warm": round(dec_ms, 5),
         "roofline": roofline, "roofline_decode": roofline_decode,
     }
+
+    # ---- decode alone at the shapes where the code streams dominate (random codes, cache-cold) --------
+    if not args.no_extra_decode:
+        result["decode_rooflines"] = [decode_only(csr, synth.WORKLOADS[n], dev)
+                                      for n in ("long_context", "gqa_llama3_8b")]
 
     # ---- CPU oracle on a bounded sample of the same workload ---------------------------------------
     if not args.no_cpu_baseline:

@@ -146,3 +146,44 @@ def test_gqa_llama3_shape_sampled_pairs():
     args = _case(18, 2, 8, 2, w.tokens, w.n_atoms, w.s, w.s)
     out = _run(*args)
     _check(out, oracle.decode_attn(*args), TOL_F16_OUT, "gqa x2x2")
+
+
+def test_llama7b_layer_full_decode_all_heads():
+    # The benchmark's decode call: 32 KV heads = 32 query heads, 4096 cached tokens, N = 4096, s = 8, batch 1.
+    w = synth.WORKLOADS["llama7b_layer"]
+    args = _case(19, w.batch, w.hq, w.hkv, w.tokens, w.n_atoms, w.s, w.s)
+    out = _run(*args)
+    _check(out, oracle.decode_attn(*args), TOL_F16_OUT, "llama7b layer, all heads")
+
+
+def _full_launch_sampled(name, picks):
+    """The whole configuration in one call (the launch bench.py times), random codes drawn on the GPU;
+    the oracle recomputes the sampled (sequence, KV head) pairs from the bits copied back."""
+    w = synth.WORKLOADS[name]
+    B, Hkv, Hq, T, N, d, s = w.batch, w.hkv, w.hq, w.tokens, w.n_atoms, w.d, w.s
+    G = Hq // Hkv
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(20)
+    unit = lambda *sh: (lambda a: (a / a.norm(dim=-1, keepdim=True)).half())(torch.randn(*sh, device=dev, generator=gen))
+    idx = lambda: torch.randint(0, N, (B, Hkv, T, s), device=dev, generator=gen, dtype=torch.int32).to(torch.int16)
+    coef = lambda: (torch.randn(B, Hkv, T, s, device=dev, generator=gen) * 3).half()
+    q, DK, DV = torch.randn(B, Hq, d, device=dev, generator=gen).half(), unit(Hkv, N, d), unit(Hkv, N, d)
+    ik, ck, iv, cv = idx(), coef(), idx(), coef()
+    out = csr.csr_decode_attn(q, DK, ik, ck, DV, iv, cv)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+    h_ = lambda t: t.cpu().numpy()
+    for b, h in picks:
+        ref = oracle.decode_attn(h_(q[b:b + 1, h * G:(h + 1) * G]), h_(DK[h:h + 1]), h_(ik[b:b + 1, h:h + 1]),
+                                 h_(ck[b:b + 1, h:h + 1]), h_(DV[h:h + 1]), h_(iv[b:b + 1, h:h + 1]),
+                                 h_(cv[b:b + 1, h:h + 1]))
+        _check(h_(out[b:b + 1, h * G:(h + 1) * G]), ref, TOL_F16_OUT, f"{name} full launch, sequence {b} KV head {h}")
+
+
+def test_long_context_full_launch_sampled():
+    _full_launch_sampled("long_context", [(0, 0), (3, 31), (2, 17)])
+
+
+def test_gqa_llama3_full_launch_sampled():
+    _full_launch_sampled("gqa_llama3_8b", [(0, 0), (7, 7), (4, 3)])

@@ -186,3 +186,38 @@ def test_llama7b_layer_full_size_sampled(algo):
     _assert_ok(_compare(X, D, w.s, idx, coef, rows=rows))
     # every index in range
     assert int(idx.view(np.uint16).max()) < w.n_atoms
+
+
+def test_long_context_shape_subset_mfma():
+    # Long-context configuration: N = 8192 atoms, s = 16 iterations; 2 dictionaries x 1024 vectors.
+    w = synth.WORKLOADS["long_context"]
+    D = np.concatenate([synth.dictionary(0, "dict_k", 1, w.n_atoms, w.d, "f16"),
+                        synth.dictionary(0, "dict_v", 1, w.n_atoms, w.d, "f16")])
+    X = np.concatenate([synth.vectors(0, "keys", 1, 1024, w.d, "f16", outliers=w.key_outliers),
+                        synth.vectors(0, "values", 1, 1024, w.d, "f16")])
+    idx, coef = _gpu_encode(X, D, w.s, csr.CSR_ENCODE_MFMA)
+    _assert_ok(_compare(X, D, w.s, idx, coef, rows=slice(0, 1024, 3)))
+
+
+def test_prefill_stress_one_layer_launch_sampled():
+    # One layer of the prefill stress configuration in one call: 16 dictionaries (8 KV heads x K, V),
+    # 16 sequences x 8192 tokens each; the oracle checks 12 sampled vectors per dictionary.
+    w = synth.WORKLOADS["prefill_stress"]
+    T = w.batch * w.tokens
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(21)
+    H = 2 * w.hkv
+    D = torch.randn(H, w.n_atoms, w.d, device=dev, generator=gen)
+    D = (D / D.norm(dim=-1, keepdim=True)).half()
+    X = torch.randn(H, T, w.d, device=dev, generator=gen)
+    X[:w.hkv, :, :w.key_outliers] *= 10
+    X = X.half()
+    idx, coef = csr.csr_encode(X, D, w.s, algo=csr.CSR_ENCODE_MFMA)
+    torch.cuda.synchronize()
+    assert int(idx.view(torch.uint8).view(torch.int16).to(torch.int32).bitwise_and(0xffff).max()) < w.n_atoms
+    rows = np.unique(np.concatenate([[0, 255, 256, T - 1], synth.stream(0, "misc", 2).integers(0, T, 8)]))
+    rt = torch.from_numpy(rows).to(dev)
+    Xs, Dh = X[:, rt].cpu().numpy(), D.cpu().numpy()
+    idx_s, coef_s = idx[:, rt].cpu().numpy(), coef[:, rt].cpu().numpy()
+    _assert_ok(_compare(Xs, Dh, w.s, idx_s, coef_s))
