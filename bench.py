@@ -28,6 +28,10 @@ if ROOT not in sys.path:
 PEAK_MFMA_F16_TFLOPS = 2500.0   # MI355X dense fp16 matrix peak
 PEAK_VALU_F32_TFLOPS = 157.3    # MI355X fp32 vector peak
 PEAK_HBM_GBS = 8000.0           # MI355X HBM3E peak
+# HBM bytes per dispatch of the dominant kernel, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (each scaled by what the counter reads for a 1 GiB copy) on this workload: fetched + written.
+# The summary under profiles/ gives the commands and the raw counts.
+PMC_TRAFFIC_BYTES = {("llama7b_layer", "mfma"): 796.7e6 + 124.2e6}
 
 
 def decode_only(csr, w, dev):
@@ -88,6 +92,11 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra-decode", action="store_true",
                     help="skip the decode-only lines at the long-context and GQA shapes")
+    ap.add_argument("--only-extra-decode", action="store_true",
+                    help="run only the decode-only lines (for profiling them apart from the main workload)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only copy 1 GiB device-to-device five times and exit: run under rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE, it shows what those counters read for a known amount of traffic")
     ap.add_argument("--cold-copies", type=int, default=16,
                     help="distinct input copies rotated through for the cache-cold decode figure")
     args = ap.parse_args()
@@ -99,8 +108,24 @@ def main():
     import numpy as np
     import torch
 
+    if args.copy_calibration:
+        torch.cuda.set_device(0)
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": 1 << 30, "copy_calibration_bytes_written": 1 << 30, "copies": 5}))
+        return
+
     import paper_2412_11741_amd as csr
     from paper_2412_11741_amd import synth
+
+    if args.only_extra_decode:
+        torch.cuda.set_device(0)
+        print(json.dumps({"decode_rooflines": [decode_only(csr, synth.WORKLOADS[n], torch.device("cuda:0"))
+                                               for n in ("long_context", "gqa_llama3_8b")]}))
+        return
 
     w = synth.WORKLOADS[args.workload]
     if w.layers != 1:
@@ -194,7 +219,9 @@ def main():
     uses_mfma = args.algo != "valu" and ews > 0
     roofline = {"kernel": "csr_encode (%s)" % ("mfma" if uses_mfma else "valu"),
                 "bound": "mfma", "achieved": round(enc_tflops, 3), "peak": PEAK_MFMA_F16_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(enc_tflops / PEAK_MFMA_F16_TFLOPS, 5), "traffic": None,
+                "unit": "TFLOP/s", "frac": round(enc_tflops / PEAK_MFMA_F16_TFLOPS, 5),
+                "traffic": PMC_TRAFFIC_BYTES.get((w.name, "mfma" if uses_mfma else "valu")),
+                "algorithmic_bytes": n_vec * (d * dict_b + code_b) + H * N * d * dict_b,
                 "flop_per_vector": 2.0 * d * N * s, "avg_launch_ms": round(enc_ms, 4)}
     dec_gbs = dec_bytes / (dec_cold_ms * 1e-3) / 1e9
     roofline_decode = {"kernel": "csr_decode_attn (4 launches), cache-cold", "bound": "hbm",
