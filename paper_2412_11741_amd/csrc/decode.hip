@@ -38,9 +38,9 @@ constexpr int kMaxTPT = 16;           // tokens per thread and chunk: their scor
 constexpr int kOutAtomsF16 = 128;     // atoms of D_V per out_kernel workgroup, fp16 dictionary
 constexpr int kOutAtomsF32 = 64;      // same, fp32 dictionary (the slice sits in LDS in its own type)
 constexpr int kQdAtoms = 64;          // atoms of D_K per qd_kernel workgroup
+constexpr int kQdTiles = 2;           // 32-atom tiles per wave of qd_mfma_kernel
 constexpr int kQTile = 32;            // queries staged in LDS at a time by qd_kernel
 constexpr int kMaxChunks = 64;
-constexpr int kOutQ = 8;               // (sequence, query head) pairs of a KV head per out_kernel workgroup
 constexpr size_t kLdsBudget = 150 * 1024;
 
 __device__ __forceinline__ float h2f(__half v) { return __half2float(v); }
@@ -136,7 +136,7 @@ __global__ __launch_bounds__(256) void qd_kernel(const TQ *__restrict__ q, const
 
 // ---------------------------------------------------------------------------------------------
 // The same product on the matrix cores, fp16 queries and dictionary (fp16 products are exact, fp32
-// accumulation).  One wave per 32-atom tile: queries are the M rows of v_mfma_f32_32x32x16_f16, atoms
+// accumulation).  Per 32-atom tile: queries are the M rows of v_mfma_f32_32x32x16_f16, atoms
 // the N columns, so a lane ends up with one atom and, per group of four accumulators, four
 // consecutive queries - the [n][gg] order of the table.  The contraction index is permuted as in the
 // encoder: lane half 0 holds dimensions 0..63, half 1 holds 64..127, i.e. 128 contiguous bytes of
@@ -151,49 +151,57 @@ __global__ __launch_bounds__(256) void qd_mfma_kernel(const __half *__restrict__
     const int h = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & 31, hf = lane >> 5;
-    const int n_tile = (blockIdx.x * 4 + wave) * 32;
-    if (n_tile >= N) return;
-    const int n = n_tile + col;
     const int ngs = G / GB;
     const int BG = B * G;
-
-    qd_half8 bfrag[8];
-    {
+    // a wave owns kQdTiles consecutive 32-atom tiles; all their rows are requested before the first product
+    const int n_first = (blockIdx.x * 4 + wave) * 32 * kQdTiles;
+    if (n_first >= N) return;
+    qd_half8 bfrag[kQdTiles][8];
+#pragma unroll
+    for (int t = 0; t < kQdTiles; ++t) {
+        const int n = n_first + t * 32 + col;
         const __half *row = DK + ((int64_t)h * N + min(n, N - 1)) * 128 + hf * 64;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const uint4 raw = *reinterpret_cast<const uint4 *>(row + 8 * j);
-            bfrag[j] = *reinterpret_cast<const qd_half8 *>(&raw);
+            bfrag[t][j] = *reinterpret_cast<const qd_half8 *>(&raw);
         }
     }
     for (int q0 = 0; q0 < BG; q0 += 32) {
-        qd_floatx16 acc;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
         const int bgq = q0 + col;  // this lane's query row of the A operand
         const bool have = bgq < BG;
         const __half *qrow = q + ((int64_t)(have ? bgq / G : 0) * Hq + h * G + (have ? bgq % G : 0)) * 128 + hf * 64;
+        qd_half8 afrag[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             uint4 raw = make_uint4(0u, 0u, 0u, 0u);
             if (have) raw = *reinterpret_cast<const uint4 *>(qrow + 8 * j);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(*reinterpret_cast<const qd_half8 *>(&raw), bfrag[j], acc, 0, 0, 0);
+            afrag[j] = *reinterpret_cast<const qd_half8 *>(&raw);
         }
-        if (n < N) {
 #pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {
-                const int bg = q0 + 8 * r4 + 4 * hf;  // first of four consecutive queries
-                if (GB == 4 && bg + 3 < BG) {          // G is a multiple of 4: same sequence, same group slice
-                    const int b = bg / G, g = bg % G;
-                    float *dst = qd + ((((int64_t)b * Hkv + h) * ngs + g / 4) * (int64_t)N + n) * 4;
-                    *reinterpret_cast<float4 *>(dst) = make_float4(scale * acc[4 * r4], scale * acc[4 * r4 + 1],
-                                                                   scale * acc[4 * r4 + 2], scale * acc[4 * r4 + 3]);
-                } else {
+        for (int t = 0; t < kQdTiles; ++t) {
+            const int n = n_first + t * 32 + col;
+            qd_floatx16 acc;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        if (bg + e < BG) {
-                            const int b = (bg + e) / G, g = (bg + e) % G;
-                            qd[((((int64_t)b * Hkv + h) * ngs + g / GB) * (int64_t)N + n) * GB + g % GB] = scale * acc[4 * r4 + e];
+            for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(afrag[j], bfrag[t][j], acc, 0, 0, 0);
+            if (n < N) {
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int bg = q0 + 8 * r4 + 4 * hf;  // first of four consecutive queries
+                    if (GB == 4 && bg + 3 < BG) {          // G is a multiple of 4: same sequence, same group slice
+                        const int b = bg / G, g = bg % G;
+                        float *dst = qd + ((((int64_t)b * Hkv + h) * ngs + g / 4) * (int64_t)N + n) * 4;
+                        *reinterpret_cast<float4 *>(dst) = make_float4(scale * acc[4 * r4], scale * acc[4 * r4 + 1],
+                                                                       scale * acc[4 * r4 + 2], scale * acc[4 * r4 + 3]);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            if (bg + e < BG) {
+                                const int b = (bg + e) / G, g = (bg + e) % G;
+                                qd[((((int64_t)b * Hkv + h) * ngs + g / GB) * (int64_t)N + n) * GB + g % GB] = scale * acc[4 * r4 + e];
+                            }
                         }
                     }
                 }
@@ -443,31 +451,31 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
 
 // ---------------------------------------------------------------------------------------------
 // part_out[h][slice][b*G+g][k] = sum_{n in slice} (sum_c w_c hist_c[n][g]) * DV[h][n][k].
-// One workgroup: a slice of D_V (ATOMS atoms) times the histograms of up to kOutQ (sequence, query head)
+// One workgroup: a slice of D_V (ATOMS atoms) times the histograms of up to NQ (sequence, query head)
 // pairs of KV head h.  All global loads - the slice, the chunk maxima, the chunk histograms - are issued
 // at once; the weights are applied when they have arrived.  Thread (half, k) owns output dimension k
 // over half of the slice's atoms; the halves meet in LDS.
-template <typename TD, int ATOMS>
+template <typename TD, int ATOMS, int NQ>
 __global__ __launch_bounds__(256) void out_kernel(const TD *__restrict__ DV, const float *__restrict__ part_hist,
                                                   const float *__restrict__ part_ml, float *__restrict__ part_out,
                                                   int32_t B, int32_t Hkv, int32_t G, int32_t GB, int32_t N,
                                                   int32_t nchunks)
 {
     __shared__ __attribute__((aligned(16))) TD dv_s[ATOMS][128];
-    __shared__ __attribute__((aligned(16))) float hist_s[kOutQ][ATOMS];
-    __shared__ float w_s[kOutQ][kMaxChunks];
-    __shared__ float half_s[kOutQ][128];
+    __shared__ __attribute__((aligned(16))) float hist_s[NQ][ATOMS];
+    __shared__ float w_s[NQ][kMaxChunks];
+    __shared__ float half_s[NQ][128];
     const int tid = threadIdx.x;
     const int n0 = blockIdx.x * ATOMS;
     const int h = blockIdx.y;
     const int ngs = G / GB;
     const int nslices = gridDim.x;
     const int BG = B * G;
-    const int bg0 = blockIdx.z * kOutQ;
-    const int nbg = min(kOutQ, BG - bg0);
+    const int bg0 = blockIdx.z * NQ;
+    const int nbg = min(NQ, BG - bg0);
     constexpr int kVec = 16 / sizeof(TD);               // elements per 16-byte load
     constexpr int kLoads = ATOMS * (128 / kVec) / 256;  // 16-byte loads per thread
-    constexpr int kElems = kOutQ * ATOMS / 256;         // (query, atom) histogram entries per thread
+    constexpr int kElems = (NQ * ATOMS + 255) / 256;    // (query, atom) histogram entries per thread
     constexpr int kEarly = 4;                           // chunks whose histograms are requested up front
 
     uint4 dv_r[kLoads];
@@ -486,7 +494,7 @@ __global__ __launch_bounds__(256) void out_kernel(const TD *__restrict__ DV, con
         const int e = i * 256 + tid;
         const int bgl = e / ATOMS, nn = e % ATOMS;
         ph[i] = nullptr;
-        if (bgl < nbg && n0 + nn < N) {
+        if (e < NQ * ATOMS && bgl < nbg && n0 + nn < N) {
             const int b = (bg0 + bgl) / G, g = (bg0 + bgl) % G;
             ph[i] = part_hist + ((((int64_t)b * Hkv + h) * ngs + g / GB) * nchunks) * (int64_t)N * GB +
                     (int64_t)(g % GB) * N + (n0 + nn);
@@ -529,33 +537,33 @@ __global__ __launch_bounds__(256) void out_kernel(const TD *__restrict__ DV, con
                 if (w > 0.0f) acc = fmaf(w, ph[i][(int64_t)c * N * GB], acc);
             }
         }
-        hist_s[bgl][nn] = acc;
+        if (e < NQ * ATOMS) hist_s[bgl][nn] = acc;
     }
     __syncthreads();
     const int k = tid & 127, half = tid >> 7;
-    float acc[kOutQ];
+    float acc[NQ];
 #pragma unroll
-    for (int r = 0; r < kOutQ; ++r) acc[r] = 0.0f;
+    for (int r = 0; r < NQ; ++r) acc[r] = 0.0f;
     // four atoms at a time: four reads of this thread's column, one 16-byte broadcast read per query
 #pragma unroll 2
     for (int nn = half * (ATOMS / 2); nn < (half + 1) * (ATOMS / 2); nn += 4) {
         const float d0 = (float)dv_s[nn][k], d1 = (float)dv_s[nn + 1][k], d2 = (float)dv_s[nn + 2][k],
                     d3 = (float)dv_s[nn + 3][k];
 #pragma unroll
-        for (int r = 0; r < kOutQ; ++r) {
+        for (int r = 0; r < NQ; ++r) {
             const float4 hv = *reinterpret_cast<const float4 *>(&hist_s[r][nn]);
             acc[r] = fmaf(hv.x, d0, fmaf(hv.y, d1, fmaf(hv.z, d2, fmaf(hv.w, d3, acc[r]))));
         }
     }
     if (half == 1) {
 #pragma unroll
-        for (int r = 0; r < kOutQ; ++r) half_s[r][k] = acc[r];
+        for (int r = 0; r < NQ; ++r) half_s[r][k] = acc[r];
     }
     __syncthreads();
     if (half == 0) {
         float *dst = part_out + (((int64_t)h * nslices + blockIdx.x) * BG + bg0) * 128;
 #pragma unroll
-        for (int r = 0; r < kOutQ; ++r)
+        for (int r = 0; r < NQ; ++r)
             if (r < nbg) dst[(int64_t)r * 128 + k] = acc[r] + half_s[r][k];
     }
 }
@@ -686,7 +694,7 @@ hipError_t launch_decode(const DecodeArgs &a, const DecodePlan &p)
     hipLaunchKernelGGL((qd_kernel<TQ, TD>), grid, dim3(256), 0, a.stream, (const TQ *)a.q,          \
                        (const TD *)a.DK, qd, a.B, a.Hq, a.Hkv, a.G, p.GB, a.N, a.scale)
         if (a.q16 && a.dict16) {
-            const dim3 mgrid((unsigned)((a.N + 127) / 128), (unsigned)a.Hkv);
+            const dim3 mgrid((unsigned)((a.N + 128 * kQdTiles - 1) / (128 * kQdTiles)), (unsigned)a.Hkv);
             hipLaunchKernelGGL(qd_mfma_kernel, mgrid, dim3(256), 0, a.stream, (const __half *)a.q,
                                (const __half *)a.DK, qd, a.B, a.Hq, a.Hkv, a.G, p.GB, a.N, a.scale);
         } else if (a.q16) CSR_QD(__half, float);
@@ -708,13 +716,22 @@ hipError_t launch_decode(const DecodeArgs &a, const DecodePlan &p)
     const int out_atoms = a.dict16 ? kOutAtomsF16 : kOutAtomsF32;
     const int nslices = (a.N + out_atoms - 1) / out_atoms;
     {
-        const dim3 grid((unsigned)nslices, (unsigned)a.Hkv, (unsigned)((a.B * a.G + kOutQ - 1) / kOutQ));
-        if (a.dict16)
-            hipLaunchKernelGGL((out_kernel<__half, kOutAtomsF16>), grid, dim3(256), 0, a.stream, (const __half *)a.DV,
-                               hist, ml, acc, a.B, a.Hkv, a.G, p.GB, a.N, p.nchunks);
-        else
-            hipLaunchKernelGGL((out_kernel<float, kOutAtomsF32>), grid, dim3(256), 0, a.stream, (const float *)a.DV,
-                               hist, ml, acc, a.B, a.Hkv, a.G, p.GB, a.N, p.nchunks);
+        const int BG = a.B * a.G;
+        const int nq = BG >= 8 ? 8 : (BG >= 4 ? 4 : (BG >= 2 ? 2 : 1));
+        const dim3 grid((unsigned)nslices, (unsigned)a.Hkv, (unsigned)((BG + nq - 1) / nq));
+#define CSR_OUT(TD, ATOMS, NQ)                                                                                   \
+    hipLaunchKernelGGL((out_kernel<TD, ATOMS, NQ>), grid, dim3(256), 0, a.stream, (const TD *)a.DV, hist, ml, acc, \
+                       a.B, a.Hkv, a.G, p.GB, a.N, p.nchunks)
+#define CSR_OUT_NQ(TD, ATOMS)                                                                                    \
+    switch (nq) {                                                                                                \
+        case 8: CSR_OUT(TD, ATOMS, 8); break;                                                                    \
+        case 4: CSR_OUT(TD, ATOMS, 4); break;                                                                    \
+        case 2: CSR_OUT(TD, ATOMS, 2); break;                                                                    \
+        default: CSR_OUT(TD, ATOMS, 1); break;                                                                   \
+    }
+        if (a.dict16) { CSR_OUT_NQ(__half, kOutAtomsF16) } else { CSR_OUT_NQ(float, kOutAtomsF32) }
+#undef CSR_OUT_NQ
+#undef CSR_OUT
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
