@@ -568,16 +568,33 @@ __global__ __launch_bounds__(256) void out_kernel(const TD *__restrict__ DV, con
     }
 }
 
-// out[b][hq][k] = (sum over slices of part_out) / softmax denominator
+// out[b][hq][k] = (sum over slices of part_out) / softmax denominator.  Thread (half, k): the slices of one
+// parity, eight loads in flight; the order of the additions is fixed, so the result is reproducible.
 template <typename TO>
-__global__ __launch_bounds__(128) void finalize_kernel(const float *__restrict__ part_out,
+__global__ __launch_bounds__(256) void finalize_kernel(const float *__restrict__ part_out,
                                                        const float *__restrict__ part_ml, TO *__restrict__ out,
                                                        int32_t B, int32_t Hq, int32_t Hkv, int32_t G, int32_t GB,
                                                        int32_t nchunks, int32_t nslices)
 {
+    __shared__ float half_s[128];
     const int hq = blockIdx.x % Hq, b = blockIdx.x / Hq;
     const int h = hq / G, g = hq % G;
     const int ngs = G / GB, gs = g / GB, gg = g % GB;
+    const int k = threadIdx.x & 127, half = threadIdx.x >> 7;
+    const int BG = B * G;
+    const int64_t stride = (int64_t)BG * 128;
+    const float *src = part_out + ((int64_t)h * nslices * BG + (b * G + g)) * 128 + k;
+    float acc[8];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) acc[r] = 0.0f;
+    int sl = half;
+    for (; sl + 14 < nslices; sl += 16) {
+#pragma unroll
+        for (int r = 0; r < 8; ++r) acc[r] += src[(int64_t)(sl + 2 * r) * stride];
+    }
+    for (; sl < nslices; sl += 2) acc[0] += src[(int64_t)sl * stride];
+    const float sum = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
+    if (half == 1) half_s[k] = sum;
     const float *ml = part_ml + ((((int64_t)b * Hkv + h) * ngs + gs) * nchunks) * (2 * GB);
     float M = -INFINITY;
     for (int c = 0; c < nchunks; ++c) M = fmaxf(M, ml[c * 2 * GB + 2 * gg]);
@@ -586,19 +603,11 @@ __global__ __launch_bounds__(128) void finalize_kernel(const float *__restrict__
         const float m = ml[c * 2 * GB + 2 * gg];
         if (m > -INFINITY) L = fmaf(__expf(m - M), ml[c * 2 * GB + 2 * gg + 1], L);
     }
-    const int BG = B * G;
-    const float *src = part_out + ((int64_t)h * nslices * BG + (b * G + g)) * 128 + threadIdx.x;
-    float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
-    int sl = 0;
-    for (; sl + 4 <= nslices; sl += 4) {
-        a0 += src[(int64_t)(sl + 0) * BG * 128];
-        a1 += src[(int64_t)(sl + 1) * BG * 128];
-        a2 += src[(int64_t)(sl + 2) * BG * 128];
-        a3 += src[(int64_t)(sl + 3) * BG * 128];
+    __syncthreads();
+    if (half == 0) {
+        const float v = L > 0.0f ? (sum + half_s[k]) / L : 0.0f;
+        out[((int64_t)b * Hq + hq) * 128 + k] = (TO)v;
     }
-    for (; sl < nslices; ++sl) a0 += src[(int64_t)sl * BG * 128];
-    const float v = L > 0.0f ? ((a0 + a1) + (a2 + a3)) / L : 0.0f;
-    out[((int64_t)b * Hq + hq) * 128 + threadIdx.x] = (TO)v;
 }
 
 template <int GB, typename TI, typename TC, int PV>
@@ -738,10 +747,10 @@ hipError_t launch_decode(const DecodeArgs &a, const DecodePlan &p)
     {
         const dim3 grid((unsigned)(a.B * a.Hq));
         if (a.out16)
-            hipLaunchKernelGGL((finalize_kernel<__half>), grid, dim3(128), 0, a.stream, acc, ml, (__half *)a.out,
+            hipLaunchKernelGGL((finalize_kernel<__half>), grid, dim3(256), 0, a.stream, acc, ml, (__half *)a.out,
                                a.B, a.Hq, a.Hkv, a.G, p.GB, p.nchunks, nslices);
         else
-            hipLaunchKernelGGL((finalize_kernel<float>), grid, dim3(128), 0, a.stream, acc, ml, (float *)a.out,
+            hipLaunchKernelGGL((finalize_kernel<float>), grid, dim3(256), 0, a.stream, acc, ml, (float *)a.out,
                                a.B, a.Hq, a.Hkv, a.G, p.GB, p.nchunks, nslices);
         return hipGetLastError();
     }
