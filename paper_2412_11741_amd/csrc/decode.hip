@@ -138,9 +138,8 @@ __global__ __launch_bounds__(256) void qd_kernel(const TQ *__restrict__ q, const
 // The same product on the matrix cores, fp16 queries and dictionary (fp16 products are exact, fp32
 // accumulation).  Per 32-atom tile: queries are the M rows of v_mfma_f32_32x32x16_f16, atoms
 // the N columns, so a lane ends up with one atom and, per group of four accumulators, four
-// consecutive queries - the [n][gg] order of the table.  The contraction index is permuted as in the
-// encoder: lane half 0 holds dimensions 0..63, half 1 holds 64..127, i.e. 128 contiguous bytes of
-// its atom row.
+// consecutive queries - the [n][gg] order of the table.  Fragment j of lane half hf holds dimensions
+// 16 j + 8 hf .. + 7, so the two lanes of a row read 32 contiguous bytes per instruction.
 typedef _Float16 qd_half8 __attribute__((ext_vector_type(8)));
 typedef float qd_floatx16 __attribute__((ext_vector_type(16)));
 
@@ -160,22 +159,22 @@ __global__ __launch_bounds__(256) void qd_mfma_kernel(const __half *__restrict__
 #pragma unroll
     for (int t = 0; t < kQdTiles; ++t) {
         const int n = n_first + t * 32 + col;
-        const __half *row = DK + ((int64_t)h * N + min(n, N - 1)) * 128 + hf * 64;
+        const __half *row = DK + ((int64_t)h * N + min(n, N - 1)) * 128 + hf * 8;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const uint4 raw = *reinterpret_cast<const uint4 *>(row + 8 * j);
+            const uint4 raw = *reinterpret_cast<const uint4 *>(row + 16 * j);
             bfrag[t][j] = *reinterpret_cast<const qd_half8 *>(&raw);
         }
     }
     for (int q0 = 0; q0 < BG; q0 += 32) {
         const int bgq = q0 + col;  // this lane's query row of the A operand
         const bool have = bgq < BG;
-        const __half *qrow = q + ((int64_t)(have ? bgq / G : 0) * Hq + h * G + (have ? bgq % G : 0)) * 128 + hf * 64;
+        const __half *qrow = q + ((int64_t)(have ? bgq / G : 0) * Hq + h * G + (have ? bgq % G : 0)) * 128 + hf * 8;
         qd_half8 afrag[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             uint4 raw = make_uint4(0u, 0u, 0u, 0u);
-            if (have) raw = *reinterpret_cast<const uint4 *>(qrow + 8 * j);
+            if (have) raw = *reinterpret_cast<const uint4 *>(qrow + 16 * j);
             afrag[j] = *reinterpret_cast<const qd_half8 *>(&raw);
         }
 #pragma unroll
@@ -663,7 +662,7 @@ bool plan_decode(int32_t B, int32_t Hq, int32_t Hkv, int64_t T, int32_t d, int32
     if (!GB) return false;
     p->GB = GB;
     p->ngs = G / GB;
-    // Split the token axis until every CU has a workgroup; every extra chunk costs one histogram
+    // Split the token axis until every CU has a workgroup (two per CU was measured slower); every extra chunk costs one histogram
     // round trip through scratch, so no more than that, except that a chunk holds at most
     // kMaxTPT x 1024 tokens (a thread keeps its tokens' scores in registers).
     const int64_t groups = (int64_t)(B > 0 ? B : 1) * Hkv * p->ngs;
