@@ -187,3 +187,21 @@ def test_long_context_full_launch_sampled():
 
 def test_gqa_llama3_full_launch_sampled():
     _full_launch_sampled("gqa_llama3_8b", [(0, 0), (7, 7), (4, 3)])
+
+
+def test_decode_is_bit_reproducible():
+    # Histogram sums are integer, partial outputs are added in a fixed order: same inputs, same bits.
+    args = _case(22, 2, 8, 2, 5000, 4096, 8, 8)
+    a, b = _run(*args), _run(*args)
+    assert np.array_equal(a.view(np.uint16), b.view(np.uint16))
+
+
+def test_sequence_longer_than_the_supported_maximum_is_refused():
+    q = torch.zeros(1, 1, 128, dtype=torch.float16, device="cuda")
+    D = torch.zeros(1, 64, 128, dtype=torch.float16, device="cuda")
+    T = (1 << 20) + 1
+    idx = torch.zeros(1, 1, T, 1, dtype=torch.int16, device="cuda")
+    coef = torch.zeros(1, 1, T, 1, dtype=torch.float16, device="cuda")
+    with pytest.raises(csr.CsrError) as e:
+        csr.csr_decode_attn(q, D, idx, coef, D, idx, coef)
+    assert "2^20" in str(e.value)

@@ -221,3 +221,24 @@ def test_prefill_stress_one_layer_launch_sampled():
     Xs, Dh = X[:, rt].cpu().numpy(), D.cpu().numpy()
     idx_s, coef_s = idx[:, rt].cpu().numpy(), coef[:, rt].cpu().numpy()
     _assert_ok(_compare(Xs, Dh, w.s, idx_s, coef_s))
+
+
+@pytest.mark.parametrize("N", [32, 96, 160, 2080])
+def test_mfma_atom_counts_that_leave_partial_stages(N):
+    # N is a multiple of the 32-atom tile but not of the 64-atom LDS stage or of the three-buffer ring.
+    H, T, d, s = 2, 300, 128, 6
+    D = synth.dictionary(8, "dict_k", H, N, d, "f16")
+    X = synth.vectors(8, "keys", H, T, d, "f16", outliers=8)
+    idx, coef = _gpu_encode(X, D, s, csr.CSR_ENCODE_MFMA)
+    _assert_ok(_compare(X, D, s, idx, coef))
+    assert int(idx.view(np.uint16).max()) < N
+
+
+def test_mfma_results_do_not_depend_on_the_run():
+    # The encoder has no atomics and no order-dependent reductions: two runs give the same bits.
+    H, T, N, d, s = 2, 1000, 1024, 128, 8
+    D = synth.dictionary(9, "dict_k", H, N, d, "f16")
+    X = synth.vectors(9, "keys", H, T, d, "f16", outliers=8)
+    a = _gpu_encode(X, D, s, csr.CSR_ENCODE_MFMA)
+    b = _gpu_encode(X, D, s, csr.CSR_ENCODE_MFMA)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
