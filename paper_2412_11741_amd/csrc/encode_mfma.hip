@@ -18,12 +18,13 @@
 //            epilogue keeps, per lane, the four largest GROUP maxima of the sweep (a group = the 16
 //            atoms one lane holds of one 32x32 output tile), with the tile number packed into the
 //            low mantissa bits so that one integer max/med3 chain tracks value and position.
-//            Whenever a group becomes a lane's new best, its 16 screened magnitudes are parked in
-//            LDS as fp16, so that after the sweep the best group's values are at hand.
-//   select   if the best group's largest parked value leads the other 15 by more than delta (plus the
-//            fp16 rounding of the parked values) and no other tracked group comes within delta of
+//            The 16 screened magnitudes of the lane's best group so far are carried along as fp16
+//            (eight packed registers, replaced by a conditional move whenever a group becomes the
+//            new best), so that after the sweep the best group's values are at hand.
+//   select   if the best group's largest kept value leads the other 15 by more than delta (plus the
+//            fp16 rounding of the kept values) and no other tracked group comes within delta of
 //            it, that atom is the iteration's pick (about 97 % of the steps on Gaussian-like
-//            data): no memory access beyond one LDS read.  Otherwise the wave resolves the token
+//            data): no memory access at all.  Otherwise the wave resolves the token
 //            together: the residual
 //            goes through LDS to all 64 lanes, which evaluate hi . d + lo . d (products of fp16
 //            pairs are exact in fp32) for every atom of every candidate group and take the largest,
@@ -68,11 +69,9 @@ constexpr int kStageAtoms = 32 * kStageTiles;         // 64
 constexpr int kStageBytes = kStageAtoms * kD * 2;     // 16 KiB, rows unpadded, chunks XOR-swizzled
 constexpr int kRing = 3;                              // stage buffers; stage st lives in buffer st % 3
 constexpr int kStageLoads = kStageAtoms / (4 * kWavesPerWG);  // load instructions per lane and stage
-constexpr int kParkPerBlock = 64 * 32;                // 16 fp16 magnitudes for each of 64 lanes
-constexpr int kParkOff = kRing * kStageBytes;
 constexpr int kScratchPerWave = 1024;                 // LDS a wave uses to share one token's state
-constexpr int kScratchOff = kParkOff + kWavesPerWG * kBlocks * kParkPerBlock;
-constexpr int kLdsBytes = kScratchOff + kWavesPerWG * kScratchPerWave;  // 68 KiB: two workgroups per CU
+constexpr int kScratchOff = kRing * kStageBytes;
+constexpr int kLdsBytes = kScratchOff + kWavesPerWG * kScratchPerWave;  // 52 KiB: two workgroups per CU
 constexpr int kTrack = 4;                             // group maxima tracked per lane and sweep
 constexpr int kNormSlices = 8;                        // workgroups per dictionary in the norm pre-pass
 // fp32 accumulation error of a 128-term dot product of exact fp16 products, relative to |hi||d|:
@@ -269,7 +268,6 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, hf = lane >> 5;
     unsigned char *scr = lds + kScratchOff + wave * kScratchPerWave;
-    unsigned char *park = lds + kParkOff + wave * kBlocks * kParkPerBlock + lane * 16;  // + bi * kParkPerBlock + {0, 1024}
 
     // Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous run of work so
     // that workgroups sharing a dictionary share an L2.
@@ -364,10 +362,14 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
     for (int g = 0; g < s; ++g) {
         // ---- screen: one MFMA sweep over the dictionary ------------------------------------
         uint32_t u[kBlocks][kTrack];
+        uint32_t keep[kBlocks][8];
 #pragma unroll
-        for (int bi = 0; bi < kBlocks; ++bi)
+        for (int bi = 0; bi < kBlocks; ++bi) {
 #pragma unroll
             for (int k = 0; k < kTrack; ++k) u[bi][k] = 0u;
+#pragma unroll
+            for (int r = 0; r < 8; ++r) keep[bi][r] = 0u;
+        }
 
         // stages 0 and 1 were requested before (at kernel start or behind the previous select phase)
         wait_vmem();
@@ -406,17 +408,12 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
                         for (int r = 0; r < 16; r += 2) m = fmaxf(fmaxf(m, fabsf(acc[bi][r])), fabsf(acc[bi][r + 1]));
                         const uint32_t v = (__float_as_uint(m) & keep_mask) | code;  // one v_and_or_b32
                         const bool new_best = v > u[bi][0];
-                        if (__ballot(new_best) != 0ull) {
-                            if (new_best) {  // park this group's magnitudes (fp16, rounded toward zero)
-                                uint32_t w[8];
+                        // keep the magnitudes (fp16, rounded toward zero) of the lane's best group so far
 #pragma unroll
-                                for (int r = 0; r < 8; ++r) {
-                                    const auto pk = __builtin_amdgcn_cvt_pkrtz(fabsf(acc[bi][2 * r]), fabsf(acc[bi][2 * r + 1]));
-                                    w[r] = *reinterpret_cast<const uint32_t *>(&pk);
-                                }
-                                *reinterpret_cast<uint4 *>(park + bi * kParkPerBlock) = make_uint4(w[0], w[1], w[2], w[3]);
-                                *reinterpret_cast<uint4 *>(park + bi * kParkPerBlock + 1024) = make_uint4(w[4], w[5], w[6], w[7]);
-                            }
+                        for (int r = 0; r < 8; ++r) {
+                            const auto pk = __builtin_amdgcn_cvt_pkrtz(fabsf(acc[bi][2 * r]), fabsf(acc[bi][2 * r + 1]));
+                            const uint32_t w = *reinterpret_cast<const uint32_t *>(&pk);
+                            keep[bi][r] = new_best ? w : keep[bi][r];
                         }
                         const uint32_t n3 = umed3(u[bi][2], u[bi][3], v);
                         const uint32_t n2 = umed3(u[bi][1], u[bi][2], v);
@@ -462,13 +459,11 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
             for (int k = 0; k < kTrack; ++k) ncand += (int)(u[bi][k] >= thr_bits) + (int)(pu[k] >= thr_bits);
             const bool overflow = u[bi][kTrack - 1] >= thr_bits || pu[kTrack - 1] >= thr_bits;
 
-            // this lane's best group as parked during the sweep: largest value, its position, runner-up
+            // this lane's best group as kept during the sweep: largest value, its position, runner-up
             float ba = -1.0f, sa = -1.0f;
             int bk = 0;
             {
-                const uint4 w0 = *reinterpret_cast<const uint4 *>(park + bi * kParkPerBlock);
-                const uint4 w1 = *reinterpret_cast<const uint4 *>(park + bi * kParkPerBlock + 1024);
-                const uint32_t w[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+                const uint32_t(&w)[8] = keep[bi];
 #pragma unroll
                 for (int r = 0; r < 8; ++r) {
                     const float2 f = __half22float2(*reinterpret_cast<const __half2 *>(&w[r]));
@@ -476,7 +471,7 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
                     if (f.y > ba) { sa = ba; ba = f.y; bk = 2 * r + 1; } else sa = fmaxf(sa, f.y);
                 }
             }
-            // parked values were rounded toward zero to 11 bits: two of them are told apart only
+            // kept values were rounded toward zero to 11 bits: two of them are told apart only
             // beyond delta + 2^-10 of the larger
             const bool close_own = !(sa < ba - delta[bi] - ba * 9.765625e-4f);
             const uint32_t mine = (uint32_t)bk | (close_own ? 16u : 0u);
