@@ -31,7 +31,7 @@ PEAK_HBM_GBS = 8000.0           # MI355X HBM3E peak
 # HBM bytes per dispatch of the dominant kernel, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (each scaled by what the counter reads for a 1 GiB copy) on this workload: fetched + written.
 # The summary under profiles/ gives the commands and the raw counts.
-PMC_TRAFFIC_BYTES = {("llama7b_layer", "mfma"): 796.7e6 + 124.2e6}
+PMC_TRAFFIC_BYTES = {("llama7b_layer", "mfma"): 750.4e6 + 126.9e6}
 
 
 def decode_only(csr, w, dev):
