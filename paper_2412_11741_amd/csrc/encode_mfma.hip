@@ -541,12 +541,14 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
             r2 += xchg32f(r2, hf);
             const int sexp_used = sexp[bi];
             // A residual that has shrunk a lot (a vector that is nearly a multiple of an atom) is
-            // scaled up again before the split, or lo would sink into the fp16 subnormals.
-            const bool shrunk = r2 < 65536.0f && r2 > 0.0f;
-            if (__ballot(shrunk) != 0ull) {
+            // scaled up again before the split, or lo would sink into the fp16 subnormals; one that
+            // has grown (atoms of norm above sqrt(2) make Eq.4 expand it) is scaled down before hi
+            // could leave the fp16 range.
+            const bool rescale = (r2 < 65536.0f && r2 > 0.0f) || (r2 >= 1073741824.0f && r2 < INFINITY);
+            if (__ballot(rescale) != 0ull) {
                 int e2 = 0;
-                (void)frexpf(r2, &e2);                       // |R| in [2^((e2-1)/2), 2^(e2/2))
-                const int k = shrunk ? 14 - (e2 + 1) / 2 : 0;  // brings |R| into [2^12.5, 2^14.5)
+                (void)frexpf(r2, &e2);                        // |R| in [2^((e2-1)/2), 2^(e2/2))
+                const int k = rescale ? 14 - (e2 + 1) / 2 : 0;  // brings |R| into [2^12.5, 2^14.5)
                 const float sc = ldexpf(1.0f, k);
 #pragma unroll
                 for (int j = 0; j < 8; ++j)

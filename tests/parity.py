@@ -1,10 +1,17 @@
 """Comparison rules between a candidate encoder / decoder output and the CPU oracle.
 
 Encode (per vector, walking the iterations in order):
-  * same atom index as the oracle  -> the coefficient must agree within `coef_tol`, relative to
-    max(|c|, 1e-6 |x|);
+  * same atom index as the oracle  -> the coefficient must agree within coef_tol * |c|, or within
+    the absolute floor below if that is larger;
   * different index -> accepted only if, at that step, the oracle's best and runner-up
-    |correlation| differ by at most tie_rel * best (a tie: either atom is a correct greedy pick).
+    |correlation| differ by at most tie_rel * best, or by at most the absolute floor (a tie: either
+    atom is a correct greedy pick).
+  Absolute floor: 2^-23 |x| (one fp32 ulp of the input's norm).  The candidate accumulates in fp32:
+  its residual carries an absolute error of that order whatever the residual has shrunk to, so on a
+  vector that is (nearly) a combination of a few atoms neither a correlation difference nor a
+  coefficient below that floor can be resolved, while the fp64 oracle still resolves them.  With
+  fp16 coefficient storage one storage ulp of the value is allowed on top (fp16 subnormals are
+  spaced 6e-8 apart: a one-ulp flip there exceeds any relative tolerance).
     From there on the two paths legitimately differ, so the remaining steps of that vector are
     checked for greedy validity instead: each pick must reach the largest |R . d_n| of the residual
     built (in float64) from the candidate's own earlier picks, within tie_rel, and its coefficient
@@ -16,6 +23,7 @@ from dataclasses import dataclass, field
 import numpy as np
 
 TIE_REL = 1e-6
+FP32_ULP = 2.0 ** -23
 
 
 @dataclass
@@ -44,14 +52,18 @@ def _as_index(a):
     return a.astype(np.int64)
 
 
-def check_encode(X, D, idx_c, coef_c, idx_o, coef_o, diag, coef_tol, tie_rel=TIE_REL, max_report=10):
+def check_encode(X, D, idx_c, coef_c, idx_o, coef_o, diag, coef_tol, tie_rel=TIE_REL, max_report=10,
+                 coef_storage="f32", coef_o_exact=None):
     """X [T, d], D [N, d] (the exact input bits, any float dtype); candidate and oracle codes [T, s];
-    diag = the oracle's diagnostics dict for these vectors."""
+    diag = the oracle's diagnostics dict for these vectors.  coef_o may be rounded to the storage type (it is what
+    the candidate's stored values are compared with); coef_o_exact, the oracle's unrounded coefficients, is then
+    what the residual of a vector that diverged at a tie is rebuilt from."""
     X = np.asarray(X, dtype=np.float64)
     D = np.asarray(D, dtype=np.float64)
     idx_c, idx_o = _as_index(idx_c), _as_index(idx_o)
     coef_c = np.asarray(coef_c, dtype=np.float64)
     coef_o = np.asarray(coef_o, dtype=np.float64)
+    coef_rebuild = coef_o if coef_o_exact is None else np.asarray(coef_o_exact, dtype=np.float64)
     T, s = idx_o.shape
     rep = EncodeReport(vectors=T, steps=T * s)
     xnorm = np.linalg.norm(X, axis=1)
@@ -59,8 +71,13 @@ def check_encode(X, D, idx_c, coef_c, idx_o, coef_o, diag, coef_tol, tie_rel=TIE
     # number of leading steps that agree, per vector
     lead = np.where(same.all(axis=1), s, np.argmin(same, axis=1))
     rep.exact_steps = int(same.sum())
-    floor = 1e-6 * xnorm[:, None]
-    denom = np.maximum(np.abs(coef_o), floor)
+    abs_floor = FP32_ULP * xnorm                       # per vector
+    ulp = np.zeros_like(coef_o)
+    if coef_storage == "f16":
+        ulp = np.spacing(np.abs(coef_o).astype(np.float16)).astype(np.float64)
+    # error measured against the larger of |c| and (floor + storage ulp) / coef_tol: `rel <= coef_tol` then
+    # reads |err| <= max(coef_tol |c|, floor + ulp)
+    denom = np.maximum(np.abs(coef_o), (abs_floor[:, None] + ulp) / coef_tol)
     rel = np.abs(coef_c - coef_o) / np.where(denom > 0, denom, 1.0)
     for t in range(T):
         L = int(lead[t])
@@ -73,7 +90,7 @@ def check_encode(X, D, idx_c, coef_c, idx_o, coef_o, diag, coef_tol, tie_rel=TIE
         if L == s:
             continue
         best, second = diag["best_abs"][t, L], diag["second_abs"][t, L]
-        if best - second > tie_rel * best:
+        if best - second > max(tie_rel * best, abs_floor[t]):
             if len(rep.failures) < max_report:
                 rep.failures.append(f"vector {t} step {L}: index {idx_c[t, L]} vs oracle {idx_o[t, L]} "
                                     f"(best {best!r}, runner-up {second!r}: not a tie)")
@@ -82,16 +99,17 @@ def check_encode(X, D, idx_c, coef_c, idx_o, coef_o, diag, coef_tol, tie_rel=TIE
         # greedy validity of the candidate's own path from step L on
         R = X[t].copy()
         for g in range(L):
-            R -= coef_o[t, g] * D[idx_o[t, g]]
+            R -= coef_rebuild[t, g] * D[idx_o[t, g]]
         for g in range(L, s):
             C = D @ R
             a = np.abs(C)
             n = int(idx_c[t, g])
-            if a[n] < a.max() * (1.0 - tie_rel) - 1e-300:
+            if a[n] < a.max() - max(tie_rel * a.max(), abs_floor[t]) - 1e-300:
                 if len(rep.failures) < max_report:
                     rep.failures.append(f"vector {t} step {g} (after tie at {L}): index {n} is not a greedy pick")
                 break
-            e = abs(coef_c[t, g] - C[n]) / max(abs(C[n]), 1e-6 * xnorm[t], 1e-300)
+            u16 = float(np.spacing(np.float16(abs(C[n])))) if coef_storage == "f16" else 0.0
+            e = abs(coef_c[t, g] - C[n]) / max(abs(C[n]), (abs_floor[t] + u16) / coef_tol, 1e-300)
             rep.max_coef_err = max(rep.max_coef_err, float(e))
             if e > coef_tol:
                 if len(rep.failures) < max_report:

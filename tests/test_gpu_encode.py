@@ -35,7 +35,8 @@ def _compare(X, D, s, idx_g, coef_g, heads=None, rows=None):
         Xh = X[h][r]
         idx_o, coef_o, diag = oracle.mp_encode(Xh, D[h], s, diagnostics=True)
         coef_o_st = coef_o.astype(coef_g.dtype).astype(np.float64)      # storage rounding, RNE
-        rep = parity.check_encode(Xh, D[h], idx_g[h][r], coef_g[h][r], idx_o, coef_o_st, diag, TOL)
+        rep = parity.check_encode(Xh, D[h], idx_g[h][r], coef_g[h][r], idx_o, coef_o_st, diag, TOL,
+                                  coef_storage="f16" if coef_g.dtype == np.float16 else "f32", coef_o_exact=coef_o)
         reports.append(rep)
     return reports
 
@@ -242,3 +243,48 @@ def test_mfma_results_do_not_depend_on_the_run():
     a = _gpu_encode(X, D, s, csr.CSR_ENCODE_MFMA)
     b = _gpu_encode(X, D, s, csr.CSR_ENCODE_MFMA)
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def _adversarial_cases():
+    rng = synth.stream(0, "misc", 3)
+    N, d = 512, 128
+    base = synth.dictionary(10, "dict_k", 1, N, d, "f16")[0].astype(np.float32)
+    cases = {}
+    # atoms far from unit norm (the screening bound scales with the largest atom norm)
+    D = base.copy(); D[::7] *= 2.0; D[1::7] *= 0.25
+    cases["atom norms 0.25 .. 2"] = (D, synth.vectors(10, "keys", 1, 200, d, "f16", outliers=8)[0])
+    # duplicated atoms: exact ties in every iteration that picks one of them -> lowest index must win
+    D = base.copy(); D[300:332] = D[10:42]
+    X = synth.vectors(11, "keys", 1, 200, d, "f16", outliers=8)[0].astype(np.float32)
+    X[:32] = D[10:42] * 3.0 + 0.01 * X[:32]
+    cases["duplicated atoms"] = (D, X)
+    # huge dynamic range inside one vector and across vectors (fp16 subnormals up to 3e4)
+    X = synth.vectors(12, "values", 1, 200, d, "f16")[0].astype(np.float32)
+    X *= np.exp(rng.uniform(-9.0, 2.0, size=X.shape)).astype(np.float32)
+    X[:50] *= 3.0e3; X[50:100] *= 1.0e-4
+    cases["dynamic range"] = (base, X)
+    # vectors that are sparse combinations of atoms: the residual collapses after a few iterations
+    X = np.zeros((200, d), dtype=np.float32)
+    for t in range(200):
+        k = rng.integers(1, 4)
+        X[t] = (rng.standard_normal(k).astype(np.float32)[:, None] * base[rng.integers(0, N, k)]).sum(0)
+    cases["sparse combinations of atoms"] = (base, X)
+    # constant vectors and single-channel vectors
+    X = np.zeros((64, d), dtype=np.float32); X[:32] = 1.5; X[32:, 5] = -7.0
+    cases["constant and one-hot vectors"] = (base, X)
+    return cases
+
+
+@pytest.mark.parametrize("name", ["atom norms 0.25 .. 2", "duplicated atoms", "dynamic range",
+                                  "sparse combinations of atoms", "constant and one-hot vectors"])
+@pytest.mark.parametrize("algo", ["valu", "mfma"])
+def test_adversarial_inputs(algo, name):
+    D, X = _adversarial_cases()[name]
+    D16, X16 = D.astype(np.float16)[None], X.astype(np.float16)[None]
+    s = 8
+    idx, coef = _gpu_encode(X16, D16, s, ALGOS[algo])
+    assert np.all(np.isfinite(coef.astype(np.float32)))
+    reports = _compare(X16, D16, s, idx, coef)
+    for rep in reports:
+        assert rep.ok, name + ": " + rep.summary() + "\n" + "\n".join(rep.failures)
+    print(f"[encode parity] {name} ({algo}): " + reports[0].summary())

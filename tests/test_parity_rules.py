@@ -54,3 +54,34 @@ def test_decode_errors():
     a = np.ones((2, 3, 4)); b = a.copy(); b[1, 2, 0] += 0.02
     rel, mx = parity.decode_errors(b, a)
     assert rel.shape == (2, 3) and abs(rel[1, 2] - 0.01) < 1e-12 and abs(mx - 0.02) < 1e-12
+
+
+def test_collapsed_residual_floor_accepts_only_what_fp32_cannot_resolve():
+    # x is exactly one atom: after the first pick the fp64 residual is ~1e-16 |x|.  A candidate working in
+    # fp32 cannot know which atom "wins" there, so any index with a coefficient below one fp32 ulp of |x|
+    # passes; a coefficient error above that floor, or a wrong first pick, still fails.
+    rng = np.random.default_rng(3)
+    D = rng.standard_normal((40, 16)); D /= np.linalg.norm(D, axis=1, keepdims=True)
+    X = 2.0 * D[7:8]
+    idx, coef, diag = oracle.mp_encode(X, D, 3, diagnostics=True)
+    assert idx[0, 0] == 7 and abs(coef[0, 1]) < 1e-12
+    cand_i, cand_c = idx.copy(), coef.copy()
+    cand_i[0, 1] = (idx[0, 1] + 5) % 40; cand_c[0, 1] = 3e-8          # noise-level pick, as fp32 would give
+    cand_c[0, 2] = 0.0
+    assert parity.check_encode(X, D, cand_i, cand_c, idx, coef, diag, 1e-3).ok
+    cand_c[0, 1] = 1e-5                                                # well above one fp32 ulp of |x| = 2.4e-7
+    assert not parity.check_encode(X, D, cand_i, cand_c, idx, coef, diag, 1e-3).ok
+    cand_i, cand_c = idx.copy(), coef.copy(); cand_i[0, 0] = 8
+    assert not parity.check_encode(X, D, cand_i, cand_c, idx, coef, diag, 1e-3).ok
+
+
+def test_fp16_storage_allows_one_storage_ulp_and_no_more():
+    X, D, idx, coef, diag = _setup(seed=2)
+    coef = coef * 1e-5                                  # stored values fall into the fp16 subnormals
+    X = X * 1e-5
+    c16 = coef.astype(np.float16).astype(np.float64)
+    one_ulp = c16 + np.spacing(np.abs(c16).astype(np.float16)).astype(np.float64)
+    assert parity.check_encode(X, D, idx, one_ulp, idx, c16, diag, 1e-3, coef_storage="f16").ok
+    three_ulp = c16 + 3 * np.spacing(np.abs(c16).astype(np.float16)).astype(np.float64)
+    assert not parity.check_encode(X, D, idx, three_ulp, idx, c16, diag, 1e-3, coef_storage="f16").ok
+    assert not parity.check_encode(X, D, idx, one_ulp, idx, c16, diag, 1e-3, coef_storage="f32").ok
