@@ -13,7 +13,8 @@
 //                    is read once, coalesced, and every thread keeps the scores of its tokens in
 //                    registers; one reduction gives the chunk's maximum.  Pass 2: the same LDS now
 //                    holds the histogram; p = exp(score - max) and the V code stream is scattered
-//                    into it.  The histogram is 64-bit fixed point (2^-32 units, integer LDS atomics):
+//                    into it.  The histogram is 64-bit fixed point (integer LDS atomics; the unit is a
+//                    power of two taken from the chunk's own value coefficients):
 //                    on this chip the LDS float atomic add is serialised lane by lane and runs about
 //                    thirty times slower than the integer one, and integer sums are exact, so the
 //                    result does not depend on the order of the adds.  The chunk's histogram (as
@@ -286,8 +287,9 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
-// p * c as a 64-bit fixed-point number in units of 2^-32 (two's complement).  |x| < 2^31 is given:
-// p <= 1 and |c| is an fp16 or a sane fp32 coefficient.  x - floor(x) is exact in fp32.
+// x as a 64-bit fixed-point number in units of 2^-32 (two's complement); needs |x| < 2^31.
+// x - floor(x) is exact in fp32.  The caller scales p * c by a power of two first (see stream_kernel),
+// so that the unit follows the data and the result does not depend on the scale of the coefficients.
 __device__ __forceinline__ unsigned long long to_fixed(float x)
 {
     const float fl = floorf(x);
@@ -313,7 +315,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     float *qd_s = reinterpret_cast<float *>(smem_raw);
     unsigned long long *hist = reinterpret_cast<unsigned long long *>(smem_raw);
-    float *red = reinterpret_cast<float *>(smem_raw + (size_t)N * GB * 8);  // [kStreamWaves][GB]
+    float *red = reinterpret_cast<float *>(smem_raw + (size_t)N * GB * 8);  // [kStreamWaves][GB] | [kStreamWaves]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -336,6 +338,9 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
         return;
     }
 
+    const int64_t code_row = ((int64_t)b * Hkv + h) * T;
+    const int n_mine = (int)((t_end - t0 + kStreamThreads - 1) / kStreamThreads);  // rounds of 1024 tokens
+
     const int table = N * GB;
     {
         const float *src = qd + (((int64_t)b * Hkv + h) * ngs + gs) * (int64_t)table;
@@ -346,10 +351,12 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
     }
     __syncthreads();
 
-    const int64_t code_row = ((int64_t)b * Hkv + h) * T;
-    const int n_mine = (int)((t_end - t0 + kStreamThreads - 1) / kStreamThreads);  // rounds of 1024 tokens
 
     // ---- pass 1: scores of this thread's tokens (token t0 + i * 1024 + tid in round i) --------
+    // Unit of the fixed-point histogram: 2^-30 of the largest |value coefficient| among this chunk's first
+    // 1024 tokens (read in the first round, next to the key codes, so that the loads overlap).  A coefficient
+    // may exceed that estimate 2^33-fold before an add could overflow.
+    float cm = 0.0f;
     float sc[kMaxTPT][GB];
     float mx[GB];
 #pragma unroll
@@ -366,6 +373,15 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
                 for (int g = 0; g < GB; ++g) acc[g] = 0.0f;
                 const TI *ip = idxK + (code_row + t) * sK;
                 const TC *cp = coefK + (code_row + t) * sK;
+                if (i == 0) {  // sample the value coefficients (see c_est below)
+                    const TC *vp = coefV + (code_row + t) * sV;
+                    for (int j0 = 0; j0 < sV; j0 += PV) {
+                        float cf[PV];
+                        CoefLoad<TC, PV>::ld(vp + j0, cf);
+#pragma unroll
+                        for (int j = 0; j < PV; ++j) cm = fmaxf(cm, fabsf(cf[j]));
+                    }
+                }
                 for (int j0 = 0; j0 < sK; j0 += PV) {
                     int id[PV];
                     float cf[PV];
@@ -387,6 +403,8 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
         const float wm = wave_max(mx[g]);
         if (lane == 0) red[wave * GB + g] = wm;
     }
+    cm = wave_max(cm);
+    if (lane == 0) red[kStreamWaves * GB + wave] = cm;
     __syncthreads();  // every score is computed: the table is free
     float m_c[GB];
 #pragma unroll
@@ -396,6 +414,21 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
         for (int w = 1; w < kStreamWaves; ++w) v = fmaxf(v, red[w * GB + g]);
         m_c[g] = v;
     }
+    float c_est = red[kStreamWaves * GB];
+#pragma unroll
+    for (int w = 1; w < kStreamWaves; ++w) c_est = fmaxf(c_est, red[kStreamWaves * GB + w]);
+    int unit_exp = -32;  // all sampled coefficients zero (or not finite): plain 2^-32 units
+    if (c_est > 0.0f && c_est < INFINITY) {
+        int e2;
+        (void)frexpf(c_est, &e2);  // c_est in [2^(e2-1), 2^e2)
+        unit_exp = e2 - 1 - 30;
+    }
+    // p is produced directly in histogram units: exp(score - max) * 2^k = exp(score - (max - k ln 2)); the sum of
+    // the p is scaled back when it is stored.
+    const int k_units = -unit_exp - 32;
+    float m_eff[GB];
+#pragma unroll
+    for (int g = 0; g < GB; ++g) m_eff[g] = m_c[g] - (float)k_units * 0.69314718f;
     for (int e = tid; e < table; e += kStreamThreads) hist[e] = 0ull;
     __syncthreads();
 
@@ -410,7 +443,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
             if (t < t_end) {
                 float p[GB];
 #pragma unroll
-                for (int g = 0; g < GB; ++g) { p[g] = __expf(sc[i][g] - m_c[g]); l_thr[g] += p[g]; }
+                for (int g = 0; g < GB; ++g) { p[g] = __expf(sc[i][g] - m_eff[g]); l_thr[g] += p[g]; }
                 const TI *ip = idxV + (code_row + t) * sV;
                 const TC *cp = coefV + (code_row + t) * sV;
                 for (int j0 = 0; j0 < sV; j0 += PV) {
@@ -441,11 +474,12 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
             float l = 0.0f;
             for (int w = 0; w < kStreamWaves; ++w) l += red[w * GB + g];
             ml[2 * g] = m_c[g];
-            ml[2 * g + 1] = l;
+            ml[2 * g + 1] = ldexpf(l, -k_units);
         }
     }
     float *dst = part_hist + slot * (int64_t)table;
-    for (int e = tid; e < table; e += kStreamThreads) dst[e] = from_fixed(hist[e]);
+    const float from_units = ldexpf(1.0f, unit_exp + 32);
+    for (int e = tid; e < table; e += kStreamThreads) dst[e] = from_fixed(hist[e]) * from_units;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -656,7 +690,7 @@ bool plan_decode(int32_t B, int32_t Hq, int32_t Hkv, int64_t T, int32_t d, int32
     for (int cand : {4, 2, 1}) {
         if (G % cand != 0) continue;
         // score table (fp32) and histogram (64-bit) share the space: the larger one counts
-        const size_t lds = (size_t)N * cand * 8 + (size_t)kStreamWaves * cand * sizeof(float);
+        const size_t lds = (size_t)N * cand * 8 + (size_t)kStreamWaves * (cand + 1) * sizeof(float);
         if (lds <= kLdsBudget) { GB = cand; p->lds_bytes = lds; break; }
     }
     if (!GB) return false;

@@ -205,3 +205,23 @@ def test_sequence_longer_than_the_supported_maximum_is_refused():
     with pytest.raises(csr.CsrError) as e:
         csr.csr_decode_attn(q, D, idx, coef, D, idx, coef)
     assert "2^20" in str(e.value)
+
+
+@pytest.mark.parametrize("scale", [2.0 ** -20, 2.0 ** 13])
+def test_value_coefficient_scale_does_not_change_relative_accuracy(scale):
+    # The histogram's fixed-point unit follows the data: tiny and huge value coefficients keep the accuracy.
+    q, DK, idxK, coefK, DV, idxV, coefV = _case(23, 2, 8, 2, 3000, 4096, 8, 8)
+    coefV = (coefV.astype(np.float32) * np.float32(scale)).astype(np.float16)
+    out = _run(q, DK, idxK, coefK, DV, idxV, coefV, out_dtype=torch.float32)
+    _check(out, oracle.decode_attn(q, DK, idxK, coefK, DV, idxV, coefV), TOL_F32_OUT, f"value coefficients x {scale:g}")
+
+
+def test_hot_atom_with_largest_fp16_coefficients_does_not_overflow():
+    # Flat softmax (all key coefficients zero), every value pair on the same atom with |c| = 60000.
+    B, Hq, Hkv, T, N, s = 1, 2, 1, 16384, 256, 8
+    q, DK, idxK, coefK, DV, idxV, coefV = _case(24, B, Hq, Hkv, T, N, s, s)
+    coefK[...] = 0
+    idxV[...] = 3
+    coefV[...] = np.float16(60000.0)
+    out = _run(q, DK, idxK, coefK, DV, idxV, coefV, out_dtype=torch.float32)
+    _check(out, oracle.decode_attn(q, DK, idxK, coefK, DV, idxV, coefV), TOL_F32_OUT, "hot atom, largest coefficients")
