@@ -11,6 +11,10 @@ Functions and the passages they follow:
   reconstruct      X~ = D r, Eq.12
   decode_attn      softmax attention of one query per sequence over K~, V~
                    ("De-Sparse to restore", last paragraph)
+  decode_attn_chunked
+                   the same with every head vector split into s_n chunks of d/s_n dimensions, each
+                   chunk with its own dictionary and codes (the s_n of Section "NeuralDict" /
+                   "Analysis for CSR": the value cache of the experiments uses s = 4, s_n = 2)
   equivalent_bits, compression_ratio, code_bytes
                    storage accounting of "Analysis for CSR"
 """
@@ -132,6 +136,41 @@ def decode_attn(q, DK, idxK, coefK, DV, idxV, coefV, scale=None, seq_lens=None, 
                                         float(scale), _ptr(sl), _ptr(out), nthreads)
     if rc != 0:
         raise RuntimeError(f"csr_oracle_decode_attn failed: {rc}")
+    return out
+
+
+def decode_attn_chunked(q, DK, idxK, coefK, DV, idxV, coefV, scale=None, seq_lens=None):
+    """Attention over a cache whose head vectors are stored as s_n chunks (Section "NeuralDict": the vector is cut
+    into s_n pieces of d/s_n dimensions, every piece sparsely represented on its own).
+
+    q [B, Hq, d]; DK [Hkv, snK, N, d/snK], idxK/coefK [B, Hkv, T, snK, sK]; likewise for V with snV, sV.
+    K~_t is the concatenation over chunks of D_c r_{t,c} (Eq.12 per chunk), then plain softmax attention,
+    written out in numpy float64.  Reading taken: every chunk has its own dictionary (a caller who shares one
+    passes it s_n times).  Returns out [B, Hq, d] float64.
+    """
+    q = _f64(q)
+    B, Hq, d = q.shape
+    Hkv = DK.shape[0]
+    G = Hq // Hkv
+    T = idxK.shape[2]
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    out = np.zeros((B, Hq, d))
+
+    def dense(D, idx, coef, b, h, L):
+        sn = D.shape[1]
+        return np.concatenate([reconstruct(idx[b, h, :L, c], coef[b, h, :L, c], D[h, c]) for c in range(sn)], axis=1)
+
+    for b in range(B):
+        L = T if seq_lens is None else int(seq_lens[b])
+        if L <= 0:
+            continue
+        for h in range(Hkv):
+            Kt, Vt = dense(DK, idxK, coefK, b, h, L), dense(DV, idxV, coefV, b, h, L)
+            for g in range(G):
+                sc = scale * (Kt @ q[b, h * G + g])
+                p = np.exp(sc - sc.max())
+                out[b, h * G + g] = (p / p.sum()) @ Vt
     return out
 
 

@@ -141,3 +141,57 @@ def test_sixteen_bit_indices_are_read_unsigned():
     c = np.ones((1, 1, 3, 1))
     assert np.array_equal(oracle.decode_attn(q, DK, idx32, c, DV, idx32, c),
                           oracle.decode_attn(q, DK, idx16, c, DV, idx16, c))
+
+
+def _chunked_case(seed, B, Hq, Hkv, T, N, d, snK, sK, snV, sV):
+    rng = np.random.default_rng(seed)
+    def dic(sn):
+        D = rng.standard_normal((Hkv, sn, N, d // sn)); return D / np.linalg.norm(D, axis=-1, keepdims=True)
+    q = rng.standard_normal((B, Hq, d))
+    DK, DV = dic(snK), dic(snV)
+    idxK = rng.integers(0, N, (B, Hkv, T, snK, sK)).astype(np.int32); coefK = rng.standard_normal((B, Hkv, T, snK, sK))
+    idxV = rng.integers(0, N, (B, Hkv, T, snV, sV)).astype(np.int32); coefV = rng.standard_normal((B, Hkv, T, snV, sV))
+    return q, DK, idxK, coefK, DV, idxV, coefV
+
+
+def _block_diagonal(D, idx, coef):
+    """Chunked dictionary [Hkv, sn, N, dc] and codes [B, Hkv, T, sn, s] as ONE dictionary of sn*N atoms of full
+    length (atom (c, n) lives in the dimensions of chunk c, zero elsewhere) with offset indices."""
+    Hkv, sn, N, dc = D.shape
+    big = np.zeros((Hkv, sn * N, sn * dc))
+    for c in range(sn):
+        big[:, c * N:(c + 1) * N, c * dc:(c + 1) * dc] = D[:, c]
+    off = (np.arange(sn) * N)[None, None, None, :, None]
+    B, _, T, _, s = idx.shape
+    return big, (idx + off).reshape(B, Hkv, T, sn * s).astype(np.int32), coef.reshape(B, Hkv, T, sn * s)
+
+
+def test_chunked_attention_with_one_chunk_is_the_plain_one():
+    q, DK, idxK, coefK, DV, idxV, coefV = _chunked_case(40, 2, 4, 2, 37, 50, 16, 1, 3, 1, 2)
+    a = oracle.decode_attn_chunked(q, DK, idxK, coefK, DV, idxV, coefV)
+    b = oracle.decode_attn(q, DK[:, 0], idxK[:, :, :, 0], coefK[:, :, :, 0], DV[:, 0], idxV[:, :, :, 0], coefV[:, :, :, 0])
+    assert np.allclose(a, b, rtol=1e-12, atol=1e-14)
+
+
+def test_chunked_attention_equals_plain_attention_on_block_diagonal_dictionaries():
+    # Independent route: cutting a vector into s_n chunks, each on its own dictionary, is the same as ONE dictionary
+    # of s_n*N zero-padded atoms; the plain C oracle on that dictionary must agree with the numpy chunked one.
+    q, DK, idxK, coefK, DV, idxV, coefV = _chunked_case(41, 2, 6, 2, 61, 40, 32, 1, 4, 2, 3)
+    a = oracle.decode_attn_chunked(q, DK, idxK, coefK, DV, idxV, coefV, scale=0.3)
+    bk, ik, ck = _block_diagonal(DK, idxK, coefK)
+    bv, iv, cv = _block_diagonal(DV, idxV, coefV)
+    bk = np.concatenate([bk, np.zeros((bk.shape[0], bv.shape[1] - bk.shape[1], bk.shape[2]))], axis=1)  # same N for both
+    b = oracle.decode_attn(q, bk, ik, ck, bv, iv, cv, scale=0.3)
+    assert np.allclose(a, b, rtol=1e-11, atol=1e-13)
+
+
+def test_chunked_attention_value_chunks_only_touch_their_own_dimensions():
+    q, DK, idxK, coefK, DV, idxV, coefV = _chunked_case(42, 1, 2, 1, 20, 30, 16, 2, 2, 4, 2)
+    base = oracle.decode_attn_chunked(q, DK, idxK, coefK, DV, idxV, coefV)
+    coefV2 = coefV.copy(); coefV2[:, :, :, 2] *= -3.0          # change chunk 2 of the values only
+    out = oracle.decode_attn_chunked(q, DK, idxK, coefK, DV, idxV, coefV2)
+    assert np.allclose(out[..., :8], base[..., :8]) and np.allclose(out[..., 12:], base[..., 12:])
+    assert np.allclose(out[..., 8:12], -3.0 * base[..., 8:12])
+    lens = np.array([7], dtype=np.int32)
+    cut = oracle.decode_attn_chunked(q, DK, idxK[:, :, :7], coefK[:, :, :7], DV, idxV[:, :, :7], coefV[:, :, :7])
+    assert np.allclose(oracle.decode_attn_chunked(q, DK, idxK, coefK, DV, idxV, coefV, seq_lens=lens), cut)
