@@ -115,7 +115,10 @@ typedef struct {
     int64_t T;          /* code rows allocated per (b, h); 0 .. 2^20                        */
     int32_t d;          /* head dimension; supported: 128                                   */
     int32_t N;          /* atoms per dictionary                                             */
-    int32_t sK, sV;     /* pairs per key / value code, 1..32                                */
+    int32_t sK, sV;     /* pairs per key / value code (per chunk), 1..32                    */
+    int32_t snK, snV;   /* chunks per head vector for keys / values (the s_n of Section
+                           "NeuralDict"); 0 or 1 = the vector is coded whole.  Supported: 1, 2, 4, 8
+                           with fp16 q and dictionaries, N a multiple of 128 and sn * s <= 32         */
     float scale;        /* score scale; 0 means 1/sqrt(d)                                   */
     int32_t q_dtype;    /* csr_dtype of q                                                   */
     int32_t dict_dtype; /* csr_dtype of DK and DV                                           */
@@ -132,6 +135,10 @@ size_t csr_decode_workspace_bytes(const csr_decode_desc *desc);
  *   q        [B][Hq][d]        in
  *   DK, DV   [Hkv][N][d]       in, shared by all sequences
  *   idxK, coefK [B][Hkv][T][sK]   in;   idxV, coefV [B][Hkv][T][sV]   in
+ *   With chunks (snK, snV > 1; the value cache of the paper's experiments uses s = 4, s_n = 2): chunk c of a head
+ *   vector is its dimensions c*d/sn .. (c+1)*d/sn - 1, coded on its own dictionary of N atoms of that length:
+ *   DK [Hkv][snK][N][d/snK], idxK, coefK [B][Hkv][T][snK][sK], indices 0..N-1 per chunk; likewise for V.  The result
+ *   is attention over the concatenation of the chunks' reconstructions (Eq.12 per chunk).
  *   seq_lens [B] int32 device pointer, or NULL for len_b = T.  Values must lie in [0, T];
  *            larger values are clamped to T, negative ones to 0.
  *   out      [B][Hq][d]        out

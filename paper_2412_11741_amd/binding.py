@@ -32,7 +32,8 @@ class EncodeDesc(ctypes.Structure):
 class DecodeDesc(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
                 ("T", ctypes.c_int64), ("d", ctypes.c_int32), ("N", ctypes.c_int32),
-                ("sK", ctypes.c_int32), ("sV", ctypes.c_int32), ("scale", ctypes.c_float),
+                ("sK", ctypes.c_int32), ("sV", ctypes.c_int32), ("snK", ctypes.c_int32),
+                ("snV", ctypes.c_int32), ("scale", ctypes.c_float),
                 ("q_dtype", ctypes.c_int32), ("dict_dtype", ctypes.c_int32),
                 ("coef_dtype", ctypes.c_int32), ("idx_dtype", ctypes.c_int32),
                 ("out_dtype", ctypes.c_int32), ("flags", ctypes.c_uint32)]
@@ -145,10 +146,15 @@ def csr_encode(X, D, s, coef_dtype=None, idx_dtype=None, algo=CSR_ENCODE_AUTO, i
 
 
 def decode_desc(q, DK, idxK, coefK, idxV, sV=None, scale=0.0, out_dtype=None):
+    """Descriptor from tensor shapes.  Whole-vector codes: DK [Hkv, N, d], idx [B, Hkv, T, s].  Chunked codes:
+    DK [Hkv, sn, N, d/sn], idx [B, Hkv, T, sn, s] (keys and values may differ in sn and s)."""
     B, Hq, d = q.shape
-    Hkv, N, _ = DK.shape
-    T, sK = idxK.shape[2], idxK.shape[3]
-    return DecodeDesc(B=B, Hq=Hq, Hkv=Hkv, T=T, d=d, N=N, sK=sK, sV=idxV.shape[3], scale=float(scale),
+    Hkv, N = DK.shape[0], DK.shape[-2]
+    T, sK = idxK.shape[2], idxK.shape[-1]
+    snK = idxK.shape[3] if idxK.dim() == 5 else 1
+    snV = idxV.shape[3] if idxV.dim() == 5 else 1
+    return DecodeDesc(B=B, Hq=Hq, Hkv=Hkv, T=T, d=d, N=N, sK=sK, sV=idxV.shape[-1], snK=snK, snV=snV,
+                      scale=float(scale),
                       q_dtype=_DT[q.dtype], dict_dtype=_DT[DK.dtype], coef_dtype=_DT[coefK.dtype],
                       idx_dtype=_IT[idxK.dtype], out_dtype=_DT[out_dtype or q.dtype], flags=0)
 
@@ -162,14 +168,21 @@ def csr_decode_workspace_bytes(desc):
 
 def csr_decode_attn(q, DK, idxK, coefK, DV, idxV, coefV, scale=0.0, seq_lens=None, out=None,
                     out_dtype=None, workspace=None):
-    """Decode attention on codes.  q [B, Hq, d]; DK/DV [Hkv, N, d]; codes [B, Hkv, T, s*] -> out [B, Hq, d]."""
+    """Decode attention on codes.  q [B, Hq, d]; DK/DV [Hkv, N, d]; codes [B, Hkv, T, s*] -> out [B, Hq, d].
+    Chunked codes: DK [Hkv, sn, N, d/sn] with codes [B, Hkv, T, sn, s] (keys and values independently)."""
     for name, t in (("q", q), ("DK", DK), ("idxK", idxK), ("coefK", coefK), ("DV", DV), ("idxV", idxV),
                     ("coefV", coefV)):
         _dev(t, name)
         if not t.is_contiguous():
             raise ValueError(f"{name} must be contiguous")
-    if DV.shape != DK.shape or DV.dtype != DK.dtype or coefV.dtype != coefK.dtype or idxV.dtype != idxK.dtype:
-        raise ValueError("key and value dictionaries / codes must share shapes' leading dims and dtypes")
+    if (DV.shape[0] != DK.shape[0] or DV.shape[-2] != DK.shape[-2] or DV.dtype != DK.dtype or
+            coefV.dtype != coefK.dtype or idxV.dtype != idxK.dtype):
+        raise ValueError("key and value dictionaries / codes must share KV heads, atoms per dictionary and dtypes")
+    for D_, i_, what in ((DK, idxK, "key"), (DV, idxV, "value")):
+        sn = i_.shape[3] if i_.dim() == 5 else 1
+        want = (DK.shape[0], sn, D_.shape[-2], q.shape[2] // sn) if i_.dim() == 5 else (DK.shape[0], D_.shape[-2], q.shape[2])
+        if tuple(D_.shape) != want:
+            raise ValueError(f"{what} dictionary shape {tuple(D_.shape)} does not match its codes (expected {want})")
     if idxV.shape[:3] != idxK.shape[:3] or coefK.shape != idxK.shape or coefV.shape != idxV.shape:
         raise ValueError("code tensors disagree in shape")
     desc = decode_desc(q, DK, idxK, coefK, idxV, scale=scale, out_dtype=out_dtype)

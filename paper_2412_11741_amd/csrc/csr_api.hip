@@ -87,7 +87,19 @@ csr_status check_decode_desc(const csr_decode_desc *d, csr::DecodePlan *plan)
     if (d->Hq / d->Hkv > 8) return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: group size %d above 8", d->Hq / d->Hkv);
     if (d->Hkv > 65535 || d->B > 65535) return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: B or Hkv above 65535");
     if (d->T > (int64_t)1 << 20) return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: T above 2^20");
-    if (!csr::plan_decode(d->B, d->Hq, d->Hkv, d->T, d->d, d->N, plan))
+    const int snK = d->snK ? d->snK : 1, snV = d->snV ? d->snV : 1;
+    for (int sn : {snK, snV}) {
+        if (sn != 1 && sn != 2 && sn != 4 && sn != 8)
+            return fail(CSR_ERR_INVALID_ARG, "csr_decode_attn: chunk counts snK=%d snV=%d must be 0, 1, 2, 4 or 8", d->snK, d->snV);
+    }
+    if (snK > 1 || snV > 1) {
+        if (d->q_dtype != CSR_F16 || d->dict_dtype != CSR_F16)
+            return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: chunked codes need fp16 queries and dictionaries");
+        if (d->N % 128 != 0) return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: chunked codes need N a multiple of 128 (got %d)", d->N);
+        if (snK * d->sK > 32 || snV * d->sV > 32)
+            return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: more than 32 pairs per token and stream (sn * s)");
+    }
+    if (!csr::plan_decode(d->B, d->Hq, d->Hkv, d->T, d->d, d->N, snK, snV, plan))
         return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: N=%d atoms do not fit the LDS-resident score and histogram tables", d->N);
     return CSR_OK;
 }
@@ -177,6 +189,7 @@ csr_status csr_decode_attn(const csr_decode_desc *desc, const void *q, const voi
     a.seq_lens = seq_lens; a.out = out;
     a.B = desc->B; a.Hq = desc->Hq; a.Hkv = desc->Hkv; a.G = desc->Hq / desc->Hkv;
     a.T = desc->T; a.d = desc->d; a.N = desc->N; a.sK = desc->sK; a.sV = desc->sV;
+    a.snK = desc->snK ? desc->snK : 1; a.snV = desc->snV ? desc->snV : 1;
     a.scale = desc->scale > 0.0f ? desc->scale : 1.0f / std::sqrt((float)desc->d);
     a.q16 = desc->q_dtype == CSR_F16;
     a.dict16 = desc->dict_dtype == CSR_F16;

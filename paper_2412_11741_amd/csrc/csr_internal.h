@@ -53,7 +53,8 @@ struct DecodeArgs {
     void *out;
     int32_t B, Hq, Hkv, G;
     int64_t T;
-    int32_t d, N, sK, sV;
+    int32_t d, N, sK, sV;  // N atoms per (chunk) dictionary, sK / sV pairs per chunk
+    int32_t snK, snV;      // chunks per head vector (>= 1)
     float scale;
     bool q16, dict16, coef16, idx16, out16;
     void *workspace;
@@ -61,7 +62,8 @@ struct DecodeArgs {
 };
 
 // Fills the plan; returns false if no kernel configuration fits (e.g. N too large for LDS).
-bool plan_decode(int32_t B, int32_t Hq, int32_t Hkv, int64_t T, int32_t d, int32_t N, DecodePlan *p);
+bool plan_decode(int32_t B, int32_t Hq, int32_t Hkv, int64_t T, int32_t d, int32_t N, int32_t snK, int32_t snV,
+                 DecodePlan *p);
 hipError_t launch_decode(const DecodeArgs &a, const DecodePlan &p);
 
 }  // namespace csr

@@ -146,24 +146,34 @@ typedef float qd_floatx16 __attribute__((ext_vector_type(16)));
 
 __global__ __launch_bounds__(256) void qd_mfma_kernel(const __half *__restrict__ q, const __half *__restrict__ DK,
                                                       float *__restrict__ qd, int32_t B, int32_t Hq, int32_t Hkv,
-                                                      int32_t G, int32_t GB, int32_t N, float scale)
+                                                      int32_t G, int32_t GB, int32_t N, int32_t sn, float scale)
 {
+    // With chunks (sn > 1) the table has sn * N entries: entry c * N + n is q's chunk c times atom n of chunk
+    // dictionary c, a dot product over dc = 128 / sn dimensions (dc / 16 of the eight MFMA steps carry data).  N is then a multiple of
+    // 128, so a 32-atom tile never straddles two chunks.
     const int h = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & 31, hf = lane >> 5;
     const int ngs = G / GB;
     const int BG = B * G;
+    const int NT = sn * N;       // table entries
+    const int dc = 128 / sn;     // dimensions per chunk
+    const int nf = dc / 16;      // MFMA steps
     // a wave owns kQdTiles consecutive 32-atom tiles; all their rows are requested before the first product
     const int n_first = (blockIdx.x * 4 + wave) * 32 * kQdTiles;
-    if (n_first >= N) return;
+    if (n_first >= NT) return;
     qd_half8 bfrag[kQdTiles][8];
 #pragma unroll
     for (int t = 0; t < kQdTiles; ++t) {
-        const int n = n_first + t * 32 + col;
-        const __half *row = DK + ((int64_t)h * N + min(n, N - 1)) * 128 + hf * 8;
+        const int v = min(n_first + t * 32 + col, NT - 1);  // row v of [Hkv][sn * N][dc]
+        const __half *row = DK + ((int64_t)h * NT + v) * dc + hf * 8;
+        const int j_first = (min(n_first + t * 32, NT - 1) / N) * nf;  // the tile's chunk (uniform over the wave)
+        // step j multiplies dimensions 16 j .. 16 j + 15 of the query: the row sits at the steps of its chunk's
+        // dimensions and is zero elsewhere
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const uint4 raw = *reinterpret_cast<const uint4 *>(row + 16 * j);
+            uint4 raw = make_uint4(0u, 0u, 0u, 0u);
+            if (j >= j_first && j < j_first + nf) raw = *reinterpret_cast<const uint4 *>(row + 16 * (j - j_first));
             bfrag[t][j] = *reinterpret_cast<const qd_half8 *>(&raw);
         }
     }
@@ -180,19 +190,20 @@ __global__ __launch_bounds__(256) void qd_mfma_kernel(const __half *__restrict__
         }
 #pragma unroll
         for (int t = 0; t < kQdTiles; ++t) {
-            const int n = n_first + t * 32 + col;
+            const int v = n_first + t * 32 + col;
             qd_floatx16 acc;
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(afrag[j], bfrag[t][j], acc, 0, 0, 0);
-            if (n < N) {
+            for (int j = 0; j < 8; ++j)
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(afrag[j], bfrag[t][j], acc, 0, 0, 0);
+            if (v < NT) {
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
                     const int bg = q0 + 8 * r4 + 4 * hf;  // first of four consecutive queries
                     if (GB == 4 && bg + 3 < BG) {          // G is a multiple of 4: same sequence, same group slice
                         const int b = bg / G, g = bg % G;
-                        float *dst = qd + ((((int64_t)b * Hkv + h) * ngs + g / 4) * (int64_t)N + n) * 4;
+                        float *dst = qd + ((((int64_t)b * Hkv + h) * ngs + g / 4) * (int64_t)NT + v) * 4;
                         *reinterpret_cast<float4 *>(dst) = make_float4(scale * acc[4 * r4], scale * acc[4 * r4 + 1],
                                                                        scale * acc[4 * r4 + 2], scale * acc[4 * r4 + 3]);
                     } else {
@@ -200,7 +211,7 @@ __global__ __launch_bounds__(256) void qd_mfma_kernel(const __half *__restrict__
                         for (int e = 0; e < 4; ++e) {
                             if (bg + e < BG) {
                                 const int b = (bg + e) / G, g = (bg + e) % G;
-                                qd[((((int64_t)b * Hkv + h) * ngs + g / GB) * (int64_t)N + n) * GB + g % GB] = scale * acc[4 * r4 + e];
+                                qd[((((int64_t)b * Hkv + h) * ngs + g / GB) * (int64_t)NT + v) * GB + g % GB] = scale * acc[4 * r4 + e];
                             }
                         }
                     }
@@ -305,17 +316,24 @@ __device__ __forceinline__ float from_fixed(unsigned long long v)
 // One workgroup: chunk c of the tokens of (sequence b, KV head h, group slice gs).
 // LDS: table as fp32 scores q.d, [N][GB] (pass 1), then as 64-bit histogram, [GB][N] (pass 2: one table
 // per query head, so that the scatter of one head spreads over all banks) | red[waves][GB]
-template <int GB, typename TI, typename TC, int PV>
+template <int GB, typename TI, typename TC, int PV, bool CH>
 __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
     const float *__restrict__ qd, const TI *__restrict__ idxK, const TC *__restrict__ coefK,
     const TI *__restrict__ idxV, const TC *__restrict__ coefV, const int32_t *__restrict__ seq_lens,
     float *__restrict__ part_hist, float *__restrict__ part_ml, int32_t Hkv, int32_t ngs, int64_t T,
-    int32_t N, int32_t sK, int32_t sV, int64_t chunk_tokens, int32_t nchunks)
+    int32_t N, int32_t sK, int32_t sV, int32_t snK_arg, int32_t snV_arg, int64_t chunk_tokens, int32_t nchunks)
 {
+    // CH = false: whole-vector codes, the chunk loops below have one trip known at compile time
+    const int snK = CH ? snK_arg : 1, snV = CH ? snV_arg : 1;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     float *qd_s = reinterpret_cast<float *>(smem_raw);
     unsigned long long *hist = reinterpret_cast<unsigned long long *>(smem_raw);
-    float *red = reinterpret_cast<float *>(smem_raw + (size_t)N * GB * 8);  // [kStreamWaves][GB] | [kStreamWaves]
+    // With chunked codes (sn > 1) a token carries sn * s pairs; pair j of chunk c addresses entry c * N + idx of a
+    // table of sn * N entries - the same kernel on a block-diagonal dictionary that is never built.
+    const int NK = snK * N, NV = snV * N;  // entries of the score table / of one query head's histogram
+    const int sKt = snK * sK, sVt = snV * sV;  // pairs per token
+    const size_t tab_bytes = (size_t)(NK * 4 > NV * 8 ? NK * 4 : NV * 8) * GB;
+    float *red = reinterpret_cast<float *>(smem_raw + tab_bytes);  // [kStreamWaves][GB] | [kStreamWaves]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -341,7 +359,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
     const int64_t code_row = ((int64_t)b * Hkv + h) * T;
     const int n_mine = (int)((t_end - t0 + kStreamThreads - 1) / kStreamThreads);  // rounds of 1024 tokens
 
-    const int table = N * GB;
+    const int table = NK * GB;
     {
         const float *src = qd + (((int64_t)b * Hkv + h) * ngs + gs) * (int64_t)table;
         for (int e = tid * 4; e < table; e += kStreamThreads * 4) {
@@ -371,26 +389,29 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
                 float acc[GB];
 #pragma unroll
                 for (int g = 0; g < GB; ++g) acc[g] = 0.0f;
-                const TI *ip = idxK + (code_row + t) * sK;
-                const TC *cp = coefK + (code_row + t) * sK;
+                const TI *ip = idxK + (code_row + t) * sKt;
+                const TC *cp = coefK + (code_row + t) * sKt;
                 if (i == 0) {  // sample the value coefficients (see c_est below)
-                    const TC *vp = coefV + (code_row + t) * sV;
-                    for (int j0 = 0; j0 < sV; j0 += PV) {
+                    const TC *vp = coefV + (code_row + t) * sVt;
+                    for (int j0 = 0; j0 < sVt; j0 += PV) {
                         float cf[PV];
                         CoefLoad<TC, PV>::ld(vp + j0, cf);
 #pragma unroll
                         for (int j = 0; j < PV; ++j) cm = fmaxf(cm, fabsf(cf[j]));
                     }
                 }
-                for (int j0 = 0; j0 < sK; j0 += PV) {
-                    int id[PV];
-                    float cf[PV];
-                    IdxLoad<TI, PV>::ld(ip + j0, id);
-                    CoefLoad<TC, PV>::ld(cp + j0, cf);
+                const float *tab = qd_s;
+                for (int ch = 0; ch < snK; ++ch, tab += N * GB, ip += sK, cp += sK) {
+                    for (int j0 = 0; j0 < sK; j0 += PV) {  // PV divides sK: a vector load stays in its chunk
+                        int id[PV];
+                        float cf[PV];
+                        IdxLoad<TI, PV>::ld(ip + j0, id);
+                        CoefLoad<TC, PV>::ld(cp + j0, cf);
 #pragma unroll
-                    for (int j = 0; j < PV; ++j) {
+                        for (int j = 0; j < PV; ++j) {
 #pragma unroll
-                        for (int g = 0; g < GB; ++g) acc[g] = fmaf(cf[j], qd_s[id[j] * GB + g], acc[g]);
+                            for (int g = 0; g < GB; ++g) acc[g] = fmaf(cf[j], tab[id[j] * GB + g], acc[g]);
+                        }
                     }
                 }
 #pragma unroll
@@ -429,7 +450,8 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
     float m_eff[GB];
 #pragma unroll
     for (int g = 0; g < GB; ++g) m_eff[g] = m_c[g] - (float)k_units * 0.69314718f;
-    for (int e = tid; e < table; e += kStreamThreads) hist[e] = 0ull;
+    const int bins = NV * GB;
+    for (int e = tid; e < bins; e += kStreamThreads) hist[e] = 0ull;
     __syncthreads();
 
     // ---- pass 2: p = exp(score - max), scatter p * c of the V codes into the histogram -----------
@@ -444,17 +466,20 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
                 float p[GB];
 #pragma unroll
                 for (int g = 0; g < GB; ++g) { p[g] = __expf(sc[i][g] - m_eff[g]); l_thr[g] += p[g]; }
-                const TI *ip = idxV + (code_row + t) * sV;
-                const TC *cp = coefV + (code_row + t) * sV;
-                for (int j0 = 0; j0 < sV; j0 += PV) {
-                    int id[PV];
-                    float cf[PV];
-                    IdxLoad<TI, PV>::ld(ip + j0, id);
-                    CoefLoad<TC, PV>::ld(cp + j0, cf);
+                const TI *ip = idxV + (code_row + t) * sVt;
+                const TC *cp = coefV + (code_row + t) * sVt;
+                unsigned long long *hb = hist;
+                for (int ch = 0; ch < snV; ++ch, hb += N, ip += sV, cp += sV) {
+                    for (int j0 = 0; j0 < sV; j0 += PV) {
+                        int id[PV];
+                        float cf[PV];
+                        IdxLoad<TI, PV>::ld(ip + j0, id);
+                        CoefLoad<TC, PV>::ld(cp + j0, cf);
 #pragma unroll
-                    for (int j = 0; j < PV; ++j) {
+                        for (int j = 0; j < PV; ++j) {
 #pragma unroll
-                        for (int g = 0; g < GB; ++g) atomicAdd(&hist[g * N + id[j]], to_fixed(p[g] * cf[j]));
+                            for (int g = 0; g < GB; ++g) atomicAdd(&hb[g * NV + id[j]], to_fixed(p[g] * cf[j]));
+                        }
                     }
                 }
             }
@@ -477,9 +502,9 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
             ml[2 * g + 1] = ldexpf(l, -k_units);
         }
     }
-    float *dst = part_hist + slot * (int64_t)table;
+    float *dst = part_hist + slot * (int64_t)bins;
     const float from_units = ldexpf(1.0f, unit_exp + 32);
-    for (int e = tid; e < table; e += kStreamThreads) dst[e] = from_fixed(hist[e]) * from_units;
+    for (int e = tid; e < bins; e += kStreamThreads) dst[e] = from_fixed(hist[e]) * from_units;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -492,8 +517,10 @@ template <typename TD, int ATOMS, int NQ>
 __global__ __launch_bounds__(256) void out_kernel(const TD *__restrict__ DV, const float *__restrict__ part_hist,
                                                   const float *__restrict__ part_ml, float *__restrict__ part_out,
                                                   int32_t B, int32_t Hkv, int32_t G, int32_t GB, int32_t N,
-                                                  int32_t nchunks)
+                                                  int32_t snV, int32_t nchunks)
 {
+    // Chunked values (snV > 1): the slice lies in one chunk c (ATOMS divides N), whose atoms have dc = 128 / snV
+    // elements and fill columns [c * dc, (c + 1) * dc) of the output; the other columns of the slice are zero.
     __shared__ __attribute__((aligned(16))) TD dv_s[ATOMS][128];
     __shared__ __attribute__((aligned(16))) float hist_s[NQ][ATOMS];
     __shared__ float w_s[NQ][kMaxChunks];
@@ -510,14 +537,18 @@ __global__ __launch_bounds__(256) void out_kernel(const TD *__restrict__ DV, con
     constexpr int kLoads = ATOMS * (128 / kVec) / 256;  // 16-byte loads per thread
     constexpr int kElems = (NQ * ATOMS + 255) / 256;    // (query, atom) histogram entries per thread
     constexpr int kEarly = 4;                           // chunks whose histograms are requested up front
+    const int NV = snV * N, dc = 128 / snV;
+    const int col0 = (n0 / N) * dc;
 
     uint4 dv_r[kLoads];
 #pragma unroll
     for (int i = 0; i < kLoads; ++i) {
         const int e = i * 256 + tid;
         const int r = e / (128 / kVec), cch = e % (128 / kVec);
+        const int col = cch * kVec - col0;
         dv_r[i] = make_uint4(0u, 0u, 0u, 0u);
-        if (n0 + r < N) dv_r[i] = *reinterpret_cast<const uint4 *>(DV + ((int64_t)h * N + n0 + r) * 128 + cch * kVec);
+        if (n0 + r < NV && col >= 0 && col < dc)
+            dv_r[i] = *reinterpret_cast<const uint4 *>(DV + ((int64_t)h * NV + n0 + r) * dc + col);
     }
     // entry i of this thread: query bgl = e / ATOMS, atom nn = e % ATOMS with e = i * 256 + tid
     const float *ph[kElems];
@@ -527,14 +558,14 @@ __global__ __launch_bounds__(256) void out_kernel(const TD *__restrict__ DV, con
         const int e = i * 256 + tid;
         const int bgl = e / ATOMS, nn = e % ATOMS;
         ph[i] = nullptr;
-        if (e < NQ * ATOMS && bgl < nbg && n0 + nn < N) {
+        if (e < NQ * ATOMS && bgl < nbg && n0 + nn < NV) {
             const int b = (bg0 + bgl) / G, g = (bg0 + bgl) % G;
-            ph[i] = part_hist + ((((int64_t)b * Hkv + h) * ngs + g / GB) * nchunks) * (int64_t)N * GB +
-                    (int64_t)(g % GB) * N + (n0 + nn);
+            ph[i] = part_hist + ((((int64_t)b * Hkv + h) * ngs + g / GB) * nchunks) * (int64_t)NV * GB +
+                    (int64_t)(g % GB) * NV + (n0 + nn);
         }
 #pragma unroll
         for (int c = 0; c < kEarly; ++c)
-            early[i][c] = (ph[i] && c < nchunks) ? ph[i][(int64_t)c * N * GB] : 0.0f;
+            early[i][c] = (ph[i] && c < nchunks) ? ph[i][(int64_t)c * NV * GB] : 0.0f;
     }
     if (tid < nbg) {
         const int b = (bg0 + tid) / G, g = (bg0 + tid) % G;
@@ -567,7 +598,7 @@ __global__ __launch_bounds__(256) void out_kernel(const TD *__restrict__ DV, con
             }
             for (int c = kEarly; c < nchunks; ++c) {
                 const float w = w_s[bgl][c];
-                if (w > 0.0f) acc = fmaf(w, ph[i][(int64_t)c * N * GB], acc);
+                if (w > 0.0f) acc = fmaf(w, ph[i][(int64_t)c * NV * GB], acc);
             }
         }
         if (e < NQ * ATOMS) hist_s[bgl][nn] = acc;
@@ -643,10 +674,10 @@ __global__ __launch_bounds__(256) void finalize_kernel(const float *__restrict__
     }
 }
 
-template <int GB, typename TI, typename TC, int PV>
+template <int GB, typename TI, typename TC, int PV, bool CH>
 hipError_t launch_stream_t(const DecodeArgs &a, const DecodePlan &p, float *qd, float *hist, float *ml)
 {
-    auto kern = stream_kernel<GB, TI, TC, PV>;
+    auto kern = stream_kernel<GB, TI, TC, PV, CH>;
     static bool attr_set = false;  // raising the dynamic-LDS limit is needed once per kernel
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -657,16 +688,21 @@ hipError_t launch_stream_t(const DecodeArgs &a, const DecodePlan &p, float *qd, 
     const dim3 grid((unsigned)p.nchunks, (unsigned)(a.Hkv * p.ngs), (unsigned)a.B);
     hipLaunchKernelGGL(kern, grid, dim3(kStreamThreads), p.lds_bytes, a.stream, qd, (const TI *)a.idxK,
                        (const TC *)a.coefK, (const TI *)a.idxV, (const TC *)a.coefV, a.seq_lens, hist, ml,
-                       a.Hkv, p.ngs, a.T, a.N, a.sK, a.sV, p.chunk_tokens, p.nchunks);
+                       a.Hkv, p.ngs, a.T, a.N, a.sK, a.sV, a.snK, a.snV, p.chunk_tokens, p.nchunks);
     return hipGetLastError();
 }
 
 template <int GB, typename TI, typename TC>
 hipError_t launch_stream_pv(const DecodeArgs &a, const DecodePlan &p, float *qd, float *hist, float *ml)
 {
-    if (a.sK % 8 == 0 && a.sV % 8 == 0) return launch_stream_t<GB, TI, TC, 8>(a, p, qd, hist, ml);
-    if (a.sK % 4 == 0 && a.sV % 4 == 0) return launch_stream_t<GB, TI, TC, 4>(a, p, qd, hist, ml);
-    return launch_stream_t<GB, TI, TC, 1>(a, p, qd, hist, ml);
+    if (a.snK > 1 || a.snV > 1) {
+        if (a.sK % 8 == 0 && a.sV % 8 == 0) return launch_stream_t<GB, TI, TC, 8, true>(a, p, qd, hist, ml);
+        if (a.sK % 4 == 0 && a.sV % 4 == 0) return launch_stream_t<GB, TI, TC, 4, true>(a, p, qd, hist, ml);
+        return launch_stream_t<GB, TI, TC, 1, true>(a, p, qd, hist, ml);
+    }
+    if (a.sK % 8 == 0 && a.sV % 8 == 0) return launch_stream_t<GB, TI, TC, 8, false>(a, p, qd, hist, ml);
+    if (a.sK % 4 == 0 && a.sV % 4 == 0) return launch_stream_t<GB, TI, TC, 4, false>(a, p, qd, hist, ml);
+    return launch_stream_t<GB, TI, TC, 1, false>(a, p, qd, hist, ml);
 }
 
 template <int GB>
@@ -682,15 +718,17 @@ hipError_t launch_stream_gb(const DecodeArgs &a, const DecodePlan &p, float *qd,
 
 }  // namespace
 
-bool plan_decode(int32_t B, int32_t Hq, int32_t Hkv, int64_t T, int32_t d, int32_t N, DecodePlan *p)
+bool plan_decode(int32_t B, int32_t Hq, int32_t Hkv, int64_t T, int32_t d, int32_t N, int32_t snK, int32_t snV,
+                 DecodePlan *p)
 {
     (void)d;
+    const size_t NK = (size_t)snK * N, NV = (size_t)snV * N;  // entries of the score table / of a histogram
     const int G = Hq / Hkv;
     int GB = 0;
     for (int cand : {4, 2, 1}) {
         if (G % cand != 0) continue;
         // score table (fp32) and histogram (64-bit) share the space: the larger one counts
-        const size_t lds = (size_t)N * cand * 8 + (size_t)kStreamWaves * (cand + 1) * sizeof(float);
+        const size_t lds = (NK * 4 > NV * 8 ? NK * 4 : NV * 8) * cand + (size_t)kStreamWaves * (cand + 1) * sizeof(float);
         if (lds <= kLdsBudget) { GB = cand; p->lds_bytes = lds; break; }
     }
     if (!GB) return false;
@@ -714,10 +752,10 @@ bool plan_decode(int32_t B, int32_t Hq, int32_t Hkv, int64_t T, int32_t d, int32
     auto r256 = [](size_t v) { return (v + 255) & ~size_t(255); };
     const size_t BHq = (size_t)(B > 0 ? B : 1) * Hq;
     size_t off = 0;
-    p->off_qd = off;   off += r256(BHq * N * sizeof(float));
-    p->off_hist = off; off += r256(BHq * N * sizeof(float) * p->nchunks);
+    p->off_qd = off;   off += r256(BHq * NK * sizeof(float));
+    p->off_hist = off; off += r256(BHq * NV * sizeof(float) * p->nchunks);
     p->off_ml = off;   off += r256(BHq * 2 * sizeof(float) * p->nchunks);
-    p->off_acc = off;  off += r256(BHq * 128 * sizeof(float) * (size_t)((N + kOutAtomsF32 - 1) / kOutAtomsF32));
+    p->off_acc = off;  off += r256(BHq * 128 * sizeof(float) * ((NV + kOutAtomsF32 - 1) / kOutAtomsF32));
     p->total_bytes = off;
     return true;
 }
@@ -736,9 +774,9 @@ hipError_t launch_decode(const DecodeArgs &a, const DecodePlan &p)
     hipLaunchKernelGGL((qd_kernel<TQ, TD>), grid, dim3(256), 0, a.stream, (const TQ *)a.q,          \
                        (const TD *)a.DK, qd, a.B, a.Hq, a.Hkv, a.G, p.GB, a.N, a.scale)
         if (a.q16 && a.dict16) {
-            const dim3 mgrid((unsigned)((a.N + 128 * kQdTiles - 1) / (128 * kQdTiles)), (unsigned)a.Hkv);
+            const dim3 mgrid((unsigned)((a.snK * a.N + 128 * kQdTiles - 1) / (128 * kQdTiles)), (unsigned)a.Hkv);
             hipLaunchKernelGGL(qd_mfma_kernel, mgrid, dim3(256), 0, a.stream, (const __half *)a.q,
-                               (const __half *)a.DK, qd, a.B, a.Hq, a.Hkv, a.G, p.GB, a.N, a.scale);
+                               (const __half *)a.DK, qd, a.B, a.Hq, a.Hkv, a.G, p.GB, a.N, a.snK, a.scale);
         } else if (a.q16) CSR_QD(__half, float);
         else if (a.dict16) CSR_QD(float, __half);
         else CSR_QD(float, float);
@@ -756,14 +794,14 @@ hipError_t launch_decode(const DecodeArgs &a, const DecodePlan &p)
         if (e != hipSuccess) return e;
     }
     const int out_atoms = a.dict16 ? kOutAtomsF16 : kOutAtomsF32;
-    const int nslices = (a.N + out_atoms - 1) / out_atoms;
+    const int nslices = (a.snV * a.N + out_atoms - 1) / out_atoms;
     {
         const int BG = a.B * a.G;
         const int nq = BG >= 8 ? 8 : (BG >= 4 ? 4 : (BG >= 2 ? 2 : 1));
         const dim3 grid((unsigned)nslices, (unsigned)a.Hkv, (unsigned)((BG + nq - 1) / nq));
 #define CSR_OUT(TD, ATOMS, NQ)                                                                                   \
     hipLaunchKernelGGL((out_kernel<TD, ATOMS, NQ>), grid, dim3(256), 0, a.stream, (const TD *)a.DV, hist, ml, acc, \
-                       a.B, a.Hkv, a.G, p.GB, a.N, p.nchunks)
+                       a.B, a.Hkv, a.G, p.GB, a.N, a.snV, p.nchunks)
 #define CSR_OUT_NQ(TD, ATOMS)                                                                                    \
     switch (nq) {                                                                                                \
         case 8: CSR_OUT(TD, ATOMS, 8); break;                                                                    \

@@ -91,6 +91,10 @@ def _dec(**kw):
     (dict(out_dtype=5), B.CSR_ERR_INVALID_ARG), (dict(flags=2), B.CSR_ERR_INVALID_ARG),
     (dict(d=64), B.CSR_ERR_UNSUPPORTED), (dict(Hq=32, Hkv=2), B.CSR_ERR_UNSUPPORTED),
     (dict(N=60000, Hq=2), B.CSR_ERR_UNSUPPORTED),
+    (dict(snV=3), B.CSR_ERR_INVALID_ARG), (dict(snK=16), B.CSR_ERR_INVALID_ARG), (dict(snK=-2), B.CSR_ERR_INVALID_ARG),
+    (dict(snV=2, q_dtype=B.CSR_F32), B.CSR_ERR_UNSUPPORTED), (dict(snV=2, dict_dtype=B.CSR_F32), B.CSR_ERR_UNSUPPORTED),
+    (dict(snK=2, N=4000), B.CSR_ERR_UNSUPPORTED), (dict(snV=8, sV=8), B.CSR_ERR_UNSUPPORTED),
+    (dict(snV=8, N=8192, Hq=2), B.CSR_ERR_UNSUPPORTED),   # 8 x 8192 histogram bins of 8 bytes exceed the LDS
 ])
 def test_decode_rejects_bad_descriptors_before_launch(kw, status):
     lib = csr.lib()
@@ -111,6 +115,14 @@ def test_decode_workspace_is_required_and_checked():
     assert lib.csr_decode_attn(ctypes.byref(d), p, p, p, p, p, p, p, None, p, ctypes.c_void_p(0x1010), need, None) == B.CSR_ERR_WORKSPACE
     assert lib.csr_decode_attn(ctypes.byref(d), None, p, p, p, p, p, p, None, p, p, need, None) == B.CSR_ERR_INVALID_ARG
     assert lib.csr_decode_attn(ctypes.byref(_dec(B=0)), None, None, None, None, None, None, None, None, None, None, 0, None) == B.CSR_OK
+
+
+def test_decode_workspace_grows_with_the_chunk_count_and_zero_means_one_chunk():
+    lib = csr.lib()
+    size = lambda **kw: lib.csr_decode_workspace_bytes(ctypes.byref(_dec(**kw)))
+    assert size(snK=0, snV=0) == size(snK=1, snV=1) == size()
+    assert size(sV=4, snV=2) > size(sV=4)   # two histograms' worth of bins per query head
+    assert size(sK=4, snK=2) > size(sK=4)   # twice the score table
 
 
 def test_binding_refuses_cpu_tensors():

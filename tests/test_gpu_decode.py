@@ -225,3 +225,54 @@ def test_hot_atom_with_largest_fp16_coefficients_does_not_overflow():
     coefV[...] = np.float16(60000.0)
     out = _run(q, DK, idxK, coefK, DV, idxV, coefV, out_dtype=torch.float32)
     _check(out, oracle.decode_attn(q, DK, idxK, coefK, DV, idxV, coefV), TOL_F32_OUT, "hot atom, largest coefficients")
+
+
+# --- chunked codes (s_n of Section "NeuralDict"; the experiments store values with s = 4, s_n = 2) ---------
+
+def _chunked_case(seed, B, Hq, Hkv, T, N, snK, sK, snV, sV):
+    d = 128
+    q = synth.queries(seed, B, Hq, d, "f16")
+    DK = synth.dictionary(seed, "dict_k", Hkv * snK, N, d // snK, "f16").reshape(Hkv, snK, N, d // snK)
+    DV = synth.dictionary(seed, "dict_v", Hkv * snV, N, d // snV, "f16").reshape(Hkv, snV, N, d // snV)
+    idxK, coefK = synth.random_codes(seed, 0, B, Hkv, T, snK * sK, N, "f16", "i16")
+    idxV, coefV = synth.random_codes(seed, 1, B, Hkv, T, snV * sV, N, "f16", "i16")
+    r = lambda a, sn, s: np.ascontiguousarray(a.reshape(B, Hkv, T, sn, s))
+    return q, DK, r(idxK, snK, sK), r(coefK, snK, sK), DV, r(idxV, snV, sV), r(coefV, snV, sV)
+
+
+def _u16(idx):
+    return idx.view(np.uint16).astype(np.int64)
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,T,N,snK,sK,snV,sV", [
+    (1, 2, 2, 700, 256, 1, 8, 2, 4),      # CSR-8 of the experiments: keys whole, values in two chunks
+    (2, 4, 4, 2500, 1024, 1, 16, 2, 8),   # CSR-16, several token chunks with a ragged tail
+    (1, 8, 2, 1300, 512, 2, 4, 2, 4),     # both chunked, query groups of 4
+    (3, 2, 1, 333, 128, 4, 2, 8, 1),      # many chunks, odd vector widths of the code loads
+    (1, 1, 1, 1, 128, 8, 4, 4, 8),        # a single token, the most pairs per token
+    (1, 4, 2, 5000, 2048, 2, 3, 4, 5),    # pair counts that are not a multiple of 4
+])
+def test_chunked_codes_against_the_concatenated_reconstruction(B, Hq, Hkv, T, N, snK, sK, snV, sV):
+    q, DK, iK, cK, DV, iV, cV = _chunked_case(21, B, Hq, Hkv, T, N, snK, sK, snV, sV)
+    DKo = DK if snK > 1 else DK[:, 0]
+    iKo, cKo = (iK, cK) if snK > 1 else (iK[:, :, :, 0], cK[:, :, :, 0])
+    out = _run(q, DKo, iKo, cKo, DV, iV, cV)
+    ref = oracle.decode_attn_chunked(q, DK, _u16(iK), cK, DV, _u16(iV), cV)
+    _check(out, ref, TOL_F16_OUT, f"chunked snK={snK} sK={sK} snV={snV} sV={sV} T={T} N={N}")
+
+
+def test_chunked_codes_with_sequence_lengths():
+    B, T = 4, 3000
+    q, DK, iK, cK, DV, iV, cV = _chunked_case(22, B, 4, 2, T, 512, 2, 4, 2, 4)
+    lens = [0, 1, 1024, T]
+    out = _run(q, DK, iK, cK, DV, iV, cV, seq_lens=lens)
+    ref = oracle.decode_attn_chunked(q, DK, _u16(iK), cK, DV, _u16(iV), cV, seq_lens=lens)
+    assert np.all(out[0] == 0)
+    _check(out[1:], ref[1:], TOL_F16_OUT, "chunked with seq_lens")
+
+
+def test_one_chunk_given_as_five_dimensional_codes_is_the_plain_path_bit_for_bit():
+    q, DK, iK, cK, DV, iV, cV = _case(23, 2, 4, 2, 1500, 512, 8, 4)
+    a = _run(q, DK, iK, cK, DV, iV, cV)
+    b = _run(q, DK[:, None], iK[:, :, :, None], cK[:, :, :, None], DV[:, None], iV[:, :, :, None], cV[:, :, :, None])
+    assert np.array_equal(a.view(np.uint16), b.view(np.uint16))
