@@ -68,9 +68,13 @@ typedef enum {
 typedef struct {
     int32_t H;          /* dictionaries (e.g. KV heads x {K,V}); >= 0                      */
     int64_t T;          /* vectors per dictionary; >= 0 (0 is a no-op)                     */
-    int32_t d;          /* vector length; supported: 128 (MFMA), multiples of 64 <= 256 (VALU) */
+    int32_t d;          /* vector length; the chunk length d / s_n must be 32, 64 or 128
+                           (VALU); the MFMA encoder takes fp16 chunks of 64 or 128              */
     int32_t N;          /* atoms per dictionary, 1..65536 (I16) or 1..2^24 (I32)            */
-    int32_t s;          /* iterations = pairs per vector, 1..32                             */
+    int32_t s;          /* iterations = pairs per vector (per chunk), 1..32                 */
+    int32_t s_n;        /* chunks per vector (Section "NeuralDict"): 0 or 1 = the vector is coded
+                           whole; else 2, 4 or 8: dimensions c*d/s_n .. (c+1)*d/s_n - 1 form chunk
+                           c, which is encoded on its own, on dictionary c, as a vector of its own */
     int32_t x_dtype;    /* csr_dtype of X                                                   */
     int32_t dict_dtype; /* csr_dtype of D; must equal x_dtype                               */
     int32_t coef_dtype; /* csr_dtype of coef                                                */
@@ -87,9 +91,9 @@ size_t csr_encode_workspace_bytes(const csr_encode_desc *desc);
 
 /*
  *   X    [H][T][d]  (strides as given)   in
- *   D    [H][N][d]                       in
- *   idx  [H][T][s]  idx_dtype            out
- *   coef [H][T][s]  coef_dtype           out
+ *   D    [H][N][d]                       in       (chunked: [H][s_n][N][d/s_n])
+ *   idx  [H][T][s]  idx_dtype            out      (chunked: [H][T][s_n][s], atom numbers 0..N-1 per chunk)
+ *   coef [H][T][s]  coef_dtype           out      (chunked: [H][T][s_n][s])
  *   workspace: device memory, 256-byte aligned, >= csr_encode_workspace_bytes(); may be NULL
  *   when that is 0.  Contents are undefined before and after.
  */

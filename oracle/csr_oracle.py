@@ -8,6 +8,10 @@ exactly, so the oracle sees the same input bits the GPU saw.
 Functions and the passages they follow:
   mp_encode        Matching Pursuit, Eq.2-4, s iterations ("Sparse representation",
                    "KV Decomposition and Sparse Storage")
+  mp_encode_chunked
+                   Matching Pursuit of every chunk of a vector on that chunk's dictionary (the s_n of
+                   Section "NeuralDict": a head vector of d_h values is cut into s_n pieces of
+                   d_h / s_n, each represented on a dictionary of atoms of that length)
   reconstruct      X~ = D r, Eq.12
   decode_attn      softmax attention of one query per sequence over K~, V~
                    ("De-Sparse to restore", last paragraph)
@@ -101,6 +105,20 @@ def mp_encode_heads(X, D, s, nthreads=0, diagnostics=False):
         diag = {k: np.stack([o[2][k] for o in outs]) for k in outs[0][2]}
         return idx, coef, diag
     return idx, coef
+
+
+def mp_encode_chunked(X, D, s, nthreads=0):
+    """Chunked Matching Pursuit: X [T, d], D [s_n, N, d / s_n] -> idx int32, coef float64 [T, s_n, s].
+
+    Chunk c of a vector is its dimensions c d/s_n .. (c+1) d/s_n - 1; it is encoded by mp_encode as a vector
+    of its own against D[c], with atom numbers local to that dictionary.  Reading taken: the chunks are
+    independent problems (each has its own residual and its own s iterations).
+    """
+    X, D = np.asarray(X), np.asarray(D)
+    sn, N, dc = D.shape
+    assert X.ndim == 2 and X.shape[1] == sn * dc
+    outs = [mp_encode(X[:, c * dc:(c + 1) * dc], D[c], s, nthreads) for c in range(sn)]
+    return np.stack([o[0] for o in outs], axis=1), np.stack([o[1] for o in outs], axis=1)
 
 
 def reconstruct(idx, coef, D):

@@ -23,7 +23,8 @@ EXPORTS = ("csr_version", "csr_last_error", "csr_code_bytes", "csr_encode_worksp
 
 class EncodeDesc(ctypes.Structure):
     _fields_ = [("H", ctypes.c_int32), ("T", ctypes.c_int64), ("d", ctypes.c_int32),
-                ("N", ctypes.c_int32), ("s", ctypes.c_int32), ("x_dtype", ctypes.c_int32),
+                ("N", ctypes.c_int32), ("s", ctypes.c_int32), ("s_n", ctypes.c_int32),
+                ("x_dtype", ctypes.c_int32),
                 ("dict_dtype", ctypes.c_int32), ("coef_dtype", ctypes.c_int32),
                 ("idx_dtype", ctypes.c_int32), ("x_stride_h", ctypes.c_int64),
                 ("x_stride_t", ctypes.c_int64), ("algo", ctypes.c_int32), ("flags", ctypes.c_uint32)]
@@ -108,7 +109,7 @@ def encode_desc(X, D, s, coef_dtype, idx_dtype, algo=CSR_ENCODE_AUTO):
     H, T, d = X.shape
     if X.stride(2) != 1:
         raise ValueError("X must be contiguous along d")
-    return EncodeDesc(H=H, T=T, d=d, N=D.shape[1], s=s, x_dtype=_DT[X.dtype], dict_dtype=_DT[D.dtype],
+    return EncodeDesc(H=H, T=T, d=d, N=D.shape[-2], s=s, s_n=D.shape[1] if D.dim() == 4 else 1, x_dtype=_DT[X.dtype], dict_dtype=_DT[D.dtype],
                       coef_dtype=_DT[coef_dtype], idx_dtype=_IT[idx_dtype],
                       x_stride_h=X.stride(0) if H > 1 and T > 0 else 0,
                       x_stride_t=X.stride(1) if T > 1 else 0, algo=algo, flags=0)
@@ -123,19 +124,22 @@ def csr_encode_workspace_bytes(desc):
 
 def csr_encode(X, D, s, coef_dtype=None, idx_dtype=None, algo=CSR_ENCODE_AUTO, idx=None, coef=None,
                workspace=None):
-    """Matching Pursuit encode.  X [H, T, d], D [H, N, d] on the GPU -> (idx, coef) [H, T, s]."""
+    """Matching Pursuit encode.  X [H, T, d], D [H, N, d] on the GPU -> (idx, coef) [H, T, s].
+    Chunked: D [H, s_n, N, d / s_n] -> (idx, coef) [H, T, s_n, s], every chunk encoded on its own dictionary."""
     _dev(X, "X"); _dev(D, "D")
-    if X.dim() != 3 or D.dim() != 3 or D.shape[0] != X.shape[0] or D.shape[2] != X.shape[2]:
-        raise ValueError("expected X [H, T, d] and D [H, N, d]")
+    if X.dim() != 3 or D.dim() not in (3, 4) or D.shape[0] != X.shape[0] or \
+            D.shape[-1] * (D.shape[1] if D.dim() == 4 else 1) != X.shape[2]:
+        raise ValueError("expected X [H, T, d] and D [H, N, d] or [H, s_n, N, d / s_n]")
     D = D.contiguous()
     coef_dtype = coef_dtype or X.dtype
     idx_dtype = idx_dtype or (torch.int16 if X.dtype == torch.float16 else torch.int32)
     desc = encode_desc(X, D, s, coef_dtype, idx_dtype, algo)
     H, T, _ = X.shape
+    shape = (H, T, s) if D.dim() == 3 else (H, T, D.shape[1], s)
     if idx is None:
-        idx = torch.empty((H, T, s), dtype=idx_dtype, device=X.device)
+        idx = torch.empty(shape, dtype=idx_dtype, device=X.device)
     if coef is None:
-        coef = torch.empty((H, T, s), dtype=coef_dtype, device=X.device)
+        coef = torch.empty(shape, dtype=coef_dtype, device=X.device)
     need = csr_encode_workspace_bytes(desc)
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=X.device)

@@ -43,8 +43,14 @@ csr_status check_encode_desc(const csr_encode_desc *d, bool *use_mfma)
     if (d->N > (1 << 24)) return fail(CSR_ERR_UNSUPPORTED, "csr_encode: N=%d above 2^24", d->N);
     if (d->x_dtype != d->dict_dtype)
         return fail(CSR_ERR_UNSUPPORTED, "csr_encode: vectors and dictionary must share one dtype");
-    if (d->d != 32 && d->d != 64 && d->d != 128)
-        return fail(CSR_ERR_UNSUPPORTED, "csr_encode: d=%d not supported (32, 64, 128)", d->d);
+    const int sn = d->s_n ? d->s_n : 1;
+    if (sn != 1 && sn != 2 && sn != 4 && sn != 8)
+        return fail(CSR_ERR_INVALID_ARG, "csr_encode: s_n=%d must be 0, 1, 2, 4 or 8", d->s_n);
+    if (d->d % sn != 0) return fail(CSR_ERR_INVALID_ARG, "csr_encode: d=%d is not a multiple of s_n=%d", d->d, sn);
+    const int dc = d->d / sn;
+    if (dc != 32 && dc != 64 && dc != 128)
+        return fail(CSR_ERR_UNSUPPORTED, "csr_encode: chunk length d/s_n=%d not supported (32, 64, 128)", dc);
+    if ((int64_t)d->H * sn > 0x7fffffffLL) return fail(CSR_ERR_UNSUPPORTED, "csr_encode: H*s_n too large");
     const int64_t st = d->x_stride_t ? d->x_stride_t : d->d;
     const int64_t sh = d->x_stride_h ? d->x_stride_h : d->T * st;
     const int64_t vec = d->x_dtype == CSR_F16 ? 8 : 4;  // elements per 16-byte load
@@ -53,15 +59,15 @@ csr_status check_encode_desc(const csr_encode_desc *d, bool *use_mfma)
                     (long long)sh, (long long)st);
     if (d->T > 0 && d->H > 1 && sh < (d->T - 1) * st + d->d)
         return fail(CSR_ERR_INVALID_ARG, "csr_encode: x_stride_h=%lld makes dictionaries' vector blocks overlap", (long long)sh);
-    if ((d->T + 63) / 64 * (int64_t)d->H > 0x7fffffffLL)
+    if ((d->T + 63) / 64 * (int64_t)d->H * sn > 0x7fffffffLL)
         return fail(CSR_ERR_UNSUPPORTED, "csr_encode: H*T too large for one launch");
     csr::EncodeArgs probe{};
-    probe.H = d->H; probe.T = d->T; probe.d = d->d; probe.N = d->N; probe.s = d->s;
+    probe.H = d->H; probe.T = d->T; probe.d = dc; probe.sn = sn; probe.N = d->N; probe.s = d->s;
     probe.f16 = d->x_dtype == CSR_F16;
     const bool mfma_ok = csr::encode_mfma_supported(probe);
     if (d->algo == CSR_ENCODE_MFMA && !mfma_ok)
-        return fail(CSR_ERR_UNSUPPORTED, "csr_encode: the MFMA encoder needs fp16 inputs, d=128 and N a multiple of 32 (got d=%d N=%d %s)",
-                    d->d, d->N, probe.f16 ? "f16" : "f32");
+        return fail(CSR_ERR_UNSUPPORTED, "csr_encode: the MFMA encoder needs fp16 inputs, chunks of 64 or 128 dimensions and N a multiple of 32 (got d/s_n=%d N=%d %s)",
+                    dc, d->N, probe.f16 ? "f16" : "f32");
     *use_mfma = (d->algo == CSR_ENCODE_MFMA) || (d->algo == CSR_ENCODE_AUTO && mfma_ok);
     return CSR_OK;
 }
@@ -124,7 +130,7 @@ size_t csr_encode_workspace_bytes(const csr_encode_desc *desc)
     bool mfma = false;
     if (check_encode_desc(desc, &mfma) != CSR_OK) return (size_t)-1;
     if (!mfma || desc->H == 0 || desc->T == 0) return 0;
-    return csr::encode_mfma_workspace_bytes(desc->H, desc->T, desc->N, desc->s);
+    return csr::encode_mfma_workspace_bytes(desc->H * (desc->s_n ? desc->s_n : 1), desc->T, desc->N, desc->s);
 }
 
 csr_status csr_encode(const csr_encode_desc *desc, const void *X, const void *D, void *idx,
@@ -137,14 +143,15 @@ csr_status csr_encode(const csr_encode_desc *desc, const void *X, const void *D,
     if (!X || !D || !idx || !coef) return fail(CSR_ERR_INVALID_ARG, "csr_encode: NULL data pointer");
     if (!aligned(X, 16) || !aligned(D, 16)) return fail(CSR_ERR_INVALID_ARG, "csr_encode: X and D must be 16-byte aligned");
     if (!aligned(idx, 4) || !aligned(coef, 4)) return fail(CSR_ERR_INVALID_ARG, "csr_encode: idx and coef must be 4-byte aligned");
-    const size_t need = mfma ? csr::encode_mfma_workspace_bytes(desc->H, desc->T, desc->N, desc->s) : 0;
+    const int sn = desc->s_n ? desc->s_n : 1;
+    const size_t need = mfma ? csr::encode_mfma_workspace_bytes(desc->H * sn, desc->T, desc->N, desc->s) : 0;
     if (need) {
         if (!workspace || workspace_bytes < need || !aligned(workspace, 256))
             return fail(CSR_ERR_WORKSPACE, "csr_encode: workspace of %zu bytes (256-byte aligned) required, got %zu", need, workspace ? workspace_bytes : (size_t)0);
     }
     csr::EncodeArgs a{};
     a.X = X; a.D = D; a.idx = idx; a.coef = coef;
-    a.H = desc->H; a.T = desc->T; a.d = desc->d; a.N = desc->N; a.s = desc->s;
+    a.H = desc->H; a.T = desc->T; a.d = desc->d / sn; a.sn = sn; a.N = desc->N; a.s = desc->s;
     a.x_stride_t = desc->x_stride_t ? desc->x_stride_t : desc->d;
     a.x_stride_h = desc->x_stride_h ? desc->x_stride_h : desc->T * a.x_stride_t;
     a.f16 = desc->x_dtype == CSR_F16;

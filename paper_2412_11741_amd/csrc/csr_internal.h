@@ -21,7 +21,8 @@ struct EncodeArgs {
     void *coef;
     int32_t H;
     int64_t T;
-    int32_t d, N, s;
+    int32_t d, N, s;                 // d = length of one chunk (the vector's length if sn == 1)
+    int32_t sn;                      // chunks per vector (>= 1); chunk c of head h uses dictionary h * sn + c
     int64_t x_stride_h, x_stride_t;  // elements, already defaulted
     bool f16;                        // X and D are fp16 (else fp32)
     bool coef16, idx16;
@@ -32,7 +33,7 @@ struct EncodeArgs {
 // fp32 vector-ALU encoder: any N, d in {32, 64, 128}.
 hipError_t launch_encode_valu(const EncodeArgs &a);
 
-// fp16 matrix-core encoder: d == 128, fp16 inputs.
+// fp16 matrix-core encoder: chunks of 64 or 128 dimensions, fp16 inputs.
 bool encode_mfma_supported(const EncodeArgs &a);
 size_t encode_mfma_workspace_bytes(int32_t H, int64_t T, int32_t N, int32_t s);
 hipError_t launch_encode_mfma(const EncodeArgs &a);

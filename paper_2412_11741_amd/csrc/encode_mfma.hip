@@ -1,4 +1,6 @@
-// Matrix-core Matching Pursuit encoder for fp16 vectors and dictionaries, d = 128 (gfx950).
+// Matrix-core Matching Pursuit encoder for fp16 vectors and dictionaries of 128 or 64 dimensions (gfx950):
+// whole head vectors, or the chunks of the paper's Section "NeuralDict" (s_n = 2), each chunk a vector of its
+// own on its own dictionary.  The description below gives the numbers for 128 dimensions.
 //
 // What is computed is exactly Eq.2-4 of the paper's Section "Sparse representation": every
 // iteration picks the atom of largest |R . d_n| (lowest n on ties), takes the signed projection as
@@ -58,17 +60,26 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int kD = 128;
 constexpr int kBlocks = 2;                            // 32-token blocks per wave
 constexpr int kWavesPerWG = 4;
 constexpr int kThreads = 64 * kWavesPerWG;            // 256
 constexpr int kTokPerWave = 32 * kBlocks;             // 64
 constexpr int kTokPerWG = kWavesPerWG * kTokPerWave;  // 256
-constexpr int kStageTiles = 2;                        // 32-atom tiles per LDS stage
-constexpr int kStageAtoms = 32 * kStageTiles;         // 64
-constexpr int kStageBytes = kStageAtoms * kD * 2;     // 16 KiB, rows unpadded, chunks XOR-swizzled
+constexpr int kStageBytes = 16384;                    // one LDS stage: rows unpadded, 16-byte pieces XOR-swizzled
 constexpr int kRing = 3;                              // stage buffers; stage st lives in buffer st % 3
-constexpr int kStageLoads = kStageAtoms / (4 * kWavesPerWG);  // load instructions per lane and stage
+constexpr int kStageLoads = kStageBytes / (16 * kThreads);  // load instructions per lane and stage (4)
+// Shapes that follow from the vector length DC (128 or 64)
+template <int DC> struct Shape {
+    static constexpr int kRowBytes = DC * 2;
+    static constexpr int kFrags = DC / 16;                       // 8-element MFMA operand fragments per lane
+    static constexpr int kStageAtoms = kStageBytes / kRowBytes;  // 64 | 128
+    static constexpr int kStageTiles = kStageAtoms / 32;         // 32-atom tiles per stage: 2 | 4
+    static constexpr int kPieces = kRowBytes / 16;               // 16-byte pieces per row: 16 | 8
+    static constexpr int kRowsPerKiB = 1024 / kRowBytes;         // rows one wave-wide load instruction fills: 4 | 8
+    // XOR term of a row's piece positions.  A 256-byte row spans all 64 banks, so 16 consecutive rows must
+    // differ; two 128-byte rows span them, so 16 consecutive rows need 8 different terms, one per row pair.
+    static __device__ __forceinline__ int swz(int row) { return DC == 128 ? (row & 15) : ((row >> 1) & 7); }
+};
 constexpr int kScratchPerWave = 1024;                 // LDS a wave uses to share one token's state
 constexpr int kScratchOff = kRing * kStageBytes;
 constexpr int kLdsBytes = kScratchOff + kWavesPerWG * kScratchPerWave;  // 52 KiB: two workgroups per CU
@@ -126,24 +137,28 @@ __device__ __forceinline__ void dot8(const half8 &a, const half8 &d, float &s0, 
 
 // One dictionary stage (64 atoms x 256 B) from global memory into an LDS buffer, no registers in
 // between.  Each wave instruction fills 1 KiB = 4 rows; lane l lands at byte 16 l of that KiB, i.e.
-// row l/16, chunk position l%16, and fetches source chunk position ^ (row & 15).  A wave's
-// instructions are 16 rows apart, so that XOR term is the same for all of them and the source is
-// (uniform stage base + 4 KiB steps) + one per-lane offset, `lane_off` = stage_lane_offset().
+// row l/16, piece position l%16, and fetches source piece position ^ swz(row).  A wave's
+// instructions are 16 rows apart (32 rows of 128 B), so that XOR term is the same for all of them and the
+// source is (uniform stage base + 4 KiB steps) + one per-lane offset, `lane_off` = stage_lane_offset().
 // Rows past the dictionary's end are not fetched; the sweep never reads those tiles.
+template <int DC>
 __device__ __forceinline__ uint32_t stage_lane_offset(int wave, int lane)
 {
-    const int row0 = wave * 4 + (lane >> 4);
-    return (uint32_t)(row0 * kD * 2 + (((lane & 15) ^ (row0 & 15)) << 4));
+    using S = Shape<DC>;
+    const int row0 = wave * S::kRowsPerKiB + lane / S::kPieces;
+    return (uint32_t)(row0 * S::kRowBytes + (((lane % S::kPieces) ^ S::swz(row0)) << 4));
 }
 
+template <int DC>
 __device__ __forceinline__ void issue_stage(const __half *__restrict__ Dh, int stage, int32_t N, unsigned char *buf,
                                             int wave, int lane, uint32_t lane_off)
 {
+    using S = Shape<DC>;
     const unsigned char *sbase = reinterpret_cast<const unsigned char *>(Dh) + (int64_t)stage * kStageBytes;
-    const int rows_left = N - stage * kStageAtoms - (wave * 4 + (lane >> 4));  // > 0 for the rows that exist
+    const int rows_left = N - stage * S::kStageAtoms - (wave * S::kRowsPerKiB + lane / S::kPieces);  // > 0 for the rows that exist
 #pragma unroll
     for (int i = 0; i < kStageLoads; ++i) {
-        if (16 * i < rows_left)
+        if (kWavesPerWG * S::kRowsPerKiB * i < rows_left)
             __builtin_amdgcn_global_load_lds(
                 (const __attribute__((address_space(1))) void *)(sbase + i * 4096 + lane_off),
                 (__attribute__((address_space(3))) void *)(buf + (i * kWavesPerWG + wave) * 1024), 16, 0, 0);
@@ -151,22 +166,25 @@ __device__ __forceinline__ void issue_stage(const __half *__restrict__ Dh, int s
 }
 
 // dnorm[h][slice] = max over the slice's atoms of |d_n|_2: the screening bound scales with it.
+template <int DC>
 __global__ __launch_bounds__(256) void dict_norm_kernel(const __half *__restrict__ Dict, float *__restrict__ dnorm, int32_t N)
 {
     __shared__ float red[4];
+    constexpr int kLanes = DC / 8;        // lanes per atom, 8 dimensions each
+    constexpr int kAtoms = 256 / kLanes;  // atoms per pass of the workgroup
     const int h = blockIdx.x, sl = blockIdx.y, tid = threadIdx.x;
-    const __half *Dh = Dict + (int64_t)h * N * kD;
-    const int sub = tid & 15;
+    const __half *Dh = Dict + (int64_t)h * N * DC;
+    const int sub = tid % kLanes;
     float best = 0.0f;
-    for (int n = sl * 16 + (tid >> 4); n < N; n += 16 * kNormSlices) {
-        const uint4 raw = *reinterpret_cast<const uint4 *>(Dh + (int64_t)n * kD + sub * 8);
+    for (int n = sl * kAtoms + tid / kLanes; n < N; n += kAtoms * kNormSlices) {
+        const uint4 raw = *reinterpret_cast<const uint4 *>(Dh + (int64_t)n * DC + sub * 8);
         float f[8];
         unpack8(raw, f);
         float ss = 0.0f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) ss = fmaf(f[e], f[e], ss);
 #pragma unroll
-        for (int m = 8; m >= 1; m >>= 1) ss += __shfl_xor(ss, m, 64);
+        for (int m = kLanes / 2; m >= 1; m >>= 1) ss += __shfl_xor(ss, m, 64);
         best = fmaxf(best, ss);
     }
 #pragma unroll
@@ -181,18 +199,20 @@ __global__ __launch_bounds__(256) void dict_norm_kernel(const __half *__restrict
 //   [0, 256)    hi, dimensions in order        [256, 512)  lo
 //   [512, 544)  tracked group values, lane half 0 then half 1
 //   [544, 552)  threshold bits, overflow flag
-// Lane (a = lane / 4, q = lane % 4) evaluates atom a of a 16-atom group over dimensions 32 q .. 32 q + 31.
+// Lane (a = lane / 4, q = lane % 4) evaluates atom a of a 16-atom group over a quarter of the dimensions.
 // Returns the arg-max of |hi . d + lo . d| (lowest index on ties) over the candidate groups, or over
 // all atoms when the overflow flag is set.
+template <int DC>
 __device__ __forceinline__ int resolve_token(const __half *__restrict__ Dh, int32_t N, int ntiles, uint32_t code_mask,
                                              const unsigned char *scr, int lane)
 {
+    constexpr int kQ = DC / 32;  // 8-element pieces of a quarter vector
     const int a = lane >> 2, q = lane & 3;
-    half8 th[4], tl[4];
+    half8 th[kQ], tl[kQ];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        th[j] = *reinterpret_cast<const half8 *>(scr + q * 64 + j * 16);
-        tl[j] = *reinterpret_cast<const half8 *>(scr + 256 + q * 64 + j * 16);
+    for (int j = 0; j < kQ; ++j) {
+        th[j] = *reinterpret_cast<const half8 *>(scr + q * (DC / 2) + j * 16);
+        tl[j] = *reinterpret_cast<const half8 *>(scr + 256 + q * (DC / 2) + j * 16);
     }
     const uint2 tf = *reinterpret_cast<const uint2 *>(scr + 544);
     const uint32_t thr_bits = __builtin_amdgcn_readfirstlane(tf.x);
@@ -202,13 +222,13 @@ __device__ __forceinline__ int resolve_token(const __half *__restrict__ Dh, int3
     int bn = 0;
     // `batch` atoms at a time: all their rows are requested before the first product waits
     auto eval = [&](const int (&n)[2], int batch) {
-        uint4 raw[2][4];
+        uint4 raw[2][kQ];
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
             if (b < batch) {
-                const __half *row = Dh + (int64_t)n[b] * kD + q * 32;
+                const __half *row = Dh + (int64_t)n[b] * DC + q * (DC / 4);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) raw[b][j] = *reinterpret_cast<const uint4 *>(row + 8 * j);
+                for (int j = 0; j < kQ; ++j) raw[b][j] = *reinterpret_cast<const uint4 *>(row + 8 * j);
             }
         }
 #pragma unroll
@@ -216,7 +236,7 @@ __device__ __forceinline__ int resolve_token(const __half *__restrict__ Dh, int3
             if (b < batch) {
                 float s0 = 0.0f, s1 = 0.0f, l0 = 0.0f, l1 = 0.0f;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
+                for (int j = 0; j < kQ; ++j) {
                     const half8 dv = *reinterpret_cast<const half8 *>(&raw[b][j]);
                     dot8(th[j], dv, s0, s1);
                     dot8(tl[j], dv, l0, l1);
@@ -255,13 +275,16 @@ __device__ __forceinline__ int resolve_token(const __half *__restrict__ Dh, int3
     return __builtin_amdgcn_readfirstlane(bn);
 }
 
+template <int DC>
 __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
     const __half *__restrict__ X, const __half *__restrict__ Dict, void *__restrict__ idx_out,
-    void *__restrict__ coef_out, const float *__restrict__ dnorm, int64_t T, int32_t N, int32_t s,
+    void *__restrict__ coef_out, const float *__restrict__ dnorm, int64_t T, int32_t N, int32_t s, int32_t sn,
     int64_t x_stride_h, int64_t x_stride_t, int32_t tiles_per_h, int32_t n_groups, int32_t idx16, int32_t coef16,
     uint32_t code_mask, int32_t first_round)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    using S = Shape<DC>;
+    constexpr int kFrags = S::kFrags, kStageTiles = S::kStageTiles, kStageAtoms = S::kStageAtoms;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -273,19 +296,23 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
     // that workgroups sharing a dictionary share an L2.
     int work = blockIdx.x;
     if ((n_groups & 7) == 0) work = (blockIdx.x & 7) * (n_groups >> 3) + (blockIdx.x >> 3);
-    const int h = work / tiles_per_h;
-    const int tile_wg = work - h * tiles_per_h;
-    const __half *Dh = Dict + (int64_t)h * N * kD;
+    // "head" hv = h * sn + ch is chunk ch of head h: a vector of DC dimensions on dictionary hv
+    const int hv = work / tiles_per_h;
+    const int tile_wg = work - hv * tiles_per_h;
+    const int h = hv / sn, ch = hv - h * sn;
+    const __half *Dh = Dict + (int64_t)hv * N * DC;
     const int ntiles = N >> 5;
     const int nstages = (N + kStageAtoms - 1) / kStageAtoms;
+    const int nstages_full = N / kStageAtoms;
 
-    const uint32_t lane_off = stage_lane_offset(wave, lane);
-    issue_stage(Dh, 0, N, lds, wave, lane, lane_off);  // in flight while the vectors are loaded
-    if (nstages > 1) issue_stage(Dh, 1, N, lds + kStageBytes, wave, lane, lane_off);
-    // LDS byte offset, inside a 32-row tile, of this lane's A fragment j (row = col, chunk 8 hf + j)
-    uint32_t frag_off[8];
+    const uint32_t lane_off = stage_lane_offset<DC>(wave, lane);
+    issue_stage<DC>(Dh, 0, N, lds, wave, lane, lane_off);  // in flight while the vectors are loaded
+    if (nstages > 1) issue_stage<DC>(Dh, 1, N, lds + kStageBytes, wave, lane, lane_off);
+    // LDS byte offset, inside a 32-row tile, of this lane's A fragment j (row = col, piece kFrags hf + j)
+    uint32_t frag_off[kFrags];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) frag_off[j] = (uint32_t)(col * kD * 2 + (((hf * 8 + j) ^ (col & 15)) << 4));
+    for (int j = 0; j < kFrags; ++j)
+        frag_off[j] = (uint32_t)(col * S::kRowBytes + (((hf * kFrags + j) ^ S::swz(col)) << 4));
 
     // Two workgroups share a CU.  Started together they would sweep together and select together;
     // holding back the one in the odd wave slot by about half a sweep makes one's select phase
@@ -300,7 +327,7 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
 
     float dmax = 0.0f;
 #pragma unroll
-    for (int i = 0; i < kNormSlices; ++i) dmax = fmaxf(dmax, dnorm[h * kNormSlices + i]);
+    for (int i = 0; i < kNormSlices; ++i) dmax = fmaxf(dmax, dnorm[hv * kNormSlices + i]);
     // ~code_mask in a vector register, so that packing value and tile code is one instruction with
     // the code as its only scalar operand
     uint32_t keep_mask;
@@ -309,7 +336,7 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
     const float pack_q = (float)(code_mask + 1) * 1.1920929e-7f;
 
     // ---- load the vectors, scale by a power of two, split into hi + lo ---------------------------
-    half8 hi[kBlocks][8], lo[kBlocks][8];
+    half8 hi[kBlocks][kFrags], lo[kBlocks][kFrags];
     bool valid[kBlocks];
     int64_t tok[kBlocks];
     int sexp[kBlocks];
@@ -319,11 +346,11 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
         tok[bi] = (int64_t)tile_wg * kTokPerWG + wave * kTokPerWave + bi * 32 + col;
         valid[bi] = tok[bi] < T;
         const int64_t tc = valid[bi] ? tok[bi] : T - 1;
-        const __half *xr = X + (int64_t)h * x_stride_h + tc * x_stride_t + hf * 64;
-        float xv[8][8];
+        const __half *xr = X + (int64_t)h * x_stride_h + tc * x_stride_t + ch * DC + hf * (DC / 2);
+        float xv[kFrags][8];
         float amax = 0.0f;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < kFrags; ++j) {
             const uint4 raw = *reinterpret_cast<const uint4 *>(xr + 8 * j);
             unpack8(raw, xv[j]);
 #pragma unroll
@@ -338,7 +365,7 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
         sexp[bi] = ex;
         float r2 = 0.0f, lo2 = 0.0f;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < kFrags; ++j) {
             half8 hv, lv;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
@@ -380,7 +407,7 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
         auto do_stage = [&](int st, auto buf_c) {
             constexpr int kBuf = decltype(buf_c)::value;
             const bool more = st + 2 < nstages;
-            if (more) issue_stage(Dh, st + 2, N, lds + ((kBuf + 2) % kRing) * kStageBytes, wave, lane, lane_off);
+            if (more) issue_stage<DC>(Dh, st + 2, N, lds + ((kBuf + 2) % kRing) * kStageBytes, wave, lane, lane_off);
             const int tiles_here = min(kStageTiles, ntiles - st * kStageTiles);
 #pragma unroll
             for (int rt = 0; rt < kStageTiles; ++rt) {
@@ -390,12 +417,12 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
                     for (int bi = 0; bi < kBlocks; ++bi)
 #pragma unroll
                         for (int r = 0; r < 16; ++r) acc[bi][r] = 0.0f;
-                    half8 a[8];  // all fragments of the row tile requested before the first MFMA waits
+                    half8 a[kFrags];  // all fragments of the row tile requested before the first MFMA waits
 #pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        a[j] = *reinterpret_cast<const half8 *>(lds + kBuf * kStageBytes + rt * 32 * kD * 2 + frag_off[j]);
+                    for (int j = 0; j < kFrags; ++j)
+                        a[j] = *reinterpret_cast<const half8 *>(lds + kBuf * kStageBytes + rt * 32 * S::kRowBytes + frag_off[j]);
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) {
+                    for (int j = 0; j < kFrags; ++j) {
 #pragma unroll
                         for (int bi = 0; bi < kBlocks; ++bi)
                             acc[bi] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[j], hi[bi][j], acc[bi], 0, 0, 0);
@@ -425,7 +452,9 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
                     }
                 }
             }
-            if (more) wait_vmem_but<kStageLoads>(); else wait_vmem();
+            // Only a complete stage takes kStageLoads load instructions: behind the fetch of a partial last stage,
+            // "all but the newest kStageLoads" could still leave loads of the next stage to be swept in flight.
+            if (st + 2 < nstages_full) wait_vmem_but<kStageLoads>(); else wait_vmem();
             __syncthreads();
         };
         for (int st = 0; st < nstages; st += kRing) {
@@ -435,8 +464,8 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
         }
         // all buffers are free now: fetch stages 0 and 1 for the next sweep behind the select phase
         if (g + 1 < s) {
-            issue_stage(Dh, 0, N, lds, wave, lane, lane_off);
-            if (nstages > 1) issue_stage(Dh, 1, N, lds + kStageBytes, wave, lane, lane_off);
+            issue_stage<DC>(Dh, 0, N, lds, wave, lane, lane_off);
+            if (nstages > 1) issue_stage<DC>(Dh, 1, N, lds + kStageBytes, wave, lane, lane_off);
         }
 
         // ---- select: the iteration's atom for every token, one 32-token block at a time -------
@@ -489,15 +518,15 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
                 todo &= todo - 1;
                 if (col == t) {
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        *reinterpret_cast<half8 *>(scr + hf * 128 + j * 16) = hi[bi][j];
-                        *reinterpret_cast<half8 *>(scr + 256 + hf * 128 + j * 16) = lo[bi][j];
+                    for (int j = 0; j < kFrags; ++j) {
+                        *reinterpret_cast<half8 *>(scr + hf * DC + j * 16) = hi[bi][j];
+                        *reinterpret_cast<half8 *>(scr + 256 + hf * DC + j * 16) = lo[bi][j];
                     }
                     *reinterpret_cast<uint4 *>(scr + 512 + hf * 16) = make_uint4(u[bi][0], u[bi][1], u[bi][2], u[bi][3]);
                     if (hf == 0) *reinterpret_cast<uint2 *>(scr + 544) = make_uint2(thr_bits, overflow ? 1u : 0u);
                 }
                 wave_lds_fence();
-                const int n_res = resolve_token(Dh, N, ntiles, code_mask, scr, lane);
+                const int n_res = resolve_token<DC>(Dh, N, ntiles, code_mask, scr, lane);
                 wave_lds_fence();
                 if (col == t) best_n[bi] = n_res;
             }
@@ -505,18 +534,18 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
         }
 
         // ---- update: c = (hi + lo) . d exactly, Eq.4 on the full-precision residual, new split ----
-        uint4 raw[kBlocks][8];  // both blocks' atom rows are requested before either is used
+        uint4 raw[kBlocks][kFrags];  // both blocks' atom rows are requested before either is used
 #pragma unroll
         for (int bi = 0; bi < kBlocks; ++bi) {
-            const __half *row = Dh + (int64_t)best_n[bi] * kD + hf * 64;
+            const __half *row = Dh + (int64_t)best_n[bi] * DC + hf * (DC / 2);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) raw[bi][j] = *reinterpret_cast<const uint4 *>(row + 8 * j);
+            for (int j = 0; j < kFrags; ++j) raw[bi][j] = *reinterpret_cast<const uint4 *>(row + 8 * j);
         }
 #pragma unroll
         for (int bi = 0; bi < kBlocks; ++bi) {
             float s0 = 0.0f, s1 = 0.0f, l0 = 0.0f, l1 = 0.0f;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
+            for (int j = 0; j < kFrags; ++j) {
                 const half8 dv = *reinterpret_cast<const half8 *>(&raw[bi][j]);
                 dot8(hi[bi][j], dv, s0, s1);
                 dot8(lo[bi][j], dv, l0, l1);
@@ -524,10 +553,10 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
             float best_c = (s0 + s1) + (l0 + l1);
             best_c += xchg32f(best_c, hf);
             if (!(rn2[bi] > 0.0f)) best_c = 0.0f;
-            float v[8][8];
+            float v[kFrags][8];
             float r2 = 0.0f;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
+            for (int j = 0; j < kFrags; ++j) {
                 float f[8];
                 unpack8(raw[bi][j], f);
                 const half8 ho = hi[bi][j], lo_o = lo[bi][j];
@@ -551,7 +580,7 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
                 const int k = rescale ? 14 - (e2 + 1) / 2 : 0;  // brings |R| into [2^12.5, 2^14.5)
                 const float sc = ldexpf(1.0f, k);
 #pragma unroll
-                for (int j = 0; j < 8; ++j)
+                for (int j = 0; j < kFrags; ++j)
 #pragma unroll
                     for (int e = 0; e < 8; ++e) v[j][e] *= sc;
                 r2 *= sc * sc;
@@ -559,7 +588,7 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
             }
             float lo2 = 0.0f;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
+            for (int j = 0; j < kFrags; ++j) {
                 half8 hv, lv;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
@@ -576,7 +605,7 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
             rn2[bi] = r2;
             delta[bi] = 2.0f * dmax * (sqrtf(lo2) + kGammaAcc * sqrtf(r2));
             if (valid[bi]) {
-                const int64_t o = ((int64_t)h * T + tok[bi]) * s + g;
+                const int64_t o = (((int64_t)h * T + tok[bi]) * sn + ch) * s + g;
                 if (hf == 0) {
                     if (idx16) reinterpret_cast<uint16_t *>(idx_out)[o] = (uint16_t)best_n[bi];
                     else reinterpret_cast<int32_t *>(idx_out)[o] = best_n[bi];
@@ -596,7 +625,7 @@ size_t r256(size_t v) { return (v + 255) & ~size_t(255); }
 
 bool encode_mfma_supported(const EncodeArgs &a)
 {
-    return a.f16 && a.d == kD && a.N >= 32 && a.N % 32 == 0 && a.N <= 65536;
+    return a.f16 && (a.d == 128 || a.d == 64) && a.N >= 32 && a.N % 32 == 0 && a.N <= 65536;
 }
 
 size_t encode_mfma_workspace_bytes(int32_t H, int64_t T, int32_t N, int32_t s)
@@ -605,10 +634,11 @@ size_t encode_mfma_workspace_bytes(int32_t H, int64_t T, int32_t N, int32_t s)
     return r256((size_t)H * kNormSlices * sizeof(float));
 }
 
-hipError_t launch_encode_mfma(const EncodeArgs &a)
+template <int DC>
+hipError_t launch_encode_mfma_t(const EncodeArgs &a)
 {
     const int64_t tiles = (a.T + kTokPerWG - 1) / kTokPerWG;
-    const int64_t groups = tiles * a.H;
+    const int64_t groups = tiles * a.H * a.sn;
     if (groups > 0x7fffffffLL) return hipErrorInvalidValue;
     float *dnorm = reinterpret_cast<float *>(a.workspace);
     const int ntiles = a.N / 32;
@@ -627,22 +657,27 @@ hipError_t launch_encode_mfma(const EncodeArgs &a)
         int v = 0;
         e = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev);
         if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(encode_mfma_kernel),
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(encode_mfma_kernel<DC>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess) return e;
         n_cus[dev] = v > 0 ? v : 1;
     }
     const int32_t first_round = groups > n_cus[dev] ? 2 * n_cus[dev] : 0;
 
-    hipLaunchKernelGGL(dict_norm_kernel, dim3((unsigned)a.H, kNormSlices), dim3(256), 0, a.stream,
+    hipLaunchKernelGGL(dict_norm_kernel<DC>, dim3((unsigned)(a.H * a.sn), kNormSlices), dim3(256), 0, a.stream,
                        (const __half *)a.D, dnorm, a.N);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(encode_mfma_kernel, dim3((unsigned)groups), dim3(kThreads), kLdsBytes, a.stream,
-                       (const __half *)a.X, (const __half *)a.D, a.idx, a.coef, dnorm, a.T, a.N, a.s, a.x_stride_h,
+    hipLaunchKernelGGL(encode_mfma_kernel<DC>, dim3((unsigned)groups), dim3(kThreads), kLdsBytes, a.stream,
+                       (const __half *)a.X, (const __half *)a.D, a.idx, a.coef, dnorm, a.T, a.N, a.s, a.sn, a.x_stride_h,
                        a.x_stride_t, (int32_t)tiles, (int32_t)groups, (int32_t)a.idx16, (int32_t)a.coef16, code_mask,
                        first_round);
     return hipGetLastError();
+}
+
+hipError_t launch_encode_mfma(const EncodeArgs &a)
+{
+    return a.d == 64 ? launch_encode_mfma_t<64>(a) : launch_encode_mfma_t<128>(a);
 }
 
 }  // namespace csr

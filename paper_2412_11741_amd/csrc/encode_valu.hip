@@ -28,7 +28,7 @@ template <int D_, typename TE, int W>
 __global__ __launch_bounds__(64 * W) void encode_valu_kernel(
     const TE *__restrict__ X, const TE *__restrict__ Dict, void *__restrict__ idx_out,
     void *__restrict__ coef_out, int64_t T, int32_t N, int32_t s, int64_t x_stride_h,
-    int64_t x_stride_t, int32_t tiles_per_h, int32_t idx16, int32_t coef16)
+    int64_t x_stride_t, int32_t tiles_per_h, int32_t sn, int32_t idx16, int32_t coef16)
 {
     __shared__ float s_abs[2][W][64];
     __shared__ float s_c[2][W][64];
@@ -36,8 +36,10 @@ __global__ __launch_bounds__(64 * W) void encode_valu_kernel(
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int h = blockIdx.x / tiles_per_h;
-    const int tile = blockIdx.x - h * tiles_per_h;
+    // chunked vectors: "head" hv = h * sn + c is chunk c of head h, a vector of D_ dimensions of its own
+    const int hv = blockIdx.x / tiles_per_h;
+    const int tile = blockIdx.x - hv * tiles_per_h;
+    const int h = hv / sn, ch = hv - h * sn;
     const int64_t t = (int64_t)tile * 64 + lane;
     const bool valid = t < T;
     const int64_t tc = valid ? t : T - 1;  // tail lanes recompute the last vector, never store
@@ -45,7 +47,7 @@ __global__ __launch_bounds__(64 * W) void encode_valu_kernel(
     constexpr int VN = Vec16<TE>::n;
     float R[D_];
     {
-        const TE *xr = X + (int64_t)h * x_stride_h + tc * x_stride_t;
+        const TE *xr = X + (int64_t)h * x_stride_h + tc * x_stride_t + ch * D_;
 #pragma unroll
         for (int k = 0; k < D_; k += VN) {
             Vec16<TE> v = *reinterpret_cast<const Vec16<TE> *>(xr + k);
@@ -57,7 +59,7 @@ __global__ __launch_bounds__(64 * W) void encode_valu_kernel(
     const int slice = (N + W - 1) / W;
     const int n0 = wave * slice;
     const int n1 = min(N, n0 + slice);
-    const TE *Dh = Dict + (int64_t)h * N * D_;
+    const TE *Dh = Dict + (int64_t)hv * N * D_;
 
     for (int g = 0; g < s; ++g) {
         float best = -1.0f, bc = 0.0f;
@@ -99,7 +101,7 @@ __global__ __launch_bounds__(64 * W) void encode_valu_kernel(
             }
         }
         if (wave == 0 && valid) {
-            const int64_t o = ((int64_t)h * T + t) * s + g;
+            const int64_t o = (((int64_t)h * T + t) * sn + ch) * s + g;
             if (idx16) reinterpret_cast<uint16_t *>(idx_out)[o] = (uint16_t)wi;
             else reinterpret_cast<int32_t *>(idx_out)[o] = wi;
             if (coef16) reinterpret_cast<__half *>(coef_out)[o] = __float2half_rn(wc);
@@ -116,12 +118,12 @@ hipError_t launch_valu_t(const EncodeArgs &a)
     const int64_t tiles = (a.T + 63) / 64;
     // More waves per workgroup when there are few vectors, so that a small job still spreads
     // over the chip; fewer (less redundant residual work) when there are many.
-    const int64_t groups = tiles * a.H;
+    const int64_t groups = tiles * a.H * a.sn;
     const dim3 grid((unsigned)groups);
 #define CSR_LAUNCH_VALU(W)                                                                      \
     hipLaunchKernelGGL((encode_valu_kernel<D_, TE, W>), grid, dim3(64 * W), 0, a.stream,         \
                        (const TE *)a.X, (const TE *)a.D, a.idx, a.coef, a.T, a.N, a.s,          \
-                       a.x_stride_h, a.x_stride_t, (int32_t)tiles, (int32_t)a.idx16,            \
+                       a.x_stride_h, a.x_stride_t, (int32_t)tiles, a.sn, (int32_t)a.idx16,      \
                        (int32_t)a.coef16)
     // (8 waves = 2 per SIMD leaves each lane the 128+ registers its residual needs.)
     if (groups >= 1024) CSR_LAUNCH_VALU(4);

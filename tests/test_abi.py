@@ -51,7 +51,10 @@ def _enc(**kw):
     (dict(x_stride_t=100), B.CSR_ERR_INVALID_ARG), (dict(x_stride_t=132), B.CSR_ERR_INVALID_ARG),
     (dict(x_stride_t=256, x_stride_h=128), B.CSR_ERR_INVALID_ARG),
     (dict(d=100), B.CSR_ERR_UNSUPPORTED), (dict(dict_dtype=B.CSR_F32), B.CSR_ERR_UNSUPPORTED),
-    (dict(d=64, algo=B.CSR_ENCODE_MFMA), B.CSR_ERR_UNSUPPORTED),
+    (dict(d=32, algo=B.CSR_ENCODE_MFMA), B.CSR_ERR_UNSUPPORTED),
+    (dict(s_n=3), B.CSR_ERR_INVALID_ARG), (dict(s_n=16), B.CSR_ERR_INVALID_ARG), (dict(s_n=-1), B.CSR_ERR_INVALID_ARG),
+    (dict(s_n=8), B.CSR_ERR_UNSUPPORTED),                              # chunks of 16 dimensions
+    (dict(s_n=4, algo=B.CSR_ENCODE_MFMA), B.CSR_ERR_UNSUPPORTED),      # chunks of 32: vector-ALU encoder only
     (dict(x_dtype=B.CSR_F32, dict_dtype=B.CSR_F32, algo=B.CSR_ENCODE_MFMA), B.CSR_ERR_UNSUPPORTED),
 ])
 def test_encode_rejects_bad_descriptors_before_launch(kw, status):
@@ -61,6 +64,15 @@ def test_encode_rejects_bad_descriptors_before_launch(kw, status):
     assert lib.csr_encode(ctypes.byref(d), fake, fake, fake, fake, None, 0, None) == status
     assert csr.last_error() != ""
     assert lib.csr_encode_workspace_bytes(ctypes.byref(d)) == ctypes.c_size_t(-1).value
+
+
+def test_encode_chunk_count_scales_the_workspace_and_zero_means_whole_vectors():
+    lib = csr.lib()
+    size = lambda **kw: lib.csr_encode_workspace_bytes(ctypes.byref(_enc(**kw)))
+    assert size(s_n=0) == size(s_n=1) == size() > 0
+    assert size(H=64, s_n=2) == size(H=128) and size(H=64, s_n=2) > size(H=64)   # one norm record per dictionary
+    assert size(s_n=4) == 0                                                    # the vector-ALU encoder needs none
+    assert size(d=64) > 0 and size(d=256, s_n=2) > 0                           # fp16 chunks of 64 / 128: matrix cores
 
 
 def test_encode_null_and_misaligned_pointers_and_noop_sizes():

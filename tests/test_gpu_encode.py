@@ -288,3 +288,64 @@ def test_adversarial_inputs(algo, name):
     for rep in reports:
         assert rep.ok, name + ": " + rep.summary() + "\n" + "\n".join(rep.failures)
     print(f"[encode parity] {name} ({algo}): " + reports[0].summary())
+
+
+# --- chunked vectors (the s_n of Section "NeuralDict"; the experiments store values with s = 4, s_n = 2) -----
+
+def _compare_chunked(X, D, s, idx_g, coef_g):
+    """X [H, T, d], D [H, sn, N, dc], codes [H, T, sn, s]: every chunk against the oracle's plain encoder."""
+    H, sn, _, dc = D.shape
+    reports = []
+    for h in range(H):
+        for c in range(sn):
+            Xc = np.ascontiguousarray(X[h][:, c * dc:(c + 1) * dc])
+            idx_o, coef_o, diag = oracle.mp_encode(Xc, D[h, c], s, diagnostics=True)
+            coef_o_st = coef_o.astype(coef_g.dtype).astype(np.float64)
+            reports.append(parity.check_encode(Xc, D[h, c], idx_g[h][:, c], coef_g[h][:, c], idx_o, coef_o_st, diag, TOL,
+                                               coef_storage="f16" if coef_g.dtype == np.float16 else "f32",
+                                               coef_o_exact=coef_o))
+    return reports
+
+
+@pytest.mark.parametrize("algo", ["valu", "mfma"])
+@pytest.mark.parametrize("H,T,N,d,sn,s", [
+    (2, 700, 1024, 128, 2, 4),     # the value cache of the experiments: two chunks of 64, four pairs each
+    (1, 300, 4096, 128, 2, 8),
+    (3, 257, 96, 128, 2, 3),       # a partial last stage of the dictionary (96 of 128 atoms), ragged tokens
+    (2, 130, 512, 256, 2, 4),      # two chunks of 128
+    (2, 100, 2080, 256, 4, 2),     # four chunks of 64
+])
+def test_chunked_vectors_every_chunk_on_its_own_dictionary(algo, H, T, N, d, sn, s):
+    dc = d // sn
+    D = synth.dictionary(31, "dict_v", H * sn, N, dc, "f16").reshape(H, sn, N, dc)
+    X = synth.vectors(31, "values", H, T, d, "f16")
+    idx, coef = _gpu_encode(X, D, s, ALGOS[algo])
+    assert idx.shape == coef.shape == (H, T, sn, s)
+    # the oracle's own chunked entry point has the same layout
+    io, co = oracle.mp_encode_chunked(X[0], D[0], s)
+    assert io.shape == idx[0].shape
+    _assert_ok(_compare_chunked(X, D, s, idx.view(np.uint16).astype(np.int32), coef))
+
+
+@pytest.mark.parametrize("N", [32, 64, 160, 4096])
+def test_mfma_vectors_of_64_dimensions(N):
+    H, T, d, s = 2, 500, 64, 6
+    D = synth.dictionary(32, "dict_k", H, N, d, "f16")
+    X = synth.vectors(32, "keys", H, T, d, "f16", outliers=4)
+    idx, coef = _gpu_encode(X, D, s, csr.CSR_ENCODE_MFMA)
+    _assert_ok(_compare(X, D, s, idx.view(np.uint16).astype(np.int32), coef))
+
+
+def test_chunked_mfma_and_valu_agree_and_strided_input():
+    H, T, N, d, sn, s = 2, 400, 1024, 128, 2, 4
+    D = synth.dictionary(33, "dict_v", H * sn, N, d // sn, "f16").reshape(H, sn, N, d // sn)
+    X = synth.vectors(33, "values", H, T, d, "f16")
+    wide = torch.zeros(H, T, 2 * d, dtype=torch.float16, device="cuda")
+    wide[:, :, d:] = torch.from_numpy(X).cuda()
+    Dg = torch.from_numpy(D).cuda()
+    im, cm = csr.csr_encode(wide[:, :, d:], Dg, s, algo=csr.CSR_ENCODE_MFMA)
+    iv, cv = csr.csr_encode(torch.from_numpy(X).cuda(), Dg, s, algo=csr.CSR_ENCODE_VALU)
+    torch.cuda.synchronize()
+    same = (im == iv).all(dim=-1).float().mean().item()
+    assert same > 0.999          # the two encoders may part only at ties
+    _assert_ok(_compare_chunked(X, D, s, im.cpu().numpy().view(np.uint16).astype(np.int32), cm.cpu().numpy()))

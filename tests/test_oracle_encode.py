@@ -241,3 +241,57 @@ def test_thread_count_does_not_change_results():
     a = oracle.mp_encode(X, D, 5, nthreads=1)
     b = oracle.mp_encode(X, D, 5, nthreads=4)
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+# --- chunked vectors (the s_n of Section "NeuralDict") ---------------------------------------------------
+
+def test_chunked_identity_dictionaries_give_each_chunks_top_coordinates_in_local_numbering():
+    rng = np.random.default_rng(11)
+    T, sn, dc, s = 40, 4, 8, 3
+    X = rng.standard_normal((T, sn * dc))
+    # chunk c's dictionary: the unit vectors in an order of its own, so that mixing up dictionaries shows
+    perms = [rng.permutation(dc) for _ in range(sn)]
+    D = np.stack([np.eye(dc)[perms[c]] for c in range(sn)])          # atom n of chunk c = e_{perm_c[n]}
+    idx, coef = oracle.mp_encode_chunked(X, D, s)
+    assert idx.shape == coef.shape == (T, sn, s)
+    for c in range(sn):
+        Xc = X[:, c * dc:(c + 1) * dc]
+        top = np.argsort(-np.abs(Xc), axis=1, kind="stable")[:, :s]     # coordinates, largest magnitude first
+        inv = np.argsort(perms[c])                                      # coordinate -> atom number
+        assert np.array_equal(idx[:, c], inv[top])
+        assert np.array_equal(coef[:, c], np.take_along_axis(Xc, top, axis=1))
+
+
+def test_chunks_are_independent_and_one_chunk_is_the_plain_encoder():
+    rng = np.random.default_rng(12)
+    T, sn, dc, N, s = 30, 2, 16, 64, 4
+    X = rng.standard_normal((T, sn * dc))
+    D = np.stack([_unit_rows(rng, N, dc) for _ in range(sn)])
+    idx, coef = oracle.mp_encode_chunked(X, D, s)
+    X2 = X.copy()
+    X2[:, dc:] = rng.standard_normal((T, dc))                           # other values in chunk 1 only
+    idx2, coef2 = oracle.mp_encode_chunked(X2, D, s)
+    assert np.array_equal(idx[:, 0], idx2[:, 0]) and np.array_equal(coef[:, 0], coef2[:, 0])
+    assert not np.array_equal(idx[:, 1], idx2[:, 1])
+    # one chunk: the plain encoder with a leading axis of length one
+    Dw = _unit_rows(rng, N, sn * dc)
+    i1, c1 = oracle.mp_encode_chunked(X, Dw[None], s)
+    i0, c0 = oracle.mp_encode(X, Dw, s)
+    assert np.array_equal(i1[:, 0], i0) and np.array_equal(c1[:, 0], c0)
+
+
+def test_chunked_energy_identity_per_chunk_and_error_of_the_concatenation():
+    rng = np.random.default_rng(13)
+    T, sn, dc, N, s = 25, 2, 32, 128, 6
+    X = rng.standard_normal((T, sn * dc))
+    D = np.stack([_unit_rows(rng, N, dc) for _ in range(sn)])
+    idx, coef = oracle.mp_encode_chunked(X, D, s)
+    rec = np.concatenate([oracle.reconstruct(idx[:, c], coef[:, c], D[c]) for c in range(sn)], axis=1)
+    # unit atoms: every step removes c^2 from the chunk's squared residual, so the whole vector's error is
+    # |x|^2 minus the sum of all squared coefficients
+    err = ((X - rec) ** 2).sum(axis=1)
+    assert np.allclose(err, (X ** 2).sum(axis=1) - (coef ** 2).sum(axis=(1, 2)), rtol=1e-10, atol=1e-12)
+    for c in range(sn):
+        Xc = X[:, c * dc:(c + 1) * dc]
+        errc = ((Xc - rec[:, c * dc:(c + 1) * dc]) ** 2).sum(axis=1)
+        assert np.allclose(errc, (Xc ** 2).sum(axis=1) - (coef[:, c] ** 2).sum(axis=1), rtol=1e-10, atol=1e-12)
