@@ -8,7 +8,9 @@ Prints ONE JSON line.  `value` is encoded KV vectors per second over the whole s
 rate (context tokens per second) and both rooflines are reported beside it, together with the CPU
 oracle timed on this machine's host cores on a bounded sample.  `decode_rooflines` adds the decode
 call alone at the long-context and GQA shapes (random codes drawn on the GPU, cache-cold), where
-the code streams rather than the dictionaries dominate the traffic.
+the code streams rather than the dictionaries dominate the traffic.  `chunked_step` is the same step in the
+storage layout of the paper's experiments ("CSR-8": keys whole with s = 8, values in s_n = 2 chunks of 64
+dimensions with s = 4 each), which runs the 64-dimensional variants of the encoder and the chunk-aware decode.
 
 All kernels run on PyTorch's current stream, and the HIP events that time them (torch.cuda.Event)
 are recorded on that same stream.
@@ -82,6 +84,60 @@ def decode_only(csr, w, dev):
             "config": {"kv_heads": Hkv, "query_heads": Hq, "atoms": N, "tokens_per_head": T, "s": s, "decode_batch": B}}
 
 
+def chunked_step(csr, synth, w, dev, steps):
+    """Encode + decode of one layer in the experiments' "CSR-8" layout: keys whole (s = 8), values in two chunks of
+    d/2 dimensions (s = 4 each, one dictionary of N atoms per chunk).  Same vectors as the main workload."""
+    import numpy as np
+    import torch
+    B, Hkv, Hq, T, N, d = w.batch, w.hkv, w.hq, w.tokens, w.n_atoms, w.d
+    sK, sV, sn = 8, 4, 2
+    g = lambda a: torch.from_numpy(a).to(dev)
+    XK = g(np.concatenate([synth.vectors(0, "keys", Hkv, T, d, "f16", outliers=w.key_outliers, token0=b) for b in range(B)]))
+    XV = g(np.concatenate([synth.vectors(0, "values", Hkv, T, d, "f16", token0=b) for b in range(B)]))
+    DK = g(synth.dictionary(0, "dict_k", Hkv, N, d, "f16"))
+    DV = g(synth.dictionary(0, "dict_v", Hkv * sn, N, d // sn, "f16").reshape(Hkv, sn, N, d // sn))
+    q = g(synth.queries(0, B, Hq, d, "f16"))
+    DKe, DVe = DK.repeat(B, 1, 1), DV.repeat(B, 1, 1, 1)
+    iK = torch.empty((B * Hkv, T, sK), dtype=torch.int16, device=dev)
+    cK = torch.empty((B * Hkv, T, sK), dtype=torch.float16, device=dev)
+    iV = torch.empty((B * Hkv, T, sn, sV), dtype=torch.int16, device=dev)
+    cV = torch.empty((B * Hkv, T, sn, sV), dtype=torch.float16, device=dev)
+    out = torch.empty((B, Hq, d), dtype=torch.float16, device=dev)
+    wsK = torch.empty(max(csr.csr_encode_workspace_bytes(csr.encode_desc(XK, DKe, sK, torch.float16, torch.int16)), 256),
+                      dtype=torch.uint8, device=dev)
+    wsV = torch.empty(max(csr.csr_encode_workspace_bytes(csr.encode_desc(XV, DVe, sV, torch.float16, torch.int16)), 256),
+                      dtype=torch.uint8, device=dev)
+    v5 = lambda t, s_: t.view(B, Hkv, T, sn, s_)
+    v4 = lambda t, s_: t.view(B, Hkv, T, s_)
+    ddesc = csr.decode_desc(q, DK, v4(iK, sK), v4(cK, sK), v5(iV, sV))
+    wsD = torch.empty(max(csr.csr_decode_workspace_bytes(ddesc), 256), dtype=torch.uint8, device=dev)
+
+    def enc_k(): csr.csr_encode(XK, DKe, sK, idx=iK, coef=cK, workspace=wsK)
+    def enc_v(): csr.csr_encode(XV, DVe, sV, idx=iV, coef=cV, workspace=wsV)
+    def dec(): csr.csr_decode_attn(q, DK, v4(iK, sK), v4(cK, sK), DV, v5(iV, sV), v5(cV, sV), out=out, workspace=wsD)
+
+    for _ in range(2):
+        enc_k(); enc_v(); dec()
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+    for i in range(steps):
+        ev[i][0].record(); enc_k(); ev[i][1].record(); enc_v(); ev[i][2].record(); dec(); ev[i][3].record()
+    torch.cuda.synchronize()
+    k_ms, v_ms, d_ms = (sum(e[j].elapsed_time(e[j + 1]) for e in ev) / steps for j in range(3))
+    nv = B * Hkv * T
+    tf = lambda flop, ms: round(flop / (ms * 1e-3) / 1e12, 2)
+    v_flop = 2.0 * (d // sn) * N * sV * sn * nv
+    dec_bytes = nv * (sK + sn * sV) * 4 + Hkv * 2 * N * d * 2 + B * Hq * d * 4
+    return {"layout": "K s=8 s_n=1, V s=4 s_n=2 (chunks of %d)" % (d // sn), "vectors_per_step": 2 * nv,
+            "value": round(2 * nv / ((k_ms + v_ms + d_ms) * 1e-3), 1), "unit": "vectors/s",
+            "encode_k_ms": round(k_ms, 4), "encode_v_ms": round(v_ms, 4), "decode_ms_warm": round(d_ms, 5),
+            "roofline_encode_v": {"kernel": "csr_encode (mfma, 64-dimensional chunks)", "bound": "mfma",
+                                  "achieved": tf(v_flop, v_ms), "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s",
+                                  "frac": round(tf(v_flop, v_ms) / PEAK_MFMA_F16_TFLOPS, 5)},
+            "decode_bytes_per_call": dec_bytes,
+            "decode_gbs_warm": round(dec_bytes / (d_ms * 1e-3) / 1e9, 1)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -92,6 +148,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra-decode", action="store_true",
                     help="skip the decode-only lines at the long-context and GQA shapes")
+    ap.add_argument("--no-chunked", action="store_true",
+                    help="skip the step in the chunked (s_n = 2 values) storage layout")
     ap.add_argument("--only-extra-decode", action="store_true",
                     help="run only the decode-only lines (for profiling them apart from the main workload)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -249,6 +307,10 @@ def main():
     if not args.no_extra_decode:
         result["decode_rooflines"] = [decode_only(csr, synth.WORKLOADS[n], dev)
                                       for n in ("long_context", "gqa_llama3_8b")]
+
+    # ---- the same layer in the chunked storage layout of the paper's experiments --------------------------
+    if not args.no_chunked and w.dtype == "f16" and d == 128:
+        result["chunked_step"] = chunked_step(csr, synth, w, dev, args.steps)
 
     # ---- CPU oracle on a bounded sample of the same workload ---------------------------------------
     if not args.no_cpu_baseline:

@@ -276,3 +276,22 @@ def test_one_chunk_given_as_five_dimensional_codes_is_the_plain_path_bit_for_bit
     a = _run(q, DK, iK, cK, DV, iV, cV)
     b = _run(q, DK[:, None], iK[:, :, :, None], cK[:, :, :, None], DV[:, None], iV[:, :, :, None], cV[:, :, :, None])
     assert np.array_equal(a.view(np.uint16), b.view(np.uint16))
+
+
+def test_end_to_end_in_the_experiments_layout_keys_whole_values_in_two_chunks():
+    # csr_encode output feeds csr_decode_attn unchanged: keys s = 8 whole, values s = 4 in each of two chunks
+    Hkv, G, T, N, d = 2, 2, 1500, 1024, 128
+    XK = synth.vectors(24, "keys", Hkv, T, d, "f16", outliers=8)
+    XV = synth.vectors(24, "values", Hkv, T, d, "f16")
+    DK = synth.dictionary(24, "dict_k", Hkv, N, d, "f16")
+    DV = synth.dictionary(24, "dict_v", Hkv * 2, N, d // 2, "f16").reshape(Hkv, 2, N, d // 2)
+    q = synth.queries(24, 1, Hkv * G, d, "f16")
+    g = lambda a: torch.from_numpy(a).cuda()
+    iK, cK = csr.csr_encode(g(XK), g(DK), 8)
+    iV, cV = csr.csr_encode(g(XV), g(DV), 4)
+    assert iV.shape == (Hkv, T, 2, 4)
+    out = csr.csr_decode_attn(g(q), g(DK), iK[None], cK[None], g(DV), iV[None], cV[None])
+    torch.cuda.synchronize()
+    iKh, cKh, iVh, cVh = (t.cpu().numpy()[None] for t in (iK, cK, iV, cV))
+    ref = oracle.decode_attn_chunked(q, DK[:, None], _u16(iKh)[:, :, :, None], cKh[:, :, :, None], DV, _u16(iVh), cVh)
+    _check(out.cpu().numpy(), ref, TOL_F16_OUT, "encode -> decode, CSR-8 layout")
