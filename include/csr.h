@@ -51,11 +51,15 @@ typedef enum {
 typedef enum { CSR_F32 = 0, CSR_F16 = 1 } csr_dtype; /* vectors, dictionaries, coefficients */
 typedef enum { CSR_I32 = 0, CSR_I16 = 1 } csr_itype; /* atom indices; I16 is unsigned        */
 
-/* Which encoder kernel runs.  AUTO picks MFMA when the shape allows it, else VALU. */
+/* Which encoder kernel runs.  AUTO picks SPLIT when a dictionary serves few vectors (the tokens of one
+ * decoding step), MFMA when the shape allows it, else VALU. */
 typedef enum {
     CSR_ENCODE_AUTO = 0,
     CSR_ENCODE_VALU = 1, /* fp32 vector-ALU correlation, any supported shape               */
-    CSR_ENCODE_MFMA = 2  /* fp16 matrix-core screening pass + exact fp32 selection          */
+    CSR_ENCODE_MFMA = 2, /* fp16 matrix-core screening pass + exact fp32 selection          */
+    CSR_ENCODE_SPLIT = 3 /* few vectors per dictionary (at most 128): every dictionary's atoms are
+                            split over several workgroups, one launch per iteration; fp16 inputs,
+                            chunks of 64 or 128 dimensions, N a multiple of 32                   */
 } csr_encode_algo;
 
 /*
@@ -66,7 +70,7 @@ typedef enum {
  * residual emits (0, 0).
  */
 typedef struct {
-    int32_t H;          /* dictionaries (e.g. KV heads x {K,V}); >= 0                      */
+    int32_t H;          /* vector blocks (e.g. sequences x KV heads x {K,V}); >= 0          */
     int64_t T;          /* vectors per dictionary; >= 0 (0 is a no-op)                     */
     int32_t d;          /* vector length; the chunk length d / s_n must be 32, 64 or 128
                            (VALU); the MFMA encoder takes fp16 chunks of 64 or 128              */
@@ -81,6 +85,14 @@ typedef struct {
     int32_t idx_dtype;  /* csr_itype of idx                                                 */
     int64_t x_stride_h; /* elements between dictionaries' vector blocks; 0 = T*d            */
     int64_t x_stride_t; /* elements between consecutive vectors; 0 = d                      */
+    int32_t dict_count; /* distinct dictionaries: block h uses dictionary h % dict_count (blocks ordered
+                           sequence-major, head-minor share the heads' dictionaries); 0 = H, one each.
+                           Must divide H                                                    */
+    int64_t code_stride_h; /* elements between consecutive blocks' codes in idx and in coef; 0 = T*s_n*s.
+                           With T = 1, idx / coef pointing at row t of a cache [H][T_max][s_n*s] and
+                           code_stride_h = T_max*s_n*s the new token's codes are appended in place
+                           (Section "KV Decomposition and Sparse Storage": a generated token is
+                           encoded like the prompt's)                                       */
     int32_t algo;       /* csr_encode_algo                                                  */
     uint32_t flags;     /* must be 0                                                        */
 } csr_encode_desc;
@@ -91,9 +103,9 @@ size_t csr_encode_workspace_bytes(const csr_encode_desc *desc);
 
 /*
  *   X    [H][T][d]  (strides as given)   in
- *   D    [H][N][d]                       in       (chunked: [H][s_n][N][d/s_n])
- *   idx  [H][T][s]  idx_dtype            out      (chunked: [H][T][s_n][s], atom numbers 0..N-1 per chunk)
- *   coef [H][T][s]  coef_dtype           out      (chunked: [H][T][s_n][s])
+ *   D    [dict_count][N][d]              in       (chunked: [dict_count][s_n][N][d/s_n])
+ *   idx  [H][T][s]  idx_dtype            out      (chunked: [H][T][s_n][s], atom numbers 0..N-1 per chunk;
+ *   coef [H][T][s]  coef_dtype           out       blocks code_stride_h elements apart)
  *   workspace: device memory, 256-byte aligned, >= csr_encode_workspace_bytes(); may be NULL
  *   when that is 0.  Contents are undefined before and after.
  */

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libcsr_hip.so")
 CSR_OK, CSR_ERR_INVALID_ARG, CSR_ERR_UNSUPPORTED, CSR_ERR_WORKSPACE, CSR_ERR_DEVICE = range(5)
 CSR_F32, CSR_F16 = 0, 1
 CSR_I32, CSR_I16 = 0, 1
-CSR_ENCODE_AUTO, CSR_ENCODE_VALU, CSR_ENCODE_MFMA = 0, 1, 2
+CSR_ENCODE_AUTO, CSR_ENCODE_VALU, CSR_ENCODE_MFMA, CSR_ENCODE_SPLIT = 0, 1, 2, 3
 
 EXPORTS = ("csr_version", "csr_last_error", "csr_code_bytes", "csr_encode_workspace_bytes",
            "csr_encode", "csr_decode_workspace_bytes", "csr_decode_attn")
@@ -27,7 +27,8 @@ class EncodeDesc(ctypes.Structure):
                 ("x_dtype", ctypes.c_int32),
                 ("dict_dtype", ctypes.c_int32), ("coef_dtype", ctypes.c_int32),
                 ("idx_dtype", ctypes.c_int32), ("x_stride_h", ctypes.c_int64),
-                ("x_stride_t", ctypes.c_int64), ("algo", ctypes.c_int32), ("flags", ctypes.c_uint32)]
+                ("x_stride_t", ctypes.c_int64), ("dict_count", ctypes.c_int32),
+                ("code_stride_h", ctypes.c_int64), ("algo", ctypes.c_int32), ("flags", ctypes.c_uint32)]
 
 
 class DecodeDesc(ctypes.Structure):
@@ -105,14 +106,17 @@ def csr_code_bytes(s, s_n=1, idx_dtype=torch.int16, coef_dtype=torch.float16):
     return int(lib().csr_code_bytes(s, s_n, _IT[idx_dtype], _DT[coef_dtype]))
 
 
-def encode_desc(X, D, s, coef_dtype, idx_dtype, algo=CSR_ENCODE_AUTO):
+def encode_desc(X, D, s, coef_dtype, idx_dtype, algo=CSR_ENCODE_AUTO, code_stride_h=0):
+    """Descriptor from tensor shapes.  D may hold fewer dictionaries than X has blocks (D.shape[0] divides
+    X.shape[0]): block h then uses dictionary h % D.shape[0]."""
     H, T, d = X.shape
     if X.stride(2) != 1:
         raise ValueError("X must be contiguous along d")
     return EncodeDesc(H=H, T=T, d=d, N=D.shape[-2], s=s, s_n=D.shape[1] if D.dim() == 4 else 1, x_dtype=_DT[X.dtype], dict_dtype=_DT[D.dtype],
                       coef_dtype=_DT[coef_dtype], idx_dtype=_IT[idx_dtype],
                       x_stride_h=X.stride(0) if H > 1 and T > 0 else 0,
-                      x_stride_t=X.stride(1) if T > 1 else 0, algo=algo, flags=0)
+                      x_stride_t=X.stride(1) if T > 1 else 0, dict_count=D.shape[0] if D.shape[0] != H else 0,
+                      code_stride_h=code_stride_h, algo=algo, flags=0)
 
 
 def csr_encode_workspace_bytes(desc):
@@ -125,21 +129,34 @@ def csr_encode_workspace_bytes(desc):
 def csr_encode(X, D, s, coef_dtype=None, idx_dtype=None, algo=CSR_ENCODE_AUTO, idx=None, coef=None,
                workspace=None):
     """Matching Pursuit encode.  X [H, T, d], D [H, N, d] on the GPU -> (idx, coef) [H, T, s].
-    Chunked: D [H, s_n, N, d / s_n] -> (idx, coef) [H, T, s_n, s], every chunk encoded on its own dictionary."""
+    Chunked: D [H, s_n, N, d / s_n] -> (idx, coef) [H, T, s_n, s], every chunk encoded on its own dictionary.
+    D may hold H' < H dictionaries (H' divides H): block h uses dictionary h % H' (blocks ordered sequence-major,
+    head-minor).  `idx` / `coef` may be views into a larger cache whose blocks are further apart (stride(0) larger
+    than one block's codes, the rest contiguous): the codes are then written in place, e.g. appended at a token
+    position."""
     _dev(X, "X"); _dev(D, "D")
-    if X.dim() != 3 or D.dim() not in (3, 4) or D.shape[0] != X.shape[0] or \
+    if X.dim() != 3 or D.dim() not in (3, 4) or D.shape[0] < 1 or X.shape[0] % D.shape[0] != 0 or \
             D.shape[-1] * (D.shape[1] if D.dim() == 4 else 1) != X.shape[2]:
-        raise ValueError("expected X [H, T, d] and D [H, N, d] or [H, s_n, N, d / s_n]")
+        raise ValueError("expected X [H, T, d] and D [H', N, d] or [H', s_n, N, d / s_n] with H' dividing H")
     D = D.contiguous()
     coef_dtype = coef_dtype or X.dtype
     idx_dtype = idx_dtype or (torch.int16 if X.dtype == torch.float16 else torch.int32)
-    desc = encode_desc(X, D, s, coef_dtype, idx_dtype, algo)
     H, T, _ = X.shape
     shape = (H, T, s) if D.dim() == 3 else (H, T, D.shape[1], s)
     if idx is None:
         idx = torch.empty(shape, dtype=idx_dtype, device=X.device)
     if coef is None:
         coef = torch.empty(shape, dtype=coef_dtype, device=X.device)
+    code_stride_h = 0
+    for name, t, dt in (("idx", idx, idx_dtype), ("coef", coef, coef_dtype)):
+        _dev(t, name)
+        if tuple(t.shape) != shape or t.dtype != dt or (T > 0 and H > 0 and not t[0].is_contiguous()):
+            raise ValueError(f"{name} must have shape {shape}, dtype {dt} and contiguous blocks")
+    if H > 1 and T > 0:
+        if idx.stride(0) != coef.stride(0):
+            raise ValueError("idx and coef must have the same distance between blocks")
+        code_stride_h = idx.stride(0)
+    desc = encode_desc(X, D, s, coef_dtype, idx_dtype, algo, code_stride_h)
     need = csr_encode_workspace_bytes(desc)
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=X.device)

@@ -25,15 +25,16 @@ bool valid_itype(int32_t v) { return v == CSR_I32 || v == CSR_I16; }
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 size_t round256(size_t v) { return (v + 255) & ~size_t(255); }
 
-// Checks everything about an encode descriptor that does not need the pointers.
-csr_status check_encode_desc(const csr_encode_desc *d, bool *use_mfma)
+// Checks everything about an encode descriptor that does not need the pointers; fills the shape part of the
+// kernels' arguments and names the kernel that will run (one of VALU, MFMA, SPLIT).
+csr_status check_encode_desc(const csr_encode_desc *d, csr::EncodeArgs *args, int *algo_out)
 {
     if (!d) return fail(CSR_ERR_INVALID_ARG, "csr_encode: descriptor is NULL");
     if (d->H < 0 || d->T < 0) return fail(CSR_ERR_INVALID_ARG, "csr_encode: H=%d T=%lld must be >= 0", d->H, (long long)d->T);
     if (d->flags != 0) return fail(CSR_ERR_INVALID_ARG, "csr_encode: flags must be 0");
     if (!valid_dtype(d->x_dtype) || !valid_dtype(d->dict_dtype) || !valid_dtype(d->coef_dtype) || !valid_itype(d->idx_dtype))
         return fail(CSR_ERR_INVALID_ARG, "csr_encode: unknown dtype / index type");
-    if (d->algo != CSR_ENCODE_AUTO && d->algo != CSR_ENCODE_VALU && d->algo != CSR_ENCODE_MFMA)
+    if (d->algo != CSR_ENCODE_AUTO && d->algo != CSR_ENCODE_VALU && d->algo != CSR_ENCODE_MFMA && d->algo != CSR_ENCODE_SPLIT)
         return fail(CSR_ERR_INVALID_ARG, "csr_encode: unknown algo %d", d->algo);
     if (d->s < 1 || d->s > 32) return fail(CSR_ERR_INVALID_ARG, "csr_encode: s=%d outside 1..32", d->s);
     if (d->N < 1) return fail(CSR_ERR_INVALID_ARG, "csr_encode: N=%d must be >= 1", d->N);
@@ -51,6 +52,8 @@ csr_status check_encode_desc(const csr_encode_desc *d, bool *use_mfma)
     if (dc != 32 && dc != 64 && dc != 128)
         return fail(CSR_ERR_UNSUPPORTED, "csr_encode: chunk length d/s_n=%d not supported (32, 64, 128)", dc);
     if ((int64_t)d->H * sn > 0x7fffffffLL) return fail(CSR_ERR_UNSUPPORTED, "csr_encode: H*s_n too large");
+    if (d->dict_count < 0 || (d->dict_count > 0 && (d->H % d->dict_count != 0)))
+        return fail(CSR_ERR_INVALID_ARG, "csr_encode: dict_count=%d must be 0 or divide H=%d", d->dict_count, d->H);
     const int64_t st = d->x_stride_t ? d->x_stride_t : d->d;
     const int64_t sh = d->x_stride_h ? d->x_stride_h : d->T * st;
     const int64_t vec = d->x_dtype == CSR_F16 ? 8 : 4;  // elements per 16-byte load
@@ -59,17 +62,41 @@ csr_status check_encode_desc(const csr_encode_desc *d, bool *use_mfma)
                     (long long)sh, (long long)st);
     if (d->T > 0 && d->H > 1 && sh < (d->T - 1) * st + d->d)
         return fail(CSR_ERR_INVALID_ARG, "csr_encode: x_stride_h=%lld makes dictionaries' vector blocks overlap", (long long)sh);
+    const int64_t code_block = d->T * sn * d->s;
+    if (d->code_stride_h < 0 || (d->code_stride_h > 0 && d->code_stride_h < code_block))
+        return fail(CSR_ERR_INVALID_ARG, "csr_encode: code_stride_h=%lld is smaller than one block's codes (%lld elements)",
+                    (long long)d->code_stride_h, (long long)code_block);
     if ((d->T + 63) / 64 * (int64_t)d->H * sn > 0x7fffffffLL)
         return fail(CSR_ERR_UNSUPPORTED, "csr_encode: H*T too large for one launch");
-    csr::EncodeArgs probe{};
-    probe.H = d->H; probe.T = d->T; probe.d = dc; probe.sn = sn; probe.N = d->N; probe.s = d->s;
-    probe.f16 = d->x_dtype == CSR_F16;
-    const bool mfma_ok = csr::encode_mfma_supported(probe);
+    csr::EncodeArgs a{};
+    a.H = d->H; a.T = d->T; a.d = dc; a.sn = sn; a.N = d->N; a.s = d->s;
+    a.x_stride_t = st; a.x_stride_h = sh;
+    a.dict_count = d->dict_count ? d->dict_count : d->H;
+    a.code_stride_h = d->code_stride_h ? d->code_stride_h : code_block;
+    a.f16 = d->x_dtype == CSR_F16;
+    a.coef16 = d->coef_dtype == CSR_F16;
+    a.idx16 = d->idx_dtype == CSR_I16;
+    const bool mfma_ok = csr::encode_mfma_supported(a), split_ok = csr::encode_split_supported(a);
     if (d->algo == CSR_ENCODE_MFMA && !mfma_ok)
         return fail(CSR_ERR_UNSUPPORTED, "csr_encode: the MFMA encoder needs fp16 inputs, chunks of 64 or 128 dimensions and N a multiple of 32 (got d/s_n=%d N=%d %s)",
-                    dc, d->N, probe.f16 ? "f16" : "f32");
-    *use_mfma = (d->algo == CSR_ENCODE_MFMA) || (d->algo == CSR_ENCODE_AUTO && mfma_ok);
+                    dc, d->N, a.f16 ? "f16" : "f32");
+    if (d->algo == CSR_ENCODE_SPLIT && !split_ok)
+        return fail(CSR_ERR_UNSUPPORTED, "csr_encode: the split encoder needs fp16 inputs, chunks of 64 or 128 dimensions, N a multiple of 32 "
+                    "and at most 128 vectors per dictionary (got d/s_n=%d N=%d %s, %lld vectors per dictionary)",
+                    dc, d->N, a.f16 ? "f16" : "f32", (long long)(a.dict_count ? (int64_t)(a.H / a.dict_count) * a.T : 0));
+    int algo = d->algo;
+    if (algo == CSR_ENCODE_AUTO) algo = split_ok ? CSR_ENCODE_SPLIT : (mfma_ok ? CSR_ENCODE_MFMA : CSR_ENCODE_VALU);
+    *args = a;
+    *algo_out = algo;
     return CSR_OK;
+}
+
+size_t encode_workspace(const csr::EncodeArgs &a, int algo)
+{
+    if (a.H == 0 || a.T == 0) return 0;
+    if (algo == CSR_ENCODE_MFMA) return csr::encode_mfma_workspace_bytes(a.dict_count * a.sn, a.T, a.N, a.s);
+    if (algo == CSR_ENCODE_SPLIT) return csr::encode_split_workspace_bytes(a);
+    return 0;
 }
 
 csr_status check_decode_desc(const csr_decode_desc *d, csr::DecodePlan *plan)
@@ -127,39 +154,33 @@ size_t csr_code_bytes(int32_t s, int32_t s_n, int32_t idx_dtype, int32_t coef_dt
 
 size_t csr_encode_workspace_bytes(const csr_encode_desc *desc)
 {
-    bool mfma = false;
-    if (check_encode_desc(desc, &mfma) != CSR_OK) return (size_t)-1;
-    if (!mfma || desc->H == 0 || desc->T == 0) return 0;
-    return csr::encode_mfma_workspace_bytes(desc->H * (desc->s_n ? desc->s_n : 1), desc->T, desc->N, desc->s);
+    csr::EncodeArgs a{};
+    int algo = 0;
+    if (check_encode_desc(desc, &a, &algo) != CSR_OK) return (size_t)-1;
+    return encode_workspace(a, algo);
 }
 
 csr_status csr_encode(const csr_encode_desc *desc, const void *X, const void *D, void *idx,
                       void *coef, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    bool mfma = false;
-    csr_status st = check_encode_desc(desc, &mfma);
+    csr::EncodeArgs a{};
+    int algo = 0;
+    csr_status st = check_encode_desc(desc, &a, &algo);
     if (st != CSR_OK) return st;
     if (desc->H == 0 || desc->T == 0) return CSR_OK;
     if (!X || !D || !idx || !coef) return fail(CSR_ERR_INVALID_ARG, "csr_encode: NULL data pointer");
     if (!aligned(X, 16) || !aligned(D, 16)) return fail(CSR_ERR_INVALID_ARG, "csr_encode: X and D must be 16-byte aligned");
     if (!aligned(idx, 4) || !aligned(coef, 4)) return fail(CSR_ERR_INVALID_ARG, "csr_encode: idx and coef must be 4-byte aligned");
-    const int sn = desc->s_n ? desc->s_n : 1;
-    const size_t need = mfma ? csr::encode_mfma_workspace_bytes(desc->H * sn, desc->T, desc->N, desc->s) : 0;
+    const size_t need = encode_workspace(a, algo);
     if (need) {
         if (!workspace || workspace_bytes < need || !aligned(workspace, 256))
             return fail(CSR_ERR_WORKSPACE, "csr_encode: workspace of %zu bytes (256-byte aligned) required, got %zu", need, workspace ? workspace_bytes : (size_t)0);
     }
-    csr::EncodeArgs a{};
     a.X = X; a.D = D; a.idx = idx; a.coef = coef;
-    a.H = desc->H; a.T = desc->T; a.d = desc->d / sn; a.sn = sn; a.N = desc->N; a.s = desc->s;
-    a.x_stride_t = desc->x_stride_t ? desc->x_stride_t : desc->d;
-    a.x_stride_h = desc->x_stride_h ? desc->x_stride_h : desc->T * a.x_stride_t;
-    a.f16 = desc->x_dtype == CSR_F16;
-    a.coef16 = desc->coef_dtype == CSR_F16;
-    a.idx16 = desc->idx_dtype == CSR_I16;
     a.workspace = workspace;
     a.stream = static_cast<hipStream_t>(hip_stream);
-    const hipError_t e = mfma ? csr::launch_encode_mfma(a) : csr::launch_encode_valu(a);
+    const hipError_t e = algo == CSR_ENCODE_MFMA ? csr::launch_encode_mfma(a)
+                         : algo == CSR_ENCODE_SPLIT ? csr::launch_encode_split(a) : csr::launch_encode_valu(a);
     if (e != hipSuccess) return fail(CSR_ERR_DEVICE, "csr_encode: %s", hipGetErrorString(e));
     return CSR_OK;
 }

@@ -24,6 +24,8 @@ struct EncodeArgs {
     int32_t d, N, s;                 // d = length of one chunk (the vector's length if sn == 1)
     int32_t sn;                      // chunks per vector (>= 1); chunk c of head h uses dictionary h * sn + c
     int64_t x_stride_h, x_stride_t;  // elements, already defaulted
+    int32_t dict_count;              // block h uses dictionary h % dict_count (already defaulted to H)
+    int64_t code_stride_h;           // elements between blocks' codes (already defaulted)
     bool f16;                        // X and D are fp16 (else fp32)
     bool coef16, idx16;
     void *workspace;
@@ -35,8 +37,14 @@ hipError_t launch_encode_valu(const EncodeArgs &a);
 
 // fp16 matrix-core encoder: chunks of 64 or 128 dimensions, fp16 inputs.
 bool encode_mfma_supported(const EncodeArgs &a);
-size_t encode_mfma_workspace_bytes(int32_t H, int64_t T, int32_t N, int32_t s);
+size_t encode_mfma_workspace_bytes(int32_t n_dicts, int64_t T, int32_t N, int32_t s);
 hipError_t launch_encode_mfma(const EncodeArgs &a);
+
+// fp16 matrix-core encoder for few vectors per dictionary (a decoding step): atoms split over workgroups,
+// one launch per iteration.
+bool encode_split_supported(const EncodeArgs &a);
+size_t encode_split_workspace_bytes(const EncodeArgs &a);
+hipError_t launch_encode_split(const EncodeArgs &a);
 
 // ---- decode ---------------------------------------------------------------------------------
 struct DecodePlan {

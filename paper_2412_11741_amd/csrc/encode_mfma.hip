@@ -279,8 +279,8 @@ template <int DC>
 __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
     const __half *__restrict__ X, const __half *__restrict__ Dict, void *__restrict__ idx_out,
     void *__restrict__ coef_out, const float *__restrict__ dnorm, int64_t T, int32_t N, int32_t s, int32_t sn,
-    int64_t x_stride_h, int64_t x_stride_t, int32_t tiles_per_h, int32_t n_groups, int32_t idx16, int32_t coef16,
-    uint32_t code_mask, int32_t first_round)
+    int64_t x_stride_h, int64_t x_stride_t, int32_t dict_count, int64_t code_stride_h, int32_t tiles_per_h,
+    int32_t n_groups, int32_t idx16, int32_t coef16, uint32_t code_mask, int32_t first_round)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     using S = Shape<DC>;
@@ -296,11 +296,13 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
     // that workgroups sharing a dictionary share an L2.
     int work = blockIdx.x;
     if ((n_groups & 7) == 0) work = (blockIdx.x & 7) * (n_groups >> 3) + (blockIdx.x >> 3);
-    // "head" hv = h * sn + ch is chunk ch of head h: a vector of DC dimensions on dictionary hv
+    // "head" hv = h * sn + ch is chunk ch of vector block h: a vector of DC dimensions on chunk ch of
+    // dictionary h % dict_count
     const int hv = work / tiles_per_h;
     const int tile_wg = work - hv * tiles_per_h;
     const int h = hv / sn, ch = hv - h * sn;
-    const __half *Dh = Dict + (int64_t)hv * N * DC;
+    const int dct = (h % dict_count) * sn + ch;
+    const __half *Dh = Dict + (int64_t)dct * N * DC;
     const int ntiles = N >> 5;
     const int nstages = (N + kStageAtoms - 1) / kStageAtoms;
     const int nstages_full = N / kStageAtoms;
@@ -327,7 +329,7 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
 
     float dmax = 0.0f;
 #pragma unroll
-    for (int i = 0; i < kNormSlices; ++i) dmax = fmaxf(dmax, dnorm[hv * kNormSlices + i]);
+    for (int i = 0; i < kNormSlices; ++i) dmax = fmaxf(dmax, dnorm[dct * kNormSlices + i]);
     // ~code_mask in a vector register, so that packing value and tile code is one instruction with
     // the code as its only scalar operand
     uint32_t keep_mask;
@@ -605,7 +607,7 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
             rn2[bi] = r2;
             delta[bi] = 2.0f * dmax * (sqrtf(lo2) + kGammaAcc * sqrtf(r2));
             if (valid[bi]) {
-                const int64_t o = (((int64_t)h * T + tok[bi]) * sn + ch) * s + g;
+                const int64_t o = (int64_t)h * code_stride_h + (tok[bi] * sn + ch) * s + g;
                 if (hf == 0) {
                     if (idx16) reinterpret_cast<uint16_t *>(idx_out)[o] = (uint16_t)best_n[bi];
                     else reinterpret_cast<int32_t *>(idx_out)[o] = best_n[bi];
@@ -664,13 +666,13 @@ hipError_t launch_encode_mfma_t(const EncodeArgs &a)
     }
     const int32_t first_round = groups > n_cus[dev] ? 2 * n_cus[dev] : 0;
 
-    hipLaunchKernelGGL(dict_norm_kernel<DC>, dim3((unsigned)(a.H * a.sn), kNormSlices), dim3(256), 0, a.stream,
+    hipLaunchKernelGGL(dict_norm_kernel<DC>, dim3((unsigned)(a.dict_count * a.sn), kNormSlices), dim3(256), 0, a.stream,
                        (const __half *)a.D, dnorm, a.N);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(encode_mfma_kernel<DC>, dim3((unsigned)groups), dim3(kThreads), kLdsBytes, a.stream,
                        (const __half *)a.X, (const __half *)a.D, a.idx, a.coef, dnorm, a.T, a.N, a.s, a.sn, a.x_stride_h,
-                       a.x_stride_t, (int32_t)tiles, (int32_t)groups, (int32_t)a.idx16, (int32_t)a.coef16, code_mask,
+                       a.x_stride_t, a.dict_count, a.code_stride_h, (int32_t)tiles, (int32_t)groups, (int32_t)a.idx16, (int32_t)a.coef16, code_mask,
                        first_round);
     return hipGetLastError();
 }

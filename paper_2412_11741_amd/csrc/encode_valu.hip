@@ -28,7 +28,8 @@ template <int D_, typename TE, int W>
 __global__ __launch_bounds__(64 * W) void encode_valu_kernel(
     const TE *__restrict__ X, const TE *__restrict__ Dict, void *__restrict__ idx_out,
     void *__restrict__ coef_out, int64_t T, int32_t N, int32_t s, int64_t x_stride_h,
-    int64_t x_stride_t, int32_t tiles_per_h, int32_t sn, int32_t idx16, int32_t coef16)
+    int64_t x_stride_t, int32_t tiles_per_h, int32_t sn, int32_t dict_count, int64_t code_stride_h, int32_t idx16,
+    int32_t coef16)
 {
     __shared__ float s_abs[2][W][64];
     __shared__ float s_c[2][W][64];
@@ -36,7 +37,8 @@ __global__ __launch_bounds__(64 * W) void encode_valu_kernel(
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    // chunked vectors: "head" hv = h * sn + c is chunk c of head h, a vector of D_ dimensions of its own
+    // chunked vectors: "head" hv = h * sn + c is chunk c of block h, a vector of D_ dimensions of its own, on
+    // chunk c of dictionary h % dict_count
     const int hv = blockIdx.x / tiles_per_h;
     const int tile = blockIdx.x - hv * tiles_per_h;
     const int h = hv / sn, ch = hv - h * sn;
@@ -59,7 +61,7 @@ __global__ __launch_bounds__(64 * W) void encode_valu_kernel(
     const int slice = (N + W - 1) / W;
     const int n0 = wave * slice;
     const int n1 = min(N, n0 + slice);
-    const TE *Dh = Dict + (int64_t)hv * N * D_;
+    const TE *Dh = Dict + ((int64_t)(h % dict_count) * sn + ch) * N * D_;
 
     for (int g = 0; g < s; ++g) {
         float best = -1.0f, bc = 0.0f;
@@ -101,7 +103,7 @@ __global__ __launch_bounds__(64 * W) void encode_valu_kernel(
             }
         }
         if (wave == 0 && valid) {
-            const int64_t o = (((int64_t)h * T + t) * sn + ch) * s + g;
+            const int64_t o = (int64_t)h * code_stride_h + (t * sn + ch) * s + g;
             if (idx16) reinterpret_cast<uint16_t *>(idx_out)[o] = (uint16_t)wi;
             else reinterpret_cast<int32_t *>(idx_out)[o] = wi;
             if (coef16) reinterpret_cast<__half *>(coef_out)[o] = __float2half_rn(wc);
@@ -123,8 +125,8 @@ hipError_t launch_valu_t(const EncodeArgs &a)
 #define CSR_LAUNCH_VALU(W)                                                                      \
     hipLaunchKernelGGL((encode_valu_kernel<D_, TE, W>), grid, dim3(64 * W), 0, a.stream,         \
                        (const TE *)a.X, (const TE *)a.D, a.idx, a.coef, a.T, a.N, a.s,          \
-                       a.x_stride_h, a.x_stride_t, (int32_t)tiles, a.sn, (int32_t)a.idx16,      \
-                       (int32_t)a.coef16)
+                       a.x_stride_h, a.x_stride_t, (int32_t)tiles, a.sn, a.dict_count, a.code_stride_h, \
+                       (int32_t)a.idx16, (int32_t)a.coef16)
     // (8 waves = 2 per SIMD leaves each lane the 128+ registers its residual needs.)
     if (groups >= 1024) CSR_LAUNCH_VALU(4);
     else CSR_LAUNCH_VALU(8);

@@ -37,7 +37,8 @@ def test_code_bytes_follow_the_papers_accounting():
 
 def _enc(**kw):
     base = dict(H=2, T=100, d=128, N=256, s=8, x_dtype=B.CSR_F16, dict_dtype=B.CSR_F16,
-                coef_dtype=B.CSR_F16, idx_dtype=B.CSR_I16, x_stride_h=0, x_stride_t=0, algo=0, flags=0)
+                coef_dtype=B.CSR_F16, idx_dtype=B.CSR_I16, x_stride_h=0, x_stride_t=0, dict_count=0,
+                code_stride_h=0, algo=0, flags=0)
     base.update(kw)
     return B.EncodeDesc(**base)
 
@@ -54,6 +55,9 @@ def _enc(**kw):
     (dict(d=32, algo=B.CSR_ENCODE_MFMA), B.CSR_ERR_UNSUPPORTED),
     (dict(s_n=3), B.CSR_ERR_INVALID_ARG), (dict(s_n=16), B.CSR_ERR_INVALID_ARG), (dict(s_n=-1), B.CSR_ERR_INVALID_ARG),
     (dict(s_n=8), B.CSR_ERR_UNSUPPORTED),                              # chunks of 16 dimensions
+    (dict(dict_count=-1), B.CSR_ERR_INVALID_ARG), (dict(H=6, dict_count=4), B.CSR_ERR_INVALID_ARG),
+    (dict(code_stride_h=-8), B.CSR_ERR_INVALID_ARG), (dict(code_stride_h=792), B.CSR_ERR_INVALID_ARG),   # < T*s = 800
+    (dict(T=200, algo=B.CSR_ENCODE_SPLIT), B.CSR_ERR_UNSUPPORTED), (dict(d=32, T=1, algo=B.CSR_ENCODE_SPLIT), B.CSR_ERR_UNSUPPORTED),
     (dict(s_n=4, algo=B.CSR_ENCODE_MFMA), B.CSR_ERR_UNSUPPORTED),      # chunks of 32: vector-ALU encoder only
     (dict(x_dtype=B.CSR_F32, dict_dtype=B.CSR_F32, algo=B.CSR_ENCODE_MFMA), B.CSR_ERR_UNSUPPORTED),
 ])
@@ -68,11 +72,26 @@ def test_encode_rejects_bad_descriptors_before_launch(kw, status):
 
 def test_encode_chunk_count_scales_the_workspace_and_zero_means_whole_vectors():
     lib = csr.lib()
-    size = lambda **kw: lib.csr_encode_workspace_bytes(ctypes.byref(_enc(**kw)))
+    size = lambda **kw: lib.csr_encode_workspace_bytes(ctypes.byref(_enc(algo=B.CSR_ENCODE_MFMA, **kw)))
     assert size(s_n=0) == size(s_n=1) == size() > 0
     assert size(H=64, s_n=2) == size(H=128) and size(H=64, s_n=2) > size(H=64)   # one norm record per dictionary
-    assert size(s_n=4) == 0                                                    # the vector-ALU encoder needs none
     assert size(d=64) > 0 and size(d=256, s_n=2) > 0                           # fp16 chunks of 64 / 128: matrix cores
+    assert size(H=64, dict_count=8) == size(H=8)                               # shared dictionaries: fewer records
+    assert lib.csr_encode_workspace_bytes(ctypes.byref(_enc(s_n=4))) == 0      # chunks of 32: the vector-ALU encoder needs none
+
+
+def test_encode_kernel_choice_follows_the_vectors_per_dictionary():
+    lib = csr.lib()
+    size = lambda **kw: lib.csr_encode_workspace_bytes(ctypes.byref(_enc(**kw)))
+    # few vectors per dictionary (a decoding step): AUTO is the split encoder, whose scratch holds residuals
+    assert size(T=1) == size(T=1, algo=B.CSR_ENCODE_SPLIT) != size(T=1, algo=B.CSR_ENCODE_MFMA)
+    assert size(T=128) == size(T=128, algo=B.CSR_ENCODE_SPLIT)
+    assert size(T=129) == size(T=129, algo=B.CSR_ENCODE_MFMA)
+    # 16 blocks on 2 dictionaries: 8 x 20 = 160 vectors per dictionary, too many for the split encoder
+    assert size(H=16, T=20, dict_count=2) == size(H=16, T=20, dict_count=2, algo=B.CSR_ENCODE_MFMA)
+    assert size(H=16, T=20, dict_count=2, algo=B.CSR_ENCODE_SPLIT) == ctypes.c_size_t(-1).value
+    assert size(H=16, T=20, dict_count=4) == size(H=16, T=20, dict_count=4, algo=B.CSR_ENCODE_SPLIT)
+    assert size(T=1, x_dtype=B.CSR_F32, dict_dtype=B.CSR_F32) == 0            # fp32: vector-ALU encoder
 
 
 def test_encode_null_and_misaligned_pointers_and_noop_sizes():

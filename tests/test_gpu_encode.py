@@ -16,7 +16,8 @@ pytestmark = pytest.mark.gpu
 # and 1e-3 covers a one-ulp flip at a rounding boundary.
 TOL = 1e-3
 
-ALGOS = {"valu": csr.CSR_ENCODE_VALU, "mfma": csr.CSR_ENCODE_MFMA}
+ALGOS = {"valu": csr.CSR_ENCODE_VALU, "mfma": csr.CSR_ENCODE_MFMA, "split": csr.CSR_ENCODE_SPLIT}
+SPLIT_MAX = 128   # vectors per dictionary the split encoder takes
 
 
 def _gpu_encode(X, D, s, algo, coef_dtype=None, idx_dtype=None):
@@ -90,21 +91,21 @@ def test_valu_smaller_head_chunks(d, dtype):
     _assert_ok(_compare(X, D, s, idx, coef))
 
 
-@pytest.mark.parametrize("algo", ["valu", "mfma"])
+@pytest.mark.parametrize("algo", ["valu", "mfma", "split"])
 @pytest.mark.parametrize("s", [1, 16, 32])
 def test_iteration_counts(algo, s):
-    H, T, N, d = 1, 192, 512, 128
+    H, T, N, d = 1, 192 if algo != "split" else 70, 512, 128
     D = synth.dictionary(4, "dict_k", H, N, d, "f16")
     X = synth.vectors(4, "keys", H, T, d, "f16", outliers=8)
     idx, coef = _gpu_encode(X, D, s, ALGOS[algo])
     _assert_ok(_compare(X, D, s, idx, coef))
 
 
-@pytest.mark.parametrize("algo", ["valu", "mfma"])
+@pytest.mark.parametrize("algo", ["valu", "mfma", "split"])
 def test_orthonormal_dictionary_recovers_top_s_coordinates(algo):
     # Identity atoms (padded with a second, rotated orthonormal basis so N is a multiple of 32 x 8):
     # with the identity alone the codes are the s largest |x_k| in order.
-    d, s, T = 128, 8, 256
+    d, s, T = 128, 8, 256 if algo != "split" else SPLIT_MAX
     D = np.eye(d, dtype=np.float16)[None]
     X = synth.vectors(5, "keys", 1, T, d, "f16", outliers=4)
     # make magnitudes distinct so the order is unique
@@ -115,7 +116,7 @@ def test_orthonormal_dictionary_recovers_top_s_coordinates(algo):
     assert np.array_equal(coef[0], np.take_along_axis(X[0], order, axis=1))
 
 
-@pytest.mark.parametrize("algo", ["valu", "mfma"])
+@pytest.mark.parametrize("algo", ["valu", "mfma", "split"])
 def test_degenerate_inputs_zero_vectors_scaled_atoms_single_vector(algo):
     H, N, d, s = 1, 256, 128, 4
     D = synth.dictionary(6, "dict_k", H, N, d, "f16")
@@ -277,9 +278,11 @@ def _adversarial_cases():
 
 @pytest.mark.parametrize("name", ["atom norms 0.25 .. 2", "duplicated atoms", "dynamic range",
                                   "sparse combinations of atoms", "constant and one-hot vectors"])
-@pytest.mark.parametrize("algo", ["valu", "mfma"])
+@pytest.mark.parametrize("algo", ["valu", "mfma", "split"])
 def test_adversarial_inputs(algo, name):
     D, X = _adversarial_cases()[name]
+    if algo == "split":
+        X = X[:SPLIT_MAX]
     D16, X16 = D.astype(np.float16)[None], X.astype(np.float16)[None]
     s = 8
     idx, coef = _gpu_encode(X16, D16, s, ALGOS[algo])
@@ -349,3 +352,72 @@ def test_chunked_mfma_and_valu_agree_and_strided_input():
     same = (im == iv).all(dim=-1).float().mean().item()
     assert same > 0.999          # the two encoders may part only at ties
     _assert_ok(_compare_chunked(X, D, s, im.cpu().numpy().view(np.uint16).astype(np.int32), cm.cpu().numpy()))
+
+
+# --- few vectors per dictionary: the tokens of a decoding step (Section "KV Decomposition and Sparse Storage") ---
+
+@pytest.mark.parametrize("H,T,N,d,sn,s,dicts", [
+    (8, 1, 4096, 128, 1, 8, 8),       # one new token for each of 8 heads
+    (16, 1, 4096, 128, 1, 8, 4),      # 4 sequences x 4 heads sharing the heads' dictionaries
+    (3, 33, 1024, 128, 1, 6, 3),      # two blocks of 32 vectors, the second with one
+    (2, 128, 512, 128, 1, 4, 2),      # the most vectors it takes
+    (24, 5, 2080, 128, 1, 5, 2),      # 60 vectors per dictionary, 65 tiles over uneven slices
+    (2, 7, 96, 128, 1, 8, 2),         # three tiles: fewer than waves
+    (4, 2, 1024, 128, 2, 4, 2),       # values in two chunks of 64
+    (6, 3, 256, 64, 1, 8, 3),         # 64-dimensional vectors
+])
+def test_split_encoder_parity(H, T, N, d, sn, s, dicts):
+    dc = d // sn
+    D = synth.dictionary(41, "dict_v", dicts * sn, N, dc, "f16").reshape(dicts, sn, N, dc)
+    X = synth.vectors(41, "values", H, T, d, "f16", outliers=4)
+    Dg = torch.from_numpy(D if sn > 1 else D[:, 0]).cuda()
+    idx, coef = csr.csr_encode(torch.from_numpy(X).cuda(), Dg, s, algo=csr.CSR_ENCODE_SPLIT)
+    torch.cuda.synchronize()
+    idx, coef = idx.cpu().numpy().reshape(H, T, sn, s), coef.cpu().numpy().reshape(H, T, sn, s)
+    D_blocks = np.stack([D[h % dicts] for h in range(H)])               # block h uses dictionary h % dicts
+    _assert_ok(_compare_chunked(X, D_blocks, s, idx.view(np.uint16).astype(np.int32), coef))
+
+
+def test_auto_picks_the_split_encoder_for_a_decoding_step_and_storage_types_do_not_move_indices():
+    H, T, N, d, s = 8, 1, 1024, 128, 8
+    D = synth.dictionary(42, "dict_k", H, N, d, "f16")
+    X = synth.vectors(42, "keys", H, T, d, "f16", outliers=8)
+    Xg, Dg = torch.from_numpy(X).cuda(), torch.from_numpy(D).cuda()
+    ia, ca = csr.csr_encode(Xg, Dg, s)
+    isp, csp = csr.csr_encode(Xg, Dg, s, algo=csr.CSR_ENCODE_SPLIT)
+    i32, c32 = csr.csr_encode(Xg, Dg, s, algo=csr.CSR_ENCODE_SPLIT, coef_dtype=torch.float32, idx_dtype=torch.int32)
+    im, cm = csr.csr_encode(Xg, Dg, s, algo=csr.CSR_ENCODE_MFMA)
+    torch.cuda.synchronize()
+    assert torch.equal(ia, isp) and torch.equal(ca, csp)                 # same kernel, same bits
+    assert np.array_equal(isp.cpu().numpy().view(np.uint16).astype(np.int32), i32.cpu().numpy())
+    assert np.array_equal(csp.cpu().numpy(), c32.cpu().numpy().astype(np.float16))
+    assert (im == isp).all(dim=-1).float().mean().item() >= 0.75         # the encoders may part only at ties
+    _assert_ok(_compare(X, D, s, i32.cpu().numpy(), c32.cpu().numpy()))
+
+
+@pytest.mark.parametrize("algo", ["split", "mfma", "valu"])
+def test_append_in_place_into_a_cache_of_codes(algo):
+    # the codes of one new token per (sequence, head) land at row `pos` of a cache [blocks][T_max][s]
+    B, Hkv, T_max, N, d, s, pos = 3, 4, 50, 512, 128, 8, 17
+    D = synth.dictionary(43, "dict_k", Hkv, N, d, "f16")
+    X = synth.vectors(43, "keys", B * Hkv, 1, d, "f16", outliers=8)
+    Xg, Dg = torch.from_numpy(X).cuda(), torch.from_numpy(D).cuda()
+    cache_i = torch.full((B * Hkv, T_max, s), -7, dtype=torch.int16, device="cuda")
+    cache_c = torch.full((B * Hkv, T_max, s), 123.0, dtype=torch.float16, device="cuda")
+    csr.csr_encode(Xg, Dg, s, algo=ALGOS[algo], idx=cache_i[:, pos:pos + 1], coef=cache_c[:, pos:pos + 1])
+    i_ref, c_ref = csr.csr_encode(Xg, Dg, s, algo=ALGOS[algo])
+    torch.cuda.synchronize()
+    assert torch.equal(cache_i[:, pos:pos + 1], i_ref) and torch.equal(cache_c[:, pos:pos + 1], c_ref)
+    keep = torch.ones(T_max, dtype=torch.bool, device="cuda"); keep[pos] = False
+    assert (cache_i[:, keep] == -7).all() and (cache_c[:, keep] == 123.0).all()    # neighbours untouched
+    D_blocks = np.stack([D[h % Hkv] for h in range(B * Hkv)])
+    _assert_ok(_compare(X, D_blocks, s, i_ref.cpu().numpy(), c_ref.cpu().numpy()))
+
+
+def test_split_results_do_not_depend_on_the_run():
+    H, T, N, d, s = 16, 4, 4096, 128, 8
+    D = synth.dictionary(44, "dict_k", H, N, d, "f16")
+    X = synth.vectors(44, "keys", H, T, d, "f16", outliers=8)
+    a = _gpu_encode(X, D, s, csr.CSR_ENCODE_SPLIT)
+    b = _gpu_encode(X, D, s, csr.CSR_ENCODE_SPLIT)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
