@@ -11,6 +11,7 @@ call alone at the long-context and GQA shapes (random codes drawn on the GPU, ca
 the code streams rather than the dictionaries dominate the traffic.  `chunked_step` is the same step in the
 storage layout of the paper's experiments ("CSR-8": keys whole with s = 8, values in s_n = 2 chunks of 64
 dimensions with s = 4 each), which runs the 64-dimensional variants of the encoder and the chunk-aware decode.
+`decode_step` is one decoding step: the new token's codes appended in place, then attention over the cache.
 
 All kernels run on PyTorch's current stream, and the HIP events that time them (torch.cuda.Event)
 are recorded on that same stream.
@@ -138,6 +139,67 @@ def chunked_step(csr, synth, w, dev, steps):
             "decode_gbs_warm": round(dec_bytes / (d_ms * 1e-3) / 1e9, 1)}
 
 
+def decode_step(csr, synth, w, dev, steps):
+    """One decoding step at the workload's shape: the new token's key and value of every (sequence, KV head) are
+    encoded straight into the next row of the code cache (csr_encode picks its few-vectors kernel), then
+    csr_decode_attn runs over the grown cache.  The cache holds random codes (the step's cost does not depend on
+    their values); T - 1 tokens are cached, the step appends token T - 1."""
+    import numpy as np
+    import torch
+    B, Hkv, Hq, T, N, d, s = w.batch, w.hkv, w.hq, w.tokens, w.n_atoms, w.d, w.s
+    g = lambda a: torch.from_numpy(a).to(dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1)
+    DK, DV = g(synth.dictionary(0, "dict_k", Hkv, N, d, "f16")), g(synth.dictionary(0, "dict_v", Hkv, N, d, "f16"))
+    q = g(synth.queries(0, B, Hq, d, "f16"))
+    XK = g(synth.vectors(1, "keys", B * Hkv, 1, d, "f16", outliers=w.key_outliers))
+    XV = g(synth.vectors(1, "values", B * Hkv, 1, d, "f16"))
+    ri = lambda: torch.randint(0, N, (B * Hkv, T, s), device=dev, generator=gen, dtype=torch.int32).to(torch.int16)
+    rc = lambda: (torch.randn(B * Hkv, T, s, device=dev, generator=gen) * 3).half()
+    # one cache tensor, keys' blocks first: with one sequence, block j of the stacked tensor uses dictionary j, so
+    # a single csr_encode call appends the keys' and the values' codes
+    icache = torch.cat([ri(), ri()])
+    ccache = torch.cat([rc(), rc()])
+    nkv = B * Hkv
+    iK, cK, iV, cV = icache[:nkv], ccache[:nkv], icache[nkv:], ccache[nkv:]
+    XKV, DKV = torch.cat([XK, XV]), torch.cat([DK, DV])
+    out = torch.empty((B, Hq, d), dtype=torch.float16, device=dev)
+    lens = torch.full((B,), T, dtype=torch.int32, device=dev)
+    row = lambda t: t[:, T - 1:T]
+    ews = csr.csr_encode_workspace_bytes(csr.encode_desc(XKV, DKV, s, torch.float16, torch.int16, code_stride_h=T * s))
+    wsE = torch.empty(max(ews, 256), dtype=torch.uint8, device=dev)
+    v = lambda t: t.view(B, Hkv, T, s)
+    wsD = torch.empty(max(csr.csr_decode_workspace_bytes(csr.decode_desc(q, DK, v(iK), v(cK), v(iV))), 256),
+                      dtype=torch.uint8, device=dev)
+
+    def append():
+        if B == 1:
+            csr.csr_encode(XKV, DKV, s, idx=row(icache), coef=row(ccache), workspace=wsE)
+        else:
+            csr.csr_encode(XK, DK, s, idx=row(iK), coef=row(cK), workspace=wsE)
+            csr.csr_encode(XV, DV, s, idx=row(iV), coef=row(cV), workspace=wsE)
+
+    def attend():
+        csr.csr_decode_attn(q, DK, v(iK), v(cK), DV, v(iV), v(cV), seq_lens=lens, out=out, workspace=wsD)
+
+    for _ in range(2):
+        append(); attend()
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    for i in range(steps):
+        ev[i][0].record(); append(); ev[i][1].record(); attend(); ev[i][2].record()
+    torch.cuda.synchronize()
+    a_ms, d_ms = (sum(e[j].elapsed_time(e[j + 1]) for e in ev) / steps for j in range(2))
+    sweep_bytes = 2 * Hkv * N * d * 2 * s     # every iteration reads every dictionary once
+    return {"append_vectors": 2 * B * Hkv, "append_ms": round(a_ms, 4), "attend_ms_warm": round(d_ms, 5),
+            "step_ms": round(a_ms + d_ms, 4), "tokens_per_s": round(B / ((a_ms + d_ms) * 1e-3), 1),
+            "roofline_append": {"kernel": "csr_encode (split), s + 1 launches per call", "bound": "hbm",
+                                "achieved": round(sweep_bytes / (a_ms * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
+                                "unit": "GB/s", "frac": round(sweep_bytes / (a_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 5),
+                                "bytes_per_step": sweep_bytes,
+                                "note": "s sweeps over all dictionaries; re-reads may be served by the Infinity Cache"}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -150,6 +212,8 @@ def main():
                     help="skip the decode-only lines at the long-context and GQA shapes")
     ap.add_argument("--no-chunked", action="store_true",
                     help="skip the step in the chunked (s_n = 2 values) storage layout")
+    ap.add_argument("--no-decode-step", action="store_true",
+                    help="skip the decoding step (append one token's codes, then attend)")
     ap.add_argument("--only-extra-decode", action="store_true",
                     help="run only the decode-only lines (for profiling them apart from the main workload)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -311,6 +375,10 @@ def main():
     # ---- the same layer in the chunked storage layout of the paper's experiments --------------------------
     if not args.no_chunked and w.dtype == "f16" and d == 128:
         result["chunked_step"] = chunked_step(csr, synth, w, dev, args.steps)
+
+    # ---- one decoding step: append the new token's codes in place, attend over the grown cache ------------
+    if not args.no_decode_step and w.dtype == "f16":
+        result["decode_step"] = decode_step(csr, synth, w, dev, args.steps)
 
     # ---- CPU oracle on a bounded sample of the same workload ---------------------------------------
     if not args.no_cpu_baseline:

@@ -295,3 +295,38 @@ def test_end_to_end_in_the_experiments_layout_keys_whole_values_in_two_chunks():
     iKh, cKh, iVh, cVh = (t.cpu().numpy()[None] for t in (iK, cK, iV, cV))
     ref = oracle.decode_attn_chunked(q, DK[:, None], _u16(iKh)[:, :, :, None], cKh[:, :, :, None], DV, _u16(iVh), cVh)
     _check(out.cpu().numpy(), ref, TOL_F16_OUT, "encode -> decode, CSR-8 layout")
+
+
+def test_decoding_steps_append_codes_in_place_and_attend_over_the_grown_cache():
+    # prefill T0 tokens, then three decoding steps: every step encodes one new key and value per
+    # (sequence, head) straight into row `len` of the code cache and attends over len + 1 tokens
+    B, Hkv, G, T0, T_max, N, d, s = 2, 2, 2, 300, 320, 512, 128, 8
+    DK = synth.dictionary(25, "dict_k", Hkv, N, d, "f16")
+    DV = synth.dictionary(25, "dict_v", Hkv, N, d, "f16")
+    XK = synth.vectors(25, "keys", B * Hkv, T_max, d, "f16", outliers=8)
+    XV = synth.vectors(25, "values", B * Hkv, T_max, d, "f16")
+    g = lambda a: torch.from_numpy(a).cuda()
+    XKg, XVg, DKg, DVg = g(XK), g(XV), g(DK), g(DV)
+    cache = {n: torch.zeros((B * Hkv, T_max, s), dtype=dt, device="cuda")
+             for n, dt in (("iK", torch.int16), ("cK", torch.float16), ("iV", torch.int16), ("cV", torch.float16))}
+    csr.csr_encode(XKg[:, :T0], DKg, s, idx=cache["iK"][:, :T0], coef=cache["cK"][:, :T0])
+    csr.csr_encode(XVg[:, :T0], DVg, s, idx=cache["iV"][:, :T0], coef=cache["cV"][:, :T0])
+    v = lambda t: t.view(B, Hkv, T_max, s)
+    for step in range(3):
+        pos = T0 + step
+        q = synth.queries(25 + step, B, Hkv * G, d, "f16")
+        csr.csr_encode(XKg[:, pos:pos + 1], DKg, s, idx=cache["iK"][:, pos:pos + 1], coef=cache["cK"][:, pos:pos + 1])
+        csr.csr_encode(XVg[:, pos:pos + 1], DVg, s, idx=cache["iV"][:, pos:pos + 1], coef=cache["cV"][:, pos:pos + 1])
+        lens = torch.full((B,), pos + 1, dtype=torch.int32, device="cuda")
+        out = csr.csr_decode_attn(g(q), DKg, v(cache["iK"]), v(cache["cK"]), DVg, v(cache["iV"]), v(cache["cV"]),
+                                  seq_lens=lens)
+        torch.cuda.synchronize()
+        h = {n: v(t).cpu().numpy() for n, t in cache.items()}
+        ref = oracle.decode_attn(q, DK, h["iK"], h["cK"], DV, h["iV"], h["cV"], seq_lens=[pos + 1] * B)
+        _check(out.cpu().numpy(), ref, TOL_F16_OUT, f"decoding step {step}")
+    # the appended rows are what encoding the whole sequence at once gives (the encoders may part at ties only)
+    i_all, _ = csr.csr_encode(XKg[:, :T0 + 3], DKg, s, algo=csr.CSR_ENCODE_MFMA)
+    torch.cuda.synchronize()
+    same = (i_all[:, T0:] == cache["iK"][:, T0:T0 + 3]).all(dim=-1).float().mean().item()
+    assert same >= 0.75, same
+    assert (cache["iK"][:, T0 + 3:] == 0).all()          # rows past the last appended one were never written
