@@ -330,3 +330,12 @@ def test_decoding_steps_append_codes_in_place_and_attend_over_the_grown_cache():
     same = (i_all[:, T0:] == cache["iK"][:, T0:T0 + 3]).all(dim=-1).float().mean().item()
     assert same >= 0.75, same
     assert (cache["iK"][:, T0 + 3:] == 0).all()          # rows past the last appended one were never written
+
+
+def test_chunked_values_full_layer_all_heads():
+    # bench.py's chunked_step decode call: 32 heads, 4096 tokens, keys s = 8 whole, values s = 4 in two chunks
+    w = synth.WORKLOADS["llama7b_layer"]
+    q, DK, iK, cK, DV, iV, cV = _chunked_case(26, w.batch, w.hq, w.hkv, w.tokens, w.n_atoms, 1, 8, 2, 4)
+    out = _run(q, DK[:, 0], iK[:, :, :, 0], cK[:, :, :, 0], DV, iV, cV)
+    ref = oracle.decode_attn_chunked(q, DK, _u16(iK), cK, DV, _u16(iV), cV)
+    _check(out, ref, TOL_F16_OUT, "llama7b layer, values in two chunks, all heads")

@@ -421,3 +421,34 @@ def test_split_results_do_not_depend_on_the_run():
     a = _gpu_encode(X, D, s, csr.CSR_ENCODE_SPLIT)
     b = _gpu_encode(X, D, s, csr.CSR_ENCODE_SPLIT)
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def test_chunked_values_full_size_sampled():
+    # bench.py's chunked_step value launch: 32 heads x 4096 vectors, two chunks of 64, s = 4, N = 4096 per chunk
+    w = synth.WORKLOADS["llama7b_layer"]
+    sn, s = 2, 4
+    D = synth.dictionary(0, "dict_v", w.hkv * sn, w.n_atoms, w.d // sn, "f16").reshape(w.hkv, sn, w.n_atoms, w.d // sn)
+    X = synth.vectors(0, "values", w.hkv, w.tokens, w.d, "f16")
+    idx, coef = _gpu_encode(X, D, s, csr.CSR_ENCODE_AUTO)
+    assert idx.shape == (w.hkv, w.tokens, sn, s) and int(idx.view(np.uint16).max()) < w.n_atoms
+    rows = np.unique(np.concatenate([[0, 255, 256, w.tokens - 1], synth.stream(0, "misc", 4).integers(0, w.tokens, 12)]))
+    _assert_ok(_compare_chunked(X[:, rows], D, s, idx[:, rows].view(np.uint16).astype(np.int32), coef[:, rows]))
+
+
+def test_decoding_step_full_size_one_token_for_every_head_of_a_layer():
+    # bench.py's decode_step append: keys' and values' new vectors of 32 heads stacked, 64 dictionaries, one call
+    w = synth.WORKLOADS["llama7b_layer"]
+    D = np.concatenate([synth.dictionary(0, "dict_k", w.hkv, w.n_atoms, w.d, "f16"),
+                        synth.dictionary(0, "dict_v", w.hkv, w.n_atoms, w.d, "f16")])
+    X = np.concatenate([synth.vectors(1, "keys", w.hkv, 1, w.d, "f16", outliers=w.key_outliers),
+                        synth.vectors(1, "values", w.hkv, 1, w.d, "f16")])
+    idx, coef = _gpu_encode(X, D, w.s, csr.CSR_ENCODE_AUTO)
+    _assert_ok(_compare(X, D, w.s, idx, coef))
+    # a batch of 16 sequences sharing the 64 dictionaries: 16 vectors per dictionary
+    B = 16
+    Xb = np.concatenate([synth.vectors(2 + b, "values", 2 * w.hkv, 1, w.d, "f16") for b in range(B)])
+    ib, cb = csr.csr_encode(torch.from_numpy(Xb).cuda(), torch.from_numpy(D).cuda(), w.s)
+    torch.cuda.synchronize()
+    blocks = [0, 63, 64, 500, B * 2 * w.hkv - 1]
+    Db = np.stack([D[h % (2 * w.hkv)] for h in blocks])
+    _assert_ok(_compare(Xb[blocks], Db, w.s, ib.cpu().numpy()[blocks], cb.cpu().numpy()[blocks]))
