@@ -216,6 +216,8 @@ def main():
                     help="skip the decoding step (append one token's codes, then attend)")
     ap.add_argument("--only-extra-decode", action="store_true",
                     help="run only the decode-only lines (for profiling them apart from the main workload)")
+    ap.add_argument("--only-chunked", action="store_true", help="run only the chunked-layout step (for profiling)")
+    ap.add_argument("--only-decode-step", action="store_true", help="run only the decoding step (for profiling)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only copy 1 GiB device-to-device five times and exit: run under rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE, it shows what those counters read for a known amount of traffic")
@@ -247,6 +249,14 @@ def main():
         torch.cuda.set_device(0)
         print(json.dumps({"decode_rooflines": [decode_only(csr, synth.WORKLOADS[n], torch.device("cuda:0"))
                                                for n in ("long_context", "gqa_llama3_8b")]}))
+        return
+
+    if args.only_chunked or args.only_decode_step:
+        torch.cuda.set_device(0)
+        w = synth.WORKLOADS[args.workload]
+        leg = chunked_step if args.only_chunked else decode_step
+        print(json.dumps({"chunked_step" if args.only_chunked else "decode_step":
+                          leg(csr, synth, w, torch.device("cuda:0"), args.steps)}))
         return
 
     w = synth.WORKLOADS[args.workload]
