@@ -316,7 +316,10 @@ __device__ __forceinline__ float from_fixed(unsigned long long v)
 // One workgroup: chunk c of the tokens of (sequence b, KV head h, group slice gs).
 // LDS: table as fp32 scores q.d, [N][GB] (pass 1), then as 64-bit histogram, [GB][N] (pass 2: one table
 // per query head, so that the scatter of one head spreads over all banks) | red[waves][GB]
-template <int GB, typename TI, typename TC, int PV, bool CH>
+// ONE: the chunk has at most 1024 tokens, one per thread (short contexts: the call is a chain of latencies, not a
+// stream).  The token's first 8 key pairs and value pairs are then requested before the score table, so that the
+// three round trips to memory overlap.  Built for the paper's storage types only (16-bit indices, fp16 coefficients).
+template <int GB, typename TI, typename TC, int PV, bool CH, bool ONE>
 __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
     const float *__restrict__ qd, const TI *__restrict__ idxK, const TC *__restrict__ coefK,
     const TI *__restrict__ idxV, const TC *__restrict__ coefV, const int32_t *__restrict__ seq_lens,
@@ -359,6 +362,17 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
     const int64_t code_row = ((int64_t)b * Hkv + h) * T;
     const int n_mine = (int)((t_end - t0 + kStreamThreads - 1) / kStreamThreads);  // rounds of 1024 tokens
 
+    uint4 pre_ki = make_uint4(0u, 0u, 0u, 0u), pre_kc = pre_ki, pre_vi = pre_ki, pre_vc = pre_ki;
+    if constexpr (ONE) {
+        static_assert(!ONE || (PV == 8 && sizeof(TI) == 2 && sizeof(TC) == 2), "prefetch is written for 16-byte code vectors");
+        if (t0 + tid < t_end) {
+            const int64_t r = code_row + t0 + tid;
+            pre_ki = *reinterpret_cast<const uint4 *>(idxK + r * sKt);
+            pre_kc = *reinterpret_cast<const uint4 *>(coefK + r * sKt);
+            pre_vi = *reinterpret_cast<const uint4 *>(idxV + r * sVt);
+            pre_vc = *reinterpret_cast<const uint4 *>(coefV + r * sVt);
+        }
+    }
     const int table = NK * GB;
     {
         const float *src = qd + (((int64_t)b * Hkv + h) * ngs + gs) * (int64_t)table;
@@ -374,13 +388,31 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
     // Unit of the fixed-point histogram: 2^-30 of the largest |value coefficient| among this chunk's first
     // 1024 tokens (read in the first round, next to the key codes, so that the loads overlap).  A coefficient
     // may exceed that estimate 2^33-fold before an add could overflow.
+    constexpr int kTPT = ONE ? 1 : kMaxTPT;
+    auto unpack_idx = [](const uint4 &r, int (&o)[PV]) {
+        if constexpr (PV == 8) {
+            o[0] = r.x & 0xffff; o[1] = r.x >> 16; o[2] = r.y & 0xffff; o[3] = r.y >> 16;
+            o[4] = r.z & 0xffff; o[5] = r.z >> 16; o[6] = r.w & 0xffff; o[7] = r.w >> 16;
+        }
+    };
+    auto unpack_coef = [](const uint4 &r, float (&o)[PV]) {
+        if constexpr (PV == 8) {
+            const __half2 *h2 = reinterpret_cast<const __half2 *>(&r);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float2 f = __half22float2(h2[j]);
+                o[2 * j] = f.x;
+                o[2 * j + 1] = f.y;
+            }
+        }
+    };
     float cm = 0.0f;
-    float sc[kMaxTPT][GB];
+    float sc[kTPT][GB];
     float mx[GB];
 #pragma unroll
     for (int g = 0; g < GB; ++g) mx[g] = -INFINITY;
 #pragma unroll
-    for (int i = 0; i < kMaxTPT; ++i) {
+    for (int i = 0; i < kTPT; ++i) {
 #pragma unroll
         for (int g = 0; g < GB; ++g) sc[i][g] = -INFINITY;
         if (i < n_mine) {
@@ -395,7 +427,8 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
                     const TC *vp = coefV + (code_row + t) * sVt;
                     for (int j0 = 0; j0 < sVt; j0 += PV) {
                         float cf[PV];
-                        CoefLoad<TC, PV>::ld(vp + j0, cf);
+                        if (ONE && j0 == 0) unpack_coef(pre_vc, cf);
+                        else CoefLoad<TC, PV>::ld(vp + j0, cf);
 #pragma unroll
                         for (int j = 0; j < PV; ++j) cm = fmaxf(cm, fabsf(cf[j]));
                     }
@@ -405,8 +438,13 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
                     for (int j0 = 0; j0 < sK; j0 += PV) {  // PV divides sK: a vector load stays in its chunk
                         int id[PV];
                         float cf[PV];
-                        IdxLoad<TI, PV>::ld(ip + j0, id);
-                        CoefLoad<TC, PV>::ld(cp + j0, cf);
+                        if (ONE && ch == 0 && j0 == 0) {
+                            unpack_idx(pre_ki, id);
+                            unpack_coef(pre_kc, cf);
+                        } else {
+                            IdxLoad<TI, PV>::ld(ip + j0, id);
+                            CoefLoad<TC, PV>::ld(cp + j0, cf);
+                        }
 #pragma unroll
                         for (int j = 0; j < PV; ++j) {
 #pragma unroll
@@ -459,7 +497,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
 #pragma unroll
     for (int g = 0; g < GB; ++g) l_thr[g] = 0.0f;
 #pragma unroll
-    for (int i = 0; i < kMaxTPT; ++i) {
+    for (int i = 0; i < kTPT; ++i) {
         if (i < n_mine) {
             const int64_t t = t0 + (int64_t)i * kStreamThreads + tid;
             if (t < t_end) {
@@ -473,8 +511,13 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
                     for (int j0 = 0; j0 < sV; j0 += PV) {
                         int id[PV];
                         float cf[PV];
-                        IdxLoad<TI, PV>::ld(ip + j0, id);
-                        CoefLoad<TC, PV>::ld(cp + j0, cf);
+                        if (ONE && ch == 0 && j0 == 0) {
+                            unpack_idx(pre_vi, id);
+                            unpack_coef(pre_vc, cf);
+                        } else {
+                            IdxLoad<TI, PV>::ld(ip + j0, id);
+                            CoefLoad<TC, PV>::ld(cp + j0, cf);
+                        }
 #pragma unroll
                         for (int j = 0; j < PV; ++j) {
 #pragma unroll
@@ -674,10 +717,10 @@ __global__ __launch_bounds__(256) void finalize_kernel(const float *__restrict__
     }
 }
 
-template <int GB, typename TI, typename TC, int PV, bool CH>
+template <int GB, typename TI, typename TC, int PV, bool CH, bool ONE = false>
 hipError_t launch_stream_t(const DecodeArgs &a, const DecodePlan &p, float *qd, float *hist, float *ml)
 {
-    auto kern = stream_kernel<GB, TI, TC, PV, CH>;
+    auto kern = stream_kernel<GB, TI, TC, PV, CH, ONE>;
     static bool attr_set = false;  // raising the dynamic-LDS limit is needed once per kernel
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -699,6 +742,10 @@ hipError_t launch_stream_pv(const DecodeArgs &a, const DecodePlan &p, float *qd,
         if (a.sK % 8 == 0 && a.sV % 8 == 0) return launch_stream_t<GB, TI, TC, 8, true>(a, p, qd, hist, ml);
         if (a.sK % 4 == 0 && a.sV % 4 == 0) return launch_stream_t<GB, TI, TC, 4, true>(a, p, qd, hist, ml);
         return launch_stream_t<GB, TI, TC, 1, true>(a, p, qd, hist, ml);
+    }
+    if constexpr (sizeof(TI) == 2 && sizeof(TC) == 2) {
+        if (a.sK % 8 == 0 && a.sV % 8 == 0 && p.chunk_tokens == kStreamThreads)
+            return launch_stream_t<GB, TI, TC, 8, false, true>(a, p, qd, hist, ml);
     }
     if (a.sK % 8 == 0 && a.sV % 8 == 0) return launch_stream_t<GB, TI, TC, 8, false>(a, p, qd, hist, ml);
     if (a.sK % 4 == 0 && a.sV % 4 == 0) return launch_stream_t<GB, TI, TC, 4, false>(a, p, qd, hist, ml);
