@@ -35,6 +35,9 @@ PEAK_HBM_GBS = 8000.0           # MI355X HBM3E peak
 # (each scaled by what the counter reads for a 1 GiB copy) on this workload: fetched + written.
 # The summary under profiles/ gives the commands and the raw counts.
 PMC_TRAFFIC_BYTES = {("llama7b_layer", "mfma"): 750.4e6 + 126.9e6}
+# The same for one csr_decode_attn call (its four kernels added up), per workload.
+PMC_DECODE_TRAFFIC_BYTES = {"llama7b_layer": 81.1e6 + 3.1e6, "long_context": 702.0e6 + 16.8e6,
+                            "gqa_llama3_8b": 720.6e6 + 115.5e6}
 
 
 def decode_only(csr, w, dev):
@@ -80,7 +83,7 @@ def decode_only(csr, w, dev):
     gbs = nbytes / (ms * 1e-3) / 1e9
     return {"workload": w.name, "kernel": "csr_decode_attn (4 launches), cache-cold", "bound": "hbm",
             "achieved": round(gbs, 2), "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 5),
-            "traffic": None, "bytes_per_call": nbytes, "avg_call_ms": round(ms, 5),
+            "traffic": PMC_DECODE_TRAFFIC_BYTES.get(w.name), "bytes_per_call": nbytes, "avg_call_ms": round(ms, 5),
             "decode_ctx_tokens_per_s": round(B * T / (ms * 1e-3), 1), "copies_rotated": copies,
             "config": {"kv_heads": Hkv, "query_heads": Hq, "atoms": N, "tokens_per_head": T, "s": s, "decode_batch": B}}
 
@@ -358,7 +361,7 @@ def main():
     dec_gbs = dec_bytes / (dec_cold_ms * 1e-3) / 1e9
     roofline_decode = {"kernel": "csr_decode_attn (4 launches), cache-cold", "bound": "hbm",
                        "achieved": round(dec_gbs, 2), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                       "frac": round(dec_gbs / PEAK_HBM_GBS, 5), "traffic": None,
+                       "frac": round(dec_gbs / PEAK_HBM_GBS, 5), "traffic": PMC_DECODE_TRAFFIC_BYTES.get(w.name),
                        "bytes_per_call": dec_bytes, "avg_call_ms": round(dec_cold_ms, 5),
                        "warm_call_ms": round(dec_ms, 5), "copies_rotated": copies}
 
