@@ -380,6 +380,22 @@ def main():
         "roofline": roofline, "roofline_decode": roofline_decode,
     }
 
+    # ---- Eq.12 on the step's codes: rebuild all keys and values densely (not part of the step) ---------------
+    rec_out = torch.empty((H, T, d), dtype=tdt, device=dev)
+    for _ in range(2):
+        csr.csr_reconstruct(D, idx, coef, out=rec_out)
+    rev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for a_, b_ in rev:
+        a_.record(); csr.csr_reconstruct(D, idx, coef, out=rec_out); b_.record()
+    torch.cuda.synchronize()
+    rec_ms = sum(a_.elapsed_time(b_) for a_, b_ in rev) / args.steps
+    rec_bytes = n_vec * (code_b + d * dict_b)
+    result["reconstruct"] = {"kernel": "csr_reconstruct", "bound": "hbm", "ms": round(rec_ms, 5),
+                             "achieved": round(rec_bytes / (rec_ms * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
+                             "unit": "GB/s", "frac": round(rec_bytes / (rec_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 5),
+                             "bytes_per_call": rec_bytes}
+    del rec_out
+
     # ---- decode alone at the shapes where the code streams dominate (random codes, cache-cold) --------
     if not args.no_extra_decode:
         result["decode_rooflines"] = [decode_only(csr, synth.WORKLOADS[n], dev)

@@ -167,6 +167,39 @@ csr_status csr_decode_attn(const csr_decode_desc *desc, const void *q, const voi
                            size_t workspace_bytes, void *hip_stream);
 
 /*
+ * De-sparse restore, Eq.12: out[h][t] = sum over the s pairs of coef * atom (per chunk with chunked codes, the
+ * chunks' results side by side).  The dense vectors are what the paper feeds to ordinary attention;
+ * csr_decode_attn does not need them, callers that post-process rebuilt keys or values do.
+ * Accumulation is fp32 in pair order.  Indices are not range-checked on the device.
+ */
+typedef struct {
+    int32_t H;          /* vector blocks; >= 0                                              */
+    int64_t T;          /* vectors per block; >= 0                                          */
+    int32_t d;          /* vector length: a multiple of 8 * s_n, at most 1024               */
+    int32_t N;          /* atoms per (chunk) dictionary                                     */
+    int32_t s;          /* pairs per vector (per chunk), 1..32                              */
+    int32_t s_n;        /* chunks per vector; 0 or 1 = whole vectors; must divide d         */
+    int32_t dict_dtype; /* csr_dtype of D                                                   */
+    int32_t coef_dtype; /* csr_dtype of coef                                                */
+    int32_t idx_dtype;  /* csr_itype of idx                                                 */
+    int32_t out_dtype;  /* csr_dtype of out                                                 */
+    int32_t dict_count; /* block h uses dictionary h % dict_count; 0 = H; must divide H     */
+    int64_t code_stride_h; /* elements between blocks' codes; 0 = T*s_n*s                   */
+    int64_t out_stride_h;  /* elements between blocks' vectors; 0 = T*out_stride_t          */
+    int64_t out_stride_t;  /* elements between consecutive vectors; 0 = d; multiple of 8    */
+    uint32_t flags;     /* must be 0                                                        */
+} csr_reconstruct_desc;
+
+/*
+ *   D    [dict_count][N][d]  (chunked: [dict_count][s_n][N][d/s_n])   in
+ *   idx, coef [H][T][s]      (chunked: [H][T][s_n][s])                in
+ *   out  [H][T][d]           (strides as given), 16-byte aligned      out
+ * No workspace.
+ */
+csr_status csr_reconstruct(const csr_reconstruct_desc *desc, const void *D, const void *idx, const void *coef,
+                           void *out, void *hip_stream);
+
+/*
  * Storage accounting of Section "Analysis for CSR": bytes kept per head vector,
  * s * s_n * (index bytes + coefficient bytes).  Returns 0 on bad arguments.
  */

@@ -18,7 +18,7 @@ CSR_I32, CSR_I16 = 0, 1
 CSR_ENCODE_AUTO, CSR_ENCODE_VALU, CSR_ENCODE_MFMA, CSR_ENCODE_SPLIT = 0, 1, 2, 3
 
 EXPORTS = ("csr_version", "csr_last_error", "csr_code_bytes", "csr_encode_workspace_bytes",
-           "csr_encode", "csr_decode_workspace_bytes", "csr_decode_attn")
+           "csr_encode", "csr_decode_workspace_bytes", "csr_decode_attn", "csr_reconstruct")
 
 
 class EncodeDesc(ctypes.Structure):
@@ -29,6 +29,14 @@ class EncodeDesc(ctypes.Structure):
                 ("idx_dtype", ctypes.c_int32), ("x_stride_h", ctypes.c_int64),
                 ("x_stride_t", ctypes.c_int64), ("dict_count", ctypes.c_int32),
                 ("code_stride_h", ctypes.c_int64), ("algo", ctypes.c_int32), ("flags", ctypes.c_uint32)]
+
+
+class ReconstructDesc(ctypes.Structure):
+    _fields_ = [("H", ctypes.c_int32), ("T", ctypes.c_int64), ("d", ctypes.c_int32), ("N", ctypes.c_int32),
+                ("s", ctypes.c_int32), ("s_n", ctypes.c_int32), ("dict_dtype", ctypes.c_int32),
+                ("coef_dtype", ctypes.c_int32), ("idx_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
+                ("dict_count", ctypes.c_int32), ("code_stride_h", ctypes.c_int64),
+                ("out_stride_h", ctypes.c_int64), ("out_stride_t", ctypes.c_int64), ("flags", ctypes.c_uint32)]
 
 
 class DecodeDesc(ctypes.Structure):
@@ -67,6 +75,8 @@ def lib():
         L.csr_encode_workspace_bytes.argtypes = [ctypes.POINTER(EncodeDesc)]
         L.csr_encode.restype = ctypes.c_int
         L.csr_encode.argtypes = [ctypes.POINTER(EncodeDesc), vp, vp, vp, vp, vp, sz, vp]
+        L.csr_reconstruct.restype = ctypes.c_int
+        L.csr_reconstruct.argtypes = [ctypes.POINTER(ReconstructDesc), vp, vp, vp, vp, vp]
         L.csr_decode_workspace_bytes.restype = sz
         L.csr_decode_workspace_bytes.argtypes = [ctypes.POINTER(DecodeDesc)]
         L.csr_decode_attn.restype = ctypes.c_int
@@ -164,6 +174,39 @@ def csr_encode(X, D, s, coef_dtype=None, idx_dtype=None, algo=CSR_ENCODE_AUTO, i
     _check(lib().csr_encode(ctypes.byref(desc), _ptr(X), _ptr(D), _ptr(idx), _ptr(coef),
                             _ptr(workspace), wsb, _stream()))
     return idx, coef
+
+
+def csr_reconstruct(D, idx, coef, out=None, out_dtype=None):
+    """Eq.12, X~ = D r.  D [H', N, d] with codes [H, T, s], or chunked D [H', s_n, N, d / s_n] with codes
+    [H, T, s_n, s] (H' divides H: block h uses dictionary h % H') -> out [H, T, d].  `idx` / `coef` may be views
+    into a larger cache (blocks further apart); `out` may be a strided view with contiguous vectors."""
+    for name, t in (("D", D), ("idx", idx), ("coef", coef)):
+        _dev(t, name)
+    chunked = D.dim() == 4
+    if D.dim() not in (3, 4) or idx.dim() != D.dim() or coef.shape != idx.shape or idx.shape[0] % D.shape[0] != 0 or \
+            (chunked and idx.shape[2] != D.shape[1]):
+        raise ValueError("expected D [H', N, d] with codes [H, T, s] or D [H', s_n, N, d/s_n] with codes [H, T, s_n, s]")
+    D = D.contiguous()
+    H, T, s = idx.shape[0], idx.shape[1], idx.shape[-1]
+    sn = D.shape[1] if chunked else 1
+    d = D.shape[-1] * sn
+    out_dtype = out_dtype or D.dtype
+    if out is None:
+        out = torch.empty((H, T, d), dtype=out_dtype, device=D.device)
+    _dev(out, "out")
+    if tuple(out.shape) != (H, T, d) or out.dtype != out_dtype or out.stride(2) != 1:
+        raise ValueError(f"out must have shape {(H, T, d)}, dtype {out_dtype} and contiguous vectors")
+    if H > 0 and T > 0 and (not idx[0].is_contiguous() or not coef[0].is_contiguous() or
+                            (H > 1 and idx.stride(0) != coef.stride(0))):
+        raise ValueError("idx and coef must have contiguous blocks, equally far apart")
+    desc = ReconstructDesc(H=H, T=T, d=d, N=D.shape[-2], s=s, s_n=sn, dict_dtype=_DT[D.dtype],
+                           coef_dtype=_DT[coef.dtype], idx_dtype=_IT[idx.dtype], out_dtype=_DT[out_dtype],
+                           dict_count=D.shape[0] if D.shape[0] != H else 0,
+                           code_stride_h=idx.stride(0) if H > 1 and T > 0 else 0,
+                           out_stride_h=out.stride(0) if H > 1 and T > 0 else 0,
+                           out_stride_t=out.stride(1) if T > 1 else 0, flags=0)
+    _check(lib().csr_reconstruct(ctypes.byref(desc), _ptr(D), _ptr(idx), _ptr(coef), _ptr(out), _stream()))
+    return out
 
 
 def decode_desc(q, DK, idxK, coefK, idxV, sV=None, scale=0.0, out_dtype=None):

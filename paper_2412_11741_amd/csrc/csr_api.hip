@@ -185,6 +185,49 @@ csr_status csr_encode(const csr_encode_desc *desc, const void *X, const void *D,
     return CSR_OK;
 }
 
+csr_status csr_reconstruct(const csr_reconstruct_desc *d, const void *D, const void *idx, const void *coef,
+                           void *out, void *hip_stream)
+{
+    if (!d) return fail(CSR_ERR_INVALID_ARG, "csr_reconstruct: descriptor is NULL");
+    if (d->H < 0 || d->T < 0) return fail(CSR_ERR_INVALID_ARG, "csr_reconstruct: H=%d T=%lld must be >= 0", d->H, (long long)d->T);
+    if (d->flags != 0) return fail(CSR_ERR_INVALID_ARG, "csr_reconstruct: flags must be 0");
+    if (!valid_dtype(d->dict_dtype) || !valid_dtype(d->coef_dtype) || !valid_dtype(d->out_dtype) || !valid_itype(d->idx_dtype))
+        return fail(CSR_ERR_INVALID_ARG, "csr_reconstruct: unknown dtype / index type");
+    if (d->s < 1 || d->s > 32) return fail(CSR_ERR_INVALID_ARG, "csr_reconstruct: s=%d outside 1..32", d->s);
+    if (d->N < 1 || d->N > (1 << 24)) return fail(CSR_ERR_INVALID_ARG, "csr_reconstruct: N=%d outside 1..2^24", d->N);
+    if (d->idx_dtype == CSR_I16 && d->N > 65536)
+        return fail(CSR_ERR_INVALID_ARG, "csr_reconstruct: N=%d does not fit unsigned 16-bit indices", d->N);
+    const int sn = d->s_n ? d->s_n : 1;
+    if (sn < 1 || d->d < 8 || d->d > 1024 || d->d % (8 * sn) != 0)
+        return fail(CSR_ERR_INVALID_ARG, "csr_reconstruct: d=%d must be a multiple of 8*s_n (s_n=%d) and at most 1024", d->d, sn);
+    if (d->dict_count < 0 || (d->dict_count > 0 && d->H % d->dict_count != 0))
+        return fail(CSR_ERR_INVALID_ARG, "csr_reconstruct: dict_count=%d must be 0 or divide H=%d", d->dict_count, d->H);
+    const int64_t code_block = d->T * sn * d->s;
+    if (d->code_stride_h < 0 || (d->code_stride_h > 0 && d->code_stride_h < code_block))
+        return fail(CSR_ERR_INVALID_ARG, "csr_reconstruct: code_stride_h=%lld is smaller than one block's codes", (long long)d->code_stride_h);
+    const int64_t st = d->out_stride_t ? d->out_stride_t : d->d;
+    const int64_t sh = d->out_stride_h ? d->out_stride_h : d->T * st;
+    if (st < d->d || st % 8 != 0 || sh % 8 != 0 || (d->T > 0 && d->H > 1 && sh < (d->T - 1) * st + d->d))
+        return fail(CSR_ERR_INVALID_ARG, "csr_reconstruct: output strides (h=%lld, t=%lld) must be multiples of 8, >= d and not overlap",
+                    (long long)sh, (long long)st);
+    if (d->H == 0 || d->T == 0) return CSR_OK;
+    if (!D || !idx || !coef || !out) return fail(CSR_ERR_INVALID_ARG, "csr_reconstruct: NULL data pointer");
+    if (!aligned(D, 16) || !aligned(out, 16)) return fail(CSR_ERR_INVALID_ARG, "csr_reconstruct: D and out must be 16-byte aligned");
+    if (!aligned(idx, 2) || !aligned(coef, 2)) return fail(CSR_ERR_INVALID_ARG, "csr_reconstruct: idx and coef must be aligned to their element size");
+    csr::ReconstructArgs a{};
+    a.D = D; a.idx = idx; a.coef = coef; a.out = out;
+    a.H = d->H; a.T = d->T; a.d = d->d; a.N = d->N; a.s = d->s; a.sn = sn;
+    a.dict_count = d->dict_count ? d->dict_count : d->H;
+    a.code_stride_h = d->code_stride_h ? d->code_stride_h : code_block;
+    a.out_stride_h = sh; a.out_stride_t = st;
+    a.dict16 = d->dict_dtype == CSR_F16; a.coef16 = d->coef_dtype == CSR_F16;
+    a.idx16 = d->idx_dtype == CSR_I16; a.out16 = d->out_dtype == CSR_F16;
+    a.stream = static_cast<hipStream_t>(hip_stream);
+    const hipError_t e = csr::launch_reconstruct(a);
+    if (e != hipSuccess) return fail(CSR_ERR_DEVICE, "csr_reconstruct: %s", hipGetErrorString(e));
+    return CSR_OK;
+}
+
 size_t csr_decode_workspace_bytes(const csr_decode_desc *desc)
 {
     csr::DecodePlan p{};

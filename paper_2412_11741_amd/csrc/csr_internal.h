@@ -46,6 +46,22 @@ bool encode_split_supported(const EncodeArgs &a);
 size_t encode_split_workspace_bytes(const EncodeArgs &a);
 hipError_t launch_encode_split(const EncodeArgs &a);
 
+// ---- reconstruct (Eq.12) --------------------------------------------------------------------
+struct ReconstructArgs {
+    const void *D;
+    const void *idx;
+    const void *coef;
+    void *out;
+    int32_t H;
+    int64_t T;
+    int32_t d, N, s, sn;  // d = whole vector length
+    int32_t dict_count;
+    int64_t code_stride_h, out_stride_h, out_stride_t;  // elements, already defaulted
+    bool dict16, coef16, idx16, out16;
+    hipStream_t stream;
+};
+hipError_t launch_reconstruct(const ReconstructArgs &a);
+
 // ---- decode ---------------------------------------------------------------------------------
 struct DecodePlan {
     int32_t GB;           // query heads of one KV head handled together by a block (1, 2 or 4)

@@ -26,6 +26,7 @@
 //   finalize_kernel  adds the slices' partial outputs, divides by the softmax denominator and
 //                    stores in the output type.  (Folding this into out_kernel's last workgroup per
 //                    head was tried: the device-scope fences it needs cost more than the launch.)
+#include <atomic>
 #include <cmath>
 
 #include "csr_internal.h"
@@ -35,6 +36,7 @@ namespace {
 
 constexpr int kStreamThreads = 1024;  // 16 waves: enough loads in flight with one workgroup per CU
 constexpr int kStreamWaves = kStreamThreads / 64;
+constexpr int kMaxDevices = 64;      // devices a process may use this library on
 constexpr int kMaxTPT = 16;           // tokens per thread and chunk: their scores stay in registers
 constexpr int kOutAtomsF16 = 128;     // atoms of D_V per out_kernel workgroup, fp16 dictionary
 constexpr int kOutAtomsF32 = 64;      // same, fp32 dictionary (the slice sits in LDS in its own type)
@@ -721,12 +723,17 @@ template <int GB, typename TI, typename TC, int PV, bool CH, bool ONE = false>
 hipError_t launch_stream_t(const DecodeArgs &a, const DecodePlan &p, float *qd, float *hist, float *ml)
 {
     auto kern = stream_kernel<GB, TI, TC, PV, CH, ONE>;
-    static bool attr_set = false;  // raising the dynamic-LDS limit is needed once per kernel
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget);
+    // raising the dynamic-LDS limit is needed once per kernel and device
+    static std::atomic<bool> attr_set[kMaxDevices];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    if (!attr_set[dev].load(std::memory_order_acquire)) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)kLdsBudget);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_set[dev].store(true, std::memory_order_release);
     }
     const dim3 grid((unsigned)p.nchunks, (unsigned)(a.Hkv * p.ngs), (unsigned)a.B);
     hipLaunchKernelGGL(kern, grid, dim3(kStreamThreads), p.lds_bytes, a.stream, qd, (const TI *)a.idxK,

@@ -47,6 +47,7 @@
 // cover all LDS banks.  Two 4-wave workgroups
 // share a CU (two waves per SIMD), so one workgroup's select / update phase (vector ALU, gathers)
 // overlaps the other's sweep (matrix cores).
+#include <atomic>
 #include <cstdio>
 #include <cstdlib>
 #include <type_traits>
@@ -650,21 +651,22 @@ hipError_t launch_encode_mfma_t(const EncodeArgs &a)
 
     // per device, once: the kernel's LDS need is above the default limit, and the number of
     // workgroups that start together (two per CU) decides which ones are held back at the start
-    static int n_cus[64] = {0};
+    static std::atomic<int> n_cus[64];
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-    if (n_cus[dev] == 0) {
+    if (n_cus[dev].load(std::memory_order_acquire) == 0) {
         int v = 0;
         e = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev);
         if (e != hipSuccess) return e;
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(encode_mfma_kernel<DC>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess) return e;
-        n_cus[dev] = v > 0 ? v : 1;
+        n_cus[dev].store(v > 0 ? v : 1, std::memory_order_release);
     }
-    const int32_t first_round = groups > n_cus[dev] ? 2 * n_cus[dev] : 0;
+    const int cus = n_cus[dev].load(std::memory_order_relaxed);
+    const int32_t first_round = groups > cus ? 2 * cus : 0;
 
     hipLaunchKernelGGL(dict_norm_kernel<DC>, dim3((unsigned)(a.dict_count * a.sn), kNormSlices), dim3(256), 0, a.stream,
                        (const __half *)a.D, dnorm, a.N);

@@ -156,6 +156,20 @@ def test_decode_workspace_grows_with_the_chunk_count_and_zero_means_one_chunk():
     assert size(sK=4, snK=2) > size(sK=4)   # twice the score table
 
 
+def test_reconstruct_rejects_bad_descriptors():
+    lib = csr.lib()
+    base = dict(H=2, T=10, d=128, N=256, s=8, s_n=1, dict_dtype=B.CSR_F16, coef_dtype=B.CSR_F16, idx_dtype=B.CSR_I16,
+                out_dtype=B.CSR_F16, dict_count=0, code_stride_h=0, out_stride_h=0, out_stride_t=0, flags=0)
+    p = ctypes.c_void_p(0x1000)
+    for kw in (dict(s=0), dict(s=33), dict(d=100), dict(d=2048), dict(s_n=3), dict(dict_count=3), dict(N=0),
+               dict(N=70000), dict(code_stride_h=79), dict(out_stride_t=120), dict(out_stride_t=132), dict(flags=1),
+               dict(out_dtype=7)):
+        d = B.ReconstructDesc(**{**base, **kw})
+        assert lib.csr_reconstruct(ctypes.byref(d), p, p, p, p, None) == B.CSR_ERR_INVALID_ARG, kw
+    assert lib.csr_reconstruct(ctypes.byref(B.ReconstructDesc(**{**base, "T": 0})), None, None, None, None, None) == B.CSR_OK
+    assert lib.csr_reconstruct(ctypes.byref(B.ReconstructDesc(**base)), None, p, p, p, None) == B.CSR_ERR_INVALID_ARG
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     X = torch.zeros(1, 4, 128, dtype=torch.float16)
