@@ -21,8 +21,8 @@
 //            atoms one lane holds of one 32x32 output tile), with the tile number packed into the
 //            low mantissa bits so that one integer max/med3 chain tracks value and position.
 //            The 16 screened magnitudes of the lane's best group so far are carried along as fp16
-//            (eight packed registers, replaced by a conditional move whenever a group becomes the
-//            new best), so that after the sweep the best group's values are at hand.
+//            (eight packed registers, rewritten under the lanes' execution mask whenever a group
+//            becomes the new best), so that after the sweep the best group's values are at hand.
 //   select   if the best group's largest kept value leads the other 15 by more than delta (plus the
 //            fp16 rounding of the kept values) and no other tracked group comes within delta of
 //            it, that atom is the iteration's pick (about 97 % of the steps on Gaussian-like
@@ -438,12 +438,15 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
                         for (int r = 0; r < 16; r += 2) m = fmaxf(fmaxf(m, fabsf(acc[bi][r])), fabsf(acc[bi][r + 1]));
                         const uint32_t v = (__float_as_uint(m) & keep_mask) | code;  // one v_and_or_b32
                         const bool new_best = v > u[bi][0];
-                        // keep the magnitudes (fp16, rounded toward zero) of the lane's best group so far
+                        // keep the magnitudes (fp16, rounded toward zero) of the lane's best group so far.  A branch,
+                        // not a select: the eight conversions then run out of line, only in the tiles in which some
+                        // lane has a new best group, and only on those lanes
+                        if (__builtin_expect(new_best, 0)) {
 #pragma unroll
-                        for (int r = 0; r < 8; ++r) {
-                            const auto pk = __builtin_amdgcn_cvt_pkrtz(fabsf(acc[bi][2 * r]), fabsf(acc[bi][2 * r + 1]));
-                            const uint32_t w = *reinterpret_cast<const uint32_t *>(&pk);
-                            keep[bi][r] = new_best ? w : keep[bi][r];
+                            for (int r = 0; r < 8; ++r) {
+                                const auto pk = __builtin_amdgcn_cvt_pkrtz(fabsf(acc[bi][2 * r]), fabsf(acc[bi][2 * r + 1]));
+                                keep[bi][r] = *reinterpret_cast<const uint32_t *>(&pk);
+                            }
                         }
                         const uint32_t n3 = umed3(u[bi][2], u[bi][3], v);
                         const uint32_t n2 = umed3(u[bi][1], u[bi][2], v);
