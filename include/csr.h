@@ -95,6 +95,10 @@ typedef struct {
                            encoded like the prompt's)                                       */
     int32_t algo;       /* csr_encode_algo                                                  */
     uint32_t flags;     /* must be 0                                                        */
+    float *res_norm2;   /* optional device pointer, [H][T][s_n] fp32, or NULL: receives |R_{s+1}|^2, the
+                           squared norm of what the s pairs leave of each vector (chunk) - by Eq.4 the
+                           squared reconstruction error |x - D r|^2 with unrounded coefficients, i.e. the
+                           vector's term of the dictionary-training loss of Section "NeuralDict"       */
 } csr_encode_desc;
 
 /* Bytes of device scratch csr_encode needs for this descriptor (may be 0); (size_t)-1 if the

@@ -28,7 +28,8 @@ class EncodeDesc(ctypes.Structure):
                 ("dict_dtype", ctypes.c_int32), ("coef_dtype", ctypes.c_int32),
                 ("idx_dtype", ctypes.c_int32), ("x_stride_h", ctypes.c_int64),
                 ("x_stride_t", ctypes.c_int64), ("dict_count", ctypes.c_int32),
-                ("code_stride_h", ctypes.c_int64), ("algo", ctypes.c_int32), ("flags", ctypes.c_uint32)]
+                ("code_stride_h", ctypes.c_int64), ("algo", ctypes.c_int32), ("flags", ctypes.c_uint32),
+                ("res_norm2", ctypes.c_void_p)]
 
 
 class ReconstructDesc(ctypes.Structure):
@@ -137,13 +138,14 @@ def csr_encode_workspace_bytes(desc):
 
 
 def csr_encode(X, D, s, coef_dtype=None, idx_dtype=None, algo=CSR_ENCODE_AUTO, idx=None, coef=None,
-               workspace=None):
+               workspace=None, res_norm2=None):
     """Matching Pursuit encode.  X [H, T, d], D [H, N, d] on the GPU -> (idx, coef) [H, T, s].
     Chunked: D [H, s_n, N, d / s_n] -> (idx, coef) [H, T, s_n, s], every chunk encoded on its own dictionary.
     D may hold H' < H dictionaries (H' divides H): block h uses dictionary h % H' (blocks ordered sequence-major,
     head-minor).  `idx` / `coef` may be views into a larger cache whose blocks are further apart (stride(0) larger
     than one block's codes, the rest contiguous): the codes are then written in place, e.g. appended at a token
-    position."""
+    position.  `res_norm2` (fp32, [H, T] or [H, T, s_n], contiguous) receives the squared norm of each vector's
+    final residual, i.e. its squared reconstruction error."""
     _dev(X, "X"); _dev(D, "D")
     if X.dim() != 3 or D.dim() not in (3, 4) or D.shape[0] < 1 or X.shape[0] % D.shape[0] != 0 or \
             D.shape[-1] * (D.shape[1] if D.dim() == 4 else 1) != X.shape[2]:
@@ -167,6 +169,12 @@ def csr_encode(X, D, s, coef_dtype=None, idx_dtype=None, algo=CSR_ENCODE_AUTO, i
             raise ValueError("idx and coef must have the same distance between blocks")
         code_stride_h = idx.stride(0)
     desc = encode_desc(X, D, s, coef_dtype, idx_dtype, algo, code_stride_h)
+    if res_norm2 is not None:
+        _dev(res_norm2, "res_norm2")
+        want = (H, T) if D.dim() == 3 else (H, T, D.shape[1])
+        if tuple(res_norm2.shape) != want or res_norm2.dtype != torch.float32 or not res_norm2.is_contiguous():
+            raise ValueError(f"res_norm2 must be a contiguous float32 tensor of shape {want}")
+        desc.res_norm2 = res_norm2.data_ptr()
     need = csr_encode_workspace_bytes(desc)
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=X.device)

@@ -176,7 +176,9 @@ csr_status csr_encode(const csr_encode_desc *desc, const void *X, const void *D,
         if (!workspace || workspace_bytes < need || !aligned(workspace, 256))
             return fail(CSR_ERR_WORKSPACE, "csr_encode: workspace of %zu bytes (256-byte aligned) required, got %zu", need, workspace ? workspace_bytes : (size_t)0);
     }
+    if (desc->res_norm2 && !aligned(desc->res_norm2, 4)) return fail(CSR_ERR_INVALID_ARG, "csr_encode: res_norm2 must be 4-byte aligned");
     a.X = X; a.D = D; a.idx = idx; a.coef = coef;
+    a.res_norm2 = desc->res_norm2;
     a.workspace = workspace;
     a.stream = static_cast<hipStream_t>(hip_stream);
     const hipError_t e = algo == CSR_ENCODE_MFMA ? csr::launch_encode_mfma(a)

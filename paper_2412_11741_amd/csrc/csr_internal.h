@@ -28,6 +28,7 @@ struct EncodeArgs {
     int64_t code_stride_h;           // elements between blocks' codes (already defaulted)
     bool f16;                        // X and D are fp16 (else fp32)
     bool coef16, idx16;
+    float *res_norm2;                // optional [H][T][sn] output, or nullptr
     void *workspace;
     hipStream_t stream;
 };

@@ -281,7 +281,8 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
     const __half *__restrict__ X, const __half *__restrict__ Dict, void *__restrict__ idx_out,
     void *__restrict__ coef_out, const float *__restrict__ dnorm, int64_t T, int32_t N, int32_t s, int32_t sn,
     int64_t x_stride_h, int64_t x_stride_t, int32_t dict_count, int64_t code_stride_h, int32_t tiles_per_h,
-    int32_t n_groups, int32_t idx16, int32_t coef16, uint32_t code_mask, int32_t first_round)
+    int32_t n_groups, int32_t idx16, int32_t coef16, uint32_t code_mask, int32_t first_round,
+    float *__restrict__ res_norm2)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     using S = Shape<DC>;
@@ -623,6 +624,11 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
             }
         }
     }
+    if (res_norm2) {  // |R_{s+1}|^2, back in the input's scale
+#pragma unroll
+        for (int bi = 0; bi < kBlocks; ++bi)
+            if (valid[bi] && hf == 0) res_norm2[((int64_t)h * T + tok[bi]) * sn + ch] = ldexpf(rn2[bi], -2 * sexp[bi]);
+    }
 }
 
 size_t r256(size_t v) { return (v + 255) & ~size_t(255); }
@@ -678,7 +684,7 @@ hipError_t launch_encode_mfma_t(const EncodeArgs &a)
     hipLaunchKernelGGL(encode_mfma_kernel<DC>, dim3((unsigned)groups), dim3(kThreads), kLdsBytes, a.stream,
                        (const __half *)a.X, (const __half *)a.D, a.idx, a.coef, dnorm, a.T, a.N, a.s, a.sn, a.x_stride_h,
                        a.x_stride_t, a.dict_count, a.code_stride_h, (int32_t)tiles, (int32_t)groups, (int32_t)a.idx16, (int32_t)a.coef16, code_mask,
-                       first_round);
+                       first_round, a.res_norm2);
     return hipGetLastError();
 }
 

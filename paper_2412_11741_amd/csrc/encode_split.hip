@@ -73,6 +73,7 @@ struct SplitParams {
     int64_t T;
     int64_t x_stride_h, x_stride_t, code_stride_h;
     int32_t N, s, sn, dict_count, M, k, g, idx16, coef16;
+    float *res_norm2;  // optional [H][T][sn]
 };
 
 // Lane (col, hf): column col of the MFMA's B operand = vector m0 + col of the block; it holds dimensions
@@ -162,14 +163,16 @@ __global__ __launch_bounds__(kThreads) void encode_split_kernel(const SplitParam
             }
             sexp_cur = sexp_prev;
         }
-        if (g == p.s) continue;  // the last launch only stores the last pair (uniform over the grid)
-
         float r2 = 0.0f;
 #pragma unroll
         for (int j = 0; j < kFrags; ++j)
 #pragma unroll
             for (int e = 0; e < 8; ++e) r2 = fmaf(R[j][e], R[j][e], r2);
         r2 += xchg32f(r2, hf);
+        if (g == p.s) {  // the last launch only stores the last pair and what is left (uniform over the grid)
+            if (p.res_norm2 && sl == 0 && valid && hf == 0) p.res_norm2[vid] = ldexpf(r2, -2 * sexp_cur);
+            continue;
+        }
         // A residual that has shrunk a lot (a vector that is nearly a multiple of an atom) is scaled up again
         // before the split, or lo would sink into the fp16 subnormals; one that has grown (atoms of norm above
         // sqrt(2) make Eq.4 expand it) is scaled down before hi could leave the fp16 range.
@@ -305,7 +308,7 @@ hipError_t launch_encode_split(const EncodeArgs &a)
     p.cand = reinterpret_cast<float4 *>(ws + pl.off_cand);
     p.V = pl.V; p.T = a.T; p.x_stride_h = a.x_stride_h; p.x_stride_t = a.x_stride_t; p.code_stride_h = a.code_stride_h;
     p.N = a.N; p.s = a.s; p.sn = a.sn; p.dict_count = a.dict_count; p.M = pl.M; p.k = pl.k;
-    p.idx16 = a.idx16; p.coef16 = a.coef16;
+    p.idx16 = a.idx16; p.coef16 = a.coef16; p.res_norm2 = a.res_norm2;
     const dim3 grid((unsigned)pl.k, (unsigned)(a.dict_count * a.sn));
     for (int g = 0; g <= a.s; ++g) {
         p.g = g;

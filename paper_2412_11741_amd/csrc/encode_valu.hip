@@ -29,7 +29,7 @@ __global__ __launch_bounds__(64 * W) void encode_valu_kernel(
     const TE *__restrict__ X, const TE *__restrict__ Dict, void *__restrict__ idx_out,
     void *__restrict__ coef_out, int64_t T, int32_t N, int32_t s, int64_t x_stride_h,
     int64_t x_stride_t, int32_t tiles_per_h, int32_t sn, int32_t dict_count, int64_t code_stride_h, int32_t idx16,
-    int32_t coef16)
+    int32_t coef16, float *__restrict__ res_norm2)
 {
     __shared__ float s_abs[2][W][64];
     __shared__ float s_c[2][W][64];
@@ -112,6 +112,12 @@ __global__ __launch_bounds__(64 * W) void encode_valu_kernel(
         // The LDS buffers alternate, so one barrier per iteration is enough: a wave can only
         // overwrite buffer `buf` two iterations later, after passing the next barrier.
     }
+    if (res_norm2 && wave == 0 && valid) {
+        float r2 = 0.0f;
+#pragma unroll
+        for (int k = 0; k < D_; ++k) r2 = fmaf(R[k], R[k], r2);
+        res_norm2[((int64_t)h * T + t) * sn + ch] = r2;
+    }
 }
 
 template <int D_, typename TE>
@@ -126,7 +132,7 @@ hipError_t launch_valu_t(const EncodeArgs &a)
     hipLaunchKernelGGL((encode_valu_kernel<D_, TE, W>), grid, dim3(64 * W), 0, a.stream,         \
                        (const TE *)a.X, (const TE *)a.D, a.idx, a.coef, a.T, a.N, a.s,          \
                        a.x_stride_h, a.x_stride_t, (int32_t)tiles, a.sn, a.dict_count, a.code_stride_h, \
-                       (int32_t)a.idx16, (int32_t)a.coef16)
+                       (int32_t)a.idx16, (int32_t)a.coef16, a.res_norm2)
     // (8 waves = 2 per SIMD leaves each lane the 128+ registers its residual needs.)
     if (groups >= 1024) CSR_LAUNCH_VALU(4);
     else CSR_LAUNCH_VALU(8);

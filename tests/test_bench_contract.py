@@ -1,0 +1,45 @@
+"""bench.py's command-line contract: what can be checked without a GPU, and the JSON line on one."""
+import json
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _bench(*args, env=None):
+    return subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), *args], capture_output=True, text=True,
+                          env={**os.environ, **(env or {})}, timeout=600)
+
+
+def test_more_than_one_gpu_is_refused_with_a_message():
+    r = _bench("--gpus", "2")
+    assert r.returncode != 0 and "single-GPU" in r.stderr and r.stdout.strip() == ""
+    r = _bench(env={"WORLD_SIZE": "2"})
+    assert r.returncode != 0 and "single-GPU" in r.stderr
+
+
+@pytest.mark.gpu
+def test_the_json_line_carries_the_contracts_fields():
+    r = _bench("--steps", "3", "--warmup", "1", "--no-extra-decode")
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [l for l in r.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1
+    out = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert key in out, key
+    assert out["n_gpus"] == 1 and out["steps"] == 3 and out["warmup"] == 1 and out["vs_baseline"] is None
+    assert out["config"]["workload"] == "llama7b_layer" and "model" not in out["config"]
+    roof = out["roofline"]
+    assert roof["bound"] == "mfma" and roof["peak"] == 2500.0 and roof["unit"] == "TFLOP/s"
+    assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-4 and roof["traffic"] > 0
+    # achieved = algorithmic flop per launch / launch time, value = vectors per second over the whole step
+    assert abs(roof["achieved"] - out["config"]["vectors_per_step"] * roof["flop_per_vector"] / (roof["avg_launch_ms"] * 1e-3) / 1e12) < 0.01 * roof["achieved"]
+    assert abs(out["value"] - out["config"]["vectors_per_step"] / (out["ms_per_step"] * 1e-3)) < 0.01 * out["value"]
+    cpu = out["cpu_baseline"]
+    assert cpu["kind"] == "oracle" and cpu["cores"] >= 1 and cpu["value"] > 0 and cpu["sample"]
+    for leg in ("roofline_decode", "chunked_step", "decode_step", "reconstruct"):
+        assert leg in out, leg

@@ -452,3 +452,34 @@ def test_decoding_step_full_size_one_token_for_every_head_of_a_layer():
     blocks = [0, 63, 64, 500, B * 2 * w.hkv - 1]
     Db = np.stack([D[h % (2 * w.hkv)] for h in blocks])
     _assert_ok(_compare(Xb[blocks], Db, w.s, ib.cpu().numpy()[blocks], cb.cpu().numpy()[blocks]))
+
+
+@pytest.mark.parametrize("algo", ["valu", "mfma", "split"])
+@pytest.mark.parametrize("sn", [1, 2])
+def test_residual_norm_output_is_the_reconstruction_error(algo, sn):
+    # |R_{s+1}|^2 per vector (chunk): the vector's term of the dictionary-training loss of Section "NeuralDict"
+    H, T, N, d, s = 3, 100, 512, 128, 6
+    dc = d // sn
+    D = synth.dictionary(61, "dict_v", H * sn, N, dc, "f16").reshape(H, sn, N, dc)
+    X = synth.vectors(61, "values", H, T, d, "f16", outliers=4)
+    X[0, 0] = 0                                                       # a zero vector leaves nothing
+    X[1, 1, :dc] = (D[1, 0, 7].astype(np.float32) * 3).astype(np.float16)   # a multiple of an atom leaves ~nothing
+    Dg = torch.from_numpy(D if sn > 1 else D[:, 0]).cuda()
+    shape = (H, T, sn) if sn > 1 else (H, T)
+    rn = torch.full(shape, -1.0, dtype=torch.float32, device="cuda")
+    idx, coef = csr.csr_encode(torch.from_numpy(X).cuda(), Dg, s, algo=ALGOS[algo], coef_dtype=torch.float32,
+                               idx_dtype=torch.int32, res_norm2=rn)
+    torch.cuda.synchronize()
+    rn = rn.cpu().numpy().reshape(H, T, sn)
+    idx, coef = idx.cpu().numpy().reshape(H, T, sn, s), coef.cpu().numpy().reshape(H, T, sn, s)
+    for h in range(H):
+        for c in range(sn):
+            Xc = X[h][:, c * dc:(c + 1) * dc].astype(np.float64)
+            # what the GPU's own pairs leave (they may differ from the oracle's at ties): x - D r in float64
+            err = ((Xc - oracle.reconstruct(idx[h, :, c], coef[h, :, c], D[h, c])) ** 2).sum(axis=1)
+            x2 = (Xc ** 2).sum(axis=1)
+            assert np.all(np.abs(rn[h, :, c] - err) <= 1e-4 * err + 1e-6 * x2), (algo, h, c, np.abs(rn[h, :, c] - err).max())
+            _, _, diag = oracle.mp_encode(Xc, D[h, c], s, diagnostics=True)
+            close = np.abs(rn[h, :, c] - diag["res_norm2"][:, s]) <= 1e-3 * x2
+            assert close.mean() > 0.97                                 # the oracle's own path, except after ties
+    assert rn[0, 0, 0] == 0.0 and rn[1, 1, 0] <= 1e-5 * float((X[1, 1, :dc].astype(np.float64) ** 2).sum())
