@@ -52,14 +52,17 @@ typedef enum { CSR_F32 = 0, CSR_F16 = 1 } csr_dtype; /* vectors, dictionaries, c
 typedef enum { CSR_I32 = 0, CSR_I16 = 1 } csr_itype; /* atom indices; I16 is unsigned        */
 
 /* Which encoder kernel runs.  AUTO picks SPLIT when a dictionary serves few vectors (the tokens of one
- * decoding step), MFMA when the shape allows it, else VALU. */
+ * decoding step), RESIDENT when the dictionary fits the LDS, MFMA when the shape allows it, else VALU. */
 typedef enum {
     CSR_ENCODE_AUTO = 0,
     CSR_ENCODE_VALU = 1, /* fp32 vector-ALU correlation, any supported shape               */
     CSR_ENCODE_MFMA = 2, /* fp16 matrix-core screening pass + exact fp32 selection          */
-    CSR_ENCODE_SPLIT = 3 /* few vectors per dictionary (at most 128): every dictionary's atoms are
+    CSR_ENCODE_SPLIT = 3, /* few vectors per dictionary (at most 128): every dictionary's atoms are
                             split over several workgroups, one launch per iteration; fp16 inputs,
                             chunks of 64 or 128 dimensions, N a multiple of 32                   */
+    CSR_ENCODE_RESIDENT = 4 /* small dictionaries (N * d/s_n * 2 bytes <= 128 KB, e.g. the 256 - 512 atoms per
+                            head of the paper's experiments): the dictionary stays in LDS, exact
+                            fp32-accumulated correlations on the matrix cores; same input types     */
 } csr_encode_algo;
 
 /*

@@ -47,6 +47,10 @@ bool encode_split_supported(const EncodeArgs &a);
 size_t encode_split_workspace_bytes(const EncodeArgs &a);
 hipError_t launch_encode_split(const EncodeArgs &a);
 
+// fp16 matrix-core encoder for dictionaries that fit the LDS (at most 128 KB).
+bool encode_resident_supported(const EncodeArgs &a);
+hipError_t launch_encode_resident(const EncodeArgs &a);
+
 // ---- reconstruct (Eq.12) --------------------------------------------------------------------
 struct ReconstructArgs {
     const void *D;

@@ -80,18 +80,25 @@ def test_encode_chunk_count_scales_the_workspace_and_zero_means_whole_vectors():
     assert lib.csr_encode_workspace_bytes(ctypes.byref(_enc(s_n=4))) == 0      # chunks of 32: the vector-ALU encoder needs none
 
 
-def test_encode_kernel_choice_follows_the_vectors_per_dictionary():
+def test_encode_kernel_choice_follows_the_vectors_per_dictionary_and_the_dictionary_size():
     lib = csr.lib()
     size = lambda **kw: lib.csr_encode_workspace_bytes(ctypes.byref(_enc(**kw)))
+    big = dict(N=4096)      # 1 MB of atoms: beyond the LDS
     # few vectors per dictionary (a decoding step): AUTO is the split encoder, whose scratch holds residuals
-    assert size(T=1) == size(T=1, algo=B.CSR_ENCODE_SPLIT) != size(T=1, algo=B.CSR_ENCODE_MFMA)
-    assert size(T=128) == size(T=128, algo=B.CSR_ENCODE_SPLIT)
-    assert size(T=129) == size(T=129, algo=B.CSR_ENCODE_MFMA)
+    assert size(T=1, **big) == size(T=1, algo=B.CSR_ENCODE_SPLIT, **big) != size(T=1, algo=B.CSR_ENCODE_MFMA, **big)
+    assert size(T=128, **big) == size(T=128, algo=B.CSR_ENCODE_SPLIT, **big)
+    assert size(T=129, **big) == size(T=129, algo=B.CSR_ENCODE_MFMA, **big) > 0
     # 16 blocks on 2 dictionaries: 8 x 20 = 160 vectors per dictionary, too many for the split encoder
-    assert size(H=16, T=20, dict_count=2) == size(H=16, T=20, dict_count=2, algo=B.CSR_ENCODE_MFMA)
-    assert size(H=16, T=20, dict_count=2, algo=B.CSR_ENCODE_SPLIT) == ctypes.c_size_t(-1).value
-    assert size(H=16, T=20, dict_count=4) == size(H=16, T=20, dict_count=4, algo=B.CSR_ENCODE_SPLIT)
+    assert size(H=16, T=20, dict_count=2, **big) == size(H=16, T=20, dict_count=2, algo=B.CSR_ENCODE_MFMA, **big)
+    assert size(H=16, T=20, dict_count=2, algo=B.CSR_ENCODE_SPLIT, **big) == ctypes.c_size_t(-1).value
+    assert size(H=16, T=20, dict_count=4, **big) == size(H=16, T=20, dict_count=4, algo=B.CSR_ENCODE_SPLIT, **big)
     assert size(T=1, x_dtype=B.CSR_F32, dict_dtype=B.CSR_F32) == 0            # fp32: vector-ALU encoder
+    # many vectors on a dictionary that fits the LDS (128 KB): the resident encoder, which needs no scratch
+    assert size(T=1000, N=512) == size(T=1000, N=512, algo=B.CSR_ENCODE_RESIDENT) == 0
+    assert size(T=1000, N=512, algo=B.CSR_ENCODE_MFMA) > 0
+    assert size(T=1000, N=544) == size(T=1000, N=544, algo=B.CSR_ENCODE_MFMA) > 0
+    assert size(T=1000, N=544, algo=B.CSR_ENCODE_RESIDENT) == ctypes.c_size_t(-1).value
+    assert size(T=1000, N=1024, d=64) == 0 and size(T=1000, N=1056, d=64) > 0  # 64-dimensional atoms: twice as many fit
 
 
 def test_encode_null_and_misaligned_pointers_and_noop_sizes():

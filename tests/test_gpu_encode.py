@@ -16,7 +16,8 @@ pytestmark = pytest.mark.gpu
 # and 1e-3 covers a one-ulp flip at a rounding boundary.
 TOL = 1e-3
 
-ALGOS = {"valu": csr.CSR_ENCODE_VALU, "mfma": csr.CSR_ENCODE_MFMA, "split": csr.CSR_ENCODE_SPLIT}
+ALGOS = {"valu": csr.CSR_ENCODE_VALU, "mfma": csr.CSR_ENCODE_MFMA, "split": csr.CSR_ENCODE_SPLIT,
+         "resident": csr.CSR_ENCODE_RESIDENT}
 SPLIT_MAX = 128   # vectors per dictionary the split encoder takes
 
 
@@ -91,7 +92,7 @@ def test_valu_smaller_head_chunks(d, dtype):
     _assert_ok(_compare(X, D, s, idx, coef))
 
 
-@pytest.mark.parametrize("algo", ["valu", "mfma", "split"])
+@pytest.mark.parametrize("algo", ["valu", "mfma", "split", "resident"])
 @pytest.mark.parametrize("s", [1, 16, 32])
 def test_iteration_counts(algo, s):
     H, T, N, d = 1, 192 if algo != "split" else 70, 512, 128
@@ -101,7 +102,7 @@ def test_iteration_counts(algo, s):
     _assert_ok(_compare(X, D, s, idx, coef))
 
 
-@pytest.mark.parametrize("algo", ["valu", "mfma", "split"])
+@pytest.mark.parametrize("algo", ["valu", "mfma", "split", "resident"])
 def test_orthonormal_dictionary_recovers_top_s_coordinates(algo):
     # Identity atoms (padded with a second, rotated orthonormal basis so N is a multiple of 32 x 8):
     # with the identity alone the codes are the s largest |x_k| in order.
@@ -116,7 +117,7 @@ def test_orthonormal_dictionary_recovers_top_s_coordinates(algo):
     assert np.array_equal(coef[0], np.take_along_axis(X[0], order, axis=1))
 
 
-@pytest.mark.parametrize("algo", ["valu", "mfma", "split"])
+@pytest.mark.parametrize("algo", ["valu", "mfma", "split", "resident"])
 def test_degenerate_inputs_zero_vectors_scaled_atoms_single_vector(algo):
     H, N, d, s = 1, 256, 128, 4
     D = synth.dictionary(6, "dict_k", H, N, d, "f16")
@@ -278,7 +279,7 @@ def _adversarial_cases():
 
 @pytest.mark.parametrize("name", ["atom norms 0.25 .. 2", "duplicated atoms", "dynamic range",
                                   "sparse combinations of atoms", "constant and one-hot vectors"])
-@pytest.mark.parametrize("algo", ["valu", "mfma", "split"])
+@pytest.mark.parametrize("algo", ["valu", "mfma", "split", "resident"])
 def test_adversarial_inputs(algo, name):
     D, X = _adversarial_cases()[name]
     if algo == "split":
@@ -395,7 +396,7 @@ def test_auto_picks_the_split_encoder_for_a_decoding_step_and_storage_types_do_n
     _assert_ok(_compare(X, D, s, i32.cpu().numpy(), c32.cpu().numpy()))
 
 
-@pytest.mark.parametrize("algo", ["split", "mfma", "valu"])
+@pytest.mark.parametrize("algo", ["split", "mfma", "valu", "resident"])
 def test_append_in_place_into_a_cache_of_codes(algo):
     # the codes of one new token per (sequence, head) land at row `pos` of a cache [blocks][T_max][s]
     B, Hkv, T_max, N, d, s, pos = 3, 4, 50, 512, 128, 8, 17
@@ -454,7 +455,7 @@ def test_decoding_step_full_size_one_token_for_every_head_of_a_layer():
     _assert_ok(_compare(Xb[blocks], Db, w.s, ib.cpu().numpy()[blocks], cb.cpu().numpy()[blocks]))
 
 
-@pytest.mark.parametrize("algo", ["valu", "mfma", "split"])
+@pytest.mark.parametrize("algo", ["valu", "mfma", "split", "resident"])
 @pytest.mark.parametrize("sn", [1, 2])
 def test_residual_norm_output_is_the_reconstruction_error(algo, sn):
     # |R_{s+1}|^2 per vector (chunk): the vector's term of the dictionary-training loss of Section "NeuralDict"
@@ -483,3 +484,33 @@ def test_residual_norm_output_is_the_reconstruction_error(algo, sn):
             close = np.abs(rn[h, :, c] - diag["res_norm2"][:, s]) <= 1e-3 * x2
             assert close.mean() > 0.97                                 # the oracle's own path, except after ties
     assert rn[0, 0, 0] == 0.0 and rn[1, 1, 0] <= 1e-5 * float((X[1, 1, :dc].astype(np.float64) ** 2).sum())
+
+
+# --- small dictionaries kept in LDS (the 256 - 512 atoms per head of the paper's experiments) -------------------
+
+@pytest.mark.parametrize("H,T,N,d,sn,s,dicts", [
+    (4, 1000, 256, 128, 1, 8, 4),      # the paper's 256 atoms per head
+    (3, 777, 512, 128, 1, 8, 3),       # the largest dictionary of 128-dimensional atoms that fits
+    (2, 513, 32, 128, 1, 4, 2),        # one tile; a second workgroup with a single vector
+    (6, 300, 1024, 128, 2, 4, 3),      # values in two chunks of 64, 1024 atoms each; blocks sharing dictionaries
+    (2, 2000, 96, 64, 1, 6, 2),        # 64-dimensional vectors, three tiles
+])
+def test_resident_encoder_parity(H, T, N, d, sn, s, dicts):
+    dc = d // sn
+    D = synth.dictionary(71, "dict_k", dicts * sn, N, dc, "f16").reshape(dicts, sn, N, dc)
+    X = synth.vectors(71, "keys", H, T, d, "f16", outliers=8)
+    Dg = torch.from_numpy(D if sn > 1 else D[:, 0]).cuda()
+    idx, coef = csr.csr_encode(torch.from_numpy(X).cuda(), Dg, s, algo=csr.CSR_ENCODE_RESIDENT)
+    ia, ca = csr.csr_encode(torch.from_numpy(X).cuda(), Dg, s)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, ia) and torch.equal(coef, ca)             # what AUTO runs for these shapes
+    idx, coef = idx.cpu().numpy().reshape(H, T, sn, s), coef.cpu().numpy().reshape(H, T, sn, s)
+    D_blocks = np.stack([D[h % dicts] for h in range(H)])
+    _assert_ok(_compare_chunked(X, D_blocks, s, idx.view(np.uint16).astype(np.int32), coef))
+
+
+def test_resident_encoder_is_refused_for_dictionaries_beyond_the_lds():
+    D = torch.zeros(1, 544, 128, dtype=torch.float16, device="cuda")
+    X = torch.zeros(1, 200, 128, dtype=torch.float16, device="cuda")
+    with pytest.raises(csr.CsrError, match="128 KB"):
+        csr.csr_encode(X, D, 4, algo=csr.CSR_ENCODE_RESIDENT)
