@@ -339,3 +339,62 @@ def test_chunked_values_full_layer_all_heads():
     out = _run(q, DK[:, 0], iK[:, :, :, 0], cK[:, :, :, 0], DV, iV, cV)
     ref = oracle.decode_attn_chunked(q, DK, _u16(iK), cK, DV, _u16(iV), cV)
     _check(out, ref, TOL_F16_OUT, "llama7b layer, values in two chunks, all heads")
+
+
+def test_a_decoding_step_can_be_captured_in_a_graph_and_replayed():
+    # append (split encoder: s + 1 launches per call) + attention (4 launches) recorded once, replayed on new data;
+    # every replay must equal the eager result of the same inputs bit for bit (nothing allocates, nothing is cleared
+    # by a memset node, every kernel argument is fixed at capture time)
+    B, Hkv, G, T_max, N, d, s, pos = 2, 2, 2, 256, 512, 128, 8, 200
+    DK = torch.from_numpy(synth.dictionary(27, "dict_k", Hkv, N, d, "f16")).cuda()
+    DV = torch.from_numpy(synth.dictionary(27, "dict_v", Hkv, N, d, "f16")).cuda()
+    iK0, cK0 = synth.random_codes(27, 0, B, Hkv, T_max, s, N, "f16", "i16")
+    iV0, cV0 = synth.random_codes(27, 1, B, Hkv, T_max, s, N, "f16", "i16")
+    g = lambda a: torch.from_numpy(a).cuda()
+    mk_cache = lambda: [g(a).view(B * Hkv, T_max, s) for a in (iK0, cK0, iV0, cV0)]
+    xk, xv = (torch.zeros((B * Hkv, 1, d), dtype=torch.float16, device="cuda") for _ in range(2))
+    q = torch.zeros((B, Hkv * G, d), dtype=torch.float16, device="cuda")
+    out = torch.zeros_like(q)
+    lens = torch.full((B,), pos + 1, dtype=torch.int32, device="cuda")
+    iK, cK, iV, cV = mk_cache()
+    edesc = csr.encode_desc(xk, DK, s, torch.float16, torch.int16, code_stride_h=T_max * s)
+    wsE = torch.empty(max(csr.csr_encode_workspace_bytes(edesc), 256), dtype=torch.uint8, device="cuda")
+    v4 = lambda t: t.view(B, Hkv, T_max, s)
+    wsD = torch.empty(max(csr.csr_decode_workspace_bytes(csr.decode_desc(q, DK, v4(iK), v4(cK), v4(iV))), 256),
+                      dtype=torch.uint8, device="cuda")
+
+    def step():
+        csr.csr_encode(xk, DK, s, idx=iK[:, pos:pos + 1], coef=cK[:, pos:pos + 1], workspace=wsE)
+        csr.csr_encode(xv, DV, s, idx=iV[:, pos:pos + 1], coef=cV[:, pos:pos + 1], workspace=wsE)
+        csr.csr_decode_attn(q, DK, v4(iK), v4(cK), DV, v4(iV), v4(cV), seq_lens=lens, out=out, workspace=wsD)
+
+    def load(seed):
+        xk.copy_(g(synth.vectors(seed, "keys", B * Hkv, 1, d, "f16", outliers=8)))
+        xv.copy_(g(synth.vectors(seed, "values", B * Hkv, 1, d, "f16")))
+        q.copy_(g(synth.queries(seed, B, Hkv * G, d, "f16")))
+
+    load(100)
+    step()                                   # eager once: per-device set-up happens outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for seed in (101, 102, 103):
+        load(seed)
+        out.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (out.clone(), iK[:, pos].clone(), cK[:, pos].clone(), iV[:, pos].clone(), cV[:, pos].clone())
+        out.zero_()
+        iK[:, pos].zero_(); cK[:, pos].zero_(); iV[:, pos].zero_(); cV[:, pos].zero_()
+        step()                               # the program's own eager work between the replays
+        torch.cuda.synchronize()
+        want = (out, iK[:, pos], cK[:, pos], iV[:, pos], cV[:, pos])
+        for a, b in zip(got, want):
+            assert torch.equal(a, b), seed
+        assert torch.isfinite(out.float()).all() and out.abs().sum() > 0
