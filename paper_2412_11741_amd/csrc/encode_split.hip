@@ -80,7 +80,7 @@ struct SplitParams {
 // hf DC/2 .. hf DC/2 + DC/2 - 1 (the contraction index is permuted the same way in both operands), as
 // kFrags pieces of 8.
 template <int DC>
-__global__ __launch_bounds__(kThreads) void encode_split_kernel(const SplitParams p)
+__global__ __launch_bounds__(kThreads, 2) void encode_split_kernel(const SplitParams p)
 {
     constexpr int kFrags = DC / 16;
     __shared__ float4 red[kWaves][32];
@@ -94,6 +94,22 @@ __global__ __launch_bounds__(kThreads) void encode_split_kernel(const SplitParam
     const int per_slice = (tiles + p.k - 1) / p.k;
     const int t_begin = sl * per_slice, t_end = min(tiles, t_begin + per_slice);
     const int g = p.g;
+
+    // This wave's first tiles of the slice are requested before anything else and stay in registers for all
+    // blocks of vectors: their fetch overlaps the dependent chain below (candidates -> atom row -> residual),
+    // which does not need them.  (The last launch sweeps nothing.)
+    constexpr int kPrefetch = 256 / DC;  // tiles: 2 of 128 dimensions, 4 of 64 (64 registers either way)
+    auto load_tile = [&](int tile, uint4 (&a)[kFrags]) {
+        const __half *row = Dh + ((int64_t)tile * 32 + col) * DC + hf * (DC / 2);
+#pragma unroll
+        for (int j = 0; j < kFrags; ++j) a[j] = *reinterpret_cast<const uint4 *>(row + 8 * j);
+    };
+    uint4 pre[kPrefetch][kFrags];
+    if (g < p.s) {
+#pragma unroll
+        for (int q = 0; q < kPrefetch; ++q)
+            if (t_begin + wave + q * kWaves < t_end) load_tile(t_begin + wave + q * kWaves, pre[q]);
+    }
 
     for (int m0 = 0; m0 < p.M; m0 += 32) {
         // vector m of this dictionary: block h = (m / T) dict_count + dict, its token m % T
@@ -210,23 +226,13 @@ __global__ __launch_bounds__(kThreads) void encode_split_kernel(const SplitParam
         // ---- this wave's tiles of the slice: c[n] = hi . d_n + lo . d_n ---------------------------
         float ba = -1.0f, bc = 0.0f;
         int bi = 0;
-        auto load_tile = [&](int tile, uint4 (&a)[kFrags]) {
-            const __half *row = Dh + ((int64_t)tile * 32 + col) * DC + hf * (DC / 2);
-#pragma unroll
-            for (int j = 0; j < kFrags; ++j) a[j] = *reinterpret_cast<const uint4 *>(row + 8 * j);
-        };
-        uint4 a_cur[kFrags], a_next[kFrags];
-        int tile = t_begin + wave;
-        if (tile < t_end) load_tile(tile, a_cur);
-        for (; tile < t_end; tile += kWaves) {
-            const bool more = tile + kWaves < t_end;
-            if (more) load_tile(tile + kWaves, a_next);  // in flight during this tile's products
+        auto sweep_tile = [&](int tile, const uint4 (&a)[kFrags]) {
             floatx16 acc;
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
 #pragma unroll
             for (int j = 0; j < kFrags; ++j) {
-                const half8 av = *reinterpret_cast<const half8 *>(&a_cur[j]);
+                const half8 av = *reinterpret_cast<const half8 *>(&a[j]);
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, hi[j], acc, 0, 0, 0);
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, lo[j], acc, 0, 0, 0);
             }
@@ -236,10 +242,15 @@ __global__ __launch_bounds__(kThreads) void encode_split_kernel(const SplitParam
                 const float ab = fabsf(acc[r]);
                 if (ab > ba) { ba = ab; bi = tile * 32 + 8 * (r >> 2) + (r & 3) + 4 * hf; bc = acc[r]; }
             }
-            if (more) {
+        };
 #pragma unroll
-                for (int j = 0; j < kFrags; ++j) a_cur[j] = a_next[j];
-            }
+        for (int q = 0; q < kPrefetch; ++q)
+            if (t_begin + wave + q * kWaves < t_end) sweep_tile(t_begin + wave + q * kWaves, pre[q]);
+        // tiles beyond the prefetched ones
+        for (int tile = t_begin + wave + kPrefetch * kWaves; tile < t_end; tile += kWaves) {
+            uint4 a_cur[kFrags];
+            load_tile(tile, a_cur);
+            sweep_tile(tile, a_cur);
         }
         // the two lanes of a vector, then the waves
         take_better(ba, bi, bc, xchg32f(ba, hf), (int)xchg32((uint32_t)bi, hf), xchg32f(bc, hf));
