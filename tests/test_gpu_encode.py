@@ -514,3 +514,19 @@ def test_resident_encoder_is_refused_for_dictionaries_beyond_the_lds():
     X = torch.zeros(1, 200, 128, dtype=torch.float16, device="cuda")
     with pytest.raises(csr.CsrError, match="128 KB"):
         csr.csr_encode(X, D, 4, algo=csr.CSR_ENCODE_RESIDENT)
+
+
+def test_dictionaries_beyond_sixteen_bit_indices():
+    # 70016 atoms need 32-bit indices: the split encoder (few vectors) and the vector-ALU encoder (AUTO's choice for
+    # many vectors, the matrix-core kernel stops at 65536 atoms) against the oracle
+    N, d, s = 70016, 128, 3
+    D = synth.dictionary(81, "dict_k", 1, N, d, "f16")
+    X = synth.vectors(81, "keys", 1, 140, d, "f16", outliers=8)
+    Dg = torch.from_numpy(D).cuda()
+    for rows in (slice(0, 5), slice(0, 140)):
+        idx, coef = csr.csr_encode(torch.from_numpy(X[:, rows]).cuda(), Dg, s, idx_dtype=torch.int32)
+        torch.cuda.synchronize()
+        assert idx.dtype == torch.int32 and int(idx.max()) < N
+        _assert_ok(_compare(X[:, rows], D, s, idx.cpu().numpy(), coef.cpu().numpy()))
+    with pytest.raises(csr.CsrError, match="16-bit"):
+        csr.csr_encode(torch.from_numpy(X).cuda(), Dg, s, idx_dtype=torch.int16)
