@@ -279,7 +279,7 @@ __device__ __forceinline__ int resolve_token(const __half *__restrict__ Dh, int3
 template <int DC>
 __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
     const __half *__restrict__ X, const __half *__restrict__ Dict, void *__restrict__ idx_out,
-    void *__restrict__ coef_out, const float *__restrict__ dnorm, int64_t T, int32_t N, int32_t s, int32_t sn,
+    void *__restrict__ coef_out, const float *__restrict__ dnorm, int64_t T, int64_t M, int32_t N, int32_t s, int32_t sn,
     int64_t x_stride_h, int64_t x_stride_t, int32_t dict_count, int64_t code_stride_h, int32_t tiles_per_h,
     int32_t n_groups, int32_t idx16, int32_t coef16, uint32_t code_mask, int32_t first_round,
     float *__restrict__ res_norm2)
@@ -298,12 +298,13 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
     // that workgroups sharing a dictionary share an L2.
     int work = blockIdx.x;
     if ((n_groups & 7) == 0) work = (blockIdx.x & 7) * (n_groups >> 3) + (blockIdx.x >> 3);
-    // "head" hv = h * sn + ch is chunk ch of vector block h: a vector of DC dimensions on chunk ch of
-    // dictionary h % dict_count
-    const int hv = work / tiles_per_h;
-    const int tile_wg = work - hv * tiles_per_h;
-    const int h = hv / sn, ch = hv - h * sn;
-    const int dct = (h % dict_count) * sn + ch;
+    // Work is dealt per dictionary, not per vector block: dct = dictionary * sn + chunk owns the vectors of all
+    // blocks that use it (block h uses dictionary h % dict_count), numbered m = (h / dict_count) * T + t, in tiles
+    // of 256.  Blocks with few vectors that share a dictionary - a batch of sequences in a decoding step - then
+    // fill tiles together instead of taking a nearly empty one each.
+    const int dct = work / tiles_per_h;
+    const int tile_wg = work - dct * tiles_per_h;
+    const int dict = dct / sn, ch = dct - dict * sn;
     const __half *Dh = Dict + (int64_t)dct * N * DC;
     const int ntiles = N >> 5;
     const int nstages = (N + kStageAtoms - 1) / kStageAtoms;
@@ -342,15 +343,19 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
     // ---- load the vectors, scale by a power of two, split into hi + lo ---------------------------
     half8 hi[kBlocks][kFrags], lo[kBlocks][kFrags];
     bool valid[kBlocks];
-    int64_t tok[kBlocks];
+    int hblk[kBlocks];    // the vector's block and its position in the block
+    int64_t tpos[kBlocks];
     int sexp[kBlocks];
     float delta[kBlocks], rn2[kBlocks];
 #pragma unroll
     for (int bi = 0; bi < kBlocks; ++bi) {
-        tok[bi] = (int64_t)tile_wg * kTokPerWG + wave * kTokPerWave + bi * 32 + col;
-        valid[bi] = tok[bi] < T;
-        const int64_t tc = valid[bi] ? tok[bi] : T - 1;
-        const __half *xr = X + (int64_t)h * x_stride_h + tc * x_stride_t + ch * DC + hf * (DC / 2);
+        const int64_t m = (int64_t)tile_wg * kTokPerWG + wave * kTokPerWave + bi * 32 + col;
+        valid[bi] = m < M;
+        const int64_t mc = valid[bi] ? m : M - 1;  // tail lanes recompute the last vector, never store
+        const int rep_b = (int)(mc / T);
+        tpos[bi] = mc - rep_b * T;
+        hblk[bi] = rep_b * dict_count + dict;
+        const __half *xr = X + (int64_t)hblk[bi] * x_stride_h + tpos[bi] * x_stride_t + ch * DC + hf * (DC / 2);
         float xv[kFrags][8];
         float amax = 0.0f;
 #pragma unroll
@@ -612,7 +617,7 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
             rn2[bi] = r2;
             delta[bi] = 2.0f * dmax * (sqrtf(lo2) + kGammaAcc * sqrtf(r2));
             if (valid[bi]) {
-                const int64_t o = (int64_t)h * code_stride_h + (tok[bi] * sn + ch) * s + g;
+                const int64_t o = (int64_t)hblk[bi] * code_stride_h + (tpos[bi] * sn + ch) * s + g;
                 if (hf == 0) {
                     if (idx16) reinterpret_cast<uint16_t *>(idx_out)[o] = (uint16_t)best_n[bi];
                     else reinterpret_cast<int32_t *>(idx_out)[o] = best_n[bi];
@@ -627,7 +632,8 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
     if (res_norm2) {  // |R_{s+1}|^2, back in the input's scale
 #pragma unroll
         for (int bi = 0; bi < kBlocks; ++bi)
-            if (valid[bi] && hf == 0) res_norm2[((int64_t)h * T + tok[bi]) * sn + ch] = ldexpf(rn2[bi], -2 * sexp[bi]);
+            if (valid[bi] && hf == 0)
+                res_norm2[((int64_t)hblk[bi] * T + tpos[bi]) * sn + ch] = ldexpf(rn2[bi], -2 * sexp[bi]);
     }
 }
 
@@ -649,8 +655,9 @@ size_t encode_mfma_workspace_bytes(int32_t H, int64_t T, int32_t N, int32_t s)
 template <int DC>
 hipError_t launch_encode_mfma_t(const EncodeArgs &a)
 {
-    const int64_t tiles = (a.T + kTokPerWG - 1) / kTokPerWG;
-    const int64_t groups = tiles * a.H * a.sn;
+    const int64_t M = (int64_t)(a.H / a.dict_count) * a.T;  // vectors per dictionary
+    const int64_t tiles = (M + kTokPerWG - 1) / kTokPerWG;
+    const int64_t groups = tiles * a.dict_count * a.sn;
     if (groups > 0x7fffffffLL) return hipErrorInvalidValue;
     float *dnorm = reinterpret_cast<float *>(a.workspace);
     const int ntiles = a.N / 32;
@@ -682,7 +689,7 @@ hipError_t launch_encode_mfma_t(const EncodeArgs &a)
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(encode_mfma_kernel<DC>, dim3((unsigned)groups), dim3(kThreads), kLdsBytes, a.stream,
-                       (const __half *)a.X, (const __half *)a.D, a.idx, a.coef, dnorm, a.T, a.N, a.s, a.sn, a.x_stride_h,
+                       (const __half *)a.X, (const __half *)a.D, a.idx, a.coef, dnorm, a.T, M, a.N, a.s, a.sn, a.x_stride_h,
                        a.x_stride_t, a.dict_count, a.code_stride_h, (int32_t)tiles, (int32_t)groups, (int32_t)a.idx16, (int32_t)a.coef16, code_mask,
                        first_round, a.res_norm2);
     return hipGetLastError();

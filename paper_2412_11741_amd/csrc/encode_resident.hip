@@ -59,7 +59,7 @@ template <int DC> __device__ __forceinline__ int swz(int row) { return DC == 128
 template <int DC>
 __global__ __launch_bounds__(kThreads) void encode_resident_kernel(
     const __half *__restrict__ X, const __half *__restrict__ Dict, void *__restrict__ idx_out,
-    void *__restrict__ coef_out, int64_t T, int32_t N, int32_t s, int32_t sn, int64_t x_stride_h, int64_t x_stride_t,
+    void *__restrict__ coef_out, int64_t T, int64_t M, int32_t N, int32_t s, int32_t sn, int64_t x_stride_h, int64_t x_stride_t,
     int32_t dict_count, int64_t code_stride_h, int32_t tiles_per_h, int32_t idx16, int32_t coef16,
     float *__restrict__ res_norm2)
 {
@@ -72,11 +72,12 @@ __global__ __launch_bounds__(kThreads) void encode_resident_kernel(
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, hf = lane >> 5;
-    // "head" hv = h * sn + ch is chunk ch of vector block h, on chunk ch of dictionary h % dict_count
-    const int hv = blockIdx.x / tiles_per_h;
-    const int tile_wg = blockIdx.x - hv * tiles_per_h;
-    const int h = hv / sn, ch = hv - h * sn;
-    const __half *Dh = Dict + ((int64_t)(h % dict_count) * sn + ch) * N * DC;
+    // work is dealt per dictionary: dct = dictionary * sn + chunk owns the vectors of all blocks that use it
+    // (block h uses dictionary h % dict_count), numbered m = (h / dict_count) * T + t, in tiles of 512
+    const int dct = blockIdx.x / tiles_per_h;
+    const int tile_wg = blockIdx.x - dct * tiles_per_h;
+    const int dict = dct / sn, ch = dct - dict * sn;
+    const __half *Dh = Dict + (int64_t)dct * N * DC;
     const int ntiles = N >> 5;
 
     // ---- the dictionary, once: piece `pos` of row `row` goes to position pos ^ swz(row) ---------------
@@ -96,17 +97,20 @@ __global__ __launch_bounds__(kThreads) void encode_resident_kernel(
     for (int j = 0; j < kFrags; ++j) frag_off[j] = (uint32_t)(col * kRowBytes + (((hf * kFrags + j) ^ swz<DC>(col)) << 4));
 
     for (int bi = 0; bi < kBlocksPerWave; ++bi) {
-        const int64_t tok = (int64_t)tile_wg * kTokPerWG + (wave * kBlocksPerWave + bi) * 32 + col;
-        if ((int64_t)tile_wg * kTokPerWG + (wave * kBlocksPerWave + bi) * 32 >= T) break;  // wave-uniform
-        const bool valid = tok < T;
-        const int64_t tc = valid ? tok : T - 1;  // tail lanes recompute the last vector, never store
+        const int64_t m = (int64_t)tile_wg * kTokPerWG + (wave * kBlocksPerWave + bi) * 32 + col;
+        if ((int64_t)tile_wg * kTokPerWG + (wave * kBlocksPerWave + bi) * 32 >= M) break;  // wave-uniform
+        const bool valid = m < M;
+        const int64_t mc = valid ? m : M - 1;  // tail lanes recompute the last vector, never store
+        const int rep = (int)(mc / T);
+        const int64_t tok = mc - rep * T;     // position in its block
+        const int h = rep * dict_count + dict;
 
         // ---- load the vector, scale by a power of two, split into hi + lo -------------------------
         half8 hi[kFrags], lo[kFrags];
         int sexp = 0;
         float rn2;
         {
-            const __half *xr = X + (int64_t)h * x_stride_h + tc * x_stride_t + ch * DC + hf * (DC / 2);
+            const __half *xr = X + (int64_t)h * x_stride_h + tok * x_stride_t + ch * DC + hf * (DC / 2);
             float xv[kFrags][8];
             float amax = 0.0f;
 #pragma unroll
@@ -257,8 +261,9 @@ bool encode_resident_supported(const EncodeArgs &a)
 template <int DC>
 static hipError_t launch_resident_t(const EncodeArgs &a)
 {
-    const int64_t tiles = (a.T + kTokPerWG - 1) / kTokPerWG;
-    const int64_t groups = tiles * a.H * a.sn;
+    const int64_t M = (int64_t)(a.H / a.dict_count) * a.T;  // vectors per dictionary
+    const int64_t tiles = (M + kTokPerWG - 1) / kTokPerWG;
+    const int64_t groups = tiles * a.dict_count * a.sn;
     if (groups > 0x7fffffffLL) return hipErrorInvalidValue;
     const int lds_bytes = a.N * DC * 2;
     // per device, once: the dictionary needs more LDS than the default limit
@@ -274,7 +279,7 @@ static hipError_t launch_resident_t(const EncodeArgs &a)
         attr_set[dev].store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL(encode_resident_kernel<DC>, dim3((unsigned)groups), dim3(kThreads), lds_bytes, a.stream,
-                       (const __half *)a.X, (const __half *)a.D, a.idx, a.coef, a.T, a.N, a.s, a.sn, a.x_stride_h,
+                       (const __half *)a.X, (const __half *)a.D, a.idx, a.coef, a.T, M, a.N, a.s, a.sn, a.x_stride_h,
                        a.x_stride_t, a.dict_count, a.code_stride_h, (int32_t)tiles, (int32_t)a.idx16, (int32_t)a.coef16,
                        a.res_norm2);
     return hipGetLastError();

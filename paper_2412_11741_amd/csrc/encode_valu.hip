@@ -27,7 +27,7 @@ template <> struct Vec16<__half> { static constexpr int n = 8; __half v[8]; };
 template <int D_, typename TE, int W>
 __global__ __launch_bounds__(64 * W) void encode_valu_kernel(
     const TE *__restrict__ X, const TE *__restrict__ Dict, void *__restrict__ idx_out,
-    void *__restrict__ coef_out, int64_t T, int32_t N, int32_t s, int64_t x_stride_h,
+    void *__restrict__ coef_out, int64_t T, int64_t M, int32_t N, int32_t s, int64_t x_stride_h,
     int64_t x_stride_t, int32_t tiles_per_h, int32_t sn, int32_t dict_count, int64_t code_stride_h, int32_t idx16,
     int32_t coef16, float *__restrict__ res_norm2)
 {
@@ -37,19 +37,22 @@ __global__ __launch_bounds__(64 * W) void encode_valu_kernel(
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    // chunked vectors: "head" hv = h * sn + c is chunk c of block h, a vector of D_ dimensions of its own, on
-    // chunk c of dictionary h % dict_count
-    const int hv = blockIdx.x / tiles_per_h;
-    const int tile = blockIdx.x - hv * tiles_per_h;
-    const int h = hv / sn, ch = hv - h * sn;
-    const int64_t t = (int64_t)tile * 64 + lane;
-    const bool valid = t < T;
-    const int64_t tc = valid ? t : T - 1;  // tail lanes recompute the last vector, never store
+    // Work is dealt per dictionary: dct = dictionary * sn + chunk owns the vectors (chunks of D_ dimensions) of all
+    // blocks that use it (block h uses dictionary h % dict_count), numbered m = (h / dict_count) * T + t, 64 a tile
+    const int dct = blockIdx.x / tiles_per_h;
+    const int tile = blockIdx.x - dct * tiles_per_h;
+    const int dict = dct / sn, ch = dct - dict * sn;
+    const int64_t m = (int64_t)tile * 64 + lane;
+    const bool valid = m < M;
+    const int64_t mc = valid ? m : M - 1;  // tail lanes recompute the last vector, never store
+    const int rep = (int)(mc / T);
+    const int64_t t = mc - rep * T;
+    const int h = rep * dict_count + dict;
 
     constexpr int VN = Vec16<TE>::n;
     float R[D_];
     {
-        const TE *xr = X + (int64_t)h * x_stride_h + tc * x_stride_t + ch * D_;
+        const TE *xr = X + (int64_t)h * x_stride_h + t * x_stride_t + ch * D_;
 #pragma unroll
         for (int k = 0; k < D_; k += VN) {
             Vec16<TE> v = *reinterpret_cast<const Vec16<TE> *>(xr + k);
@@ -61,7 +64,7 @@ __global__ __launch_bounds__(64 * W) void encode_valu_kernel(
     const int slice = (N + W - 1) / W;
     const int n0 = wave * slice;
     const int n1 = min(N, n0 + slice);
-    const TE *Dh = Dict + ((int64_t)(h % dict_count) * sn + ch) * N * D_;
+    const TE *Dh = Dict + (int64_t)dct * N * D_;
 
     for (int g = 0; g < s; ++g) {
         float best = -1.0f, bc = 0.0f;
@@ -123,14 +126,15 @@ __global__ __launch_bounds__(64 * W) void encode_valu_kernel(
 template <int D_, typename TE>
 hipError_t launch_valu_t(const EncodeArgs &a)
 {
-    const int64_t tiles = (a.T + 63) / 64;
+    const int64_t M = (int64_t)(a.H / a.dict_count) * a.T;  // vectors per dictionary
+    const int64_t tiles = (M + 63) / 64;
     // More waves per workgroup when there are few vectors, so that a small job still spreads
     // over the chip; fewer (less redundant residual work) when there are many.
-    const int64_t groups = tiles * a.H * a.sn;
+    const int64_t groups = tiles * a.dict_count * a.sn;
     const dim3 grid((unsigned)groups);
 #define CSR_LAUNCH_VALU(W)                                                                      \
     hipLaunchKernelGGL((encode_valu_kernel<D_, TE, W>), grid, dim3(64 * W), 0, a.stream,         \
-                       (const TE *)a.X, (const TE *)a.D, a.idx, a.coef, a.T, a.N, a.s,          \
+                       (const TE *)a.X, (const TE *)a.D, a.idx, a.coef, a.T, M, a.N, a.s,       \
                        a.x_stride_h, a.x_stride_t, (int32_t)tiles, a.sn, a.dict_count, a.code_stride_h, \
                        (int32_t)a.idx16, (int32_t)a.coef16, a.res_norm2)
     // (8 waves = 2 per SIMD leaves each lane the 128+ registers its residual needs.)

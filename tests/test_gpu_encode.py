@@ -530,3 +530,27 @@ def test_dictionaries_beyond_sixteen_bit_indices():
         _assert_ok(_compare(X[:, rows], D, s, idx.cpu().numpy(), coef.cpu().numpy()))
     with pytest.raises(csr.CsrError, match="16-bit"):
         csr.csr_encode(torch.from_numpy(X).cuda(), Dg, s, idx_dtype=torch.int16)
+
+
+@pytest.mark.parametrize("algo", ["mfma", "valu", "resident"])
+def test_blocks_that_share_a_dictionary_are_packed_into_tiles_together(algo):
+    # 75 sequences x 4 heads with 3 new vectors each: 225 vectors per dictionary, spread over 75 blocks, written
+    # in place into a cache of codes; every block must get exactly its own vectors' codes
+    B, Hkv, T, T_max, N, d, s, pos = 75, 4, 3, 11, 512, 128, 5, 6
+    D = synth.dictionary(91, "dict_k", Hkv, N, d, "f16")
+    X = synth.vectors(91, "keys", B * Hkv, T, d, "f16", outliers=8)
+    ci = torch.full((B * Hkv, T_max, s), -3, dtype=torch.int16, device="cuda")
+    cc = torch.full((B * Hkv, T_max, s), 77.0, dtype=torch.float16, device="cuda")
+    rn = torch.full((B * Hkv, T), -1.0, dtype=torch.float32, device="cuda")
+    csr.csr_encode(torch.from_numpy(X).cuda(), torch.from_numpy(D).cuda(), s, algo=ALGOS[algo],
+                   idx=ci[:, pos:pos + T], coef=cc[:, pos:pos + T], res_norm2=rn)
+    torch.cuda.synchronize()
+    keep = torch.ones(T_max, dtype=torch.bool, device="cuda"); keep[pos:pos + T] = False
+    assert (ci[:, keep] == -3).all() and (cc[:, keep] == 77.0).all() and (rn >= 0).all()
+    blocks = [0, 1, 5, 150, 151, 298, 299]
+    Db = np.stack([D[h % Hkv] for h in blocks])
+    _assert_ok(_compare(X[blocks], Db, s, ci[:, pos:pos + T].cpu().numpy()[blocks], cc[:, pos:pos + T].cpu().numpy()[blocks]))
+    # and all blocks agree with a call that gives every block its own (repeated) dictionary
+    i2, c2 = csr.csr_encode(torch.from_numpy(X).cuda(), torch.from_numpy(np.tile(D, (B, 1, 1))).cuda(), s, algo=ALGOS[algo])
+    torch.cuda.synchronize()
+    assert torch.equal(i2, ci[:, pos:pos + T]) and torch.equal(c2, cc[:, pos:pos + T])
