@@ -46,5 +46,22 @@ def build(verbose: bool = False, extra=()) -> str:
     return LIB
 
 
+C_SMOKE_SRC = os.path.join(os.path.dirname(HERE), "tests", "c_abi", "smoke.c")
+C_SMOKE_BIN = os.path.join(HERE, "csr_c_smoke.bin")
+
+
+def build_c_smoke(verbose: bool = False) -> str:
+    """The plain-C user of the ABI (tests/c_abi/smoke.c), compiled by the host C compiler against the library."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = [os.environ.get("CC", "gcc"), "-std=c99", "-O1", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I", INCLUDE,
+           "-I", os.path.join(rocm, "include"), C_SMOKE_SRC, "-o", C_SMOKE_BIN, "-L", HERE, "-lcsr_hip",
+           "-L", os.path.join(rocm, "lib"), "-lamdhip64", "-lm", "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return C_SMOKE_BIN
+
+
 if __name__ == "__main__":
     print(build(verbose=True, extra=sys.argv[1:]))
+    print(build_c_smoke(verbose=True))

@@ -183,3 +183,12 @@ def test_binding_refuses_cpu_tensors():
     D = torch.zeros(1, 32, 128, dtype=torch.float16)
     with pytest.raises(ValueError, match="GPU tensor"):
         csr.csr_encode(X, D, 4)
+
+
+def test_the_header_is_plain_c99():
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    prog = '#include "csr.h"\nint main(void) { csr_encode_desc e; csr_decode_desc d; csr_reconstruct_desc r; (void)e; (void)d; (void)r; return 0; }\n'
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-I",
+                        os.path.join(root, "include"), "-x", "c", "-"], input=prog, text=True, capture_output=True)
+    assert r.returncode == 0, r.stderr
