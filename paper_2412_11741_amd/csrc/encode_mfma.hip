@@ -44,9 +44,10 @@
 // two MFMAs.  Dictionary stages (64 atoms, 16 KiB) go from global memory straight into LDS
 // (global_load_lds_dwordx4) through a ring of three buffers, fetched two stages ahead, 16-byte
 // chunks XOR-swizzled by the row number so that 16 consecutive rows read at the same logical chunk
-// cover all LDS banks.  Two 4-wave workgroups
-// share a CU (two waves per SIMD), so one workgroup's select / update phase (vector ALU, gathers)
-// overlaps the other's sweep (matrix cores).
+// cover all LDS banks.  Two waves per SIMD either way: two 4-wave workgroups
+// share a CU, so one workgroup's select / update phase (vector ALU, gathers) overlaps the other's
+// sweep (matrix cores), or - for launches large enough - one 8-wave workgroup has the CU, whose 512
+// vectors share every dictionary stage (half the stage traffic per MFMA).
 #include <atomic>
 #include <cstdio>
 #include <cstdlib>
@@ -62,13 +63,13 @@ typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kBlocks = 2;                            // 32-token blocks per wave
-constexpr int kWavesPerWG = 4;
-constexpr int kThreads = 64 * kWavesPerWG;            // 256
 constexpr int kTokPerWave = 32 * kBlocks;             // 64
-constexpr int kTokPerWG = kWavesPerWG * kTokPerWave;  // 256
+// Waves per workgroup W: 8 (512 vectors, one workgroup per CU) for launches that fill the chip that way - twice
+// the vectors share a dictionary stage, so half the stage traffic per MFMA, 3 % faster although the eight waves
+// then select and update at the same time - and 4 (256 vectors, two workgroups per CU) for smaller ones.
 constexpr int kStageBytes = 16384;                    // one LDS stage: rows unpadded, 16-byte pieces XOR-swizzled
 constexpr int kRing = 3;                              // stage buffers; stage st lives in buffer st % 3
-constexpr int kStageLoads = kStageBytes / (16 * kThreads);  // load instructions per lane and stage (4)
+template <int W> constexpr int stage_loads() { return kStageBytes / (16 * 64 * W); }  // load instructions per lane and stage
 // Shapes that follow from the vector length DC (128 or 64)
 template <int DC> struct Shape {
     static constexpr int kRowBytes = DC * 2;
@@ -83,7 +84,7 @@ template <int DC> struct Shape {
 };
 constexpr int kScratchPerWave = 1024;                 // LDS a wave uses to share one token's state
 constexpr int kScratchOff = kRing * kStageBytes;
-constexpr int kLdsBytes = kScratchOff + kWavesPerWG * kScratchPerWave;  // 52 KiB: two workgroups per CU
+template <int W> constexpr int lds_bytes() { return kScratchOff + W * kScratchPerWave; }  // 52 KiB (W = 4) | 56 KiB
 constexpr int kTrack = 4;                             // group maxima tracked per lane and sweep
 constexpr int kNormSlices = 8;                        // workgroups per dictionary in the norm pre-pass
 // fp32 accumulation error of a 128-term dot product of exact fp16 products, relative to |hi||d|:
@@ -150,7 +151,7 @@ __device__ __forceinline__ uint32_t stage_lane_offset(int wave, int lane)
     return (uint32_t)(row0 * S::kRowBytes + (((lane % S::kPieces) ^ S::swz(row0)) << 4));
 }
 
-template <int DC>
+template <int DC, int W>
 __device__ __forceinline__ void issue_stage(const __half *__restrict__ Dh, int stage, int32_t N, unsigned char *buf,
                                             int wave, int lane, uint32_t lane_off)
 {
@@ -158,11 +159,11 @@ __device__ __forceinline__ void issue_stage(const __half *__restrict__ Dh, int s
     const unsigned char *sbase = reinterpret_cast<const unsigned char *>(Dh) + (int64_t)stage * kStageBytes;
     const int rows_left = N - stage * S::kStageAtoms - (wave * S::kRowsPerKiB + lane / S::kPieces);  // > 0 for the rows that exist
 #pragma unroll
-    for (int i = 0; i < kStageLoads; ++i) {
-        if (kWavesPerWG * S::kRowsPerKiB * i < rows_left)
+    for (int i = 0; i < stage_loads<W>(); ++i) {
+        if (W * S::kRowsPerKiB * i < rows_left)
             __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void *)(sbase + i * 4096 + lane_off),
-                (__attribute__((address_space(3))) void *)(buf + (i * kWavesPerWG + wave) * 1024), 16, 0, 0);
+                (const __attribute__((address_space(1))) void *)(sbase + i * (W * 1024) + lane_off),
+                (__attribute__((address_space(3))) void *)(buf + (i * W + wave) * 1024), 16, 0, 0);
     }
 }
 
@@ -276,8 +277,8 @@ __device__ __forceinline__ int resolve_token(const __half *__restrict__ Dh, int3
     return __builtin_amdgcn_readfirstlane(bn);
 }
 
-template <int DC>
-__global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
+template <int DC, int W>
+__global__ __launch_bounds__(64 * W, 8 / W) void encode_mfma_kernel(
     const __half *__restrict__ X, const __half *__restrict__ Dict, void *__restrict__ idx_out,
     void *__restrict__ coef_out, const float *__restrict__ dnorm, int64_t T, int64_t M, int32_t N, int32_t s, int32_t sn,
     int64_t x_stride_h, int64_t x_stride_t, int32_t dict_count, int64_t code_stride_h, int32_t tiles_per_h,
@@ -311,8 +312,8 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
     const int nstages_full = N / kStageAtoms;
 
     const uint32_t lane_off = stage_lane_offset<DC>(wave, lane);
-    issue_stage<DC>(Dh, 0, N, lds, wave, lane, lane_off);  // in flight while the vectors are loaded
-    if (nstages > 1) issue_stage<DC>(Dh, 1, N, lds + kStageBytes, wave, lane, lane_off);
+    issue_stage<DC, W>(Dh, 0, N, lds, wave, lane, lane_off);  // in flight while the vectors are loaded
+    if (nstages > 1) issue_stage<DC, W>(Dh, 1, N, lds + kStageBytes, wave, lane, lane_off);
     // LDS byte offset, inside a 32-row tile, of this lane's A fragment j (row = col, piece kFrags hf + j)
     uint32_t frag_off[kFrags];
 #pragma unroll
@@ -349,7 +350,7 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
     float delta[kBlocks], rn2[kBlocks];
 #pragma unroll
     for (int bi = 0; bi < kBlocks; ++bi) {
-        const int64_t m = (int64_t)tile_wg * kTokPerWG + wave * kTokPerWave + bi * 32 + col;
+        const int64_t m = (int64_t)tile_wg * (W * kTokPerWave) + wave * kTokPerWave + bi * 32 + col;
         valid[bi] = m < M;
         const int64_t mc = valid[bi] ? m : M - 1;  // tail lanes recompute the last vector, never store
         const int rep_b = (int)(mc / T);
@@ -416,7 +417,7 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
         auto do_stage = [&](int st, auto buf_c) {
             constexpr int kBuf = decltype(buf_c)::value;
             const bool more = st + 2 < nstages;
-            if (more) issue_stage<DC>(Dh, st + 2, N, lds + ((kBuf + 2) % kRing) * kStageBytes, wave, lane, lane_off);
+            if (more) issue_stage<DC, W>(Dh, st + 2, N, lds + ((kBuf + 2) % kRing) * kStageBytes, wave, lane, lane_off);
             const int tiles_here = min(kStageTiles, ntiles - st * kStageTiles);
 #pragma unroll
             for (int rt = 0; rt < kStageTiles; ++rt) {
@@ -464,9 +465,9 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
                     }
                 }
             }
-            // Only a complete stage takes kStageLoads load instructions: behind the fetch of a partial last stage,
-            // "all but the newest kStageLoads" could still leave loads of the next stage to be swept in flight.
-            if (st + 2 < nstages_full) wait_vmem_but<kStageLoads>(); else wait_vmem();
+            // Only a complete stage takes the full count of load instructions: behind the fetch of a partial last
+            // stage, "all but the newest ones" could still leave loads of the next stage to be swept in flight.
+            if (st + 2 < nstages_full) wait_vmem_but<stage_loads<W>()>(); else wait_vmem();
             __syncthreads();
         };
         for (int st = 0; st < nstages; st += kRing) {
@@ -476,8 +477,8 @@ __global__ __launch_bounds__(kThreads, 2) void encode_mfma_kernel(
         }
         // all buffers are free now: fetch stages 0 and 1 for the next sweep behind the select phase
         if (g + 1 < s) {
-            issue_stage<DC>(Dh, 0, N, lds, wave, lane, lane_off);
-            if (nstages > 1) issue_stage<DC>(Dh, 1, N, lds + kStageBytes, wave, lane, lane_off);
+            issue_stage<DC, W>(Dh, 0, N, lds, wave, lane, lane_off);
+            if (nstages > 1) issue_stage<DC, W>(Dh, 1, N, lds + kStageBytes, wave, lane, lane_off);
         }
 
         // ---- select: the iteration's atom for every token, one 32-token block at a time -------
@@ -652,9 +653,10 @@ size_t encode_mfma_workspace_bytes(int32_t H, int64_t T, int32_t N, int32_t s)
     return r256((size_t)H * kNormSlices * sizeof(float));
 }
 
-template <int DC>
-hipError_t launch_encode_mfma_t(const EncodeArgs &a)
+template <int DC, int W>
+hipError_t launch_encode_mfma_w(const EncodeArgs &a, int cus)
 {
+    constexpr int kTokPerWG = W * kTokPerWave;
     const int64_t M = (int64_t)(a.H / a.dict_count) * a.T;  // vectors per dictionary
     const int64_t tiles = (M + kTokPerWG - 1) / kTokPerWG;
     const int64_t groups = tiles * a.dict_count * a.sn;
@@ -665,8 +667,35 @@ hipError_t launch_encode_mfma_t(const EncodeArgs &a)
     while ((1 << bits) < ntiles) ++bits;
     const uint32_t code_mask = (1u << bits) - 1u;
 
-    // per device, once: the kernel's LDS need is above the default limit, and the number of
-    // workgroups that start together (two per CU) decides which ones are held back at the start
+    // per device, once: the kernel's LDS need is above the default limit
+    static std::atomic<bool> attr_set[64];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (!attr_set[dev].load(std::memory_order_acquire)) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(encode_mfma_kernel<DC, W>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes<W>());
+        if (e != hipSuccess) return e;
+        attr_set[dev].store(true, std::memory_order_release);
+    }
+    // the workgroups that start together (two per CU with 4 waves each) are the ones held back at the start
+    const int32_t first_round = (W == 4 && groups > cus) ? 2 * cus : 0;
+
+    hipLaunchKernelGGL(dict_norm_kernel<DC>, dim3((unsigned)(a.dict_count * a.sn), kNormSlices), dim3(256), 0, a.stream,
+                       (const __half *)a.D, dnorm, a.N);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((encode_mfma_kernel<DC, W>), dim3((unsigned)groups), dim3(64 * W), lds_bytes<W>(), a.stream,
+                       (const __half *)a.X, (const __half *)a.D, a.idx, a.coef, dnorm, a.T, M, a.N, a.s, a.sn, a.x_stride_h,
+                       a.x_stride_t, a.dict_count, a.code_stride_h, (int32_t)tiles, (int32_t)groups, (int32_t)a.idx16, (int32_t)a.coef16, code_mask,
+                       first_round, a.res_norm2);
+    return hipGetLastError();
+}
+
+template <int DC>
+hipError_t launch_encode_mfma_t(const EncodeArgs &a)
+{
     static std::atomic<int> n_cus[64];
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -676,23 +705,14 @@ hipError_t launch_encode_mfma_t(const EncodeArgs &a)
         int v = 0;
         e = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev);
         if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(encode_mfma_kernel<DC>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-        if (e != hipSuccess) return e;
         n_cus[dev].store(v > 0 ? v : 1, std::memory_order_release);
     }
     const int cus = n_cus[dev].load(std::memory_order_relaxed);
-    const int32_t first_round = groups > cus ? 2 * cus : 0;
-
-    hipLaunchKernelGGL(dict_norm_kernel<DC>, dim3((unsigned)(a.dict_count * a.sn), kNormSlices), dim3(256), 0, a.stream,
-                       (const __half *)a.D, dnorm, a.N);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(encode_mfma_kernel<DC>, dim3((unsigned)groups), dim3(kThreads), kLdsBytes, a.stream,
-                       (const __half *)a.X, (const __half *)a.D, a.idx, a.coef, dnorm, a.T, M, a.N, a.s, a.sn, a.x_stride_h,
-                       a.x_stride_t, a.dict_count, a.code_stride_h, (int32_t)tiles, (int32_t)groups, (int32_t)a.idx16, (int32_t)a.coef16, code_mask,
-                       first_round, a.res_norm2);
-    return hipGetLastError();
+    // 512-vector workgroups (one per CU) once there is one for every CU
+    const int64_t M = (int64_t)(a.H / a.dict_count) * a.T;
+    const int64_t groups8 = (M + 8 * kTokPerWave - 1) / (8 * kTokPerWave) * a.dict_count * a.sn;
+    if (groups8 >= (int64_t)cus) return launch_encode_mfma_w<DC, 8>(a, cus);
+    return launch_encode_mfma_w<DC, 4>(a, cus);
 }
 
 hipError_t launch_encode_mfma(const EncodeArgs &a)
