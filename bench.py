@@ -34,7 +34,7 @@ PEAK_HBM_GBS = 8000.0           # MI355X HBM3E peak
 # HBM bytes per dispatch of the dominant kernel, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (each scaled by what the counter reads for a 1 GiB copy) on this workload: fetched + written.
 # The summary under profiles/ gives the commands and the raw counts.
-PMC_TRAFFIC_BYTES = {("llama7b_layer", "mfma"): 851.3e6 + 171.2e6}
+PMC_TRAFFIC_BYTES = {("llama7b_layer", "mfma"): 754.3e6 + 144.4e6}
 # The same for one csr_decode_attn call (its four kernels added up), per workload.
 PMC_DECODE_TRAFFIC_BYTES = {"llama7b_layer": 80.8e6 + 3.1e6, "long_context": 702.0e6 + 16.8e6,
                             "gqa_llama3_8b": 720.6e6 + 115.5e6}
