@@ -554,3 +554,17 @@ def test_blocks_that_share_a_dictionary_are_packed_into_tiles_together(algo):
     i2, c2 = csr.csr_encode(torch.from_numpy(X).cuda(), torch.from_numpy(np.tile(D, (B, 1, 1))).cuda(), s, algo=ALGOS[algo])
     torch.cuda.synchronize()
     assert torch.equal(i2, ci[:, pos:pos + T]) and torch.equal(c2, cc[:, pos:pos + T])
+
+
+def test_mfma_eight_wave_workgroups_with_a_ragged_last_tile():
+    # 64 dictionaries x 2100 vectors: five 512-vector workgroups per dictionary (at least one per CU in all, so the
+    # 8-wave configuration runs), the last with 52 vectors; 96 atoms leave a partial dictionary stage as well
+    H, T, N, d, s = 64, 2100, 96, 128, 3
+    D = synth.dictionary(95, "dict_k", H, N, d, "f16")
+    X = synth.vectors(95, "keys", H, T, d, "f16", outliers=8)
+    idx, coef = _gpu_encode(X, D, s, csr.CSR_ENCODE_MFMA)
+    rows = np.array([0, 63, 64, 511, 512, 2047, 2048, 2049, 2098, 2099])
+    _assert_ok(_compare(X, D, s, idx, coef, heads=[0, 1, 31, 62, 63], rows=rows))
+    iv, cv = _gpu_encode(X, D, s, csr.CSR_ENCODE_VALU)
+    same = (idx == iv).all(axis=-1).mean()
+    assert same > 0.995, same          # all vectors, against the other encoder: they may part at ties only
