@@ -113,6 +113,7 @@ size_t csr_encode_workspace_bytes(const csr_encode_desc *desc);
  *   D    [dict_count][N][d]              in       (chunked: [dict_count][s_n][N][d/s_n])
  *   idx  [H][T][s]  idx_dtype            out      (chunked: [H][T][s_n][s], atom numbers 0..N-1 per chunk;
  *   coef [H][T][s]  coef_dtype           out       blocks code_stride_h elements apart)
+ *   X and D must be 16-byte aligned; idx and coef to their element size.
  *   workspace: device memory, 256-byte aligned, >= csr_encode_workspace_bytes(); may be NULL
  *   when that is 0.  Contents are undefined before and after.
  */
@@ -166,6 +167,7 @@ size_t csr_decode_workspace_bytes(const csr_decode_desc *desc);
  *            larger values are clamped to T, negative ones to 0.
  *   out      [B][Hq][d]        out
  *   workspace: device memory, 256-byte aligned, >= csr_decode_workspace_bytes().
+ *   q, DK, DV, the four code streams and out must be 16-byte aligned.
  * Indices are not range-checked on the device: an index >= N reads outside the score table.
  */
 csr_status csr_decode_attn(const csr_decode_desc *desc, const void *q, const void *DK,

@@ -176,7 +176,8 @@ csr_status csr_encode(const csr_encode_desc *desc, const void *X, const void *D,
     if (desc->H == 0 || desc->T == 0) return CSR_OK;
     if (!X || !D || !idx || !coef) return fail(CSR_ERR_INVALID_ARG, "csr_encode: NULL data pointer");
     if (!aligned(X, 16) || !aligned(D, 16)) return fail(CSR_ERR_INVALID_ARG, "csr_encode: X and D must be 16-byte aligned");
-    if (!aligned(idx, 4) || !aligned(coef, 4)) return fail(CSR_ERR_INVALID_ARG, "csr_encode: idx and coef must be 4-byte aligned");
+    if (!aligned(idx, a.idx16 ? 2 : 4) || !aligned(coef, a.coef16 ? 2 : 4))
+        return fail(CSR_ERR_INVALID_ARG, "csr_encode: idx and coef must be aligned to their element size");
     const size_t need = encode_workspace(a, algo);
     if (need) {
         if (!workspace || workspace_bytes < need || !aligned(workspace, 256))
@@ -222,7 +223,8 @@ csr_status csr_reconstruct(const csr_reconstruct_desc *d, const void *D, const v
     if (d->H == 0 || d->T == 0) return CSR_OK;
     if (!D || !idx || !coef || !out) return fail(CSR_ERR_INVALID_ARG, "csr_reconstruct: NULL data pointer");
     if (!aligned(D, 16) || !aligned(out, 16)) return fail(CSR_ERR_INVALID_ARG, "csr_reconstruct: D and out must be 16-byte aligned");
-    if (!aligned(idx, 2) || !aligned(coef, 2)) return fail(CSR_ERR_INVALID_ARG, "csr_reconstruct: idx and coef must be aligned to their element size");
+    if (!aligned(idx, d->idx_dtype == CSR_I16 ? 2 : 4) || !aligned(coef, d->coef_dtype == CSR_F16 ? 2 : 4))
+        return fail(CSR_ERR_INVALID_ARG, "csr_reconstruct: idx and coef must be aligned to their element size");
     csr::ReconstructArgs a{};
     a.D = D; a.idx = idx; a.coef = coef; a.out = out;
     a.H = d->H; a.T = d->T; a.d = d->d; a.N = d->N; a.s = d->s; a.sn = sn;

@@ -108,6 +108,12 @@ def test_encode_null_and_misaligned_pointers_and_noop_sizes():
     assert lib.csr_encode(None, ok, ok, ok, ok, None, 0, None) == B.CSR_ERR_INVALID_ARG
     assert lib.csr_encode(ctypes.byref(d), None, ok, ok, ok, None, 0, None) == B.CSR_ERR_INVALID_ARG
     assert lib.csr_encode(ctypes.byref(d), ctypes.c_void_p(0x1004), ok, ok, ok, None, 0, None) == B.CSR_ERR_INVALID_ARG
+    # codes: aligned to their element size (a row of a cache of 16-bit codes may start at any even address)
+    odd, even = ctypes.c_void_p(0x1001), ctypes.c_void_p(0x1002)
+    assert lib.csr_encode(ctypes.byref(d), ok, ok, odd, ok, None, 0, None) == B.CSR_ERR_INVALID_ARG
+    assert lib.csr_encode(ctypes.byref(d), ok, ok, even, even, None, 0, None) == B.CSR_ERR_WORKSPACE   # passed the pointer checks
+    d32 = _enc(idx_dtype=B.CSR_I32, coef_dtype=B.CSR_F32)
+    assert lib.csr_encode(ctypes.byref(d32), ok, ok, even, ok, None, 0, None) == B.CSR_ERR_INVALID_ARG
     # empty problems are a no-op and touch nothing, even with NULL pointers
     assert lib.csr_encode(ctypes.byref(_enc(T=0)), None, None, None, None, None, 0, None) == B.CSR_OK
     assert lib.csr_encode(ctypes.byref(_enc(H=0)), None, None, None, None, None, 0, None) == B.CSR_OK

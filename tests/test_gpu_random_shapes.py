@@ -1,0 +1,107 @@
+"""GPU parity on seeded random shapes: every encoder that takes the shape, shared dictionaries, chunks, in-place
+codes - against the oracle's plain Matching Pursuit per chunk - and the decode call on the resulting codes."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2412_11741_amd as csr
+from paper_2412_11741_amd import synth
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+ALGOS = {"valu": csr.CSR_ENCODE_VALU, "mfma": csr.CSR_ENCODE_MFMA, "split": csr.CSR_ENCODE_SPLIT,
+         "resident": csr.CSR_ENCODE_RESIDENT}
+
+
+def _draw(seed):
+    rng = np.random.default_rng(1000 + seed)
+    sn = int(rng.choice([1, 1, 2]))
+    dc = int(rng.choice([64, 128]))
+    d = dc * sn
+    N = 32 * int(rng.integers(1, 40))
+    dicts = int(rng.integers(1, 5))
+    reps = int(rng.integers(1, 4))
+    T = int(rng.choice([1, 2, 7, 33, 70, 300]))
+    s = int(rng.integers(1, 10))
+    return dict(sn=sn, dc=dc, d=d, N=N, dicts=dicts, H=dicts * reps, T=T, s=s, pad=int(rng.integers(0, 3)))
+
+
+def _supported(c, algo):
+    M = c["H"] // c["dicts"] * c["T"]
+    if algo == "split":
+        return M <= 128
+    if algo == "resident":
+        return c["N"] * c["dc"] * 2 <= 128 * 1024
+    return True
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_encoders_on_random_shapes(seed):
+    c = _draw(seed)
+    H, T, N, d, dc, sn, s, dicts = (c[k] for k in ("H", "T", "N", "d", "dc", "sn", "s", "dicts"))
+    D = synth.dictionary(200 + seed, "dict_k", dicts * sn, N, dc, "f16").reshape(dicts, sn, N, dc)
+    X = synth.vectors(200 + seed, "keys", H, T, d, "f16", outliers=4)
+    Dg = torch.from_numpy(D if sn > 1 else D[:, 0]).cuda()
+    Xg = torch.from_numpy(X).cuda()
+    T_max = T + c["pad"]
+    D_blocks = np.stack([D[h % dicts] for h in range(H)])
+    results = {}
+    for name, algo in ALGOS.items():
+        if not _supported(c, name):
+            continue
+        shape = (H, T_max, sn, s) if sn > 1 else (H, T_max, s)
+        ci = torch.full(shape, -1, dtype=torch.int16, device="cuda")
+        cc = torch.full(shape, 9.0, dtype=torch.float16, device="cuda")
+        rn = torch.empty((H, T, sn) if sn > 1 else (H, T), dtype=torch.float32, device="cuda")
+        csr.csr_encode(Xg, Dg, s, algo=algo, idx=ci[:, c["pad"]:], coef=cc[:, c["pad"]:], res_norm2=rn)
+        torch.cuda.synchronize()
+        assert (ci[:, :c["pad"]] == -1).all() and (cc[:, :c["pad"]] == 9.0).all(), name
+        idx = ci[:, c["pad"]:].cpu().numpy().reshape(H, T, sn, s)
+        coef = cc[:, c["pad"]:].cpu().numpy().reshape(H, T, sn, s)
+        results[name] = idx
+        for h in range(H):
+            for ch in range(sn):
+                Xc = np.ascontiguousarray(X[h][:, ch * dc:(ch + 1) * dc])
+                io, co, diag = oracle.mp_encode(Xc, D_blocks[h, ch], s, diagnostics=True)
+                rep = parity.check_encode(Xc, D_blocks[h, ch], idx[h][:, ch], coef[h][:, ch], io,
+                                          co.astype(np.float16).astype(np.float64), diag, 1e-3, coef_storage="f16",
+                                          coef_o_exact=co)
+                assert rep.ok, (name, c, h, ch, rep.summary(), rep.failures[:3])
+        assert torch.isfinite(rn).all() and (rn >= 0).all(), name
+    assert results, c
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_decode_on_random_shapes_with_chunks(seed):
+    rng = np.random.default_rng(3000 + seed)
+    B, Hkv, G = int(rng.integers(1, 4)), int(rng.integers(1, 4)), int(rng.choice([1, 2, 4]))
+    T = int(rng.choice([1, 5, 100, 1025, 3000]))
+    N = 128 * int(rng.integers(1, 9))
+    snK, snV = int(rng.choice([1, 2])), int(rng.choice([1, 2, 4]))
+    sK, sV = int(rng.integers(1, 9)), int(rng.integers(1, 9))
+    d = 128
+    q = synth.queries(300 + seed, B, Hkv * G, d, "f16")
+    DK = synth.dictionary(300 + seed, "dict_k", Hkv * snK, N, d // snK, "f16").reshape(Hkv, snK, N, d // snK)
+    DV = synth.dictionary(300 + seed, "dict_v", Hkv * snV, N, d // snV, "f16").reshape(Hkv, snV, N, d // snV)
+    iK, cK = synth.random_codes(300 + seed, 0, B, Hkv, T, snK * sK, N, "f16", "i16")
+    iV, cV = synth.random_codes(300 + seed, 1, B, Hkv, T, snV * sV, N, "f16", "i16")
+    r = lambda a, sn, s: np.ascontiguousarray(a.reshape(B, Hkv, T, sn, s))
+    iK, cK, iV, cV = r(iK, snK, sK), r(cK, snK, sK), r(iV, snV, sV), r(cV, snV, sV)
+    lens = rng.integers(0, T + 1, size=B).astype(np.int32)
+    lens[0] = T
+    g = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    sq = lambda D, i, c, sn: (D, i, c) if sn > 1 else (D[:, 0], i[:, :, :, 0], c[:, :, :, 0])
+    aK, aV = sq(DK, iK, cK, snK), sq(DV, iV, cV, snV)
+    out = csr.csr_decode_attn(g(q), g(aK[0]), g(aK[1]), g(aK[2]), g(aV[0]), g(aV[1]), g(aV[2]),
+                              seq_lens=torch.from_numpy(lens).cuda())
+    torch.cuda.synchronize()
+    u = lambda i: i.view(np.uint16).astype(np.int64)
+    ref = oracle.decode_attn_chunked(q, DK, u(iK), cK, DV, u(iV), cV, seq_lens=lens)
+    out = out.cpu().numpy()
+    for b in range(B):
+        if lens[b] == 0:
+            assert np.all(out[b] == 0)
+    rel, _ = parity.decode_errors(out[lens > 0], ref[lens > 0])
+    assert rel.max() <= 2e-3, (seed, rel.max())
