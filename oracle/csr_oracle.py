@@ -192,6 +192,70 @@ def decode_attn_chunked(q, DK, idxK, coefK, DV, idxV, coefV, scale=None, seq_len
     return out
 
 
+def rope_rotate(X, positions, base, layout=0):
+    """Rotary position embedding of the rows of X [T, d] at integer positions [T] (float64).
+
+    Section "Position embedding makes nonstationary Keys" has the keys sparsely represented BEFORE the position
+    embedding, so attention must rotate the rebuilt keys.  The paper does not restate the embedding; this is the
+    public rotary definition: dimension pair k = 0 .. d/2-1 is turned by the angle p * base^(-2k/d) at position p.
+    layout 0 pairs dimension k with k + d/2, layout 1 pairs 2k with 2k + 1.
+    """
+    X = _f64(X)
+    T, d = X.shape
+    hd = d // 2
+    theta = np.asarray(base, dtype=np.float64) ** (-2.0 * np.arange(hd, dtype=np.float64) / d)
+    ang = np.asarray(positions, dtype=np.float64).reshape(T, 1) * theta.reshape(1, hd)
+    co, si = np.cos(ang), np.sin(ang)
+    if layout == 0:
+        a, b = X[:, :hd], X[:, hd:]
+    else:
+        a, b = X[:, 0::2], X[:, 1::2]
+    ra, rb = a * co - b * si, b * co + a * si
+    out = np.empty_like(X)
+    if layout == 0:
+        out[:, :hd], out[:, hd:] = ra, rb
+    else:
+        out[:, 0::2], out[:, 1::2] = ra, rb
+    return out
+
+
+def decode_attn_rope(q, DK, idxK, coefK, DV, idxV, coefV, rope_base, layout=0, pos0=0, scale=None, seq_lens=None):
+    """Attention over a cache whose keys were coded before the rotary embedding.
+
+    q [B, Hq, d] is the query as attention receives it (already rotated at its own position).  Cache token t of
+    every sequence sits at position pos0 + t: its key is rebuilt by Eq.12, K~_t = D_K r_t, rotated there, and
+    then plain softmax attention runs, written out in numpy float64.  Values carry no position (whole or
+    chunked codes: DV [Hkv, N, d] with idxV [B, Hkv, T, sV], or DV [Hkv, snV, N, d/snV] with idxV
+    [B, Hkv, T, snV, sV]); keys are whole vectors, DK [Hkv, N, d], idxK [B, Hkv, T, sK].
+    Returns out [B, Hq, d] float64.
+    """
+    q = _f64(q)
+    B, Hq, d = q.shape
+    Hkv = DK.shape[0]
+    G = Hq // Hkv
+    T = idxK.shape[2]
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    out = np.zeros((B, Hq, d))
+    for b in range(B):
+        L = T if seq_lens is None else int(seq_lens[b])
+        if L <= 0:
+            continue
+        pos = pos0 + np.arange(L)
+        for h in range(Hkv):
+            Kt = rope_rotate(reconstruct(idxK[b, h, :L], coefK[b, h, :L], DK[h]), pos, rope_base, layout)
+            if DV.ndim == 4:
+                Vt = np.concatenate([reconstruct(idxV[b, h, :L, c], coefV[b, h, :L, c], DV[h, c])
+                                     for c in range(DV.shape[1])], axis=1)
+            else:
+                Vt = reconstruct(idxV[b, h, :L], coefV[b, h, :L], DV[h])
+            for g in range(G):
+                sc = scale * (Kt @ q[b, h * G + g])
+                p = np.exp(sc - sc.max())
+                out[b, h * G + g] = (p / p.sum()) @ Vt
+    return out
+
+
 # --- storage accounting, "Analysis for CSR" ---------------------------------------------------
 
 def code_bytes(s, s_n=1, idx_bytes=2, coef_bytes=2):

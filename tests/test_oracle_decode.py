@@ -195,3 +195,110 @@ def test_chunked_attention_value_chunks_only_touch_their_own_dimensions():
     lens = np.array([7], dtype=np.int32)
     cut = oracle.decode_attn_chunked(q, DK, idxK[:, :, :7], coefK[:, :, :7], DV, idxV[:, :, :7], coefV[:, :, :7])
     assert np.allclose(oracle.decode_attn_chunked(q, DK, idxK, coefK, DV, idxV, coefV, seq_lens=lens), cut)
+
+
+# --- keys coded before the rotary embedding (Section "Position embedding makes nonstationary Keys") ------------
+
+def _complex_rotate(X, pos, base, layout):
+    """The rotary embedding as multiplication of complex pairs by e^{i p theta_k} (independent of the oracle's
+    real-arithmetic form)."""
+    T, d = X.shape
+    hd = d // 2
+    z = X[:, :hd] + 1j * X[:, hd:] if layout == 0 else X[:, 0::2] + 1j * X[:, 1::2]
+    k = np.arange(hd)
+    w = np.exp(1j * np.outer(np.asarray(pos, dtype=np.float64), np.exp(-2.0 * k / d * np.log(base))))
+    z = z * w
+    out = np.empty_like(X)
+    if layout == 0:
+        out[:, :hd], out[:, hd:] = z.real, z.imag
+    else:
+        out[:, 0::2], out[:, 1::2] = z.real, z.imag
+    return out
+
+
+def test_rotary_single_pair_closed_form():
+    # d = 2: one pair, theta_0 = 1; the unit vector e_0 at position p becomes (cos p, sin p)
+    pos = np.array([0, 1, 2, 7])
+    X = np.tile(np.array([[1.0, 0.0]]), (4, 1))
+    for layout in (0, 1):
+        out = oracle.rope_rotate(X, pos, 10000.0, layout)
+        np.testing.assert_allclose(out, np.stack([np.cos(pos), np.sin(pos)], axis=1), atol=1e-15)
+    # d = 4, base 16: theta = (1, 1/4); layout 0 pairs (0,2),(1,3), layout 1 pairs (0,1),(2,3)
+    x = np.array([[1.0, 2.0, 3.0, 4.0]])
+    p = 3.0
+    c0, s0, c1, s1 = np.cos(p), np.sin(p), np.cos(p / 4), np.sin(p / 4)
+    np.testing.assert_allclose(oracle.rope_rotate(x, [3], 16.0, 0)[0],
+                               [1 * c0 - 3 * s0, 2 * c1 - 4 * s1, 3 * c0 + 1 * s0, 4 * c1 + 2 * s1], atol=1e-14)
+    np.testing.assert_allclose(oracle.rope_rotate(x, [3], 16.0, 1)[0],
+                               [1 * c0 - 2 * s0, 2 * c0 + 1 * s0, 3 * c1 - 4 * s1, 4 * c1 + 3 * s1], atol=1e-14)
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+def test_rotary_matches_complex_multiplication_and_keeps_norms(layout):
+    rng = np.random.default_rng(40 + layout)
+    X = rng.standard_normal((50, 32))
+    pos = rng.integers(0, 100000, size=50)
+    out = oracle.rope_rotate(X, pos, 10000.0, layout)
+    np.testing.assert_allclose(out, _complex_rotate(X, pos, 10000.0, layout), rtol=1e-9, atol=1e-9)
+    np.testing.assert_allclose(np.linalg.norm(out, axis=1), np.linalg.norm(X, axis=1), rtol=1e-12)
+    # position 0 is the identity; rotations compose additively
+    np.testing.assert_array_equal(oracle.rope_rotate(X, np.zeros(50), 10000.0, layout), X)
+    twice = oracle.rope_rotate(oracle.rope_rotate(X, pos, 10000.0, layout), 17 - pos, 10000.0, layout)
+    np.testing.assert_allclose(twice, oracle.rope_rotate(X, np.full(50, 17), 10000.0, layout), atol=1e-9)
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+def test_rope_attention_against_library_attention_on_rotated_rebuilt_keys(layout):
+    rng = np.random.default_rng(42)
+    B, Hq, Hkv, T, d, N, sK, sV = 2, 4, 2, 37, 16, 24, 4, 3
+    q, DK, idxK, coefK, DV, idxV, coefV = _case(rng, B, Hq, Hkv, T, d, N, sK, sV)
+    out = oracle.decode_attn_rope(q, DK, idxK, coefK, DV, idxV, coefV, 500.0, layout, pos0=11, scale=0.4)
+    G = Hq // Hkv
+    for b in range(B):
+        for hq in range(Hq):
+            h = hq // G
+            K = _complex_rotate(_dense(idxK[b, h], coefK[b, h], DK[h]), 11 + np.arange(T), 500.0, layout)
+            ref = _sdpa(q[b, hq], K, _dense(idxV[b, h], coefV[b, h], DV[h]), 0.4)
+            np.testing.assert_allclose(out[b, hq], ref, rtol=1e-9, atol=1e-11)
+
+
+def test_rope_attention_depends_on_relative_positions_only():
+    # turning the query by +m and placing the cache m positions later leaves every score unchanged
+    rng = np.random.default_rng(43)
+    B, H, T, d, N, s = 1, 2, 29, 16, 20, 3
+    q, DK, idxK, coefK, DV, idxV, coefV = _case(rng, B, H, H, T, d, N, s, s)
+    base = 10000.0
+    q_at = lambda p: np.stack([oracle.rope_rotate(q[0], np.full(H, p), base, 0)])  # noqa: E731
+    a = oracle.decode_attn_rope(q_at(T), DK, idxK, coefK, DV, idxV, coefV, base, 0, pos0=0)
+    b = oracle.decode_attn_rope(q_at(T + 1000), DK, idxK, coefK, DV, idxV, coefV, base, 0, pos0=1000)
+    np.testing.assert_allclose(a, b, rtol=1e-9, atol=1e-11)
+    # and it is NOT the position-free attention (the rotation matters)
+    plain = oracle.decode_attn(q_at(T), DK, idxK, coefK, DV, idxV, coefV)
+    assert np.abs(a - plain).max() > 1e-3
+
+
+def test_rope_attention_single_token_and_lengths_and_chunked_values():
+    rng = np.random.default_rng(44)
+    B, H, T, d, N, s = 3, 2, 12, 8, 10, 2
+    q, DK, idxK, coefK, DV, idxV, coefV = _case(rng, B, H, H, T, d, N, s, s)
+    one = oracle.decode_attn_rope(q, DK, idxK[:, :, :1], coefK[:, :, :1], DV, idxV[:, :, :1], coefV[:, :, :1], 10000.0)
+    for b in range(B):
+        for h in range(H):
+            np.testing.assert_allclose(one[b, h], _dense(idxV[b, h, :1], coefV[b, h, :1], DV[h])[0], atol=1e-13)
+    lens = np.array([5, 0, 12], dtype=np.int32)
+    out = oracle.decode_attn_rope(q, DK, idxK, coefK, DV, idxV, coefV, 10000.0, seq_lens=lens)
+    assert np.all(out[1] == 0.0)
+    cut = oracle.decode_attn_rope(q[:1], DK, idxK[:1, :, :5], coefK[:1, :, :5], DV, idxV[:1, :, :5], coefV[:1, :, :5], 10000.0)
+    np.testing.assert_allclose(out[0], cut[0], rtol=1e-12)
+    # chunked values: two chunks on block-diagonal dictionaries equal whole-vector values
+    DVc = rng.standard_normal((H, 2, N, d // 2))
+    idxVc = rng.integers(0, N, size=(B, H, T, 2, s)).astype(np.int32)
+    coefVc = rng.standard_normal((B, H, T, 2, s))
+    DVw = np.zeros((H, 2 * N, d))
+    DVw[:, :N, :d // 2], DVw[:, N:, d // 2:] = DVc[:, 0], DVc[:, 1]
+    idxVw = np.concatenate([idxVc[:, :, :, 0], idxVc[:, :, :, 1] + N], axis=3)
+    coefVw = np.concatenate([coefVc[:, :, :, 0], coefVc[:, :, :, 1]], axis=3)
+    DKw = np.concatenate([DK, np.zeros_like(DK)], axis=1)  # same atom count for both whole dictionaries
+    a = oracle.decode_attn_rope(q, DK, idxK, coefK, DVc, idxVc, coefVc, 10000.0, 1, pos0=3)
+    b = oracle.decode_attn_rope(q, DKw, idxK, coefK, DVw, idxVw, coefVw, 10000.0, 1, pos0=3)
+    np.testing.assert_allclose(a, b, rtol=1e-12, atol=1e-14)
