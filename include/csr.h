@@ -126,8 +126,8 @@ csr_status csr_encode(const csr_encode_desc *desc, const void *X, const void *D,
  *   p       = softmax over the valid tokens t < len_b
  *   out     = DV[h]^T applied to hist, hist[n] = sum_{t,j : idxV = n} p_t * coefV[b][h][t][j]
  * which equals softmax attention over K~ = D_K r_K, V~ = D_V r_V of Eq.12.  No mask beyond the
- * sequence length, no position embedding (the paper's Section "KV cache in attention" sets it
- * aside).  A sequence with len_b = 0 yields zeros.  Accumulation is fp32, except the V-side histogram,
+ * sequence length; no position embedding (the paper's Section "KV cache in attention" sets it
+ * aside) unless rope_base is set, see there.  A sequence with len_b = 0 yields zeros.  Accumulation is fp32, except the V-side histogram,
  * which is summed exactly in 64-bit fixed point (the unit is a power of two, 2^-30 of the largest value
  * coefficient among the first 1024 tokens of each chunk of at most 16384 tokens), so the result does not depend on
  * the order in which the hardware serves the scatter: the same inputs give the same bits on every run.
@@ -150,6 +150,18 @@ typedef struct {
     int32_t idx_dtype;  /* csr_itype of idxK and idxV                                       */
     int32_t out_dtype;  /* csr_dtype of out                                                 */
     uint32_t flags;     /* must be 0                                                        */
+    float rope_base;    /* 0: the cached keys are in the frame of the query (no position embedding, or keys
+                           coded after it).  > 1: the keys were coded BEFORE the rotary position embedding
+                           (Section "Position embedding makes nonstationary Keys"): cache token t is rebuilt by
+                           Eq.12 and turned to position rope_pos0 + t, frequency pair k by the angle
+                           position * rope_base^(-2k/d); q is the query as attention receives it, already
+                           turned at its own position.  Supported with the paper's storage types (fp16 q and
+                           dictionaries, 16-bit indices, fp16 coefficients), whole-vector keys (snK <= 1),
+                           sK a multiple of 4 and a key dictionary of at most 128 KB (N <= 512): the kernel
+                           keeps it in LDS.  Scores then carry the rounding of the turned query to fp16
+                           (relative 2^-11 per component) instead of fp32 accuracy.               */
+    int32_t rope_layout; /* 0: pair k is dimensions (k, k + d/2); 1: dimensions (2k, 2k + 1)    */
+    int64_t rope_pos0;  /* position of cache token 0 of every sequence; 0 .. 2^40              */
 } csr_decode_desc;
 
 /* Bytes of device scratch csr_decode_attn needs; (size_t)-1 if the descriptor is invalid. */

@@ -47,7 +47,8 @@ class DecodeDesc(ctypes.Structure):
                 ("snV", ctypes.c_int32), ("scale", ctypes.c_float),
                 ("q_dtype", ctypes.c_int32), ("dict_dtype", ctypes.c_int32),
                 ("coef_dtype", ctypes.c_int32), ("idx_dtype", ctypes.c_int32),
-                ("out_dtype", ctypes.c_int32), ("flags", ctypes.c_uint32)]
+                ("out_dtype", ctypes.c_int32), ("flags", ctypes.c_uint32),
+                ("rope_base", ctypes.c_float), ("rope_layout", ctypes.c_int32), ("rope_pos0", ctypes.c_int64)]
 
 
 class CsrError(RuntimeError):
@@ -217,7 +218,8 @@ def csr_reconstruct(D, idx, coef, out=None, out_dtype=None):
     return out
 
 
-def decode_desc(q, DK, idxK, coefK, idxV, sV=None, scale=0.0, out_dtype=None):
+def decode_desc(q, DK, idxK, coefK, idxV, sV=None, scale=0.0, out_dtype=None, rope_base=0.0, rope_layout=0,
+                rope_pos0=0):
     """Descriptor from tensor shapes.  Whole-vector codes: DK [Hkv, N, d], idx [B, Hkv, T, s].  Chunked codes:
     DK [Hkv, sn, N, d/sn], idx [B, Hkv, T, sn, s] (keys and values may differ in sn and s)."""
     B, Hq, d = q.shape
@@ -228,7 +230,8 @@ def decode_desc(q, DK, idxK, coefK, idxV, sV=None, scale=0.0, out_dtype=None):
     return DecodeDesc(B=B, Hq=Hq, Hkv=Hkv, T=T, d=d, N=N, sK=sK, sV=idxV.shape[-1], snK=snK, snV=snV,
                       scale=float(scale),
                       q_dtype=_DT[q.dtype], dict_dtype=_DT[DK.dtype], coef_dtype=_DT[coefK.dtype],
-                      idx_dtype=_IT[idxK.dtype], out_dtype=_DT[out_dtype or q.dtype], flags=0)
+                      idx_dtype=_IT[idxK.dtype], out_dtype=_DT[out_dtype or q.dtype], flags=0,
+                      rope_base=float(rope_base), rope_layout=int(rope_layout), rope_pos0=int(rope_pos0))
 
 
 def csr_decode_workspace_bytes(desc):
@@ -239,9 +242,10 @@ def csr_decode_workspace_bytes(desc):
 
 
 def csr_decode_attn(q, DK, idxK, coefK, DV, idxV, coefV, scale=0.0, seq_lens=None, out=None,
-                    out_dtype=None, workspace=None):
+                    out_dtype=None, workspace=None, rope_base=0.0, rope_layout=0, rope_pos0=0):
     """Decode attention on codes.  q [B, Hq, d]; DK/DV [Hkv, N, d]; codes [B, Hkv, T, s*] -> out [B, Hq, d].
-    Chunked codes: DK [Hkv, sn, N, d/sn] with codes [B, Hkv, T, sn, s] (keys and values independently)."""
+    Chunked codes: DK [Hkv, sn, N, d/sn] with codes [B, Hkv, T, sn, s] (keys and values independently).
+    rope_base > 1: the keys were coded before the rotary embedding; cache token t sits at position rope_pos0 + t."""
     for name, t in (("q", q), ("DK", DK), ("idxK", idxK), ("coefK", coefK), ("DV", DV), ("idxV", idxV),
                     ("coefV", coefV)):
         _dev(t, name)
@@ -257,7 +261,8 @@ def csr_decode_attn(q, DK, idxK, coefK, DV, idxV, coefV, scale=0.0, seq_lens=Non
             raise ValueError(f"{what} dictionary shape {tuple(D_.shape)} does not match its codes (expected {want})")
     if idxV.shape[:3] != idxK.shape[:3] or coefK.shape != idxK.shape or coefV.shape != idxV.shape:
         raise ValueError("code tensors disagree in shape")
-    desc = decode_desc(q, DK, idxK, coefK, idxV, scale=scale, out_dtype=out_dtype)
+    desc = decode_desc(q, DK, idxK, coefK, idxV, scale=scale, out_dtype=out_dtype, rope_base=rope_base,
+                       rope_layout=rope_layout, rope_pos0=rope_pos0)
     if out is None:
         out = torch.empty(q.shape, dtype=out_dtype or q.dtype, device=q.device)
     need = csr_decode_workspace_bytes(desc)

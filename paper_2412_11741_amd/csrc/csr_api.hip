@@ -138,7 +138,23 @@ csr_status check_decode_desc(const csr_decode_desc *d, csr::DecodePlan *plan)
         if (snK * d->sK > 32 || snV * d->sV > 32)
             return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: more than 32 pairs per token and stream (sn * s)");
     }
-    if (!csr::plan_decode(d->B, d->Hq, d->Hkv, d->T, d->d, d->N, snK, snV, plan))
+    const bool rope = d->rope_base != 0.0f;
+    if (rope) {
+        if (!(d->rope_base > 1.0f) || std::isinf(d->rope_base))
+            return fail(CSR_ERR_INVALID_ARG, "csr_decode_attn: rope_base must be 0 (off) or a finite number above 1");
+        if (d->rope_layout != 0 && d->rope_layout != 1)
+            return fail(CSR_ERR_INVALID_ARG, "csr_decode_attn: rope_layout=%d must be 0 or 1", d->rope_layout);
+        if (d->rope_pos0 < 0 || d->rope_pos0 > (int64_t)1 << 40)
+            return fail(CSR_ERR_INVALID_ARG, "csr_decode_attn: rope_pos0 outside 0 .. 2^40");
+        if (d->q_dtype != CSR_F16 || d->dict_dtype != CSR_F16 || d->coef_dtype != CSR_F16 || d->idx_dtype != CSR_I16)
+            return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: rotary keys need fp16 queries, dictionaries and coefficients and 16-bit indices");
+        if (!csr::decode_rope_shape_supported(d->d, d->N, d->sK, snK))
+            return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: rotary keys need whole-vector key codes, sK a multiple of 4 and a key "
+                                             "dictionary of at most 128 KB (N=%d, sK=%d, snK=%d)", d->N, d->sK, snK);
+    } else if (d->rope_layout != 0 || d->rope_pos0 != 0) {
+        return fail(CSR_ERR_INVALID_ARG, "csr_decode_attn: rope_layout and rope_pos0 must be 0 when rope_base is 0");
+    }
+    if (!csr::plan_decode(d->B, d->Hq, d->Hkv, d->T, d->d, d->N, snK, snV, rope, plan))
         return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: N=%d atoms do not fit the LDS-resident score and histogram tables", d->N);
     return CSR_OK;
 }
@@ -273,6 +289,7 @@ csr_status csr_decode_attn(const csr_decode_desc *desc, const void *q, const voi
     a.T = desc->T; a.d = desc->d; a.N = desc->N; a.sK = desc->sK; a.sV = desc->sV;
     a.snK = desc->snK ? desc->snK : 1; a.snV = desc->snV ? desc->snV : 1;
     a.scale = desc->scale > 0.0f ? desc->scale : 1.0f / std::sqrt((float)desc->d);
+    a.rope_base = desc->rope_base; a.rope_layout = desc->rope_layout; a.rope_pos0 = desc->rope_pos0;
     a.q16 = desc->q_dtype == CSR_F16;
     a.dict16 = desc->dict_dtype == CSR_F16;
     a.coef16 = desc->coef_dtype == CSR_F16;

@@ -86,14 +86,23 @@ struct DecodeArgs {
     int32_t d, N, sK, sV;  // N atoms per (chunk) dictionary, sK / sV pairs per chunk
     int32_t snK, snV;      // chunks per head vector (>= 1)
     float scale;
+    float rope_base;       // > 0: keys were coded before the rotary embedding (theta_k = rope_base^(-2k/d))
+    int32_t rope_layout;   // 0: pair k = dimensions (k, k + d/2); 1: (2k, 2k + 1)
+    int64_t rope_pos0;     // position of cache token 0
     bool q16, dict16, coef16, idx16, out16;
     void *workspace;
     hipStream_t stream;
 };
 
 // Fills the plan; returns false if no kernel configuration fits (e.g. N too large for LDS).
+// rope: the plan is for the kernel that keeps the key dictionary in LDS (keys coded before the rotary embedding).
 bool plan_decode(int32_t B, int32_t Hq, int32_t Hkv, int64_t T, int32_t d, int32_t N, int32_t snK, int32_t snV,
-                 DecodePlan *p);
+                 bool rope, DecodePlan *p);
 hipError_t launch_decode(const DecodeArgs &a, const DecodePlan &p);
+
+// Streaming kernel for keys coded before the rotary embedding (decode_rope.hip); fills the same chunk histograms,
+// maxima and sums as the position-free one.
+bool decode_rope_shape_supported(int32_t d, int32_t N, int32_t sK, int32_t snK);
+hipError_t launch_stream_rope(const DecodeArgs &a, const DecodePlan &p, float *hist, float *ml);
 
 }  // namespace csr

@@ -30,43 +30,18 @@
 #include <cmath>
 
 #include "csr_internal.h"
+#include "decode_common.h"
 
 namespace csr {
 namespace {
 
-constexpr int kStreamThreads = 1024;  // 16 waves: enough loads in flight with one workgroup per CU
-constexpr int kStreamWaves = kStreamThreads / 64;
-constexpr int kMaxDevices = 64;      // devices a process may use this library on
-constexpr int kMaxTPT = 16;           // tokens per thread and chunk: their scores stay in registers
+using namespace dec;
+
 constexpr int kOutAtomsF16 = 128;     // atoms of D_V per out_kernel workgroup, fp16 dictionary
 constexpr int kOutAtomsF32 = 64;      // same, fp32 dictionary (the slice sits in LDS in its own type)
 constexpr int kQdAtoms = 64;          // atoms of D_K per qd_kernel workgroup
 constexpr int kQdTiles = 2;           // 32-atom tiles per wave of qd_mfma_kernel
 constexpr int kQTile = 32;            // queries staged in LDS at a time by qd_kernel
-constexpr int kMaxChunks = 64;
-constexpr size_t kLdsBudget = 150 * 1024;
-
-__device__ __forceinline__ float h2f(__half v) { return __half2float(v); }
-
-template <typename T> __device__ __forceinline__ void load8(const T *p, float (&o)[8]);
-template <> __device__ __forceinline__ void load8<__half>(const __half *p, float (&o)[8])
-{
-    const uint4 raw = *reinterpret_cast<const uint4 *>(p);
-    const __half2 *h2 = reinterpret_cast<const __half2 *>(&raw);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const float2 f = __half22float2(h2[j]);
-        o[2 * j] = f.x;
-        o[2 * j + 1] = f.y;
-    }
-}
-template <> __device__ __forceinline__ void load8<float>(const float *p, float (&o)[8])
-{
-    const float4 a = *reinterpret_cast<const float4 *>(p);
-    const float4 b = *reinterpret_cast<const float4 *>(p + 4);
-    o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w;
-    o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
-}
 
 // ---------------------------------------------------------------------------------------------
 // qd[b][h][gs][n][gg] = scale * q[b][h*G + gs*GB + gg] . DK[h][n]
@@ -222,99 +197,6 @@ __global__ __launch_bounds__(256) void qd_mfma_kernel(const __half *__restrict__
         }
     }
 }
-
-// ---------------------------------------------------------------------------------------------
-// Code-stream loads: PV pairs of one token at a time, widened to int / float registers.
-template <typename TI, int PV> struct IdxLoad;
-template <> struct IdxLoad<uint16_t, 8> {
-    static __device__ __forceinline__ void ld(const uint16_t *p, int (&o)[8]) {
-        const uint4 r = *reinterpret_cast<const uint4 *>(p);
-        o[0] = r.x & 0xffff; o[1] = r.x >> 16; o[2] = r.y & 0xffff; o[3] = r.y >> 16;
-        o[4] = r.z & 0xffff; o[5] = r.z >> 16; o[6] = r.w & 0xffff; o[7] = r.w >> 16;
-    }
-};
-template <> struct IdxLoad<uint16_t, 4> {
-    static __device__ __forceinline__ void ld(const uint16_t *p, int (&o)[4]) {
-        const uint2 r = *reinterpret_cast<const uint2 *>(p);
-        o[0] = r.x & 0xffff; o[1] = r.x >> 16; o[2] = r.y & 0xffff; o[3] = r.y >> 16;
-    }
-};
-template <> struct IdxLoad<uint16_t, 1> {
-    static __device__ __forceinline__ void ld(const uint16_t *p, int (&o)[1]) { o[0] = p[0]; }
-};
-template <> struct IdxLoad<int32_t, 8> {
-    static __device__ __forceinline__ void ld(const int32_t *p, int (&o)[8]) {
-        const int4 a = *reinterpret_cast<const int4 *>(p);
-        const int4 b = *reinterpret_cast<const int4 *>(p + 4);
-        o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w; o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
-    }
-};
-template <> struct IdxLoad<int32_t, 4> {
-    static __device__ __forceinline__ void ld(const int32_t *p, int (&o)[4]) {
-        const int4 a = *reinterpret_cast<const int4 *>(p);
-        o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w;
-    }
-};
-template <> struct IdxLoad<int32_t, 1> {
-    static __device__ __forceinline__ void ld(const int32_t *p, int (&o)[1]) { o[0] = p[0]; }
-};
-
-template <typename TC, int PV> struct CoefLoad;
-template <> struct CoefLoad<__half, 8> {
-    static __device__ __forceinline__ void ld(const __half *p, float (&o)[8]) { load8<__half>(p, o); }
-};
-template <> struct CoefLoad<__half, 4> {
-    static __device__ __forceinline__ void ld(const __half *p, float (&o)[4]) {
-        const uint2 raw = *reinterpret_cast<const uint2 *>(p);
-        const __half2 *h2 = reinterpret_cast<const __half2 *>(&raw);
-        const float2 f0 = __half22float2(h2[0]), f1 = __half22float2(h2[1]);
-        o[0] = f0.x; o[1] = f0.y; o[2] = f1.x; o[3] = f1.y;
-    }
-};
-template <> struct CoefLoad<__half, 1> {
-    static __device__ __forceinline__ void ld(const __half *p, float (&o)[1]) { o[0] = h2f(p[0]); }
-};
-template <> struct CoefLoad<float, 8> {
-    static __device__ __forceinline__ void ld(const float *p, float (&o)[8]) { load8<float>(p, o); }
-};
-template <> struct CoefLoad<float, 4> {
-    static __device__ __forceinline__ void ld(const float *p, float (&o)[4]) {
-        const float4 a = *reinterpret_cast<const float4 *>(p);
-        o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w;
-    }
-};
-template <> struct CoefLoad<float, 1> {
-    static __device__ __forceinline__ void ld(const float *p, float (&o)[1]) { o[0] = p[0]; }
-};
-
-__device__ __forceinline__ float wave_max(float v)
-{
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
-    return v;
-}
-__device__ __forceinline__ float wave_sum(float v)
-{
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
-    return v;
-}
-
-// x as a 64-bit fixed-point number in units of 2^-32 (two's complement); needs |x| < 2^31.
-// x - floor(x) is exact in fp32.  The caller scales p * c by a power of two first (see stream_kernel),
-// so that the unit follows the data and the result does not depend on the scale of the coefficients.
-__device__ __forceinline__ unsigned long long to_fixed(float x)
-{
-    const float fl = floorf(x);
-    const int hi = (int)fl;
-    const unsigned lo = (unsigned)((x - fl) * 4294967296.0f);
-    return ((unsigned long long)(unsigned)hi << 32) | lo;
-}
-__device__ __forceinline__ float from_fixed(unsigned long long v)
-{
-    return (float)(int)(unsigned)(v >> 32) + (float)(unsigned)(v & 0xffffffffull) * 2.3283064365386963e-10f;
-}
-
 // One workgroup: chunk c of the tokens of (sequence b, KV head h, group slice gs).
 // LDS: table as fp32 scores q.d, [N][GB] (pass 1), then as 64-bit histogram, [GB][N] (pass 2: one table
 // per query head, so that the scatter of one head spreads over all banks) | red[waves][GB]
@@ -773,16 +655,18 @@ hipError_t launch_stream_gb(const DecodeArgs &a, const DecodePlan &p, float *qd,
 }  // namespace
 
 bool plan_decode(int32_t B, int32_t Hq, int32_t Hkv, int64_t T, int32_t d, int32_t N, int32_t snK, int32_t snV,
-                 DecodePlan *p)
+                 bool rope, DecodePlan *p)
 {
-    (void)d;
     const size_t NK = (size_t)snK * N, NV = (size_t)snV * N;  // entries of the score table / of a histogram
     const int G = Hq / Hkv;
     int GB = 0;
     for (int cand : {4, 2, 1}) {
         if (G % cand != 0) continue;
-        // score table (fp32) and histogram (64-bit) share the space: the larger one counts
-        const size_t lds = (NK * 4 > NV * 8 ? NK * 4 : NV * 8) * cand + (size_t)kStreamWaves * (cand + 1) * sizeof(float);
+        if (rope && cand > 2) continue;  // the rotary kernel keeps a turned query per head in registers
+        // score table (fp32; with rotary keys the dictionary itself, fp16 rows) and histogram (64-bit) share the
+        // space: the larger one counts
+        const size_t first = rope ? (size_t)N * d * 2 : NK * 4 * cand;
+        const size_t lds = (first > NV * 8 * cand ? first : NV * 8 * cand) + (size_t)kStreamWaves * (cand + 1) * sizeof(float);
         if (lds <= kLdsBudget) { GB = cand; p->lds_bytes = lds; break; }
     }
     if (!GB) return false;
@@ -822,6 +706,10 @@ hipError_t launch_decode(const DecodeArgs &a, const DecodePlan &p)
     float *ml = reinterpret_cast<float *>(ws + p.off_ml);
     float *acc = reinterpret_cast<float *>(ws + p.off_acc);
 
+    if (a.rope_base > 0.0f) {
+        const hipError_t e = launch_stream_rope(a, p, hist, ml);
+        if (e != hipSuccess) return e;
+    } else {
     {
         const dim3 grid((unsigned)((a.N + kQdAtoms - 1) / kQdAtoms), (unsigned)a.Hkv);
 #define CSR_QD(TQ, TD)                                                                              \
@@ -846,6 +734,7 @@ hipError_t launch_decode(const DecodeArgs &a, const DecodePlan &p)
             default: e = launch_stream_gb<1>(a, p, qd, hist, ml); break;
         }
         if (e != hipSuccess) return e;
+    }
     }
     const int out_atoms = a.dict16 ? kOutAtomsF16 : kOutAtomsF32;
     const int nslices = (a.snV * a.N + out_atoms - 1) / out_atoms;

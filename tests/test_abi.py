@@ -139,6 +139,17 @@ def _dec(**kw):
     (dict(snV=2, q_dtype=B.CSR_F32), B.CSR_ERR_UNSUPPORTED), (dict(snV=2, dict_dtype=B.CSR_F32), B.CSR_ERR_UNSUPPORTED),
     (dict(snK=2, N=4000), B.CSR_ERR_UNSUPPORTED), (dict(snV=8, sV=8), B.CSR_ERR_UNSUPPORTED),
     (dict(snV=8, N=8192, Hq=2), B.CSR_ERR_UNSUPPORTED),   # 8 x 8192 histogram bins of 8 bytes exceed the LDS
+    # keys coded before the rotary embedding: the key dictionary has to fit the LDS, paper's storage types only
+    (dict(rope_base=10000.0), B.CSR_ERR_UNSUPPORTED),                      # N = 4096
+    (dict(rope_base=10000.0, N=512, sK=6), B.CSR_ERR_UNSUPPORTED),
+    (dict(rope_base=10000.0, N=512, snK=2, sK=4), B.CSR_ERR_UNSUPPORTED),
+    (dict(rope_base=10000.0, N=512, coef_dtype=B.CSR_F32), B.CSR_ERR_UNSUPPORTED),
+    (dict(rope_base=10000.0, N=512, idx_dtype=B.CSR_I32), B.CSR_ERR_UNSUPPORTED),
+    (dict(rope_base=1.0, N=512), B.CSR_ERR_INVALID_ARG), (dict(rope_base=-3.0, N=512), B.CSR_ERR_INVALID_ARG),
+    (dict(rope_base=float("inf"), N=512), B.CSR_ERR_INVALID_ARG),
+    (dict(rope_base=10000.0, N=512, rope_layout=2), B.CSR_ERR_INVALID_ARG),
+    (dict(rope_base=10000.0, N=512, rope_pos0=-1), B.CSR_ERR_INVALID_ARG),
+    (dict(rope_layout=1), B.CSR_ERR_INVALID_ARG), (dict(rope_pos0=5), B.CSR_ERR_INVALID_ARG),   # set without rope_base
 ])
 def test_decode_rejects_bad_descriptors_before_launch(kw, status):
     lib = csr.lib()
@@ -159,6 +170,13 @@ def test_decode_workspace_is_required_and_checked():
     assert lib.csr_decode_attn(ctypes.byref(d), p, p, p, p, p, p, p, None, p, ctypes.c_void_p(0x1010), need, None) == B.CSR_ERR_WORKSPACE
     assert lib.csr_decode_attn(ctypes.byref(d), None, p, p, p, p, p, p, None, p, p, need, None) == B.CSR_ERR_INVALID_ARG
     assert lib.csr_decode_attn(ctypes.byref(_dec(B=0)), None, None, None, None, None, None, None, None, None, None, 0, None) == B.CSR_OK
+
+
+def test_decode_accepts_rotary_descriptors_within_the_resident_limit():
+    lib = csr.lib()
+    for kw in (dict(N=512), dict(N=256, Hq=2, Hkv=2, sK=4), dict(N=128, snV=2, sV=4, rope_layout=1, rope_pos0=1 << 30)):
+        need = lib.csr_decode_workspace_bytes(ctypes.byref(_dec(rope_base=10000.0, **kw)))
+        assert 0 < need < 1 << 32, kw
 
 
 def test_decode_workspace_grows_with_the_chunk_count_and_zero_means_one_chunk():
