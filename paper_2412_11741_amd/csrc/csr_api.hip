@@ -155,7 +155,8 @@ csr_status check_decode_desc(const csr_decode_desc *d, csr::DecodePlan *plan)
         return fail(CSR_ERR_INVALID_ARG, "csr_decode_attn: rope_layout and rope_pos0 must be 0 when rope_base is 0");
     }
     if (!csr::plan_decode(d->B, d->Hq, d->Hkv, d->T, d->d, d->N, snK, snV, rope, plan))
-        return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: N=%d atoms do not fit the LDS-resident score and histogram tables", d->N);
+        return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: N=%d atoms do not fit the LDS-resident score and histogram tables, or T=%lld "
+                                         "exceeds what 64 token chunks hold", d->N, (long long)d->T);
     return CSR_OK;
 }
 

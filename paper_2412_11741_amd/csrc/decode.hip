@@ -662,11 +662,11 @@ bool plan_decode(int32_t B, int32_t Hq, int32_t Hkv, int64_t T, int32_t d, int32
     int GB = 0;
     for (int cand : {4, 2, 1}) {
         if (G % cand != 0) continue;
-        if (rope && cand > 2) continue;  // the rotary kernel keeps a turned query per head in registers
         // score table (fp32; with rotary keys the dictionary itself, fp16 rows) and histogram (64-bit) share the
         // space: the larger one counts
         const size_t first = rope ? (size_t)N * d * 2 : NK * 4 * cand;
-        const size_t lds = (first > NV * 8 * cand ? first : NV * 8 * cand) + (size_t)kStreamWaves * (cand + 1) * sizeof(float);
+        const size_t lds = (first > NV * 8 * cand ? first : NV * 8 * cand) + (size_t)kStreamWaves * (cand + 1) * sizeof(float) +
+                           (rope ? kRopeTableBytes : 0);
         if (lds <= kLdsBudget) { GB = cand; p->lds_bytes = lds; break; }
     }
     if (!GB) return false;
@@ -677,14 +677,17 @@ bool plan_decode(int32_t B, int32_t Hq, int32_t Hkv, int64_t T, int32_t d, int32
     // kMaxTPT x 1024 tokens (a thread keeps its tokens' scores in registers).
     const int64_t groups = (int64_t)(B > 0 ? B : 1) * Hkv * p->ngs;
     int64_t want = (256 + groups - 1) / groups;
-    const int64_t most = T > 0 ? (T + kStreamThreads - 1) / kStreamThreads : 1;
-    const int64_t least = T > 0 ? (T + (int64_t)kMaxTPT * kStreamThreads - 1) / ((int64_t)kMaxTPT * kStreamThreads) : 1;
+    const int64_t threads = rope ? kRopeThreads : kStreamThreads;  // tokens per round of the streaming kernel
+    const int64_t tpt = rope ? rope_rounds(GB) : kMaxTPT;
+    const int64_t most = T > 0 ? (T + threads - 1) / threads : 1;
+    const int64_t least = T > 0 ? (T + tpt * threads - 1) / (tpt * threads) : 1;
     if (want > most) want = most;
+    if (want > kMaxChunks) want = kMaxChunks;
     if (want < least) want = least;
-    if (want > kMaxChunks) return false;
+    if (want > kMaxChunks) return false;  // T beyond kMaxChunks chunks of the most tokens a chunk can hold
     if (want < 1) want = 1;
-    int64_t ct = T > 0 ? (T + want - 1) / want : kStreamThreads;
-    ct = (ct + kStreamThreads - 1) / kStreamThreads * kStreamThreads;
+    int64_t ct = T > 0 ? (T + want - 1) / want : threads;
+    ct = (ct + threads - 1) / threads * threads;
     p->chunk_tokens = ct;
     p->nchunks = T > 0 ? (int32_t)((T + ct - 1) / ct) : 1;
     auto r256 = [](size_t v) { return (v + 255) & ~size_t(255); };

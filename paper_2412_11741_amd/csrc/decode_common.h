@@ -10,6 +10,12 @@ constexpr int kStreamWaves = kStreamThreads / 64;
 constexpr int kMaxDevices = 64;      // devices a process may use this library on
 constexpr int kMaxTPT = 16;           // tokens per thread and chunk: their scores stay in registers
 constexpr int kMaxChunks = 64;
+constexpr int kRopeThreads = 1024;    // the rotary-key kernel: tokens per round
+constexpr int kRopeWaves = kRopeThreads / 64;
+// rounds a chunk of the rotary-key kernel may have: one score per round and query head stays in registers, and
+// the kernel has 128 of them per lane
+constexpr int rope_rounds(int GB) { return GB >= 4 ? 4 : 8; }
+constexpr size_t kRopeTableBytes = 8 * 32 * 4 + 8 * 4 * 8 * 4 + 64 * 8;  // rotation constants, a group's query pairs, theta
 constexpr size_t kLdsBudget = 150 * 1024;
 
 __device__ __forceinline__ float h2f(__half v) { return __half2float(v); }

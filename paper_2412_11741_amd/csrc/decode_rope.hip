@@ -3,21 +3,27 @@
 // so attention has to rotate the rebuilt key K~_t = D_K r_t of Eq.12 to its position t).
 //
 // The rotation depends on the token, so the one score table q . d_n of the position-free path no longer
-// exists.  What survives is the transposition: (Rot(t) K~_t) . q = K~_t . (Rot(-t) q) = sum_j c_j d_{i_j} . q~_t,
-// i.e. s gathered atom rows dotted with a query turned back by the token's position.  That is d multiply-adds
-// per pair instead of one, so it only pays while the atom rows come from LDS: the kernel keeps the whole key
-// dictionary of its KV head there (N * d * 2 bytes <= 128 KB, the paper's own dictionary sizes) and is bound by
-// the vector ALU, not by HBM.  Values carry no position: the V side is the same histogram scatter as in
-// stream_kernel, and out_kernel / finalize_kernel run unchanged on its results.
+// exists: every (token, pair) costs a gathered atom row and d multiply-adds instead of one table entry.  That
+// only pays while the atom rows come from LDS: the kernel keeps the whole key dictionary of its KV head there
+// (N * d * 2 bytes <= 128 KB, the paper's own dictionary sizes) and is bound by the vector ALU and the LDS, not by
+// HBM.  Values carry no position: the V side is the same histogram scatter as in stream_kernel, and out_kernel /
+// finalize_kernel run unchanged on its results.
 //
-// Mapping of pass 1.  A wave handles 64 consecutive tokens per round; lane l owns token l (it loads that token's
-// codes, coalesced, and keeps its score).  The 16 lanes of a quarter wave share the work of one token at a time:
-// sub-lane j holds frequency pairs 4j .. 4j+3 of the turned-back query (8 numbers) and reads the matching
-// 16 bytes of every gathered atom row, so a quarter reads one whole 256-byte row per load: all 64 banks once.
-// In step u the quarter works on its token 16*quarter + u, whose codes come from the owner lane by a lane
-// permute; the 16 partial scores meet in a 4-step butterfly.  From step to step the query is turned by one more
-// position (a fixed rotation per pair), from round to round by the rest of the 1024-token stride; the starting
-// angle of every lane is reduced in double precision, so positions in the hundreds of thousands stay accurate.
+// Two ways to spend the multiply-adds, chosen by the number of query heads that share the KV head:
+//   one query head:  (Rot(t) K~_t) . q = K~_t . (Rot(-t) q) = sum_j c_j (d_{i_j} . q~_t): the query is turned back
+//                    to the token's position and dotted with each gathered row (packed fp16 dot products);
+//   a query group:   K~_t is rebuilt in fp32 from the gathered rows, turned to its position once and dotted with
+//                    every query of the group.
+//
+// Mapping of pass 1.  A wave handles 64 consecutive tokens per round.  The 8 lanes of an eighth of the wave share the
+// work of one token at a time: each holds 8 of the 64 frequency pairs and reads the matching two 16-byte pieces of
+// every gathered row.  In step u eighth e works on token 8u + e of the wave's 64: all its lanes read that token's
+// codes straight from memory (the same 16 bytes; the eighths' tokens are neighbours, so the wave reads one
+// 128-byte line per stream and step, requested one step ahead), the 8 partial scores meet in a 3-step butterfly of
+// cross-lane adds, and lane (e, u) keeps the score: it is the lane that handles this token's value codes in
+// pass 2.  From step to step the rotation advances by 8 positions (a fixed rotation per pair, fp32), from round to
+// round by the rest of the round's stride; the starting angle of every lane is reduced in double precision, so
+// positions in the hundreds of thousands stay accurate.
 #include <atomic>
 #include <cmath>
 
@@ -42,10 +48,37 @@ __device__ __forceinline__ uint32_t pack_half2(float a, float b)
     return *reinterpret_cast<const uint32_t *>(&h);
 }
 
-// LDS: atom rows of D_K[h], 256 bytes each, the two members of every frequency pair side by side (pass 1);
-// the 64-bit histogram [GB][NV] (pass 2) | red[waves][GB] | red[waves]
-template <int GB, int PVK, int PV>
-__global__ __launch_bounds__(kStreamThreads) void stream_rope_kernel(
+__device__ __forceinline__ float lo_half(uint32_t w)
+{
+    const uint16_t v = (uint16_t)(w & 0xffffu);
+    return h2f(*reinterpret_cast<const __half *>(&v));
+}
+__device__ __forceinline__ float hi_half(uint32_t w)
+{
+    const uint16_t v = (uint16_t)(w >> 16);
+    return h2f(*reinterpret_cast<const __half *>(&v));
+}
+
+// v + (v of the lane whose number differs in bit 0 / 1 / 2): cross-lane adds inside a row of 16 lanes
+template <int CTRL> __device__ __forceinline__ float dpp_add(float v)
+{
+    const int o = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
+    return v + __int_as_float(o);
+}
+__device__ __forceinline__ float sum8(float v)
+{
+    v = dpp_add<0xB1>(v);   // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E>(v);   // quad_perm [2,3,0,1]
+    v = dpp_add<0x141>(v);  // row_half_mirror: lane i of every 8 with lane 7 - i, which lies in the other quad
+    return v;
+}
+
+// LDS: atom rows of D_K[h], 256 bytes each, the two members of every frequency pair side by side (pass 1), later the
+// 64-bit histogram [GB][NV] (pass 2) | red[waves][GB] | red[waves] | rotation constants [8 lane classes][32] |
+// the group's query pairs, packed fp16 [8 lane classes][4][8] (ROTK only) | theta_k as doubles [64]
+// TPT: rounds of 1024 tokens a chunk may have (a lane keeps one score per round and query head).
+template <int GB, bool ROTK, int PVK, int PV, int TPT>
+__global__ __launch_bounds__(kRopeThreads) void stream_rope_kernel(
     const __half *__restrict__ q, const __half *__restrict__ DK, const uint16_t *__restrict__ idxK,
     const __half *__restrict__ coefK, const uint16_t *__restrict__ idxV, const __half *__restrict__ coefV,
     const int32_t *__restrict__ seq_lens, float *__restrict__ part_hist, float *__restrict__ part_ml, int32_t Hq,
@@ -55,10 +88,12 @@ __global__ __launch_bounds__(kStreamThreads) void stream_rope_kernel(
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     unsigned long long *hist = reinterpret_cast<unsigned long long *>(smem_raw);
     float *red = reinterpret_cast<float *>(smem_raw + tab_bytes);
+    float *ctab = red + kRopeWaves * (GB + 1);           // [8][32]: cos, sin of a step; cos, sin of the round jump
+    uint32_t *qtab = reinterpret_cast<uint32_t *>(ctab + 8 * 32);  // [8][GB][8]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int sub = lane & 15, quarter = lane >> 4;
+    const int sub = lane & 7, eighth = lane >> 3;
     const int c = blockIdx.x;
     const int h = blockIdx.y / ngs, gs = blockIdx.y % ngs;
     const int b = blockIdx.z;
@@ -78,12 +113,12 @@ __global__ __launch_bounds__(kStreamThreads) void stream_rope_kernel(
         return;
     }
     const int64_t code_row = ((int64_t)b * Hkv + h) * T;
-    const int n_mine = (int)((t_end - t0 + kStreamThreads - 1) / kStreamThreads);  // rounds of 1024 tokens
+    const int n_mine = (int)((t_end - t0 + kRopeThreads - 1) / kRopeThreads);  // rounds of 1024 tokens
 
     // ---- the key dictionary into LDS, frequency pairs made adjacent -----------------------------------------
     {
         const __half *src = DK + (int64_t)h * N * 128;
-        for (int e = tid; e < N * 16; e += kStreamThreads) {
+        for (int e = tid; e < N * 16; e += kRopeThreads) {
             const int row = e >> 4, j = e & 15;
             uint4 v;
             if (layout == 0) {  // pair k = dimensions (k, k + 64): take 4 + 4 and interleave
@@ -100,52 +135,104 @@ __global__ __launch_bounds__(kStreamThreads) void stream_rope_kernel(
         }
     }
 
-    // ---- this lane's four frequency pairs: the query turned back to the lane's first position ---------------
-    // position of the token the quarter handles in step 0 of round 0
-    const int64_t pos_start = pos0 + t0 + wave * 64 + quarter * 16;
-    float c1[4], s1[4], cj[4], sj[4];  // one position further; the rest of the stride between rounds
-    float qa[GB][4], qb[GB][4];        // q~ pairs, fp32
-    {
-        const double l2b = log2((double)rope_base);
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int k = 4 * sub + p;
-            const double theta = exp2(-(2.0 * k / 128.0) * l2b);
-            auto reduced = [&](double turns_of) {
-                const double a = turns_of * theta;
-                return (float)(a - 6.283185307179586476925 * rint(a * 0.15915494309189533577));
-            };
-            float a1 = reduced(1.0), aj = reduced((double)(kStreamThreads - 16)), a0 = reduced((double)pos_start);
-            c1[p] = cosf(a1); s1[p] = sinf(a1);
-            cj[p] = cosf(aj); sj[p] = sinf(aj);
-            const float c0 = cosf(a0), s0 = sinf(a0);
+    // ---- frequency pairs of a lane: slot e < 4 lives in row piece `sub`, e >= 4 in piece 8 + sub (128 bytes
+    // further); piece p holds pairs 4p .. 4p+3.  What depends on `sub` only goes to LDS, computed once. --------
+    // theta_k of all 64 pairs, in double, once per workgroup
+    double *theta = reinterpret_cast<double *>(qtab + 8 * 4 * 8);  // [64]
+    if (tid < 64) theta[tid] = exp2(-(2.0 * tid / 128.0) * log2((double)rope_base));
+    __syncthreads();
+    auto pair_of = [](int sb, int e) { return 4 * (e < 4 ? sb : sb + 8) + (e & 3); };
+    // cos and sin of positions * theta_k: the angle is reduced to [-1/2, 1/2] revolutions in double, then the
+    // hardware sine and cosine (which take revolutions) are accurate to about 1e-6
+    auto cos_sin = [&](int k, double positions, float &co, float &si) {
+        const double r = positions * theta[k] * 0.15915494309189533577;
+        const float f = (float)(r - rint(r));
+        co = __builtin_amdgcn_cosf(f);
+        si = __builtin_amdgcn_sinf(f);
+    };
+    if (tid < 64) {
+        const int sb = tid >> 3, e = tid & 7, k = pair_of(sb, e);
+        cos_sin(k, 8.0, ctab[sb * 32 + e], ctab[sb * 32 + 8 + e]);
+        cos_sin(k, (double)(kRopeThreads - 64), ctab[sb * 32 + 16 + e], ctab[sb * 32 + 24 + e]);
+        if constexpr (ROTK) {
 #pragma unroll
             for (int g = 0; g < GB; ++g) {
                 const __half *qp = q + ((int64_t)b * Hq + (int64_t)h * G + gs * GB + g) * 128;
-                const float a = scale * h2f(layout == 0 ? qp[k] : qp[2 * k]);
-                const float bb = scale * h2f(layout == 0 ? qp[k + 64] : qp[2 * k + 1]);
-                // Rot(-pos) (a, b)
-                qa[g][p] = a * c0 + bb * s0;
-                qb[g][p] = bb * c0 - a * s0;
+                const __half2 pk = __halves2half2(layout == 0 ? qp[k] : qp[2 * k], layout == 0 ? qp[k + 64] : qp[2 * k + 1]);
+                qtab[(sb * GB + g) * 8 + e] = *reinterpret_cast<const uint32_t *>(&pk);
+            }
+        }
+    }
+    const unsigned char *rows0 = smem_raw + sub * 16;
+    const float *my_c = ctab + sub * 32;
+    const uint32_t *my_q = qtab + sub * GB * 8;
+    // the rotating state, at the position of the token this eighth handles in step 0 of round 0.
+    // ROTK: (ra, rb) = (cos, sin) of position * theta; else: the query pair turned back by that angle, scaled
+    constexpr int NR = ROTK ? 1 : GB;
+    float ra[NR][8], rb[NR][8];
+    {
+        const int64_t pos_start = pos0 + t0 + wave * 64 + eighth;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int k = pair_of(sub, e);
+            float c0, s0;
+            cos_sin(k, (double)pos_start, c0, s0);
+            if constexpr (ROTK) {
+                ra[0][e] = c0;
+                rb[0][e] = s0;
+            } else {
+#pragma unroll
+                for (int g = 0; g < GB; ++g) {  // Rot(-pos) (a, b)
+                    const __half *qp = q + ((int64_t)b * Hq + (int64_t)h * G + gs * GB + g) * 128;
+                    const float a = scale * h2f(layout == 0 ? qp[k] : qp[2 * k]);
+                    const float bb = scale * h2f(layout == 0 ? qp[k + 64] : qp[2 * k + 1]);
+                    ra[g][e] = a * c0 + bb * s0;
+                    rb[g][e] = bb * c0 - a * s0;
+                }
             }
         }
     }
     __syncthreads();
 
+    // turn the state on by the angles whose cosines and sines sit at `cs` (8 + 8 floats)
+    auto advance = [&](const float *cs) {
+        float cc[8], ss[8];
+#pragma unroll
+        for (int e = 0; e < 8; e += 4) {
+            *reinterpret_cast<float4 *>(&cc[e]) = *reinterpret_cast<const float4 *>(cs + e);
+            *reinterpret_cast<float4 *>(&ss[e]) = *reinterpret_cast<const float4 *>(cs + 8 + e);
+        }
+#pragma unroll
+        for (int g = 0; g < NR; ++g) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float a = ra[g][e], bb = rb[g][e];
+                if constexpr (ROTK) {  // (cos, sin) forward
+                    ra[g][e] = a * cc[e] - bb * ss[e];
+                    rb[g][e] = bb * cc[e] + a * ss[e];
+                } else {               // the query further back
+                    ra[g][e] = a * cc[e] + bb * ss[e];
+                    rb[g][e] = bb * cc[e] - a * ss[e];
+                }
+            }
+        }
+    };
+
     // ---- pass 1 ---------------------------------------------------------------------------------------------
+    const int nblk = sK / PVK;  // pair blocks per token
     float cm = 0.0f;
-    float sc[kMaxTPT][GB];
+    float sc[TPT][GB];
     float mx[GB];
 #pragma unroll
     for (int g = 0; g < GB; ++g) mx[g] = -INFINITY;
-    const unsigned char *my_rows = smem_raw + sub * 16;
 #pragma unroll
-    for (int i = 0; i < kMaxTPT; ++i) {
+    for (int i = 0; i < TPT; ++i) {
 #pragma unroll
         for (int g = 0; g < GB; ++g) sc[i][g] = -INFINITY;
         // (a wave whose 64 tokens of this round all lie past the end has none in later rounds either)
-        if (i < n_mine && t0 + (int64_t)i * kStreamThreads + wave * 64 < t_end) {
-            const int64_t t = t0 + (int64_t)i * kStreamThreads + tid;  // the token this lane owns in round i
+        if (i < n_mine && t0 + (int64_t)i * kRopeThreads + wave * 64 < t_end) {
+            // the token whose score this lane keeps in round i: the one its eighth handles in step `sub`
+            const int64_t t = t0 + (int64_t)i * kRopeThreads + wave * 64 + 8 * sub + eighth;
             const bool have = t < t_end;
             if (i == 0 && have) {  // sample the value coefficients for the histogram unit (see stream_kernel)
                 const __half *vp = coefV + (code_row + t) * sVt;
@@ -159,103 +246,117 @@ __global__ __launch_bounds__(kStreamThreads) void stream_rope_kernel(
             float mine[GB];
 #pragma unroll
             for (int g = 0; g < GB; ++g) mine[g] = 0.0f;
-            for (int j0 = 0; j0 < sK; j0 += PVK) {
-                // the owner's PVK pairs: indices and coefficients as packed 16-bit words (absent tokens: zeros)
-                uint32_t wi[PVK / 2], wc[PVK / 2];
-#pragma unroll
-                for (int w = 0; w < PVK / 2; ++w) wi[w] = wc[w] = 0u;
-                if (have) {
-                    const uint16_t *ip = idxK + (code_row + t) * sK + j0;
-                    const __half *cp = coefK + (code_row + t) * sK + j0;
-                    if constexpr (PVK == 8) {
-                        const uint4 a = *reinterpret_cast<const uint4 *>(ip);
-                        const uint4 bq = *reinterpret_cast<const uint4 *>(cp);
-                        wi[0] = a.x; wi[1] = a.y; wi[2] = a.z; wi[3] = a.w;
-                        wc[0] = bq.x; wc[1] = bq.y; wc[2] = bq.z; wc[3] = bq.w;
-                    } else {
-                        const uint2 a = *reinterpret_cast<const uint2 *>(ip);
-                        const uint2 bq = *reinterpret_cast<const uint2 *>(cp);
-                        wi[0] = a.x; wi[1] = a.y;
-                        wc[0] = bq.x; wc[1] = bq.y;
-                    }
+            // PVK pairs of the token of step u, read by all 8 lanes of the eighth (one 16-byte piece, and the 8
+            // eighths' tokens are neighbours: a wave reads 128 contiguous bytes per stream and step); indices and
+            // coefficients as packed 16-bit words.  Requested one block ahead of its use.
+            const int64_t tw = t0 + (int64_t)i * kRopeThreads + wave * 64 + eighth;  // + 8 u
+            uint32_t ni[PVK / 2], nc[PVK / 2];
+            auto fetch = [&](int u, int jb) {
+                const int64_t tu = min(tw + 8 * u, t_end - 1);  // past the end: the last token again, score unused
+                const uint16_t *ip = idxK + (code_row + tu) * sK + jb * PVK;
+                const __half *cp = coefK + (code_row + tu) * sK + jb * PVK;
+                if constexpr (PVK == 8) {
+                    const uint4 a = *reinterpret_cast<const uint4 *>(ip);
+                    const uint4 bq = *reinterpret_cast<const uint4 *>(cp);
+                    ni[0] = a.x; ni[1] = a.y; ni[2] = a.z; ni[3] = a.w;
+                    nc[0] = bq.x; nc[1] = bq.y; nc[2] = bq.z; nc[3] = bq.w;
+                } else {
+                    const uint2 a = *reinterpret_cast<const uint2 *>(ip);
+                    const uint2 bq = *reinterpret_cast<const uint2 *>(cp);
+                    ni[0] = a.x; ni[1] = a.y;
+                    nc[0] = bq.x; nc[1] = bq.y;
                 }
-                // the turned-back query of this round's first step (kept across the pair blocks of a token by
-                // re-deriving it: the step rotations below run on copies)
-                float ra[GB][4], rb[GB][4];
+            };
+            fetch(0, 0);
+#pragma unroll 1
+            for (int u = 0; u < 8; ++u) {
+                float part[GB];
+                float ka[ROTK ? 8 : 1], kb[ROTK ? 8 : 1];  // ROTK: K~ of this lane's 8 pairs, fp32
+                uint32_t qp[ROTK ? 1 : GB][8];             // else: the turned-back queries as fp16 pairs
+                if constexpr (ROTK) {
 #pragma unroll
-                for (int g = 0; g < GB; ++g) {
+                    for (int e = 0; e < 8; ++e) ka[e] = kb[e] = 0.0f;
+                } else {
 #pragma unroll
-                    for (int p = 0; p < 4; ++p) { ra[g][p] = qa[g][p]; rb[g][p] = qb[g][p]; }
+                    for (int g = 0; g < GB; ++g) {
+                        part[g] = 0.0f;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) qp[g][e] = pack_half2(ra[g][e], rb[g][e]);
+                    }
                 }
 #pragma unroll 1
-                for (int u = 0; u < 16; ++u) {
-                    const int owner = (lane & 48) | u;
-                    uint32_t ti[PVK / 2], tc[PVK / 2];
+                for (int jb = 0; jb < nblk; ++jb) {
+                    uint32_t to[PVK], tc[PVK / 2];
 #pragma unroll
-                    for (int w = 0; w < PVK / 2; ++w) {
-                        ti[w] = (uint32_t)__shfl((int)wi[w], owner, 64);
-                        tc[w] = (uint32_t)__shfl((int)wc[w], owner, 64);
-                    }
-                    uint32_t qp[GB][4];
+                    for (int jj = 0; jj < PVK; ++jj) to[jj] = ((jj & 1) ? (ni[jj >> 1] >> 16) : (ni[jj >> 1] & 0xffffu)) * 256u;
 #pragma unroll
-                    for (int g = 0; g < GB; ++g) {
-#pragma unroll
-                        for (int p = 0; p < 4; ++p) qp[g][p] = pack_half2(ra[g][p], rb[g][p]);
-                    }
-                    float acc[GB];
-#pragma unroll
-                    for (int g = 0; g < GB; ++g) acc[g] = 0.0f;
+                    for (int w = 0; w < PVK / 2; ++w) tc[w] = nc[w];
+                    if (jb + 1 < nblk) fetch(u, jb + 1);
+                    else if (u < 7) fetch(u + 1, 0);
 #pragma unroll
                     for (int jj = 0; jj < PVK; ++jj) {
-                        const uint32_t id = (jj & 1) ? (ti[jj >> 1] >> 16) : (ti[jj >> 1] & 0xffffu);
-                        const uint32_t cw = (jj & 1) ? (tc[jj >> 1] >> 16) : (tc[jj >> 1] & 0xffffu);
-                        const uint16_t cs = (uint16_t)cw;
-                        const float cf = h2f(*reinterpret_cast<const __half *>(&cs));
-                        const uint4 dv = *reinterpret_cast<const uint4 *>(my_rows + id * 256u);
+                        const float cf = (jj & 1) ? hi_half(tc[jj >> 1]) : lo_half(tc[jj >> 1]);
+                        const uint4 d0 = *reinterpret_cast<const uint4 *>(rows0 + to[jj]);
+                        const uint4 d1 = *reinterpret_cast<const uint4 *>(rows0 + to[jj] + 128);
+                        if constexpr (ROTK) {
+                            const uint32_t dw[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
 #pragma unroll
-                        for (int g = 0; g < GB; ++g) {
-                            float part = dot2(qp[g][0], dv.x, 0.0f);
-                            part = dot2(qp[g][1], dv.y, part);
-                            part = dot2(qp[g][2], dv.z, part);
-                            part = dot2(qp[g][3], dv.w, part);
-                            acc[g] = fmaf(cf, part, acc[g]);
-                        }
-                    }
+                            for (int e = 0; e < 8; ++e) {
+                                ka[e] = fmaf(cf, lo_half(dw[e]), ka[e]);
+                                kb[e] = fmaf(cf, hi_half(dw[e]), kb[e]);
+                            }
+                        } else {
 #pragma unroll
-                    for (int g = 0; g < GB; ++g) {
-                        float v = acc[g];
-                        v += __shfl_xor(v, 1, 64);
-                        v += __shfl_xor(v, 2, 64);
-                        v += __shfl_xor(v, 4, 64);
-                        v += __shfl_xor(v, 8, 64);
-                        if (sub == u) mine[g] += v;
-                    }
-                    // one position further
-#pragma unroll
-                    for (int g = 0; g < GB; ++g) {
-#pragma unroll
-                        for (int p = 0; p < 4; ++p) {
-                            const float a = ra[g][p], bb = rb[g][p];
-                            ra[g][p] = a * c1[p] + bb * s1[p];
-                            rb[g][p] = bb * c1[p] - a * s1[p];
+                            for (int g = 0; g < GB; ++g) {
+                                float p = dot2(qp[g][0], d0.x, 0.0f);
+                                p = dot2(qp[g][1], d0.y, p);
+                                p = dot2(qp[g][2], d0.z, p);
+                                p = dot2(qp[g][3], d0.w, p);
+                                p = dot2(qp[g][4], d1.x, p);
+                                p = dot2(qp[g][5], d1.y, p);
+                                p = dot2(qp[g][6], d1.z, p);
+                                p = dot2(qp[g][7], d1.w, p);
+                                part[g] = fmaf(cf, p, part[g]);
+                            }
                         }
                     }
                 }
-                if (j0 + PVK >= sK) {  // last pair block: carry the query on to the next round's first position
+                if constexpr (ROTK) {
+                    // turned to the token's position, rounded to fp16 pairs, dotted with every query of the group
+                    uint32_t kp[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        kp[e] = pack_half2(ka[e] * ra[0][e] - kb[e] * rb[0][e], kb[e] * ra[0][e] + ka[e] * rb[0][e]);
 #pragma unroll
                     for (int g = 0; g < GB; ++g) {
-#pragma unroll
-                        for (int p = 0; p < 4; ++p) {
-                            const float a = ra[g][p], bb = rb[g][p];
-                            qa[g][p] = a * cj[p] + bb * sj[p];
-                            qb[g][p] = bb * cj[p] - a * sj[p];
-                        }
+                        const uint4 q0 = *reinterpret_cast<const uint4 *>(my_q + g * 8);
+                        const uint4 q1 = *reinterpret_cast<const uint4 *>(my_q + g * 8 + 4);
+                        float p = dot2(q0.x, kp[0], 0.0f);
+                        p = dot2(q0.y, kp[1], p);
+                        p = dot2(q0.z, kp[2], p);
+                        p = dot2(q0.w, kp[3], p);
+                        p = dot2(q1.x, kp[4], p);
+                        p = dot2(q1.y, kp[5], p);
+                        p = dot2(q1.z, kp[6], p);
+                        p = dot2(q1.w, kp[7], p);
+                        part[g] = p;
                     }
                 }
+#pragma unroll
+                for (int g = 0; g < GB; ++g) {
+                    const float v = sum8(part[g]);
+                    if (sub == u) mine[g] += v;
+                }
+                advance(my_c);  // 8 positions on: the next step's token
             }
+            advance(my_c + 16);  // the rest of the round's stride
             if (have) {
 #pragma unroll
-                for (int g = 0; g < GB; ++g) { sc[i][g] = mine[g]; mx[g] = fmaxf(mx[g], mine[g]); }
+                for (int g = 0; g < GB; ++g) {
+                    const float v = ROTK ? mine[g] * scale : mine[g];
+                    sc[i][g] = v;
+                    mx[g] = fmaxf(mx[g], v);
+                }
             }
         }
     }
@@ -265,19 +366,19 @@ __global__ __launch_bounds__(kStreamThreads) void stream_rope_kernel(
         if (lane == 0) red[wave * GB + g] = wm;
     }
     cm = wave_max(cm);
-    if (lane == 0) red[kStreamWaves * GB + wave] = cm;
+    if (lane == 0) red[kRopeWaves * GB + wave] = cm;
     __syncthreads();  // every score is computed: the dictionary rows are free
     float m_c[GB];
 #pragma unroll
     for (int g = 0; g < GB; ++g) {
         float v = red[g];
 #pragma unroll
-        for (int w = 1; w < kStreamWaves; ++w) v = fmaxf(v, red[w * GB + g]);
+        for (int w = 1; w < kRopeWaves; ++w) v = fmaxf(v, red[w * GB + g]);
         m_c[g] = v;
     }
-    float c_est = red[kStreamWaves * GB];
+    float c_est = red[kRopeWaves * GB];
 #pragma unroll
-    for (int w = 1; w < kStreamWaves; ++w) c_est = fmaxf(c_est, red[kStreamWaves * GB + w]);
+    for (int w = 1; w < kRopeWaves; ++w) c_est = fmaxf(c_est, red[kRopeWaves * GB + w]);
     int unit_exp = -32;
     if (c_est > 0.0f && c_est < INFINITY) {
         int e2;
@@ -289,7 +390,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_rope_kernel(
 #pragma unroll
     for (int g = 0; g < GB; ++g) m_eff[g] = m_c[g] - (float)k_units * 0.69314718f;
     const int bins = NV * GB;
-    for (int e = tid; e < bins; e += kStreamThreads) hist[e] = 0ull;
+    for (int e = tid; e < bins; e += kRopeThreads) hist[e] = 0ull;
     __syncthreads();
 
     // ---- pass 2: p = exp(score - max) in histogram units, scatter p * c of the V codes -----------------------
@@ -297,9 +398,9 @@ __global__ __launch_bounds__(kStreamThreads) void stream_rope_kernel(
 #pragma unroll
     for (int g = 0; g < GB; ++g) l_thr[g] = 0.0f;
 #pragma unroll
-    for (int i = 0; i < kMaxTPT; ++i) {
+    for (int i = 0; i < TPT; ++i) {
         if (i < n_mine) {
-            const int64_t t = t0 + (int64_t)i * kStreamThreads + tid;
+            const int64_t t = t0 + (int64_t)i * kRopeThreads + (tid & ~63) + 8 * sub + eighth;  // as in pass 1
             if (t < t_end) {
                 float p[GB];
 #pragma unroll
@@ -335,20 +436,20 @@ __global__ __launch_bounds__(kStreamThreads) void stream_rope_kernel(
     for (int g = 0; g < GB; ++g) {
         if (tid == g) {
             float l = 0.0f;
-            for (int w = 0; w < kStreamWaves; ++w) l += red[w * GB + g];
+            for (int w = 0; w < kRopeWaves; ++w) l += red[w * GB + g];
             ml[2 * g] = m_c[g];
             ml[2 * g + 1] = ldexpf(l, -k_units);
         }
     }
     float *dst = part_hist + slot * (int64_t)bins;
     const float from_units = ldexpf(1.0f, unit_exp + 32);
-    for (int e = tid; e < bins; e += kStreamThreads) dst[e] = from_fixed(hist[e]) * from_units;
+    for (int e = tid; e < bins; e += kRopeThreads) dst[e] = from_fixed(hist[e]) * from_units;
 }
 
-template <int GB, int PVK, int PV>
+template <int GB, bool ROTK, int PVK, int PV>
 hipError_t launch_rope_t(const DecodeArgs &a, const DecodePlan &p, float *hist, float *ml)
 {
-    auto kern = stream_rope_kernel<GB, PVK, PV>;
+    auto kern = stream_rope_kernel<GB, ROTK, PVK, PV, rope_rounds(GB)>;
     static std::atomic<bool> attr_set[kMaxDevices];
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -360,10 +461,10 @@ hipError_t launch_rope_t(const DecodeArgs &a, const DecodePlan &p, float *hist, 
         if (e != hipSuccess) return e;
         attr_set[dev].store(true, std::memory_order_release);
     }
-    const size_t red_bytes = (size_t)kStreamWaves * (GB + 1) * sizeof(float);
-    const uint32_t tab_bytes = (uint32_t)(p.lds_bytes - red_bytes);
+    // the plan's LDS size = dictionary / histogram | reductions | constant tables (see plan_decode)
+    const uint32_t tab_bytes = (uint32_t)(p.lds_bytes - (size_t)kStreamWaves * (GB + 1) * sizeof(float) - kRopeTableBytes);
     const dim3 grid((unsigned)p.nchunks, (unsigned)(a.Hkv * p.ngs), (unsigned)a.B);
-    hipLaunchKernelGGL(kern, grid, dim3(kStreamThreads), p.lds_bytes, a.stream, (const __half *)a.q,
+    hipLaunchKernelGGL(kern, grid, dim3(kRopeThreads), p.lds_bytes, a.stream, (const __half *)a.q,
                        (const __half *)a.DK, (const uint16_t *)a.idxK, (const __half *)a.coefK,
                        (const uint16_t *)a.idxV, (const __half *)a.coefV, a.seq_lens, hist, ml, a.Hq, a.Hkv, a.G, p.ngs,
                        a.T, a.N, a.sK, a.sV, a.snV, a.scale, a.rope_base, a.rope_layout, a.rope_pos0, p.chunk_tokens,
@@ -371,19 +472,19 @@ hipError_t launch_rope_t(const DecodeArgs &a, const DecodePlan &p, float *hist, 
     return hipGetLastError();
 }
 
-template <int GB, int PVK>
+template <int GB, bool ROTK, int PVK>
 hipError_t launch_rope_pv(const DecodeArgs &a, const DecodePlan &p, float *hist, float *ml)
 {
-    if (a.sV % 8 == 0) return launch_rope_t<GB, PVK, 8>(a, p, hist, ml);
-    if (a.sV % 4 == 0) return launch_rope_t<GB, PVK, 4>(a, p, hist, ml);
-    return launch_rope_t<GB, PVK, 1>(a, p, hist, ml);
+    if (a.sV % 8 == 0) return launch_rope_t<GB, ROTK, PVK, 8>(a, p, hist, ml);
+    if (a.sV % 4 == 0) return launch_rope_t<GB, ROTK, PVK, 4>(a, p, hist, ml);
+    return launch_rope_t<GB, ROTK, PVK, 1>(a, p, hist, ml);
 }
 
-template <int GB>
+template <int GB, bool ROTK>
 hipError_t launch_rope_gb(const DecodeArgs &a, const DecodePlan &p, float *hist, float *ml)
 {
-    if (a.sK % 8 == 0) return launch_rope_pv<GB, 8>(a, p, hist, ml);
-    return launch_rope_pv<GB, 4>(a, p, hist, ml);
+    if (a.sK % 8 == 0) return launch_rope_pv<GB, ROTK, 8>(a, p, hist, ml);
+    return launch_rope_pv<GB, ROTK, 4>(a, p, hist, ml);
 }
 
 }  // namespace
@@ -396,8 +497,9 @@ bool decode_rope_shape_supported(int32_t d, int32_t N, int32_t sK, int32_t snK)
 hipError_t launch_stream_rope(const DecodeArgs &a, const DecodePlan &p, float *hist, float *ml)
 {
     switch (p.GB) {
-        case 2: return launch_rope_gb<2>(a, p, hist, ml);
-        case 1: return launch_rope_gb<1>(a, p, hist, ml);
+        case 4: return launch_rope_gb<4, true>(a, p, hist, ml);
+        case 2: return launch_rope_gb<2, true>(a, p, hist, ml);
+        case 1: return launch_rope_gb<1, false>(a, p, hist, ml);
     }
     return hipErrorInvalidValue;
 }
