@@ -677,8 +677,8 @@ bool plan_decode(int32_t B, int32_t Hq, int32_t Hkv, int64_t T, int32_t d, int32
     // kMaxTPT x 1024 tokens (a thread keeps its tokens' scores in registers).
     const int64_t groups = (int64_t)(B > 0 ? B : 1) * Hkv * p->ngs;
     int64_t want = (256 + groups - 1) / groups;
-    const int64_t threads = rope ? kRopeThreads : kStreamThreads;  // tokens per round of the streaming kernel
-    const int64_t tpt = rope ? rope_rounds(GB) : kMaxTPT;
+    const int64_t threads = rope ? rope_threads(GB) : kStreamThreads;  // tokens per round of the streaming kernel
+    const int64_t tpt = rope ? rope_rounds(GB) : kMaxTPT;          // rounds per chunk
     const int64_t most = T > 0 ? (T + threads - 1) / threads : 1;
     const int64_t least = T > 0 ? (T + tpt * threads - 1) / (tpt * threads) : 1;
     if (want > most) want = most;

@@ -10,11 +10,11 @@ constexpr int kStreamWaves = kStreamThreads / 64;
 constexpr int kMaxDevices = 64;      // devices a process may use this library on
 constexpr int kMaxTPT = 16;           // tokens per thread and chunk: their scores stay in registers
 constexpr int kMaxChunks = 64;
-constexpr int kRopeThreads = 1024;    // the rotary-key kernel: tokens per round
-constexpr int kRopeWaves = kRopeThreads / 64;
-// rounds a chunk of the rotary-key kernel may have: one score per round and query head stays in registers, and
-// the kernel has 128 of them per lane
-constexpr int rope_rounds(int GB) { return GB >= 4 ? 4 : 8; }
+// The rotary-key kernel (decode_rope.hip).  One query head at a time: 16 waves with 128 registers each; a query group
+// keeps a rebuilt key and the group's scores in registers: 8 waves with 256 each.
+constexpr int rope_threads(int GB) { return GB >= 2 ? 512 : 1024; }  // tokens per round
+// rounds a chunk may have: one score per round and query head stays in registers
+constexpr int rope_rounds(int GB) { return GB == 2 ? 16 : 8; }
 constexpr size_t kRopeTableBytes = 8 * 32 * 4 + 8 * 4 * 8 * 4 + 64 * 8;  // rotation constants, a group's query pairs, theta
 constexpr size_t kLdsBudget = 150 * 1024;
 

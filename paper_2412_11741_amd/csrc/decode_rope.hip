@@ -73,22 +73,125 @@ __device__ __forceinline__ float sum8(float v)
     return v;
 }
 
+// The rest of a chunk, common to the kernels below: the chunk's maximum, the unit of the fixed-point histogram,
+// pass 2 (p = exp(score - max) in histogram units, scatter p * c of the V codes into the LDS histogram, which takes
+// the place of the dictionary rows), and the chunk's histogram, maximum and sum to scratch - exactly what
+// stream_kernel of the position-free path leaves for out_kernel.
+// owner_off: the token of a round (0 .. THREADS-1) whose score this lane holds in sc[round].
+template <int GB, int PV, int TPT, int THREADS>
+__device__ __forceinline__ void finish_chunk(unsigned char *smem_raw, float *red, const float (&sc)[TPT][GB], const float (&mx)[GB],
+                                             float cm, int n_mine, int64_t t0, int64_t t_end, int64_t code_row, int owner_off,
+                                             const uint16_t *__restrict__ idxV, const __half *__restrict__ coefV, int32_t N,
+                                             int32_t sV, int32_t snV, float *ml, float *part_hist, int64_t slot)
+{
+    constexpr int WAVES = THREADS / 64;
+    unsigned long long *hist = reinterpret_cast<unsigned long long *>(smem_raw);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int NV = snV * N, sVt = snV * sV;
+#pragma unroll
+    for (int g = 0; g < GB; ++g) {
+        const float wm = wave_max(mx[g]);
+        if (lane == 0) red[wave * GB + g] = wm;
+    }
+    cm = wave_max(cm);
+    if (lane == 0) red[WAVES * GB + wave] = cm;
+    __syncthreads();  // every score is computed: the dictionary rows are free
+    float m_c[GB];
+#pragma unroll
+    for (int g = 0; g < GB; ++g) {
+        float v = red[g];
+#pragma unroll
+        for (int w = 1; w < WAVES; ++w) v = fmaxf(v, red[w * GB + g]);
+        m_c[g] = v;
+    }
+    float c_est = red[WAVES * GB];
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) c_est = fmaxf(c_est, red[WAVES * GB + w]);
+    int unit_exp = -32;
+    if (c_est > 0.0f && c_est < INFINITY) {
+        int e2;
+        (void)frexpf(c_est, &e2);
+        unit_exp = e2 - 1 - 30;
+    }
+    const int k_units = -unit_exp - 32;
+    float m_eff[GB];
+#pragma unroll
+    for (int g = 0; g < GB; ++g) m_eff[g] = m_c[g] - (float)k_units * 0.69314718f;
+    const int bins = NV * GB;
+    for (int e = tid; e < bins; e += THREADS) hist[e] = 0ull;
+    __syncthreads();
+
+    // ---- pass 2: p = exp(score - max) in histogram units, scatter p * c of the V codes -----------------------
+    float l_thr[GB];
+#pragma unroll
+    for (int g = 0; g < GB; ++g) l_thr[g] = 0.0f;
+#pragma unroll
+    for (int i = 0; i < TPT; ++i) {
+        if (i < n_mine) {
+            const int64_t t = t0 + (int64_t)i * THREADS + owner_off;
+            if (t < t_end) {
+                float p[GB];
+#pragma unroll
+                for (int g = 0; g < GB; ++g) { p[g] = __expf(sc[i][g] - m_eff[g]); l_thr[g] += p[g]; }
+                const uint16_t *ip = idxV + (code_row + t) * sVt;
+                const __half *cp = coefV + (code_row + t) * sVt;
+                unsigned long long *hb = hist;
+                for (int ch = 0; ch < snV; ++ch, hb += N, ip += sV, cp += sV) {
+                    for (int j0 = 0; j0 < sV; j0 += PV) {
+                        int id[PV];
+                        float cf[PV];
+                        IdxLoad<uint16_t, PV>::ld(ip + j0, id);
+                        CoefLoad<__half, PV>::ld(cp + j0, cf);
+#pragma unroll
+                        for (int j = 0; j < PV; ++j) {
+#pragma unroll
+                            for (int g = 0; g < GB; ++g) atomicAdd(&hb[g * NV + id[j]], to_fixed(p[g] * cf[j]));
+                        }
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+#pragma unroll
+    for (int g = 0; g < GB; ++g) {
+        const float ws = wave_sum(l_thr[g]);
+        if (lane == 0) red[wave * GB + g] = ws;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int g = 0; g < GB; ++g) {
+        if (tid == g) {
+            float l = 0.0f;
+            for (int w = 0; w < WAVES; ++w) l += red[w * GB + g];
+            ml[2 * g] = m_c[g];
+            ml[2 * g + 1] = ldexpf(l, -k_units);
+        }
+    }
+    float *dst = part_hist + slot * (int64_t)bins;
+    const float from_units = ldexpf(1.0f, unit_exp + 32);
+    for (int e = tid; e < bins; e += THREADS) dst[e] = from_fixed(hist[e]) * from_units;
+}
+
+
 // LDS: atom rows of D_K[h], 256 bytes each, the two members of every frequency pair side by side (pass 1), later the
 // 64-bit histogram [GB][NV] (pass 2) | red[waves][GB] | red[waves] | rotation constants [8 lane classes][32] |
 // the group's query pairs, packed fp16 [8 lane classes][4][8] (ROTK only) | theta_k as doubles [64]
-// TPT: rounds of 1024 tokens a chunk may have (a lane keeps one score per round and query head).
-template <int GB, bool ROTK, int PVK, int PV, int TPT>
-__global__ __launch_bounds__(kRopeThreads) void stream_rope_kernel(
+// TPT: rounds of rope_threads(GB) tokens a chunk may have (a lane keeps one score per round and query head).
+// ONEB: a key code is exactly one block of PVK pairs.
+template <int GB, bool ROTK, int PVK, bool ONEB, int PV, int TPT>
+__global__ __launch_bounds__(rope_threads(GB)) void stream_rope_kernel(
     const __half *__restrict__ q, const __half *__restrict__ DK, const uint16_t *__restrict__ idxK,
     const __half *__restrict__ coefK, const uint16_t *__restrict__ idxV, const __half *__restrict__ coefV,
     const int32_t *__restrict__ seq_lens, float *__restrict__ part_hist, float *__restrict__ part_ml, int32_t Hq,
     int32_t Hkv, int32_t G, int32_t ngs, int64_t T, int32_t N, int32_t sK, int32_t sV, int32_t snV, float scale,
     float rope_base, int32_t layout, int64_t pos0, int64_t chunk_tokens, int32_t nchunks, uint32_t tab_bytes)
 {
+    constexpr int THREADS = rope_threads(GB), WAVES = THREADS / 64;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    unsigned long long *hist = reinterpret_cast<unsigned long long *>(smem_raw);
     float *red = reinterpret_cast<float *>(smem_raw + tab_bytes);
-    float *ctab = red + kRopeWaves * (GB + 1);           // [8][32]: cos, sin of a step; cos, sin of the round jump
+    float *ctab = red + WAVES * (GB + 1);           // [8][32]: cos, sin of a step; cos, sin of the round jump
     uint32_t *qtab = reinterpret_cast<uint32_t *>(ctab + 8 * 32);  // [8][GB][8]
 
     const int tid = threadIdx.x;
@@ -97,7 +200,7 @@ __global__ __launch_bounds__(kRopeThreads) void stream_rope_kernel(
     const int c = blockIdx.x;
     const int h = blockIdx.y / ngs, gs = blockIdx.y % ngs;
     const int b = blockIdx.z;
-    const int NV = snV * N, sVt = snV * sV;
+    const int sVt = snV * sV;
 
     int64_t len = T;
     if (seq_lens) {
@@ -113,12 +216,12 @@ __global__ __launch_bounds__(kRopeThreads) void stream_rope_kernel(
         return;
     }
     const int64_t code_row = ((int64_t)b * Hkv + h) * T;
-    const int n_mine = (int)((t_end - t0 + kRopeThreads - 1) / kRopeThreads);  // rounds of 1024 tokens
+    const int n_mine = (int)((t_end - t0 + THREADS - 1) / THREADS);  // rounds of THREADS tokens
 
     // ---- the key dictionary into LDS, frequency pairs made adjacent -----------------------------------------
     {
         const __half *src = DK + (int64_t)h * N * 128;
-        for (int e = tid; e < N * 16; e += kRopeThreads) {
+        for (int e = tid; e < N * 16; e += THREADS) {
             const int row = e >> 4, j = e & 15;
             uint4 v;
             if (layout == 0) {  // pair k = dimensions (k, k + 64): take 4 + 4 and interleave
@@ -153,7 +256,7 @@ __global__ __launch_bounds__(kRopeThreads) void stream_rope_kernel(
     if (tid < 64) {
         const int sb = tid >> 3, e = tid & 7, k = pair_of(sb, e);
         cos_sin(k, 8.0, ctab[sb * 32 + e], ctab[sb * 32 + 8 + e]);
-        cos_sin(k, (double)(kRopeThreads - 64), ctab[sb * 32 + 16 + e], ctab[sb * 32 + 24 + e]);
+        cos_sin(k, (double)(THREADS - 64), ctab[sb * 32 + 16 + e], ctab[sb * 32 + 24 + e]);
         if constexpr (ROTK) {
 #pragma unroll
             for (int g = 0; g < GB; ++g) {
@@ -219,7 +322,7 @@ __global__ __launch_bounds__(kRopeThreads) void stream_rope_kernel(
     };
 
     // ---- pass 1 ---------------------------------------------------------------------------------------------
-    const int nblk = sK / PVK;  // pair blocks per token
+    const int nblk = ONEB ? 1 : sK / PVK;  // pair blocks per token (ONEB: known to be one)
     float cm = 0.0f;
     float sc[TPT][GB];
     float mx[GB];
@@ -230,9 +333,9 @@ __global__ __launch_bounds__(kRopeThreads) void stream_rope_kernel(
 #pragma unroll
         for (int g = 0; g < GB; ++g) sc[i][g] = -INFINITY;
         // (a wave whose 64 tokens of this round all lie past the end has none in later rounds either)
-        if (i < n_mine && t0 + (int64_t)i * kRopeThreads + wave * 64 < t_end) {
+        if (i < n_mine && t0 + (int64_t)i * THREADS + wave * 64 < t_end) {
             // the token whose score this lane keeps in round i: the one its eighth handles in step `sub`
-            const int64_t t = t0 + (int64_t)i * kRopeThreads + wave * 64 + 8 * sub + eighth;
+            const int64_t t = t0 + (int64_t)i * THREADS + wave * 64 + 8 * sub + eighth;
             const bool have = t < t_end;
             if (i == 0 && have) {  // sample the value coefficients for the histogram unit (see stream_kernel)
                 const __half *vp = coefV + (code_row + t) * sVt;
@@ -249,7 +352,7 @@ __global__ __launch_bounds__(kRopeThreads) void stream_rope_kernel(
             // PVK pairs of the token of step u, read by all 8 lanes of the eighth (one 16-byte piece, and the 8
             // eighths' tokens are neighbours: a wave reads 128 contiguous bytes per stream and step); indices and
             // coefficients as packed 16-bit words.  Requested one block ahead of its use.
-            const int64_t tw = t0 + (int64_t)i * kRopeThreads + wave * 64 + eighth;  // + 8 u
+            const int64_t tw = t0 + (int64_t)i * THREADS + wave * 64 + eighth;  // + 8 u
             uint32_t ni[PVK / 2], nc[PVK / 2];
             auto fetch = [&](int u, int jb) {
                 const int64_t tu = min(tw + 8 * u, t_end - 1);  // past the end: the last token again, score unused
@@ -360,96 +463,14 @@ __global__ __launch_bounds__(kRopeThreads) void stream_rope_kernel(
             }
         }
     }
-#pragma unroll
-    for (int g = 0; g < GB; ++g) {
-        const float wm = wave_max(mx[g]);
-        if (lane == 0) red[wave * GB + g] = wm;
-    }
-    cm = wave_max(cm);
-    if (lane == 0) red[kRopeWaves * GB + wave] = cm;
-    __syncthreads();  // every score is computed: the dictionary rows are free
-    float m_c[GB];
-#pragma unroll
-    for (int g = 0; g < GB; ++g) {
-        float v = red[g];
-#pragma unroll
-        for (int w = 1; w < kRopeWaves; ++w) v = fmaxf(v, red[w * GB + g]);
-        m_c[g] = v;
-    }
-    float c_est = red[kRopeWaves * GB];
-#pragma unroll
-    for (int w = 1; w < kRopeWaves; ++w) c_est = fmaxf(c_est, red[kRopeWaves * GB + w]);
-    int unit_exp = -32;
-    if (c_est > 0.0f && c_est < INFINITY) {
-        int e2;
-        (void)frexpf(c_est, &e2);
-        unit_exp = e2 - 1 - 30;
-    }
-    const int k_units = -unit_exp - 32;
-    float m_eff[GB];
-#pragma unroll
-    for (int g = 0; g < GB; ++g) m_eff[g] = m_c[g] - (float)k_units * 0.69314718f;
-    const int bins = NV * GB;
-    for (int e = tid; e < bins; e += kRopeThreads) hist[e] = 0ull;
-    __syncthreads();
-
-    // ---- pass 2: p = exp(score - max) in histogram units, scatter p * c of the V codes -----------------------
-    float l_thr[GB];
-#pragma unroll
-    for (int g = 0; g < GB; ++g) l_thr[g] = 0.0f;
-#pragma unroll
-    for (int i = 0; i < TPT; ++i) {
-        if (i < n_mine) {
-            const int64_t t = t0 + (int64_t)i * kRopeThreads + (tid & ~63) + 8 * sub + eighth;  // as in pass 1
-            if (t < t_end) {
-                float p[GB];
-#pragma unroll
-                for (int g = 0; g < GB; ++g) { p[g] = __expf(sc[i][g] - m_eff[g]); l_thr[g] += p[g]; }
-                const uint16_t *ip = idxV + (code_row + t) * sVt;
-                const __half *cp = coefV + (code_row + t) * sVt;
-                unsigned long long *hb = hist;
-                for (int ch = 0; ch < snV; ++ch, hb += N, ip += sV, cp += sV) {
-                    for (int j0 = 0; j0 < sV; j0 += PV) {
-                        int id[PV];
-                        float cf[PV];
-                        IdxLoad<uint16_t, PV>::ld(ip + j0, id);
-                        CoefLoad<__half, PV>::ld(cp + j0, cf);
-#pragma unroll
-                        for (int j = 0; j < PV; ++j) {
-#pragma unroll
-                            for (int g = 0; g < GB; ++g) atomicAdd(&hb[g * NV + id[j]], to_fixed(p[g] * cf[j]));
-                        }
-                    }
-                }
-            }
-        }
-    }
-    __syncthreads();
-
-#pragma unroll
-    for (int g = 0; g < GB; ++g) {
-        const float ws = wave_sum(l_thr[g]);
-        if (lane == 0) red[wave * GB + g] = ws;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int g = 0; g < GB; ++g) {
-        if (tid == g) {
-            float l = 0.0f;
-            for (int w = 0; w < kRopeWaves; ++w) l += red[w * GB + g];
-            ml[2 * g] = m_c[g];
-            ml[2 * g + 1] = ldexpf(l, -k_units);
-        }
-    }
-    float *dst = part_hist + slot * (int64_t)bins;
-    const float from_units = ldexpf(1.0f, unit_exp + 32);
-    for (int e = tid; e < bins; e += kRopeThreads) dst[e] = from_fixed(hist[e]) * from_units;
+    finish_chunk<GB, PV, TPT, THREADS>(smem_raw, red, sc, mx, cm, n_mine, t0, t_end, code_row, wave * 64 + 8 * sub + eighth,
+                                            idxV, coefV, N, sV, snV, ml, part_hist, slot);
 }
 
-template <int GB, bool ROTK, int PVK, int PV>
+template <int GB, bool ROTK, int PVK, bool ONEB, int PV>
 hipError_t launch_rope_t(const DecodeArgs &a, const DecodePlan &p, float *hist, float *ml)
 {
-    auto kern = stream_rope_kernel<GB, ROTK, PVK, PV, rope_rounds(GB)>;
+    auto kern = stream_rope_kernel<GB, ROTK, PVK, ONEB, PV, rope_rounds(GB)>;
     static std::atomic<bool> attr_set[kMaxDevices];
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -464,7 +485,7 @@ hipError_t launch_rope_t(const DecodeArgs &a, const DecodePlan &p, float *hist, 
     // the plan's LDS size = dictionary / histogram | reductions | constant tables (see plan_decode)
     const uint32_t tab_bytes = (uint32_t)(p.lds_bytes - (size_t)kStreamWaves * (GB + 1) * sizeof(float) - kRopeTableBytes);
     const dim3 grid((unsigned)p.nchunks, (unsigned)(a.Hkv * p.ngs), (unsigned)a.B);
-    hipLaunchKernelGGL(kern, grid, dim3(kRopeThreads), p.lds_bytes, a.stream, (const __half *)a.q,
+    hipLaunchKernelGGL(kern, grid, dim3(rope_threads(GB)), p.lds_bytes, a.stream, (const __half *)a.q,
                        (const __half *)a.DK, (const uint16_t *)a.idxK, (const __half *)a.coefK,
                        (const uint16_t *)a.idxV, (const __half *)a.coefV, a.seq_lens, hist, ml, a.Hq, a.Hkv, a.G, p.ngs,
                        a.T, a.N, a.sK, a.sV, a.snV, a.scale, a.rope_base, a.rope_layout, a.rope_pos0, p.chunk_tokens,
@@ -472,19 +493,20 @@ hipError_t launch_rope_t(const DecodeArgs &a, const DecodePlan &p, float *hist, 
     return hipGetLastError();
 }
 
-template <int GB, bool ROTK, int PVK>
+template <int GB, bool ROTK, int PVK, bool ONEB>
 hipError_t launch_rope_pv(const DecodeArgs &a, const DecodePlan &p, float *hist, float *ml)
 {
-    if (a.sV % 8 == 0) return launch_rope_t<GB, ROTK, PVK, 8>(a, p, hist, ml);
-    if (a.sV % 4 == 0) return launch_rope_t<GB, ROTK, PVK, 4>(a, p, hist, ml);
-    return launch_rope_t<GB, ROTK, PVK, 1>(a, p, hist, ml);
+    if (a.sV % 8 == 0) return launch_rope_t<GB, ROTK, PVK, ONEB, 8>(a, p, hist, ml);
+    if (a.sV % 4 == 0) return launch_rope_t<GB, ROTK, PVK, ONEB, 4>(a, p, hist, ml);
+    return launch_rope_t<GB, ROTK, PVK, ONEB, 1>(a, p, hist, ml);
 }
 
 template <int GB, bool ROTK>
 hipError_t launch_rope_gb(const DecodeArgs &a, const DecodePlan &p, float *hist, float *ml)
 {
-    if (a.sK % 8 == 0) return launch_rope_pv<GB, ROTK, 8>(a, p, hist, ml);
-    return launch_rope_pv<GB, ROTK, 4>(a, p, hist, ml);
+    if (a.sK == 8) return launch_rope_pv<GB, ROTK, 8, true>(a, p, hist, ml);  // the paper's key codes
+    if (a.sK % 8 == 0) return launch_rope_pv<GB, ROTK, 8, false>(a, p, hist, ml);
+    return launch_rope_pv<GB, ROTK, 4, false>(a, p, hist, ml);
 }
 
 }  // namespace
