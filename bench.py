@@ -12,6 +12,8 @@ the code streams rather than the dictionaries dominate the traffic.  `chunked_st
 storage layout of the paper's experiments ("CSR-8": keys whole with s = 8, values in s_n = 2 chunks of 64
 dimensions with s = 4 each), which runs the 64-dimensional variants of the encoder and the chunk-aware decode.
 `decode_step` is one decoding step: the new token's codes appended in place, then attention over the cache.
+`rope_decode` is csr_decode_attn on keys coded before the rotary embedding (rope_base set), at the dictionary sizes
+of the paper's own experiments (256 atoms per KV head), where the key dictionary stays in LDS.
 
 All kernels run on PyTorch's current stream, and the HIP events that time them (torch.cuda.Event)
 are recorded on that same stream.
@@ -142,6 +144,69 @@ def chunked_step(csr, synth, w, dev, steps):
             "decode_gbs_warm": round(dec_bytes / (d_ms * 1e-3) / 1e9, 1)}
 
 
+# Shapes of the rotary-key decode: the paper's dictionary budget (8192 atoms over 32 heads, 2048 over 8 KV heads:
+# 256 per KV head) and cache layout (keys whole with s = 8, values in 2 chunks with s = 4), 32768 cached tokens.
+ROPE_SHAPES = [
+    {"name": "rope_mha_32heads", "B": 4, "Hq": 32, "Hkv": 32, "T": 32768, "N": 256, "sK": 8, "sV": 4, "snV": 2},
+    {"name": "rope_gqa_8x4heads", "B": 8, "Hq": 32, "Hkv": 8, "T": 32768, "N": 256, "sK": 8, "sV": 4, "snV": 2},
+]
+
+
+def rope_decode(csr, dev, steps):
+    """csr_decode_attn with rope_base = 10000 on ROPE_SHAPES (random codes drawn on the GPU), next to the
+    position-free call on the same tensors.  The rotary path is bound by the vector ALU: its arithmetic per
+    (sequence, KV head, token) is the rebuild of the key (2 s d flop), its rotation (6 flop per frequency pair)
+    and one dot product per query head of the group (2 d flop each), priced against the fp32 vector peak."""
+    import torch
+    d = 128
+    out = []
+    for sh in ROPE_SHAPES:
+        B, Hq, Hkv, T, N, sK, sV, snV = (sh[k] for k in ("B", "Hq", "Hkv", "T", "N", "sK", "sV", "snV"))
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(2)
+
+        def unit(*shape):
+            a = torch.randn(*shape, device=dev, generator=gen)
+            return (a / a.norm(dim=-1, keepdim=True)).half()
+
+        ri = lambda *shape: torch.randint(0, N, shape, device=dev, generator=gen, dtype=torch.int32).to(torch.int16)
+        rc = lambda *shape: (torch.randn(*shape, device=dev, generator=gen) * 3).half()
+        q, DK, DV = torch.randn(B, Hq, d, device=dev, generator=gen).half(), unit(Hkv, N, d), unit(Hkv, snV, N, d // snV)
+        iK, cK = ri(B, Hkv, T, sK), rc(B, Hkv, T, sK)
+        iV, cV = ri(B, Hkv, T, snV, sV), rc(B, Hkv, T, snV, sV)
+        o = torch.empty(B, Hq, d, device=dev, dtype=torch.float16)
+        times = {}
+        for base in (10000.0, 0.0):
+            desc = csr.decode_desc(q, DK, iK, cK, iV, rope_base=base)
+            ws = torch.empty(max(csr.csr_decode_workspace_bytes(desc), 256), dtype=torch.uint8, device=dev)
+            run = lambda: csr.csr_decode_attn(q, DK, iK, cK, DV, iV, cV, out=o, workspace=ws, rope_base=base)
+            for _ in range(2):
+                run()
+            torch.cuda.synchronize()
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+            for a_, b_ in ev:
+                a_.record(); run(); b_.record()
+            torch.cuda.synchronize()
+            times[base] = sum(a_.elapsed_time(b_) for a_, b_ in ev) / steps
+        ms = times[10000.0]
+        G = Hq // Hkv
+        flop = B * Hkv * T * (2 * sK * d + 6 * (d // 2) + 2 * d * G)
+        tf = flop / (ms * 1e-3) / 1e12
+        code_bytes = B * Hkv * T * (sK + snV * sV) * 4
+        out.append({"workload": sh["name"], "kernel": "csr_decode_attn, rope_base = 10000 (3 launches)", "bound": "alu",
+                    "achieved": round(tf, 2), "peak": PEAK_VALU_F32_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(tf / PEAK_VALU_F32_TFLOPS, 5), "flop_per_call": flop, "avg_call_ms": round(ms, 5),
+                    "key_tokens_per_s": round(B * Hkv * T / (ms * 1e-3), 1),
+                    "decode_ctx_tokens_per_s": round(B * T / (ms * 1e-3), 1),
+                    "code_gbs": round(code_bytes / (ms * 1e-3) / 1e9, 1),
+                    "dense_fp16_cache_gbs_equivalent": round(B * Hkv * T * 2 * d * 2 / (ms * 1e-3) / 1e9, 1),
+                    "position_free_call_ms": round(times[0.0], 5),
+                    "config": {"kv_heads": Hkv, "query_heads": Hq, "atoms": N, "tokens_per_head": T, "sK": sK, "sV": sV,
+                               "snV": snV, "decode_batch": B}})
+        del q, DK, DV, iK, cK, iV, cV, o, ws
+    return out
+
+
 def decode_step(csr, synth, w, dev, steps):
     """One decoding step at the workload's shape: the new token's key and value of every (sequence, KV head) are
     encoded straight into the next row of the code cache (csr_encode picks its few-vectors kernel), then
@@ -238,6 +303,8 @@ def main():
                     help="run only the decode-only lines (for profiling them apart from the main workload)")
     ap.add_argument("--only-chunked", action="store_true", help="run only the chunked-layout step (for profiling)")
     ap.add_argument("--only-decode-step", action="store_true", help="run only the decoding step (for profiling)")
+    ap.add_argument("--no-rope", action="store_true", help="skip the rotary-key decode shapes")
+    ap.add_argument("--only-rope", action="store_true", help="run only the rotary-key decode shapes (for profiling)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only copy 1 GiB device-to-device five times and exit: run under rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE, it shows what those counters read for a known amount of traffic")
@@ -269,6 +336,11 @@ def main():
         torch.cuda.set_device(0)
         print(json.dumps({"decode_rooflines": [decode_only(csr, synth.WORKLOADS[n], torch.device("cuda:0"))
                                                for n in ("long_context", "gqa_llama3_8b")]}))
+        return
+
+    if args.only_rope:
+        torch.cuda.set_device(0)
+        print(json.dumps({"rope_decode": rope_decode(csr, torch.device("cuda:0"), args.steps)}))
         return
 
     if args.only_chunked or args.only_decode_step:
@@ -425,6 +497,10 @@ def main():
     # ---- one decoding step: append the new token's codes in place, attend over the grown cache ------------
     if not args.no_decode_step and w.dtype == "f16":
         result["decode_step"] = decode_step(csr, synth, w, dev, args.steps)
+
+    # ---- decode attention on keys coded before the rotary embedding, paper-sized dictionaries -------------
+    if not args.no_rope:
+        result["rope_decode"] = rope_decode(csr, dev, args.steps)
 
     # ---- CPU oracle on a bounded sample of the same workload ---------------------------------------
     if not args.no_cpu_baseline:

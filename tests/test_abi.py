@@ -179,6 +179,17 @@ def test_decode_accepts_rotary_descriptors_within_the_resident_limit():
         assert 0 < need < 1 << 32, kw
 
 
+def test_decode_accepts_one_long_sequence_up_to_the_token_limit():
+    # few (sequence, head) pairs and a long context: the token axis is cut into the most chunks the plan allows
+    lib = csr.lib()
+    for kw in (dict(B=1, Hq=1, Hkv=1, T=1 << 20), dict(B=1, Hq=8, Hkv=8, T=300000),
+               dict(B=1, Hq=2, Hkv=2, T=40000, N=256, rope_base=10000.0)):
+        need = lib.csr_decode_workspace_bytes(ctypes.byref(_dec(**kw)))
+        assert 0 < need < 1 << 34, kw
+    # the rotary kernel keeps a score per round in registers: its chunks hold fewer tokens
+    assert lib.csr_decode_workspace_bytes(ctypes.byref(_dec(B=1, Hq=1, Hkv=1, T=1 << 20, N=256, rope_base=1e4))) == ctypes.c_size_t(-1).value
+
+
 def test_decode_workspace_grows_with_the_chunk_count_and_zero_means_one_chunk():
     lib = csr.lib()
     size = lambda **kw: lib.csr_decode_workspace_bytes(ctypes.byref(_dec(**kw)))
