@@ -105,3 +105,36 @@ def test_decode_on_random_shapes_with_chunks(seed):
             assert np.all(out[b] == 0)
     rel, _ = parity.decode_errors(out[lens > 0], ref[lens > 0])
     assert rel.max() <= 2e-3, (seed, rel.max())
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_rotary_key_decode_on_random_shapes(seed):
+    rng = np.random.default_rng(4000 + seed)
+    B, Hkv, G = int(rng.integers(1, 4)), int(rng.integers(1, 4)), int(rng.choice([1, 2, 3, 4, 8]))
+    T = int(rng.choice([1, 7, 100, 513, 1025, 2100, 9000]))
+    sK, snV, sV = int(rng.choice([4, 8, 12, 16])), int(rng.choice([1, 2])), int(rng.integers(1, 9))
+    N = int(rng.choice([128, 256, 384, 512] if snV > 1 else [64, 200, 256, 384, 512]))  # chunked values: multiples of 128
+    layout, pos0 = int(rng.integers(0, 2)), int(rng.choice([0, 1, 4096, 123457]))
+    base = float(rng.choice([10000.0, 500000.0]))
+    d = 128
+    q = synth.queries(400 + seed, B, Hkv * G, d, "f16")
+    DK = synth.dictionary(400 + seed, "dict_k", Hkv, N, d, "f16")
+    DV = synth.dictionary(400 + seed, "dict_v", Hkv * snV, N, d // snV, "f16").reshape(Hkv, snV, N, d // snV)
+    iK, cK = synth.random_codes(400 + seed, 0, B, Hkv, T, sK, N, "f16", "i16")
+    iV, cV = synth.random_codes(400 + seed, 1, B, Hkv, T, snV * sV, N, "f16", "i16")
+    iV, cV = (np.ascontiguousarray(a.reshape(B, Hkv, T, snV, sV)) for a in (iV, cV))
+    lens = rng.integers(0, T + 1, size=B).astype(np.int32)
+    lens[0] = T
+    g = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    aV = (DV, iV, cV) if snV > 1 else (DV[:, 0], iV[:, :, :, 0], cV[:, :, :, 0])
+    print(f"[rotary random] seed {seed}: B{B} Hkv{Hkv} G{G} T{T} N{N} sK{sK} snV{snV} sV{sV} layout{layout} pos0 {pos0}", flush=True)
+    out = csr.csr_decode_attn(g(q), g(DK), g(iK), g(cK), g(aV[0]), g(aV[1]), g(aV[2]), seq_lens=torch.from_numpy(lens).cuda(),
+                              rope_base=base, rope_layout=layout, rope_pos0=pos0)
+    torch.cuda.synchronize()
+    ref = oracle.decode_attn_rope(q, DK, iK, cK, aV[0], aV[1], aV[2], base, layout, pos0, seq_lens=lens)
+    out = out.cpu().numpy()
+    for b in range(B):
+        if lens[b] == 0:
+            assert np.all(out[b] == 0)
+    rel, _ = parity.decode_errors(out[lens > 0], ref[lens > 0])
+    assert rel.max() <= 2e-3, (seed, rel.max())
