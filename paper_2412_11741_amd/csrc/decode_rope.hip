@@ -5,8 +5,8 @@
 // The rotation depends on the token, so the one score table q . d_n of the position-free path no longer
 // exists: every (token, pair) costs a gathered atom row and d multiply-adds instead of one table entry.  That
 // only pays while the atom rows come from LDS: the kernel keeps the whole key dictionary of its KV head there
-// (N * d * 2 bytes <= 128 KB, the paper's own dictionary sizes) and is bound by the vector ALU and the LDS, not by
-// HBM.  Values carry no position: the V side is the same histogram scatter as in stream_kernel, and out_kernel /
+// (N * d * 2 bytes <= 128 KB, the paper's own dictionary sizes) and is bound by the vector ALU (the count of its
+// instructions), not by HBM.  Values carry no position: the V side is the same histogram scatter as in stream_kernel, and out_kernel /
 // finalize_kernel run unchanged on its results.
 //
 // Two ways to spend the multiply-adds, chosen by the number of query heads that share the KV head:
@@ -73,7 +73,7 @@ __device__ __forceinline__ float sum8(float v)
     return v;
 }
 
-// The rest of a chunk, common to the kernels below: the chunk's maximum, the unit of the fixed-point histogram,
+// The rest of a chunk, common to all variants of the kernel below: the chunk's maximum, the unit of the fixed-point histogram,
 // pass 2 (p = exp(score - max) in histogram units, scatter p * c of the V codes into the LDS histogram, which takes
 // the place of the dictionary rows), and the chunk's histogram, maximum and sum to scratch - exactly what
 // stream_kernel of the position-free path leaves for out_kernel.
