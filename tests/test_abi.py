@@ -186,8 +186,12 @@ def test_decode_accepts_one_long_sequence_up_to_the_token_limit():
                dict(B=1, Hq=2, Hkv=2, T=40000, N=256, rope_base=10000.0)):
         need = lib.csr_decode_workspace_bytes(ctypes.byref(_dec(**kw)))
         assert 0 < need < 1 << 34, kw
-    # the rotary kernel keeps a score per round in registers: its chunks hold fewer tokens
-    assert lib.csr_decode_workspace_bytes(ctypes.byref(_dec(B=1, Hq=1, Hkv=1, T=1 << 20, N=256, rope_base=1e4))) == ctypes.c_size_t(-1).value
+    # the rotary kernel keeps a score per round in registers: its chunks hold fewer tokens (the header states the limits)
+    none = ctypes.c_size_t(-1).value
+    rope = lambda **kw: lib.csr_decode_workspace_bytes(ctypes.byref(_dec(N=256, rope_base=1e4, **kw)))
+    assert rope(B=1, Hq=1, Hkv=1, T=1 << 20) == none
+    assert rope(Hq=2, Hkv=2, T=1 << 19) != none and rope(Hq=2, Hkv=2, T=(1 << 19) + 1) == none
+    assert rope(Hq=8, Hkv=2, T=1 << 18) != none and rope(Hq=8, Hkv=2, T=(1 << 18) + 1) == none
 
 
 def test_decode_workspace_grows_with_the_chunk_count_and_zero_means_one_chunk():
