@@ -13,7 +13,8 @@ storage layout of the paper's experiments ("CSR-8": keys whole with s = 8, value
 dimensions with s = 4 each), which runs the 64-dimensional variants of the encoder and the chunk-aware decode.
 `decode_step` is one decoding step: the new token's codes appended in place, then attention over the cache.
 `rope_decode` is csr_decode_attn on keys coded before the rotary embedding (rope_base set), at the dictionary sizes
-of the paper's own experiments (256 atoms per KV head), where the key dictionary stays in LDS.
+of the paper's own experiments (256 atoms per KV head), where the key dictionary stays in LDS; `paper_sized_step` is
+the chunked step with those dictionaries and that decode.
 
 All kernels run on PyTorch's current stream, and the HIP events that time them (torch.cuda.Event)
 are recorded on that same stream.
@@ -90,12 +91,14 @@ def decode_only(csr, w, dev):
             "config": {"kv_heads": Hkv, "query_heads": Hq, "atoms": N, "tokens_per_head": T, "s": s, "decode_batch": B}}
 
 
-def chunked_step(csr, synth, w, dev, steps):
+def chunked_step(csr, synth, w, dev, steps, n_atoms=None, rope_base=0.0):
     """Encode + decode of one layer in the experiments' "CSR-8" layout: keys whole (s = 8), values in two chunks of
-    d/2 dimensions (s = 4 each, one dictionary of N atoms per chunk).  Same vectors as the main workload."""
+    d/2 dimensions (s = 4 each, one dictionary of N atoms per chunk).  Same vectors as the main workload.
+    n_atoms overrides the workload's dictionary size (256: the paper's own budget per head, which csr_encode serves
+    with its LDS-resident kernel); rope_base > 0 attends with the keys taken as coded before the rotary embedding."""
     import numpy as np
     import torch
-    B, Hkv, Hq, T, N, d = w.batch, w.hkv, w.hq, w.tokens, w.n_atoms, w.d
+    B, Hkv, Hq, T, N, d = w.batch, w.hkv, w.hq, w.tokens, n_atoms or w.n_atoms, w.d
     sK, sV, sn = 8, 4, 2
     g = lambda a: torch.from_numpy(a).to(dev)
     XK = g(np.concatenate([synth.vectors(0, "keys", Hkv, T, d, "f16", outliers=w.key_outliers, token0=b) for b in range(B)]))
@@ -115,12 +118,13 @@ def chunked_step(csr, synth, w, dev, steps):
                       dtype=torch.uint8, device=dev)
     v5 = lambda t, s_: t.view(B, Hkv, T, sn, s_)
     v4 = lambda t, s_: t.view(B, Hkv, T, s_)
-    ddesc = csr.decode_desc(q, DK, v4(iK, sK), v4(cK, sK), v5(iV, sV))
+    ddesc = csr.decode_desc(q, DK, v4(iK, sK), v4(cK, sK), v5(iV, sV), rope_base=rope_base)
     wsD = torch.empty(max(csr.csr_decode_workspace_bytes(ddesc), 256), dtype=torch.uint8, device=dev)
 
     def enc_k(): csr.csr_encode(XK, DKe, sK, idx=iK, coef=cK, workspace=wsK)
     def enc_v(): csr.csr_encode(XV, DVe, sV, idx=iV, coef=cV, workspace=wsV)
-    def dec(): csr.csr_decode_attn(q, DK, v4(iK, sK), v4(cK, sK), DV, v5(iV, sV), v5(cV, sV), out=out, workspace=wsD)
+    def dec(): csr.csr_decode_attn(q, DK, v4(iK, sK), v4(cK, sK), DV, v5(iV, sV), v5(cV, sV), out=out, workspace=wsD,
+                                   rope_base=rope_base)
 
     for _ in range(2):
         enc_k(); enc_v(); dec()
@@ -134,10 +138,15 @@ def chunked_step(csr, synth, w, dev, steps):
     tf = lambda flop, ms: round(flop / (ms * 1e-3) / 1e12, 2)
     v_flop = 2.0 * (d // sn) * N * sV * sn * nv
     dec_bytes = nv * (sK + sn * sV) * 4 + Hkv * 2 * N * d * 2 + B * Hq * d * 4
-    return {"layout": "K s=8 s_n=1, V s=4 s_n=2 (chunks of %d)" % (d // sn), "vectors_per_step": 2 * nv,
+    resident = N * d * 2 <= 128 * 1024   # csr_encode's choice for dictionaries that fit the LDS
+    k_flop = 2.0 * d * N * sK * nv
+    return {"layout": "K s=8 s_n=1, V s=4 s_n=2 (chunks of %d)" % (d // sn), "atoms": N, "rope_base": rope_base,
+            "vectors_per_step": 2 * nv,
             "value": round(2 * nv / ((k_ms + v_ms + d_ms) * 1e-3), 1), "unit": "vectors/s",
             "encode_k_ms": round(k_ms, 4), "encode_v_ms": round(v_ms, 4), "decode_ms_warm": round(d_ms, 5),
-            "roofline_encode_v": {"kernel": "csr_encode (mfma, 64-dimensional chunks)", "bound": "mfma",
+            "encode_k_tflops": tf(k_flop, k_ms),
+            "roofline_encode_v": {"kernel": "csr_encode (%s, 64-dimensional chunks)" % ("resident" if resident else "mfma"),
+                                  "bound": "mfma",
                                   "achieved": tf(v_flop, v_ms), "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s",
                                   "frac": round(tf(v_flop, v_ms) / PEAK_MFMA_F16_TFLOPS, 5)},
             "decode_bytes_per_call": dec_bytes,
@@ -347,8 +356,11 @@ def main():
         torch.cuda.set_device(0)
         w = synth.WORKLOADS[args.workload]
         leg = chunked_step if args.only_chunked else decode_step
-        print(json.dumps({"chunked_step" if args.only_chunked else "decode_step":
-                          leg(csr, synth, w, torch.device("cuda:0"), args.steps)}))
+        res = {"chunked_step" if args.only_chunked else "decode_step": leg(csr, synth, w, torch.device("cuda:0"), args.steps)}
+        if args.only_chunked and not args.no_rope:
+            res["paper_sized_step"] = chunked_step(csr, synth, w, torch.device("cuda:0"), args.steps, n_atoms=256,
+                                                   rope_base=10000.0)
+        print(json.dumps(res))
         return
 
     w = synth.WORKLOADS[args.workload]
@@ -493,6 +505,10 @@ def main():
     # ---- the same layer in the chunked storage layout of the paper's experiments --------------------------
     if not args.no_chunked and w.dtype == "f16" and d == 128:
         result["chunked_step"] = chunked_step(csr, synth, w, dev, args.steps)
+        # the same layer with the paper's own dictionary budget (256 atoms per head) and keys coded before the
+        # rotary embedding: the LDS-resident encoder and the rotary-key decode together
+        if not args.no_rope:
+            result["paper_sized_step"] = chunked_step(csr, synth, w, dev, args.steps, n_atoms=256, rope_base=10000.0)
 
     # ---- one decoding step: append the new token's codes in place, attend over the grown cache ------------
     if not args.no_decode_step and w.dtype == "f16":

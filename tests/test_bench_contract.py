@@ -41,7 +41,8 @@ def test_the_json_line_carries_the_contracts_fields():
     assert abs(out["value"] - out["config"]["vectors_per_step"] / (out["ms_per_step"] * 1e-3)) < 0.01 * out["value"]
     cpu = out["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["cores"] >= 1 and cpu["value"] > 0 and cpu["sample"]
-    for leg in ("roofline_decode", "chunked_step", "decode_step", "reconstruct", "rope_decode"):
+    for leg in ("roofline_decode", "chunked_step", "paper_sized_step", "decode_step", "reconstruct", "rope_decode"):
         assert leg in out, leg
+    assert out["paper_sized_step"]["atoms"] == 256 and out["paper_sized_step"]["rope_base"] == 10000.0
     for r_ in out["rope_decode"]:
         assert r_["bound"] == "alu" and r_["peak"] == 157.3 and abs(r_["frac"] - r_["achieved"] / r_["peak"]) < 1e-4
