@@ -60,9 +60,11 @@ typedef enum {
     CSR_ENCODE_SPLIT = 3, /* few vectors per dictionary (at most 128): every dictionary's atoms are
                             split over several workgroups, one launch per iteration; fp16 inputs,
                             chunks of 64 or 128 dimensions, N a multiple of 32                   */
-    CSR_ENCODE_RESIDENT = 4 /* small dictionaries (N * d/s_n * 2 bytes <= 128 KB, e.g. the 256 - 512 atoms per
+    CSR_ENCODE_RESIDENT = 4, /* small dictionaries (N * d/s_n * 2 bytes <= 128 KB, e.g. the 256 - 512 atoms per
                             head of the paper's experiments): the dictionary stays in LDS, exact
                             fp32-accumulated correlations on the matrix cores; same input types     */
+    CSR_ENCODE_GRAM = 5  /* at most 256 atoms: the correlations of all atoms are updated with the Gram matrix
+                            of the dictionary (kept in LDS) instead of being recomputed; same input types  */
 } csr_encode_algo;
 
 /*

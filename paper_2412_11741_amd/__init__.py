@@ -2,7 +2,7 @@
 
 The product is libcsr_hip.so (C ABI in include/csr.h); this package is its thin binding.
 """
-from .binding import (CSR_ENCODE_AUTO, CSR_ENCODE_MFMA, CSR_ENCODE_RESIDENT, CSR_ENCODE_SPLIT, CSR_ENCODE_VALU,
+from .binding import (CSR_ENCODE_AUTO, CSR_ENCODE_GRAM, CSR_ENCODE_MFMA, CSR_ENCODE_RESIDENT, CSR_ENCODE_SPLIT, CSR_ENCODE_VALU,
                       CsrError,  # noqa: F401
                       csr_code_bytes, csr_decode_attn, csr_decode_workspace_bytes, csr_encode,
                       csr_encode_workspace_bytes, csr_reconstruct, decode_desc, encode_desc, last_error, lib)

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libcsr_hip.so")
 CSR_OK, CSR_ERR_INVALID_ARG, CSR_ERR_UNSUPPORTED, CSR_ERR_WORKSPACE, CSR_ERR_DEVICE = range(5)
 CSR_F32, CSR_F16 = 0, 1
 CSR_I32, CSR_I16 = 0, 1
-CSR_ENCODE_AUTO, CSR_ENCODE_VALU, CSR_ENCODE_MFMA, CSR_ENCODE_SPLIT, CSR_ENCODE_RESIDENT = 0, 1, 2, 3, 4
+CSR_ENCODE_AUTO, CSR_ENCODE_VALU, CSR_ENCODE_MFMA, CSR_ENCODE_SPLIT, CSR_ENCODE_RESIDENT, CSR_ENCODE_GRAM = 0, 1, 2, 3, 4, 5
 
 EXPORTS = ("csr_version", "csr_last_error", "csr_code_bytes", "csr_encode_workspace_bytes",
            "csr_encode", "csr_decode_workspace_bytes", "csr_decode_attn", "csr_reconstruct")

@@ -35,7 +35,7 @@ csr_status check_encode_desc(const csr_encode_desc *d, csr::EncodeArgs *args, in
     if (!valid_dtype(d->x_dtype) || !valid_dtype(d->dict_dtype) || !valid_dtype(d->coef_dtype) || !valid_itype(d->idx_dtype))
         return fail(CSR_ERR_INVALID_ARG, "csr_encode: unknown dtype / index type");
     if (d->algo != CSR_ENCODE_AUTO && d->algo != CSR_ENCODE_VALU && d->algo != CSR_ENCODE_MFMA && d->algo != CSR_ENCODE_SPLIT &&
-        d->algo != CSR_ENCODE_RESIDENT)
+        d->algo != CSR_ENCODE_RESIDENT && d->algo != CSR_ENCODE_GRAM)
         return fail(CSR_ERR_INVALID_ARG, "csr_encode: unknown algo %d", d->algo);
     if (d->s < 1 || d->s > 32) return fail(CSR_ERR_INVALID_ARG, "csr_encode: s=%d outside 1..32", d->s);
     if (d->N < 1) return fail(CSR_ERR_INVALID_ARG, "csr_encode: N=%d must be >= 1", d->N);
@@ -89,6 +89,9 @@ csr_status check_encode_desc(const csr_encode_desc *d, csr::EncodeArgs *args, in
     if (d->algo == CSR_ENCODE_RESIDENT && !resident_ok)
         return fail(CSR_ERR_UNSUPPORTED, "csr_encode: the LDS-resident encoder needs fp16 inputs, chunks of 64 or 128 dimensions, N a multiple "
                     "of 32 and a dictionary of at most 128 KB (got d/s_n=%d N=%d %s)", dc, d->N, a.f16 ? "f16" : "f32");
+    if (d->algo == CSR_ENCODE_GRAM && !csr::encode_gram_supported(a))
+        return fail(CSR_ERR_UNSUPPORTED, "csr_encode: the Gram encoder needs fp16 inputs, chunks of 64 or 128 dimensions and N a multiple "
+                    "of 32, at most 256 (got d/s_n=%d N=%d %s)", dc, d->N, a.f16 ? "f16" : "f32");
     int algo = d->algo;
     if (algo == CSR_ENCODE_AUTO)
         algo = split_ok ? CSR_ENCODE_SPLIT : resident_ok ? CSR_ENCODE_RESIDENT : mfma_ok ? CSR_ENCODE_MFMA : CSR_ENCODE_VALU;
@@ -207,7 +210,8 @@ csr_status csr_encode(const csr_encode_desc *desc, const void *X, const void *D,
     a.stream = static_cast<hipStream_t>(hip_stream);
     const hipError_t e = algo == CSR_ENCODE_MFMA ? csr::launch_encode_mfma(a)
                          : algo == CSR_ENCODE_SPLIT ? csr::launch_encode_split(a)
-                         : algo == CSR_ENCODE_RESIDENT ? csr::launch_encode_resident(a) : csr::launch_encode_valu(a);
+                         : algo == CSR_ENCODE_RESIDENT ? csr::launch_encode_resident(a)
+                         : algo == CSR_ENCODE_GRAM ? csr::launch_encode_gram(a) : csr::launch_encode_valu(a);
     if (e != hipSuccess) return fail(CSR_ERR_DEVICE, "csr_encode: %s", hipGetErrorString(e));
     return CSR_OK;
 }

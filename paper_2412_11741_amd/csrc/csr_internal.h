@@ -51,6 +51,10 @@ hipError_t launch_encode_split(const EncodeArgs &a);
 bool encode_resident_supported(const EncodeArgs &a);
 hipError_t launch_encode_resident(const EncodeArgs &a);
 
+// fp16 encoder for dictionaries of at most 256 atoms: Gram-matrix update of the correlations.
+bool encode_gram_supported(const EncodeArgs &a);
+hipError_t launch_encode_gram(const EncodeArgs &a);
+
 // ---- reconstruct (Eq.12) --------------------------------------------------------------------
 struct ReconstructArgs {
     const void *D;

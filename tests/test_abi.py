@@ -60,6 +60,9 @@ def _enc(**kw):
     (dict(T=200, algo=B.CSR_ENCODE_SPLIT), B.CSR_ERR_UNSUPPORTED), (dict(d=32, T=1, algo=B.CSR_ENCODE_SPLIT), B.CSR_ERR_UNSUPPORTED),
     (dict(s_n=4, algo=B.CSR_ENCODE_MFMA), B.CSR_ERR_UNSUPPORTED),      # chunks of 32: vector-ALU encoder only
     (dict(x_dtype=B.CSR_F32, dict_dtype=B.CSR_F32, algo=B.CSR_ENCODE_MFMA), B.CSR_ERR_UNSUPPORTED),
+    (dict(N=512, algo=B.CSR_ENCODE_GRAM), B.CSR_ERR_UNSUPPORTED),      # the Gram matrix has to fit the LDS
+    (dict(N=200, algo=B.CSR_ENCODE_GRAM), B.CSR_ERR_UNSUPPORTED), (dict(N=256, d=32, algo=B.CSR_ENCODE_GRAM), B.CSR_ERR_UNSUPPORTED),
+    (dict(N=256, x_dtype=B.CSR_F32, dict_dtype=B.CSR_F32, algo=B.CSR_ENCODE_GRAM), B.CSR_ERR_UNSUPPORTED),
 ])
 def test_encode_rejects_bad_descriptors_before_launch(kw, status):
     lib = csr.lib()

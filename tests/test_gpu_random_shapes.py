@@ -12,7 +12,7 @@ from tests import parity
 pytestmark = pytest.mark.gpu
 
 ALGOS = {"valu": csr.CSR_ENCODE_VALU, "mfma": csr.CSR_ENCODE_MFMA, "split": csr.CSR_ENCODE_SPLIT,
-         "resident": csr.CSR_ENCODE_RESIDENT}
+         "resident": csr.CSR_ENCODE_RESIDENT, "gram": csr.CSR_ENCODE_GRAM}
 
 
 def _draw(seed):
@@ -34,6 +34,8 @@ def _supported(c, algo):
         return M <= 128
     if algo == "resident":
         return c["N"] * c["dc"] * 2 <= 128 * 1024
+    if algo == "gram":
+        return c["N"] <= 256
     return True
 
 
