@@ -216,6 +216,36 @@ def rope_decode(csr, dev, steps):
     return out
 
 
+def small_dict_encoders(csr, dev, steps):
+    """The two encoders for dictionaries that fit the LDS - CSR_ENCODE_RESIDENT (what AUTO picks) and
+    CSR_ENCODE_GRAM (the Gram-matrix update of the correlations) - on 64 dictionaries x 4096 vectors of 128
+    dimensions (the benchmark layer's vector count), unit-norm Gaussian atoms and N(0,1) vectors drawn on the GPU."""
+    import torch
+    H, T, d = 64, 4096, 128
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(3)
+    X = torch.randn(H, T, d, device=dev, generator=gen).half()
+    out = []
+    for N in (32, 128, 256):
+        D = torch.randn(H, N, d, device=dev, generator=gen)
+        D = (D / D.norm(dim=-1, keepdim=True)).half()
+        for name, algo in (("resident", csr.CSR_ENCODE_RESIDENT), ("gram", csr.CSR_ENCODE_GRAM)):
+            row = {"atoms": N, "encoder": name}
+            for s in (1, 8):
+                idx = torch.empty((H, T, s), dtype=torch.int16, device=dev)
+                coef = torch.empty((H, T, s), dtype=torch.float16, device=dev)
+                for _ in range(2):
+                    csr.csr_encode(X, D, s, algo=algo, idx=idx, coef=coef)
+                torch.cuda.synchronize()
+                ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+                for a_, b_ in ev:
+                    a_.record(); csr.csr_encode(X, D, s, algo=algo, idx=idx, coef=coef); b_.record()
+                torch.cuda.synchronize()
+                row["ms_s%d" % s] = round(sum(a_.elapsed_time(b_) for a_, b_ in ev) / steps, 4)
+            out.append(row)
+    return out
+
+
 def decode_step(csr, synth, w, dev, steps):
     """One decoding step at the workload's shape: the new token's key and value of every (sequence, KV head) are
     encoded straight into the next row of the code cache (csr_encode picks its few-vectors kernel), then
@@ -312,6 +342,8 @@ def main():
                     help="run only the decode-only lines (for profiling them apart from the main workload)")
     ap.add_argument("--only-chunked", action="store_true", help="run only the chunked-layout step (for profiling)")
     ap.add_argument("--only-decode-step", action="store_true", help="run only the decoding step (for profiling)")
+    ap.add_argument("--only-small-dict", action="store_true",
+                    help="time the LDS-resident and the Gram-update encoder on small dictionaries (for profiling)")
     ap.add_argument("--no-rope", action="store_true", help="skip the rotary-key decode shapes")
     ap.add_argument("--only-rope", action="store_true", help="run only the rotary-key decode shapes (for profiling)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -345,6 +377,11 @@ def main():
         torch.cuda.set_device(0)
         print(json.dumps({"decode_rooflines": [decode_only(csr, synth.WORKLOADS[n], torch.device("cuda:0"))
                                                for n in ("long_context", "gqa_llama3_8b")]}))
+        return
+
+    if args.only_small_dict:
+        torch.cuda.set_device(0)
+        print(json.dumps({"small_dict_encoders": small_dict_encoders(csr, torch.device("cuda:0"), args.steps)}))
         return
 
     if args.only_rope:
