@@ -106,8 +106,7 @@ __global__ __launch_bounds__(kThreads) void encode_gram_kernel(
 #pragma unroll
         for (int f = 0; f < kF; ++f) bfr[f] = atom_frag(i, f);
         const int sw = i & swz_mask;
-#pragma unroll 4
-        for (int t = 0; t < ntile; ++t) {  // (N is a multiple of 32: at least two tiles; four rows' loads in flight)
+        for (int t = 0; t < ntile; ++t) {
             floatx4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
             for (int f = 0; f < kF; ++f) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(atom_frag(16 * t + col, f), bfr[f], acc, 0, 0, 0);
