@@ -64,7 +64,9 @@ typedef enum {
                             head of the paper's experiments): the dictionary stays in LDS, exact
                             fp32-accumulated correlations on the matrix cores; same input types     */
     CSR_ENCODE_GRAM = 5  /* at most 256 atoms: the correlations of all atoms are updated with the Gram matrix
-                            of the dictionary (kept in LDS) instead of being recomputed; same input types  */
+                            of the dictionary (kept in LDS, in fp16: atom norms must stay below 250) instead of
+                            being recomputed; same input types.  Never picked by AUTO: on this chip it is
+                            slower than RESIDENT                                                         */
 } csr_encode_algo;
 
 /*
