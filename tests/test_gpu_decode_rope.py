@@ -116,3 +116,33 @@ def test_keys_encoded_before_rotation_end_to_end():
         p = np.exp(sc - sc.max())
         dense[0, h] = (p / p.sum()) @ XV[h].astype(np.float64)
     assert np.linalg.norm(ref - dense) < np.linalg.norm(dense)  # loose: sanity only
+
+
+@pytest.mark.parametrize("shape,picks", [("rope_mha_32heads", [(0, 0), (3, 31), (2, 17)]),
+                                         ("rope_gqa_8x4heads", [(0, 0), (7, 7), (4, 3)])])
+def test_bench_shapes_full_launch_sampled(shape, picks):
+    """The whole configuration bench.py times in one call (random codes drawn on the GPU, keys whole with s = 8,
+    values in two chunks with s = 4, 32768 tokens at positions from 1000 on); the oracle recomputes the sampled
+    (sequence, KV head) pairs from the bits copied back."""
+    import bench
+    sh = next(x for x in bench.ROPE_SHAPES if x["name"] == shape)
+    B, Hq, Hkv, T, N, sK, sV, snV = (sh[k] for k in ("B", "Hq", "Hkv", "T", "N", "sK", "sV", "snV"))
+    G, d = Hq // Hkv, 128
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(21)
+    unit = lambda *s_: (lambda a: (a / a.norm(dim=-1, keepdim=True)).half())(torch.randn(*s_, device=dev, generator=gen))
+    ri = lambda *s_: torch.randint(0, N, s_, device=dev, generator=gen, dtype=torch.int32).to(torch.int16)
+    rc = lambda *s_: (torch.randn(*s_, device=dev, generator=gen) * 3).half()
+    q, DK, DV = torch.randn(B, Hq, d, device=dev, generator=gen).half(), unit(Hkv, N, d), unit(Hkv, snV, N, d // snV)
+    iK, cK, iV, cV = ri(B, Hkv, T, sK), rc(B, Hkv, T, sK), ri(B, Hkv, T, snV, sV), rc(B, Hkv, T, snV, sV)
+    out = csr.csr_decode_attn(q, DK, iK, cK, DV, iV, cV, rope_base=10000.0, rope_pos0=1000)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+    h_ = lambda t: t.cpu().numpy()
+    for b, h in picks:
+        print(f"[rope full launch] {shape} sequence {b} KV head {h}", flush=True)
+        ref = oracle.decode_attn_rope(h_(q[b:b + 1, h * G:(h + 1) * G]), h_(DK[h:h + 1]), h_(iK[b:b + 1, h:h + 1]),
+                                      h_(cK[b:b + 1, h:h + 1]), h_(DV[h:h + 1]), h_(iV[b:b + 1, h:h + 1]),
+                                      h_(cV[b:b + 1, h:h + 1]), 10000.0, 0, 1000)
+        _check(h_(out[b:b + 1, h * G:(h + 1) * G]), ref, f"{shape} full launch, sequence {b} KV head {h}")
