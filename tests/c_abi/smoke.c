@@ -131,9 +131,31 @@ int main(void)
     }
     if (!(ref > 0.0) || sqrt(err / ref) > 2e-3) { printf("decode: one cached token, relative error %g\n", sqrt(err / ref)); return 7; }
 
+    /* the same attention with the keys taken as coded before the rotary embedding: with a single cached token the
+     * soft-max weight is 1 whatever the rotation, so the output is again that token's value */
+    q.rope_base = 10000.0f; q.rope_layout = 0; q.rope_pos0 = 5;
+    if (csr_decode_workspace_bytes(&q) > (dneed ? dneed : 256)) { printf("rotary decode wants a larger workspace\n"); return 9; }
+    CHECK_HIP(hipMemset(dOut, 0, 2 * D));
+    CHECK_CSR(csr_decode_attn(&q, dQ, dD, dIdx, dCoef, (const char *)dD + 2 * N * D, idxV, coefV, (const int32_t *)dLens, dOut,
+                              dWs2, dneed ? dneed : 256, NULL));
+    CHECK_HIP(hipDeviceSynchronize());
+    unsigned short hOut2[D];
+    CHECK_HIP(hipMemcpy(hOut2, dOut, sizeof hOut2, hipMemcpyDeviceToHost));
+    if (memcmp(hOut, hOut2, sizeof hOut) != 0) { printf("rotary decode of one cached token differs from the plain one\n"); return 10; }
+
+    /* the Gram-update encoder is a different kernel for the same codes */
+    e.algo = CSR_ENCODE_GRAM;
+    CHECK_HIP(hipMemset(dIdx, 0xff, sizeof hIdx));
+    CHECK_CSR(csr_encode(&e, dX, dD, dIdx, dCoef, NULL, 0, NULL));
+    CHECK_HIP(hipDeviceSynchronize());
+    unsigned short hIdx2[H * T * S];
+    CHECK_HIP(hipMemcpy(hIdx2, dIdx, sizeof hIdx2, hipMemcpyDeviceToHost));
+    if (memcmp(hIdx, hIdx2, sizeof hIdx) != 0) { printf("the Gram encoder picked other atoms\n"); return 11; }
+    e.algo = CSR_ENCODE_AUTO;
+
     /* an invalid request comes back as a status with a message, not as a crash */
     e.s = 0;
     if (csr_encode(&e, dX, dD, dIdx, dCoef, dWs, need, NULL) != CSR_ERR_INVALID_ARG || csr_last_error()[0] == 0) return 8;
-    printf("c abi smoke ok: encode, reconstruct, decode (rel err %.2e)\n", sqrt(err / ref));
+    printf("c abi smoke ok: encode (two kernels), reconstruct, decode (plain and rotary keys; rel err %.2e)\n", sqrt(err / ref));
     return 0;
 }
