@@ -253,10 +253,18 @@ __global__ __launch_bounds__(rope_threads(GB)) void stream_rope_kernel(
         co = __builtin_amdgcn_cosf(f);
         si = __builtin_amdgcn_sinf(f);
     };
+    // the step constants are applied dozens of times in a row, so their angles get the library's accurate sine and
+    // cosine (one thread per constant, once per workgroup); a lane's starting phase above is applied once
+    auto cos_sin_exact = [&](int k, double positions, float &co, float &si) {
+        const double r = positions * theta[k] * 0.15915494309189533577;
+        const double a = (r - rint(r)) * 6.283185307179586476925;
+        co = (float)cos(a);
+        si = (float)sin(a);
+    };
     if (tid < 64) {
         const int sb = tid >> 3, e = tid & 7, k = pair_of(sb, e);
-        cos_sin(k, 8.0, ctab[sb * 32 + e], ctab[sb * 32 + 8 + e]);
-        cos_sin(k, (double)(THREADS - 64), ctab[sb * 32 + 16 + e], ctab[sb * 32 + 24 + e]);
+        cos_sin_exact(k, 8.0, ctab[sb * 32 + e], ctab[sb * 32 + 8 + e]);
+        cos_sin_exact(k, (double)(THREADS - 64), ctab[sb * 32 + 16 + e], ctab[sb * 32 + 24 + e]);
         if constexpr (ROTK) {
 #pragma unroll
             for (int g = 0; g < GB; ++g) {
