@@ -21,6 +21,21 @@ def test_more_than_one_gpu_is_refused_with_a_message():
     assert r.returncode != 0 and "single-GPU" in r.stderr
 
 
+def test_the_rotary_bench_shapes_are_shapes_the_library_takes():
+    # (descriptor checks run on the host: no GPU needed)
+    import ctypes
+    sys.path.insert(0, ROOT)
+    import bench
+    import paper_2412_11741_amd as csr
+    from paper_2412_11741_amd import binding as B
+    for sh in bench.ROPE_SHAPES:
+        d = B.DecodeDesc(B=sh["B"], Hq=sh["Hq"], Hkv=sh["Hkv"], T=sh["T"], d=128, N=sh["N"], sK=sh["sK"], sV=sh["sV"], snK=1,
+                         snV=sh["snV"], scale=0.0, q_dtype=B.CSR_F16, dict_dtype=B.CSR_F16, coef_dtype=B.CSR_F16,
+                         idx_dtype=B.CSR_I16, out_dtype=B.CSR_F16, flags=0, rope_base=10000.0, rope_layout=0, rope_pos0=0)
+        need = csr.lib().csr_decode_workspace_bytes(ctypes.byref(d))
+        assert 0 < need < 1 << 32, (sh, csr.last_error())
+
+
 @pytest.mark.gpu
 def test_the_json_line_carries_the_contracts_fields():
     r = _bench("--steps", "3", "--warmup", "1", "--no-extra-decode")
