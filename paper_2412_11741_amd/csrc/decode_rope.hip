@@ -277,7 +277,7 @@ __global__ __launch_bounds__(rope_threads(GB)) void stream_rope_kernel(
     const unsigned char *rows0 = smem_raw + sub * 16;
     const float *my_c = ctab + sub * 32;
     const uint32_t *my_q = qtab + sub * GB * 8;
-    // the rotating state, at the position of the token this eighth handles in step 0 of round 0.
+    // the rotating state, at the position of the first token this eighth handles (step 0 of the first pass over 64).
     // ROTK: (ra, rb) = (cos, sin) of position * theta; else: the query pair turned back by that angle, scaled
     constexpr int NR = ROTK ? 1 : GB;
     float ra[NR][8], rb[NR][8];
