@@ -226,6 +226,17 @@ csr_status csr_reconstruct(const csr_reconstruct_desc *desc, const void *D, cons
                            void *out, void *hip_stream);
 
 /*
+ * Squared Euclidean norms of dictionary atoms: norms2[n] = |D[n]|^2 (fp32 sum) for the n_atoms rows of d elements
+ * of D - all dictionaries of a call are one such array, n_atoms = dictionaries * (chunks *) N.  Section "Sparse
+ * representation" takes the atoms to have unit norm; csr_encode does not check it (the result is Eq.2-4 for
+ * whatever atoms it is given), so a caller that wants the check runs this first.
+ *   D       device, aligned to its element type     in
+ *   norms2  device, [n_atoms] float                 out
+ * n_atoms >= 0, 1 <= d <= 65536.  No workspace.
+ */
+csr_status csr_atom_norms2(const void *D, int32_t dict_dtype, int64_t n_atoms, int32_t d, float *norms2, void *hip_stream);
+
+/*
  * Storage accounting of Section "Analysis for CSR": bytes kept per head vector,
  * s * s_n * (index bytes + coefficient bytes).  Returns 0 on bad arguments.
  */

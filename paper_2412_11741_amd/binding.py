@@ -79,6 +79,8 @@ def lib():
         L.csr_encode.argtypes = [ctypes.POINTER(EncodeDesc), vp, vp, vp, vp, vp, sz, vp]
         L.csr_reconstruct.restype = ctypes.c_int
         L.csr_reconstruct.argtypes = [ctypes.POINTER(ReconstructDesc), vp, vp, vp, vp, vp]
+        L.csr_atom_norms2.restype = ctypes.c_int
+        L.csr_atom_norms2.argtypes = [vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, vp, vp]
         L.csr_decode_workspace_bytes.restype = sz
         L.csr_decode_workspace_bytes.argtypes = [ctypes.POINTER(DecodeDesc)]
         L.csr_decode_attn.restype = ctypes.c_int
@@ -215,6 +217,23 @@ def csr_reconstruct(D, idx, coef, out=None, out_dtype=None):
                            out_stride_h=out.stride(0) if H > 1 and T > 0 else 0,
                            out_stride_t=out.stride(1) if T > 1 else 0, flags=0)
     _check(lib().csr_reconstruct(ctypes.byref(desc), _ptr(D), _ptr(idx), _ptr(coef), _ptr(out), _stream()))
+    return out
+
+
+def csr_atom_norms2(D, out=None):
+    """Squared norms of the atoms of D [..., N, d] (fp16 or fp32) -> fp32 [..., N]; Section "Sparse representation"
+    takes them to be 1."""
+    _dev(D, "D")
+    if D.dim() < 2 or D.dtype not in _DT:
+        raise ValueError("D must be [..., N, d] in fp16 or fp32")
+    D = D.contiguous()
+    shape = tuple(D.shape[:-1])
+    if out is None:
+        out = torch.empty(shape, dtype=torch.float32, device=D.device)
+    _dev(out, "out")
+    if tuple(out.shape) != shape or out.dtype != torch.float32 or not out.is_contiguous():
+        raise ValueError(f"out must be a contiguous fp32 tensor of shape {shape}")
+    _check(lib().csr_atom_norms2(_ptr(D), _DT[D.dtype], out.numel(), D.shape[-1], _ptr(out), _stream()))
     return out
 
 

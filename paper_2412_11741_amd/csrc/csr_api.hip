@@ -260,6 +260,20 @@ csr_status csr_reconstruct(const csr_reconstruct_desc *d, const void *D, const v
     return CSR_OK;
 }
 
+csr_status csr_atom_norms2(const void *D, int32_t dict_dtype, int64_t n_atoms, int32_t d, float *norms2, void *hip_stream)
+{
+    if (!valid_dtype(dict_dtype)) return fail(CSR_ERR_INVALID_ARG, "csr_atom_norms2: unknown dtype %d", dict_dtype);
+    if (n_atoms < 0 || d < 1 || d > 65536)
+        return fail(CSR_ERR_INVALID_ARG, "csr_atom_norms2: n_atoms=%lld must be >= 0 and d=%d in 1..65536", (long long)n_atoms, d);
+    if (n_atoms == 0) return CSR_OK;
+    if (!D || !norms2) return fail(CSR_ERR_INVALID_ARG, "csr_atom_norms2: NULL pointer");
+    if (!aligned(D, dict_dtype == CSR_F16 ? 2 : 4) || !aligned(norms2, 4))
+        return fail(CSR_ERR_INVALID_ARG, "csr_atom_norms2: misaligned pointer");
+    const hipError_t e = csr::launch_atom_norms2(D, dict_dtype == CSR_F16, n_atoms, d, norms2, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail(CSR_ERR_DEVICE, "csr_atom_norms2: %s", hipGetErrorString(e));
+    return CSR_OK;
+}
+
 size_t csr_decode_workspace_bytes(const csr_decode_desc *desc)
 {
     csr::DecodePlan p{};

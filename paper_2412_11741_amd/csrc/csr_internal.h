@@ -55,6 +55,9 @@ hipError_t launch_encode_resident(const EncodeArgs &a);
 bool encode_gram_supported(const EncodeArgs &a);
 hipError_t launch_encode_gram(const EncodeArgs &a);
 
+// ---- atom norms -----------------------------------------------------------------------------------------------------
+hipError_t launch_atom_norms2(const void *D, bool f16, int64_t n_atoms, int32_t d, float *out, hipStream_t stream);
+
 // ---- reconstruct (Eq.12) --------------------------------------------------------------------
 struct ReconstructArgs {
     const void *D;

@@ -219,6 +219,19 @@ def test_reconstruct_rejects_bad_descriptors():
     assert lib.csr_reconstruct(ctypes.byref(B.ReconstructDesc(**base)), None, p, p, p, None) == B.CSR_ERR_INVALID_ARG
 
 
+def test_atom_norms2_rejects_bad_arguments():
+    lib = csr.lib()
+    p = ctypes.c_void_p(0x1000)
+    assert lib.csr_atom_norms2(p, 7, 10, 128, p, None) == B.CSR_ERR_INVALID_ARG
+    assert lib.csr_atom_norms2(p, B.CSR_F16, -1, 128, p, None) == B.CSR_ERR_INVALID_ARG
+    assert lib.csr_atom_norms2(p, B.CSR_F16, 10, 0, p, None) == B.CSR_ERR_INVALID_ARG
+    assert lib.csr_atom_norms2(p, B.CSR_F16, 10, 70000, p, None) == B.CSR_ERR_INVALID_ARG
+    assert lib.csr_atom_norms2(None, B.CSR_F16, 10, 128, p, None) == B.CSR_ERR_INVALID_ARG
+    assert lib.csr_atom_norms2(ctypes.c_void_p(0x1002), B.CSR_F32, 10, 128, p, None) == B.CSR_ERR_INVALID_ARG
+    assert b"misaligned" in lib.csr_last_error()
+    assert lib.csr_atom_norms2(None, B.CSR_F16, 0, 128, None, None) == B.CSR_OK
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     X = torch.zeros(1, 4, 128, dtype=torch.float16)
