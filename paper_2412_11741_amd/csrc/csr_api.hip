@@ -26,7 +26,7 @@ bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) %
 size_t round256(size_t v) { return (v + 255) & ~size_t(255); }
 
 // Checks everything about an encode descriptor that does not need the pointers; fills the shape part of the
-// kernels' arguments and names the kernel that will run (one of VALU, MFMA, SPLIT).
+// kernels' arguments and names the kernel that will run (AUTO resolved to one of the others).
 csr_status check_encode_desc(const csr_encode_desc *d, csr::EncodeArgs *args, int *algo_out)
 {
     if (!d) return fail(CSR_ERR_INVALID_ARG, "csr_encode: descriptor is NULL");
