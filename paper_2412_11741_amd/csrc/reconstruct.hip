@@ -46,6 +46,15 @@ __device__ __forceinline__ int load_idx(const int32_t *p) { return *p; }
 __device__ __forceinline__ float load_coef(const __half *p) { return __half2float(*p); }
 __device__ __forceinline__ float load_coef(const float *p) { return *p; }
 
+// Workgroups are dealt to the 8 XCDs round-robin, and each XCD has an L2 of its own (4 MB).  Numbered plainly, the
+// workgroups in flight span several dictionaries and every L2 would have to hold all of them; give each XCD a
+// contiguous eighth of the elements instead, so that at any time it gathers from one or two dictionaries.
+__device__ __forceinline__ int64_t xcd_contiguous_block()
+{
+    const unsigned b = blockIdx.x, per = gridDim.x >> 3;
+    return b < per * 8u ? (int64_t)(b & 7u) * per + (b >> 3) : (int64_t)b;
+}
+
 struct Where {
     int64_t h, t, code;
     int ch, pc;
@@ -74,7 +83,7 @@ __global__ __launch_bounds__(256) void reconstruct_kernel(const TD *__restrict__
 {
     const int pieces = d >> 3;             // lanes per vector
     const int dc = d / sn, ppc = dc >> 3;  // dimensions / pieces per chunk
-    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t e = xcd_contiguous_block() * 256 + threadIdx.x;
     if (e >= total) return;
     const Where w = locate(e, pieces, ppc, T, sn, s, code_stride_h);
     const TD *Dh = Dict + ((int64_t)(w.h % dict_count) * sn + w.ch) * N * dc + w.pc * 8;
@@ -103,7 +112,7 @@ __global__ __launch_bounds__(256) void reconstruct_vec_kernel(const TD *__restri
 {
     const int pieces = d >> 3;
     const int dc = d / sn, ppc = dc >> 3;
-    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t e = xcd_contiguous_block() * 256 + threadIdx.x;
     if (e >= total) return;
     const Where w = locate(e, pieces, ppc, T, sn, 8 * G, code_stride_h);
     uint4 qi[G], qc[G];
