@@ -297,8 +297,9 @@ __global__ __launch_bounds__(64 * W, 8 / W) void encode_mfma_kernel(
 
     // Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous run of work so
     // that workgroups sharing a dictionary share an L2.
+    // (The n_groups % 8 workgroups at the end keep their own numbers.)
     int work = blockIdx.x;
-    if ((n_groups & 7) == 0) work = (blockIdx.x & 7) * (n_groups >> 3) + (blockIdx.x >> 3);
+    if ((int)blockIdx.x < (n_groups & ~7)) work = (blockIdx.x & 7) * (n_groups >> 3) + (blockIdx.x >> 3);
     // Work is dealt per dictionary, not per vector block: dct = dictionary * sn + chunk owns the vectors of all
     // blocks that use it (block h uses dictionary h % dict_count), numbered m = (h / dict_count) * T + t, in tiles
     // of 256.  Blocks with few vectors that share a dictionary - a batch of sequences in a decoding step - then
