@@ -106,6 +106,14 @@ typedef struct {
                            squared norm of what the s pairs leave of each vector (chunk) - by Eq.4 the
                            squared reconstruction error |x - D r|^2 with unrounded coefficients, i.e. the
                            vector's term of the dictionary-training loss of Section "NeuralDict"       */
+    const void *gram;   /* optional device pointer, or NULL: the Gram matrices of D as csr_gram_build writes them
+                           ([dict_count][N][N] fp16; chunked [dict_count][s_n][N][N]).  With them, CSR_ENCODE_GRAM -
+                           and CSR_ENCODE_AUTO - encode up to 16 vectors per dictionary (the tokens of one decoding
+                           step) with ONE sweep of each dictionary instead of s: later iterations read one row of
+                           the Gram matrix per vector.  fp16 inputs, chunks of 64 or 128, N a multiple of 32, at
+                           most 16384.  Results are those of the other encoders (the Gram recursion screens, the
+                           decision is taken on the atoms).  Other explicit algos ignore it.  The matrices must
+                           belong to exactly this D                                                      */
 } csr_encode_desc;
 
 /* Bytes of device scratch csr_encode needs for this descriptor (may be 0); (size_t)-1 if the
@@ -224,6 +232,17 @@ typedef struct {
  */
 csr_status csr_reconstruct(const csr_reconstruct_desc *desc, const void *D, const void *idx, const void *coef,
                            void *out, void *hip_stream);
+
+/*
+ * Gram matrices G = D D^T of n_dicts dictionaries of N atoms with d elements each (fp16; with chunks, n_dicts counts
+ * the chunk dictionaries and d is the chunk length): gram[k][i][n] = fp16(d_i . d_n), for csr_encode_desc.gram.
+ * This is the "C - c G[i,:]" form of Eq.2-4's correlations; prepare it once per dictionary.
+ *   D     device, [n_dicts][N][d] fp16, 16-byte aligned            in
+ *   gram  device, csr_gram_bytes(n_dicts, N) bytes, 16-byte aligned  out
+ * d must be 64 or 128, N a multiple of 32, at most 16384; n_dicts at most 65535.  No workspace.
+ */
+size_t csr_gram_bytes(int32_t n_dicts, int32_t N);
+csr_status csr_gram_build(const void *D, int32_t n_dicts, int32_t N, int32_t d, void *gram, void *hip_stream);
 
 /*
  * Squared Euclidean norms of dictionary atoms: norms2[n] = |D[n]|^2 (fp32 sum) for the n_atoms rows of d elements

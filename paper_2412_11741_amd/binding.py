@@ -18,7 +18,8 @@ CSR_I32, CSR_I16 = 0, 1
 CSR_ENCODE_AUTO, CSR_ENCODE_VALU, CSR_ENCODE_MFMA, CSR_ENCODE_SPLIT, CSR_ENCODE_RESIDENT, CSR_ENCODE_GRAM = 0, 1, 2, 3, 4, 5
 
 EXPORTS = ("csr_version", "csr_last_error", "csr_code_bytes", "csr_encode_workspace_bytes",
-           "csr_encode", "csr_decode_workspace_bytes", "csr_decode_attn", "csr_reconstruct")
+           "csr_encode", "csr_decode_workspace_bytes", "csr_decode_attn", "csr_reconstruct", "csr_atom_norms2",
+           "csr_gram_bytes", "csr_gram_build")
 
 
 class EncodeDesc(ctypes.Structure):
@@ -29,7 +30,7 @@ class EncodeDesc(ctypes.Structure):
                 ("idx_dtype", ctypes.c_int32), ("x_stride_h", ctypes.c_int64),
                 ("x_stride_t", ctypes.c_int64), ("dict_count", ctypes.c_int32),
                 ("code_stride_h", ctypes.c_int64), ("algo", ctypes.c_int32), ("flags", ctypes.c_uint32),
-                ("res_norm2", ctypes.c_void_p)]
+                ("res_norm2", ctypes.c_void_p), ("gram", ctypes.c_void_p)]
 
 
 class ReconstructDesc(ctypes.Structure):
@@ -79,6 +80,10 @@ def lib():
         L.csr_encode.argtypes = [ctypes.POINTER(EncodeDesc), vp, vp, vp, vp, vp, sz, vp]
         L.csr_reconstruct.restype = ctypes.c_int
         L.csr_reconstruct.argtypes = [ctypes.POINTER(ReconstructDesc), vp, vp, vp, vp, vp]
+        L.csr_gram_bytes.restype = sz
+        L.csr_gram_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32]
+        L.csr_gram_build.restype = ctypes.c_int
+        L.csr_gram_build.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp]
         L.csr_atom_norms2.restype = ctypes.c_int
         L.csr_atom_norms2.argtypes = [vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, vp, vp]
         L.csr_decode_workspace_bytes.restype = sz
@@ -140,15 +145,35 @@ def csr_encode_workspace_bytes(desc):
     return int(n)
 
 
+def csr_gram_build(D, out=None):
+    """Gram matrices of fp16 dictionaries D [H', N, d] (or chunked [H', s_n, N, d / s_n]) -> fp16 [H', N, N]
+    ([H', s_n, N, N]), for csr_encode(..., gram=...): C - c G[i, :], the Gram form of Eq.2-4's correlations."""
+    _dev(D, "D")
+    if D.dim() not in (3, 4) or D.dtype != torch.float16:
+        raise ValueError("D must be an fp16 tensor [H', N, d] or [H', s_n, N, d / s_n]")
+    D = D.contiguous()
+    N, d = D.shape[-2], D.shape[-1]
+    shape = tuple(D.shape[:-1]) + (N,)
+    n_dicts = D.numel() // (N * d) if N * d else 0
+    if out is None:
+        out = torch.empty(shape, dtype=torch.float16, device=D.device)
+    _dev(out, "out")
+    if tuple(out.shape) != shape or out.dtype != torch.float16 or not out.is_contiguous():
+        raise ValueError(f"out must be a contiguous fp16 tensor of shape {shape}")
+    _check(lib().csr_gram_build(_ptr(D), n_dicts, N, d, _ptr(out), _stream()))
+    return out
+
+
 def csr_encode(X, D, s, coef_dtype=None, idx_dtype=None, algo=CSR_ENCODE_AUTO, idx=None, coef=None,
-               workspace=None, res_norm2=None):
+               workspace=None, res_norm2=None, gram=None):
     """Matching Pursuit encode.  X [H, T, d], D [H, N, d] on the GPU -> (idx, coef) [H, T, s].
     Chunked: D [H, s_n, N, d / s_n] -> (idx, coef) [H, T, s_n, s], every chunk encoded on its own dictionary.
     D may hold H' < H dictionaries (H' divides H): block h uses dictionary h % H' (blocks ordered sequence-major,
     head-minor).  `idx` / `coef` may be views into a larger cache whose blocks are further apart (stride(0) larger
     than one block's codes, the rest contiguous): the codes are then written in place, e.g. appended at a token
     position.  `res_norm2` (fp32, [H, T] or [H, T, s_n], contiguous) receives the squared norm of each vector's
-    final residual, i.e. its squared reconstruction error."""
+    final residual, i.e. its squared reconstruction error.  `gram` (csr_gram_build(D)) lets a few vectors per
+    dictionary - one decoding step's - be encoded with one sweep of each dictionary instead of s."""
     _dev(X, "X"); _dev(D, "D")
     if X.dim() != 3 or D.dim() not in (3, 4) or D.shape[0] < 1 or X.shape[0] % D.shape[0] != 0 or \
             D.shape[-1] * (D.shape[1] if D.dim() == 4 else 1) != X.shape[2]:
@@ -178,6 +203,12 @@ def csr_encode(X, D, s, coef_dtype=None, idx_dtype=None, algo=CSR_ENCODE_AUTO, i
         if tuple(res_norm2.shape) != want or res_norm2.dtype != torch.float32 or not res_norm2.is_contiguous():
             raise ValueError(f"res_norm2 must be a contiguous float32 tensor of shape {want}")
         desc.res_norm2 = res_norm2.data_ptr()
+    if gram is not None:
+        _dev(gram, "gram")
+        want = tuple(D.shape[:-1]) + (D.shape[-2],)
+        if tuple(gram.shape) != want or gram.dtype != torch.float16 or not gram.is_contiguous():
+            raise ValueError(f"gram must be a contiguous fp16 tensor of shape {want} (csr_gram_build(D))")
+        desc.gram = gram.data_ptr()
     need = csr_encode_workspace_bytes(desc)
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=X.device)

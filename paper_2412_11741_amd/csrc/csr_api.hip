@@ -20,6 +20,8 @@ csr_status fail(csr_status st, const char *fmt, ...)
     return st;
 }
 
+constexpr int kAlgoGramStep = 100;  // CSR_ENCODE_GRAM with the descriptor's Gram matrices (internal)
+
 bool valid_dtype(int32_t v) { return v == CSR_F32 || v == CSR_F16; }
 bool valid_itype(int32_t v) { return v == CSR_I32 || v == CSR_I16; }
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -89,12 +91,19 @@ csr_status check_encode_desc(const csr_encode_desc *d, csr::EncodeArgs *args, in
     if (d->algo == CSR_ENCODE_RESIDENT && !resident_ok)
         return fail(CSR_ERR_UNSUPPORTED, "csr_encode: the LDS-resident encoder needs fp16 inputs, chunks of 64 or 128 dimensions, N a multiple "
                     "of 32 and a dictionary of at most 128 KB (got d/s_n=%d N=%d %s)", dc, d->N, a.f16 ? "f16" : "f32");
-    if (d->algo == CSR_ENCODE_GRAM && !csr::encode_gram_supported(a))
+    a.gram = d->gram;
+    const bool step_ok = d->gram != nullptr && csr::encode_gramstep_supported(a);
+    if (d->algo == CSR_ENCODE_GRAM && d->gram && !step_ok)
+        return fail(CSR_ERR_UNSUPPORTED, "csr_encode: the Gram encoder with prepared Gram matrices needs fp16 inputs, chunks of 64 or 128 "
+                    "dimensions, N a multiple of 32, at most 16384, and at most 16 vectors per dictionary (got d/s_n=%d N=%d %s, %lld "
+                    "vectors per dictionary)", dc, d->N, a.f16 ? "f16" : "f32", (long long)(a.dict_count ? (int64_t)(a.H / a.dict_count) * a.T : 0));
+    if (d->algo == CSR_ENCODE_GRAM && !d->gram && !csr::encode_gram_supported(a))
         return fail(CSR_ERR_UNSUPPORTED, "csr_encode: the Gram encoder needs fp16 inputs, chunks of 64 or 128 dimensions and N a multiple "
-                    "of 32, at most 256 (got d/s_n=%d N=%d %s)", dc, d->N, a.f16 ? "f16" : "f32");
+                    "of 32, at most 256 - or the descriptor's gram matrices (got d/s_n=%d N=%d %s)", dc, d->N, a.f16 ? "f16" : "f32");
     int algo = d->algo;
+    if (algo == CSR_ENCODE_GRAM && d->gram) algo = kAlgoGramStep;
     if (algo == CSR_ENCODE_AUTO)
-        algo = split_ok ? CSR_ENCODE_SPLIT : resident_ok ? CSR_ENCODE_RESIDENT : mfma_ok ? CSR_ENCODE_MFMA : CSR_ENCODE_VALU;
+        algo = step_ok ? kAlgoGramStep : split_ok ? CSR_ENCODE_SPLIT : resident_ok ? CSR_ENCODE_RESIDENT : mfma_ok ? CSR_ENCODE_MFMA : CSR_ENCODE_VALU;
     *args = a;
     *algo_out = algo;
     return CSR_OK;
@@ -105,6 +114,7 @@ size_t encode_workspace(const csr::EncodeArgs &a, int algo)
     if (a.H == 0 || a.T == 0) return 0;
     if (algo == CSR_ENCODE_MFMA) return csr::encode_mfma_workspace_bytes(a.dict_count * a.sn, a.T, a.N, a.s);
     if (algo == CSR_ENCODE_SPLIT) return csr::encode_split_workspace_bytes(a);
+    if (algo == kAlgoGramStep) return csr::encode_gramstep_workspace_bytes(a);
     return 0;
 }
 
@@ -204,6 +214,7 @@ csr_status csr_encode(const csr_encode_desc *desc, const void *X, const void *D,
             return fail(CSR_ERR_WORKSPACE, "csr_encode: workspace of %zu bytes (256-byte aligned) required, got %zu", need, workspace ? workspace_bytes : (size_t)0);
     }
     if (desc->res_norm2 && !aligned(desc->res_norm2, 4)) return fail(CSR_ERR_INVALID_ARG, "csr_encode: res_norm2 must be 4-byte aligned");
+    if (algo == kAlgoGramStep && !aligned(desc->gram, 16)) return fail(CSR_ERR_INVALID_ARG, "csr_encode: gram must be 16-byte aligned");
     a.X = X; a.D = D; a.idx = idx; a.coef = coef;
     a.res_norm2 = desc->res_norm2;
     a.workspace = workspace;
@@ -211,7 +222,8 @@ csr_status csr_encode(const csr_encode_desc *desc, const void *X, const void *D,
     const hipError_t e = algo == CSR_ENCODE_MFMA ? csr::launch_encode_mfma(a)
                          : algo == CSR_ENCODE_SPLIT ? csr::launch_encode_split(a)
                          : algo == CSR_ENCODE_RESIDENT ? csr::launch_encode_resident(a)
-                         : algo == CSR_ENCODE_GRAM ? csr::launch_encode_gram(a) : csr::launch_encode_valu(a);
+                         : algo == CSR_ENCODE_GRAM ? csr::launch_encode_gram(a)
+                         : algo == kAlgoGramStep ? csr::launch_encode_gramstep(a) : csr::launch_encode_valu(a);
     if (e != hipSuccess) return fail(CSR_ERR_DEVICE, "csr_encode: %s", hipGetErrorString(e));
     return CSR_OK;
 }
@@ -257,6 +269,25 @@ csr_status csr_reconstruct(const csr_reconstruct_desc *d, const void *D, const v
     a.stream = static_cast<hipStream_t>(hip_stream);
     const hipError_t e = csr::launch_reconstruct(a);
     if (e != hipSuccess) return fail(CSR_ERR_DEVICE, "csr_reconstruct: %s", hipGetErrorString(e));
+    return CSR_OK;
+}
+
+size_t csr_gram_bytes(int32_t n_dicts, int32_t N)
+{
+    if (n_dicts < 0 || N < 0) return (size_t)-1;
+    return (size_t)n_dicts * (size_t)N * (size_t)N * 2;
+}
+
+csr_status csr_gram_build(const void *D, int32_t n_dicts, int32_t N, int32_t d, void *gram, void *hip_stream)
+{
+    if (n_dicts < 0 || n_dicts > 65535) return fail(CSR_ERR_INVALID_ARG, "csr_gram_build: n_dicts=%d outside 0..65535", n_dicts);
+    if (!csr::gram_build_supported(N, d))
+        return fail(CSR_ERR_UNSUPPORTED, "csr_gram_build: needs rows of 64 or 128 elements and N a multiple of 32, at most 16384 (got d=%d N=%d)", d, N);
+    if (n_dicts == 0) return CSR_OK;
+    if (!D || !gram) return fail(CSR_ERR_INVALID_ARG, "csr_gram_build: NULL pointer");
+    if (!aligned(D, 16) || !aligned(gram, 16)) return fail(CSR_ERR_INVALID_ARG, "csr_gram_build: D and gram must be 16-byte aligned");
+    const hipError_t e = csr::launch_gram_build(D, n_dicts, N, d, gram, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail(CSR_ERR_DEVICE, "csr_gram_build: %s", hipGetErrorString(e));
     return CSR_OK;
 }
 

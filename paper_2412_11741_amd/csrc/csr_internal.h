@@ -29,6 +29,7 @@ struct EncodeArgs {
     bool f16;                        // X and D are fp16 (else fp32)
     bool coef16, idx16;
     float *res_norm2;                // optional [H][T][sn] output, or nullptr
+    const void *gram;                // optional Gram matrices [dict_count * sn][N][N] fp16 (csr_gram_build), or nullptr
     void *workspace;
     hipStream_t stream;
 };
@@ -54,6 +55,13 @@ hipError_t launch_encode_resident(const EncodeArgs &a);
 // fp16 encoder for dictionaries of at most 256 atoms: Gram-matrix update of the correlations.
 bool encode_gram_supported(const EncodeArgs &a);
 hipError_t launch_encode_gram(const EncodeArgs &a);
+
+// Gram update with the Gram matrices in device memory: a few vectors per dictionary of up to 16384 atoms.
+bool encode_gramstep_supported(const EncodeArgs &a);
+size_t encode_gramstep_workspace_bytes(const EncodeArgs &a);
+hipError_t launch_encode_gramstep(const EncodeArgs &a);
+bool gram_build_supported(int32_t N, int32_t d);
+hipError_t launch_gram_build(const void *D, int32_t n_dicts, int32_t N, int32_t d, void *G, hipStream_t stream);
 
 // ---- atom norms -----------------------------------------------------------------------------------------------------
 hipError_t launch_atom_norms2(const void *D, bool f16, int64_t n_atoms, int32_t d, float *out, hipStream_t stream);

@@ -1,0 +1,459 @@
+// Matching Pursuit encoder with the Gram-matrix residual update for FEW vectors per LARGE dictionary (gfx950): the
+// tokens generated in one decoding step, which Section "KV Decomposition and Sparse Storage" encodes like the
+// prompt's (Eq.2-4 of Section "Sparse representation", s iterations).
+//
+// With one vector per dictionary every iteration of Eq.2 is a matrix-vector product that reads the whole dictionary
+// (1 MB at N = 4096): s sweeps of every dictionary per generated token.  All correlations obey
+//     C_{g+1}[n] = (R_g - c_g d_i) . d_n = C_g[n] - c_g G[i][n],        G = D D^T,
+// so with G prepared once per dictionary (csr_gram_build: N x N fp16 in device memory, 32 MB at N = 4096) only the
+// first iteration sweeps the dictionary; each later one reads ONE row of G (2 N bytes) per vector.
+//
+//   launch 1, sweep_kernel, workgroup (dictionary, 256-atom slice): C_1[n] = x . d_n for the dictionary's vectors
+//       (exact fp16 products, fp32 sums) into scratch, and the slice's largest squared atom norm.
+//   launch 2, iterate_kernel, one workgroup per vector: the correlations live in registers (8 consecutive atoms per
+//       thread and round), the fp32 residual R in every wave.  Per iteration: block arg-max of |C|; the row of G and
+//       of D of that atom are requested at once; every atom whose |C| lies within 2 delta of the maximum is a
+//       candidate, and the candidates' R . d are evaluated in fp32 from the atoms themselves (largest wins, lowest
+//       atom on ties) - the recursion only SCREENS, as the fp16 sweeps of the other encoders do:
+//           |C_g[n] - R_g . d_n| <= delta_g,   delta_1 = gamma |x| dmax,
+//           delta_{g+1} = delta_g + |c_g| (dmax^2 (2^-12 + gamma) + 2^-25) + 2^-22 |x| dmax
+//       (gamma bounds the fp32 accumulation of a dot product of exact fp16 products; |G| <= dmax^2; 2^-25 covers
+//       fp16-subnormal entries of G).  More candidates than the list holds (a residual that is almost orthogonal to
+//       everything, a dictionary of equal atoms): all N atoms are evaluated.  Then Eq.4 on R with the unrounded
+//       coefficient, and the recursion on C.
+#include "csr_internal.h"
+
+namespace csr {
+namespace {
+
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+constexpr int kSweepThreads = 256;
+constexpr int kSliceAtoms = 256;        // atoms per sweep workgroup
+constexpr int kIterWaves = 8;
+constexpr int kIterThreads = 64 * kIterWaves;
+constexpr int kMaxRounds = 4;           // rounds of 8 atoms per thread: N <= 512 * 8 * 4
+constexpr int kMaxAtoms = kIterThreads * 8 * kMaxRounds;  // 16384
+constexpr int kMaxVectors = 16;         // per dictionary; more are the split encoder's shape
+constexpr int kCand = 256;              // candidate list; beyond it every atom is evaluated
+constexpr float kGammaAcc = 1.6e-5f;    // fp32 accumulation of a 128-term dot product of exact fp16 products
+
+__device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c)
+{
+    return __builtin_amdgcn_fdot2(*reinterpret_cast<const half2v *>(&a), *reinterpret_cast<const half2v *>(&b), c, false);
+}
+__device__ __forceinline__ float dot8(const uint4 &a, const uint4 &b)
+{
+    return dot2(a.w, b.w, dot2(a.z, b.z, dot2(a.y, b.y, dot2(a.x, b.x, 0.0f))));
+}
+__device__ __forceinline__ void unpack8(const uint4 &raw, float (&f)[8])
+{
+    const __half2 *h2 = reinterpret_cast<const __half2 *>(&raw);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float2 v = __half22float2(h2[j]);
+        f[2 * j] = v.x;
+        f[2 * j + 1] = v.y;
+    }
+}
+// sum over the LPR (8 or 16) consecutive lanes that hold one row
+template <int LPR> __device__ __forceinline__ float row_sum(float v)
+{
+#pragma unroll
+    for (int m = 1; m < LPR; m <<= 1) v += __shfl_xor(v, m, 64);
+    return v;
+}
+// (|c|, atom, c) candidates: larger |c| wins, the lower atom on equal |c|
+__device__ __forceinline__ void take_better(float &ba, int &bi, float &bc, float oa, int oi, float oc)
+{
+    if (oa > ba || (oa == ba && oi < bi)) { ba = oa; bi = oi; bc = oc; }
+}
+
+// where vector m (0 .. M-1) of dictionary dct lives: blocks that share a dictionary are numbered one after the other
+struct VecAt {
+    int64_t x_off;   // elements from X to the chunk
+    int64_t code;    // elements from idx / coef to its first pair
+    int64_t norm;    // elements from res_norm2
+};
+__device__ __forceinline__ VecAt locate(int dct, int64_t m, int64_t T, int sn, int s, int DC, int dict_count, int64_t x_stride_h,
+                                        int64_t x_stride_t, int64_t code_stride_h)
+{
+    const int dict = dct / sn, ch = dct - dict * sn;
+    const int64_t rep = m / T, tok = m - rep * T;
+    const int64_t h = rep * dict_count + dict;
+    VecAt v;
+    v.x_off = h * x_stride_h + tok * x_stride_t + (int64_t)ch * DC;
+    v.code = h * code_stride_h + (tok * sn + ch) * s;
+    v.norm = (h * T + tok) * sn + ch;
+    return v;
+}
+
+// ---- G = D D^T, fp16, row-major [dictionary][N][N] -------------------------------------------------------------------
+// v_mfma_f32_16x16x32_f16: lane (col = lane % 16, q = lane / 16) supplies dimensions 8 q .. 8 q + 7 of every
+// 32-dimension slice of row col of both operands and receives the products of rows 4 q .. 4 q + 3 of A with row col
+// of B.  A wave owns 16 rows i of G and walks the 16-atom tiles t of the columns.
+template <int DC>
+__global__ __launch_bounds__(256) void gram_build_kernel(const __half *__restrict__ Dict, __half *__restrict__ G, int32_t N)
+{
+    constexpr int kF = DC / 32;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = lane & 15, q = lane >> 4;
+    const int ntile = N >> 4;
+    const int rb = blockIdx.x * 4 + wave;
+    if (rb >= ntile) return;  // (wave-uniform; no barriers in this kernel)
+    const __half *Dh = Dict + (int64_t)blockIdx.y * N * DC;
+    __half *Gd = G + (int64_t)blockIdx.y * N * N;
+    auto atom_frag = [&](int n, int f) { return *reinterpret_cast<const half8 *>(Dh + (int64_t)n * DC + 32 * f + 8 * q); };
+    const int i = 16 * rb + col;
+    half8 bfr[kF];
+#pragma unroll
+    for (int f = 0; f < kF; ++f) bfr[f] = atom_frag(i, f);
+    for (int t = 0; t < ntile; ++t) {
+        floatx4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int f = 0; f < kF; ++f) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(atom_frag(16 * t + col, f), bfr[f], acc, 0, 0, 0);
+        // acc[e] = d_n . d_i for n = 16 t + 4 q + e
+        const __half2 p0 = __floats2half2_rn(acc[0], acc[1]), p1 = __floats2half2_rn(acc[2], acc[3]);
+        uint2 w;
+        w.x = *reinterpret_cast<const uint32_t *>(&p0);
+        w.y = *reinterpret_cast<const uint32_t *>(&p1);
+        *reinterpret_cast<uint2 *>(Gd + (int64_t)i * N + 16 * t + 4 * q) = w;
+    }
+}
+
+// ---- launch 1: C_1 and the atom norms ----------------------------------------------------------------------------------
+// LPR = DC / 8 lanes read one atom row (16 bytes each), 64 / LPR rows per wave and load.
+template <int DC>
+__global__ __launch_bounds__(kSweepThreads) void sweep_kernel(const __half *__restrict__ X, const __half *__restrict__ Dict,
+                                                              float *__restrict__ Cbuf, float *__restrict__ dmax2_part, int64_t T,
+                                                              int32_t M, int32_t N, int32_t s, int32_t sn, int64_t x_stride_h,
+                                                              int64_t x_stride_t, int32_t dict_count, int32_t nslices)
+{
+    constexpr int LPR = DC / 8, RPW = 64 / LPR;
+    __shared__ float red[kSweepThreads / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int piece = lane % LPR, rg = lane / LPR;
+    const int dct = blockIdx.x / nslices, sl = blockIdx.x - dct * nslices;
+    const __half *Dh = Dict + (int64_t)dct * N * DC;
+    float nmax = 0.0f;
+    for (int m0 = 0; m0 < M; m0 += 8) {
+        uint4 xp[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            xp[j] = make_uint4(0u, 0u, 0u, 0u);
+            if (m0 + j < M) {
+                const VecAt v = locate(dct, m0 + j, T, sn, s, DC, dict_count, x_stride_h, x_stride_t, 0);
+                xp[j] = *reinterpret_cast<const uint4 *>(X + v.x_off + 8 * piece);
+            }
+        }
+        for (int r0 = sl * kSliceAtoms + wave * RPW; r0 < (sl + 1) * kSliceAtoms; r0 += (kSweepThreads / 64) * RPW) {
+            const int r = r0 + rg;
+            const int rc = r < N ? r : N - 1;  // the last slice may be ragged: those lanes recompute the last atom
+            const uint4 dr = *reinterpret_cast<const uint4 *>(Dh + (int64_t)rc * DC + 8 * piece);
+            if (m0 == 0) nmax = fmaxf(nmax, row_sum<LPR>(dot8(dr, dr)));
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if (m0 + j < M) {  // (uniform)
+                    const float c = row_sum<LPR>(dot8(xp[j], dr));
+                    if (piece == 0 && r < N) Cbuf[((int64_t)dct * M + m0 + j) * N + r] = c;
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) nmax = fmaxf(nmax, __shfl_xor(nmax, m, 64));
+    if (lane == 0) red[wave] = nmax;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float v = red[0];
+        for (int w = 1; w < kSweepThreads / 64; ++w) v = fmaxf(v, red[w]);
+        dmax2_part[(int64_t)dct * nslices + sl] = v;
+    }
+}
+
+// ---- launch 2: the s iterations of one vector ------------------------------------------------------------------------------
+template <int DC, int NR>
+__global__ __launch_bounds__(kIterThreads) void iterate_kernel(const __half *__restrict__ X, const __half *__restrict__ Dict,
+                                                               const __half *__restrict__ G, const float *__restrict__ Cbuf,
+                                                               const float *__restrict__ dmax2_part, void *__restrict__ idx_out,
+                                                               void *__restrict__ coef_out, int64_t T, int32_t M, int32_t N, int32_t s,
+                                                               int32_t sn, int64_t x_stride_h, int64_t x_stride_t, int32_t dict_count,
+                                                               int64_t code_stride_h, int32_t nslices, int32_t idx16, int32_t coef16,
+                                                               float *__restrict__ res_norm2)
+{
+    constexpr int LPR = DC / 8, RPW = 64 / LPR;
+    __shared__ unsigned long long keys[2][kIterWaves];
+    __shared__ int cnt[2];
+    __shared__ int cand[2][kCand];
+    __shared__ float4 best[2][kIterWaves];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int piece = lane % LPR, rg = lane / LPR;
+    const int dct = blockIdx.x / M;
+    const int m = blockIdx.x - dct * M;
+    const VecAt at = locate(dct, m, T, sn, s, DC, dict_count, x_stride_h, x_stride_t, code_stride_h);
+    const __half *Dh = Dict + (int64_t)dct * N * DC;
+    const __half *Gd = G + (int64_t)dct * N * N;
+    const float *Cv = Cbuf + ((int64_t)dct * M + m) * N;
+
+    if (tid == 0) { cnt[0] = 0; cnt[1] = 0; }  // (ordered before the first use by the first barrier of the loop)
+
+    float dmax2 = 0.0f;
+    for (int sl = 0; sl < nslices; ++sl) dmax2 = fmaxf(dmax2, dmax2_part[(int64_t)dct * nslices + sl]);
+    const float dmax = sqrtf(dmax2);
+    const float g_eps = dmax2 * (2.44140625e-4f + kGammaAcc) + 2.98023224e-8f;  // |G16 - G| <= g_eps
+
+    // the residual: every group of LPR lanes holds all of it, 8 dimensions per lane, the same in all waves
+    float R[8];
+    {
+        const uint4 raw = *reinterpret_cast<const uint4 *>(X + at.x_off + 8 * piece);
+        unpack8(raw, R);
+    }
+    float r2 = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) r2 = fmaf(R[e], R[e], r2);
+    r2 = row_sum<LPR>(r2);
+    const float xnorm = sqrtf(r2);
+
+    // this thread's correlations: atoms 8 (tid + 512 j) + e
+    float C[NR][8];
+#pragma unroll
+    for (int j = 0; j < NR; ++j) {
+        const int n0 = 8 * (tid + kIterThreads * j);
+        float4 lo = make_float4(0.f, 0.f, 0.f, 0.f), hi = lo;
+        if (n0 < N) {  // (N is a multiple of 8)
+            lo = *reinterpret_cast<const float4 *>(Cv + n0);
+            hi = *reinterpret_cast<const float4 *>(Cv + n0 + 4);
+        }
+        C[j][0] = lo.x; C[j][1] = lo.y; C[j][2] = lo.z; C[j][3] = lo.w;
+        C[j][4] = hi.x; C[j][5] = hi.y; C[j][6] = hi.z; C[j][7] = hi.w;
+    }
+    float delta = kGammaAcc * xnorm * dmax;
+
+    for (int g = 0; g < s; ++g) {
+        const int p = g & 1;
+        // ---- screen: the largest |C| of the block, lowest atom on equal values ----------------------------------
+        unsigned long long key = 0ull;
+#pragma unroll
+        for (int j = 0; j < NR; ++j) {
+            const int n0 = 8 * (tid + kIterThreads * j);
+            if (n0 < N) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const unsigned long long k = ((unsigned long long)(__float_as_uint(C[j][e]) & 0x7fffffffu) << 32) |
+                                                 (unsigned long long)(0xffffffffu - (uint32_t)(n0 + e));
+                    key = k > key ? k : key;
+                }
+            }
+        }
+#pragma unroll
+        for (int mm = 32; mm >= 1; mm >>= 1) {
+            const uint32_t ohi = (uint32_t)__shfl_xor((int)(uint32_t)(key >> 32), mm, 64);
+            const uint32_t olo = (uint32_t)__shfl_xor((int)(uint32_t)key, mm, 64);
+            const unsigned long long o = ((unsigned long long)ohi << 32) | olo;
+            key = o > key ? o : key;
+        }
+        if (lane == 0) keys[p][wave] = key;
+        if (tid == 0) cnt[p ^ 1] = 0;  // the other list was last read before the previous iteration's last barrier
+        __syncthreads();
+        key = keys[p][0];
+#pragma unroll
+        for (int w = 1; w < kIterWaves; ++w) key = keys[p][w] > key ? keys[p][w] : key;
+        const int n1 = (int)(0xffffffffu - (uint32_t)key);  // an atom below N: every key carries one
+        const float A1 = __uint_as_float((uint32_t)(key >> 32));
+        const bool zero = !(r2 > 0.0f);
+
+        // requested now, used after the decision (which is n1 almost always)
+        uint4 gp[NR];
+#pragma unroll
+        for (int j = 0; j < NR; ++j) {
+            const int n0 = 8 * (tid + kIterThreads * j);
+            gp[j] = make_uint4(0u, 0u, 0u, 0u);
+            if (n0 < N) gp[j] = *reinterpret_cast<const uint4 *>(Gd + (int64_t)n1 * N + n0);
+        }
+        const uint4 d1p = *reinterpret_cast<const uint4 *>(Dh + (int64_t)n1 * DC + 8 * piece);
+
+        // ---- candidates: everything within 2 delta of the maximum -----------------------------------------------------
+        const float thr = A1 - 2.0f * delta;
+#pragma unroll
+        for (int j = 0; j < NR; ++j) {
+            const int n0 = 8 * (tid + kIterThreads * j);
+            if (n0 < N) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    if (!zero && n0 + e != n1 && fabsf(C[j][e]) >= thr) {
+                        const int slot = atomicAdd(&cnt[p], 1);
+                        if (slot < kCand) cand[p][slot] = n0 + e;
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        const int L = cnt[p];
+
+        // ---- exact R . d of the candidates, from the atoms themselves --------------------------------------------------
+        float ba = -1.0f, bc = 0.0f;
+        int bn = 0x7fffffff;
+        {
+            const bool all = L > kCand;
+            const int total = all ? N : L + 1;  // list entry 0 is n1
+            for (int base = 0; base < total; base += kIterWaves * RPW) {
+                const int ci = base + wave * RPW + rg;
+                const bool live = ci < total;
+                int n = n1;
+                if (live && all) n = ci;
+                if (live && !all && ci > 0) n = cand[p][ci - 1];
+                uint4 raw = d1p;
+                if (n != n1) raw = *reinterpret_cast<const uint4 *>(Dh + (int64_t)n * DC + 8 * piece);
+                float dn[8];
+                unpack8(raw, dn);
+                float c = 0.0f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) c = fmaf(R[e], dn[e], c);
+                c = row_sum<LPR>(c);
+                if (live) take_better(ba, bn, bc, fabsf(c), n, c);
+            }
+#pragma unroll
+            for (int mm = LPR; mm < 64; mm <<= 1) {
+                const float oa = __shfl_xor(ba, mm, 64), oc = __shfl_xor(bc, mm, 64);
+                const int on = __shfl_xor(bn, mm, 64);
+                take_better(ba, bn, bc, oa, on, oc);
+            }
+            if (lane == 0) best[p][wave] = make_float4(ba, __int_as_float(bn), bc, 0.0f);
+        }
+        __syncthreads();
+        {
+            const float4 b0 = best[p][0];
+            ba = b0.x; bn = __float_as_int(b0.y); bc = b0.z;
+#pragma unroll
+            for (int w = 1; w < kIterWaves; ++w) {
+                const float4 b = best[p][w];
+                take_better(ba, bn, bc, b.x, __float_as_int(b.y), b.z);
+            }
+        }
+        int best_n = bn;
+        float best_c = bc;
+        if (bn == 0x7fffffff) { best_n = n1; best_c = __uint_as_float(0x7fc00000u); }  // nothing compares: NaN in, NaN out
+        if (zero) { best_n = 0; best_c = 0.0f; }
+
+        // ---- Eq.4 on the residual (unrounded c), the recursion on the correlations -----------------------------------
+        {
+            uint4 raw = d1p;
+            if (best_n != n1) raw = *reinterpret_cast<const uint4 *>(Dh + (int64_t)best_n * DC + 8 * piece);  // (uniform)
+            float dn[8];
+            unpack8(raw, dn);
+            float r2n = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                R[e] = fmaf(-best_c, dn[e], R[e]);
+                r2n = fmaf(R[e], R[e], r2n);
+            }
+            r2 = row_sum<LPR>(r2n);
+        }
+#pragma unroll
+        for (int j = 0; j < NR; ++j) {
+            const int n0 = 8 * (tid + kIterThreads * j);
+            if (n0 < N) {
+                uint4 raw = gp[j];
+                if (best_n != n1) raw = *reinterpret_cast<const uint4 *>(Gd + (int64_t)best_n * N + n0);  // (uniform)
+                float gv[8];
+                unpack8(raw, gv);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) C[j][e] = fmaf(-best_c, gv[e], C[j][e]);
+            }
+        }
+        delta += fabsf(best_c) * g_eps + 2.4e-7f * xnorm * dmax;
+
+        if (tid == 0) {
+            const int64_t o = at.code + g;
+            if (idx16) reinterpret_cast<uint16_t *>(idx_out)[o] = (uint16_t)best_n;
+            else reinterpret_cast<int32_t *>(idx_out)[o] = best_n;
+            if (coef16) reinterpret_cast<__half *>(coef_out)[o] = __float2half_rn(best_c);
+            else reinterpret_cast<float *>(coef_out)[o] = best_c;
+        }
+    }
+    if (res_norm2 && tid == 0) res_norm2[at.norm] = r2;
+}
+
+struct StepPlan {
+    int64_t M;        // vectors per dictionary
+    int64_t dicts;    // dictionaries (chunk dictionaries counted)
+    int nslices;
+    size_t c_bytes, total;
+};
+
+StepPlan plan_step(const EncodeArgs &a)
+{
+    StepPlan p{};
+    p.M = (int64_t)(a.H / a.dict_count) * a.T;
+    p.dicts = (int64_t)a.dict_count * a.sn;
+    p.nslices = (a.N + kSliceAtoms - 1) / kSliceAtoms;
+    p.c_bytes = ((size_t)p.dicts * p.M * a.N * sizeof(float) + 255) & ~size_t(255);
+    p.total = p.c_bytes + (((size_t)p.dicts * p.nslices * sizeof(float) + 255) & ~size_t(255));
+    return p;
+}
+
+template <int DC, int NR>
+void launch_iterate(const EncodeArgs &a, const StepPlan &p, const float *Cbuf, const float *dpart)
+{
+    hipLaunchKernelGGL((iterate_kernel<DC, NR>), dim3((unsigned)(p.dicts * p.M)), dim3(kIterThreads), 0, a.stream,
+                       (const __half *)a.X, (const __half *)a.D, (const __half *)a.gram, Cbuf, dpart, a.idx, a.coef, a.T, (int32_t)p.M,
+                       a.N, a.s, a.sn, a.x_stride_h, a.x_stride_t, a.dict_count, a.code_stride_h, p.nslices, (int32_t)a.idx16,
+                       (int32_t)a.coef16, a.res_norm2);
+}
+
+template <int DC>
+hipError_t launch_step_t(const EncodeArgs &a)
+{
+    const StepPlan p = plan_step(a);
+    char *ws = static_cast<char *>(a.workspace);
+    float *Cbuf = reinterpret_cast<float *>(ws);
+    float *dpart = reinterpret_cast<float *>(ws + p.c_bytes);
+    hipLaunchKernelGGL(sweep_kernel<DC>, dim3((unsigned)(p.dicts * p.nslices)), dim3(kSweepThreads), 0, a.stream, (const __half *)a.X,
+                       (const __half *)a.D, Cbuf, dpart, a.T, (int32_t)p.M, a.N, a.s, a.sn, a.x_stride_h, a.x_stride_t, a.dict_count,
+                       p.nslices);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int rounds = (a.N + kIterThreads * 8 - 1) / (kIterThreads * 8);
+    if (rounds <= 1) launch_iterate<DC, 1>(a, p, Cbuf, dpart);
+    else if (rounds == 2) launch_iterate<DC, 2>(a, p, Cbuf, dpart);
+    else launch_iterate<DC, 4>(a, p, Cbuf, dpart);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool encode_gramstep_supported(const EncodeArgs &a)
+{
+    if (!(a.f16 && (a.d == 128 || a.d == 64) && a.N >= 32 && a.N % 32 == 0 && a.N <= kMaxAtoms)) return false;
+    if (a.dict_count < 1 || a.H % a.dict_count != 0) return false;
+    const int64_t M = (int64_t)(a.H / a.dict_count) * a.T;
+    const int64_t dicts = (int64_t)a.dict_count * a.sn;
+    const int64_t nslices = (a.N + kSliceAtoms - 1) / kSliceAtoms;
+    return M <= kMaxVectors && dicts * nslices <= 0x7fffffffLL && dicts * M <= 0x7fffffffLL;
+}
+
+size_t encode_gramstep_workspace_bytes(const EncodeArgs &a) { return plan_step(a).total; }
+
+hipError_t launch_encode_gramstep(const EncodeArgs &a)
+{
+    return a.d == 64 ? launch_step_t<64>(a) : launch_step_t<128>(a);
+}
+
+bool gram_build_supported(int32_t N, int32_t d) { return (d == 128 || d == 64) && N >= 32 && N % 32 == 0 && N <= kMaxAtoms; }
+
+hipError_t launch_gram_build(const void *D, int32_t n_dicts, int32_t N, int32_t d, void *G, hipStream_t stream)
+{
+    const dim3 grid((unsigned)((N / 16 + 3) / 4), (unsigned)n_dicts);
+    if (d == 64)
+        hipLaunchKernelGGL(gram_build_kernel<64>, grid, dim3(256), 0, stream, (const __half *)D, (__half *)G, N);
+    else
+        hipLaunchKernelGGL(gram_build_kernel<128>, grid, dim3(256), 0, stream, (const __half *)D, (__half *)G, N);
+    return hipGetLastError();
+}
+
+}  // namespace csr
