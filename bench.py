@@ -274,29 +274,44 @@ def decode_step(csr, synth, w, dev, steps):
     lens = torch.full((B,), T, dtype=torch.int32, device=dev)
     row = lambda t: t[:, T - 1:T]
     ews = csr.csr_encode_workspace_bytes(csr.encode_desc(XKV, DKV, s, torch.float16, torch.int16, code_stride_h=T * s))
-    wsE = torch.empty(max(ews, 256), dtype=torch.uint8, device=dev)
+    wsE = torch.empty(max(ews, 2 * B * Hkv * N * 4 + (1 << 20), 256), dtype=torch.uint8, device=dev)   # either encoder's
     v = lambda t: t.view(B, Hkv, T, s)
     wsD = torch.empty(max(csr.csr_decode_workspace_bytes(csr.decode_desc(q, DK, v(iK), v(cK), v(iV))), 256),
                       dtype=torch.uint8, device=dev)
 
+    # G = D D^T per dictionary, prepared once like the dictionaries themselves (not part of a step): with it the
+    # append sweeps every dictionary once instead of s times
+    GKV = csr.csr_gram_build(DKV)
+    GK, GV = GKV[:Hkv], GKV[Hkv:]
+    use_gram = [True]
+
     def append():
+        gk = dict(gram=GKV) if use_gram[0] else {}
         if B == 1:
-            csr.csr_encode(XKV, DKV, s, idx=row(icache), coef=row(ccache), workspace=wsE)
+            csr.csr_encode(XKV, DKV, s, idx=row(icache), coef=row(ccache), workspace=wsE, **gk)
         else:
-            csr.csr_encode(XK, DK, s, idx=row(iK), coef=row(cK), workspace=wsE)
-            csr.csr_encode(XV, DV, s, idx=row(iV), coef=row(cV), workspace=wsE)
+            csr.csr_encode(XK, DK, s, idx=row(iK), coef=row(cK), workspace=wsE, **(dict(gram=GK) if use_gram[0] else {}))
+            csr.csr_encode(XV, DV, s, idx=row(iV), coef=row(cV), workspace=wsE, **(dict(gram=GV) if use_gram[0] else {}))
 
     def attend():
         csr.csr_decode_attn(q, DK, v(iK), v(cK), DV, v(iV), v(cV), seq_lens=lens, out=out, workspace=wsD)
 
-    for _ in range(2):
-        append(); attend()
-    torch.cuda.synchronize()
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
-    for i in range(steps):
-        ev[i][0].record(); append(); ev[i][1].record(); attend(); ev[i][2].record()
-    torch.cuda.synchronize()
-    a_ms, d_ms = (sum(e[j].elapsed_time(e[j + 1]) for e in ev) / steps for j in range(2))
+    def timed():
+        for _ in range(2):
+            append(); attend()
+        torch.cuda.synchronize()
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+        for i in range(steps):
+            ev[i][0].record(); append(); ev[i][1].record(); attend(); ev[i][2].record()
+        torch.cuda.synchronize()
+        return [sum(e[j].elapsed_time(e[j + 1]) for e in ev) / steps for j in range(2)]
+
+    use_gram[0] = False
+    split_ms, _ = timed()
+    split_row = (row(icache).clone(), row(ccache).clone())
+    use_gram[0] = True
+    a_ms, d_ms = timed()
+    same_codes = bool(torch.equal(row(icache), split_row[0]))
     # the same step recorded once in a HIP graph and replayed: the launches lose their gaps
     graph = torch.cuda.CUDAGraph()
     side = torch.cuda.Stream()
@@ -313,13 +328,24 @@ def decode_step(csr, synth, w, dev, steps):
         a_.record(); graph.replay(); b_.record()
     torch.cuda.synchronize()
     g_ms = sum(a_.elapsed_time(b_) for a_, b_ in gev) / steps
-    sweep_bytes = 2 * Hkv * N * d * 2 * s     # every iteration reads every dictionary once
-    return {"append_vectors": 2 * B * Hkv, "append_ms": round(a_ms, 4), "attend_ms_warm": round(d_ms, 5),
+    dict_bytes = 2 * Hkv * N * d * 2
+    sweep_bytes = dict_bytes * s              # without G every iteration reads every dictionary once
+    nvec = 2 * B * Hkv
+    gram_bytes = dict_bytes + nvec * ((s - 1) * 2 * N + 2 * 4 * N)   # one sweep, a row of G per later iteration, C_1 out and in
+    return {"append_vectors": nvec, "append_ms": round(a_ms, 4), "attend_ms_warm": round(d_ms, 5),
             "step_ms": round(a_ms + d_ms, 4), "step_ms_graph": round(g_ms, 4),
             "tokens_per_s": round(B / (min(g_ms, a_ms + d_ms) * 1e-3), 1),
-            "roofline_append": {"kernel": "csr_encode (split), s + 1 launches per call", "bound": "hbm",
-                                "achieved": round(sweep_bytes / (a_ms * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
-                                "unit": "GB/s", "frac": round(sweep_bytes / (a_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 5),
+            "append_ms_without_gram": round(split_ms, 4), "same_atoms_as_without_gram": same_codes,
+            "gram_matrices_mb": round(GKV.numel() * 2 / 1e6, 1),
+            "roofline_append": {"kernel": "csr_encode with the dictionaries' Gram matrices (sweep + iterate, 2 launches)",
+                                "bound": "hbm", "achieved": round(gram_bytes / (a_ms * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
+                                "unit": "GB/s", "frac": round(gram_bytes / (a_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 5),
+                                "bytes_per_step": gram_bytes,
+                                "note": "one sweep of every dictionary, then s - 1 rows of G per vector: the iterations "
+                                        "are a chain of dependent loads, one workgroup per vector"},
+            "roofline_append_without_gram": {"kernel": "csr_encode (split), s + 1 launches per call", "bound": "hbm",
+                                "achieved": round(sweep_bytes / (split_ms * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
+                                "unit": "GB/s", "frac": round(sweep_bytes / (split_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 5),
                                 "bytes_per_step": sweep_bytes,
                                 "note": "s sweeps over all dictionaries; re-reads may be served by the Infinity Cache"}}
 

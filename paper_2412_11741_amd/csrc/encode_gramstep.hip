@@ -58,17 +58,43 @@ __device__ __forceinline__ void unpack8(const uint4 &raw, float (&f)[8])
         f[2 * j + 1] = v.y;
     }
 }
-// sum over the LPR (8 or 16) consecutive lanes that hold one row
+template <int CTRL> __device__ __forceinline__ float dpp_add(float v)
+{
+    return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+// sum over the LPR (8 or 16) consecutive lanes that hold one row; every one of them gets it
 template <int LPR> __device__ __forceinline__ float row_sum(float v)
 {
-#pragma unroll
-    for (int m = 1; m < LPR; m <<= 1) v += __shfl_xor(v, m, 64);
+    v = dpp_add<0xB1>(v);   // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E>(v);   // quad_perm [2,3,0,1]
+    v = dpp_add<0x141>(v);  // row_half_mirror: lane i of every 8 with lane 7 - i
+    if (LPR == 16) v = dpp_add<0x140>(v);  // row_mirror: lane i of every 16 with lane 15 - i
     return v;
 }
 // (|c|, atom, c) candidates: larger |c| wins, the lower atom on equal |c|
 __device__ __forceinline__ void take_better(float &ba, int &bi, float &bc, float oa, int oi, float oc)
 {
     if (oa > ba || (oa == ba && oi < bi)) { ba = oa; bi = oi; bc = oc; }
+}
+
+// (a1 >= a2 >= 0), the two largest of a set, merged with those of the lane that the DPP pattern names (a disjoint set;
+// rows outside ROWS keep their own): the two largest of the union
+template <int CTRL, int ROWS> __device__ __forceinline__ void top2_dpp(float &a1, float &a2)
+{
+    const float o1 = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(a1), CTRL, ROWS, 0xf, false));
+    const float o2 = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(a2), CTRL, ROWS, 0xf, false));
+    a2 = fmaxf(fmaxf(a2, o2), fminf(a1, o1));
+    a1 = fmaxf(a1, o1);
+}
+// R . d in fp32 for the row whose 8-dimension piece this lane holds (R the same piece); all LPR lanes get the sum
+template <int LPR> __device__ __forceinline__ float exact_dot(const float (&R)[8], const uint4 &raw)
+{
+    float dn[8];
+    unpack8(raw, dn);
+    float c = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) c = fmaf(R[e], dn[e], c);
+    return row_sum<LPR>(c);
 }
 
 // where vector m (0 .. M-1) of dictionary dct lives: blocks that share a dictionary are numbered one after the other
@@ -184,10 +210,10 @@ __global__ __launch_bounds__(kIterThreads) void iterate_kernel(const __half *__r
                                                                float *__restrict__ res_norm2)
 {
     constexpr int LPR = DC / 8, RPW = 64 / LPR;
-    __shared__ unsigned long long keys[2][kIterWaves];
-    __shared__ int cnt[2];
-    __shared__ int cand[2][kCand];
-    __shared__ float4 best[2][kIterWaves];
+    __shared__ float4 keys[2][kIterWaves];  // (by iteration parity: a wave may run one barrier ahead)
+    __shared__ int cnt;
+    __shared__ int cand[kCand];
+    __shared__ float4 best[kIterWaves];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -199,8 +225,6 @@ __global__ __launch_bounds__(kIterThreads) void iterate_kernel(const __half *__r
     const __half *Dh = Dict + (int64_t)dct * N * DC;
     const __half *Gd = G + (int64_t)dct * N * N;
     const float *Cv = Cbuf + ((int64_t)dct * M + m) * N;
-
-    if (tid == 0) { cnt[0] = 0; cnt[1] = 0; }  // (ordered before the first use by the first barrier of the loop)
 
     float dmax2 = 0.0f;
     for (int sl = 0; sl < nslices; ++sl) dmax2 = fmaxf(dmax2, dmax2_part[(int64_t)dct * nslices + sl]);
@@ -236,35 +260,49 @@ __global__ __launch_bounds__(kIterThreads) void iterate_kernel(const __half *__r
 
     for (int g = 0; g < s; ++g) {
         const int p = g & 1;
-        // ---- screen: the largest |C| of the block, lowest atom on equal values ----------------------------------
-        unsigned long long key = 0ull;
+        // ---- screen: the two largest |C| of the block and the atom of the largest --------------------------------------
+        // (which of several EQUAL largest values is named does not matter: a tie sends the iteration down the
+        // candidate path, where the atoms themselves decide)
+        float a1 = 0.0f, a2 = 0.0f;
+        int na = 8 * tid < N ? 8 * tid : 0;
 #pragma unroll
         for (int j = 0; j < NR; ++j) {
             const int n0 = 8 * (tid + kIterThreads * j);
             if (n0 < N) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    const unsigned long long k = ((unsigned long long)(__float_as_uint(C[j][e]) & 0x7fffffffu) << 32) |
-                                                 (unsigned long long)(0xffffffffu - (uint32_t)(n0 + e));
-                    key = k > key ? k : key;
+                    const float v = fabsf(C[j][e]);
+                    a2 = fmaxf(a2, fminf(a1, v));
+                    na = v > a1 ? n0 + e : na;
+                    a1 = fmaxf(a1, v);
                 }
             }
         }
-#pragma unroll
-        for (int mm = 32; mm >= 1; mm >>= 1) {
-            const uint32_t ohi = (uint32_t)__shfl_xor((int)(uint32_t)(key >> 32), mm, 64);
-            const uint32_t olo = (uint32_t)__shfl_xor((int)(uint32_t)key, mm, 64);
-            const unsigned long long o = ((unsigned long long)ohi << 32) | olo;
-            key = o > key ? o : key;
+        float w1 = a1, w2 = a2;
+        top2_dpp<0xB1, 0xF>(w1, w2);   // quad_perm [1,0,3,2]
+        top2_dpp<0x4E, 0xF>(w1, w2);   // quad_perm [2,3,0,1]
+        top2_dpp<0x141, 0xF>(w1, w2);  // row_half_mirror
+        top2_dpp<0x140, 0xF>(w1, w2);  // row_mirror: every lane has its row's two largest
+        top2_dpp<0x142, 0xA>(w1, w2);  // row_bcast15: rows 1 and 3 take in the row before them
+        top2_dpp<0x143, 0xC>(w1, w2);  // row_bcast31: row 3 takes in rows 0 and 1; lane 63 has the wave's
+        w1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w1), 63));
+        w2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w2), 63));
+        {
+            const unsigned long long holders = __ballot(a1 == w1);
+            const int src = holders ? __ffsll((long long)holders) - 1 : 0;
+            const int nw = __builtin_amdgcn_readlane(na, src);
+            if (lane == 0) keys[p][wave] = make_float4(w1, w2, __int_as_float(nw), 0.0f);
         }
-        if (lane == 0) keys[p][wave] = key;
-        if (tid == 0) cnt[p ^ 1] = 0;  // the other list was last read before the previous iteration's last barrier
-        __syncthreads();
-        key = keys[p][0];
+        __syncthreads();  // the only barrier of an iteration whose maximum stands clear of the rest
+        float A1 = 0.0f, A2 = 0.0f;
+        int n1 = 0;
 #pragma unroll
-        for (int w = 1; w < kIterWaves; ++w) key = keys[p][w] > key ? keys[p][w] : key;
-        const int n1 = (int)(0xffffffffu - (uint32_t)key);  // an atom below N: every key carries one
-        const float A1 = __uint_as_float((uint32_t)(key >> 32));
+        for (int w = 0; w < kIterWaves; ++w) {
+            const float4 k = keys[p][w];
+            A2 = fmaxf(A2, fmaxf(fminf(A1, k.x), k.y));
+            n1 = k.x > A1 ? __float_as_int(k.z) : n1;
+            A1 = fmaxf(A1, k.x);
+        }
         const bool zero = !(r2 > 0.0f);
 
         // requested now, used after the decision (which is n1 almost always)
@@ -277,28 +315,34 @@ __global__ __launch_bounds__(kIterThreads) void iterate_kernel(const __half *__r
         }
         const uint4 d1p = *reinterpret_cast<const uint4 *>(Dh + (int64_t)n1 * DC + 8 * piece);
 
-        // ---- candidates: everything within 2 delta of the maximum -----------------------------------------------------
         const float thr = A1 - 2.0f * delta;
+        int best_n = n1;
+        float best_c;
+        if (zero || !(A2 >= thr)) {
+            // ---- no other atom within 2 delta: every wave computes the coefficient itself ----------------------------------
+            best_c = exact_dot<LPR>(R, d1p);
+        } else {
+            // ---- candidates: everything within 2 delta of the maximum -------------------------------------------------
+            if (tid == 0) cnt = 0;
+            __syncthreads();
 #pragma unroll
-        for (int j = 0; j < NR; ++j) {
-            const int n0 = 8 * (tid + kIterThreads * j);
-            if (n0 < N) {
+            for (int j = 0; j < NR; ++j) {
+                const int n0 = 8 * (tid + kIterThreads * j);
+                if (n0 < N) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    if (!zero && n0 + e != n1 && fabsf(C[j][e]) >= thr) {
-                        const int slot = atomicAdd(&cnt[p], 1);
-                        if (slot < kCand) cand[p][slot] = n0 + e;
+                    for (int e = 0; e < 8; ++e) {
+                        if (n0 + e != n1 && fabsf(C[j][e]) >= thr) {
+                            const int slot = atomicAdd(&cnt, 1);
+                            if (slot < kCand) cand[slot] = n0 + e;
+                        }
                     }
                 }
             }
-        }
-        __syncthreads();
-        const int L = cnt[p];
-
-        // ---- exact R . d of the candidates, from the atoms themselves --------------------------------------------------
-        float ba = -1.0f, bc = 0.0f;
-        int bn = 0x7fffffff;
-        {
+            __syncthreads();
+            const int L = cnt;
+            // exact R . d of the candidates, from the atoms themselves
+            float ba = -1.0f, bc = 0.0f;
+            int bn = 0x7fffffff;
             const bool all = L > kCand;
             const int total = all ? N : L + 1;  // list entry 0 is n1
             for (int base = 0; base < total; base += kIterWaves * RPW) {
@@ -306,15 +350,10 @@ __global__ __launch_bounds__(kIterThreads) void iterate_kernel(const __half *__r
                 const bool live = ci < total;
                 int n = n1;
                 if (live && all) n = ci;
-                if (live && !all && ci > 0) n = cand[p][ci - 1];
+                if (live && !all && ci > 0) n = cand[ci - 1];
                 uint4 raw = d1p;
                 if (n != n1) raw = *reinterpret_cast<const uint4 *>(Dh + (int64_t)n * DC + 8 * piece);
-                float dn[8];
-                unpack8(raw, dn);
-                float c = 0.0f;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) c = fmaf(R[e], dn[e], c);
-                c = row_sum<LPR>(c);
+                const float c = exact_dot<LPR>(R, raw);
                 if (live) take_better(ba, bn, bc, fabsf(c), n, c);
             }
 #pragma unroll
@@ -323,21 +362,19 @@ __global__ __launch_bounds__(kIterThreads) void iterate_kernel(const __half *__r
                 const int on = __shfl_xor(bn, mm, 64);
                 take_better(ba, bn, bc, oa, on, oc);
             }
-            if (lane == 0) best[p][wave] = make_float4(ba, __int_as_float(bn), bc, 0.0f);
-        }
-        __syncthreads();
-        {
-            const float4 b0 = best[p][0];
+            if (lane == 0) best[wave] = make_float4(ba, __int_as_float(bn), bc, 0.0f);
+            __syncthreads();
+            const float4 b0 = best[0];
             ba = b0.x; bn = __float_as_int(b0.y); bc = b0.z;
 #pragma unroll
             for (int w = 1; w < kIterWaves; ++w) {
-                const float4 b = best[p][w];
+                const float4 b = best[w];
                 take_better(ba, bn, bc, b.x, __float_as_int(b.y), b.z);
             }
+            best_n = bn;
+            best_c = bc;
+            if (bn == 0x7fffffff) { best_n = n1; best_c = __uint_as_float(0x7fc00000u); }  // nothing compares: NaN in, NaN out
         }
-        int best_n = bn;
-        float best_c = bc;
-        if (bn == 0x7fffffff) { best_n = n1; best_c = __uint_as_float(0x7fc00000u); }  // nothing compares: NaN in, NaN out
         if (zero) { best_n = 0; best_c = 0.0f; }
 
         // ---- Eq.4 on the residual (unrounded c), the recursion on the correlations -----------------------------------
