@@ -153,9 +153,29 @@ int main(void)
     if (memcmp(hIdx, hIdx2, sizeof hIdx) != 0) { printf("the Gram encoder picked other atoms\n"); return 11; }
     e.algo = CSR_ENCODE_AUTO;
 
+    /* and so is the one that takes the dictionaries' Gram matrices from device memory (T vectors per dictionary) */
+    {
+        void *dG = NULL, *dWs2 = NULL;
+        size_t gbytes = csr_gram_bytes(H, N);
+        CHECK_HIP(hipMalloc(&dG, gbytes));
+        CHECK_CSR(csr_gram_build(dD, H, N, D, dG, NULL));
+        e.gram = dG;
+        size_t need2 = csr_encode_workspace_bytes(&e);
+        if (need2 == (size_t)-1 || need2 == 0) { printf("bad descriptor with gram: %s\n", csr_last_error()); return 12; }
+        CHECK_HIP(hipMalloc(&dWs2, need2));
+        CHECK_HIP(hipMemset(dIdx, 0xff, sizeof hIdx));
+        CHECK_CSR(csr_encode(&e, dX, dD, dIdx, dCoef, dWs2, need2, NULL));
+        CHECK_HIP(hipDeviceSynchronize());
+        CHECK_HIP(hipMemcpy(hIdx2, dIdx, sizeof hIdx2, hipMemcpyDeviceToHost));
+        if (memcmp(hIdx, hIdx2, sizeof hIdx) != 0) { printf("the Gram-step encoder picked other atoms\n"); return 13; }
+        e.gram = NULL;
+        CHECK_HIP(hipFree(dG));
+        CHECK_HIP(hipFree(dWs2));
+    }
+
     /* an invalid request comes back as a status with a message, not as a crash */
     e.s = 0;
     if (csr_encode(&e, dX, dD, dIdx, dCoef, dWs, need, NULL) != CSR_ERR_INVALID_ARG || csr_last_error()[0] == 0) return 8;
-    printf("c abi smoke ok: encode (two kernels), reconstruct, decode (plain and rotary keys; rel err %.2e)\n", sqrt(err / ref));
+    printf("c abi smoke ok: encode (three kernels), reconstruct, decode (plain and rotary keys; rel err %.2e)\n", sqrt(err / ref));
     return 0;
 }
