@@ -59,5 +59,7 @@ def test_the_json_line_carries_the_contracts_fields():
     for leg in ("roofline_decode", "chunked_step", "paper_sized_step", "decode_step", "reconstruct", "rope_decode"):
         assert leg in out, leg
     assert out["paper_sized_step"]["atoms"] == 256 and out["paper_sized_step"]["rope_base"] == 10000.0
+    step = out["decode_step"]   # appended with the Gram matrices, and without them: the same atoms, faster
+    assert step["same_atoms_as_without_gram"] and 0 < step["append_ms"] < step["append_ms_without_gram"]
     for r_ in out["rope_decode"]:
         assert r_["bound"] == "alu" and r_["peak"] == 157.3 and abs(r_["frac"] - r_["achieved"] / r_["peak"]) < 1e-4
