@@ -12,7 +12,8 @@ from tests import parity
 pytestmark = pytest.mark.gpu
 
 ALGOS = {"valu": csr.CSR_ENCODE_VALU, "mfma": csr.CSR_ENCODE_MFMA, "split": csr.CSR_ENCODE_SPLIT,
-         "resident": csr.CSR_ENCODE_RESIDENT, "gram": csr.CSR_ENCODE_GRAM}
+         "resident": csr.CSR_ENCODE_RESIDENT, "gram": csr.CSR_ENCODE_GRAM,
+         "gram step": csr.CSR_ENCODE_GRAM}   # with the Gram matrices prepared in device memory
 
 
 def _draw(seed):
@@ -36,6 +37,8 @@ def _supported(c, algo):
         return c["N"] * c["dc"] * 2 <= 128 * 1024
     if algo == "gram":
         return c["N"] <= 256
+    if algo == "gram step":
+        return M <= 16
     return True
 
 
@@ -57,7 +60,8 @@ def test_encoders_on_random_shapes(seed):
         ci = torch.full(shape, -1, dtype=torch.int16, device="cuda")
         cc = torch.full(shape, 9.0, dtype=torch.float16, device="cuda")
         rn = torch.empty((H, T, sn) if sn > 1 else (H, T), dtype=torch.float32, device="cuda")
-        csr.csr_encode(Xg, Dg, s, algo=algo, idx=ci[:, c["pad"]:], coef=cc[:, c["pad"]:], res_norm2=rn)
+        extra = dict(gram=csr.csr_gram_build(Dg)) if name == "gram step" else {}
+        csr.csr_encode(Xg, Dg, s, algo=algo, idx=ci[:, c["pad"]:], coef=cc[:, c["pad"]:], res_norm2=rn, **extra)
         torch.cuda.synchronize()
         assert (ci[:, :c["pad"]] == -1).all() and (cc[:, :c["pad"]] == 9.0).all(), name
         idx = ci[:, c["pad"]:].cpu().numpy().reshape(H, T, sn, s)
