@@ -52,7 +52,8 @@ typedef enum { CSR_F32 = 0, CSR_F16 = 1 } csr_dtype; /* vectors, dictionaries, c
 typedef enum { CSR_I32 = 0, CSR_I16 = 1 } csr_itype; /* atom indices; I16 is unsigned        */
 
 /* Which encoder kernel runs.  AUTO picks SPLIT when a dictionary serves few vectors (the tokens of one
- * decoding step), RESIDENT when the dictionary fits the LDS, MFMA when the shape allows it, else VALU. */
+ * decoding step; GRAM instead when the descriptor brings the dictionaries' Gram matrices and there are at
+ * most 16), RESIDENT when the dictionary fits the LDS, MFMA when the shape allows it, else VALU. */
 typedef enum {
     CSR_ENCODE_AUTO = 0,
     CSR_ENCODE_VALU = 1, /* fp32 vector-ALU correlation, any supported shape               */
@@ -63,10 +64,13 @@ typedef enum {
     CSR_ENCODE_RESIDENT = 4, /* small dictionaries (N * d/s_n * 2 bytes <= 128 KB, e.g. the 256 - 512 atoms per
                             head of the paper's experiments): the dictionary stays in LDS, exact
                             fp32-accumulated correlations on the matrix cores; same input types     */
-    CSR_ENCODE_GRAM = 5  /* at most 256 atoms: the correlations of all atoms are updated with the Gram matrix
-                            of the dictionary (kept in LDS, in fp16: atom norms must stay below 250) instead of
-                            being recomputed; same input types.  Never picked by AUTO: on this chip it is
-                            slower than RESIDENT                                                         */
+    CSR_ENCODE_GRAM = 5  /* the correlations of all atoms are updated with the Gram matrix of the dictionary
+                            (in fp16: atom norms must stay below 250) instead of being recomputed; same input
+                            types.  Without csr_encode_desc.gram: at most 256 atoms, the matrix is built into LDS
+                            by every workgroup; never picked by AUTO (on this chip it is slower than RESIDENT).
+                            With csr_encode_desc.gram (csr_gram_build): up to 16384 atoms and at most 16 vectors
+                            per dictionary, the decoding-step shape; AUTO picks it whenever gram is given and
+                            the shape fits                                                               */
 } csr_encode_algo;
 
 /*
