@@ -104,6 +104,51 @@ def test_encode_kernel_choice_follows_the_vectors_per_dictionary_and_the_diction
     assert size(T=1000, N=1024, d=64) == 0 and size(T=1000, N=1056, d=64) > 0  # 64-dimensional atoms: twice as many fit
 
 
+def test_gram_matrices_in_the_descriptor_select_the_decoding_step_gram_encoder():
+    lib = csr.lib()
+    G = 0x2000
+    size = lambda **kw: lib.csr_encode_workspace_bytes(ctypes.byref(_enc(**kw)))
+    bad = ctypes.c_size_t(-1).value
+    big = dict(N=4096)
+    # scratch: C_1 (N floats per vector) and the slices' norm records; by default whenever gram is given and fits
+    want = 2 * 1 * 4096 * 4 + 256
+    assert size(T=1, gram=G, **big) == size(T=1, gram=G, algo=B.CSR_ENCODE_GRAM, **big) == want
+    assert size(T=16, gram=G, **big) == 2 * 16 * 4096 * 4 + 256
+    assert size(T=1, gram=G, **big) != size(T=1, **big)                       # (the split encoder's is another)
+    # more than 16 vectors per dictionary: refused when asked for, otherwise the encoder the shape would get anyway
+    assert size(T=17, gram=G, algo=B.CSR_ENCODE_GRAM, **big) == bad and "at most 16 vectors" in csr.last_error()
+    assert size(T=17, gram=G, **big) == size(T=17, **big)
+    assert size(H=8, T=4, dict_count=2, gram=G, **big) == 2 * 16 * 4096 * 4 + 256
+    assert size(H=8, T=5, dict_count=2, gram=G, algo=B.CSR_ENCODE_GRAM, **big) == bad
+    # other explicit kernels ignore the matrices; without them GRAM is the LDS form with its 256 atoms
+    assert size(T=1, gram=G, algo=B.CSR_ENCODE_SPLIT, **big) == size(T=1, algo=B.CSR_ENCODE_SPLIT, **big)
+    assert size(T=1, algo=B.CSR_ENCODE_GRAM, **big) == bad
+    assert size(T=1, N=16384, gram=G) > 0 and size(T=1, N=16416, gram=G, algo=B.CSR_ENCODE_GRAM) == bad
+    assert size(T=1, gram=G, x_dtype=B.CSR_F32, dict_dtype=B.CSR_F32, algo=B.CSR_ENCODE_GRAM) == bad
+    assert size(T=1, d=256, s_n=2, gram=G, **big) == 2 * 2 * 4096 * 4 + 256   # a Gram matrix per chunk dictionary
+    # the matrices' pointer is checked like the others
+    ok = ctypes.c_void_p(0x1000)
+    d = _enc(T=1, gram=0x2004, **big)
+    ws = ctypes.c_void_p(0x4000)
+    assert lib.csr_encode(ctypes.byref(d), ok, ok, ok, ok, ws, 1 << 20, None) == B.CSR_ERR_INVALID_ARG
+    assert "gram" in csr.last_error()
+    assert lib.csr_encode(ctypes.byref(_enc(T=1, gram=G, **big)), ok, ok, ok, ok, None, 0, None) == B.CSR_ERR_WORKSPACE
+
+
+def test_gram_build_arguments():
+    lib = csr.lib()
+    assert lib.csr_gram_bytes(64, 4096) == 64 * 4096 * 4096 * 2 and lib.csr_gram_bytes(0, 4096) == 0
+    assert lib.csr_gram_bytes(-1, 4096) == ctypes.c_size_t(-1).value
+    p = ctypes.c_void_p(0x1000)
+    assert lib.csr_gram_build(p, 2, 100, 128, p, None) == B.CSR_ERR_UNSUPPORTED      # N a multiple of 32
+    assert lib.csr_gram_build(p, 2, 256, 32, p, None) == B.CSR_ERR_UNSUPPORTED       # rows of 64 or 128 elements
+    assert lib.csr_gram_build(p, 2, 16416, 128, p, None) == B.CSR_ERR_UNSUPPORTED
+    assert lib.csr_gram_build(p, 70000, 256, 128, p, None) == B.CSR_ERR_INVALID_ARG
+    assert lib.csr_gram_build(None, 2, 256, 128, p, None) == B.CSR_ERR_INVALID_ARG
+    assert lib.csr_gram_build(p, 2, 256, 128, ctypes.c_void_p(0x1008), None) == B.CSR_ERR_INVALID_ARG
+    assert lib.csr_gram_build(None, 0, 256, 128, None, None) == B.CSR_OK
+
+
 def test_encode_null_and_misaligned_pointers_and_noop_sizes():
     lib = csr.lib()
     d = _enc()
