@@ -341,9 +341,10 @@ def test_chunked_values_full_layer_all_heads():
     _check(out, ref, TOL_F16_OUT, "llama7b layer, values in two chunks, all heads")
 
 
-@pytest.mark.parametrize("rope_base", [0.0, 10000.0])
-def test_a_decoding_step_can_be_captured_in_a_graph_and_replayed(rope_base):
-    # (rope_base set: the keys count as coded before the rotary embedding and the other streaming kernel runs)
+@pytest.mark.parametrize("rope_base,gram", [(0.0, False), (10000.0, False), (0.0, True)])
+def test_a_decoding_step_can_be_captured_in_a_graph_and_replayed(rope_base, gram):
+    # (rope_base set: the keys count as coded before the rotary embedding and the other streaming kernel runs;
+    # gram: the append takes the dictionaries' Gram matrices - its two launches instead of the split encoder's)
     # append (split encoder: s + 1 launches per call) + attention (4 launches) recorded once, replayed on new data;
     # every replay must equal the eager result of the same inputs bit for bit (nothing allocates, nothing is cleared
     # by a memset node, every kernel argument is fixed at capture time)
@@ -360,14 +361,16 @@ def test_a_decoding_step_can_be_captured_in_a_graph_and_replayed(rope_base):
     lens = torch.full((B,), pos + 1, dtype=torch.int32, device="cuda")
     iK, cK, iV, cV = mk_cache()
     edesc = csr.encode_desc(xk, DK, s, torch.float16, torch.int16, code_stride_h=T_max * s)
-    wsE = torch.empty(max(csr.csr_encode_workspace_bytes(edesc), 256), dtype=torch.uint8, device="cuda")
+    wsE = torch.empty(max(csr.csr_encode_workspace_bytes(edesc), 1 << 20), dtype=torch.uint8, device="cuda")
+    gk = dict(gram=csr.csr_gram_build(DK)) if gram else {}
+    gv = dict(gram=csr.csr_gram_build(DV)) if gram else {}
     v4 = lambda t: t.view(B, Hkv, T_max, s)
     wsD = torch.empty(max(csr.csr_decode_workspace_bytes(csr.decode_desc(q, DK, v4(iK), v4(cK), v4(iV), rope_base=rope_base)), 256),
                       dtype=torch.uint8, device="cuda")
 
     def step():
-        csr.csr_encode(xk, DK, s, idx=iK[:, pos:pos + 1], coef=cK[:, pos:pos + 1], workspace=wsE)
-        csr.csr_encode(xv, DV, s, idx=iV[:, pos:pos + 1], coef=cV[:, pos:pos + 1], workspace=wsE)
+        csr.csr_encode(xk, DK, s, idx=iK[:, pos:pos + 1], coef=cK[:, pos:pos + 1], workspace=wsE, **gk)
+        csr.csr_encode(xv, DV, s, idx=iV[:, pos:pos + 1], coef=cV[:, pos:pos + 1], workspace=wsE, **gv)
         csr.csr_decode_attn(q, DK, v4(iK), v4(cK), DV, v4(iV), v4(cV), seq_lens=lens, out=out, workspace=wsD,
                             rope_base=rope_base, rope_pos0=7 if rope_base else 0)
 
