@@ -53,7 +53,7 @@ typedef enum { CSR_I32 = 0, CSR_I16 = 1 } csr_itype; /* atom indices; I16 is uns
 
 /* Which encoder kernel runs.  AUTO picks SPLIT when a dictionary serves few vectors (the tokens of one
  * decoding step; GRAM instead when the descriptor brings the dictionaries' Gram matrices and there are at
- * most 16), RESIDENT when the dictionary fits the LDS, MFMA when the shape allows it, else VALU. */
+ * most 128), RESIDENT when the dictionary fits the LDS, MFMA when the shape allows it, else VALU. */
 typedef enum {
     CSR_ENCODE_AUTO = 0,
     CSR_ENCODE_VALU = 1, /* fp32 vector-ALU correlation, any supported shape               */
@@ -68,7 +68,7 @@ typedef enum {
                             (in fp16: atom norms must stay below 250) instead of being recomputed; same input
                             types.  Without csr_encode_desc.gram: at most 256 atoms, the matrix is built into LDS
                             by every workgroup; never picked by AUTO (on this chip it is slower than RESIDENT).
-                            With csr_encode_desc.gram (csr_gram_build): up to 16384 atoms and at most 16 vectors
+                            With csr_encode_desc.gram (csr_gram_build): up to 16384 atoms and at most 128 vectors
                             per dictionary, the decoding-step shape; AUTO picks it whenever gram is given and
                             the shape fits                                                               */
 } csr_encode_algo;
@@ -112,7 +112,7 @@ typedef struct {
                            vector's term of the dictionary-training loss of Section "NeuralDict"       */
     const void *gram;   /* optional device pointer, or NULL: the Gram matrices of D as csr_gram_build writes them
                            ([dict_count][N][N] fp16; chunked [dict_count][s_n][N][N]).  With them, CSR_ENCODE_GRAM -
-                           and CSR_ENCODE_AUTO - encode up to 16 vectors per dictionary (the tokens of one decoding
+                           and CSR_ENCODE_AUTO - encode up to 128 vectors per dictionary (the tokens of one decoding
                            step) with ONE sweep of each dictionary instead of s: later iterations read one row of
                            the Gram matrix per vector.  fp16 inputs, chunks of 64 or 128, N a multiple of 32, at
                            most 16384.  Results are those of the other encoders (the Gram recursion screens, the

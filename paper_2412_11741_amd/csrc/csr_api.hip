@@ -95,7 +95,7 @@ csr_status check_encode_desc(const csr_encode_desc *d, csr::EncodeArgs *args, in
     const bool step_ok = d->gram != nullptr && csr::encode_gramstep_supported(a);
     if (d->algo == CSR_ENCODE_GRAM && d->gram && !step_ok)
         return fail(CSR_ERR_UNSUPPORTED, "csr_encode: the Gram encoder with prepared Gram matrices needs fp16 inputs, chunks of 64 or 128 "
-                    "dimensions, N a multiple of 32, at most 16384, and at most 16 vectors per dictionary (got d/s_n=%d N=%d %s, %lld "
+                    "dimensions, N a multiple of 32, at most 16384, and at most 128 vectors per dictionary (got d/s_n=%d N=%d %s, %lld "
                     "vectors per dictionary)", dc, d->N, a.f16 ? "f16" : "f32", (long long)(a.dict_count ? (int64_t)(a.H / a.dict_count) * a.T : 0));
     if (d->algo == CSR_ENCODE_GRAM && !d->gram && !csr::encode_gram_supported(a))
         return fail(CSR_ERR_UNSUPPORTED, "csr_encode: the Gram encoder needs fp16 inputs, chunks of 64 or 128 dimensions and N a multiple "

@@ -9,7 +9,8 @@
 // first iteration sweeps the dictionary; each later one reads ONE row of G (2 N bytes) per vector.
 //
 //   launch 1, sweep_kernel, workgroup (dictionary, 256-atom slice): C_1[n] = x . d_n for the dictionary's vectors
-//       (exact fp16 products, fp32 sums) into scratch, and the slice's largest squared atom norm.
+//       (exact fp16 products, fp32 sums) into scratch, and the slice's largest squared atom norm.  Up to 8 vectors
+//       per dictionary on the vector ALU (the launch is bound by reading the dictionaries), more on the matrix cores.
 //   launch 2, iterate_kernel, one workgroup per vector: the correlations live in registers (8 consecutive atoms per
 //       thread and round), the fp32 residual R in every wave.  Per iteration: block arg-max of |C|; the row of G and
 //       of D of that atom are requested at once; every atom whose |C| lies within 2 delta of the maximum is a
@@ -29,6 +30,7 @@ namespace {
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kSweepThreads = 256;
 constexpr int kSliceAtoms = 256;        // atoms per sweep workgroup
@@ -36,7 +38,10 @@ constexpr int kIterWaves = 8;
 constexpr int kIterThreads = 64 * kIterWaves;
 constexpr int kMaxRounds = 4;           // rounds of 8 atoms per thread: N <= 512 * 8 * 4
 constexpr int kMaxAtoms = kIterThreads * 8 * kMaxRounds;  // 16384
-constexpr int kMaxVectors = 16;         // per dictionary; more are the split encoder's shape
+constexpr int kMaxVectors = 128;        // per dictionary: a decoding step of up to 128 sequences
+constexpr int kValuSweepVectors = 8;    // up to here the sweep is a matrix-vector product on the vector ALU
+constexpr int kSweepTiles = 2;          // 32-atom tiles per wave of the matrix-core sweep (4 waves: 256 atoms)
+static_assert(kSliceAtoms == (kSweepThreads / 64) * 32 * kSweepTiles, "a sweep workgroup covers one slice");
 constexpr int kCand = 256;              // candidate list; beyond it every atom is evaluated
 constexpr float kGammaAcc = 1.6e-5f;    // fp32 accumulation of a 128-term dot product of exact fp16 products
 
@@ -190,6 +195,80 @@ __global__ __launch_bounds__(kSweepThreads) void sweep_kernel(const __half *__re
     }
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1) nmax = fmaxf(nmax, __shfl_xor(nmax, m, 64));
+    if (lane == 0) red[wave] = nmax;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float v = red[0];
+        for (int w = 1; w < kSweepThreads / 64; ++w) v = fmaxf(v, red[w]);
+        dmax2_part[(int64_t)dct * nslices + sl] = v;
+    }
+}
+
+// The same launch for more than a handful of vectors per dictionary, on the matrix cores: v_mfma_f32_32x32x16_f16 with
+// 32 vectors as the rows of A and 32 atoms as the columns of B.  Lane (col = lane % 32, hf = lane / 32) supplies
+// dimensions 16 j + 8 hf .. + 7 of step j for vector col (A) and atom col (B) - 16 contiguous bytes of a row per step -
+// and receives, in accumulator 4 r4 + e, the product of vector 8 r4 + 4 hf + e with atom col.  A wave keeps the rows
+// of its kSweepTiles tiles in registers and walks the vectors 32 at a time.
+template <int DC>
+__global__ __launch_bounds__(kSweepThreads) void sweep_mfma_kernel(const __half *__restrict__ X, const __half *__restrict__ Dict,
+                                                                   float *__restrict__ Cbuf, float *__restrict__ dmax2_part, int64_t T,
+                                                                   int32_t M, int32_t N, int32_t s, int32_t sn, int64_t x_stride_h,
+                                                                   int64_t x_stride_t, int32_t dict_count, int32_t nslices)
+{
+    constexpr int NF = DC / 16;  // matrix-core steps per product
+    __shared__ float red[kSweepThreads / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = lane & 31, hf = lane >> 5;
+    const int dct = blockIdx.x / nslices, sl = blockIdx.x - dct * nslices;
+    const __half *Dh = Dict + (int64_t)dct * N * DC;
+    const int n_first = sl * kSliceAtoms + wave * 32 * kSweepTiles;
+    float nmax = 0.0f;
+    half8 bfrag[kSweepTiles][NF];
+#pragma unroll
+    for (int t = 0; t < kSweepTiles; ++t) {
+        const int n = n_first + 32 * t + col;
+        const int nc = n < N ? n : N - 1;  // the last slice may be ragged: those lanes hold the last atom again
+        float nn = 0.0f;
+#pragma unroll
+        for (int j = 0; j < NF; ++j) {
+            const uint4 raw = *reinterpret_cast<const uint4 *>(Dh + (int64_t)nc * DC + 16 * j + 8 * hf);
+            bfrag[t][j] = *reinterpret_cast<const half8 *>(&raw);
+            nn += dot8(raw, raw);
+        }
+        nn += __shfl_xor(nn, 32, 64);  // the other half of the atom's dimensions
+        nmax = fmaxf(nmax, nn);
+    }
+    for (int v0 = 0; v0 < M; v0 += 32) {
+        const int m = v0 + col;
+        half8 afrag[NF];
+        {
+            const VecAt at = locate(dct, m < M ? m : M - 1, T, sn, s, DC, dict_count, x_stride_h, x_stride_t, 0);
+#pragma unroll
+            for (int j = 0; j < NF; ++j) {
+                uint4 raw = make_uint4(0u, 0u, 0u, 0u);
+                if (m < M) raw = *reinterpret_cast<const uint4 *>(X + at.x_off + 16 * j + 8 * hf);
+                afrag[j] = *reinterpret_cast<const half8 *>(&raw);
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < kSweepTiles; ++t) {
+            floatx16 acc;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+#pragma unroll
+            for (int j = 0; j < NF; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(afrag[j], bfrag[t][j], acc, 0, 0, 0);
+            const int n = n_first + 32 * t + col;
+            if (n < N) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int mv = v0 + 8 * (r >> 2) + 4 * hf + (r & 3);
+                    if (mv < M) Cbuf[((int64_t)dct * M + mv) * N + n] = acc[r];
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int mm = 32; mm >= 1; mm >>= 1) nmax = fmaxf(nmax, __shfl_xor(nmax, mm, 64));
     if (lane == 0) red[wave] = nmax;
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -450,9 +529,14 @@ hipError_t launch_step_t(const EncodeArgs &a)
     char *ws = static_cast<char *>(a.workspace);
     float *Cbuf = reinterpret_cast<float *>(ws);
     float *dpart = reinterpret_cast<float *>(ws + p.c_bytes);
-    hipLaunchKernelGGL(sweep_kernel<DC>, dim3((unsigned)(p.dicts * p.nslices)), dim3(kSweepThreads), 0, a.stream, (const __half *)a.X,
-                       (const __half *)a.D, Cbuf, dpart, a.T, (int32_t)p.M, a.N, a.s, a.sn, a.x_stride_h, a.x_stride_t, a.dict_count,
-                       p.nslices);
+    if (p.M <= kValuSweepVectors)
+        hipLaunchKernelGGL(sweep_kernel<DC>, dim3((unsigned)(p.dicts * p.nslices)), dim3(kSweepThreads), 0, a.stream, (const __half *)a.X,
+                           (const __half *)a.D, Cbuf, dpart, a.T, (int32_t)p.M, a.N, a.s, a.sn, a.x_stride_h, a.x_stride_t, a.dict_count,
+                           p.nslices);
+    else
+        hipLaunchKernelGGL(sweep_mfma_kernel<DC>, dim3((unsigned)(p.dicts * p.nslices)), dim3(kSweepThreads), 0, a.stream,
+                           (const __half *)a.X, (const __half *)a.D, Cbuf, dpart, a.T, (int32_t)p.M, a.N, a.s, a.sn, a.x_stride_h,
+                           a.x_stride_t, a.dict_count, p.nslices);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int rounds = (a.N + kIterThreads * 8 - 1) / (kIterThreads * 8);

@@ -115,11 +115,11 @@ def test_gram_matrices_in_the_descriptor_select_the_decoding_step_gram_encoder()
     assert size(T=1, gram=G, **big) == size(T=1, gram=G, algo=B.CSR_ENCODE_GRAM, **big) == want
     assert size(T=16, gram=G, **big) == 2 * 16 * 4096 * 4 + 256
     assert size(T=1, gram=G, **big) != size(T=1, **big)                       # (the split encoder's is another)
-    # more than 16 vectors per dictionary: refused when asked for, otherwise the encoder the shape would get anyway
-    assert size(T=17, gram=G, algo=B.CSR_ENCODE_GRAM, **big) == bad and "at most 16 vectors" in csr.last_error()
-    assert size(T=17, gram=G, **big) == size(T=17, **big)
+    # more than 128 vectors per dictionary: refused when asked for, otherwise the encoder the shape would get anyway
+    assert size(T=129, gram=G, algo=B.CSR_ENCODE_GRAM, **big) == bad and "at most 128 vectors" in csr.last_error()
+    assert size(T=129, gram=G, **big) == size(T=129, **big)
     assert size(H=8, T=4, dict_count=2, gram=G, **big) == 2 * 16 * 4096 * 4 + 256
-    assert size(H=8, T=5, dict_count=2, gram=G, algo=B.CSR_ENCODE_GRAM, **big) == bad
+    assert size(H=8, T=33, dict_count=2, gram=G, algo=B.CSR_ENCODE_GRAM, **big) == bad
     # other explicit kernels ignore the matrices; without them GRAM is the LDS form with its 256 atoms
     assert size(T=1, gram=G, algo=B.CSR_ENCODE_SPLIT, **big) == size(T=1, algo=B.CSR_ENCODE_SPLIT, **big)
     assert size(T=1, algo=B.CSR_ENCODE_GRAM, **big) == bad

@@ -32,6 +32,9 @@ def test_gram_build_matches_numpy(dicts, N, d):
     (2, 3, 16384, 64, 1, 6, 2),      # the largest dictionary, 64-dimensional vectors
     (3, 5, 96, 128, 1, 4, 3),        # fewer atoms than one sweep slice
     (2, 1, 4128, 128, 1, 8, 2),      # a ragged last slice, a partly filled second round
+    (64, 1, 4096, 128, 1, 8, 2),     # a decoding step of 32 sequences: the sweep runs on the matrix cores
+    (6, 42, 1056, 128, 2, 4, 2),     # 126 vectors per dictionary, three blocks sharing each, two chunks of 64
+    (5, 25, 2080, 64, 1, 5, 1),      # 125 vectors of 64 dimensions on one dictionary, ragged vector and atom tiles
 ])
 def test_gram_step_encoder_parity(H, T, N, d, sn, s, dicts):
     dc = d // sn
@@ -114,9 +117,9 @@ def test_gram_step_is_the_default_with_gram_matrices_appends_in_place_and_agrees
 
 def test_gram_step_limits():
     D = torch.from_numpy(synth.dictionary(84, "dict_k", 1, 512, 128, "f16")).cuda()
-    X = torch.from_numpy(synth.vectors(84, "keys", 1, 17, 128, "f16")).cuda()
+    X = torch.from_numpy(synth.vectors(84, "keys", 1, 129, 128, "f16")).cuda()
     G = csr.csr_gram_build(D)
-    with pytest.raises(csr.CsrError, match="at most 16 vectors"):
+    with pytest.raises(csr.CsrError, match="at most 128 vectors"):
         csr.csr_encode(X, D, 4, algo=csr.CSR_ENCODE_GRAM, gram=G)
     # by default more vectors than that simply take the encoder they would take without G
     a = csr.csr_encode(X, D, 4, gram=G)

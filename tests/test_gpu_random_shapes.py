@@ -38,7 +38,7 @@ def _supported(c, algo):
     if algo == "gram":
         return c["N"] <= 256
     if algo == "gram step":
-        return M <= 16
+        return M <= 128
     return True
 
 
