@@ -34,10 +34,12 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kSweepThreads = 256;
 constexpr int kSliceAtoms = 256;        // atoms per sweep workgroup
-constexpr int kIterWaves = 8;
-constexpr int kIterThreads = 64 * kIterWaves;
+constexpr int kIterThreadsMax = 512;     // threads of an iterate workgroup: 512 when few vectors wait (the chain of an
+                                        // iteration is shortest), 128 or 256 from kThroughputVectors per dictionary on
+                                        // (what every wave repeats - merge, coefficient, residual - is done by fewer)
+constexpr int kThroughputVectors = 12;
 constexpr int kMaxRounds = 4;           // rounds of 8 atoms per thread: N <= 512 * 8 * 4
-constexpr int kMaxAtoms = kIterThreads * 8 * kMaxRounds;  // 16384
+constexpr int kMaxAtoms = kIterThreadsMax * 8 * kMaxRounds;  // 16384
 constexpr int kMaxVectors = 128;        // per dictionary: a decoding step of up to 128 sequences
 constexpr int kValuSweepVectors = 8;    // up to here the sweep is a matrix-vector product on the vector ALU
 constexpr int kSweepTiles = 2;          // 32-atom tiles per wave of the matrix-core sweep (4 waves: 256 atoms)
@@ -279,8 +281,8 @@ __global__ __launch_bounds__(kSweepThreads) void sweep_mfma_kernel(const __half 
 }
 
 // ---- launch 2: the s iterations of one vector ------------------------------------------------------------------------------
-template <int DC, int NR>
-__global__ __launch_bounds__(kIterThreads) void iterate_kernel(const __half *__restrict__ X, const __half *__restrict__ Dict,
+template <int DC, int NR, int THREADS>
+__global__ __launch_bounds__(THREADS) void iterate_kernel(const __half *__restrict__ X, const __half *__restrict__ Dict,
                                                                const __half *__restrict__ G, const float *__restrict__ Cbuf,
                                                                const float *__restrict__ dmax2_part, void *__restrict__ idx_out,
                                                                void *__restrict__ coef_out, int64_t T, int32_t M, int32_t N, int32_t s,
@@ -289,6 +291,7 @@ __global__ __launch_bounds__(kIterThreads) void iterate_kernel(const __half *__r
                                                                float *__restrict__ res_norm2)
 {
     constexpr int LPR = DC / 8, RPW = 64 / LPR;
+    constexpr int kIterThreads = THREADS, kIterWaves = THREADS / 64;
     __shared__ float4 keys[2][kIterWaves];  // (by iteration parity: a wave may run one barrier ahead)
     __shared__ int cnt;
     __shared__ int cand[kCand];
@@ -513,10 +516,10 @@ StepPlan plan_step(const EncodeArgs &a)
     return p;
 }
 
-template <int DC, int NR>
+template <int DC, int NR, int THREADS>
 void launch_iterate(const EncodeArgs &a, const StepPlan &p, const float *Cbuf, const float *dpart)
 {
-    hipLaunchKernelGGL((iterate_kernel<DC, NR>), dim3((unsigned)(p.dicts * p.M)), dim3(kIterThreads), 0, a.stream,
+    hipLaunchKernelGGL((iterate_kernel<DC, NR, THREADS>), dim3((unsigned)(p.dicts * p.M)), dim3(THREADS), 0, a.stream,
                        (const __half *)a.X, (const __half *)a.D, (const __half *)a.gram, Cbuf, dpart, a.idx, a.coef, a.T, (int32_t)p.M,
                        a.N, a.s, a.sn, a.x_stride_h, a.x_stride_t, a.dict_count, a.code_stride_h, p.nslices, (int32_t)a.idx16,
                        (int32_t)a.coef16, a.res_norm2);
@@ -539,10 +542,11 @@ hipError_t launch_step_t(const EncodeArgs &a)
                            a.x_stride_t, a.dict_count, p.nslices);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int rounds = (a.N + kIterThreads * 8 - 1) / (kIterThreads * 8);
-    if (rounds <= 1) launch_iterate<DC, 1>(a, p, Cbuf, dpart);
-    else if (rounds == 2) launch_iterate<DC, 2>(a, p, Cbuf, dpart);
-    else launch_iterate<DC, 4>(a, p, Cbuf, dpart);
+    if (p.M >= kThroughputVectors && a.N <= 128 * 8 * kMaxRounds) launch_iterate<DC, 4, 128>(a, p, Cbuf, dpart);
+    else if (p.M >= kThroughputVectors && a.N <= 256 * 8 * kMaxRounds) launch_iterate<DC, 4, 256>(a, p, Cbuf, dpart);
+    else if (a.N <= 512 * 8) launch_iterate<DC, 1, 512>(a, p, Cbuf, dpart);
+    else if (a.N <= 512 * 8 * 2) launch_iterate<DC, 2, 512>(a, p, Cbuf, dpart);
+    else launch_iterate<DC, 4, 512>(a, p, Cbuf, dpart);
     return hipGetLastError();
 }
 
