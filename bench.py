@@ -11,7 +11,8 @@ call alone at the long-context and GQA shapes (random codes drawn on the GPU, ca
 the code streams rather than the dictionaries dominate the traffic.  `chunked_step` is the same step in the
 storage layout of the paper's experiments ("CSR-8": keys whole with s = 8, values in s_n = 2 chunks of 64
 dimensions with s = 4 each), which runs the 64-dimensional variants of the encoder and the chunk-aware decode.
-`decode_step` is one decoding step: the new token's codes appended in place, then attention over the cache.
+`decode_step` is one decoding step: the new token's codes appended in place, then attention over the cache
+(`decode_step_gqa`: the same at the grouped-query shape, 8 sequences on shared dictionaries).
 `rope_decode` is csr_decode_attn on keys coded before the rotary embedding (rope_base set), at the dictionary sizes
 of the paper's own experiments (256 atoms per KV head), where the key dictionary stays in LDS; `paper_sized_step` is
 the chunked step with those dictionaries and that decode.
@@ -335,6 +336,7 @@ def decode_step(csr, synth, w, dev, steps):
     return {"append_vectors": nvec, "append_ms": round(a_ms, 4), "attend_ms_warm": round(d_ms, 5),
             "step_ms": round(a_ms + d_ms, 4), "step_ms_graph": round(g_ms, 4),
             "tokens_per_s": round(B / (min(g_ms, a_ms + d_ms) * 1e-3), 1),
+            "workload": w.name, "decode_batch": B,
             "append_ms_without_gram": round(split_ms, 4), "same_atoms_as_without_gram": same_codes,
             "gram_matrices_mb": round(GKV.numel() * 2 / 1e6, 1),
             "roofline_append": {"kernel": "csr_encode with the dictionaries' Gram matrices (sweep + iterate, 2 launches)",
@@ -420,6 +422,8 @@ def main():
         w = synth.WORKLOADS[args.workload]
         leg = chunked_step if args.only_chunked else decode_step
         res = {"chunked_step" if args.only_chunked else "decode_step": leg(csr, synth, w, torch.device("cuda:0"), args.steps)}
+        if args.only_decode_step:
+            res["decode_step_gqa"] = decode_step(csr, synth, synth.WORKLOADS["gqa_llama3_8b"], torch.device("cuda:0"), args.steps)
         if args.only_chunked and not args.no_rope:
             res["paper_sized_step"] = chunked_step(csr, synth, w, torch.device("cuda:0"), args.steps, n_atoms=256,
                                                    rope_base=10000.0)
@@ -576,6 +580,9 @@ def main():
     # ---- one decoding step: append the new token's codes in place, attend over the grown cache ------------
     if not args.no_decode_step and w.dtype == "f16":
         result["decode_step"] = decode_step(csr, synth, w, dev, args.steps)
+        if not args.no_extra_decode:
+            # a batch of sequences on shared dictionaries: 8 new keys and 8 new values per dictionary and step
+            result["decode_step_gqa"] = decode_step(csr, synth, synth.WORKLOADS["gqa_llama3_8b"], dev, args.steps)
 
     # ---- decode attention on keys coded before the rotary embedding, paper-sized dictionaries -------------
     if not args.no_rope:
