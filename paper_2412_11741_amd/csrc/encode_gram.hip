@@ -6,8 +6,9 @@
 // of another sweep over the dictionary.  A workgroup builds the Gram matrix of its dictionary once with the matrix
 // cores and keeps it in LDS in fp16 (N x N x 2 bytes <= 128 KB).  The rounding of G makes the recursion a SCREEN,
 // exactly like the fp16 sweeps of the other encoders: |C_g[n] - R_g . d_n| <= delta_g with
-//     delta_1 = gamma |x| dmax,    delta_{g+1} = delta_g + |c_g| dmax^2 (2^-12 + gamma) + 2^-22 |x| dmax
-// (gamma bounds the fp32 accumulation of a dot product of exact fp16 products; |G| <= dmax^2).  The decision is
+//     delta_1 = gamma |x| dmax,    delta_{g+1} = delta_g + |c_g| dmax^2 (2^-12 + gamma) + 2^-22 rmax dmax
+// (gamma bounds the fp32 accumulation of a dot product of exact fp16 products; |G| <= dmax^2; rmax is the largest
+// residual norm so far).  The decision is
 // taken exactly: every vector keeps its residual R in fp32 registers, gathers the rows of the screen's best AND
 // second-best atom, and computes both R . d in fp32 - the coefficient of Eq.3 needs the winner's anyway.  When the
 // second is within 2 delta of the first, the exact values decide (lowest index on ties); when even the third is,
@@ -173,6 +174,7 @@ __global__ __launch_bounds__(kThreads) void encode_gram_kernel(
             for (int e = 0; e < 4; ++e) C[t][e] = acc[e];
         }
         float delta = kGammaAcc * xnorm * dmax;
+        float rmax = xnorm;  // largest residual norm so far
 
         for (int g = 0; g < s; ++g) {
             // ---- screen: the three largest |C| of the vector, atom number in the low 8 bits -------------
@@ -288,7 +290,8 @@ __global__ __launch_bounds__(kThreads) void encode_gram_kernel(
                     }
                 }
             }
-            delta += fabsf(best_c) * g_eps + 2.4e-7f * xnorm * dmax;
+            rmax = fmaxf(rmax, sqrtf(r2));  // (atoms longer than sqrt 2 can make a residual grow)
+            delta += fabsf(best_c) * g_eps + 2.4e-7f * rmax * dmax;
 
             if (valid && q == 0) {
                 const int64_t o = (int64_t)h * code_stride_h + (tok * sn + ch) * s + g;

@@ -17,9 +17,10 @@
 //       candidate, and the candidates' R . d are evaluated in fp32 from the atoms themselves (largest wins, lowest
 //       atom on ties) - the recursion only SCREENS, as the fp16 sweeps of the other encoders do:
 //           |C_g[n] - R_g . d_n| <= delta_g,   delta_1 = gamma |x| dmax,
-//           delta_{g+1} = delta_g + |c_g| (dmax^2 (2^-12 + gamma) + 2^-25) + 2^-22 |x| dmax
+//           delta_{g+1} = delta_g + |c_g| (dmax^2 (2^-12 + gamma) + 2^-25) + 2^-22 rmax dmax
 //       (gamma bounds the fp32 accumulation of a dot product of exact fp16 products; |G| <= dmax^2; 2^-25 covers
-//       fp16-subnormal entries of G).  More candidates than the list holds (a residual that is almost orthogonal to
+//       fp16-subnormal entries of G; rmax is the largest residual norm so far: the last term is the rounding of the
+//       fp32 residual and of the recursion itself).  More candidates than the list holds (a residual that is almost orthogonal to
 //       everything, a dictionary of equal atoms): all N atoms are evaluated.  Then Eq.4 on R with the unrounded
 //       coefficient, and the recursion on C.
 #include "csr_internal.h"
@@ -339,6 +340,7 @@ __global__ __launch_bounds__(THREADS) void iterate_kernel(const __half *__restri
         C[j][4] = hi.x; C[j][5] = hi.y; C[j][6] = hi.z; C[j][7] = hi.w;
     }
     float delta = kGammaAcc * xnorm * dmax;
+    float rmax = xnorm;  // largest residual norm so far
 
     for (int g = 0; g < s; ++g) {
         const int p = g & 1;
@@ -485,7 +487,8 @@ __global__ __launch_bounds__(THREADS) void iterate_kernel(const __half *__restri
                 for (int e = 0; e < 8; ++e) C[j][e] = fmaf(-best_c, gv[e], C[j][e]);
             }
         }
-        delta += fabsf(best_c) * g_eps + 2.4e-7f * xnorm * dmax;
+        rmax = fmaxf(rmax, sqrtf(r2));  // (atoms longer than sqrt 2 can make a residual grow)
+        delta += fabsf(best_c) * g_eps + 2.4e-7f * rmax * dmax;
 
         if (tid == 0) {
             const int64_t o = at.code + g;

@@ -115,6 +115,21 @@ def test_gram_step_is_the_default_with_gram_matrices_appends_in_place_and_agrees
     assert torch.equal(again[0], i_ref) and torch.equal(again[1], c_ref)
 
 
+def test_both_gram_encoders_with_atoms_long_enough_to_make_residuals_grow():
+    # |d|^2 > 2: Eq.4 can lengthen the residual, and the screening bound follows the largest residual norm so far
+    H, T, N, d, s = 2, 16, 256, 128, 12
+    D = synth.dictionary(85, "dict_k", H, N, d, "f16").astype(np.float32)
+    D[:, ::3] *= 3.0
+    D[:, 1::3] *= 1.6
+    D = D.astype(np.float16)
+    X = synth.vectors(85, "keys", H, T, d, "f16", outliers=8)
+    Dg, Xg = torch.from_numpy(D).cuda(), torch.from_numpy(X).cuda()
+    for kw in (dict(algo=csr.CSR_ENCODE_GRAM), dict(gram=csr.csr_gram_build(Dg))):
+        idx, coef = csr.csr_encode(Xg, Dg, s, coef_dtype=torch.float32, idx_dtype=torch.int32, **kw)
+        torch.cuda.synchronize()
+        _assert_ok(_compare_chunked(X, D[:, None], s, idx.cpu().numpy().reshape(H, T, 1, s), coef.cpu().numpy().reshape(H, T, 1, s)))
+
+
 def test_gram_step_limits():
     D = torch.from_numpy(synth.dictionary(84, "dict_k", 1, 512, 128, "f16")).cuda()
     X = torch.from_numpy(synth.vectors(84, "keys", 1, 129, 128, "f16")).cuda()
