@@ -11,8 +11,9 @@
 //   launch 1, sweep_kernel, workgroup (dictionary, 256-atom slice): C_1[n] = x . d_n for the dictionary's vectors
 //       (exact fp16 products, fp32 sums) into scratch, and the slice's largest squared atom norm.  Up to 8 vectors
 //       per dictionary on the vector ALU (the launch is bound by reading the dictionaries), more on the matrix cores.
-//   launch 2, iterate_kernel, one workgroup per vector: the correlations live in registers (8 consecutive atoms per
-//       thread and round), the fp32 residual R in every wave.  Per iteration: block arg-max of |C|; the row of G and
+//   launch 2, iterate_kernel, one workgroup per vector (8 waves when few vectors wait and the length of the chain
+//       counts, 2 or 4 from 12 vectors per dictionary on, when instruction issue does): the correlations live in
+//       registers (8 consecutive atoms per thread and round), the fp32 residual R in every wave.  Per iteration: block arg-max of |C|; the row of G and
 //       of D of that atom are requested at once; every atom whose |C| lies within 2 delta of the maximum is a
 //       candidate, and the candidates' R . d are evaluated in fp32 from the atoms themselves (largest wins, lowest
 //       atom on ties) - the recursion only SCREENS, as the fp16 sweeps of the other encoders do:
@@ -326,7 +327,7 @@ __global__ __launch_bounds__(THREADS) void iterate_kernel(const __half *__restri
     r2 = row_sum<LPR>(r2);
     const float xnorm = sqrtf(r2);
 
-    // this thread's correlations: atoms 8 (tid + 512 j) + e
+    // this thread's correlations: atoms 8 (tid + THREADS j) + e
     float C[NR][8];
 #pragma unroll
     for (int j = 0; j < NR; ++j) {
