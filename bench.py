@@ -561,7 +561,9 @@ def main():
     result["reconstruct"] = {"kernel": "csr_reconstruct", "bound": "hbm", "ms": round(rec_ms, 5),
                              "achieved": round(rec_bytes / (rec_ms * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
                              "unit": "GB/s", "frac": round(rec_bytes / (rec_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 5),
-                             "bytes_per_call": rec_bytes}
+                             "bytes_per_call": rec_bytes,
+                             "note": "the s atom rows per vector (8x the output at s = 8) are gathers from L2: the "
+                                     "address path of the CUs (64 B per clock each), not HBM, bounds this call"}
     del rec_out
 
     # ---- decode alone at the shapes where the code streams dominate (random codes, cache-cold) --------
