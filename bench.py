@@ -12,7 +12,8 @@ the code streams rather than the dictionaries dominate the traffic.  `chunked_st
 storage layout of the paper's experiments ("CSR-8": keys whole with s = 8, values in s_n = 2 chunks of 64
 dimensions with s = 4 each), which runs the 64-dimensional variants of the encoder and the chunk-aware decode.
 `decode_step` is one decoding step: the new token's codes appended in place, then attention over the cache
-(`decode_step_gqa`: the same at the grouped-query shape, 8 sequences on shared dictionaries).
+(`decode_step_gqa`: the same at the grouped-query shape, 8 sequences on shared dictionaries; `decode_step_batch64`:
+the benchmark layer serving 64 sequences).
 `rope_decode` is csr_decode_attn on keys coded before the rotary embedding (rope_base set), at the dictionary sizes
 of the paper's own experiments (256 atoms per KV head), where the key dictionary stays in LDS; `paper_sized_step` is
 the chunked step with those dictionaries and that decode.
@@ -424,6 +425,9 @@ def main():
         res = {"chunked_step" if args.only_chunked else "decode_step": leg(csr, synth, w, torch.device("cuda:0"), args.steps)}
         if args.only_decode_step:
             res["decode_step_gqa"] = decode_step(csr, synth, synth.WORKLOADS["gqa_llama3_8b"], torch.device("cuda:0"), args.steps)
+            import dataclasses
+            res["decode_step_batch64"] = decode_step(csr, synth, dataclasses.replace(w, name=w.name + " x 64 sequences", batch=64),
+                                                     torch.device("cuda:0"), args.steps)
         if args.only_chunked and not args.no_rope:
             res["paper_sized_step"] = chunked_step(csr, synth, w, torch.device("cuda:0"), args.steps, n_atoms=256,
                                                    rope_base=10000.0)
@@ -585,6 +589,10 @@ def main():
         if not args.no_extra_decode:
             # a batch of sequences on shared dictionaries: 8 new keys and 8 new values per dictionary and step
             result["decode_step_gqa"] = decode_step(csr, synth, synth.WORKLOADS["gqa_llama3_8b"], dev, args.steps)
+            # the benchmark layer serving 64 sequences: 64 new keys and 64 new values per dictionary and step
+            import dataclasses
+            result["decode_step_batch64"] = decode_step(csr, synth, dataclasses.replace(w, name=w.name + " x 64 sequences", batch=64),
+                                                        dev, args.steps)
 
     # ---- decode attention on keys coded before the rotary embedding, paper-sized dictionaries -------------
     if not args.no_rope:
