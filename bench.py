@@ -36,13 +36,42 @@ if ROOT not in sys.path:
 PEAK_MFMA_F16_TFLOPS = 2500.0   # MI355X dense fp16 matrix peak
 PEAK_VALU_F32_TFLOPS = 157.3    # MI355X fp32 vector peak
 PEAK_HBM_GBS = 8000.0           # MI355X HBM3E peak
-# HBM bytes per dispatch of the dominant kernel, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (each scaled by what the counter reads for a 1 GiB copy) on this workload: fetched + written.
-# The summary under profiles/ gives the commands and the raw counts.
-PMC_TRAFFIC_BYTES = {("llama7b_layer", "mfma"): 754.3e6 + 144.4e6}
-# The same for one csr_decode_attn call (its four kernels added up), per workload.
-PMC_DECODE_TRAFFIC_BYTES = {"llama7b_layer": 80.8e6 + 3.1e6, "long_context": 702.0e6 + 16.8e6,
-                            "gqa_llama3_8b": 720.6e6 + 115.5e6}
+# HBM bytes per dispatch of the dominant kernel (fetched + written), RECORDED from earlier rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE runs (each scaled by what the counter reads for a 1 GiB copy): hardware counters cannot be
+# read from inside this process, so `traffic` in the JSON line is not a measurement of this run; `traffic_source`
+# names the summary under profiles/ that holds the commands and the raw counts.
+PMC_TRAFFIC_BYTES = {("llama7b_layer", "mfma"): (754.3e6 + 144.4e6, "profiles/encode_mfma_kernel_llama7b_layer.txt")}
+# The same for one csr_decode_attn call (its launches added up), per workload.
+PMC_DECODE_TRAFFIC_BYTES = {
+    "llama7b_layer": (80.8e6 + 3.1e6, "profiles/decode_kernels_llama7b_layer.txt"),
+    "long_context": (702.0e6 + 16.8e6, "profiles/decode_kernels_long_context_gqa.txt"),
+    "gqa_llama3_8b": (720.6e6 + 115.5e6, "profiles/decode_kernels_long_context_gqa.txt")}
+
+
+def recorded_traffic(table, key):
+    """{"traffic": bytes or None, "traffic_source": file or None}: counter traffic recorded under profiles/."""
+    t = table.get(key)
+    return {"traffic": t[0] if t else None, "traffic_source": (t[1] + " (recorded rocprofv3 --pmc run, not this run)") if t else None}
+
+
+def median(xs):
+    xs = sorted(xs)
+    n = len(xs)
+    return xs[n // 2] if n % 2 else 0.5 * (xs[n // 2 - 1] + xs[n // 2])
+
+
+def timed_ms(fn, reps, warmup=2):
+    """Median and list of HIP-event times (ms) of `reps` calls of fn on the current stream."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for a_, b_ in ev:
+        a_.record(); fn(); b_.record()
+    torch.cuda.synchronize()
+    ms = [a_.elapsed_time(b_) for a_, b_ in ev]
+    return median(ms), ms
 
 
 def decode_only(csr, w, dev):
@@ -84,13 +113,54 @@ def decode_only(csr, w, dev):
         run(sets[r % copies])
         ev[r][1].record()
     torch.cuda.synchronize()
-    ms = sum(a.elapsed_time(b) for a, b in ev) / reps
+    ms = median([a.elapsed_time(b) for a, b in ev])
     gbs = nbytes / (ms * 1e-3) / 1e9
     return {"workload": w.name, "kernel": "csr_decode_attn (4 launches), cache-cold", "bound": "hbm",
             "achieved": round(gbs, 2), "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 5),
-            "traffic": PMC_DECODE_TRAFFIC_BYTES.get(w.name), "bytes_per_call": nbytes, "avg_call_ms": round(ms, 5),
+            **recorded_traffic(PMC_DECODE_TRAFFIC_BYTES, w.name), "bytes_per_call": nbytes, "median_call_ms": round(ms, 5),
             "decode_ctx_tokens_per_s": round(B * T / (ms * 1e-3), 1), "copies_rotated": copies,
             "config": {"kv_heads": Hkv, "query_heads": Hq, "atoms": N, "tokens_per_head": T, "s": s, "decode_batch": B}}
+
+
+def encode_only(csr, w, dev, reps):
+    """csr_encode alone at workload `w`'s full shape, one launch per layer: every (sequence, KV head) block of keys
+    and of values in one call on the heads' shared dictionaries (2 Hkv dictionaries, block h on dictionary
+    h % (2 Hkv)).  Vectors N(0,1) with the keys' outlier channels x 10, unit-norm Gaussian atoms, drawn on the GPU
+    with a fixed seed.  A workload of several layers is streamed layer by layer through the same buffers (the
+    encoder's time does not depend on the values), and the time is that of all its layers."""
+    import torch
+    B, Hkv, T, N, d, s = w.batch, w.hkv, w.tokens, w.n_atoms, w.d, w.s
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(5)
+    dicts, H = 2 * Hkv, 2 * Hkv * B
+    D = torch.randn(dicts, N, d, device=dev, generator=gen)
+    D = (D / D.norm(dim=-1, keepdim=True)).half()
+    X = torch.empty(H, T, d, device=dev, dtype=torch.float16)
+    for h in range(H):
+        x = torch.randn(T, d, device=dev, generator=gen)
+        if h % dicts < Hkv:
+            x[:, :w.key_outliers] *= 10
+        X[h] = x.half()
+    idx = torch.empty((H, T, s), dtype=torch.int16, device=dev)
+    coef = torch.empty((H, T, s), dtype=torch.float16, device=dev)
+    need = csr.csr_encode_workspace_bytes(csr.encode_desc(X, D, s, torch.float16, torch.int16))
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+
+    def run():
+        for _ in range(w.layers):
+            csr.csr_encode(X, D, s, idx=idx, coef=coef, workspace=ws)
+
+    ms, all_ms = timed_ms(run, reps, warmup=1)
+    n_vec = H * T * w.layers
+    flop = 2.0 * d * N * s * n_vec
+    tf = flop / (ms * 1e-3) / 1e12
+    return {"workload": w.name, "kernel": "csr_encode (mfma)", "bound": "mfma", "achieved": round(tf, 2),
+            "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / PEAK_MFMA_F16_TFLOPS, 5), "traffic": None,
+            "vectors": n_vec, "launches": w.layers, "vectors_per_launch": H * T, "flop_per_vector": 2.0 * d * N * s,
+            "median_ms": round(ms, 3), "all_ms": [round(m, 3) for m in all_ms],
+            "encode_vectors_per_s": round(n_vec / (ms * 1e-3), 1),
+            "config": {"kv_heads": Hkv, "atoms": N, "tokens_per_head": T, "s": s, "sequences": B, "layers": w.layers,
+                       "dictionaries_per_launch": dicts, "blocks_per_launch": H}}
 
 
 def chunked_step(csr, synth, w, dev, steps, n_atoms=None, rope_base=0.0):
@@ -135,7 +205,7 @@ def chunked_step(csr, synth, w, dev, steps, n_atoms=None, rope_base=0.0):
     for i in range(steps):
         ev[i][0].record(); enc_k(); ev[i][1].record(); enc_v(); ev[i][2].record(); dec(); ev[i][3].record()
     torch.cuda.synchronize()
-    k_ms, v_ms, d_ms = (sum(e[j].elapsed_time(e[j + 1]) for e in ev) / steps for j in range(3))
+    k_ms, v_ms, d_ms = (median([e[j].elapsed_time(e[j + 1]) for e in ev]) for j in range(3))
     nv = B * Hkv * T
     tf = lambda flop, ms: round(flop / (ms * 1e-3) / 1e12, 2)
     v_flop = 2.0 * (d // sn) * N * sV * sn * nv
@@ -198,7 +268,7 @@ def rope_decode(csr, dev, steps):
             for a_, b_ in ev:
                 a_.record(); run(); b_.record()
             torch.cuda.synchronize()
-            times[base] = sum(a_.elapsed_time(b_) for a_, b_ in ev) / steps
+            times[base] = median([a_.elapsed_time(b_) for a_, b_ in ev])
         ms = times[10000.0]
         G = Hq // Hkv
         flop = B * Hkv * T * (2 * sK * d + 6 * (d // 2) + 2 * d * G)
@@ -206,7 +276,7 @@ def rope_decode(csr, dev, steps):
         code_bytes = B * Hkv * T * (sK + snV * sV) * 4
         out.append({"workload": sh["name"], "kernel": "csr_decode_attn, rope_base = 10000 (3 launches)", "bound": "alu",
                     "achieved": round(tf, 2), "peak": PEAK_VALU_F32_TFLOPS, "unit": "TFLOP/s",
-                    "frac": round(tf / PEAK_VALU_F32_TFLOPS, 5), "flop_per_call": flop, "avg_call_ms": round(ms, 5),
+                    "frac": round(tf / PEAK_VALU_F32_TFLOPS, 5), "flop_per_call": flop, "median_call_ms": round(ms, 5),
                     "key_tokens_per_s": round(B * Hkv * T / (ms * 1e-3), 1),
                     "decode_ctx_tokens_per_s": round(B * T / (ms * 1e-3), 1),
                     "code_gbs": round(code_bytes / (ms * 1e-3) / 1e9, 1),
@@ -243,7 +313,7 @@ def small_dict_encoders(csr, dev, steps):
                 for a_, b_ in ev:
                     a_.record(); csr.csr_encode(X, D, s, algo=algo, idx=idx, coef=coef); b_.record()
                 torch.cuda.synchronize()
-                row["ms_s%d" % s] = round(sum(a_.elapsed_time(b_) for a_, b_ in ev) / steps, 4)
+                row["ms_s%d" % s] = round(median([a_.elapsed_time(b_) for a_, b_ in ev]), 4)
             out.append(row)
     return out
 
@@ -306,7 +376,7 @@ def decode_step(csr, synth, w, dev, steps):
         for i in range(steps):
             ev[i][0].record(); append(); ev[i][1].record(); attend(); ev[i][2].record()
         torch.cuda.synchronize()
-        return [sum(e[j].elapsed_time(e[j + 1]) for e in ev) / steps for j in range(2)]
+        return [median([e[j].elapsed_time(e[j + 1]) for e in ev]) for j in range(2)]
 
     use_gram[0] = False
     split_ms, _ = timed()
@@ -329,7 +399,7 @@ def decode_step(csr, synth, w, dev, steps):
     for a_, b_ in gev:
         a_.record(); graph.replay(); b_.record()
     torch.cuda.synchronize()
-    g_ms = sum(a_.elapsed_time(b_) for a_, b_ in gev) / steps
+    g_ms = median([a_.elapsed_time(b_) for a_, b_ in gev])
     dict_bytes = 2 * Hkv * N * d * 2
     sweep_bytes = dict_bytes * s              # without G every iteration reads every dictionary once
     nvec = 2 * B * Hkv
@@ -367,6 +437,10 @@ def main():
                     help="skip the step in the chunked (s_n = 2 values) storage layout")
     ap.add_argument("--no-decode-step", action="store_true",
                     help="skip the decoding step (append one token's codes, then attend)")
+    ap.add_argument("--no-extra-encode", action="store_true",
+                    help="skip the encode-only lines at the long-context, GQA and prefill-stress shapes")
+    ap.add_argument("--only-extra-encode", action="store_true",
+                    help="run only the encode-only lines (for profiling them apart from the main workload)")
     ap.add_argument("--only-extra-decode", action="store_true",
                     help="run only the decode-only lines (for profiling them apart from the main workload)")
     ap.add_argument("--only-chunked", action="store_true", help="run only the chunked-layout step (for profiling)")
@@ -406,6 +480,12 @@ def main():
         torch.cuda.set_device(0)
         print(json.dumps({"decode_rooflines": [decode_only(csr, synth.WORKLOADS[n], torch.device("cuda:0"))
                                                for n in ("long_context", "gqa_llama3_8b")]}))
+        return
+
+    if args.only_extra_encode:
+        torch.cuda.set_device(0)
+        print(json.dumps({"encode_rooflines": [encode_only(csr, synth.WORKLOADS[n], torch.device("cuda:0"), 3)
+                                               for n in ("long_context", "gqa_llama3_8b", "prefill_stress")]}))
         return
 
     if args.only_small_dict:
@@ -494,8 +574,8 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_step = wall * 1e3 / args.steps
-    enc_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
-    dec_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
+    enc_ms = median([e[0].elapsed_time(e[1]) for e in ev])
+    dec_ms = median([e[1].elapsed_time(e[2]) for e in ev])
 
     # ---- cache-cold decode: rotate distinct copies so nothing is served from the Infinity Cache --
     code_b = csr.csr_code_bytes(s, 1, tit, tdt)
@@ -518,7 +598,7 @@ def main():
         decode(**sets[r % copies])
         cev[r][1].record()
     torch.cuda.synchronize()
-    dec_cold_ms = sum(a.elapsed_time(b) for a, b in cev) / reps
+    dec_cold_ms = median([a.elapsed_time(b) for a, b in cev])
     del sets
 
     enc_flop = 2.0 * d * N * s * n_vec
@@ -527,14 +607,15 @@ def main():
     roofline = {"kernel": "csr_encode (%s)" % ("mfma" if uses_mfma else "valu"),
                 "bound": "mfma", "achieved": round(enc_tflops, 3), "peak": PEAK_MFMA_F16_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(enc_tflops / PEAK_MFMA_F16_TFLOPS, 5),
-                "traffic": PMC_TRAFFIC_BYTES.get((w.name, "mfma" if uses_mfma else "valu")),
+                **recorded_traffic(PMC_TRAFFIC_BYTES, (w.name, "mfma" if uses_mfma else "valu")),
                 "algorithmic_bytes": n_vec * (d * dict_b + code_b) + H * N * d * dict_b,
-                "flop_per_vector": 2.0 * d * N * s, "avg_launch_ms": round(enc_ms, 4)}
+                "flop_per_vector": 2.0 * d * N * s, "median_launch_ms": round(enc_ms, 4),
+                "avg_launch_ms": round(sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps, 4)}
     dec_gbs = dec_bytes / (dec_cold_ms * 1e-3) / 1e9
     roofline_decode = {"kernel": "csr_decode_attn (4 launches), cache-cold", "bound": "hbm",
                        "achieved": round(dec_gbs, 2), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                       "frac": round(dec_gbs / PEAK_HBM_GBS, 5), "traffic": PMC_DECODE_TRAFFIC_BYTES.get(w.name),
-                       "bytes_per_call": dec_bytes, "avg_call_ms": round(dec_cold_ms, 5),
+                       "frac": round(dec_gbs / PEAK_HBM_GBS, 5), **recorded_traffic(PMC_DECODE_TRAFFIC_BYTES, w.name),
+                       "bytes_per_call": dec_bytes, "median_call_ms": round(dec_cold_ms, 5),
                        "warm_call_ms": round(dec_ms, 5), "copies_rotated": copies}
 
     result = {
@@ -542,7 +623,10 @@ def main():
         "value": round(n_vec / (ms_step * 1e-3), 1), "unit": "vectors/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f16" if uses_mfma else "f32", "data": "synthetic",
-        "config": {"workload": w.name, "kv_heads": Hkv, "query_heads": Hq, "head_dim": d, "atoms": N,
+        "config": {"workload": w.name,
+                   "workload_note": "the configuration the metric is quoted on (BASELINE.json configs[1]); the larger "
+                                    "single-GPU shapes are in encode_rooflines and decode_rooflines",
+                   "kv_heads": Hkv, "query_heads": Hq, "head_dim": d, "atoms": N,
                    "tokens_per_head": T, "s": s, "decode_batch": B, "vectors_per_step": n_vec,
                    "storage": f"{w.dtype}+{w.itype}", "encode_algo": args.algo},
         "encode_vectors_per_s": round(n_vec / (enc_ms * 1e-3), 1), "encode_ms": round(enc_ms, 4),
@@ -560,7 +644,7 @@ def main():
     for a_, b_ in rev:
         a_.record(); csr.csr_reconstruct(D, idx, coef, out=rec_out); b_.record()
     torch.cuda.synchronize()
-    rec_ms = sum(a_.elapsed_time(b_) for a_, b_ in rev) / args.steps
+    rec_ms = median([a_.elapsed_time(b_) for a_, b_ in rev])
     rec_bytes = n_vec * (code_b + d * dict_b)
     result["reconstruct"] = {"kernel": "csr_reconstruct", "bound": "hbm", "ms": round(rec_ms, 5),
                              "achieved": round(rec_bytes / (rec_ms * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
@@ -574,6 +658,13 @@ def main():
     if not args.no_extra_decode:
         result["decode_rooflines"] = [decode_only(csr, synth.WORKLOADS[n], dev)
                                       for n in ("long_context", "gqa_llama3_8b")]
+
+    # ---- encode alone at the full shapes of the larger configurations (one launch per layer) ------------------
+    if not args.no_extra_encode and uses_mfma:
+        torch.cuda.empty_cache()
+        result["encode_rooflines"] = [encode_only(csr, synth.WORKLOADS[n], dev, 3)
+                                      for n in ("long_context", "gqa_llama3_8b", "prefill_stress")]
+        torch.cuda.empty_cache()
 
     # ---- the same layer in the chunked storage layout of the paper's experiments --------------------------
     if not args.no_chunked and w.dtype == "f16" and d == 128:

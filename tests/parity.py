@@ -31,7 +31,9 @@ class EncodeReport:
     vectors: int = 0
     steps: int = 0
     exact_steps: int = 0
-    tie_vectors: int = 0
+    tie_vectors: int = 0          # vectors whose path left the oracle's at an accepted tie (either clause)
+    floor_ties: int = 0           # ... of which only the absolute-floor clause (not the relative one) accepted
+    floor_coefs: int = 0          # coefficients outside coef_tol * |c| that only the absolute floor accepted
     failures: list = field(default_factory=list)
     max_coef_err: float = 0.0
 
@@ -41,7 +43,8 @@ class EncodeReport:
 
     def summary(self):
         return (f"{self.vectors} vectors, {self.exact_steps}/{self.steps} steps index-identical, "
-                f"{self.tie_vectors} vectors diverged at an accepted tie, "
+                f"{self.tie_vectors} vectors diverged at an accepted tie ({self.floor_ties} by the absolute floor only), "
+                f"{self.floor_coefs} coefficients accepted by the absolute floor only, "
                 f"{len(self.failures)} failures, max rel coef err {self.max_coef_err:.3e}")
 
 
@@ -79,10 +82,13 @@ def check_encode(X, D, idx_c, coef_c, idx_o, coef_o, diag, coef_tol, tie_rel=TIE
     # reads |err| <= max(coef_tol |c|, floor + ulp)
     denom = np.maximum(np.abs(coef_o), (abs_floor[:, None] + ulp) / coef_tol)
     rel = np.abs(coef_c - coef_o) / np.where(denom > 0, denom, 1.0)
+    # the same error against |c| alone: where it exceeds coef_tol although `rel` does not, the floor decided
+    plain = np.abs(coef_c - coef_o) > coef_tol * np.abs(coef_o)
     for t in range(T):
         L = int(lead[t])
         if L:
             e = float(rel[t, :L].max())
+            rep.floor_coefs += int(np.count_nonzero(plain[t, :L] & (rel[t, :L] <= coef_tol)))
             rep.max_coef_err = max(rep.max_coef_err, e)
             if e > coef_tol and len(rep.failures) < max_report:
                 g = int(np.argmax(rel[t, :L]))
@@ -96,6 +102,8 @@ def check_encode(X, D, idx_c, coef_c, idx_o, coef_o, diag, coef_tol, tie_rel=TIE
                                     f"(best {best!r}, runner-up {second!r}: not a tie)")
             continue
         rep.tie_vectors += 1
+        if best - second > tie_rel * best:
+            rep.floor_ties += 1
         # greedy validity of the candidate's own path from step L on
         R = X[t].copy()
         for g in range(L):
@@ -120,10 +128,26 @@ def check_encode(X, D, idx_c, coef_c, idx_o, coef_o, diag, coef_tol, tie_rel=TIE
 
 
 def decode_errors(out_c, out_o):
-    """Relative L2 error per (b, hq) and the largest absolute error."""
+    """Relative L2 error per (b, hq), and the largest absolute error of any element relative to the largest
+    |element| of its own (b, hq) output vector (0 where that vector is all zero)."""
     out_c = np.asarray(out_c, dtype=np.float64)
     out_o = np.asarray(out_o, dtype=np.float64)
+    if not out_o.size:
+        return np.zeros(out_o.shape[:-1]), 0.0
     num = np.linalg.norm(out_c - out_o, axis=-1)
     den = np.linalg.norm(out_o, axis=-1)
     rel = np.where(den > 0, num / np.where(den > 0, den, 1.0), num)
-    return rel, float(np.abs(out_c - out_o).max()) if out_o.size else 0.0
+    peak = np.abs(out_o).max(axis=-1)
+    worst = np.abs(out_c - out_o).max(axis=-1)
+    mx = np.where(peak > 0, worst / np.where(peak > 0, peak, 1.0), worst)
+    return rel, float(mx.max())
+
+
+def assert_decode_close(out_c, out_o, tol, what=""):
+    """Both rules of the decode comparison: relative L2 error per (sequence, query head) and every element's
+    absolute error against the largest |element| of its output vector, each at most tol."""
+    rel, mx = decode_errors(out_c, out_o)
+    assert np.all(np.isfinite(np.asarray(out_c, dtype=np.float64))), what + ": non-finite output"
+    assert rel.size == 0 or rel.max() <= tol, f"{what}: relative L2 error {rel.max():.3e} above {tol:.1e}"
+    assert mx <= tol, f"{what}: largest element error {mx:.3e} of the vector's peak, above {tol:.1e}"
+    return rel, mx

@@ -36,9 +36,22 @@ def test_the_rotary_bench_shapes_are_shapes_the_library_takes():
         assert 0 < need < 1 << 32, (sh, csr.last_error())
 
 
+def test_recorded_counter_traffic_names_a_committed_profile_summary():
+    # `traffic` in the JSON line is a recorded rocprofv3 --pmc figure, labelled as such: its source must exist
+    sys.path.insert(0, ROOT)
+    import bench
+    for table in (bench.PMC_TRAFFIC_BYTES, bench.PMC_DECODE_TRAFFIC_BYTES):
+        for key in table:
+            rec = bench.recorded_traffic(table, key)
+            assert rec["traffic"] > 0 and "recorded" in rec["traffic_source"]
+            assert os.path.isfile(os.path.join(ROOT, rec["traffic_source"].split(" ")[0])), rec
+    assert bench.recorded_traffic(bench.PMC_TRAFFIC_BYTES, "no such workload") == {"traffic": None, "traffic_source": None}
+    assert bench.median([3.0, 1.0, 2.0]) == 2.0 and bench.median([4.0, 1.0, 2.0, 3.0]) == 2.5
+
+
 @pytest.mark.gpu
 def test_the_json_line_carries_the_contracts_fields():
-    r = _bench("--steps", "3", "--warmup", "1", "--no-extra-decode")
+    r = _bench("--steps", "3", "--warmup", "1", "--no-extra-decode", "--no-extra-encode")
     assert r.returncode == 0, r.stderr[-2000:]
     lines = [l for l in r.stdout.splitlines() if l.strip()]
     assert len(lines) == 1
@@ -51,8 +64,9 @@ def test_the_json_line_carries_the_contracts_fields():
     roof = out["roofline"]
     assert roof["bound"] == "mfma" and roof["peak"] == 2500.0 and roof["unit"] == "TFLOP/s"
     assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-4 and roof["traffic"] > 0
+    assert os.path.isfile(os.path.join(ROOT, roof["traffic_source"].split(" ")[0]))
     # achieved = algorithmic flop per launch / launch time, value = vectors per second over the whole step
-    assert abs(roof["achieved"] - out["config"]["vectors_per_step"] * roof["flop_per_vector"] / (roof["avg_launch_ms"] * 1e-3) / 1e12) < 0.01 * roof["achieved"]
+    assert abs(roof["achieved"] - out["config"]["vectors_per_step"] * roof["flop_per_vector"] / (roof["median_launch_ms"] * 1e-3) / 1e12) < 0.01 * roof["achieved"]
     assert abs(out["value"] - out["config"]["vectors_per_step"] / (out["ms_per_step"] * 1e-3)) < 0.01 * out["value"]
     cpu = out["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["cores"] >= 1 and cpu["value"] > 0 and cpu["sample"]

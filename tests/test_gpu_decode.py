@@ -27,10 +27,8 @@ def _run(q, DK, idxK, coefK, DV, idxV, coefV, scale=0.0, seq_lens=None, out_dtyp
 
 
 def _check(out, ref, tol, what=""):
-    rel, mx = parity.decode_errors(out, ref)
-    print(f"[decode parity] {what} max rel L2 {rel.max():.2e}, max abs {mx:.2e}")
-    assert np.all(np.isfinite(out.astype(np.float64)))
-    assert rel.max() <= tol, (what, rel.max())
+    rel, mx = parity.assert_decode_close(out, ref, tol, what)
+    print(f"[decode parity] {what} max rel L2 {rel.max():.2e}, max element error / peak {mx:.2e}")
 
 
 def _case(seed, B, Hq, Hkv, T, N, sK, sV, dtype="f16", itype="i16"):

@@ -1,5 +1,6 @@
 """The comparison rules of tests/parity.py, exercised on the CPU with mistakes planted on purpose."""
 import numpy as np
+import pytest
 
 import oracle
 from tests import parity
@@ -54,6 +55,15 @@ def test_decode_errors():
     a = np.ones((2, 3, 4)); b = a.copy(); b[1, 2, 0] += 0.02
     rel, mx = parity.decode_errors(b, a)
     assert rel.shape == (2, 3) and abs(rel[1, 2] - 0.01) < 1e-12 and abs(mx - 0.02) < 1e-12
+    parity.assert_decode_close(b, a, 0.021)
+    # one element off by 2 % of its vector's peak fails the element rule although the L2 error is 1 %
+    with pytest.raises(AssertionError, match="largest element error"):
+        parity.assert_decode_close(b, a, 0.015)
+    with pytest.raises(AssertionError, match="relative L2"):
+        parity.assert_decode_close(b, a, 0.005)
+    # the element rule is relative to the vector's own peak, not to the whole output's
+    c = a.copy(); c[0] *= 1e-3; e = c.copy(); e[0, 0, 0] += 1e-4
+    assert parity.decode_errors(e, c)[1] > 0.09
 
 
 def test_collapsed_residual_floor_accepts_only_what_fp32_cannot_resolve():
