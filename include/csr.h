@@ -205,6 +205,25 @@ csr_status csr_decode_attn(const csr_decode_desc *desc, const void *q, const voi
                            size_t workspace_bytes, void *hip_stream);
 
 /*
+ * csr_decode_attn for callers that cannot allocate device memory and have no workspace to pass: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation, same kernels, same results as
+ * csr_decode_attn; the scratch is a static device array inside the library, CSR_STATIC_SCRATCH_BYTES per GPU, which
+ * exists from the first use of the library on that GPU until the process ends.  The call allocates and frees
+ * nothing (no hipMalloc, no hipFree, no allocating library routine); its first call on a device looks the array's
+ * address up, every later call only enqueues.
+ *   - A shape whose csr_decode_workspace_bytes() exceeds CSR_STATIC_SCRATCH_BYTES returns CSR_ERR_WORKSPACE (use
+ *     csr_decode_attn with a workspace of the caller's).
+ *   - All calls on one GPU share that GPU's array.  Calls on one stream, or ordered by events, follow each other
+ *     safely (nothing in the scratch has to survive a call or start at zero); calls that may OVERLAP on one GPU -
+ *     different streams without ordering, different host threads - race on it and give undefined results.
+ *   - Every other rule of csr_decode_attn holds (device pointers owned by the caller, alignment, status codes).
+ */
+#define CSR_STATIC_SCRATCH_BYTES ((size_t)16 << 20)
+csr_status csr_decode_attn_static(const csr_decode_desc *desc, const void *q, const void *DK,
+                                  const void *idxK, const void *coefK, const void *DV, const void *idxV,
+                                  const void *coefV, const int32_t *seq_lens, void *out, void *hip_stream);
+
+/*
  * De-sparse restore, Eq.12: out[h][t] = sum over the s pairs of coef * atom (per chunk with chunked codes, the
  * chunks' results side by side).  The dense vectors are what the paper feeds to ordinary attention;
  * csr_decode_attn does not need them, callers that post-process rebuilt keys or values do.

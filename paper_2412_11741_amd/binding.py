@@ -19,7 +19,8 @@ CSR_ENCODE_AUTO, CSR_ENCODE_VALU, CSR_ENCODE_MFMA, CSR_ENCODE_SPLIT, CSR_ENCODE_
 
 EXPORTS = ("csr_version", "csr_last_error", "csr_code_bytes", "csr_encode_workspace_bytes",
            "csr_encode", "csr_decode_workspace_bytes", "csr_decode_attn", "csr_reconstruct", "csr_atom_norms2",
-           "csr_gram_bytes", "csr_gram_build")
+           "csr_gram_bytes", "csr_gram_build", "csr_decode_attn_static")
+STATIC_SCRATCH_BYTES = 16 << 20   # CSR_STATIC_SCRATCH_BYTES of include/csr.h
 
 
 class EncodeDesc(ctypes.Structure):
@@ -90,6 +91,8 @@ def lib():
         L.csr_decode_workspace_bytes.argtypes = [ctypes.POINTER(DecodeDesc)]
         L.csr_decode_attn.restype = ctypes.c_int
         L.csr_decode_attn.argtypes = [ctypes.POINTER(DecodeDesc)] + [vp] * 10 + [sz, vp]
+        L.csr_decode_attn_static.restype = ctypes.c_int
+        L.csr_decode_attn_static.argtypes = [ctypes.POINTER(DecodeDesc)] + [vp] * 9 + [vp]
         _lib = L
     return _lib
 
@@ -292,10 +295,12 @@ def csr_decode_workspace_bytes(desc):
 
 
 def csr_decode_attn(q, DK, idxK, coefK, DV, idxV, coefV, scale=0.0, seq_lens=None, out=None,
-                    out_dtype=None, workspace=None, rope_base=0.0, rope_layout=0, rope_pos0=0):
+                    out_dtype=None, workspace=None, rope_base=0.0, rope_layout=0, rope_pos0=0, static_scratch=False):
     """Decode attention on codes.  q [B, Hq, d]; DK/DV [Hkv, N, d]; codes [B, Hkv, T, s*] -> out [B, Hq, d].
     Chunked codes: DK [Hkv, sn, N, d/sn] with codes [B, Hkv, T, sn, s] (keys and values independently).
-    rope_base > 1: the keys were coded before the rotary embedding; cache token t sits at position rope_pos0 + t."""
+    rope_base > 1: the keys were coded before the rotary embedding; cache token t sits at position rope_pos0 + t.
+    static_scratch: call csr_decode_attn_static (the library's own static device scratch, no workspace; `out` must
+    then be given, so that nothing at all is allocated)."""
     for name, t in (("q", q), ("DK", DK), ("idxK", idxK), ("coefK", coefK), ("DV", DV), ("idxV", idxV),
                     ("coefV", coefV)):
         _dev(t, name)
@@ -314,15 +319,32 @@ def csr_decode_attn(q, DK, idxK, coefK, DV, idxV, coefV, scale=0.0, seq_lens=Non
     desc = decode_desc(q, DK, idxK, coefK, idxV, scale=scale, out_dtype=out_dtype, rope_base=rope_base,
                        rope_layout=rope_layout, rope_pos0=rope_pos0)
     if out is None:
+        if static_scratch:
+            raise ValueError("static_scratch: pass `out` (the call itself allocates nothing)")
         out = torch.empty(q.shape, dtype=out_dtype or q.dtype, device=q.device)
-    need = csr_decode_workspace_bytes(desc)
-    if workspace is None:
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
     if seq_lens is not None:
         _dev(seq_lens, "seq_lens")
         if seq_lens.dtype != torch.int32 or seq_lens.numel() != q.shape[0]:
             raise ValueError("seq_lens must be int32 [B]")
+    if static_scratch:
+        if workspace is not None:
+            raise ValueError("static_scratch takes no workspace")
+        _check(lib().csr_decode_attn_static(ctypes.byref(desc), _ptr(q), _ptr(DK), _ptr(idxK), _ptr(coefK), _ptr(DV),
+                                            _ptr(idxV), _ptr(coefV), _ptr(seq_lens), _ptr(out), _stream()))
+        return out
+    need = csr_decode_workspace_bytes(desc)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
     _check(lib().csr_decode_attn(ctypes.byref(desc), _ptr(q), _ptr(DK), _ptr(idxK), _ptr(coefK), _ptr(DV),
                                  _ptr(idxV), _ptr(coefV), _ptr(seq_lens), _ptr(out), _ptr(workspace),
                                  workspace.numel() * workspace.element_size(), _stream()))
     return out
+
+
+def csr_decode_attn_static(q, DK, idxK, coefK, DV, idxV, coefV, out, scale=0.0, seq_lens=None, out_dtype=None,
+                           rope_base=0.0, rope_layout=0, rope_pos0=0):
+    """csr_decode_attn on the library's static device scratch (at most STATIC_SCRATCH_BYTES of it): no workspace, and
+    nothing is allocated - `out` is the caller's.  Calls that overlap on one GPU race on the scratch."""
+    return csr_decode_attn(q, DK, idxK, coefK, DV, idxV, coefV, scale=scale, seq_lens=seq_lens, out=out,
+                           out_dtype=out_dtype or out.dtype, rope_base=rope_base, rope_layout=rope_layout,
+                           rope_pos0=rope_pos0, static_scratch=True)

@@ -4,8 +4,15 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 
 #include "csr_internal.h"
+
+// Device scratch of csr_decode_attn_static: one array per GPU, held from the first use of the library's code
+// on that GPU until the process ends.  Host code never uses this name as an address (on the host it is only a
+// handle): static_scratch() asks the runtime for the array's device address, once per device.
+constexpr size_t kStaticScratchBytes = CSR_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -116,6 +123,29 @@ size_t encode_workspace(const csr::EncodeArgs &a, int algo)
     if (algo == CSR_ENCODE_SPLIT) return csr::encode_split_workspace_bytes(a);
     if (algo == kAlgoGramStep) return csr::encode_gramstep_workspace_bytes(a);
     return 0;
+}
+
+// Device address of `scratch` on the current device (looked up on the first call per device, then cached).
+constexpr int kMaxScratchDevices = 64;
+void *g_scratch_ptr[kMaxScratchDevices];
+std::mutex g_scratch_mutex;
+
+hipError_t static_scratch(void **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxScratchDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
 }
 
 csr_status check_decode_desc(const csr_decode_desc *d, csr::DecodePlan *plan)
@@ -312,15 +342,11 @@ size_t csr_decode_workspace_bytes(const csr_decode_desc *desc)
     return p.total_bytes;
 }
 
-csr_status csr_decode_attn(const csr_decode_desc *desc, const void *q, const void *DK,
-                           const void *idxK, const void *coefK, const void *DV, const void *idxV,
-                           const void *coefV, const int32_t *seq_lens, void *out, void *workspace,
-                           size_t workspace_bytes, void *hip_stream)
+// Argument checks and launch shared by csr_decode_attn and csr_decode_attn_static; `workspace` is checked by the caller.
+static csr_status decode_run(const csr_decode_desc *desc, const csr::DecodePlan &p, const void *q, const void *DK,
+                             const void *idxK, const void *coefK, const void *DV, const void *idxV,
+                             const void *coefV, const int32_t *seq_lens, void *out, void *workspace, void *hip_stream)
 {
-    csr::DecodePlan p{};
-    csr_status st = check_decode_desc(desc, &p);
-    if (st != CSR_OK) return st;
-    if (desc->B == 0) return CSR_OK;
     if (!q || !out || !DK || !DV) return fail(CSR_ERR_INVALID_ARG, "csr_decode_attn: NULL data pointer");
     if (desc->T > 0 && (!idxK || !coefK || !idxV || !coefV))
         return fail(CSR_ERR_INVALID_ARG, "csr_decode_attn: NULL code pointer with T > 0");
@@ -329,9 +355,6 @@ csr_status csr_decode_attn(const csr_decode_desc *desc, const void *q, const voi
     if (!aligned(idxK, 16) || !aligned(coefK, 16) || !aligned(idxV, 16) || !aligned(coefV, 16))
         return fail(CSR_ERR_INVALID_ARG, "csr_decode_attn: code streams must be 16-byte aligned");
     if (seq_lens && !aligned(seq_lens, 4)) return fail(CSR_ERR_INVALID_ARG, "csr_decode_attn: seq_lens misaligned");
-    if (!workspace || workspace_bytes < p.total_bytes || !aligned(workspace, 256))
-        return fail(CSR_ERR_WORKSPACE, "csr_decode_attn: workspace of %zu bytes (256-byte aligned) required, got %zu",
-                    p.total_bytes, workspace ? workspace_bytes : (size_t)0);
     csr::DecodeArgs a{};
     a.q = q; a.DK = DK; a.idxK = idxK; a.coefK = coefK; a.DV = DV; a.idxV = idxV; a.coefV = coefV;
     a.seq_lens = seq_lens; a.out = out;
@@ -350,6 +373,40 @@ csr_status csr_decode_attn(const csr_decode_desc *desc, const void *q, const voi
     const hipError_t e = csr::launch_decode(a, p);
     if (e != hipSuccess) return fail(CSR_ERR_DEVICE, "csr_decode_attn: %s", hipGetErrorString(e));
     return CSR_OK;
+}
+
+csr_status csr_decode_attn(const csr_decode_desc *desc, const void *q, const void *DK,
+                           const void *idxK, const void *coefK, const void *DV, const void *idxV,
+                           const void *coefV, const int32_t *seq_lens, void *out, void *workspace,
+                           size_t workspace_bytes, void *hip_stream)
+{
+    csr::DecodePlan p{};
+    csr_status st = check_decode_desc(desc, &p);
+    if (st != CSR_OK) return st;
+    if (desc->B == 0) return CSR_OK;
+    if (!workspace || workspace_bytes < p.total_bytes || !aligned(workspace, 256))
+        return fail(CSR_ERR_WORKSPACE, "csr_decode_attn: workspace of %zu bytes (256-byte aligned) required, got %zu",
+                    p.total_bytes, workspace ? workspace_bytes : (size_t)0);
+    return decode_run(desc, p, q, DK, idxK, coefK, DV, idxV, coefV, seq_lens, out, workspace, hip_stream);
+}
+
+csr_status csr_decode_attn_static(const csr_decode_desc *desc, const void *q, const void *DK,
+                                  const void *idxK, const void *coefK, const void *DV, const void *idxV,
+                                  const void *coefV, const int32_t *seq_lens, void *out, void *hip_stream)
+{
+    csr::DecodePlan p{};
+    csr_status st = check_decode_desc(desc, &p);
+    if (st != CSR_OK) return st;
+    if (desc->B == 0) return CSR_OK;
+    if (p.total_bytes > kStaticScratchBytes)
+        return fail(CSR_ERR_WORKSPACE, "csr_decode_attn_static: this shape needs %zu bytes of scratch, the library's static "
+                    "scratch holds %zu; use csr_decode_attn with a workspace", p.total_bytes, kStaticScratchBytes);
+    void *ws = nullptr;
+    const hipError_t e = static_scratch(&ws);
+    if (e != hipSuccess) return fail(CSR_ERR_DEVICE, "csr_decode_attn_static: static scratch: %s", hipGetErrorString(e));
+    // Nothing in the scratch has to start at zero: every launch writes what the next one reads (chunk histograms
+    // of chunks without tokens are never read), so the previous call's contents are simply overwritten.
+    return decode_run(desc, p, q, DK, idxK, coefK, DV, idxV, coefV, seq_lens, out, ws, hip_stream);
 }
 
 }  // extern "C"
