@@ -143,10 +143,11 @@ csr_status csr_encode(const csr_encode_desc *desc, const void *X, const void *D,
  *   out     = DV[h]^T applied to hist, hist[n] = sum_{t,j : idxV = n} p_t * coefV[b][h][t][j]
  * which equals softmax attention over K~ = D_K r_K, V~ = D_V r_V of Eq.12.  No mask beyond the
  * sequence length; no position embedding (the paper's Section "KV cache in attention" sets it
- * aside) unless rope_base is set, see there.  A sequence with len_b = 0 yields zeros.  Accumulation is fp32, except the V-side histogram,
- * which is summed exactly in 64-bit fixed point (the unit is a power of two, 2^-30 of the largest value
- * coefficient among the first 1024 tokens of each chunk of at most 16384 tokens), so the result does not depend on
- * the order in which the hardware serves the scatter: the same inputs give the same bits on every run.
+ * aside) unless rope_base is set, see there.  A sequence with len_b = 0 yields zeros.  Accumulation is fp32, except the
+ * V-side histogram, which is summed exactly in fixed point with integer atomics (per chunk of at most 16384 tokens: 32-bit
+ * bins whose unit is fitted to the data, checked after the scatter for overflow and for resolution, and repeated in 64-bit
+ * bins where the check fails), so the result does not depend on the order in which the hardware serves the scatter: the
+ * same inputs give the same bits on every run.
  */
 typedef struct {
     int32_t B;          /* sequences; >= 0                                                  */

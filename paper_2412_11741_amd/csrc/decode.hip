@@ -198,32 +198,31 @@ __global__ __launch_bounds__(256) void qd_mfma_kernel(const __half *__restrict__
     }
 }
 // One workgroup: chunk c of the tokens of (sequence b, KV head h, group slice gs).
-// LDS: table as fp32 scores q.d, [N][GB] (pass 1), then as 64-bit histogram, [GB][N] (pass 2: one table
-// per query head, so that the scatter of one head spreads over all banks) | red[waves][GB]
-// ONE: the chunk has at most 1024 tokens, one per thread (short contexts: the call is a chain of latencies, not a
-// stream).  The token's first 8 key pairs and value pairs are then requested before the score table, so that the
-// three round trips to memory overlap.  Built for the paper's storage types only (16-bit indices, fp16 coefficients).
-template <int GB, typename TI, typename TC, int PV, bool CH, bool ONE>
+// LDS: the table of scores q.d, fp32 [N][GB] (pass 1), then the fixed-point histogram (pass 2, see finish_chunk) |
+// reduction scratch.
+// TPT: rounds of 1024 tokens a chunk may have; a thread keeps the scores of its tokens (one per round) in registers.
+// VL > 0: a token's key code and its value code are VL 16-byte vectors of indices and of coefficients each (16-bit
+// indices, fp16 coefficients, whole-vector codes, s = 8 VL): the vectors are requested ahead of their use - the
+// first rounds' before the score table is loaded - so that several round trips to memory overlap.
+template <int GB, typename TI, typename TC, int PV, bool CH, int TPT, int VL>
 __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
     const float *__restrict__ qd, const TI *__restrict__ idxK, const TC *__restrict__ coefK,
     const TI *__restrict__ idxV, const TC *__restrict__ coefV, const int32_t *__restrict__ seq_lens,
     float *__restrict__ part_hist, float *__restrict__ part_ml, int32_t Hkv, int32_t ngs, int64_t T,
-    int32_t N, int32_t sK, int32_t sV, int32_t snK_arg, int32_t snV_arg, int64_t chunk_tokens, int32_t nchunks)
+    int32_t N, int32_t sK, int32_t sV, int32_t snK_arg, int32_t snV_arg, int64_t chunk_tokens, int32_t nchunks,
+    uint32_t tab_bytes)
 {
     // CH = false: whole-vector codes, the chunk loops below have one trip known at compile time
-    const int snK = CH ? snK_arg : 1, snV = CH ? snV_arg : 1;
+    const int snK = CH ? snK_arg : 1;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     float *qd_s = reinterpret_cast<float *>(smem_raw);
-    unsigned long long *hist = reinterpret_cast<unsigned long long *>(smem_raw);
     // With chunked codes (sn > 1) a token carries sn * s pairs; pair j of chunk c addresses entry c * N + idx of a
     // table of sn * N entries - the same kernel on a block-diagonal dictionary that is never built.
-    const int NK = snK * N, NV = snV * N;  // entries of the score table / of one query head's histogram
-    const int sKt = snK * sK, sVt = snV * sV;  // pairs per token
-    const size_t tab_bytes = (size_t)(NK * 4 > NV * 8 ? NK * 4 : NV * 8) * GB;
-    float *red = reinterpret_cast<float *>(smem_raw + tab_bytes);  // [kStreamWaves][GB] | [kStreamWaves]
+    const int NK = snK * N;    // entries of the score table
+    const int sKt = snK * sK;  // pairs per token
+    float *red = reinterpret_cast<float *>(smem_raw + tab_bytes);
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
     const int c = blockIdx.x;
     const int h = blockIdx.y / ngs, gs = blockIdx.y % ngs;
     const int b = blockIdx.z;
@@ -246,15 +245,16 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
     const int64_t code_row = ((int64_t)b * Hkv + h) * T;
     const int n_mine = (int)((t_end - t0 + kStreamThreads - 1) / kStreamThreads);  // rounds of 1024 tokens
 
-    uint4 pre_ki = make_uint4(0u, 0u, 0u, 0u), pre_kc = pre_ki, pre_vi = pre_ki, pre_vc = pre_ki;
-    if constexpr (ONE) {
-        static_assert(!ONE || (PV == 8 && sizeof(TI) == 2 && sizeof(TC) == 2), "prefetch is written for 16-byte code vectors");
-        if (t0 + tid < t_end) {
-            const int64_t r = code_row + t0 + tid;
-            pre_ki = *reinterpret_cast<const uint4 *>(idxK + r * sKt);
-            pre_kc = *reinterpret_cast<const uint4 *>(coefK + r * sKt);
-            pre_vi = *reinterpret_cast<const uint4 *>(idxV + r * sVt);
-            pre_vc = *reinterpret_cast<const uint4 *>(coefV + r * sVt);
+    static_assert(VL == 0 || (sizeof(TI) == 2 && sizeof(TC) == 2 && PV == 8 && !CH), "16-byte code vectors");
+    const int64_t tok0 = t0 + tid;  // this thread's token of round 0
+    constexpr int PF = prefetch_rounds<GB, TPT, VL>();
+    CodeVec<VL> ring[PF];
+    CodeWalk<VL, kStreamThreads> walk(idxK, coefK, code_row + tok0);  // walks PF rounds ahead of the current one
+    if constexpr (VL > 0) {
+#pragma unroll
+        for (int k = 0; k < PF; ++k) {
+            fetch_codes<VL>(ring[k], walk.ip, walk.cp, k < n_mine && tok0 + (int64_t)k * kStreamThreads < t_end);
+            walk.next();
         }
     }
     const int table = NK * GB;
@@ -267,72 +267,68 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
     }
     __syncthreads();
 
-
     // ---- pass 1: scores of this thread's tokens (token t0 + i * 1024 + tid in round i) --------
-    // Unit of the fixed-point histogram: 2^-30 of the largest |value coefficient| among this chunk's first
-    // 1024 tokens (read in the first round, next to the key codes, so that the loads overlap).  A coefficient
-    // may exceed that estimate 2^33-fold before an add could overflow.
-    constexpr int kTPT = ONE ? 1 : kMaxTPT;
-    auto unpack_idx = [](const uint4 &r, int (&o)[PV]) {
-        if constexpr (PV == 8) {
-            o[0] = r.x & 0xffff; o[1] = r.x >> 16; o[2] = r.y & 0xffff; o[3] = r.y >> 16;
-            o[4] = r.z & 0xffff; o[5] = r.z >> 16; o[6] = r.w & 0xffff; o[7] = r.w >> 16;
-        }
-    };
-    auto unpack_coef = [](const uint4 &r, float (&o)[PV]) {
-        if constexpr (PV == 8) {
-            const __half2 *h2 = reinterpret_cast<const __half2 *>(&r);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float2 f = __half22float2(h2[j]);
-                o[2 * j] = f.x;
-                o[2 * j + 1] = f.y;
-            }
-        }
-    };
-    float cm = 0.0f;
-    float sc[kTPT][GB];
+    float sc[TPT][GB];
     float mx[GB];
 #pragma unroll
     for (int g = 0; g < GB; ++g) mx[g] = -INFINITY;
 #pragma unroll
-    for (int i = 0; i < kTPT; ++i) {
+    for (int i = 0; i < TPT; ++i) {
 #pragma unroll
         for (int g = 0; g < GB; ++g) sc[i][g] = -INFINITY;
+    }
+    auto pairs = [&](const float *tab, const int (&id)[PV], const float (&cf)[PV], float (&acc)[GB]) {
+#pragma unroll
+        for (int j = 0; j < PV; ++j) {
+            if constexpr (GB == 4) {
+                const float4 t4 = *reinterpret_cast<const float4 *>(tab + id[j] * 4);
+                acc[0] = fmaf(cf[j], t4.x, acc[0]); acc[1] = fmaf(cf[j], t4.y, acc[1]);
+                acc[2] = fmaf(cf[j], t4.z, acc[2]); acc[3] = fmaf(cf[j], t4.w, acc[3]);
+            } else if constexpr (GB == 2) {
+                const float2 t2 = *reinterpret_cast<const float2 *>(tab + id[j] * 2);
+                acc[0] = fmaf(cf[j], t2.x, acc[0]); acc[1] = fmaf(cf[j], t2.y, acc[1]);
+            } else {
+                acc[0] = fmaf(cf[j], tab[id[j]], acc[0]);
+            }
+        }
+    };
+    (void)0;
+#pragma unroll
+    for (int i = 0; i < TPT; ++i) {
         if (i < n_mine) {
-            const int64_t t = t0 + (int64_t)i * kStreamThreads + tid;
+            round_fence();
+            const int64_t t = tok0 + (int64_t)i * kStreamThreads;
+            CodeVec<VL> cur;
+            if constexpr (VL > 0) {
+                take_codes<VL>(cur, ring[i % PF]);
+                if (i + PF < TPT) {
+                    fetch_codes<VL>(ring[i % PF], walk.ip, walk.cp, i + PF < n_mine && t + (int64_t)PF * kStreamThreads < t_end);
+                    walk.next();
+                }
+            }
             if (t < t_end) {
                 float acc[GB];
 #pragma unroll
                 for (int g = 0; g < GB; ++g) acc[g] = 0.0f;
-                const TI *ip = idxK + (code_row + t) * sKt;
-                const TC *cp = coefK + (code_row + t) * sKt;
-                if (i == 0) {  // sample the value coefficients (see c_est below)
-                    const TC *vp = coefV + (code_row + t) * sVt;
-                    for (int j0 = 0; j0 < sVt; j0 += PV) {
-                        float cf[PV];
-                        if (ONE && j0 == 0) unpack_coef(pre_vc, cf);
-                        else CoefLoad<TC, PV>::ld(vp + j0, cf);
+                if constexpr (VL > 0) {
 #pragma unroll
-                        for (int j = 0; j < PV; ++j) cm = fmaxf(cm, fabsf(cf[j]));
+                    for (int v = 0; v < VL; ++v) {
+                        int id[8];
+                        float cf[8];
+                        unpack8(cur.i[v], cur.c[v], id, cf);
+                        pairs(qd_s, id, cf, acc);
                     }
-                }
-                const float *tab = qd_s;
-                for (int ch = 0; ch < snK; ++ch, tab += N * GB, ip += sK, cp += sK) {
-                    for (int j0 = 0; j0 < sK; j0 += PV) {  // PV divides sK: a vector load stays in its chunk
-                        int id[PV];
-                        float cf[PV];
-                        if (ONE && ch == 0 && j0 == 0) {
-                            unpack_idx(pre_ki, id);
-                            unpack_coef(pre_kc, cf);
-                        } else {
+                } else {
+                    const TI *ip = idxK + (code_row + t) * sKt;
+                    const TC *cp = coefK + (code_row + t) * sKt;
+                    const float *tab = qd_s;
+                    for (int ch = 0; ch < snK; ++ch, tab += N * GB, ip += sK, cp += sK) {
+                        for (int j0 = 0; j0 < sK; j0 += PV) {  // PV divides sK: a vector load stays in its chunk
+                            int id[PV];
+                            float cf[PV];
                             IdxLoad<TI, PV>::ld(ip + j0, id);
                             CoefLoad<TC, PV>::ld(cp + j0, cf);
-                        }
-#pragma unroll
-                        for (int j = 0; j < PV; ++j) {
-#pragma unroll
-                            for (int g = 0; g < GB; ++g) acc[g] = fmaf(cf[j], tab[id[j] * GB + g], acc[g]);
+                            pairs(tab, id, cf, acc);
                         }
                     }
                 }
@@ -341,97 +337,8 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
             }
         }
     }
-#pragma unroll
-    for (int g = 0; g < GB; ++g) {
-        const float wm = wave_max(mx[g]);
-        if (lane == 0) red[wave * GB + g] = wm;
-    }
-    cm = wave_max(cm);
-    if (lane == 0) red[kStreamWaves * GB + wave] = cm;
-    __syncthreads();  // every score is computed: the table is free
-    float m_c[GB];
-#pragma unroll
-    for (int g = 0; g < GB; ++g) {
-        float v = red[g];
-#pragma unroll
-        for (int w = 1; w < kStreamWaves; ++w) v = fmaxf(v, red[w * GB + g]);
-        m_c[g] = v;
-    }
-    float c_est = red[kStreamWaves * GB];
-#pragma unroll
-    for (int w = 1; w < kStreamWaves; ++w) c_est = fmaxf(c_est, red[kStreamWaves * GB + w]);
-    int unit_exp = -32;  // all sampled coefficients zero (or not finite): plain 2^-32 units
-    if (c_est > 0.0f && c_est < INFINITY) {
-        int e2;
-        (void)frexpf(c_est, &e2);  // c_est in [2^(e2-1), 2^e2)
-        unit_exp = e2 - 1 - 30;
-    }
-    // p is produced directly in histogram units: exp(score - max) * 2^k = exp(score - (max - k ln 2)); the sum of
-    // the p is scaled back when it is stored.
-    const int k_units = -unit_exp - 32;
-    float m_eff[GB];
-#pragma unroll
-    for (int g = 0; g < GB; ++g) m_eff[g] = m_c[g] - (float)k_units * 0.69314718f;
-    const int bins = NV * GB;
-    for (int e = tid; e < bins; e += kStreamThreads) hist[e] = 0ull;
-    __syncthreads();
-
-    // ---- pass 2: p = exp(score - max), scatter p * c of the V codes into the histogram -----------
-    float l_thr[GB];
-#pragma unroll
-    for (int g = 0; g < GB; ++g) l_thr[g] = 0.0f;
-#pragma unroll
-    for (int i = 0; i < kTPT; ++i) {
-        if (i < n_mine) {
-            const int64_t t = t0 + (int64_t)i * kStreamThreads + tid;
-            if (t < t_end) {
-                float p[GB];
-#pragma unroll
-                for (int g = 0; g < GB; ++g) { p[g] = __expf(sc[i][g] - m_eff[g]); l_thr[g] += p[g]; }
-                const TI *ip = idxV + (code_row + t) * sVt;
-                const TC *cp = coefV + (code_row + t) * sVt;
-                unsigned long long *hb = hist;
-                for (int ch = 0; ch < snV; ++ch, hb += N, ip += sV, cp += sV) {
-                    for (int j0 = 0; j0 < sV; j0 += PV) {
-                        int id[PV];
-                        float cf[PV];
-                        if (ONE && ch == 0 && j0 == 0) {
-                            unpack_idx(pre_vi, id);
-                            unpack_coef(pre_vc, cf);
-                        } else {
-                            IdxLoad<TI, PV>::ld(ip + j0, id);
-                            CoefLoad<TC, PV>::ld(cp + j0, cf);
-                        }
-#pragma unroll
-                        for (int j = 0; j < PV; ++j) {
-#pragma unroll
-                            for (int g = 0; g < GB; ++g) atomicAdd(&hb[g * NV + id[j]], to_fixed(p[g] * cf[j]));
-                        }
-                    }
-                }
-            }
-        }
-    }
-    __syncthreads();  // all atomics landed; `red` is free again
-
-#pragma unroll
-    for (int g = 0; g < GB; ++g) {
-        const float ws = wave_sum(l_thr[g]);
-        if (lane == 0) red[wave * GB + g] = ws;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int g = 0; g < GB; ++g) {
-        if (tid == g) {
-            float l = 0.0f;
-            for (int w = 0; w < kStreamWaves; ++w) l += red[w * GB + g];
-            ml[2 * g] = m_c[g];
-            ml[2 * g + 1] = ldexpf(l, -k_units);
-        }
-    }
-    float *dst = part_hist + slot * (int64_t)bins;
-    const float from_units = ldexpf(1.0f, unit_exp + 32);
-    for (int e = tid; e < bins; e += kStreamThreads) dst[e] = from_fixed(hist[e]) * from_units;
+    finish_chunk<GB, TI, TC, PV, CH, TPT, kStreamThreads, VL>(smem_raw, red, sc, mx, n_mine, t0, t_end, code_row, tid, idxV,
+                                                             coefV, N, sV, snV_arg, ml, part_hist, slot);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -511,10 +418,11 @@ __global__ __launch_bounds__(256) void out_kernel(const TD *__restrict__ DV, con
         *reinterpret_cast<uint4 *>(&dv_s[e / (128 / kVec)][(e % (128 / kVec)) * kVec]) = dv_r[i];
     }
     __syncthreads();
+    float hacc[kElems];
 #pragma unroll
     for (int i = 0; i < kElems; ++i) {
         const int e = i * 256 + tid;
-        const int bgl = e / ATOMS, nn = e % ATOMS;
+        const int bgl = e / ATOMS;
         float acc = 0.0f;
         if (ph[i]) {
             // a chunk without tokens has weight 0 and a histogram that was never written: skip, not multiply
@@ -523,12 +431,33 @@ __global__ __launch_bounds__(256) void out_kernel(const TD *__restrict__ DV, con
                 const float w = c < nchunks ? w_s[bgl][c] : 0.0f;
                 if (w > 0.0f) acc = fmaf(w, early[i][c], acc);
             }
-            for (int c = kEarly; c < nchunks; ++c) {
-                const float w = w_s[bgl][c];
-                if (w > 0.0f) acc = fmaf(w, ph[i][(int64_t)c * NV * GB], acc);
+        }
+        hacc[i] = acc;
+    }
+    // the remaining chunks, four at a time: all their loads are requested before the first is used (a histogram that
+    // was never written is read too, and dropped with its zero weight)
+    for (int c0 = kEarly; c0 < nchunks; c0 += 4) {
+        float v[kElems][4];
+#pragma unroll
+        for (int i = 0; i < kElems; ++i) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                v[i][u] = (ph[i] && c0 + u < nchunks) ? ph[i][(int64_t)(c0 + u) * NV * GB] : 0.0f;
+        }
+#pragma unroll
+        for (int i = 0; i < kElems; ++i) {
+            const int bgl = (i * 256 + tid) / ATOMS;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float w = (ph[i] && c0 + u < nchunks) ? w_s[bgl][c0 + u] : 0.0f;
+                if (w > 0.0f) hacc[i] = fmaf(w, v[i][u], hacc[i]);
             }
         }
-        if (e < NQ * ATOMS) hist_s[bgl][nn] = acc;
+    }
+#pragma unroll
+    for (int i = 0; i < kElems; ++i) {
+        const int e = i * 256 + tid;
+        if (e < NQ * ATOMS) hist_s[e / ATOMS][e % ATOMS] = hacc[i];
     }
     __syncthreads();
     const int k = tid & 127, half = tid >> 7;
@@ -601,10 +530,10 @@ __global__ __launch_bounds__(256) void finalize_kernel(const float *__restrict__
     }
 }
 
-template <int GB, typename TI, typename TC, int PV, bool CH, bool ONE = false>
+template <int GB, typename TI, typename TC, int PV, bool CH, int TPT = max_rounds(GB), int VL = 0>
 hipError_t launch_stream_t(const DecodeArgs &a, const DecodePlan &p, float *qd, float *hist, float *ml)
 {
-    auto kern = stream_kernel<GB, TI, TC, PV, CH, ONE>;
+    auto kern = stream_kernel<GB, TI, TC, PV, CH, TPT, VL>;
     // raising the dynamic-LDS limit is needed once per kernel and device
     static std::atomic<bool> attr_set[kMaxDevices];
     int dev = 0;
@@ -620,7 +549,8 @@ hipError_t launch_stream_t(const DecodeArgs &a, const DecodePlan &p, float *qd, 
     const dim3 grid((unsigned)p.nchunks, (unsigned)(a.Hkv * p.ngs), (unsigned)a.B);
     hipLaunchKernelGGL(kern, grid, dim3(kStreamThreads), p.lds_bytes, a.stream, qd, (const TI *)a.idxK,
                        (const TC *)a.coefK, (const TI *)a.idxV, (const TC *)a.coefV, a.seq_lens, hist, ml,
-                       a.Hkv, p.ngs, a.T, a.N, a.sK, a.sV, a.snK, a.snV, p.chunk_tokens, p.nchunks);
+                       a.Hkv, p.ngs, a.T, a.N, a.sK, a.sV, a.snK, a.snV, p.chunk_tokens, p.nchunks,
+                       (uint32_t)(p.lds_bytes - kRedBytes));
     return hipGetLastError();
 }
 
@@ -633,8 +563,17 @@ hipError_t launch_stream_pv(const DecodeArgs &a, const DecodePlan &p, float *qd,
         return launch_stream_t<GB, TI, TC, 1, true>(a, p, qd, hist, ml);
     }
     if constexpr (sizeof(TI) == 2 && sizeof(TC) == 2) {
-        if (a.sK % 8 == 0 && a.sV % 8 == 0 && p.chunk_tokens == kStreamThreads)
-            return launch_stream_t<GB, TI, TC, 8, false, true>(a, p, qd, hist, ml);
+        // the paper's storage (16-bit indices, fp16 coefficients) with 8 or 16 pairs per code: 16-byte code vectors
+        // requested ahead; chunks of at most 1024 tokens (short contexts) keep one score per thread
+        const int rounds = (int)(p.chunk_tokens / kStreamThreads);
+        if (a.sK == 8 && a.sV == 8)
+            return rounds == 1 ? launch_stream_t<GB, TI, TC, 8, false, 1, 1>(a, p, qd, hist, ml)
+                 : rounds <= 8 ? launch_stream_t<GB, TI, TC, 8, false, 8, 1>(a, p, qd, hist, ml)
+                               : launch_stream_t<GB, TI, TC, 8, false, max_rounds(GB), 1>(a, p, qd, hist, ml);
+        if (a.sK == 16 && a.sV == 16)
+            return rounds == 1 ? launch_stream_t<GB, TI, TC, 8, false, 1, 2>(a, p, qd, hist, ml)
+                 : rounds <= 8 ? launch_stream_t<GB, TI, TC, 8, false, 8, 2>(a, p, qd, hist, ml)
+                               : launch_stream_t<GB, TI, TC, 8, false, max_rounds(GB), 2>(a, p, qd, hist, ml);
     }
     if (a.sK % 8 == 0 && a.sV % 8 == 0) return launch_stream_t<GB, TI, TC, 8, false>(a, p, qd, hist, ml);
     if (a.sK % 4 == 0 && a.sV % 4 == 0) return launch_stream_t<GB, TI, TC, 4, false>(a, p, qd, hist, ml);
@@ -665,8 +604,8 @@ bool plan_decode(int32_t B, int32_t Hq, int32_t Hkv, int64_t T, int32_t d, int32
         // score table (fp32; with rotary keys the dictionary itself, fp16 rows) and histogram (64-bit) share the
         // space: the larger one counts
         const size_t first = rope ? (size_t)N * d * 2 : NK * 4 * cand;
-        const size_t lds = (first > NV * 8 * cand ? first : NV * 8 * cand) + (size_t)kStreamWaves * (cand + 1) * sizeof(float) +
-                           (rope ? kRopeTableBytes : 0);
+        const size_t tab = ((first > NV * 8 * cand ? first : NV * 8 * cand) + 15) & ~size_t(15);
+        const size_t lds = tab + kRedBytes + (rope ? kRopeTableBytes : 0);
         if (lds <= kLdsBudget) { GB = cand; p->lds_bytes = lds; break; }
     }
     if (!GB) return false;
@@ -678,7 +617,7 @@ bool plan_decode(int32_t B, int32_t Hq, int32_t Hkv, int64_t T, int32_t d, int32
     const int64_t groups = (int64_t)(B > 0 ? B : 1) * Hkv * p->ngs;
     int64_t want = (256 + groups - 1) / groups;
     const int64_t threads = rope ? rope_threads(GB) : kStreamThreads;  // tokens per round of the streaming kernel
-    const int64_t tpt = rope ? rope_rounds(GB) : kMaxTPT;          // rounds per chunk
+    const int64_t tpt = rope ? rope_rounds(GB) : max_rounds(GB);   // rounds per chunk
     const int64_t most = T > 0 ? (T + threads - 1) / threads : 1;
     const int64_t least = T > 0 ? (T + tpt * threads - 1) / (tpt * threads) : 1;
     if (want > most) want = most;

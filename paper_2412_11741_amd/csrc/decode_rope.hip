@@ -73,110 +73,8 @@ __device__ __forceinline__ float sum8(float v)
     return v;
 }
 
-// The rest of a chunk, common to all variants of the kernel below: the chunk's maximum, the unit of the fixed-point histogram,
-// pass 2 (p = exp(score - max) in histogram units, scatter p * c of the V codes into the LDS histogram, which takes
-// the place of the dictionary rows), and the chunk's histogram, maximum and sum to scratch - exactly what
-// stream_kernel of the position-free path leaves for out_kernel.
-// owner_off: the token of a round (0 .. THREADS-1) whose score this lane holds in sc[round].
-template <int GB, int PV, int TPT, int THREADS>
-__device__ __forceinline__ void finish_chunk(unsigned char *smem_raw, float *red, const float (&sc)[TPT][GB], const float (&mx)[GB],
-                                             float cm, int n_mine, int64_t t0, int64_t t_end, int64_t code_row, int owner_off,
-                                             const uint16_t *__restrict__ idxV, const __half *__restrict__ coefV, int32_t N,
-                                             int32_t sV, int32_t snV, float *ml, float *part_hist, int64_t slot)
-{
-    constexpr int WAVES = THREADS / 64;
-    unsigned long long *hist = reinterpret_cast<unsigned long long *>(smem_raw);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int NV = snV * N, sVt = snV * sV;
-#pragma unroll
-    for (int g = 0; g < GB; ++g) {
-        const float wm = wave_max(mx[g]);
-        if (lane == 0) red[wave * GB + g] = wm;
-    }
-    cm = wave_max(cm);
-    if (lane == 0) red[WAVES * GB + wave] = cm;
-    __syncthreads();  // every score is computed: the dictionary rows are free
-    float m_c[GB];
-#pragma unroll
-    for (int g = 0; g < GB; ++g) {
-        float v = red[g];
-#pragma unroll
-        for (int w = 1; w < WAVES; ++w) v = fmaxf(v, red[w * GB + g]);
-        m_c[g] = v;
-    }
-    float c_est = red[WAVES * GB];
-#pragma unroll
-    for (int w = 1; w < WAVES; ++w) c_est = fmaxf(c_est, red[WAVES * GB + w]);
-    int unit_exp = -32;
-    if (c_est > 0.0f && c_est < INFINITY) {
-        int e2;
-        (void)frexpf(c_est, &e2);
-        unit_exp = e2 - 1 - 30;
-    }
-    const int k_units = -unit_exp - 32;
-    float m_eff[GB];
-#pragma unroll
-    for (int g = 0; g < GB; ++g) m_eff[g] = m_c[g] - (float)k_units * 0.69314718f;
-    const int bins = NV * GB;
-    for (int e = tid; e < bins; e += THREADS) hist[e] = 0ull;
-    __syncthreads();
-
-    // ---- pass 2: p = exp(score - max) in histogram units, scatter p * c of the V codes -----------------------
-    float l_thr[GB];
-#pragma unroll
-    for (int g = 0; g < GB; ++g) l_thr[g] = 0.0f;
-#pragma unroll
-    for (int i = 0; i < TPT; ++i) {
-        if (i < n_mine) {
-            const int64_t t = t0 + (int64_t)i * THREADS + owner_off;
-            if (t < t_end) {
-                float p[GB];
-#pragma unroll
-                for (int g = 0; g < GB; ++g) { p[g] = __expf(sc[i][g] - m_eff[g]); l_thr[g] += p[g]; }
-                const uint16_t *ip = idxV + (code_row + t) * sVt;
-                const __half *cp = coefV + (code_row + t) * sVt;
-                unsigned long long *hb = hist;
-                for (int ch = 0; ch < snV; ++ch, hb += N, ip += sV, cp += sV) {
-                    for (int j0 = 0; j0 < sV; j0 += PV) {
-                        int id[PV];
-                        float cf[PV];
-                        IdxLoad<uint16_t, PV>::ld(ip + j0, id);
-                        CoefLoad<__half, PV>::ld(cp + j0, cf);
-#pragma unroll
-                        for (int j = 0; j < PV; ++j) {
-#pragma unroll
-                            for (int g = 0; g < GB; ++g) atomicAdd(&hb[g * NV + id[j]], to_fixed(p[g] * cf[j]));
-                        }
-                    }
-                }
-            }
-        }
-    }
-    __syncthreads();
-
-#pragma unroll
-    for (int g = 0; g < GB; ++g) {
-        const float ws = wave_sum(l_thr[g]);
-        if (lane == 0) red[wave * GB + g] = ws;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int g = 0; g < GB; ++g) {
-        if (tid == g) {
-            float l = 0.0f;
-            for (int w = 0; w < WAVES; ++w) l += red[w * GB + g];
-            ml[2 * g] = m_c[g];
-            ml[2 * g + 1] = ldexpf(l, -k_units);
-        }
-    }
-    float *dst = part_hist + slot * (int64_t)bins;
-    const float from_units = ldexpf(1.0f, unit_exp + 32);
-    for (int e = tid; e < bins; e += THREADS) dst[e] = from_fixed(hist[e]) * from_units;
-}
-
-
 // LDS: atom rows of D_K[h], 256 bytes each, the two members of every frequency pair side by side (pass 1), later the
-// 64-bit histogram [GB][NV] (pass 2) | red[waves][GB] | red[waves] | rotation constants [8 lane classes][32] |
+// fixed-point histogram (pass 2, finish_chunk) | reduction scratch | rotation constants [8 lane classes][32] |
 // the group's query pairs, packed fp16 [8 lane classes][4][8] (ROTK only) | theta_k as doubles [64]
 // TPT: rounds of rope_threads(GB) tokens a chunk may have (a lane keeps one score per round and query head).
 // ONEB: a key code is exactly one block of PVK pairs.
@@ -188,10 +86,10 @@ __global__ __launch_bounds__(rope_threads(GB)) void stream_rope_kernel(
     int32_t Hkv, int32_t G, int32_t ngs, int64_t T, int32_t N, int32_t sK, int32_t sV, int32_t snV, float scale,
     float rope_base, int32_t layout, int64_t pos0, int64_t chunk_tokens, int32_t nchunks, uint32_t tab_bytes)
 {
-    constexpr int THREADS = rope_threads(GB), WAVES = THREADS / 64;
+    constexpr int THREADS = rope_threads(GB);
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     float *red = reinterpret_cast<float *>(smem_raw + tab_bytes);
-    float *ctab = red + WAVES * (GB + 1);           // [8][32]: cos, sin of a step; cos, sin of the round jump
+    float *ctab = red + kRedBytes / sizeof(float);  // [8][32]: cos, sin of a step; cos, sin of the round jump
     uint32_t *qtab = reinterpret_cast<uint32_t *>(ctab + 8 * 32);  // [8][GB][8]
 
     const int tid = threadIdx.x;
@@ -200,7 +98,6 @@ __global__ __launch_bounds__(rope_threads(GB)) void stream_rope_kernel(
     const int c = blockIdx.x;
     const int h = blockIdx.y / ngs, gs = blockIdx.y % ngs;
     const int b = blockIdx.z;
-    const int sVt = snV * sV;
 
     int64_t len = T;
     if (seq_lens) {
@@ -331,7 +228,6 @@ __global__ __launch_bounds__(rope_threads(GB)) void stream_rope_kernel(
 
     // ---- pass 1 ---------------------------------------------------------------------------------------------
     const int nblk = ONEB ? 1 : sK / PVK;  // pair blocks per token (ONEB: known to be one)
-    float cm = 0.0f;
     float sc[TPT][GB];
     float mx[GB];
 #pragma unroll
@@ -345,15 +241,6 @@ __global__ __launch_bounds__(rope_threads(GB)) void stream_rope_kernel(
             // the token whose score this lane keeps in round i: the one its eighth handles in step `sub`
             const int64_t t = t0 + (int64_t)i * THREADS + wave * 64 + 8 * sub + eighth;
             const bool have = t < t_end;
-            if (i == 0 && have) {  // sample the value coefficients for the histogram unit (see stream_kernel)
-                const __half *vp = coefV + (code_row + t) * sVt;
-                for (int j0 = 0; j0 < sVt; j0 += PV) {
-                    float cf[PV];
-                    CoefLoad<__half, PV>::ld(vp + j0, cf);
-#pragma unroll
-                    for (int j = 0; j < PV; ++j) cm = fmaxf(cm, fabsf(cf[j]));
-                }
-            }
             float mine[GB];
 #pragma unroll
             for (int g = 0; g < GB; ++g) mine[g] = 0.0f;
@@ -471,8 +358,9 @@ __global__ __launch_bounds__(rope_threads(GB)) void stream_rope_kernel(
             }
         }
     }
-    finish_chunk<GB, PV, TPT, THREADS>(smem_raw, red, sc, mx, cm, n_mine, t0, t_end, code_row, wave * 64 + 8 * sub + eighth,
-                                            idxV, coefV, N, sV, snV, ml, part_hist, slot);
+    finish_chunk<GB, uint16_t, __half, PV, true, TPT, THREADS, 0>(smem_raw, red, sc, mx, n_mine, t0, t_end, code_row,
+                                                                  wave * 64 + 8 * sub + eighth, idxV, coefV, N, sV, snV, ml,
+                                                                  part_hist, slot);
 }
 
 template <int GB, bool ROTK, int PVK, bool ONEB, int PV>
@@ -491,7 +379,7 @@ hipError_t launch_rope_t(const DecodeArgs &a, const DecodePlan &p, float *hist, 
         attr_set[dev].store(true, std::memory_order_release);
     }
     // the plan's LDS size = dictionary / histogram | reductions | constant tables (see plan_decode)
-    const uint32_t tab_bytes = (uint32_t)(p.lds_bytes - (size_t)kStreamWaves * (GB + 1) * sizeof(float) - kRopeTableBytes);
+    const uint32_t tab_bytes = (uint32_t)(p.lds_bytes - kRedBytes - kRopeTableBytes);
     const dim3 grid((unsigned)p.nchunks, (unsigned)(a.Hkv * p.ngs), (unsigned)a.B);
     hipLaunchKernelGGL(kern, grid, dim3(rope_threads(GB)), p.lds_bytes, a.stream, (const __half *)a.q,
                        (const __half *)a.DK, (const uint16_t *)a.idxK, (const __half *)a.coefK,

@@ -225,6 +225,37 @@ def test_hot_atom_with_largest_fp16_coefficients_does_not_overflow():
     _check(out, oracle.decode_attn(q, DK, idxK, coefK, DV, idxV, coefV), TOL_F32_OUT, "hot atom, largest coefficients")
 
 
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_value_coefficients_that_grow_far_beyond_the_sampled_ones(dtype):
+    # The histogram unit is chosen from the value coefficients of a chunk's first 1024 tokens.  Here those are zero
+    # (then tiny), and the later tokens carry coefficients 2^20 times larger (fp32 storage: 2^40): the 32-bit
+    # scatter must notice that its unit does not fit and the result must still be right.
+    B, Hq, Hkv, T, N, s = 1, 4, 1, 6000, 512, 8
+    q, DK, idxK, coefK, DV, idxV, coefV = _case(25, B, Hq, Hkv, T, N, s, s, dtype=dtype, itype="i16" if dtype == "f16" else "i32")
+    big = 2.0 ** 40 if dtype == "f32" else 2.0 ** 9
+    for head_scale in (0.0, 2.0 ** -11):
+        cv = coefV.astype(np.float64)
+        cv[:, :, :1024] *= head_scale
+        cv[:, :, 1024:] *= big
+        cv = cv.astype(coefV.dtype)
+        out = _run(q, DK, idxK, coefK, DV, idxV, cv, out_dtype=torch.float32)
+        _check(out, oracle.decode_attn(q, DK, idxK, coefK, DV, idxV, cv), TOL_F32_OUT, f"growing coefficients ({dtype}, x{head_scale})")
+
+
+def test_an_outlier_coefficient_in_the_sample_and_a_diffuse_tail():
+    # One sampled value coefficient is 2^14 times the typical one while nearly all of the attention mass sits on a
+    # flat tail of tokens far below the maximum score: the adds of the tail are tiny against a unit fitted to the
+    # outlier, which the resolution check of the 32-bit scatter has to catch.
+    B, Hq, Hkv, T, N, s = 1, 1, 1, 16384, 4096, 8
+    q, DK, idxK, coefK, DV, idxV, coefV = _case(26, B, Hq, Hkv, T, N, s, s, dtype="f32", itype="i32")
+    coefK[...] = 0
+    coefK[0, 0, 0, 0] = 9.0 / max(abs(float(q[0, 0] @ DK[0, idxK[0, 0, 0, 0]])) / np.sqrt(128.0), 1e-3)
+    coefK[0, 0, 0, 0] *= np.sign(float(q[0, 0] @ DK[0, idxK[0, 0, 0, 0]]))      # token 0 leads by a score of 9
+    coefV[0, 0, 5, 3] = 2.0 ** 14 * 3.0
+    out = _run(q, DK, idxK, coefK, DV, idxV, coefV, out_dtype=torch.float32)
+    _check(out, oracle.decode_attn(q, DK, idxK, coefK, DV, idxV, coefV), TOL_F32_OUT, "outlier in the sample, diffuse tail")
+
+
 # --- chunked codes (s_n of Section "NeuralDict"; the experiments store values with s = 4, s_n = 2) ---------
 
 def _chunked_case(seed, B, Hq, Hkv, T, N, snK, sK, snV, sV):
