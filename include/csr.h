@@ -83,8 +83,8 @@ typedef enum {
 typedef struct {
     int32_t H;          /* vector blocks (e.g. sequences x KV heads x {K,V}); >= 0          */
     int64_t T;          /* vectors per dictionary; >= 0 (0 is a no-op)                     */
-    int32_t d;          /* vector length; the chunk length d / s_n must be 32, 64 or 128
-                           (VALU); the MFMA encoder takes fp16 chunks of 64 or 128              */
+    int32_t d;          /* vector length; the chunk length d / s_n must be 32, 64 or 128 (VALU and, for
+                           fp16, MFMA); the other encoders take fp16 chunks of 64 or 128        */
     int32_t N;          /* atoms per dictionary, 1..65536 (I16) or 1..2^24 (I32)            */
     int32_t s;          /* iterations = pairs per vector (per chunk), 1..32                 */
     int32_t s_n;        /* chunks per vector (Section "NeuralDict"): 0 or 1 = the vector is coded
@@ -175,8 +175,8 @@ typedef struct {
                            turned at its own position.  Supported with the paper's storage types (fp16 q and
                            dictionaries, 16-bit indices, fp16 coefficients), whole-vector keys (snK <= 1),
                            sK a multiple of 4 and a key dictionary of at most 128 KB (N <= 512): the kernel
-                           keeps it in LDS.  T is then at most 2^19 (2^18 when Hq/Hkv is a multiple of
-                           4).  Scores carry the rounding of the turned query (or key) to fp16, a
+                           keeps it in LDS.  T is then at most 2^19 when Hq/Hkv is a multiple of
+                           4.  Scores carry the rounding of the turned query (or key) to fp16, a
                            relative 2^-11 per component, instead of fp32 accuracy.                 */
     int32_t rope_layout; /* 0: pair k is dimensions (k, k + d/2); 1: dimensions (2k, 2k + 1)    */
     int64_t rope_pos0;  /* position of cache token 0 of every sequence; 0 .. 2^40              */

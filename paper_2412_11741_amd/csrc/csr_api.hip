@@ -88,7 +88,7 @@ csr_status check_encode_desc(const csr_encode_desc *d, csr::EncodeArgs *args, in
     a.idx16 = d->idx_dtype == CSR_I16;
     const bool mfma_ok = csr::encode_mfma_supported(a), split_ok = csr::encode_split_supported(a);
     if (d->algo == CSR_ENCODE_MFMA && !mfma_ok)
-        return fail(CSR_ERR_UNSUPPORTED, "csr_encode: the MFMA encoder needs fp16 inputs, chunks of 64 or 128 dimensions and N a multiple of 32 (got d/s_n=%d N=%d %s)",
+        return fail(CSR_ERR_UNSUPPORTED, "csr_encode: the MFMA encoder needs fp16 inputs, chunks of 32, 64 or 128 dimensions and N a multiple of 32 (got d/s_n=%d N=%d %s)",
                     dc, d->N, a.f16 ? "f16" : "f32");
     if (d->algo == CSR_ENCODE_SPLIT && !split_ok)
         return fail(CSR_ERR_UNSUPPORTED, "csr_encode: the split encoder needs fp16 inputs, chunks of 64 or 128 dimensions, N a multiple of 32 "
@@ -197,9 +197,10 @@ csr_status check_decode_desc(const csr_decode_desc *d, csr::DecodePlan *plan)
     } else if (d->rope_layout != 0 || d->rope_pos0 != 0) {
         return fail(CSR_ERR_INVALID_ARG, "csr_decode_attn: rope_layout and rope_pos0 must be 0 when rope_base is 0");
     }
-    if (!csr::plan_decode(d->B, d->Hq, d->Hkv, d->T, d->d, d->N, snK, snV, rope, plan))
+    const bool wide_codes = d->idx_dtype == CSR_I16 && d->coef_dtype == CSR_F16 && snK == 1 && snV == 1 && d->sK == 16 && d->sV == 16;
+    if (!csr::plan_decode(d->B, d->Hq, d->Hkv, d->T, d->d, d->N, snK, snV, rope, wide_codes, plan))
         return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: N=%d atoms do not fit the LDS-resident score and histogram tables, or T=%lld "
-                                         "exceeds what 64 token chunks hold", d->N, (long long)d->T);
+                                         "exceeds what 128 token chunks hold", d->N, (long long)d->T);
     return CSR_OK;
 }
 

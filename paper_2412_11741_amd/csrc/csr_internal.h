@@ -111,8 +111,9 @@ struct DecodeArgs {
 
 // Fills the plan; returns false if no kernel configuration fits (e.g. N too large for LDS).
 // rope: the plan is for the kernel that keeps the key dictionary in LDS (keys coded before the rotary embedding).
+// wide_codes: 16 pairs per key and per value code in the paper's storage types (two 16-byte vectors per stream).
 bool plan_decode(int32_t B, int32_t Hq, int32_t Hkv, int64_t T, int32_t d, int32_t N, int32_t snK, int32_t snV,
-                 bool rope, DecodePlan *p);
+                 bool rope, bool wide_codes, DecodePlan *p);
 hipError_t launch_decode(const DecodeArgs &a, const DecodePlan &p);
 
 // Streaming kernel for keys coded before the rotary embedding (decode_rope.hip); fills the same chunk histograms,

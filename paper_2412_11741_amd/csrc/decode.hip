@@ -197,6 +197,61 @@ __global__ __launch_bounds__(256) void qd_mfma_kernel(const __half *__restrict__
         }
     }
 }
+// ---------------------------------------------------------------------------------------------
+// The same table for few queries per KV head (at most 8: short batches without query groups), fp16 queries and
+// dictionary.  With so few rows the matrix cores have nothing to do and what counts is how the dictionary is read:
+// here 16 lanes share an atom row (16 bytes each, so a wave instruction reads four whole rows, 1 KiB contiguous),
+// all eight row requests of a thread are issued before the first is used, the products are packed fp16 dot products
+// with fp32 accumulation (exact products, as on the matrix cores) and the 16 partial sums of a row meet in four
+// cross-lane adds.  Whole-vector codes only (the chunked table stays with qd_mfma_kernel).
+typedef _Float16 qd_half2 __attribute__((ext_vector_type(2)));
+template <int NQ>
+__global__ __launch_bounds__(256) void qd_rows_kernel(const __half *__restrict__ q, const __half *__restrict__ DK,
+                                                      float *__restrict__ qd, int32_t B, int32_t Hq, int32_t Hkv,
+                                                      int32_t G, int32_t GB, int32_t N, float scale)
+{
+    constexpr int kRows = 8;                      // atom rows per thread; 16 threads per row: 128 atoms per workgroup
+    const int h = blockIdx.y;
+    const int tid = threadIdx.x;
+    const int sub = tid & 15, arow = tid >> 4;
+    const int n_base = blockIdx.x * (16 * kRows);
+    const int ngs = G / GB;
+    const int BG = B * G;                         // <= NQ
+    uint4 a[kRows];
+#pragma unroll
+    for (int i = 0; i < kRows; ++i) {
+        const int n = n_base + arow + 16 * i;
+        a[i] = make_uint4(0u, 0u, 0u, 0u);
+        if (n < N) a[i] = *reinterpret_cast<const uint4 *>(DK + ((int64_t)h * N + n) * 128 + sub * 8);
+    }
+    uint4 qv[NQ];
+#pragma unroll
+    for (int r = 0; r < NQ; ++r) {
+        qv[r] = make_uint4(0u, 0u, 0u, 0u);
+        if (r < BG) qv[r] = *reinterpret_cast<const uint4 *>(q + ((int64_t)(r / G) * Hq + h * G + r % G) * 128 + sub * 8);
+    }
+    auto dot8 = [](const uint4 &x, const uint4 &y) {
+        const qd_half2 *xp = reinterpret_cast<const qd_half2 *>(&x), *yp = reinterpret_cast<const qd_half2 *>(&y);
+        float acc = __builtin_amdgcn_fdot2(xp[0], yp[0], 0.0f, false);
+        acc = __builtin_amdgcn_fdot2(xp[1], yp[1], acc, false);
+        acc = __builtin_amdgcn_fdot2(xp[2], yp[2], acc, false);
+        return __builtin_amdgcn_fdot2(xp[3], yp[3], acc, false);
+    };
+    // lane `sub` of a row keeps query `sub`'s product, so that one store instruction per row writes all queries
+    const int64_t my_off = sub < BG ? ((((int64_t)(sub / G) * Hkv + h) * ngs + (sub % G) / GB) * (int64_t)N) * GB + (sub % G) % GB : 0;
+#pragma unroll
+    for (int i = 0; i < kRows; ++i) {
+        const int n = n_base + arow + 16 * i;
+        float mine = 0.0f;
+#pragma unroll
+        for (int r = 0; r < NQ; ++r) {
+            const float d = row_reduce<16>(dot8(a[i], qv[r]), OpAdd());
+            if (sub == r) mine = d;
+        }
+        if (sub < BG && n < N) qd[my_off + (int64_t)n * GB] = scale * mine;
+    }
+}
+
 // One workgroup: chunk c of the tokens of (sequence b, KV head h, group slice gs).
 // LDS: the table of scores q.d, fp32 [N][GB] (pass 1), then the fixed-point histogram (pass 2, see finish_chunk) |
 // reduction scratch.
@@ -249,11 +304,11 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
     const int64_t tok0 = t0 + tid;  // this thread's token of round 0
     constexpr int PF = prefetch_rounds<GB, TPT, VL>();
     CodeVec<VL> ring[PF];
-    CodeWalk<VL, kStreamThreads> walk(idxK, coefK, code_row + tok0);  // walks PF rounds ahead of the current one
+    CodeWalk<VL, kStreamThreads> walk(idxK, coefK, code_row + t0, tid);  // walks PF rounds ahead of the current one
     if constexpr (VL > 0) {
 #pragma unroll
         for (int k = 0; k < PF; ++k) {
-            fetch_codes<VL>(ring[k], walk.ip, walk.cp, k < n_mine && tok0 + (int64_t)k * kStreamThreads < t_end);
+            fetch_codes<VL, kStreamThreads>(ring[k], walk, k < n_mine && tok0 + (int64_t)k * kStreamThreads < t_end);
             walk.next();
         }
     }
@@ -302,7 +357,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
             if constexpr (VL > 0) {
                 take_codes<VL>(cur, ring[i % PF]);
                 if (i + PF < TPT) {
-                    fetch_codes<VL>(ring[i % PF], walk.ip, walk.cp, i + PF < n_mine && t + (int64_t)PF * kStreamThreads < t_end);
+                    fetch_codes<VL, kStreamThreads>(ring[i % PF], walk, i + PF < n_mine && t + (int64_t)PF * kStreamThreads < t_end);
                     walk.next();
                 }
             }
@@ -594,7 +649,7 @@ hipError_t launch_stream_gb(const DecodeArgs &a, const DecodePlan &p, float *qd,
 }  // namespace
 
 bool plan_decode(int32_t B, int32_t Hq, int32_t Hkv, int64_t T, int32_t d, int32_t N, int32_t snK, int32_t snV,
-                 bool rope, DecodePlan *p)
+                 bool rope, bool wide_codes, DecodePlan *p)
 {
     const size_t NK = (size_t)snK * N, NV = (size_t)snV * N;  // entries of the score table / of a histogram
     const int G = Hq / Hkv;
@@ -617,6 +672,7 @@ bool plan_decode(int32_t B, int32_t Hq, int32_t Hkv, int64_t T, int32_t d, int32
     const int64_t groups = (int64_t)(B > 0 ? B : 1) * Hkv * p->ngs;
     int64_t want = (256 + groups - 1) / groups;
     const int64_t threads = rope ? rope_threads(GB) : kStreamThreads;  // tokens per round of the streaming kernel
+    (void)wide_codes;
     const int64_t tpt = rope ? rope_rounds(GB) : max_rounds(GB);   // rounds per chunk
     const int64_t most = T > 0 ? (T + threads - 1) / threads : 1;
     const int64_t least = T > 0 ? (T + tpt * threads - 1) / (tpt * threads) : 1;
@@ -657,7 +713,15 @@ hipError_t launch_decode(const DecodeArgs &a, const DecodePlan &p)
 #define CSR_QD(TQ, TD)                                                                              \
     hipLaunchKernelGGL((qd_kernel<TQ, TD>), grid, dim3(256), 0, a.stream, (const TQ *)a.q,          \
                        (const TD *)a.DK, qd, a.B, a.Hq, a.Hkv, a.G, p.GB, a.N, a.scale)
-        if (a.q16 && a.dict16) {
+        const int BG = a.B * a.G;
+        if (a.q16 && a.dict16 && a.snK == 1 && BG <= 8) {
+            const dim3 rgrid((unsigned)((a.N + 127) / 128), (unsigned)a.Hkv);
+#define CSR_QDR(NQ)                                                                                        \
+    hipLaunchKernelGGL((qd_rows_kernel<NQ>), rgrid, dim3(256), 0, a.stream, (const __half *)a.q,           \
+                       (const __half *)a.DK, qd, a.B, a.Hq, a.Hkv, a.G, p.GB, a.N, a.scale)
+            if (BG <= 1) CSR_QDR(1); else if (BG <= 2) CSR_QDR(2); else if (BG <= 4) CSR_QDR(4); else CSR_QDR(8);
+#undef CSR_QDR
+        } else if (a.q16 && a.dict16) {
             const dim3 mgrid((unsigned)((a.snK * a.N + 128 * kQdTiles - 1) / (128 * kQdTiles)), (unsigned)a.Hkv);
             hipLaunchKernelGGL(qd_mfma_kernel, mgrid, dim3(256), 0, a.stream, (const __half *)a.q,
                                (const __half *)a.DK, qd, a.B, a.Hq, a.Hkv, a.G, p.GB, a.N, a.snK, a.scale);

@@ -13,7 +13,7 @@ constexpr int kMaxDevices = 64;      // devices a process may use this library o
 constexpr int kMaxTPT = 16;           // tokens per thread and chunk: their scores stay in registers
 // ... with four query heads per workgroup only 8 (32 of the 128 registers a thread of a 1024-thread workgroup has)
 constexpr int max_rounds(int GB) { return GB == 4 ? 8 : kMaxTPT; }
-constexpr int kMaxChunks = 64;
+constexpr int kMaxChunks = 128;
 // The rotary-key kernel (decode_rope.hip).  One query head at a time: 16 waves with 128 registers each; a query group
 // keeps a rebuilt key and the group's scores in registers: 8 waves with 256 each.
 constexpr int rope_threads(int GB) { return GB >= 2 ? 512 : 1024; }  // tokens per round
@@ -206,31 +206,34 @@ template <int VL> struct CodeVec { uint4 i[VL > 0 ? VL : 1], c[VL > 0 ? VL : 1];
 template <int GB, int TPT, int VL> constexpr int prefetch_rounds() { return GB == 1 && VL == 1 && TPT >= 4 ? 2 : 1; }
 
 // The 16-byte code vectors of the token of round i (token t0 + i * threads + off), zeros past the end.
-template <int VL>
-__device__ __forceinline__ void fetch_codes(CodeVec<VL> &r, const uint4 *ip, const uint4 *cp, bool have)
+// The code streams of a thread's tokens, walked round by round: two workgroup-uniform base addresses (the code
+// vectors of the chunk's first token) and one 32-bit offset per thread, in 16-byte vectors.  The offset passes
+// through an empty asm statement at every step, so that the compiler cannot work out all rounds' addresses ahead of
+// time (they would occupy registers from the start of the loop).
+template <int VL, int THREADS> struct CodeWalk {
+    const uint4 *ib, *cb;   // uniform
+    uint32_t off;           // this thread's token of the round the walk stands at, times VL
+    __device__ __forceinline__ CodeWalk(const void *idx, const void *coef, int64_t first_token, int owner_off)
+        : ib(reinterpret_cast<const uint4 *>(idx) + first_token * (VL > 0 ? VL : 1)),
+          cb(reinterpret_cast<const uint4 *>(coef) + first_token * (VL > 0 ? VL : 1)),
+          off((uint32_t)owner_off * (VL > 0 ? VL : 1)) {}
+    __device__ __forceinline__ void next()
+    {
+        off += THREADS * (VL > 0 ? VL : 1);
+        asm volatile("" : "+v"(off));
+    }
+};
+// The 16-byte code vectors of the token the walk stands at (zeros if `have` is false).
+template <int VL, int THREADS>
+__device__ __forceinline__ void fetch_codes(CodeVec<VL> &r, const CodeWalk<VL, THREADS> &w, bool have)
 {
 #pragma unroll
     for (int v = 0; v < (VL > 0 ? VL : 1); ++v) r.i[v] = r.c[v] = make_uint4(0u, 0u, 0u, 0u);
     if (have) {
 #pragma unroll
-        for (int v = 0; v < VL; ++v) { r.i[v] = ip[v]; r.c[v] = cp[v]; }
+        for (int v = 0; v < VL; ++v) { r.i[v] = w.ib[w.off + v]; r.c[v] = w.cb[w.off + v]; }
     }
 }
-// The code streams of a thread's tokens, walked round by round.  The pointers pass through an empty asm statement at
-// every step, so that the compiler cannot work out all rounds' addresses ahead of time (two 64-bit addresses per
-// round would otherwise occupy registers from the start of the loop).
-template <int VL, int THREADS> struct CodeWalk {
-    const uint4 *ip, *cp;
-    __device__ __forceinline__ CodeWalk(const void *idx, const void *coef, int64_t token)
-        : ip(reinterpret_cast<const uint4 *>(idx) + token * (VL > 0 ? VL : 1)),
-          cp(reinterpret_cast<const uint4 *>(coef) + token * (VL > 0 ? VL : 1)) {}
-    __device__ __forceinline__ void next()
-    {
-        ip += (int64_t)THREADS * (VL > 0 ? VL : 1);
-        cp += (int64_t)THREADS * (VL > 0 ? VL : 1);
-        asm volatile("" : "+v"(ip), "+v"(cp));
-    }
-};
 // Takes over the code vectors that were requested a round ago: `cur` must hold them (so the wait for that request
 // comes here) BEFORE a later round's request is issued into `nxt`; the empty asm statements keep the compiler from
 // moving the copy - and with it the wait - behind the new request, where it would wait for both.
@@ -288,12 +291,12 @@ __device__ __forceinline__ void finish_chunk(unsigned char *smem_raw, float *red
     auto prime = [&](CodeWalk<VL, THREADS> &w) {   // requests rounds 0 .. PF-1, leaves w at round PF
 #pragma unroll
         for (int k = 0; k < PF; ++k) {
-            fetch_codes<VL>(ring[k], w.ip, w.cp, k < n_mine && tok0 + (int64_t)k * THREADS < t_end);
+            fetch_codes<VL, THREADS>(ring[k], w, k < n_mine && tok0 + (int64_t)k * THREADS < t_end);
             w.next();
         }
     };
     if constexpr (VL > 0) {
-        CodeWalk<VL, THREADS> w0(idxV, coefV, code_row + tok0);
+        CodeWalk<VL, THREADS> w0(idxV, coefV, code_row + t0, owner_off);
         prime(w0);
     }
 #pragma unroll
@@ -379,7 +382,7 @@ __device__ __forceinline__ void finish_chunk(unsigned char *smem_raw, float *red
 #pragma unroll
         for (int g = 0; g < GB; ++g) scale[g] = ldexpf(1.0f, k_exp[g]);
         float s_thr = 0.0f, m_thr = 0.0f;  // sum and maximum of p' * sum_j |c_j| over this thread's tokens and heads
-        CodeWalk<VL, THREADS> walk(idxV, coefV, code_row + tok0);  // walks PF rounds ahead of the current one
+        CodeWalk<VL, THREADS> walk(idxV, coefV, code_row + t0, owner_off);  // walks PF rounds ahead of the current one
         if constexpr (VL > 0) {
             if (attempt > 0) prime(walk);
             else {
@@ -398,7 +401,7 @@ __device__ __forceinline__ void finish_chunk(unsigned char *smem_raw, float *red
                     if constexpr (VL > 0) {
                         take_codes<VL>(cur, ring[i % PF]);
                         if (i + PF < TPT) {
-                            fetch_codes<VL>(ring[i % PF], walk.ip, walk.cp, i + PF < n_mine && t + (int64_t)PF * THREADS < t_end);
+                            fetch_codes<VL, THREADS>(ring[i % PF], walk, i + PF < n_mine && t + (int64_t)PF * THREADS < t_end);
                             walk.next();
                         }
                     }

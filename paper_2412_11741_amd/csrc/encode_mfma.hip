@@ -1,6 +1,6 @@
-// Matrix-core Matching Pursuit encoder for fp16 vectors and dictionaries of 128 or 64 dimensions (gfx950):
-// whole head vectors, or the chunks of the paper's Section "NeuralDict" (s_n = 2), each chunk a vector of its
-// own on its own dictionary.  The description below gives the numbers for 128 dimensions.
+// Matrix-core Matching Pursuit encoder for fp16 vectors and dictionaries of 128, 64 or 32 dimensions (gfx950):
+// whole head vectors, or the chunks of the paper's Section "NeuralDict" (s_n = 2 or 4 at a head dimension of 128),
+// each chunk a vector of its own on its own dictionary.  The description below gives the numbers for 128 dimensions.
 //
 // What is computed is exactly Eq.2-4 of the paper's Section "Sparse representation": every
 // iteration picks the atom of largest |R . d_n| (lowest n on ties), takes the signed projection as
@@ -70,17 +70,21 @@ constexpr int kTokPerWave = 32 * kBlocks;             // 64
 constexpr int kStageBytes = 16384;                    // one LDS stage: rows unpadded, 16-byte pieces XOR-swizzled
 constexpr int kRing = 3;                              // stage buffers; stage st lives in buffer st % 3
 template <int W> constexpr int stage_loads() { return kStageBytes / (16 * 64 * W); }  // load instructions per lane and stage
-// Shapes that follow from the vector length DC (128 or 64)
+// Shapes that follow from the vector length DC (128, 64 or 32)
 template <int DC> struct Shape {
     static constexpr int kRowBytes = DC * 2;
     static constexpr int kFrags = DC / 16;                       // 8-element MFMA operand fragments per lane
-    static constexpr int kStageAtoms = kStageBytes / kRowBytes;  // 64 | 128
-    static constexpr int kStageTiles = kStageAtoms / 32;         // 32-atom tiles per stage: 2 | 4
-    static constexpr int kPieces = kRowBytes / 16;               // 16-byte pieces per row: 16 | 8
-    static constexpr int kRowsPerKiB = 1024 / kRowBytes;         // rows one wave-wide load instruction fills: 4 | 8
+    static constexpr int kStageAtoms = kStageBytes / kRowBytes;  // 64 | 128 | 256
+    static constexpr int kStageTiles = kStageAtoms / 32;         // 32-atom tiles per stage: 2 | 4 | 8
+    static constexpr int kPieces = kRowBytes / 16;               // 16-byte pieces per row: 16 | 8 | 4
+    static constexpr int kRowsPerKiB = 1024 / kRowBytes;         // rows one wave-wide load instruction fills: 4 | 8 | 16
     // XOR term of a row's piece positions.  A 256-byte row spans all 64 banks, so 16 consecutive rows must
-    // differ; two 128-byte rows span them, so 16 consecutive rows need 8 different terms, one per row pair.
-    static __device__ __forceinline__ int swz(int row) { return DC == 128 ? (row & 15) : ((row >> 1) & 7); }
+    // differ; two 128-byte rows span them, so 16 consecutive rows need 8 different terms, one per row pair;
+    // four 64-byte rows span them: 4 terms, one per group of four rows.
+    static __device__ __forceinline__ int swz(int row)
+    {
+        return DC == 128 ? (row & 15) : DC == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3);
+    }
 };
 constexpr int kScratchPerWave = 1024;                 // LDS a wave uses to share one token's state
 constexpr int kScratchOff = kRing * kStageBytes;
@@ -645,7 +649,7 @@ size_t r256(size_t v) { return (v + 255) & ~size_t(255); }
 
 bool encode_mfma_supported(const EncodeArgs &a)
 {
-    return a.f16 && (a.d == 128 || a.d == 64) && a.N >= 32 && a.N % 32 == 0 && a.N <= 65536;
+    return a.f16 && (a.d == 128 || a.d == 64 || a.d == 32) && a.N >= 32 && a.N % 32 == 0 && a.N <= 65536;
 }
 
 size_t encode_mfma_workspace_bytes(int32_t H, int64_t T, int32_t N, int32_t s)
@@ -718,7 +722,7 @@ hipError_t launch_encode_mfma_t(const EncodeArgs &a)
 
 hipError_t launch_encode_mfma(const EncodeArgs &a)
 {
-    return a.d == 64 ? launch_encode_mfma_t<64>(a) : launch_encode_mfma_t<128>(a);
+    return a.d == 32 ? launch_encode_mfma_t<32>(a) : a.d == 64 ? launch_encode_mfma_t<64>(a) : launch_encode_mfma_t<128>(a);
 }
 
 }  // namespace csr

@@ -52,13 +52,13 @@ def _enc(**kw):
     (dict(x_stride_t=100), B.CSR_ERR_INVALID_ARG), (dict(x_stride_t=132), B.CSR_ERR_INVALID_ARG),
     (dict(x_stride_t=256, x_stride_h=128), B.CSR_ERR_INVALID_ARG),
     (dict(d=100), B.CSR_ERR_UNSUPPORTED), (dict(dict_dtype=B.CSR_F32), B.CSR_ERR_UNSUPPORTED),
-    (dict(d=32, algo=B.CSR_ENCODE_MFMA), B.CSR_ERR_UNSUPPORTED),
+    (dict(d=16, algo=B.CSR_ENCODE_MFMA), B.CSR_ERR_UNSUPPORTED),
     (dict(s_n=3), B.CSR_ERR_INVALID_ARG), (dict(s_n=16), B.CSR_ERR_INVALID_ARG), (dict(s_n=-1), B.CSR_ERR_INVALID_ARG),
     (dict(s_n=8), B.CSR_ERR_UNSUPPORTED),                              # chunks of 16 dimensions
     (dict(dict_count=-1), B.CSR_ERR_INVALID_ARG), (dict(H=6, dict_count=4), B.CSR_ERR_INVALID_ARG),
     (dict(code_stride_h=-8), B.CSR_ERR_INVALID_ARG), (dict(code_stride_h=792), B.CSR_ERR_INVALID_ARG),   # < T*s = 800
     (dict(T=200, algo=B.CSR_ENCODE_SPLIT), B.CSR_ERR_UNSUPPORTED), (dict(d=32, T=1, algo=B.CSR_ENCODE_SPLIT), B.CSR_ERR_UNSUPPORTED),
-    (dict(s_n=4, algo=B.CSR_ENCODE_MFMA), B.CSR_ERR_UNSUPPORTED),      # chunks of 32: vector-ALU encoder only
+    (dict(s_n=4, algo=B.CSR_ENCODE_RESIDENT), B.CSR_ERR_UNSUPPORTED),  # chunks of 32: matrix-core or vector-ALU encoder
     (dict(x_dtype=B.CSR_F32, dict_dtype=B.CSR_F32, algo=B.CSR_ENCODE_MFMA), B.CSR_ERR_UNSUPPORTED),
     (dict(N=512, algo=B.CSR_ENCODE_GRAM), B.CSR_ERR_UNSUPPORTED),      # the Gram matrix has to fit the LDS
     (dict(N=200, algo=B.CSR_ENCODE_GRAM), B.CSR_ERR_UNSUPPORTED), (dict(N=256, d=32, algo=B.CSR_ENCODE_GRAM), B.CSR_ERR_UNSUPPORTED),
@@ -80,7 +80,8 @@ def test_encode_chunk_count_scales_the_workspace_and_zero_means_whole_vectors():
     assert size(H=64, s_n=2) == size(H=128) and size(H=64, s_n=2) > size(H=64)   # one norm record per dictionary
     assert size(d=64) > 0 and size(d=256, s_n=2) > 0                           # fp16 chunks of 64 / 128: matrix cores
     assert size(H=64, dict_count=8) == size(H=8)                               # shared dictionaries: fewer records
-    assert lib.csr_encode_workspace_bytes(ctypes.byref(_enc(s_n=4))) == 0      # chunks of 32: the vector-ALU encoder needs none
+    assert size(s_n=4) > 0 and size(d=32) > 0                                  # ... and of 32 (s_n = 4 of a 128-dim head)
+    assert size(H=64, s_n=4) == size(H=256)
 
 
 def test_encode_kernel_choice_follows_the_vectors_per_dictionary_and_the_dictionary_size():
@@ -237,9 +238,10 @@ def test_decode_accepts_one_long_sequence_up_to_the_token_limit():
     # the rotary kernel keeps a score per round in registers: its chunks hold fewer tokens (the header states the limits)
     none = ctypes.c_size_t(-1).value
     rope = lambda **kw: lib.csr_decode_workspace_bytes(ctypes.byref(_dec(N=256, rope_base=1e4, **kw)))
-    assert rope(B=1, Hq=1, Hkv=1, T=1 << 20) == none
-    assert rope(Hq=2, Hkv=2, T=1 << 19) != none and rope(Hq=2, Hkv=2, T=(1 << 19) + 1) == none
-    assert rope(Hq=8, Hkv=2, T=1 << 18) != none and rope(Hq=8, Hkv=2, T=(1 << 18) + 1) == none
+    assert rope(B=1, Hq=1, Hkv=1, T=1 << 20) != none and rope(Hq=2, Hkv=2, T=1 << 20) != none
+    assert rope(Hq=8, Hkv=2, T=1 << 19) != none and rope(Hq=8, Hkv=2, T=(1 << 19) + 1) == none
+    # four query heads per KV head and workgroup keep 8 rounds of 1024 tokens per chunk, 128 chunks: the whole 2^20
+    assert lib.csr_decode_workspace_bytes(ctypes.byref(_dec(B=1, Hq=4, Hkv=1, T=1 << 20))) != none
 
 
 def test_decode_workspace_grows_with_the_chunk_count_and_zero_means_one_chunk():

@@ -432,6 +432,29 @@ def test_chunked_vectors_every_chunk_on_its_own_dictionary(algo, H, T, N, d, sn,
     _assert_ok(_compare_chunked(X, D, s, idx.view(np.uint16).astype(np.int32), coef))
 
 
+@pytest.mark.parametrize("H,T,N,d,sn,s", [
+    (2, 700, 1024, 128, 4, 2),     # s_n = 4 of the dictionary-size tables of Section "NeuralDict": four chunks of 32
+    (1, 300, 4096, 128, 4, 4),
+    (3, 257, 96, 128, 4, 3),       # a partial dictionary stage (96 of 256 atoms), ragged tokens
+    (2, 500, 320, 32, 1, 6),       # vectors of 32 dimensions, a stage and a quarter
+    (64, 2100, 160, 128, 4, 2),    # 8-wave workgroups with a ragged last tile
+])
+def test_mfma_chunks_of_32_dimensions(H, T, N, d, sn, s):
+    dc = d // sn
+    D = synth.dictionary(34, "dict_v", H * sn, N, dc, "f16").reshape(H, sn, N, dc)
+    X = synth.vectors(34, "values", H, T, d, "f16", outliers=2)
+    Dg = torch.from_numpy(D if sn > 1 else D[:, 0]).cuda()
+    idx, coef = csr.csr_encode(torch.from_numpy(X).cuda(), Dg, s, algo=csr.CSR_ENCODE_MFMA)
+    ia, ca = csr.csr_encode(torch.from_numpy(X).cuda(), Dg, s)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, ia) and torch.equal(coef, ca)          # what AUTO runs for these shapes
+    idx, coef = idx.cpu().numpy().reshape(H, T, sn, s), coef.cpu().numpy().reshape(H, T, sn, s)
+    heads = range(H) if H <= 3 else [0, 31, 63]
+    _assert_ok(_compare_chunked(X[list(heads)], D[list(heads)], s, idx[list(heads)].view(np.uint16).astype(np.int32),
+                                coef[list(heads)]))
+    assert int(idx.view(np.uint16).max()) < N
+
+
 @pytest.mark.parametrize("N", [32, 64, 160, 4096])
 def test_mfma_vectors_of_64_dimensions(N):
     H, T, d, s = 2, 500, 64, 6
