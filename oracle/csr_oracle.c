@@ -32,7 +32,13 @@
  *   - No division by |d|^2: atoms are taken as unit norm as Section "Sparse
  *     representation" states; the dictionary bits are used as given.
  *   - Eq.4 uses the unrounded coefficient; rounding to the storage type is the
- *     caller's business (done on the returned doubles).
+ *     caller's business (done on the returned doubles).  That is the default
+ *     ("open loop").  Section "Analysis for CSR" stores the coefficients as
+ *     fp16, and Eq.4 does not say which value it subtracts; the other reading
+ *     ("closed loop") is offered as an option: the coefficient is rounded to
+ *     its storage type first, the ROUNDED value is what is stored and what
+ *     Eq.4 subtracts, so that the residual the iterations work on is exactly
+ *     the error of the code as it is stored.
  *   - Attention scale is a parameter (the paper never writes the formula); no
  *     mask, no position embedding (Section "KV cache in attention" sets the
  *     position embedding aside).
@@ -64,6 +70,24 @@ int csr_oracle_max_threads(void)
 }
 
 /*
+ * x rounded to the nearest fp16 value (IEEE binary16: 10 fraction bits, exponents -14 .. 15, subnormals with a
+ * spacing of 2^-24, ties to even, overflow to infinity), returned as a double.  Written from the format's
+ * definition: the spacing of fp16 values around x is 2^(e - 10) with e = floor(log2 |x|), at least -14.
+ */
+static double round_to_half(double x)
+{
+    if (x == 0.0 || isnan(x) || isinf(x)) return x;
+    int e;
+    (void)frexp(fabs(x), &e);        /* |x| = f 2^e, f in [0.5, 1)  =>  floor(log2 |x|) = e - 1 */
+    int e2 = e - 1;
+    if (e2 < -14) e2 = -14;
+    const double q = ldexp(1.0, e2 - 10);
+    const double r = nearbyint(x / q) * q;   /* default rounding mode: to nearest, ties to even */
+    if (fabs(r) > 65504.0) return x > 0 ? INFINITY : -INFINITY;
+    return r;
+}
+
+/*
  * Matching Pursuit for T vectors against one dictionary.
  *   X          [T][d]   input vectors
  *   D          [N][d]   atoms (rows)
@@ -72,13 +96,16 @@ int csr_oracle_max_threads(void)
  *   best_abs   [T][s]   out (may be NULL): |C| of the picked atom
  *   second_abs [T][s]   out (may be NULL): largest |C| among all other atoms
  *   res_norm2  [T][s+1] out (may be NULL): |R_g|^2 before iteration g = 1..s, then after the last
+ *   closed_loop  0: Eq.4 subtracts the unrounded coefficient, which is also what is returned;
+ *                1 / 2: the coefficient is rounded to fp16 / fp32 first; the rounded value is returned
+ *                and subtracted (see the readings above)
  * Returns 0, or -1 on bad sizes / allocation failure.
  */
 int csr_oracle_mp_encode(const double *X, const double *D, int64_t T, int d, int N, int s,
                          int32_t *idx, double *coef, double *best_abs, double *second_abs,
-                         double *res_norm2, int nthreads)
+                         double *res_norm2, int nthreads, int closed_loop)
 {
-    if (T < 0 || d <= 0 || N <= 0 || s < 0) return -1;
+    if (T < 0 || d <= 0 || N <= 0 || s < 0 || closed_loop < 0 || closed_loop > 2) return -1;
     int fail = 0;
 #ifdef _OPENMP
     if (nthreads <= 0) nthreads = omp_get_max_threads();
@@ -131,6 +158,8 @@ int csr_oracle_mp_encode(const double *X, const double *D, int64_t T, int d, int
                     if (best_abs) best_abs[t * s + g] = babs;
                     /* Eq.2 read as the signed projection */
                     double c = C[best];
+                    if (closed_loop == 1) c = round_to_half(c);
+                    else if (closed_loop == 2) c = (double)(float)c;
                     idx[t * s + g] = best;
                     coef[t * s + g] = c;
                     /* Eq.4 */

@@ -7,7 +7,8 @@ exactly, so the oracle sees the same input bits the GPU saw.
 
 Functions and the passages they follow:
   mp_encode        Matching Pursuit, Eq.2-4, s iterations ("Sparse representation",
-                   "KV Decomposition and Sparse Storage")
+                   "KV Decomposition and Sparse Storage"); optionally with Eq.4 subtracting the coefficient as
+                   it is stored (fp16, "Analysis for CSR")
   mp_encode_chunked
                    Matching Pursuit of every chunk of a vector on that chunk's dictionary (the s_n of
                    Section "NeuralDict": a head vector of d_h values is cut into s_n pieces of
@@ -40,7 +41,7 @@ def _load():
         i64, i32, p = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
         lib.csr_oracle_max_threads.restype = ctypes.c_int
         lib.csr_oracle_mp_encode.restype = ctypes.c_int
-        lib.csr_oracle_mp_encode.argtypes = [p, p, i64, i32, i32, i32, p, p, p, p, p, i32]
+        lib.csr_oracle_mp_encode.argtypes = [p, p, i64, i32, i32, i32, p, p, p, p, p, i32, i32]
         lib.csr_oracle_reconstruct.restype = ctypes.c_int
         lib.csr_oracle_reconstruct.argtypes = [p, p, p, i64, i32, i32, i32, p]
         lib.csr_oracle_decode_attn.restype = ctypes.c_int
@@ -69,13 +70,16 @@ def _ptr(a):
     return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
 
 
-def mp_encode(X, D, s, nthreads=0, diagnostics=False):
+def mp_encode(X, D, s, nthreads=0, diagnostics=False, closed_loop=None):
     """Matching Pursuit of X[T, d] against atoms D[N, d] for s iterations.
 
     Returns (idx int32 [T, s], coef float64 [T, s]) and, with diagnostics=True, a
     third dict with best_abs / second_abs [T, s] (|correlation| of the picked atom
     and of the runner-up) and res_norm2 [T, s+1] (squared residual norms).
+    closed_loop: None - Eq.4 subtracts the unrounded coefficient (the default reading); "f16" / "f32" - the
+    coefficient is rounded to that storage type first, and the rounded value is both returned and subtracted.
     """
+    cl = {None: 0, "f16": 1, "f32": 2}[closed_loop]
     X, D = _f64(X), _f64(D)
     assert X.ndim == 2 and D.ndim == 2 and X.shape[1] == D.shape[1]
     T, d = X.shape
@@ -88,7 +92,7 @@ def mp_encode(X, D, s, nthreads=0, diagnostics=False):
         second = np.zeros((T, s))
         rn = np.zeros((T, s + 1))
     rc = _load().csr_oracle_mp_encode(_ptr(X), _ptr(D), T, d, N, s, _ptr(idx), _ptr(coef),
-                                      _ptr(best), _ptr(second), _ptr(rn), nthreads)
+                                      _ptr(best), _ptr(second), _ptr(rn), nthreads, cl)
     if rc != 0:
         raise RuntimeError(f"csr_oracle_mp_encode failed: {rc}")
     if diagnostics:

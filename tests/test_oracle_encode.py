@@ -295,3 +295,76 @@ def test_chunked_energy_identity_per_chunk_and_error_of_the_concatenation():
         Xc = X[:, c * dc:(c + 1) * dc]
         errc = ((Xc - rec[:, c * dc:(c + 1) * dc]) ** 2).sum(axis=1)
         assert np.allclose(errc, (Xc ** 2).sum(axis=1) - (coef[:, c] ** 2).sum(axis=1), rtol=1e-10, atol=1e-12)
+
+
+# --- Eq.4 with the coefficient as it is stored ("closed loop": Section "Analysis for CSR" stores fp16) -------------
+
+def test_closed_loop_on_the_identity_dictionary_has_a_closed_form():
+    # Orthonormal atoms: the residual's coordinates are independent.  x = (1000.3, 0.1, 0, ...): fp16 values near
+    # 1000 are 0.5 apart, so the stored first coefficient is 1000.5 and leaves -0.2 on coordinate 0 - more than the
+    # 0.1 on coordinate 1.  Closed loop therefore picks atom 0 AGAIN (coefficient fp16(-0.2) = -0.199951171875),
+    # then atom 1 (fp16(0.1) = 0.0999755859375); open loop picks atom 1 second and then has nothing left.
+    d = 8
+    D = np.eye(d)
+    x = np.zeros((1, d)); x[0, 0] = 1000.3; x[0, 1] = 0.1
+    io, co = oracle.mp_encode(x, D, 3)
+    assert io[0].tolist() == [0, 1, 0] and co[0, 0] == pytest.approx(1000.3) and co[0, 1] == pytest.approx(0.1)
+    assert abs(co[0, 2]) < 1e-12
+    ic, cc = oracle.mp_encode(x, D, 3, closed_loop="f16")
+    assert ic[0].tolist() == [0, 0, 1]
+    assert cc[0].tolist() == [1000.5, -0.199951171875, 0.0999755859375]
+    # fp32 storage: 1000.3 is not an fp32 value either, but the remainder (3e-5) stays below 0.1
+    i32, c32 = oracle.mp_encode(x, D, 3, closed_loop="f32")
+    assert i32[0].tolist() == [0, 1, 0] and c32[0, 0] == float(np.float32(1000.3)) and c32[0, 1] == float(np.float32(0.1))
+    assert c32[0, 2] == float(np.float32(1000.3 - float(np.float32(1000.3))))
+
+
+@pytest.mark.parametrize("storage,np_t", [("f16", np.float16), ("f32", np.float32)])
+def test_closed_loop_residual_is_the_error_of_the_stored_code(storage, np_t):
+    # What closed loop is for: x - sum_g c_g d_{i_g}, with the coefficients exactly as returned (= as stored), equals
+    # the residual the iterations worked on; every returned coefficient is a value of the storage type; and each
+    # step is still the greedy pick (largest |R . d_n|) on that residual.  Open loop with rounding applied
+    # afterwards does not have the first property.
+    rng = np.random.default_rng(5)
+    N, d, s, T = 48, 12, 5, 30
+    D = _unit_rows(rng, N, d)
+    X = rng.standard_normal((T, d)) * 37.0
+    idx, coef, diag = oracle.mp_encode(X, D, s, diagnostics=True, closed_loop=storage)
+    assert np.array_equal(coef, coef.astype(np_t).astype(np.float64))
+    R = X.copy()
+    for g in range(s):
+        C = R @ D.T
+        n = np.argmax(np.abs(C), axis=1)
+        assert np.array_equal(n, idx[:, g])
+        c = C[np.arange(T), n]
+        assert np.array_equal(coef[:, g], c.astype(np_t).astype(np.float64))       # the projection, rounded
+        assert np.allclose((R ** 2).sum(axis=1), diag["res_norm2"][:, g], rtol=1e-12)
+        R = R - coef[:, g:g + 1] * D[n]
+    assert np.allclose((R ** 2).sum(axis=1), diag["res_norm2"][:, s], rtol=1e-12)
+    io, co = oracle.mp_encode(X, D, s)
+    stored_open = co.astype(np_t).astype(np.float64)
+    R_open = X - np.einsum("tg,tgk->tk", stored_open, D[io])
+    if storage == "f16":   # rounding after the fact leaves an error the open-loop residual does not know about
+        _, _, dopen = oracle.mp_encode(X, D, s, diagnostics=True)
+        assert np.abs((R_open ** 2).sum(axis=1) - dopen["res_norm2"][:, s]).max() > 1e-6
+
+
+def test_closed_loop_equals_open_loop_when_every_coefficient_is_a_storage_value():
+    # identity dictionary and fp16 inputs: every coefficient is a coordinate of x, already an fp16 value
+    rng = np.random.default_rng(6)
+    X = rng.standard_normal((50, 16)).astype(np.float16).astype(np.float64)
+    D = np.eye(16)
+    io, co = oracle.mp_encode(X, D, 6)
+    ic, cc = oracle.mp_encode(X, D, 6, closed_loop="f16")
+    assert np.array_equal(io, ic) and np.array_equal(co, cc)
+
+
+def test_fp16_rounding_of_the_oracle_matches_the_formats_definition():
+    # round_to_half is only reachable through closed loop: one atom, one step, c = x . d = x
+    vals = np.array([1.0, 1.00048828125, 1.000732421875, 2049.0, 2051.0, 65519.0, 65520.0, 6.1e-5, 5.9e-8, 2.9e-8, 3.1e-8,
+                     -0.1, 1e-9, 0.333333333])
+    _, c = oracle.mp_encode(vals[:, None], np.ones((1, 1)), 1, closed_loop="f16")
+    with np.errstate(over="ignore"):
+        want = vals.astype(np.float16).astype(np.float64)          # numpy's own binary16 conversion (ties to even)
+    assert np.array_equal(c[:, 0], want)
+    assert want[1] == 1.0 and want[3] == 2048.0 and want[4] == 2052.0 and np.isinf(want[6]) and want[5] == 65504.0
