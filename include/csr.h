@@ -73,6 +73,13 @@ typedef enum {
                             the shape fits                                                               */
 } csr_encode_algo;
 
+/* csr_encode_desc.flags.  CLOSED_LOOP: Eq.4 subtracts the coefficient AS IT IS STORED - c_g is rounded to coef_dtype
+ * first (Section "Analysis for CSR" stores fp16), so the residual the later iterations work on is exactly the error
+ * of the stored code, and res_norm2 is the squared error of the stored code.  The default (flag clear) subtracts the
+ * unrounded c_g and rounds on store only; with fp32 coefficients the two coincide.  Taken by the VALU, MFMA, SPLIT
+ * and RESIDENT encoders (the Gram forms return CSR_ERR_UNSUPPORTED, and AUTO does not choose them with the flag). */
+#define CSR_FLAG_CLOSED_LOOP 1u
+
 /*
  * Matching Pursuit encode (Eq.2-4), H independent dictionaries with T vectors each.
  * For every vector x: R_1 = x; for g = 1..s: i_g = argmax_n |R_g . d_n| (lowest n on ties),
@@ -105,7 +112,7 @@ typedef struct {
                            (Section "KV Decomposition and Sparse Storage": a generated token is
                            encoded like the prompt's)                                       */
     int32_t algo;       /* csr_encode_algo                                                  */
-    uint32_t flags;     /* must be 0                                                        */
+    uint32_t flags;     /* 0 or CSR_FLAG_CLOSED_LOOP                                        */
     float *res_norm2;   /* optional device pointer, [H][T][s_n] fp32, or NULL: receives |R_{s+1}|^2, the
                            squared norm of what the s pairs leave of each vector (chunk) - by Eq.4 the
                            squared reconstruction error |x - D r|^2 with unrounded coefficients, i.e. the

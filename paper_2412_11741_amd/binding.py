@@ -16,6 +16,7 @@ CSR_OK, CSR_ERR_INVALID_ARG, CSR_ERR_UNSUPPORTED, CSR_ERR_WORKSPACE, CSR_ERR_DEV
 CSR_F32, CSR_F16 = 0, 1
 CSR_I32, CSR_I16 = 0, 1
 CSR_ENCODE_AUTO, CSR_ENCODE_VALU, CSR_ENCODE_MFMA, CSR_ENCODE_SPLIT, CSR_ENCODE_RESIDENT, CSR_ENCODE_GRAM = 0, 1, 2, 3, 4, 5
+CSR_FLAG_CLOSED_LOOP = 1
 
 EXPORTS = ("csr_version", "csr_last_error", "csr_code_bytes", "csr_encode_workspace_bytes",
            "csr_encode", "csr_decode_workspace_bytes", "csr_decode_attn", "csr_reconstruct", "csr_atom_norms2",
@@ -128,7 +129,7 @@ def csr_code_bytes(s, s_n=1, idx_dtype=torch.int16, coef_dtype=torch.float16):
     return int(lib().csr_code_bytes(s, s_n, _IT[idx_dtype], _DT[coef_dtype]))
 
 
-def encode_desc(X, D, s, coef_dtype, idx_dtype, algo=CSR_ENCODE_AUTO, code_stride_h=0):
+def encode_desc(X, D, s, coef_dtype, idx_dtype, algo=CSR_ENCODE_AUTO, code_stride_h=0, flags=0):
     """Descriptor from tensor shapes.  D may hold fewer dictionaries than X has blocks (D.shape[0] divides
     X.shape[0]): block h then uses dictionary h % D.shape[0]."""
     H, T, d = X.shape
@@ -138,7 +139,7 @@ def encode_desc(X, D, s, coef_dtype, idx_dtype, algo=CSR_ENCODE_AUTO, code_strid
                       coef_dtype=_DT[coef_dtype], idx_dtype=_IT[idx_dtype],
                       x_stride_h=X.stride(0) if H > 1 and T > 0 else 0,
                       x_stride_t=X.stride(1) if T > 1 else 0, dict_count=D.shape[0] if D.shape[0] != H else 0,
-                      code_stride_h=code_stride_h, algo=algo, flags=0)
+                      code_stride_h=code_stride_h, algo=algo, flags=flags)
 
 
 def csr_encode_workspace_bytes(desc):
@@ -168,7 +169,7 @@ def csr_gram_build(D, out=None):
 
 
 def csr_encode(X, D, s, coef_dtype=None, idx_dtype=None, algo=CSR_ENCODE_AUTO, idx=None, coef=None,
-               workspace=None, res_norm2=None, gram=None):
+               workspace=None, res_norm2=None, gram=None, closed_loop=False):
     """Matching Pursuit encode.  X [H, T, d], D [H, N, d] on the GPU -> (idx, coef) [H, T, s].
     Chunked: D [H, s_n, N, d / s_n] -> (idx, coef) [H, T, s_n, s], every chunk encoded on its own dictionary.
     D may hold H' < H dictionaries (H' divides H): block h uses dictionary h % H' (blocks ordered sequence-major,
@@ -176,7 +177,8 @@ def csr_encode(X, D, s, coef_dtype=None, idx_dtype=None, algo=CSR_ENCODE_AUTO, i
     than one block's codes, the rest contiguous): the codes are then written in place, e.g. appended at a token
     position.  `res_norm2` (fp32, [H, T] or [H, T, s_n], contiguous) receives the squared norm of each vector's
     final residual, i.e. its squared reconstruction error.  `gram` (csr_gram_build(D)) lets a few vectors per
-    dictionary - one decoding step's - be encoded with one sweep of each dictionary instead of s."""
+    dictionary - one decoding step's - be encoded with one sweep of each dictionary instead of s.
+    closed_loop: CSR_FLAG_CLOSED_LOOP - Eq.4 subtracts the coefficient as it is stored (rounded to coef_dtype)."""
     _dev(X, "X"); _dev(D, "D")
     if X.dim() != 3 or D.dim() not in (3, 4) or D.shape[0] < 1 or X.shape[0] % D.shape[0] != 0 or \
             D.shape[-1] * (D.shape[1] if D.dim() == 4 else 1) != X.shape[2]:
@@ -199,7 +201,7 @@ def csr_encode(X, D, s, coef_dtype=None, idx_dtype=None, algo=CSR_ENCODE_AUTO, i
         if idx.stride(0) != coef.stride(0):
             raise ValueError("idx and coef must have the same distance between blocks")
         code_stride_h = idx.stride(0)
-    desc = encode_desc(X, D, s, coef_dtype, idx_dtype, algo, code_stride_h)
+    desc = encode_desc(X, D, s, coef_dtype, idx_dtype, algo, code_stride_h, CSR_FLAG_CLOSED_LOOP if closed_loop else 0)
     if res_norm2 is not None:
         _dev(res_norm2, "res_norm2")
         want = (H, T) if D.dim() == 3 else (H, T, D.shape[1])

@@ -40,7 +40,8 @@ csr_status check_encode_desc(const csr_encode_desc *d, csr::EncodeArgs *args, in
 {
     if (!d) return fail(CSR_ERR_INVALID_ARG, "csr_encode: descriptor is NULL");
     if (d->H < 0 || d->T < 0) return fail(CSR_ERR_INVALID_ARG, "csr_encode: H=%d T=%lld must be >= 0", d->H, (long long)d->T);
-    if (d->flags != 0) return fail(CSR_ERR_INVALID_ARG, "csr_encode: flags must be 0");
+    if ((d->flags & ~CSR_FLAG_CLOSED_LOOP) != 0) return fail(CSR_ERR_INVALID_ARG, "csr_encode: unknown flags 0x%x", d->flags);
+    const bool closed = (d->flags & CSR_FLAG_CLOSED_LOOP) != 0;
     if (!valid_dtype(d->x_dtype) || !valid_dtype(d->dict_dtype) || !valid_dtype(d->coef_dtype) || !valid_itype(d->idx_dtype))
         return fail(CSR_ERR_INVALID_ARG, "csr_encode: unknown dtype / index type");
     if (d->algo != CSR_ENCODE_AUTO && d->algo != CSR_ENCODE_VALU && d->algo != CSR_ENCODE_MFMA && d->algo != CSR_ENCODE_SPLIT &&
@@ -99,7 +100,10 @@ csr_status check_encode_desc(const csr_encode_desc *d, csr::EncodeArgs *args, in
         return fail(CSR_ERR_UNSUPPORTED, "csr_encode: the LDS-resident encoder needs fp16 inputs, chunks of 64 or 128 dimensions, N a multiple "
                     "of 32 and a dictionary of at most 128 KB (got d/s_n=%d N=%d %s)", dc, d->N, a.f16 ? "f16" : "f32");
     a.gram = d->gram;
-    const bool step_ok = d->gram != nullptr && csr::encode_gramstep_supported(a);
+    a.closed_loop = closed;
+    if (closed && d->algo == CSR_ENCODE_GRAM)
+        return fail(CSR_ERR_UNSUPPORTED, "csr_encode: the Gram encoders do not take CSR_FLAG_CLOSED_LOOP");
+    const bool step_ok = !closed && d->gram != nullptr && csr::encode_gramstep_supported(a);
     if (d->algo == CSR_ENCODE_GRAM && d->gram && !step_ok)
         return fail(CSR_ERR_UNSUPPORTED, "csr_encode: the Gram encoder with prepared Gram matrices needs fp16 inputs, chunks of 64 or 128 "
                     "dimensions, N a multiple of 32, at most 16384, and at most 128 vectors per dictionary (got d/s_n=%d N=%d %s, %lld "

@@ -13,6 +13,12 @@ namespace csr {
 
 constexpr int kWave = 64;  // CDNA wavefront width
 
+// How the encoder kernels are told about the coefficients: bit 0 - stored as fp16 (else fp32); bit 1 - closed loop:
+// Eq.4 subtracts the coefficient as it is stored.  Only fp16 storage rounds (the kernels' own coefficient is fp32).
+constexpr int32_t kCoefF16 = 1, kCoefClosed = 2;
+__host__ __device__ inline bool coef_is_f16(int32_t mode) { return (mode & kCoefF16) != 0; }
+__host__ __device__ inline bool coef_rounds_in_loop(int32_t mode) { return (mode & (kCoefF16 | kCoefClosed)) == (kCoefF16 | kCoefClosed); }
+
 // ---- encode ---------------------------------------------------------------------------------
 struct EncodeArgs {
     const void *X;
@@ -28,6 +34,7 @@ struct EncodeArgs {
     int64_t code_stride_h;           // elements between blocks' codes (already defaulted)
     bool f16;                        // X and D are fp16 (else fp32)
     bool coef16, idx16;
+    bool closed_loop;                // Eq.4 subtracts the coefficient as it is stored (CSR_FLAG_CLOSED_LOOP)
     float *res_norm2;                // optional [H][T][sn] output, or nullptr
     const void *gram;                // optional Gram matrices [dict_count * sn][N][N] fp16 (csr_gram_build), or nullptr
     void *workspace;

@@ -286,7 +286,7 @@ __global__ __launch_bounds__(64 * W, 8 / W) void encode_mfma_kernel(
     const __half *__restrict__ X, const __half *__restrict__ Dict, void *__restrict__ idx_out,
     void *__restrict__ coef_out, const float *__restrict__ dnorm, int64_t T, int64_t M, int32_t N, int32_t s, int32_t sn,
     int64_t x_stride_h, int64_t x_stride_t, int32_t dict_count, int64_t code_stride_h, int32_t tiles_per_h,
-    int32_t n_groups, int32_t idx16, int32_t coef16, uint32_t code_mask, int32_t first_round,
+    int32_t n_groups, int32_t idx16, int32_t coef_mode, uint32_t code_mask, int32_t first_round,
     float *__restrict__ res_norm2)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
@@ -571,6 +571,8 @@ __global__ __launch_bounds__(64 * W, 8 / W) void encode_mfma_kernel(
             float best_c = (s0 + s1) + (l0 + l1);
             best_c += xchg32f(best_c, hf);
             if (!(rn2[bi] > 0.0f)) best_c = 0.0f;
+            // closed loop: what Eq.4 subtracts is the coefficient as it will be stored (rounded in the input's scale)
+            if (coef_rounds_in_loop(coef_mode)) best_c = ldexpf(__half2float(__float2half_rn(ldexpf(best_c, -sexp[bi]))), sexp[bi]);
             float v[kFrags][8];
             float r2 = 0.0f;
 #pragma unroll
@@ -629,7 +631,7 @@ __global__ __launch_bounds__(64 * W, 8 / W) void encode_mfma_kernel(
                     else reinterpret_cast<int32_t *>(idx_out)[o] = best_n[bi];
                 } else {
                     const float c_out = ldexpf(best_c, -sexp_used);
-                    if (coef16) reinterpret_cast<__half *>(coef_out)[o] = __float2half_rn(c_out);
+                    if (coef_is_f16(coef_mode)) reinterpret_cast<__half *>(coef_out)[o] = __float2half_rn(c_out);
                     else reinterpret_cast<float *>(coef_out)[o] = c_out;
                 }
             }
@@ -693,7 +695,8 @@ hipError_t launch_encode_mfma_w(const EncodeArgs &a, int cus)
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((encode_mfma_kernel<DC, W>), dim3((unsigned)groups), dim3(64 * W), lds_bytes<W>(), a.stream,
                        (const __half *)a.X, (const __half *)a.D, a.idx, a.coef, dnorm, a.T, M, a.N, a.s, a.sn, a.x_stride_h,
-                       a.x_stride_t, a.dict_count, a.code_stride_h, (int32_t)tiles, (int32_t)groups, (int32_t)a.idx16, (int32_t)a.coef16, code_mask,
+                       a.x_stride_t, a.dict_count, a.code_stride_h, (int32_t)tiles, (int32_t)groups, (int32_t)a.idx16,
+                       (a.coef16 ? kCoefF16 : 0) | (a.closed_loop ? kCoefClosed : 0), code_mask,
                        first_round, a.res_norm2);
     return hipGetLastError();
 }

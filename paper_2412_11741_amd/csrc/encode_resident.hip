@@ -156,7 +156,7 @@ template <int DC, int OCC>
 __global__ __launch_bounds__(kThreads, OCC) void encode_resident_kernel(
     const __half *__restrict__ X, const __half *__restrict__ Dict, void *__restrict__ idx_out,
     void *__restrict__ coef_out, int64_t T, int64_t M, int32_t N, int32_t s, int32_t sn, int64_t x_stride_h, int64_t x_stride_t,
-    int32_t dict_count, int64_t code_stride_h, int32_t tiles_per_h, int32_t idx16, int32_t coef16, uint32_t code_mask,
+    int32_t dict_count, int64_t code_stride_h, int32_t tiles_per_h, int32_t idx16, int32_t coef_mode, uint32_t code_mask,
     float *__restrict__ res_norm2)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
@@ -390,6 +390,8 @@ __global__ __launch_bounds__(kThreads, OCC) void encode_resident_kernel(
             float best_c = (c0 + c1) + (c2 + c3);
             best_c += xchg32f(best_c, hf);
             if (!(rn2 > 0.0f)) best_c = 0.0f;
+            // closed loop: what Eq.4 subtracts is the coefficient as it will be stored (rounded in the input's scale)
+            if (coef_rounds_in_loop(coef_mode)) best_c = ldexpf(__half2float(__float2half_rn(ldexpf(best_c, -sexp))), sexp);
             float r2 = 0.0f;
 #pragma unroll
             for (int j = 0; j < kFrags; ++j) {
@@ -437,7 +439,7 @@ __global__ __launch_bounds__(kThreads, OCC) void encode_resident_kernel(
                     else reinterpret_cast<int32_t *>(idx_out)[o] = best_n;
                 } else {
                     const float c_out = ldexpf(best_c, -sexp_used);
-                    if (coef16) reinterpret_cast<__half *>(coef_out)[o] = __float2half_rn(c_out);
+                    if (coef_is_f16(coef_mode)) reinterpret_cast<__half *>(coef_out)[o] = __float2half_rn(c_out);
                     else reinterpret_cast<float *>(coef_out)[o] = c_out;
                 }
             }
@@ -480,8 +482,8 @@ static hipError_t launch_resident_t(const EncodeArgs &a)
     }
     hipLaunchKernelGGL((encode_resident_kernel<DC, OCC>), dim3((unsigned)groups), dim3(kThreads), lds_bytes, a.stream,
                        (const __half *)a.X, (const __half *)a.D, a.idx, a.coef, a.T, M, a.N, a.s, a.sn, a.x_stride_h,
-                       a.x_stride_t, a.dict_count, a.code_stride_h, (int32_t)tiles, (int32_t)a.idx16, (int32_t)a.coef16,
-                       code_mask, a.res_norm2);
+                       a.x_stride_t, a.dict_count, a.code_stride_h, (int32_t)tiles, (int32_t)a.idx16,
+                       (a.coef16 ? kCoefF16 : 0) | (a.closed_loop ? kCoefClosed : 0), code_mask, a.res_norm2);
     return hipGetLastError();
 }
 

@@ -72,7 +72,7 @@ struct SplitParams {
     int64_t V;         // vectors in all
     int64_t T;
     int64_t x_stride_h, x_stride_t, code_stride_h;
-    int32_t N, s, sn, dict_count, M, k, g, idx16, coef16;
+    int32_t N, s, sn, dict_count, M, k, g, idx16, coef16;   // coef16: kCoefF16 | kCoefClosed
     float *res_norm2;  // optional [H][T][sn]
 };
 
@@ -155,6 +155,8 @@ __global__ __launch_bounds__(kThreads, 2) void encode_split_kernel(const SplitPa
             const float *Rp = p.Rbuf + ((int64_t)prev * p.V + vid) * DC + hf * (DC / 2);
             const __half *row = Dh + (int64_t)bi * DC + hf * (DC / 2);
             const int sexp_prev = p.sexp[(int64_t)prev * p.V + vid];
+            // closed loop: what Eq.4 subtracts is the coefficient as it will be stored (rounded in the input's scale)
+            if (coef_rounds_in_loop(p.coef16)) bc = ldexpf(__half2float(__float2half_rn(ldexpf(bc, -sexp_prev))), sexp_prev);
 #pragma unroll
             for (int j = 0; j < kFrags; ++j) {
                 const float4 r0 = *reinterpret_cast<const float4 *>(Rp + 8 * j);
@@ -173,7 +175,7 @@ __global__ __launch_bounds__(kThreads, 2) void encode_split_kernel(const SplitPa
                     else reinterpret_cast<int32_t *>(p.idx_out)[o] = bi;
                 } else {
                     const float c_out = ldexpf(bc, -sexp_prev);
-                    if (p.coef16) reinterpret_cast<__half *>(p.coef_out)[o] = __float2half_rn(c_out);
+                    if (coef_is_f16(p.coef16)) reinterpret_cast<__half *>(p.coef_out)[o] = __float2half_rn(c_out);
                     else reinterpret_cast<float *>(p.coef_out)[o] = c_out;
                 }
             }
@@ -319,7 +321,7 @@ hipError_t launch_encode_split(const EncodeArgs &a)
     p.cand = reinterpret_cast<float4 *>(ws + pl.off_cand);
     p.V = pl.V; p.T = a.T; p.x_stride_h = a.x_stride_h; p.x_stride_t = a.x_stride_t; p.code_stride_h = a.code_stride_h;
     p.N = a.N; p.s = a.s; p.sn = a.sn; p.dict_count = a.dict_count; p.M = pl.M; p.k = pl.k;
-    p.idx16 = a.idx16; p.coef16 = a.coef16; p.res_norm2 = a.res_norm2;
+    p.idx16 = a.idx16; p.coef16 = (a.coef16 ? kCoefF16 : 0) | (a.closed_loop ? kCoefClosed : 0); p.res_norm2 = a.res_norm2;
     const dim3 grid((unsigned)pl.k, (unsigned)(a.dict_count * a.sn));
     for (int g = 0; g <= a.s; ++g) {
         p.g = g;

@@ -29,7 +29,7 @@ __global__ __launch_bounds__(64 * W) void encode_valu_kernel(
     const TE *__restrict__ X, const TE *__restrict__ Dict, void *__restrict__ idx_out,
     void *__restrict__ coef_out, int64_t T, int64_t M, int32_t N, int32_t s, int64_t x_stride_h,
     int64_t x_stride_t, int32_t tiles_per_h, int32_t sn, int32_t dict_count, int64_t code_stride_h, int32_t idx16,
-    int32_t coef16, float *__restrict__ res_norm2)
+    int32_t coef_mode, float *__restrict__ res_norm2)
 {
     __shared__ float s_abs[2][W][64];
     __shared__ float s_c[2][W][64];
@@ -95,7 +95,9 @@ __global__ __launch_bounds__(64 * W) void encode_valu_kernel(
             const float a = s_abs[buf][w][lane];
             if (a > wb) { wb = a; wc = s_c[buf][w][lane]; wi = s_i[buf][w][lane]; }
         }
-        // Eq.4 with the unrounded coefficient; per-lane gather of the chosen atom.
+        // Eq.4 with the unrounded coefficient (or, closed loop, with the coefficient as it is stored); per-lane
+        // gather of the chosen atom.
+        if (coef_rounds_in_loop(coef_mode)) wc = __half2float(__float2half_rn(wc));
         {
             const TE *row = Dh + (int64_t)wi * D_;
 #pragma unroll
@@ -109,7 +111,7 @@ __global__ __launch_bounds__(64 * W) void encode_valu_kernel(
             const int64_t o = (int64_t)h * code_stride_h + (t * sn + ch) * s + g;
             if (idx16) reinterpret_cast<uint16_t *>(idx_out)[o] = (uint16_t)wi;
             else reinterpret_cast<int32_t *>(idx_out)[o] = wi;
-            if (coef16) reinterpret_cast<__half *>(coef_out)[o] = __float2half_rn(wc);
+            if (coef_is_f16(coef_mode)) reinterpret_cast<__half *>(coef_out)[o] = __float2half_rn(wc);
             else reinterpret_cast<float *>(coef_out)[o] = wc;
         }
         // The LDS buffers alternate, so one barrier per iteration is enough: a wave can only
@@ -136,7 +138,7 @@ hipError_t launch_valu_t(const EncodeArgs &a)
     hipLaunchKernelGGL((encode_valu_kernel<D_, TE, W>), grid, dim3(64 * W), 0, a.stream,         \
                        (const TE *)a.X, (const TE *)a.D, a.idx, a.coef, a.T, M, a.N, a.s,       \
                        a.x_stride_h, a.x_stride_t, (int32_t)tiles, a.sn, a.dict_count, a.code_stride_h, \
-                       (int32_t)a.idx16, (int32_t)a.coef16, a.res_norm2)
+                       (int32_t)a.idx16, (a.coef16 ? kCoefF16 : 0) | (a.closed_loop ? kCoefClosed : 0), a.res_norm2)
     // (8 waves = 2 per SIMD leaves each lane the 128+ registers its residual needs.)
     if (groups >= 1024) CSR_LAUNCH_VALU(4);
     else CSR_LAUNCH_VALU(8);

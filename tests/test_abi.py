@@ -48,7 +48,8 @@ def _enc(**kw):
     (dict(s=0), B.CSR_ERR_INVALID_ARG), (dict(s=33), B.CSR_ERR_INVALID_ARG),
     (dict(N=0), B.CSR_ERR_INVALID_ARG), (dict(N=70000), B.CSR_ERR_INVALID_ARG),
     (dict(x_dtype=7), B.CSR_ERR_INVALID_ARG), (dict(idx_dtype=3), B.CSR_ERR_INVALID_ARG),
-    (dict(flags=1), B.CSR_ERR_INVALID_ARG), (dict(algo=9), B.CSR_ERR_INVALID_ARG),
+    (dict(flags=2), B.CSR_ERR_INVALID_ARG), (dict(flags=5), B.CSR_ERR_INVALID_ARG), (dict(algo=9), B.CSR_ERR_INVALID_ARG),
+    (dict(flags=1, N=256, algo=B.CSR_ENCODE_GRAM), B.CSR_ERR_UNSUPPORTED),
     (dict(x_stride_t=100), B.CSR_ERR_INVALID_ARG), (dict(x_stride_t=132), B.CSR_ERR_INVALID_ARG),
     (dict(x_stride_t=256, x_stride_h=128), B.CSR_ERR_INVALID_ARG),
     (dict(d=100), B.CSR_ERR_UNSUPPORTED), (dict(dict_dtype=B.CSR_F32), B.CSR_ERR_UNSUPPORTED),

@@ -692,3 +692,78 @@ def test_mfma_eight_wave_workgroups_with_a_ragged_last_tile():
     iv, cv = _gpu_encode(X, D, s, csr.CSR_ENCODE_VALU)
     same = (idx == iv).all(axis=-1).mean()
     assert same > 0.995, same          # all vectors, against the other encoder: they may part at ties only
+
+
+# --- Eq.4 with the stored coefficient (CSR_FLAG_CLOSED_LOOP; Section "Analysis for CSR" stores fp16) -------------
+
+def _compare_closed(X, D, s, idx_g, coef_g):
+    reports = []
+    for h in range(X.shape[0]):
+        idx_o, coef_o, diag = oracle.mp_encode(X[h], D[h], s, diagnostics=True, closed_loop="f16")
+        reports.append(parity.check_encode(X[h], D[h], idx_g[h], coef_g[h], idx_o, coef_o, diag, TOL, coef_storage="f16"))
+    return reports
+
+
+@pytest.mark.parametrize("algo", ["valu", "mfma", "split", "resident"])
+def test_closed_loop_matches_the_oracles_closed_loop(algo):
+    H, T, N, d, s = 2, 300 if algo != "split" else 100, 512, 128, 8
+    D = synth.dictionary(101, "dict_k", H, N, d, "f16")
+    X = synth.vectors(101, "keys", H, T, d, "f16", outliers=8)
+    Xg, Dg = torch.from_numpy(X).cuda(), torch.from_numpy(D).cuda()
+    rn = torch.empty(H, T, dtype=torch.float32, device="cuda")
+    idx, coef = csr.csr_encode(Xg, Dg, s, algo=ALGOS[algo], closed_loop=True, res_norm2=rn)
+    io, co = csr.csr_encode(Xg, Dg, s, algo=ALGOS[algo])
+    torch.cuda.synchronize()
+    idx, coef = idx.cpu().numpy(), coef.cpu().numpy()
+    reports = _compare_closed(X, D, s, idx, coef)
+    for rep in reports:
+        assert rep.ok, rep.summary() + "\n" + "\n".join(rep.failures)
+    print(f"[encode parity] closed loop ({algo}): " + reports[0].summary())
+    # the two readings do part: later coefficients (and, now and then, atoms) change once the rounding of an early
+    # coefficient stays in the residual
+    assert (idx != io.cpu().numpy()).any() or (coef != co.cpu().numpy()).any()
+    # and the reported residual norm is the error of the code AS STORED
+    for h in range(H):
+        err = ((X[h].astype(np.float64) - oracle.reconstruct(idx[h], coef[h], D[h])) ** 2).sum(axis=1)
+        x2 = (X[h].astype(np.float64) ** 2).sum(axis=1)
+        assert np.all(np.abs(rn[h].cpu().numpy() - err) <= 1e-4 * err + 1e-6 * x2)
+
+
+@pytest.mark.parametrize("algo", ["valu", "mfma", "split", "resident"])
+def test_closed_loop_third_pick_differs_from_the_open_loop_on_a_nearly_orthonormal_dictionary(algo):
+    # identity atoms, the first turned by a small angle so that the first projection (1000 cos a + 0.1 sin a) is not
+    # an fp16 value: the stored 1000.0 leaves +0.002 of the first atom in the closed-loop residual, which changes
+    # the third pick (atom 1 with +0.00195 instead of atom 0 with -0.002: what the oracle's two readings give)
+    d = 128
+    D2 = np.eye(d, dtype=np.float16)[None].copy()
+    a = 0.02
+    D2[0, 0, 0], D2[0, 0, 1] = np.float16(np.cos(a)), np.float16(np.sin(a))
+    X = np.zeros((1, 40, d), dtype=np.float16)
+    X[0, :, 0] = np.float16(1000.0)
+    X[0, :, 1] = np.float16(0.1)
+    idx, coef = _gpu_encode_closed(X, D2, 3, ALGOS[algo])
+    io, co, diag = oracle.mp_encode(X[0], D2[0], 3, diagnostics=True, closed_loop="f16")
+    rep = parity.check_encode(X[0], D2[0], idx[0], coef[0], io, co, diag, TOL, coef_storage="f16")
+    assert rep.ok, rep.summary() + "\n" + "\n".join(rep.failures)
+    assert io[0].tolist() == [0, 1, 1] and np.array_equal(idx[0].view(np.uint16).astype(np.int64), io)
+    assert oracle.mp_encode(X[0], D2[0], 3)[0][0].tolist() == [0, 1, 0]
+
+
+def _gpu_encode_closed(X, D, s, algo):
+    idx, coef = csr.csr_encode(torch.from_numpy(X).cuda(), torch.from_numpy(D).cuda(), s, algo=algo, closed_loop=True)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), coef.cpu().numpy()
+
+
+def test_closed_loop_with_fp32_coefficients_is_the_open_loop():
+    H, T, N, d, s = 2, 200, 512, 128, 6
+    D = synth.dictionary(102, "dict_k", H, N, d, "f16")
+    X = synth.vectors(102, "keys", H, T, d, "f16", outliers=8)
+    Xg, Dg = torch.from_numpy(X).cuda(), torch.from_numpy(D).cuda()
+    for algo in (csr.CSR_ENCODE_MFMA, csr.CSR_ENCODE_VALU):
+        a = csr.csr_encode(Xg, Dg, s, algo=algo, coef_dtype=torch.float32, closed_loop=True)
+        b = csr.csr_encode(Xg, Dg, s, algo=algo, coef_dtype=torch.float32)
+        torch.cuda.synchronize()
+        assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+    with pytest.raises(csr.CsrError, match="CLOSED_LOOP"):
+        csr.csr_encode(Xg[:, :4], Dg[:, :256], s, algo=csr.CSR_ENCODE_GRAM, closed_loop=True)
