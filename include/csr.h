@@ -180,10 +180,11 @@ typedef struct {
                            Eq.12 and turned to position rope_pos0 + t, frequency pair k by the angle
                            position * rope_base^(-2k/d); q is the query as attention receives it, already
                            turned at its own position.  Supported with the paper's storage types (fp16 q and
-                           dictionaries, 16-bit indices, fp16 coefficients), whole-vector keys (snK <= 1),
-                           sK a multiple of 4 and a key dictionary of at most 128 KB (N <= 512): the kernel
-                           keeps it in LDS.  T is then at most 2^19 when Hq/Hkv is a multiple of
-                           4.  Scores carry the rounding of the turned query (or key) to fp16, a
+                           dictionaries, 16-bit indices, fp16 coefficients), whole-vector keys (snK <= 1) and
+                           sK a multiple of 4.  A key dictionary of at most 128 KB (N <= 512, the paper's own
+                           sizes) stays in LDS; a larger one is gathered row by row from device memory, which
+                           is correct but several times slower (256 bytes per code pair instead of 4).
+                           T is then at most 2^19 when Hq/Hkv is a multiple of 4.  Scores carry the rounding of the turned query (or key) to fp16, a
                            relative 2^-11 per component, instead of fp32 accuracy.                 */
     int32_t rope_layout; /* 0: pair k is dimensions (k, k + d/2); 1: dimensions (2k, 2k + 1)    */
     int64_t rope_pos0;  /* position of cache token 0 of every sequence; 0 .. 2^40              */

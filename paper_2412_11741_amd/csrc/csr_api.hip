@@ -196,8 +196,8 @@ csr_status check_decode_desc(const csr_decode_desc *d, csr::DecodePlan *plan)
         if (d->q_dtype != CSR_F16 || d->dict_dtype != CSR_F16 || d->coef_dtype != CSR_F16 || d->idx_dtype != CSR_I16)
             return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: rotary keys need fp16 queries, dictionaries and coefficients and 16-bit indices");
         if (!csr::decode_rope_shape_supported(d->d, d->N, d->sK, snK))
-            return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: rotary keys need whole-vector key codes, sK a multiple of 4 and a key "
-                                             "dictionary of at most 128 KB (N=%d, sK=%d, snK=%d)", d->N, d->sK, snK);
+            return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: rotary keys need whole-vector key codes and sK a multiple of 4 "
+                                             "(N=%d, sK=%d, snK=%d)", d->N, d->sK, snK);
     } else if (d->rope_layout != 0 || d->rope_pos0 != 0) {
         return fail(CSR_ERR_INVALID_ARG, "csr_decode_attn: rope_layout and rope_pos0 must be 0 when rope_base is 0");
     }

@@ -658,7 +658,7 @@ bool plan_decode(int32_t B, int32_t Hq, int32_t Hkv, int64_t T, int32_t d, int32
         if (G % cand != 0) continue;
         // score table (fp32; with rotary keys the dictionary itself, fp16 rows) and histogram (64-bit) share the
         // space: the larger one counts
-        const size_t first = rope ? (size_t)N * d * 2 : NK * 4 * cand;
+        const size_t first = rope ? (rope_dictionary_fits_lds(N) ? (size_t)N * d * 2 : 0) : NK * 4 * cand;
         const size_t tab = ((first > NV * 8 * cand ? first : NV * 8 * cand) + 15) & ~size_t(15);
         const size_t lds = tab + kRedBytes + (rope ? kRopeTableBytes : 0);
         if (lds <= kLdsBudget) { GB = cand; p->lds_bytes = lds; break; }

@@ -19,6 +19,8 @@ constexpr int kMaxChunks = 128;
 constexpr int rope_threads(int GB) { return GB >= 2 ? 512 : 1024; }  // tokens per round
 // rounds a chunk may have: one score per round and query head stays in registers
 constexpr int rope_rounds(int GB) { return GB == 2 ? 16 : 8; }
+// the rotary-key kernel keeps the key dictionary of its KV head in LDS when it fits (at most 512 atoms of 128 halves)
+constexpr bool rope_dictionary_fits_lds(int N) { return (size_t)N * 256 <= 128 * 1024; }
 constexpr size_t kRopeTableBytes = 8 * 32 * 4 + 8 * 4 * 8 * 4 + 64 * 8;  // rotation constants, a group's query pairs, theta
 constexpr size_t kLdsBudget = 150 * 1024;
 // Reduction scratch of the streaming kernels, in 4-byte words behind the table / histogram (WAVES <= 16, GB <= 4):

@@ -78,7 +78,10 @@ __device__ __forceinline__ float sum8(float v)
 // the group's query pairs, packed fp16 [8 lane classes][4][8] (ROTK only) | theta_k as doubles [64]
 // TPT: rounds of rope_threads(GB) tokens a chunk may have (a lane keeps one score per round and query head).
 // ONEB: a key code is exactly one block of PVK pairs.
-template <int GB, bool ROTK, int PVK, bool ONEB, int PV, int TPT>
+// GLOBAL: the key dictionary does not fit the LDS (more than 512 atoms): every gathered row piece then comes from
+// device memory - the L2 for dictionaries of a few MB - instead, brought into the same pair-adjacent form in
+// registers.  The arithmetic is the same; the call is then bound by those gathers (256 bytes per code pair).
+template <int GB, bool ROTK, int PVK, bool ONEB, int PV, int TPT, bool GLOBAL>
 __global__ __launch_bounds__(rope_threads(GB)) void stream_rope_kernel(
     const __half *__restrict__ q, const __half *__restrict__ DK, const uint16_t *__restrict__ idxK,
     const __half *__restrict__ coefK, const uint16_t *__restrict__ idxV, const __half *__restrict__ coefV,
@@ -116,7 +119,7 @@ __global__ __launch_bounds__(rope_threads(GB)) void stream_rope_kernel(
     const int n_mine = (int)((t_end - t0 + THREADS - 1) / THREADS);  // rounds of THREADS tokens
 
     // ---- the key dictionary into LDS, frequency pairs made adjacent -----------------------------------------
-    {
+    if constexpr (!GLOBAL) {
         const __half *src = DK + (int64_t)h * N * 128;
         for (int e = tid; e < N * 16; e += THREADS) {
             const int row = e >> 4, j = e & 15;
@@ -172,6 +175,25 @@ __global__ __launch_bounds__(rope_threads(GB)) void stream_rope_kernel(
         }
     }
     const unsigned char *rows0 = smem_raw + sub * 16;
+    // GLOBAL: this lane's two 16-byte pieces (pairs 4 sub .. 4 sub + 3 and 32 + 4 sub .. + 3) of the atom row at byte
+    // offset `off` of the head's dictionary, the members of every pair made adjacent
+    const unsigned char *grow = reinterpret_cast<const unsigned char *>(DK + (int64_t)h * N * 128);
+    auto global_pieces = [&](uint32_t off, uint4 &d0, uint4 &d1) {
+        if (layout == 0) {  // pair k = dimensions (k, k + 64): 4 + 4 halves from both halves of the row, interleaved
+            auto weave = [](const uint2 &lo, const uint2 &hi) {
+                return make_uint4((lo.x & 0xffffu) | (hi.x << 16), (lo.x >> 16) | (hi.x & 0xffff0000u),
+                                  (lo.y & 0xffffu) | (hi.y << 16), (lo.y >> 16) | (hi.y & 0xffff0000u));
+            };
+            const unsigned char *r = grow + off + sub * 8;
+            const uint2 a0 = *reinterpret_cast<const uint2 *>(r), b0 = *reinterpret_cast<const uint2 *>(r + 128);
+            const uint2 a1 = *reinterpret_cast<const uint2 *>(r + 64), b1 = *reinterpret_cast<const uint2 *>(r + 192);
+            d0 = weave(a0, b0);
+            d1 = weave(a1, b1);
+        } else {            // pair k = dimensions (2k, 2k + 1): already adjacent
+            d0 = *reinterpret_cast<const uint4 *>(grow + off + sub * 16);
+            d1 = *reinterpret_cast<const uint4 *>(grow + off + 128 + sub * 16);
+        }
+    };
     const float *my_c = ctab + sub * 32;
     const uint32_t *my_q = qtab + sub * GB * 8;
     // the rotating state, at the position of the first token this eighth handles (step 0 of the first pass over 64).
@@ -294,8 +316,13 @@ __global__ __launch_bounds__(rope_threads(GB)) void stream_rope_kernel(
 #pragma unroll
                     for (int jj = 0; jj < PVK; ++jj) {
                         const float cf = (jj & 1) ? hi_half(tc[jj >> 1]) : lo_half(tc[jj >> 1]);
-                        const uint4 d0 = *reinterpret_cast<const uint4 *>(rows0 + to[jj]);
-                        const uint4 d1 = *reinterpret_cast<const uint4 *>(rows0 + to[jj] + 128);
+                        uint4 d0, d1;
+                        if constexpr (GLOBAL) {
+                            global_pieces(to[jj], d0, d1);
+                        } else {
+                            d0 = *reinterpret_cast<const uint4 *>(rows0 + to[jj]);
+                            d1 = *reinterpret_cast<const uint4 *>(rows0 + to[jj] + 128);
+                        }
                         if constexpr (ROTK) {
                             const uint32_t dw[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
 #pragma unroll
@@ -363,10 +390,10 @@ __global__ __launch_bounds__(rope_threads(GB)) void stream_rope_kernel(
                                                                   part_hist, slot);
 }
 
-template <int GB, bool ROTK, int PVK, bool ONEB, int PV>
+template <int GB, bool ROTK, int PVK, bool ONEB, int PV, bool GLOBAL>
 hipError_t launch_rope_t(const DecodeArgs &a, const DecodePlan &p, float *hist, float *ml)
 {
-    auto kern = stream_rope_kernel<GB, ROTK, PVK, ONEB, PV, rope_rounds(GB)>;
+    auto kern = stream_rope_kernel<GB, ROTK, PVK, ONEB, PV, rope_rounds(GB), GLOBAL>;
     static std::atomic<bool> attr_set[kMaxDevices];
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -389,27 +416,31 @@ hipError_t launch_rope_t(const DecodeArgs &a, const DecodePlan &p, float *hist, 
     return hipGetLastError();
 }
 
-template <int GB, bool ROTK, int PVK, bool ONEB>
+template <int GB, bool ROTK, int PVK, bool ONEB, bool GLOBAL>
 hipError_t launch_rope_pv(const DecodeArgs &a, const DecodePlan &p, float *hist, float *ml)
 {
-    if (a.sV % 8 == 0) return launch_rope_t<GB, ROTK, PVK, ONEB, 8>(a, p, hist, ml);
-    if (a.sV % 4 == 0) return launch_rope_t<GB, ROTK, PVK, ONEB, 4>(a, p, hist, ml);
-    return launch_rope_t<GB, ROTK, PVK, ONEB, 1>(a, p, hist, ml);
+    if (a.sV % 8 == 0) return launch_rope_t<GB, ROTK, PVK, ONEB, 8, GLOBAL>(a, p, hist, ml);
+    if (a.sV % 4 == 0) return launch_rope_t<GB, ROTK, PVK, ONEB, 4, GLOBAL>(a, p, hist, ml);
+    return launch_rope_t<GB, ROTK, PVK, ONEB, 1, GLOBAL>(a, p, hist, ml);
 }
 
 template <int GB, bool ROTK>
 hipError_t launch_rope_gb(const DecodeArgs &a, const DecodePlan &p, float *hist, float *ml)
 {
-    if (a.sK == 8) return launch_rope_pv<GB, ROTK, 8, true>(a, p, hist, ml);  // the paper's key codes
-    if (a.sK % 8 == 0) return launch_rope_pv<GB, ROTK, 8, false>(a, p, hist, ml);
-    return launch_rope_pv<GB, ROTK, 4, false>(a, p, hist, ml);
+    if (!rope_dictionary_fits_lds(a.N)) {  // rows gathered from device memory
+        if (a.sK % 8 == 0) return launch_rope_pv<GB, ROTK, 8, false, true>(a, p, hist, ml);
+        return launch_rope_pv<GB, ROTK, 4, false, true>(a, p, hist, ml);
+    }
+    if (a.sK == 8) return launch_rope_pv<GB, ROTK, 8, true, false>(a, p, hist, ml);  // the paper's key codes
+    if (a.sK % 8 == 0) return launch_rope_pv<GB, ROTK, 8, false, false>(a, p, hist, ml);
+    return launch_rope_pv<GB, ROTK, 4, false, false>(a, p, hist, ml);
 }
 
 }  // namespace
 
 bool decode_rope_shape_supported(int32_t d, int32_t N, int32_t sK, int32_t snK)
 {
-    return d == 128 && snK == 1 && sK % 4 == 0 && (size_t)N * 256 <= 128 * 1024;
+    return d == 128 && snK == 1 && sK % 4 == 0 && N <= 65536;
 }
 
 hipError_t launch_stream_rope(const DecodeArgs &a, const DecodePlan &p, float *hist, float *ml)

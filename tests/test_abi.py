@@ -190,7 +190,7 @@ def _dec(**kw):
     (dict(snK=2, N=4000), B.CSR_ERR_UNSUPPORTED), (dict(snV=8, sV=8), B.CSR_ERR_UNSUPPORTED),
     (dict(snV=8, N=8192, Hq=2), B.CSR_ERR_UNSUPPORTED),   # 8 x 8192 histogram bins of 8 bytes exceed the LDS
     # keys coded before the rotary embedding: the key dictionary has to fit the LDS, paper's storage types only
-    (dict(rope_base=10000.0), B.CSR_ERR_UNSUPPORTED),                      # N = 4096
+    (dict(rope_base=10000.0, N=70000, idx_dtype=B.CSR_I16), B.CSR_ERR_INVALID_ARG),
     (dict(rope_base=10000.0, N=512, sK=6), B.CSR_ERR_UNSUPPORTED),
     (dict(rope_base=10000.0, N=512, snK=2, sK=4), B.CSR_ERR_UNSUPPORTED),
     (dict(rope_base=10000.0, N=512, coef_dtype=B.CSR_F32), B.CSR_ERR_UNSUPPORTED),
@@ -224,7 +224,8 @@ def test_decode_workspace_is_required_and_checked():
 
 def test_decode_accepts_rotary_descriptors_within_the_resident_limit():
     lib = csr.lib()
-    for kw in (dict(N=512), dict(N=256, Hq=2, Hkv=2, sK=4), dict(N=128, snV=2, sV=4, rope_layout=1, rope_pos0=1 << 30)):
+    for kw in (dict(N=512), dict(N=256, Hq=2, Hkv=2, sK=4), dict(N=128, snV=2, sV=4, rope_layout=1, rope_pos0=1 << 30),
+               dict(N=768), dict(N=4096, Hq=4, Hkv=1), dict(N=8192, sK=16, sV=16)):   # beyond the LDS: gathered rows
         need = lib.csr_decode_workspace_bytes(ctypes.byref(_dec(rope_base=10000.0, **kw)))
         assert 0 < need < 1 << 32, kw
 

@@ -49,6 +49,23 @@ def _check(out, ref, what):
 
 
 @pytest.mark.parametrize("B,Hq,Hkv,T,N,sK,sV,snV,layout,pos0", [
+    (2, 4, 4, 1500, 768, 8, 8, 1, 0, 0),        # 16384 + 8192 atoms over 32 heads (the appendix's largest setting): 768 per head
+    (1, 8, 2, 2100, 4096, 8, 8, 1, 0, 11),      # the benchmark's dictionaries, query groups of 4, rotate-half pairs
+    (2, 2, 2, 1025, 4096, 16, 4, 1, 1, 5000),   # interleaved pairs, two blocks of 8 key pairs
+    (1, 2, 1, 700, 1024, 4, 8, 2, 1, 3),        # groups of 2, 4 key pairs per token, values in two chunks
+    (1, 3, 3, 3000, 8192, 16, 16, 1, 0, 100000),  # the long-context dictionaries, far positions
+])
+def test_rotary_keys_with_dictionaries_beyond_the_lds(B, Hq, Hkv, T, N, sK, sV, snV, layout, pos0):
+    # larger key dictionaries than the LDS holds: the same arithmetic on rows gathered from device memory
+    args = _case(77, B, Hq, Hkv, T, N, sK, sV, snV)
+    lens = np.full(B, T, dtype=np.int32)
+    lens[-1] = max(1, T - 333)
+    out = _run(args, 10000.0, layout, pos0, seq_lens=lens)
+    ref = oracle.decode_attn_rope(*args, 10000.0, layout, pos0, seq_lens=lens)
+    _check(out, ref, f"gathered rows: B{B} Hq{Hq} Hkv{Hkv} T{T} N{N} sK{sK} sV{sV} snV{snV} layout{layout} pos0 {pos0}")
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,T,N,sK,sV,snV,layout,pos0", [
     (2, 4, 4, 3000, 512, 8, 8, 1, 0, 0),        # MHA, the largest resident dictionary, three rounds of 1024
     (2, 8, 2, 1500, 256, 8, 4, 1, 1, 17),       # query groups of 4 = two slices of 2, interleaved pairs
     (1, 2, 2, 40000, 256, 8, 8, 1, 0, 100000),  # several chunks, many rounds, positions past 10^5
