@@ -206,7 +206,8 @@ size_t csr_decode_workspace_bytes(const csr_decode_desc *desc);
  *   out      [B][Hq][d]        out
  *   workspace: device memory, 256-byte aligned, >= csr_decode_workspace_bytes().
  *   q, DK, DV, the four code streams and out must be 16-byte aligned.
- * Indices are not range-checked on the device: an index >= N reads outside the score table.
+ * Indices are not range-checked on the device: an index >= N reads outside the score table (csr_check_codes counts
+ * such indices, off the hot path).
  */
 csr_status csr_decode_attn(const csr_decode_desc *desc, const void *q, const void *DK,
                            const void *idxK, const void *coefK, const void *DV, const void *idxV,
@@ -286,6 +287,16 @@ csr_status csr_gram_build(const void *D, int32_t n_dicts, int32_t N, int32_t d, 
  * n_atoms >= 0, 1 <= d <= 65536.  No workspace.
  */
 csr_status csr_atom_norms2(const void *D, int32_t dict_dtype, int64_t n_atoms, int32_t d, float *norms2, void *hip_stream);
+
+/*
+ * Atom indices of a code stream that lie outside [0, N) (16-bit indices read unsigned; negative 32-bit ones count):
+ * *bad receives their number.  Eq.12 addresses the dictionary with the stored index as it is: csr_decode_attn and
+ * csr_reconstruct do not range-check on the device, so codes that were not written by csr_encode (a cache loaded
+ * from elsewhere) can be looked at first.  One read of the index stream, off the hot path.
+ *   idx    device, `count` indices of idx_dtype, contiguous      in
+ *   bad    device, one int64, 8-byte aligned                     out (valid once the stream has run)
+ */
+csr_status csr_check_codes(const void *idx, int32_t idx_dtype, int64_t count, int32_t N, int64_t *bad, void *hip_stream);
 
 /*
  * Storage accounting of Section "Analysis for CSR": bytes kept per head vector,

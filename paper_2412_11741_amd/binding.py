@@ -20,7 +20,7 @@ CSR_FLAG_CLOSED_LOOP = 1
 
 EXPORTS = ("csr_version", "csr_last_error", "csr_code_bytes", "csr_encode_workspace_bytes",
            "csr_encode", "csr_decode_workspace_bytes", "csr_decode_attn", "csr_reconstruct", "csr_atom_norms2",
-           "csr_gram_bytes", "csr_gram_build", "csr_decode_attn_static")
+           "csr_gram_bytes", "csr_gram_build", "csr_decode_attn_static", "csr_check_codes")
 STATIC_SCRATCH_BYTES = 16 << 20   # CSR_STATIC_SCRATCH_BYTES of include/csr.h
 
 
@@ -88,6 +88,8 @@ def lib():
         L.csr_gram_build.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp]
         L.csr_atom_norms2.restype = ctypes.c_int
         L.csr_atom_norms2.argtypes = [vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, vp, vp]
+        L.csr_check_codes.restype = ctypes.c_int
+        L.csr_check_codes.argtypes = [vp, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, vp, vp]
         L.csr_decode_workspace_bytes.restype = sz
         L.csr_decode_workspace_bytes.argtypes = [ctypes.POINTER(DecodeDesc)]
         L.csr_decode_attn.restype = ctypes.c_int
@@ -270,6 +272,21 @@ def csr_atom_norms2(D, out=None):
     if tuple(out.shape) != shape or out.dtype != torch.float32 or not out.is_contiguous():
         raise ValueError(f"out must be a contiguous fp32 tensor of shape {shape}")
     _check(lib().csr_atom_norms2(_ptr(D), _DT[D.dtype], out.numel(), D.shape[-1], _ptr(out), _stream()))
+    return out
+
+
+def csr_check_codes(idx, N, out=None):
+    """Number of atom indices of `idx` (int16 read unsigned, or int32; contiguous) outside [0, N), as a one-element
+    int64 GPU tensor (`out`, or a new one)."""
+    _dev(idx, "idx")
+    if idx.dtype not in _IT or not idx.is_contiguous():
+        raise ValueError("idx must be a contiguous int16 or int32 tensor")
+    if out is None:
+        out = torch.empty(1, dtype=torch.int64, device=idx.device)
+    _dev(out, "out")
+    if out.dtype != torch.int64 or out.numel() != 1:
+        raise ValueError("out must be one int64")
+    _check(lib().csr_check_codes(_ptr(idx), _IT[idx.dtype], idx.numel(), int(N), _ptr(out), _stream()))
     return out
 
 

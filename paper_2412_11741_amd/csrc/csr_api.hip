@@ -340,6 +340,17 @@ csr_status csr_atom_norms2(const void *D, int32_t dict_dtype, int64_t n_atoms, i
     return CSR_OK;
 }
 
+csr_status csr_check_codes(const void *idx, int32_t idx_dtype, int64_t count, int32_t N, int64_t *bad, void *hip_stream)
+{
+    if (!valid_itype(idx_dtype)) return fail(CSR_ERR_INVALID_ARG, "csr_check_codes: unknown index type %d", idx_dtype);
+    if (count < 0 || N < 1) return fail(CSR_ERR_INVALID_ARG, "csr_check_codes: count=%lld must be >= 0 and N=%d >= 1", (long long)count, N);
+    if (!bad || (count > 0 && !idx)) return fail(CSR_ERR_INVALID_ARG, "csr_check_codes: NULL pointer");
+    if (!aligned(idx, idx_dtype == CSR_I16 ? 2 : 4) || !aligned(bad, 8)) return fail(CSR_ERR_INVALID_ARG, "csr_check_codes: misaligned pointer");
+    const hipError_t e = csr::launch_check_codes(idx, idx_dtype == CSR_I16, count, N, bad, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail(CSR_ERR_DEVICE, "csr_check_codes: %s", hipGetErrorString(e));
+    return CSR_OK;
+}
+
 size_t csr_decode_workspace_bytes(const csr_decode_desc *desc)
 {
     csr::DecodePlan p{};

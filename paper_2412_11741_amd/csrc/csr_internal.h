@@ -72,6 +72,7 @@ hipError_t launch_gram_build(const void *D, int32_t n_dicts, int32_t N, int32_t 
 
 // ---- atom norms -----------------------------------------------------------------------------------------------------
 hipError_t launch_atom_norms2(const void *D, bool f16, int64_t n_atoms, int32_t d, float *out, hipStream_t stream);
+hipError_t launch_check_codes(const void *idx, bool idx16, int64_t count, int32_t N, int64_t *bad, hipStream_t stream);
 
 // ---- reconstruct (Eq.12) --------------------------------------------------------------------
 struct ReconstructArgs {

@@ -22,12 +22,12 @@
 #include <atomic>
 
 #include "csr_internal.h"
+#include "encode_common.h"
 
 namespace csr {
 namespace {
 
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef float floatx4 __attribute__((ext_vector_type(4)));
+using namespace enc;
 
 constexpr int kWaves = 8;                    // two per SIMD, 256 registers each; one workgroup per CU (G fills the LDS)
 constexpr int kThreads = 64 * kWaves;
@@ -35,12 +35,9 @@ constexpr int kBlocksPerWave = 4;            // 16-vector blocks a wave works th
 constexpr int kTokPerWG = kWaves * kBlocksPerWave * 16;  // 512
 constexpr int kMaxAtoms = 256;
 constexpr int kMaxTiles = kMaxAtoms / 16;
-// fp32 accumulation error of a 128-term dot product of exact fp16 products, relative to |a||b|
-constexpr float kGammaAcc = 1.6e-5f;
 
 __device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
 __device__ __forceinline__ uint32_t umin(uint32_t a, uint32_t b) { return a < b ? a : b; }
-__device__ __forceinline__ uint32_t umed3(uint32_t a, uint32_t b, uint32_t c) { return umax(umin(a, b), umin(umax(a, b), c)); }
 
 // sum over the 4 lanes of a vector (lanes col, col + 16, col + 32, col + 48)
 __device__ __forceinline__ float sum4(float v)

@@ -25,14 +25,12 @@
 //       everything, a dictionary of equal atoms): all N atoms are evaluated.  Then Eq.4 on R with the unrounded
 //       coefficient, and the recursion on C.
 #include "csr_internal.h"
+#include "encode_common.h"
 
 namespace csr {
 namespace {
 
-typedef _Float16 half2v __attribute__((ext_vector_type(2)));
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
+using namespace enc;
 
 constexpr int kSweepThreads = 256;
 constexpr int kSliceAtoms = 256;        // atoms per sweep workgroup
@@ -47,7 +45,6 @@ constexpr int kValuSweepVectors = 8;    // up to here the sweep is a matrix-vect
 constexpr int kSweepTiles = 2;          // 32-atom tiles per wave of the matrix-core sweep (4 waves: 256 atoms)
 static_assert(kSliceAtoms == (kSweepThreads / 64) * 32 * kSweepTiles, "a sweep workgroup covers one slice");
 constexpr int kCand = 256;              // candidate list; beyond it every atom is evaluated
-constexpr float kGammaAcc = 1.6e-5f;    // fp32 accumulation of a 128-term dot product of exact fp16 products
 
 __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c)
 {
@@ -56,16 +53,6 @@ __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c)
 __device__ __forceinline__ float dot8(const uint4 &a, const uint4 &b)
 {
     return dot2(a.w, b.w, dot2(a.z, b.z, dot2(a.y, b.y, dot2(a.x, b.x, 0.0f))));
-}
-__device__ __forceinline__ void unpack8(const uint4 &raw, float (&f)[8])
-{
-    const __half2 *h2 = reinterpret_cast<const __half2 *>(&raw);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const float2 v = __half22float2(h2[j]);
-        f[2 * j] = v.x;
-        f[2 * j + 1] = v.y;
-    }
 }
 template <int CTRL> __device__ __forceinline__ float dpp_add(float v)
 {
@@ -79,11 +66,6 @@ template <int LPR> __device__ __forceinline__ float row_sum(float v)
     v = dpp_add<0x141>(v);  // row_half_mirror: lane i of every 8 with lane 7 - i
     if (LPR == 16) v = dpp_add<0x140>(v);  // row_mirror: lane i of every 16 with lane 15 - i
     return v;
-}
-// (|c|, atom, c) candidates: larger |c| wins, the lower atom on equal |c|
-__device__ __forceinline__ void take_better(float &ba, int &bi, float &bc, float oa, int oi, float oc)
-{
-    if (oa > ba || (oa == ba && oi < bi)) { ba = oa; bi = oi; bc = oc; }
 }
 
 // (a1 >= a2 >= 0), the two largest of a set, merged with those of the lane that the DPP pattern names (a disjoint set;

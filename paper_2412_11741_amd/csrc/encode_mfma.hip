@@ -54,13 +54,12 @@
 #include <type_traits>
 
 #include "csr_internal.h"
+#include "encode_common.h"
 
 namespace csr {
 namespace {
 
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef _Float16 half2v __attribute__((ext_vector_type(2)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
+using namespace enc;
 
 constexpr int kBlocks = 2;                            // 32-token blocks per wave
 constexpr int kTokPerWave = 32 * kBlocks;             // 64
@@ -91,55 +90,12 @@ constexpr int kScratchOff = kRing * kStageBytes;
 template <int W> constexpr int lds_bytes() { return kScratchOff + W * kScratchPerWave; }  // 52 KiB (W = 4) | 56 KiB
 constexpr int kTrack = 4;                             // group maxima tracked per lane and sweep
 constexpr int kNormSlices = 8;                        // workgroups per dictionary in the norm pre-pass
-// fp32 accumulation error of a 128-term dot product of exact fp16 products, relative to |hi||d|:
-// 129 roundings of at most 2^-23 each (this also covers accumulators that truncate).
-constexpr float kGammaAcc = 1.6e-5f;
 
-__device__ __forceinline__ uint32_t umed3(uint32_t a, uint32_t b, uint32_t c)
-{
-    return max(min(a, b), min(max(a, b), c));
-}
 
-// value of the other lane of the pair (lane ^ 32)
-__device__ __forceinline__ uint32_t xchg32(uint32_t v, int hf)
-{
-    const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
-    return hf ? r[0] : r[1];
-}
-__device__ __forceinline__ float xchg32f(float v, int hf) { return __uint_as_float(xchg32(__float_as_uint(v), hf)); }
 
-__device__ __forceinline__ void unpack8(const uint4 &raw, float (&f)[8])
-{
-    const __half2 *h2 = reinterpret_cast<const __half2 *>(&raw);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const float2 v = __half22float2(h2[j]);
-        f[2 * j] = v.x;
-        f[2 * j + 1] = v.y;
-    }
-}
 
-__device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-// waits until at most `n` of this wave's vector memory operations are still in flight
-template <int N_LEFT>
-__device__ __forceinline__ void wait_vmem_but() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N_LEFT) : "memory"); }
 
-// LDS traffic inside one wave needs no barrier (the LDS executes a wave's instructions in order),
-// only that the compiler keeps the order and waits for the data.
-__device__ __forceinline__ void wave_lds_fence()
-{
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-}
 
-// 8 dimensions of a dot product: a (fp16 x 8) . d (fp16 x 8), two fp32 accumulators
-__device__ __forceinline__ void dot8(const half8 &a, const half8 &d, float &s0, float &s1)
-{
-    s0 = __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 0, 1), __builtin_shufflevector(d, d, 0, 1), s0, false);
-    s1 = __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 2, 3), __builtin_shufflevector(d, d, 2, 3), s1, false);
-    s0 = __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 4, 5), __builtin_shufflevector(d, d, 4, 5), s0, false);
-    s1 = __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 6, 7), __builtin_shufflevector(d, d, 6, 7), s1, false);
-}
 
 // One dictionary stage (64 atoms x 256 B) from global memory into an LDS buffer, no registers in
 // between.  Each wave instruction fills 1 KiB = 4 rows; lane l lands at byte 16 l of that KiB, i.e.
@@ -286,7 +242,7 @@ __global__ __launch_bounds__(64 * W, 8 / W) void encode_mfma_kernel(
     const __half *__restrict__ X, const __half *__restrict__ Dict, void *__restrict__ idx_out,
     void *__restrict__ coef_out, const float *__restrict__ dnorm, int64_t T, int64_t M, int32_t N, int32_t s, int32_t sn,
     int64_t x_stride_h, int64_t x_stride_t, int32_t dict_count, int64_t code_stride_h, int32_t tiles_per_h,
-    int32_t n_groups, int32_t idx16, int32_t coef_mode, uint32_t code_mask, int32_t first_round,
+    int32_t n_groups, int32_t idx16, int32_t coef_mode, uint32_t code_mask,
     float *__restrict__ res_norm2)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
@@ -324,17 +280,6 @@ __global__ __launch_bounds__(64 * W, 8 / W) void encode_mfma_kernel(
 #pragma unroll
     for (int j = 0; j < kFrags; ++j)
         frag_off[j] = (uint32_t)(col * S::kRowBytes + (((hf * kFrags + j) ^ S::swz(col)) << 4));
-
-    // Two workgroups share a CU.  Started together they would sweep together and select together;
-    // holding back the one in the odd wave slot by about half a sweep makes one's select phase
-    // (vector ALU, gathers) fall into the other's sweep (matrix cores).  Only the workgroups that
-    // start with the kernel need this; later ones start whenever a slot frees up.
-    if ((int)blockIdx.x < first_round) {
-        // HW_ID bits 3:0 = this wave's slot on its SIMD; a workgroup waits for its slowest wave anyway
-        if (__builtin_amdgcn_s_getreg(0xF804) & 1) {
-            for (int i = 0; i < nstages; ++i) __builtin_amdgcn_s_sleep(16);
-        }
-    }
 
     float dmax = 0.0f;
 #pragma unroll
@@ -398,7 +343,7 @@ __global__ __launch_bounds__(64 * W, 8 / W) void encode_mfma_kernel(
         r2 += xchg32f(r2, hf);
         lo2 += xchg32f(lo2, hf);
         rn2[bi] = r2;
-        delta[bi] = 2.0f * dmax * (sqrtf(lo2) + kGammaAcc * sqrtf(r2));
+        delta[bi] = screen_delta(dmax, lo2, r2);
     }
 
     for (int g = 0; g < s; ++g) {
@@ -623,7 +568,7 @@ __global__ __launch_bounds__(64 * W, 8 / W) void encode_mfma_kernel(
             }
             lo2 += xchg32f(lo2, hf);
             rn2[bi] = r2;
-            delta[bi] = 2.0f * dmax * (sqrtf(lo2) + kGammaAcc * sqrtf(r2));
+            delta[bi] = screen_delta(dmax, lo2, r2);
             if (valid[bi]) {
                 const int64_t o = (int64_t)hblk[bi] * code_stride_h + (tpos[bi] * sn + ch) * s + g;
                 if (hf == 0) {
@@ -661,7 +606,7 @@ size_t encode_mfma_workspace_bytes(int32_t H, int64_t T, int32_t N, int32_t s)
 }
 
 template <int DC, int W>
-hipError_t launch_encode_mfma_w(const EncodeArgs &a, int cus)
+hipError_t launch_encode_mfma_w(const EncodeArgs &a)
 {
     constexpr int kTokPerWG = W * kTokPerWave;
     const int64_t M = (int64_t)(a.H / a.dict_count) * a.T;  // vectors per dictionary
@@ -686,9 +631,6 @@ hipError_t launch_encode_mfma_w(const EncodeArgs &a, int cus)
         if (e != hipSuccess) return e;
         attr_set[dev].store(true, std::memory_order_release);
     }
-    // the workgroups that start together (two per CU with 4 waves each) are the ones held back at the start
-    const int32_t first_round = (W == 4 && groups > cus) ? 2 * cus : 0;
-
     hipLaunchKernelGGL(dict_norm_kernel<DC>, dim3((unsigned)(a.dict_count * a.sn), kNormSlices), dim3(256), 0, a.stream,
                        (const __half *)a.D, dnorm, a.N);
     e = hipGetLastError();
@@ -697,7 +639,7 @@ hipError_t launch_encode_mfma_w(const EncodeArgs &a, int cus)
                        (const __half *)a.X, (const __half *)a.D, a.idx, a.coef, dnorm, a.T, M, a.N, a.s, a.sn, a.x_stride_h,
                        a.x_stride_t, a.dict_count, a.code_stride_h, (int32_t)tiles, (int32_t)groups, (int32_t)a.idx16,
                        (a.coef16 ? kCoefF16 : 0) | (a.closed_loop ? kCoefClosed : 0), code_mask,
-                       first_round, a.res_norm2);
+                       a.res_norm2);
     return hipGetLastError();
 }
 
@@ -719,8 +661,8 @@ hipError_t launch_encode_mfma_t(const EncodeArgs &a)
     // 512-vector workgroups (one per CU) once there is one for every CU
     const int64_t M = (int64_t)(a.H / a.dict_count) * a.T;
     const int64_t groups8 = (M + 8 * kTokPerWave - 1) / (8 * kTokPerWave) * a.dict_count * a.sn;
-    if (groups8 >= (int64_t)cus) return launch_encode_mfma_w<DC, 8>(a, cus);
-    return launch_encode_mfma_w<DC, 4>(a, cus);
+    if (groups8 >= (int64_t)cus) return launch_encode_mfma_w<DC, 8>(a);
+    return launch_encode_mfma_w<DC, 4>(a);
 }
 
 hipError_t launch_encode_mfma(const EncodeArgs &a)

@@ -25,12 +25,12 @@
 #include <atomic>
 
 #include "csr_internal.h"
+#include "encode_common.h"
 
 namespace csr {
 namespace {
 
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
+using namespace enc;
 
 constexpr int kWaves = 8;                    // two per SIMD; one workgroup per CU (the dictionary fills the LDS)
 constexpr int kThreads = 64 * kWaves;
@@ -39,44 +39,11 @@ constexpr int kTokPerWG = kWaves * kBlocksPerWave * 32;  // 512
 constexpr int kMaxDictBytes = 128 * 1024;
 constexpr int kScratchPerWave = 1024;        // LDS a wave uses to share one vector's state
 constexpr int kTrack = 4;                    // group maxima tracked per lane and sweep
-// fp32 accumulation error of a 128-term dot product of exact fp16 products, relative to |hi||d|
-constexpr float kGammaAcc = 1.6e-5f;
 
-__device__ __forceinline__ uint32_t umed3(uint32_t a, uint32_t b, uint32_t c) { return max(min(a, b), min(max(a, b), c)); }
 
-__device__ __forceinline__ uint32_t xchg32(uint32_t v, int hf)
-{
-    const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
-    return hf ? r[0] : r[1];
-}
-__device__ __forceinline__ float xchg32f(float v, int hf) { return __uint_as_float(xchg32(__float_as_uint(v), hf)); }
 
-__device__ __forceinline__ void unpack8(const uint4 &raw, float (&f)[8])
-{
-    const __half2 *h2 = reinterpret_cast<const __half2 *>(&raw);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const float2 v = __half22float2(h2[j]);
-        f[2 * j] = v.x;
-        f[2 * j + 1] = v.y;
-    }
-}
 
-// 8 dimensions of a dot product: a (fp16 x 8) . d (fp16 x 8), two fp32 accumulators
-__device__ __forceinline__ void dot8(const half8 &a, const half8 &d, float &s0, float &s1)
-{
-    s0 = __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 0, 1), __builtin_shufflevector(d, d, 0, 1), s0, false);
-    s1 = __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 2, 3), __builtin_shufflevector(d, d, 2, 3), s1, false);
-    s0 = __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 4, 5), __builtin_shufflevector(d, d, 4, 5), s0, false);
-    s1 = __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 6, 7), __builtin_shufflevector(d, d, 6, 7), s1, false);
-}
 
-// LDS traffic inside one wave needs no barrier, only that the compiler keeps the order and waits for the data.
-__device__ __forceinline__ void wave_lds_fence()
-{
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-}
 
 // XOR term of a row's 16-byte piece positions, so that 16 consecutive rows read at one logical piece cover all
 // banks: a 256-byte row spans the 64 banks (16 different terms), two 128-byte rows span them (8, one per pair).
@@ -268,7 +235,7 @@ __global__ __launch_bounds__(kThreads, OCC) void encode_resident_kernel(
             }
             rn2 = r2 + xchg32f(r2, hf);
             lo2 += xchg32f(lo2, hf);
-            delta = 2.0f * dmax * (sqrtf(lo2) + kGammaAcc * sqrtf(rn2));
+            delta = screen_delta(dmax, lo2, rn2);
         }
 
         for (int g = 0; g < s; ++g) {
@@ -431,7 +398,7 @@ __global__ __launch_bounds__(kThreads, OCC) void encode_resident_kernel(
             }
             lo2 += xchg32f(lo2, hf);
             rn2 = r2;
-            delta = 2.0f * dmax * (sqrtf(lo2) + kGammaAcc * sqrtf(r2));
+            delta = screen_delta(dmax, lo2, r2);
             if (valid) {
                 const int64_t o = (int64_t)h * code_stride_h + (tok * sn + ch) * s + g;
                 if (hf == 0) {

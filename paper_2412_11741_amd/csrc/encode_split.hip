@@ -24,12 +24,12 @@
 #include <cmath>
 
 #include "csr_internal.h"
+#include "encode_common.h"
 
 namespace csr {
 namespace {
 
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
+using namespace enc;
 
 constexpr int kWaves = 4;
 constexpr int kThreads = 64 * kWaves;
@@ -37,29 +37,8 @@ constexpr int kMaxVectors = 128;  // per dictionary; beyond that the prefill enc
 constexpr int kMaxSlices = 16;
 constexpr int kTargetGroups = 512;  // workgroups per launch aimed at (two per CU)
 
-__device__ __forceinline__ uint32_t xchg32(uint32_t v, int hf)
-{
-    const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
-    return hf ? r[0] : r[1];
-}
-__device__ __forceinline__ float xchg32f(float v, int hf) { return __uint_as_float(xchg32(__float_as_uint(v), hf)); }
 
-__device__ __forceinline__ void unpack8(const uint4 &raw, float (&f)[8])
-{
-    const __half2 *h2 = reinterpret_cast<const __half2 *>(&raw);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const float2 v = __half22float2(h2[j]);
-        f[2 * j] = v.x;
-        f[2 * j + 1] = v.y;
-    }
-}
 
-// (|c|, atom, c) candidates: larger |c| wins, the lower atom on equal |c|
-__device__ __forceinline__ void take_better(float &ba, int &bi, float &bc, float oa, int oi, float oc)
-{
-    if (oa > ba || (oa == ba && oi < bi)) { ba = oa; bi = oi; bc = oc; }
-}
 
 struct SplitParams {
     const __half *X;

@@ -33,3 +33,20 @@ def test_empty_and_output_checks():
     with pytest.raises(ValueError, match="shape"):
         csr.csr_atom_norms2(torch.zeros(2, 8, 64, dtype=torch.float16, device="cuda"),
                             out=torch.zeros(16, dtype=torch.float32, device="cuda"))
+
+
+def test_check_codes_counts_indices_outside_the_dictionary():
+    rng = np.random.default_rng(8)
+    for dtype, N in ((np.int32, 1000), (np.int16, 40000), (np.int16, 4096)):
+        idx = rng.integers(0, N, size=(3, 7, 1001, 8)).astype(np.int64)
+        bad = rng.random(idx.shape) < 0.001
+        idx[bad] = N + rng.integers(0, 20000, size=int(bad.sum()))
+        if dtype == np.int32:
+            idx[0, 0, 0, 0] = -5; bad[0, 0, 0, 0] = True            # a negative index is outside too
+        host = idx.astype(np.uint16).view(np.int16) if dtype == np.int16 else idx.astype(np.int32)
+        got = csr.csr_check_codes(torch.from_numpy(host).cuda(), N)
+        torch.cuda.synchronize()
+        assert int(got.item()) == int(bad.sum()) > 0
+    clean = torch.zeros(5, 8, dtype=torch.int16, device="cuda")
+    assert int(csr.csr_check_codes(clean, 1).item()) == 0
+    assert int(csr.csr_check_codes(clean[:0], 7).item()) == 0
