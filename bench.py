@@ -54,6 +54,21 @@ def recorded_traffic(table, key):
     return {"traffic": t[0] if t else None, "traffic_source": (t[1] + " (recorded rocprofv3 --pmc run, not this run)") if t else None}
 
 
+def mfma_only_rate():
+    """What the matrix cores of this GPU sustain with nothing else running (paper_2412_11741_amd/mfma_rate.bin, built
+    from csrc/probe/mfma_rate.hip): {"mfma_only_tflops_random": .., "mfma_only_tflops_smooth": ..}, or None if the
+    probe is not built.  Run as a child process before this process touches the GPU."""
+    import subprocess
+    exe = os.path.join(ROOT, "paper_2412_11741_amd", "mfma_rate.bin")
+    if not os.path.exists(exe):
+        return None
+    try:
+        out = subprocess.run([exe], capture_output=True, text=True, timeout=60)
+        return json.loads(out.stdout.strip().splitlines()[-1]) if out.returncode == 0 else None
+    except Exception:
+        return None
+
+
 def median(xs):
     xs = sorted(xs)
     n = len(xs)
@@ -481,6 +496,8 @@ def main():
         print(json.dumps({"copy_calibration_bytes_read": 1 << 30, "copy_calibration_bytes_written": 1 << 30, "copies": 5}))
         return
 
+    probe = mfma_only_rate()
+
     import paper_2412_11741_amd as csr
     from paper_2412_11741_amd import synth
 
@@ -619,6 +636,11 @@ def main():
                 "algorithmic_bytes": n_vec * (d * dict_b + code_b) + H * N * d * dict_b,
                 "flop_per_vector": 2.0 * d * N * s, "median_launch_ms": round(enc_ms, 4),
                 "avg_launch_ms": round(sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps, 4)}
+    if probe:
+        # the chip is power-limited under matrix-core load: a loop of nothing but this MFMA on random operands runs
+        # well below the nominal peak, and that rate is what a kernel feeding the matrix cores real data can approach
+        roofline["mfma_only_sustained"] = probe
+        roofline["frac_of_mfma_only_encoder_like"] = round(enc_tflops / probe["mfma_only_tflops_encoder_like"], 5)
     dec_gbs = dec_bytes / (dec_cold_ms * 1e-3) / 1e9
     roofline_decode = {"kernel": "csr_decode_attn (4 launches), cache-cold", "bound": "hbm",
                        "achieved": round(dec_gbs, 2), "peak": PEAK_HBM_GBS, "unit": "GB/s",

@@ -62,6 +62,22 @@ def build_c_smoke(verbose: bool = False) -> str:
     return C_SMOKE_BIN
 
 
+PROBE_SRC = os.path.join(CSRC, "probe", "mfma_rate.hip")
+PROBE_BIN = os.path.join(HERE, "mfma_rate.bin")
+
+
+def build_probe(verbose: bool = False) -> str:
+    """The stand-alone matrix-core rate probe (csrc/probe/mfma_rate.hip): what the chip sustains on MFMA alone."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           PROBE_SRC, "-o", PROBE_BIN]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return PROBE_BIN
+
+
 if __name__ == "__main__":
     print(build(verbose=True, extra=sys.argv[1:]))
     print(build_c_smoke(verbose=True))
+    print(build_probe(verbose=True))

@@ -543,6 +543,150 @@ __global__ __launch_bounds__(256) void out_kernel(const TD *__restrict__ DV, con
     }
 }
 
+// The same for fp16 dictionaries, whole-vector values and ONE (sequence, query head) pair per KV head (a single
+// sequence without query groups; with more pairs out_kernel's LDS-staged slice is the faster form), with the slice read the way qd_rows_kernel reads D_K: 16 lanes
+// share an atom row (16 bytes each), all eight row requests of a thread are issued ahead of everything else, and the
+// slice never passes through LDS.  Thread (arow, sub) owns dimensions 8 sub .. 8 sub + 7 of atoms arow + 16 i; it takes
+// the combined histogram values of its atoms from LDS (one value per atom and pair, shared by the 16 lanes of the
+// row), and the 16 atom groups meet through lane exchanges inside a wave and LDS across the four waves.
+template <int NQ>
+__global__ __launch_bounds__(256) void out_rows_kernel(const __half *__restrict__ DV, const float *__restrict__ part_hist,
+                                                       const float *__restrict__ part_ml, float *__restrict__ part_out,
+                                                       int32_t B, int32_t Hkv, int32_t G, int32_t GB, int32_t N, int32_t nchunks)
+{
+    constexpr int ATOMS = kOutAtomsF16, kRows = ATOMS / 16;
+    __shared__ __attribute__((aligned(16))) float hist_s[NQ][ATOMS];
+    __shared__ float w_s[NQ][kMaxChunks];
+    __shared__ __attribute__((aligned(16))) float red_s[4][NQ][128];
+    const int tid = threadIdx.x;
+    const int sub = tid & 15, arow = tid >> 4;
+    const int n0 = blockIdx.x * ATOMS;
+    const int h = blockIdx.y;
+    const int ngs = G / GB;
+    const int nslices = gridDim.x;
+    const int BG = B * G;
+    const int bg0 = blockIdx.z * NQ;
+    const int nbg = min(NQ, BG - bg0);
+    constexpr int kElems = (NQ * ATOMS + 255) / 256;
+    constexpr int kEarly = 4;
+
+    uint4 raw[kRows];
+#pragma unroll
+    for (int i = 0; i < kRows; ++i) {
+        const int n = n0 + arow + 16 * i;
+        raw[i] = make_uint4(0u, 0u, 0u, 0u);
+        if (n < N) raw[i] = *reinterpret_cast<const uint4 *>(DV + ((int64_t)h * N + n) * 128 + sub * 8);
+    }
+    const float *ph[kElems];
+    float early[kElems][kEarly];
+#pragma unroll
+    for (int i = 0; i < kElems; ++i) {
+        const int e = i * 256 + tid;
+        const int bgl = e / ATOMS, nn = e % ATOMS;
+        ph[i] = nullptr;
+        if (e < NQ * ATOMS && bgl < nbg && n0 + nn < N) {
+            const int b = (bg0 + bgl) / G, g = (bg0 + bgl) % G;
+            ph[i] = part_hist + ((((int64_t)b * Hkv + h) * ngs + g / GB) * nchunks) * (int64_t)N * GB +
+                    (int64_t)(g % GB) * N + (n0 + nn);
+        }
+#pragma unroll
+        for (int c = 0; c < kEarly; ++c)
+            early[i][c] = (ph[i] && c < nchunks) ? ph[i][(int64_t)c * N * GB] : 0.0f;
+    }
+    if (tid < nbg) {
+        const int b = (bg0 + tid) / G, g = (bg0 + tid) % G;
+        const int gs = g / GB, gg = g % GB;
+        const float *ml = part_ml + ((((int64_t)b * Hkv + h) * ngs + gs) * nchunks) * (2 * GB);
+        float M = -INFINITY;
+        for (int c = 0; c < nchunks; ++c) M = fmaxf(M, ml[c * 2 * GB + 2 * gg]);
+        for (int c = 0; c < nchunks; ++c) {
+            const float m = ml[c * 2 * GB + 2 * gg];
+            w_s[tid][c] = (m > -INFINITY) ? __expf(m - M) : 0.0f;
+        }
+    }
+    __syncthreads();
+    float hacc[kElems];
+#pragma unroll
+    for (int i = 0; i < kElems; ++i) {
+        const int bgl = (i * 256 + tid) / ATOMS;
+        float acc = 0.0f;
+        if (ph[i]) {
+            // a chunk without tokens has weight 0 and a histogram that was never written: skip, not multiply
+#pragma unroll
+            for (int c = 0; c < kEarly; ++c) {
+                const float w = c < nchunks ? w_s[bgl][c] : 0.0f;
+                if (w > 0.0f) acc = fmaf(w, early[i][c], acc);
+            }
+        }
+        hacc[i] = acc;
+    }
+    for (int c0 = kEarly; c0 < nchunks; c0 += 4) {
+        float v[kElems][4];
+#pragma unroll
+        for (int i = 0; i < kElems; ++i) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                v[i][u] = (ph[i] && c0 + u < nchunks) ? ph[i][(int64_t)(c0 + u) * N * GB] : 0.0f;
+        }
+#pragma unroll
+        for (int i = 0; i < kElems; ++i) {
+            const int bgl = (i * 256 + tid) / ATOMS;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float w = (ph[i] && c0 + u < nchunks) ? w_s[bgl][c0 + u] : 0.0f;
+                if (w > 0.0f) hacc[i] = fmaf(w, v[i][u], hacc[i]);
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < kElems; ++i) {
+        const int e = i * 256 + tid;
+        if (e < NQ * ATOMS) hist_s[e / ATOMS][e % ATOMS] = hacc[i];
+    }
+    __syncthreads();
+    float acc[NQ][8];
+#pragma unroll
+    for (int r = 0; r < NQ; ++r)
+#pragma unroll
+        for (int k = 0; k < 8; ++k) acc[r][k] = 0.0f;
+#pragma unroll
+    for (int i = 0; i < kRows; ++i) {
+        float d[8];
+        load8_raw(raw[i], d);
+#pragma unroll
+        for (int r = 0; r < NQ; ++r) {
+            const float hv = hist_s[r][arow + 16 * i];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) acc[r][k] = fmaf(hv, d[k], acc[r][k]);
+        }
+    }
+    // the four atom groups of a wave (rows of 16 lanes) meet through two lane exchanges, the waves through LDS
+    const int wave = tid >> 6, lane = tid & 63;
+#pragma unroll
+    for (int r = 0; r < NQ; ++r) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            float v = acc[r][k];
+            v += __shfl_xor(v, 16, 64);
+            v += __shfl_xor(v, 32, 64);
+            acc[r][k] = v;
+        }
+    }
+    if (lane < 16) {
+#pragma unroll
+        for (int r = 0; r < NQ; ++r) {
+            *reinterpret_cast<float4 *>(&red_s[wave][r][8 * sub]) = make_float4(acc[r][0], acc[r][1], acc[r][2], acc[r][3]);
+            *reinterpret_cast<float4 *>(&red_s[wave][r][8 * sub + 4]) = make_float4(acc[r][4], acc[r][5], acc[r][6], acc[r][7]);
+        }
+    }
+    __syncthreads();
+    float *dst = part_out + (((int64_t)h * nslices + blockIdx.x) * BG + bg0) * 128;
+    for (int e = tid; e < nbg * 128; e += 256) {
+        const int r = e >> 7, k = e & 127;
+        dst[e] = (red_s[0][r][k] + red_s[1][r][k]) + (red_s[2][r][k] + red_s[3][r][k]);
+    }
+}
+
 // out[b][hq][k] = (sum over slices of part_out) / softmax denominator.  Thread (half, k): the slices of one
 // parity, eight loads in flight; the order of the additions is fixed, so the result is reproducible.
 template <typename TO>
@@ -758,7 +902,13 @@ hipError_t launch_decode(const DecodeArgs &a, const DecodePlan &p)
         case 2: CSR_OUT(TD, ATOMS, 2); break;                                                                    \
         default: CSR_OUT(TD, ATOMS, 1); break;                                                                   \
     }
-        if (a.dict16) { CSR_OUT_NQ(__half, kOutAtomsF16) } else { CSR_OUT_NQ(float, kOutAtomsF32) }
+#define CSR_OUTR(NQ)                                                                                              \
+    hipLaunchKernelGGL((out_rows_kernel<NQ>), grid, dim3(256), 0, a.stream, (const __half *)a.DV, hist, ml, acc, a.B, \
+                       a.Hkv, a.G, p.GB, a.N, p.nchunks)
+        if (a.dict16 && a.snV == 1 && nq == 1) {   // measured faster for one pair per KV head only
+            CSR_OUTR(1);
+        } else if (a.dict16) { CSR_OUT_NQ(__half, kOutAtomsF16) } else { CSR_OUT_NQ(float, kOutAtomsF32) }
+#undef CSR_OUTR
 #undef CSR_OUT_NQ
 #undef CSR_OUT
         hipError_t e = hipGetLastError();

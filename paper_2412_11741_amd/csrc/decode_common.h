@@ -46,6 +46,16 @@ template <> __device__ __forceinline__ void load8<__half>(const __half *p, float
         o[2 * j + 1] = f.y;
     }
 }
+__device__ __forceinline__ void load8_raw(const uint4 &raw, float (&o)[8])   // 8 packed halves, already in registers
+{
+    const __half2 *h2 = reinterpret_cast<const __half2 *>(&raw);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float2 f = __half22float2(h2[j]);
+        o[2 * j] = f.x;
+        o[2 * j + 1] = f.y;
+    }
+}
 template <> __device__ __forceinline__ void load8<float>(const float *p, float (&o)[8])
 {
     const float4 a = *reinterpret_cast<const float4 *>(p);
