@@ -57,10 +57,13 @@ def recorded_traffic(table, key):
 def mfma_only_rate():
     """What the matrix cores of this GPU sustain with nothing else running (paper_2412_11741_amd/mfma_rate.bin, built
     from csrc/probe/mfma_rate.hip): {"mfma_only_tflops_random": .., "mfma_only_tflops_smooth": ..}, or None if the
-    probe is not built.  Run as a child process before this process touches the GPU."""
+    probe is not built.  Run as a child process before this process touches the GPU; left out under a profiler
+    (whose preloaded library has initialised the GPU already, and whose kernel statistics it would only clutter)."""
     import subprocess
     exe = os.path.join(ROOT, "paper_2412_11741_amd", "mfma_rate.bin")
     if not os.path.exists(exe):
+        return None
+    if any(k.startswith(("ROCPROF", "ROCP_")) for k in os.environ) or "rocprof" in os.environ.get("LD_PRELOAD", ""):
         return None
     try:
         out = subprocess.run([exe], capture_output=True, text=True, timeout=60)
@@ -472,6 +475,8 @@ def main():
                     help="time the LDS-resident and the Gram-update encoder on small dictionaries (for profiling)")
     ap.add_argument("--no-rope", action="store_true", help="skip the rotary-key decode shapes")
     ap.add_argument("--only-rope", action="store_true", help="run only the rotary-key decode shapes (for profiling)")
+    ap.add_argument("--no-mfma-probe", action="store_true",
+                    help="do not run the stand-alone matrix-core rate probe (a child process) first")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only copy 1 GiB device-to-device five times and exit: run under rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE, it shows what those counters read for a known amount of traffic")
@@ -496,7 +501,7 @@ def main():
         print(json.dumps({"copy_calibration_bytes_read": 1 << 30, "copy_calibration_bytes_written": 1 << 30, "copies": 5}))
         return
 
-    probe = mfma_only_rate()
+    probe = None if args.no_mfma_probe else mfma_only_rate()
 
     import paper_2412_11741_amd as csr
     from paper_2412_11741_amd import synth

@@ -201,8 +201,10 @@ csr_status check_decode_desc(const csr_decode_desc *d, csr::DecodePlan *plan)
     } else if (d->rope_layout != 0 || d->rope_pos0 != 0) {
         return fail(CSR_ERR_INVALID_ARG, "csr_decode_attn: rope_layout and rope_pos0 must be 0 when rope_base is 0");
     }
-    const bool wide_codes = d->idx_dtype == CSR_I16 && d->coef_dtype == CSR_F16 && snK == 1 && snV == 1 && d->sK == 16 && d->sV == 16;
-    if (!csr::plan_decode(d->B, d->Hq, d->Hkv, d->T, d->d, d->N, snK, snV, rope, wide_codes, plan))
+    const int code_vecs = d->idx_dtype == CSR_I16 && d->coef_dtype == CSR_F16 && snK == 1 && snV == 1 && d->sK == d->sV &&
+                                  (d->sK == 8 || d->sK == 16)
+                              ? d->sK / 8 : 0;
+    if (!csr::plan_decode(d->B, d->Hq, d->Hkv, d->T, d->d, d->N, snK, snV, rope, code_vecs, plan))
         return fail(CSR_ERR_UNSUPPORTED, "csr_decode_attn: N=%d atoms do not fit the LDS-resident score and histogram tables, or T=%lld "
                                          "exceeds what 128 token chunks hold", d->N, (long long)d->T);
     return CSR_OK;

@@ -119,9 +119,10 @@ struct DecodeArgs {
 
 // Fills the plan; returns false if no kernel configuration fits (e.g. N too large for LDS).
 // rope: the plan is for the kernel that keeps the key dictionary in LDS (keys coded before the rotary embedding).
-// wide_codes: 16 pairs per key and per value code in the paper's storage types (two 16-byte vectors per stream).
+// code_vecs: 1 or 2 if key and value codes are whole-vector codes of 8 or 16 pairs in the paper's storage types
+// (one or two 16-byte vectors per token and stream: the streaming kernel's fast variants), else 0.
 bool plan_decode(int32_t B, int32_t Hq, int32_t Hkv, int64_t T, int32_t d, int32_t N, int32_t snK, int32_t snV,
-                 bool rope, bool wide_codes, DecodePlan *p);
+                 bool rope, int code_vecs, DecodePlan *p);
 hipError_t launch_decode(const DecodeArgs &a, const DecodePlan &p);
 
 // Streaming kernel for keys coded before the rotary embedding (decode_rope.hip); fills the same chunk histograms,

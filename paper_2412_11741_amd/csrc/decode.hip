@@ -303,7 +303,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
     static_assert(VL == 0 || (sizeof(TI) == 2 && sizeof(TC) == 2 && PV == 8 && !CH), "16-byte code vectors");
     const int64_t tok0 = t0 + tid;  // this thread's token of round 0
     constexpr int PF = prefetch_rounds<GB, TPT, VL>();
-    CodeVec<VL> ring[PF];
+    CodeVec<VL> ring[PF + 1];  // round i reads slot i % (PF + 1) while round i + PF is requested into the slot round i - 1 left
     CodeWalk<VL, kStreamThreads> walk(idxK, coefK, code_row + t0, tid);  // walks PF rounds ahead of the current one
     if constexpr (VL > 0) {
 #pragma unroll
@@ -315,10 +315,26 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
     const int table = NK * GB;
     {
         const float *src = qd + (((int64_t)b * Hkv + h) * ngs + gs) * (int64_t)table;
-        for (int e = tid * 4; e < table; e += kStreamThreads * 4) {
-            if (e + 4 <= table) *reinterpret_cast<float4 *>(qd_s + e) = *reinterpret_cast<const float4 *>(src + e);
-            else for (int r = e; r < table; ++r) qd_s[r] = src[r];
+        constexpr int U = 4;   // 16-byte pieces a thread requests together: one round trip to L2 instead of four
+        const int whole = table & ~3;
+        for (int e0 = tid * 4; e0 < whole; e0 += U * kStreamThreads * 4) {
+            float4 v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {   // past the end: the first piece again, not stored (no load under a branch)
+                const int e = e0 + u * kStreamThreads * 4;
+                v[u] = *reinterpret_cast<const float4 *>(src + (e < whole ? e : 0));
+            }
+            // all four pieces are live here: the requests above cannot be strung out between the stores below
+            asm volatile("" : "+v"(v[0].x), "+v"(v[0].y), "+v"(v[0].z), "+v"(v[0].w), "+v"(v[1].x), "+v"(v[1].y), "+v"(v[1].z),
+                              "+v"(v[1].w), "+v"(v[2].x), "+v"(v[2].y), "+v"(v[2].z), "+v"(v[2].w), "+v"(v[3].x), "+v"(v[3].y),
+                              "+v"(v[3].z), "+v"(v[3].w));
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int e = e0 + u * kStreamThreads * 4;
+                if (e < whole) *reinterpret_cast<float4 *>(qd_s + e) = v[u];
+            }
         }
+        if (tid < table - whole) qd_s[whole + tid] = src[whole + tid];
     }
     __syncthreads();
 
@@ -353,11 +369,11 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
         if (i < n_mine) {
             round_fence();
             const int64_t t = tok0 + (int64_t)i * kStreamThreads;
-            CodeVec<VL> cur;
+            CodeVec<VL> &cur = ring[i % (PF + 1)];
             if constexpr (VL > 0) {
-                take_codes<VL>(cur, ring[i % PF]);
+                await_codes<VL>(cur);
                 if (i + PF < TPT) {
-                    fetch_codes<VL, kStreamThreads>(ring[i % PF], walk, i + PF < n_mine && t + (int64_t)PF * kStreamThreads < t_end);
+                    fetch_codes<VL, kStreamThreads>(ring[(i + PF) % (PF + 1)], walk, i + PF < n_mine && t + (int64_t)PF * kStreamThreads < t_end);
                     walk.next();
                 }
             }
@@ -793,7 +809,7 @@ hipError_t launch_stream_gb(const DecodeArgs &a, const DecodePlan &p, float *qd,
 }  // namespace
 
 bool plan_decode(int32_t B, int32_t Hq, int32_t Hkv, int64_t T, int32_t d, int32_t N, int32_t snK, int32_t snV,
-                 bool rope, bool wide_codes, DecodePlan *p)
+                 bool rope, int code_vecs, DecodePlan *p)
 {
     const size_t NK = (size_t)snK * N, NV = (size_t)snV * N;  // entries of the score table / of a histogram
     const int G = Hq / Hkv;
@@ -816,7 +832,7 @@ bool plan_decode(int32_t B, int32_t Hq, int32_t Hkv, int64_t T, int32_t d, int32
     const int64_t groups = (int64_t)(B > 0 ? B : 1) * Hkv * p->ngs;
     int64_t want = (256 + groups - 1) / groups;
     const int64_t threads = rope ? rope_threads(GB) : kStreamThreads;  // tokens per round of the streaming kernel
-    (void)wide_codes;
+    (void)code_vecs;
     const int64_t tpt = rope ? rope_rounds(GB) : max_rounds(GB);   // rounds per chunk
     const int64_t most = T > 0 ? (T + threads - 1) / threads : 1;
     const int64_t least = T > 0 ? (T + tpt * threads - 1) / (tpt * threads) : 1;

@@ -217,7 +217,6 @@ template <int VL> struct CodeVec { uint4 i[VL > 0 ? VL : 1], c[VL > 0 ? VL : 1];
 // per workgroup, one vector per code: what bounds that kernel is the number of bytes in flight per CU), else one.
 template <int GB, int TPT, int VL> constexpr int prefetch_rounds() { return GB == 1 && VL == 1 && TPT >= 4 ? 2 : 1; }
 
-// The 16-byte code vectors of the token of round i (token t0 + i * threads + off), zeros past the end.
 // The code streams of a thread's tokens, walked round by round: two workgroup-uniform base addresses (the code
 // vectors of the chunk's first token) and one 32-bit offset per thread, in 16-byte vectors.  The offset passes
 // through an empty asm statement at every step, so that the compiler cannot work out all rounds' addresses ahead of
@@ -235,24 +234,26 @@ template <int VL, int THREADS> struct CodeWalk {
         asm volatile("" : "+v"(off));
     }
 };
-// The 16-byte code vectors of the token the walk stands at (zeros if `have` is false).
+// Requests the 16-byte code vectors of the token the walk stands at.  Without such a token (`have` false: past the
+// end of the chunk) the chunk's first token is requested instead and the caller ignores what arrives: a request
+// under a branch would make the destination registers the meeting point of two paths, and the compiler then copies
+// them - and waits for the request - right behind it.
 template <int VL, int THREADS>
 __device__ __forceinline__ void fetch_codes(CodeVec<VL> &r, const CodeWalk<VL, THREADS> &w, bool have)
 {
+    const uint32_t o = have ? w.off : 0u;
 #pragma unroll
-    for (int v = 0; v < (VL > 0 ? VL : 1); ++v) r.i[v] = r.c[v] = make_uint4(0u, 0u, 0u, 0u);
-    if (have) {
-#pragma unroll
-        for (int v = 0; v < VL; ++v) { r.i[v] = w.ib[w.off + v]; r.c[v] = w.cb[w.off + v]; }
+    for (int v = 0; v < (VL > 0 ? VL : 1); ++v) {
+        if constexpr (VL > 0) { r.i[v] = w.ib[o + v]; r.c[v] = w.cb[o + v]; }
+        else r.i[v] = r.c[v] = make_uint4(0u, 0u, 0u, 0u);
     }
 }
-// Takes over the code vectors that were requested a round ago: `cur` must hold them (so the wait for that request
-// comes here) BEFORE a later round's request is issued into `nxt`; the empty asm statements keep the compiler from
-// moving the copy - and with it the wait - behind the new request, where it would wait for both.
+// The code vectors of the current round must have arrived BEFORE a later round's request is issued: the empty asm
+// statements make the compiler place the wait for them here, where only older requests are outstanding, instead of
+// behind the new request, where it would wait for both.
 template <int VL>
-__device__ __forceinline__ void take_codes(CodeVec<VL> &cur, const CodeVec<VL> &nxt)
+__device__ __forceinline__ void await_codes(CodeVec<VL> &cur)
 {
-    cur = nxt;
 #pragma unroll
     for (int v = 0; v < (VL > 0 ? VL : 1); ++v) {
         asm volatile("" : "+v"(cur.i[v].x), "+v"(cur.i[v].y), "+v"(cur.i[v].z), "+v"(cur.i[v].w));
@@ -299,7 +300,7 @@ __device__ __forceinline__ void finish_chunk(unsigned char *smem_raw, float *red
     // ---- the chunk's maximum; a sample of the value coefficients (the first round's tokens) ---------------
     float cm = 0.0f;
     constexpr int PF = prefetch_rounds<GB, TPT, VL>();
-    CodeVec<VL> ring[PF];
+    CodeVec<VL> ring[PF + 1];  // round i reads slot i % (PF + 1) while round i + PF is requested into the slot round i - 1 left
     auto prime = [&](CodeWalk<VL, THREADS> &w) {   // requests rounds 0 .. PF-1, leaves w at round PF
 #pragma unroll
         for (int k = 0; k < PF; ++k) {
@@ -322,8 +323,10 @@ __device__ __forceinline__ void finish_chunk(unsigned char *smem_raw, float *red
             int id[8];
             float cf[8];
             unpack8(ring[0].i[v], ring[0].c[v], id, cf);
+            if (n_mine > 0 && tok0 < t_end) {   // else the vectors are not this thread's
 #pragma unroll
-            for (int j = 0; j < 8; ++j) cm = fmaxf(cm, fabsf(cf[j]));
+                for (int j = 0; j < 8; ++j) cm = fmaxf(cm, fabsf(cf[j]));
+            }
         }
     } else {
         if (n_mine > 0 && tok0 < t_end) {
@@ -409,11 +412,11 @@ __device__ __forceinline__ void finish_chunk(unsigned char *smem_raw, float *red
                 if (i < n_mine) {
                     round_fence();
                     const int64_t t = tok0 + (int64_t)i * THREADS;
-                    CodeVec<VL> cur;
+                    CodeVec<VL> &cur = ring[i % (PF + 1)];
                     if constexpr (VL > 0) {
-                        take_codes<VL>(cur, ring[i % PF]);
+                        await_codes<VL>(cur);
                         if (i + PF < TPT) {
-                            fetch_codes<VL, THREADS>(ring[i % PF], walk, i + PF < n_mine && t + (int64_t)PF * THREADS < t_end);
+                            fetch_codes<VL, THREADS>(ring[(i + PF) % (PF + 1)], walk, i + PF < n_mine && t + (int64_t)PF * THREADS < t_end);
                             walk.next();
                         }
                     }
@@ -494,13 +497,25 @@ __device__ __forceinline__ void finish_chunk(unsigned char *smem_raw, float *red
         for (int g = 0; g < GB; ++g) {
             h2[g] = 0.0f;
             const float from_units = ldexpf(1.0f, -k_exp[g]);
-            for (int e = tid; e < NV; e += THREADS) {
-                const uint2 pn = *reinterpret_cast<const uint2 *>(h32 + 2 * (g * NV + e));
-                tot += (unsigned long long)pn.x + pn.y;
-                high |= pn.x | pn.y;
-                const float v = (float)(int)(pn.x - pn.y);  // exact while both stay below 2^31
-                h2[g] = fmaf(v, v, h2[g]);
-                dst[g * NV + e] = v * from_units;
+            constexpr int U = 4;   // bins read together: the LDS round trips of a thread overlap
+            for (int e0 = tid; e0 < NV; e0 += U * THREADS) {
+                uint2 pn[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {   // past the end: bin 0, ignored below (no load under a branch)
+                    const int e = e0 + u * THREADS;
+                    pn[u] = *reinterpret_cast<const uint2 *>(h32 + 2 * (g * NV + (e < NV ? e : 0)));
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int e = e0 + u * THREADS;
+                    if (e < NV) {
+                        tot += (unsigned long long)pn[u].x + pn[u].y;
+                        high |= pn[u].x | pn[u].y;
+                        const float v = (float)(int)(pn[u].x - pn[u].y);  // exact while both stay below 2^31
+                        h2[g] = fmaf(v, v, h2[g]);
+                        dst[g * NV + e] = v * from_units;
+                    }
+                }
             }
         }
         // per wave: s - tot (as integers: the sums are exact from here on), max single add, high bits, |hist|^2
