@@ -18,6 +18,12 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno
          "-Wall", "-Wno-unused-function"]
 
 
+# decode.hip: the streaming kernel's rounds are unrolled by pragma (the scores of a thread's tokens live in registers);
+# the 32 rounds of its four-head variant exceed the compiler's default size limit for such an unroll, and a loop left
+# rolled would put the score array into scratch memory.
+PER_FILE_FLAGS = {"decode.hip": ["-mllvm", "-pragma-unroll-threshold=200000"]}
+
+
 def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
@@ -31,7 +37,7 @@ def build(verbose: bool = False, extra=()) -> str:
     with tempfile.TemporaryDirectory(prefix="csr_build_") as tmp:
         def compile_one(src):
             obj = os.path.join(tmp, os.path.basename(src) + ".o")
-            cmd = [hipcc, *compile_flags, *extra, "-I", INCLUDE, "-I", CSRC, "-c", src, "-o", obj]
+            cmd = [hipcc, *compile_flags, *PER_FILE_FLAGS.get(os.path.basename(src), []), *extra, "-I", INCLUDE, "-I", CSRC, "-c", src, "-o", obj]
             if verbose:
                 print(" ".join(cmd), flush=True)
             subprocess.run(cmd, check=True)

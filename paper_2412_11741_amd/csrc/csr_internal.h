@@ -95,6 +95,7 @@ struct DecodePlan {
     int32_t GB;           // query heads of one KV head handled together by a block (1, 2 or 4)
     int32_t ngs;          // group slices per KV head = G / GB
     int32_t nchunks;      // split of the token axis
+    int32_t threads;      // threads of a workgroup of the streaming kernel = tokens per round
     int64_t chunk_tokens; // tokens per chunk (multiple of the block's token step)
     size_t off_qd, off_hist, off_ml, off_acc, total_bytes;
     size_t lds_bytes;     // dynamic LDS of the streaming kernel

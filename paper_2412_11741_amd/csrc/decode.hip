@@ -255,12 +255,12 @@ __global__ __launch_bounds__(256) void qd_rows_kernel(const __half *__restrict__
 // One workgroup: chunk c of the tokens of (sequence b, KV head h, group slice gs).
 // LDS: the table of scores q.d, fp32 [N][GB] (pass 1), then the fixed-point histogram (pass 2, see finish_chunk) |
 // reduction scratch.
-// TPT: rounds of 1024 tokens a chunk may have; a thread keeps the scores of its tokens (one per round) in registers.
+// TPT: rounds of stream_threads(GB) tokens a chunk may have; a thread keeps the scores of its tokens (one per round) in registers.
 // VL > 0: a token's key code and its value code are VL 16-byte vectors of indices and of coefficients each (16-bit
 // indices, fp16 coefficients, whole-vector codes, s = 8 VL): the vectors are requested ahead of their use - the
 // first rounds' before the score table is loaded - so that several round trips to memory overlap.
-template <int GB, typename TI, typename TC, int PV, bool CH, int TPT, int VL>
-__global__ __launch_bounds__(kStreamThreads) void stream_kernel(
+template <int GB, typename TI, typename TC, int PV, bool CH, int TPT, int VL, int THREADS = kStreamThreads>
+__global__ __launch_bounds__(THREADS) void stream_kernel(
     const float *__restrict__ qd, const TI *__restrict__ idxK, const TC *__restrict__ coefK,
     const TI *__restrict__ idxV, const TC *__restrict__ coefV, const int32_t *__restrict__ seq_lens,
     float *__restrict__ part_hist, float *__restrict__ part_ml, int32_t Hkv, int32_t ngs, int64_t T,
@@ -298,17 +298,17 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
     }
 
     const int64_t code_row = ((int64_t)b * Hkv + h) * T;
-    const int n_mine = (int)((t_end - t0 + kStreamThreads - 1) / kStreamThreads);  // rounds of 1024 tokens
+    const int n_mine = (int)((t_end - t0 + THREADS - 1) / THREADS);  // rounds of THREADS tokens
 
     static_assert(VL == 0 || (sizeof(TI) == 2 && sizeof(TC) == 2 && PV == 8 && !CH), "16-byte code vectors");
     const int64_t tok0 = t0 + tid;  // this thread's token of round 0
     constexpr int PF = prefetch_rounds<GB, TPT, VL>();
     CodeVec<VL> ring[PF + 1];  // round i reads slot i % (PF + 1) while round i + PF is requested into the slot round i - 1 left
-    CodeWalk<VL, kStreamThreads> walk(idxK, coefK, code_row + t0, tid);  // walks PF rounds ahead of the current one
+    CodeWalk<VL, THREADS> walk(idxK, coefK, code_row + t0, tid);  // walks PF rounds ahead of the current one
     if constexpr (VL > 0) {
 #pragma unroll
         for (int k = 0; k < PF; ++k) {
-            fetch_codes<VL, kStreamThreads>(ring[k], walk, k < n_mine && tok0 + (int64_t)k * kStreamThreads < t_end);
+            fetch_codes<VL, THREADS>(ring[k], walk, k < n_mine && tok0 + (int64_t)k * THREADS < t_end);
             walk.next();
         }
     }
@@ -317,11 +317,11 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
         const float *src = qd + (((int64_t)b * Hkv + h) * ngs + gs) * (int64_t)table;
         constexpr int U = 4;   // 16-byte pieces a thread requests together: one round trip to L2 instead of four
         const int whole = table & ~3;
-        for (int e0 = tid * 4; e0 < whole; e0 += U * kStreamThreads * 4) {
+        for (int e0 = tid * 4; e0 < whole; e0 += U * THREADS * 4) {
             float4 v[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {   // past the end: the first piece again, not stored (no load under a branch)
-                const int e = e0 + u * kStreamThreads * 4;
+                const int e = e0 + u * THREADS * 4;
                 v[u] = *reinterpret_cast<const float4 *>(src + (e < whole ? e : 0));
             }
             // all four pieces are live here: the requests above cannot be strung out between the stores below
@@ -330,7 +330,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
                               "+v"(v[3].z), "+v"(v[3].w));
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int e = e0 + u * kStreamThreads * 4;
+                const int e = e0 + u * THREADS * 4;
                 if (e < whole) *reinterpret_cast<float4 *>(qd_s + e) = v[u];
             }
         }
@@ -338,7 +338,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
     }
     __syncthreads();
 
-    // ---- pass 1: scores of this thread's tokens (token t0 + i * 1024 + tid in round i) --------
+    // ---- pass 1: scores of this thread's tokens (token t0 + i * THREADS + tid in round i) --------
     float sc[TPT][GB];
     float mx[GB];
 #pragma unroll
@@ -368,12 +368,12 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
     for (int i = 0; i < TPT; ++i) {
         if (i < n_mine) {
             round_fence();
-            const int64_t t = tok0 + (int64_t)i * kStreamThreads;
+            const int64_t t = tok0 + (int64_t)i * THREADS;
             CodeVec<VL> &cur = ring[i % (PF + 1)];
             if constexpr (VL > 0) {
                 await_codes<VL>(cur);
                 if (i + PF < TPT) {
-                    fetch_codes<VL, kStreamThreads>(ring[(i + PF) % (PF + 1)], walk, i + PF < n_mine && t + (int64_t)PF * kStreamThreads < t_end);
+                    fetch_codes<VL, THREADS>(ring[(i + PF) % (PF + 1)], walk, i + PF < n_mine && t + (int64_t)PF * THREADS < t_end);
                     walk.next();
                 }
             }
@@ -408,7 +408,7 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(
             }
         }
     }
-    finish_chunk<GB, TI, TC, PV, CH, TPT, kStreamThreads, VL>(smem_raw, red, sc, mx, n_mine, t0, t_end, code_row, tid, idxV,
+    finish_chunk<GB, TI, TC, PV, CH, TPT, THREADS, VL>(smem_raw, red, sc, mx, n_mine, t0, t_end, code_row, tid, idxV,
                                                              coefV, N, sV, snV_arg, ml, part_hist, slot);
 }
 
@@ -745,10 +745,10 @@ __global__ __launch_bounds__(256) void finalize_kernel(const float *__restrict__
     }
 }
 
-template <int GB, typename TI, typename TC, int PV, bool CH, int TPT = max_rounds(GB), int VL = 0>
+template <int GB, typename TI, typename TC, int PV, bool CH, int TPT = max_rounds(GB), int VL = 0, int THREADS = kStreamThreads>
 hipError_t launch_stream_t(const DecodeArgs &a, const DecodePlan &p, float *qd, float *hist, float *ml)
 {
-    auto kern = stream_kernel<GB, TI, TC, PV, CH, TPT, VL>;
+    auto kern = stream_kernel<GB, TI, TC, PV, CH, TPT, VL, THREADS>;
     // raising the dynamic-LDS limit is needed once per kernel and device
     static std::atomic<bool> attr_set[kMaxDevices];
     int dev = 0;
@@ -762,7 +762,7 @@ hipError_t launch_stream_t(const DecodeArgs &a, const DecodePlan &p, float *qd, 
         attr_set[dev].store(true, std::memory_order_release);
     }
     const dim3 grid((unsigned)p.nchunks, (unsigned)(a.Hkv * p.ngs), (unsigned)a.B);
-    hipLaunchKernelGGL(kern, grid, dim3(kStreamThreads), p.lds_bytes, a.stream, qd, (const TI *)a.idxK,
+    hipLaunchKernelGGL(kern, grid, dim3(THREADS), p.lds_bytes, a.stream, qd, (const TI *)a.idxK,
                        (const TC *)a.coefK, (const TI *)a.idxV, (const TC *)a.coefV, a.seq_lens, hist, ml,
                        a.Hkv, p.ngs, a.T, a.N, a.sK, a.sV, a.snK, a.snV, p.chunk_tokens, p.nchunks,
                        (uint32_t)(p.lds_bytes - kRedBytes));
@@ -780,6 +780,10 @@ hipError_t launch_stream_pv(const DecodeArgs &a, const DecodePlan &p, float *qd,
     if constexpr (sizeof(TI) == 2 && sizeof(TC) == 2) {
         // the paper's storage (16-bit indices, fp16 coefficients) with 8 or 16 pairs per code: 16-byte code vectors
         // requested ahead; chunks of at most 1024 tokens (short contexts) keep one score per thread
+        if constexpr (GB == 4) {
+            if (p.threads == kLongThreads4)
+                return launch_stream_t<GB, TI, TC, 8, false, kLongRounds4, 1, kLongThreads4>(a, p, qd, hist, ml);
+        }
         const int rounds = (int)(p.chunk_tokens / kStreamThreads);
         if (a.sK == 8 && a.sV == 8)
             return rounds == 1 ? launch_stream_t<GB, TI, TC, 8, false, 1, 1>(a, p, qd, hist, ml)
@@ -828,12 +832,15 @@ bool plan_decode(int32_t B, int32_t Hq, int32_t Hkv, int64_t T, int32_t d, int32
     p->ngs = G / GB;
     // Split the token axis until every CU has a workgroup (two per CU was measured slower); every extra chunk costs one histogram
     // round trip through scratch, so no more than that, except that a chunk holds at most
-    // kMaxTPT x 1024 tokens (a thread keeps its tokens' scores in registers).
+    // max_rounds x stream_threads tokens (a thread keeps its tokens' scores in registers).
     const int64_t groups = (int64_t)(B > 0 ? B : 1) * Hkv * p->ngs;
     int64_t want = (256 + groups - 1) / groups;
-    const int64_t threads = rope ? rope_threads(GB) : kStreamThreads;  // tokens per round of the streaming kernel
-    (void)code_vecs;
-    const int64_t tpt = rope ? rope_rounds(GB) : max_rounds(GB);   // rounds per chunk
+    int64_t threads = rope ? rope_threads(GB) : kStreamThreads;  // tokens per round of the streaming kernel
+    int64_t tpt = rope ? rope_rounds(GB) : max_rounds(GB);       // rounds per chunk
+    // four query heads, 8 pairs per code in the paper's storage types, a context too long for `want` chunks of the
+    // 16-wave shape: the 8-wave shape with four times the rounds
+    if (!rope && GB == 4 && code_vecs == 1 && T > want * tpt * threads) { threads = kLongThreads4; tpt = kLongRounds4; }
+    p->threads = (int32_t)threads;
     const int64_t most = T > 0 ? (T + threads - 1) / threads : 1;
     const int64_t least = T > 0 ? (T + tpt * threads - 1) / (tpt * threads) : 1;
     if (want > most) want = most;

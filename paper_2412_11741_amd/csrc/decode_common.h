@@ -7,12 +7,19 @@
 namespace csr {
 namespace dec {
 
-constexpr int kStreamThreads = 1024;  // 16 waves: enough loads in flight with one workgroup per CU
-constexpr int kStreamWaves = kStreamThreads / 64;
+// Threads of a workgroup of the position-free streaming kernel = tokens per round: 16 waves (enough loads in flight
+// with one workgroup per CU) of 128 registers each.
+constexpr int kStreamThreads = 1024;
 constexpr int kMaxDevices = 64;      // devices a process may use this library on
-constexpr int kMaxTPT = 16;           // tokens per thread and chunk: their scores stay in registers
-// ... with four query heads per workgroup only 8 (32 of the 128 registers a thread of a 1024-thread workgroup has)
-constexpr int max_rounds(int GB) { return GB == 4 ? 8 : kMaxTPT; }
+// Rounds per chunk: a thread keeps the scores of its tokens (one per round and query head) in registers.  With four
+// query heads per workgroup only 8 (32 of the 128 registers) ...
+constexpr int max_rounds(int GB) { return GB == 4 ? 8 : 16; }
+// ... which makes long contexts many short chunks, and every chunk costs a fixed 10 us (dispatch, table load, histogram
+// clear and read-out, checks).  For those the four-head kernel has a second shape: 8 waves of 256 registers keep 32
+// rounds - chunks of 16384 tokens, like the other variants' (measured at 8 sequences x 8 KV heads x 131072 tokens:
+// 185 against 211 us per call).  Built for the paper's storage types with 8 pairs per code.
+constexpr int kLongThreads4 = 512;
+constexpr int kLongRounds4 = 32;
 constexpr int kMaxChunks = 128;
 // The rotary-key kernel (decode_rope.hip).  One query head at a time: 16 waves with 128 registers each; a query group
 // keeps a rebuilt key and the group's scores in registers: 8 waves with 256 each.

@@ -187,6 +187,37 @@ def test_gqa_llama3_full_launch_sampled():
     _full_launch_sampled("gqa_llama3_8b", [(0, 0), (7, 7), (4, 3)])
 
 
+def test_four_query_heads_long_context_shape_ragged_lengths_and_a_hot_atom():
+    # 8 sequences x 8 KV heads x 4 query heads with more than 32768 cached tokens run the streaming kernel's
+    # 8-wave shape (32 rounds of 512 tokens per chunk).  Ragged lengths cut chunks at every kind of boundary; in
+    # sequence 4 every value pair sits on one atom with the largest fp16 coefficients, which the 32-bit histogram
+    # cannot hold (the scatter has to notice and repeat itself in the wide form).  Codes are drawn on the GPU; the
+    # oracle recomputes sampled (sequence, KV head) pairs from the bits copied back.
+    B, Hkv, G, T, N, d, s = 8, 8, 4, 36000, 4096, 128, 8
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(27)
+    unit = lambda *sh: (lambda a: (a / a.norm(dim=-1, keepdim=True)).half())(torch.randn(*sh, device=dev, generator=gen))
+    idx = lambda: torch.randint(0, N, (B, Hkv, T, s), device=dev, generator=gen, dtype=torch.int32).to(torch.int16)
+    coef = lambda: (torch.randn(B, Hkv, T, s, device=dev, generator=gen) * 3).half()
+    q, DK, DV = torch.randn(B, Hkv * G, d, device=dev, generator=gen).half(), unit(Hkv, N, d), unit(Hkv, N, d)
+    ik, ck, iv, cv = idx(), coef(), idx(), coef()
+    ck[4] = 0
+    iv[4] = 7
+    cv[4] = 60000.0
+    lens = np.array([T, 1, 0, 20000, T - 1, 32769, 16385, T], dtype=np.int32)
+    sl = torch.from_numpy(lens).to(dev)
+    out = csr.csr_decode_attn(q, DK, ik, ck, DV, iv, cv, seq_lens=sl, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out).all() and torch.all(out[2] == 0)
+    h_ = lambda t: t.cpu().numpy()
+    for b, h in [(0, 0), (4, 3), (5, 7), (1, 2), (6, 1), (3, 5), (7, 7)]:
+        ref = oracle.decode_attn(h_(q[b:b + 1, h * G:(h + 1) * G]), h_(DK[h:h + 1]), h_(ik[b:b + 1, h:h + 1]),
+                                 h_(ck[b:b + 1, h:h + 1]), h_(DV[h:h + 1]), h_(iv[b:b + 1, h:h + 1]),
+                                 h_(cv[b:b + 1, h:h + 1]), seq_lens=lens[b:b + 1])
+        _check(h_(out[b:b + 1, h * G:(h + 1) * G]), ref, TOL_F32_OUT, f"long four-head shape, sequence {b} KV head {h}")
+
+
 def test_decode_is_bit_reproducible():
     # Histogram sums are integer, partial outputs are added in a fixed order: same inputs, same bits.
     args = _case(22, 2, 8, 2, 5000, 4096, 8, 8)
