@@ -363,7 +363,6 @@ __global__ __launch_bounds__(THREADS) void stream_kernel(
             }
         }
     };
-    (void)0;
 #pragma unroll
     for (int i = 0; i < TPT; ++i) {
         if (i < n_mine) {
@@ -441,7 +440,8 @@ __global__ __launch_bounds__(256) void out_kernel(const TD *__restrict__ DV, con
     constexpr int kVec = 16 / sizeof(TD);               // elements per 16-byte load
     constexpr int kLoads = ATOMS * (128 / kVec) / 256;  // 16-byte loads per thread
     constexpr int kElems = (NQ * ATOMS + 255) / 256;    // (query, atom) histogram entries per thread
-    constexpr int kEarly = 4;                           // chunks whose histograms are requested up front
+    constexpr int kEarly = 8;                           // chunks whose histograms are requested up front (one round trip
+                                                        // for the 8 chunks a long grouped-query context has)
     const int NV = snV * N, dc = 128 / snV;
     const int col0 = (n0 / N) * dc;
 
