@@ -131,6 +131,30 @@ int main(void)
     }
     if (!(ref > 0.0) || sqrt(err / ref) > 2e-3) { printf("decode: one cached token, relative error %g\n", sqrt(err / ref)); return 7; }
 
+    /* the entry point that allocates nothing (its scratch is a static device array of the library): same bits */
+    {
+        unsigned short hOutS[D];
+        CHECK_HIP(hipMemset(dOut, 0, 2 * D));
+        CHECK_CSR(csr_decode_attn_static(&q, dQ, dD, dIdx, dCoef, (const char *)dD + 2 * N * D, idxV, coefV,
+                                         (const int32_t *)dLens, dOut, NULL));
+        CHECK_HIP(hipDeviceSynchronize());
+        CHECK_HIP(hipMemcpy(hOutS, dOut, sizeof hOutS, hipMemcpyDeviceToHost));
+        if (memcmp(hOut, hOutS, sizeof hOut) != 0) { printf("csr_decode_attn_static differs from csr_decode_attn\n"); return 14; }
+    }
+    /* the encoder's indices all lie inside the dictionary; with a dictionary one atom shorter, those equal to N - 1 do not */
+    {
+        long long *dBad, hBad[2];
+        int top = 0;
+        CHECK_HIP(hipMalloc((void **)&dBad, 16));
+        CHECK_CSR(csr_check_codes(dIdx, CSR_I16, (int64_t)H * T * S, N, (int64_t *)dBad, NULL));
+        CHECK_CSR(csr_check_codes(dIdx, CSR_I16, (int64_t)H * T * S, N - 1, (int64_t *)(dBad + 1), NULL));
+        CHECK_HIP(hipDeviceSynchronize());
+        CHECK_HIP(hipMemcpy(hBad, dBad, sizeof hBad, hipMemcpyDeviceToHost));
+        for (int i = 0; i < H * T * S; ++i) top += hIdx[i] == N - 1;
+        if (hBad[0] != 0 || hBad[1] != top) { printf("csr_check_codes counted %lld and %lld (expected 0 and %d)\n", hBad[0], hBad[1], top); return 15; }
+        CHECK_HIP(hipFree(dBad));
+    }
+
     /* the same attention with the keys taken as coded before the rotary embedding: with a single cached token the
      * soft-max weight is 1 whatever the rotation, so the output is again that token's value */
     q.rope_base = 10000.0f; q.rope_layout = 0; q.rope_pos0 = 5;
@@ -176,6 +200,6 @@ int main(void)
     /* an invalid request comes back as a status with a message, not as a crash */
     e.s = 0;
     if (csr_encode(&e, dX, dD, dIdx, dCoef, dWs, need, NULL) != CSR_ERR_INVALID_ARG || csr_last_error()[0] == 0) return 8;
-    printf("c abi smoke ok: encode (three kernels), reconstruct, decode (plain and rotary keys; rel err %.2e)\n", sqrt(err / ref));
+    printf("c abi smoke ok: encode (three kernels), reconstruct, decode (workspace, static scratch, rotary keys; rel err %.2e), code check\n", sqrt(err / ref));
     return 0;
 }
