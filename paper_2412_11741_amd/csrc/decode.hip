@@ -7,24 +7,26 @@
 // so per cached token only its 2s-odd code pairs are read from HBM instead of 2d values.
 //
 // Four launches on the caller's stream:
-//   qd_kernel        qd[b][h][n][g] = scale * q[b][hg] . d^K_n  (matrix cores when both are fp16)
+//   score table      qd[b][h][n][g] = scale * q[b][hg] . d^K_n: qd_rows_kernel (few queries per KV head: a plain read
+//                    of the dictionary with packed dot products), qd_mfma_kernel (matrix cores), qd_kernel (fp32)
 //   stream_kernel    one workgroup per (token chunk, KV head x group slice, sequence), two passes over
 //                    its tokens.  Pass 1: the score table qd sits in LDS as [N][GB]; the K code stream
 //                    is read once, coalesced, and every thread keeps the scores of its tokens in
-//                    registers; one reduction gives the chunk's maximum.  Pass 2: the same LDS now
-//                    holds the histogram; p = exp(score - max) and the V code stream is scattered
-//                    into it.  The histogram is 64-bit fixed point (integer LDS atomics; the unit is a
-//                    power of two taken from the chunk's own value coefficients):
-//                    on this chip the LDS float atomic add is serialised lane by lane and runs about
+//                    registers; one reduction gives the chunk's maximum.  Pass 2 (finish_chunk in
+//                    decode_common.h): the same LDS now holds the histogram; p = exp(score - max) and the V
+//                    code stream is scattered into it with integer LDS atomics - fixed point, 32-bit
+//                    sign-split bins with a check after the scatter and a 64-bit form to fall back on: on
+//                    this chip the LDS float atomic add is serialised lane by lane and runs about
 //                    thirty times slower than the integer one, and integer sums are exact, so the
 //                    result does not depend on the order of the adds.  The chunk's histogram (as
 //                    fp32), maximum and sum go to scratch.
-//   out_kernel       combines chunk histograms with exp(m_c - M) weights and multiplies by a slice of
-//                    D_V for up to eight (sequence, query head) pairs of a KV head at once; one partial output
-//                    per slice goes to scratch (no float atomics anywhere: the result is the same
+//   D_V x histogram  combines chunk histograms with exp(m_c - M) weights and multiplies by a slice of D_V:
+//                    out_rows_kernel (one pair per KV head), out_kernel (up to eight (sequence, query head) pairs
+//                    of a KV head at once), out_mfma_kernel (up to 32, on the matrix cores in fp32); one partial
+//                    output per slice goes to scratch (no float atomics anywhere: the result is the same
 //                    bits on every run)
 //   finalize_kernel  adds the slices' partial outputs, divides by the softmax denominator and
-//                    stores in the output type.  (Folding this into out_kernel's last workgroup per
+//                    stores in the output type.  (Folding this into the last workgroup per
 //                    head was tried: the device-scope fences it needs cost more than the launch.)
 #include <atomic>
 #include <cmath>
@@ -409,6 +411,159 @@ __global__ __launch_bounds__(THREADS) void stream_kernel(
     }
     finish_chunk<GB, TI, TC, PV, CH, TPT, THREADS, VL>(smem_raw, red, sc, mx, n_mine, t0, t_end, code_row, tid, idxV,
                                                              coefV, N, sV, snV_arg, ml, part_hist, slot);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same product for many (sequence, query head) pairs per KV head (grouped queries, batches of sequences): a
+// 128-atom slice of D_V times the combined histograms of up to 32 pairs on the matrix cores, in fp32
+// (v_mfma_f32_32x32x2_f32: the histogram needs all 24 bits).  The slice is staged once per 32 pairs instead of once
+// per 8, and an LDS read feeds 32 x 32 multiply-adds instead of 4.  Pairs are the M rows (the histogram sits in LDS
+// atom-major, [atom][pair], so the 32 lanes of a k-step read one row), dimensions the N columns: a lane reads the
+// two neighbouring halves (dimensions 2n, 2n + 1 of a 64-dimension half) of an atom row as one 32-bit word and
+// feeds them to two accumulator tiles.  Wave w takes dimension half w & 1 and atom half w >> 1 of the slice; the two
+// atom halves meet in LDS.  fp16 dictionary, whole-vector value codes, N a multiple of 128.
+// kBatch: chunk histograms in flight together (4: contexts of at most 4 chunks, fewer registers; 8: long ones).
+constexpr int kOutMfmaPairs = 32;
+template <int kBatch>
+__global__ __launch_bounds__(256) void out_mfma_kernel(const __half *__restrict__ DV, const float *__restrict__ part_hist,
+                                                       const float *__restrict__ part_ml, float *__restrict__ part_out,
+                                                       int32_t B, int32_t Hkv, int32_t G, int32_t GB, int32_t N,
+                                                       int32_t nchunks)
+{
+    constexpr int ATOMS = 128, P = kOutMfmaPairs, kPad = P + 1;
+    // the D_V slice as fp16 [atom][dimension]; afterwards the second atom half's partial result, fp32 [pair][dimension]
+    __shared__ __attribute__((aligned(16))) unsigned char dv_raw[ATOMS * 128 * sizeof(__half)];
+    __shared__ float hist_t[ATOMS][kPad];   // combined histogram, [atom][pair]; one word of padding per row
+    __shared__ float w_s[P][kBatch > 4 ? kMaxChunks : 4];   // chunk weights
+    __half(*dv_s)[128] = reinterpret_cast<__half(*)[128]>(dv_raw);
+    float(*red_s)[128] = reinterpret_cast<float(*)[128]>(dv_raw);
+    static_assert(P * 128 * sizeof(float) <= sizeof(dv_raw), "partial result fits the slice's space");
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n0 = blockIdx.x * ATOMS;
+    const int h = blockIdx.y;
+    const int ngs = G / GB;
+    const int nslices = gridDim.x;
+    const int BG = B * G;
+    const int bg0 = blockIdx.z * P;
+    const int nbg = min(P, BG - bg0);
+    constexpr int kLoads = ATOMS * 16 / 256;      // 16-byte pieces of the slice per thread
+    constexpr int kQuads = P * ATOMS / 4 / 256;   // (pair, four atoms) histogram entries per thread
+
+    uint4 dv_r[kLoads];
+#pragma unroll
+    for (int i = 0; i < kLoads; ++i) {
+        const int e = i * 256 + tid;
+        dv_r[i] = *reinterpret_cast<const uint4 *>(DV + ((int64_t)h * N + n0 + e / 16) * 128 + (e % 16) * 8);
+    }
+    // quad i of this thread: pair q / 32, atoms 4 (q % 32) .. + 3 with q = i * 256 + tid
+    const float *ph[kQuads];
+#pragma unroll
+    for (int i = 0; i < kQuads; ++i) {
+        const int q = i * 256 + tid;
+        const int bgl = q / (ATOMS / 4), a4 = (q % (ATOMS / 4)) * 4;
+        ph[i] = nullptr;
+        if (bgl < nbg) {
+            const int b = (bg0 + bgl) / G, g = (bg0 + bgl) % G;
+            ph[i] = part_hist + ((((int64_t)b * Hkv + h) * ngs + g / GB) * nchunks) * (int64_t)N * GB +
+                    (int64_t)(g % GB) * N + (n0 + a4);
+        }
+    }
+    auto request = [&](float4 (&v)[kQuads][kBatch], int c0) {
+#pragma unroll
+        for (int i = 0; i < kQuads; ++i)
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u)
+                v[i][u] = (ph[i] && c0 + u < nchunks) ? *reinterpret_cast<const float4 *>(ph[i] + (int64_t)(c0 + u) * N * GB)
+                                                      : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    };
+    float4 first[kQuads][kBatch];
+    request(first, 0);
+    if (tid < nbg) {
+        const int b = (bg0 + tid) / G, g = (bg0 + tid) % G;
+        const int gs = g / GB, gg = g % GB;
+        const float *ml = part_ml + ((((int64_t)b * Hkv + h) * ngs + gs) * nchunks) * (2 * GB);
+        float M = -INFINITY;
+        for (int c = 0; c < nchunks; ++c) M = fmaxf(M, ml[c * 2 * GB + 2 * gg]);
+        for (int c = 0; c < nchunks; ++c) {
+            const float m = ml[c * 2 * GB + 2 * gg];
+            w_s[tid][c] = (m > -INFINITY) ? __expf(m - M) : 0.0f;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < kLoads; ++i) {
+        const int e = i * 256 + tid;
+        *reinterpret_cast<uint4 *>(&dv_s[e / 16][(e % 16) * 8]) = dv_r[i];
+    }
+    __syncthreads();
+    float4 hacc[kQuads];
+#pragma unroll
+    for (int i = 0; i < kQuads; ++i) hacc[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    // a chunk without tokens has weight 0 and a histogram that was never written: skipped, not multiplied
+    auto combine = [&](const float4 (&v)[kQuads][kBatch], int c0) {
+#pragma unroll
+        for (int i = 0; i < kQuads; ++i) {
+            const int bgl = (i * 256 + tid) / (ATOMS / 4);
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                const float w = (ph[i] && c0 + u < nchunks) ? w_s[bgl][c0 + u] : 0.0f;
+                if (w > 0.0f) {
+                    hacc[i].x = fmaf(w, v[i][u].x, hacc[i].x); hacc[i].y = fmaf(w, v[i][u].y, hacc[i].y);
+                    hacc[i].z = fmaf(w, v[i][u].z, hacc[i].z); hacc[i].w = fmaf(w, v[i][u].w, hacc[i].w);
+                }
+            }
+        }
+    };
+    combine(first, 0);
+    if constexpr (kBatch > 4) {   // launched only then: more chunks than one batch
+        for (int c0 = kBatch; c0 < nchunks; c0 += kBatch) {
+            request(first, c0);
+            combine(first, c0);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < kQuads; ++i) {
+        const int q = i * 256 + tid;
+        const int bgl = q / (ATOMS / 4), a4 = (q % (ATOMS / 4)) * 4;
+        hist_t[a4][bgl] = hacc[i].x; hist_t[a4 + 1][bgl] = hacc[i].y;
+        hist_t[a4 + 2][bgl] = hacc[i].z; hist_t[a4 + 3][bgl] = hacc[i].w;
+    }
+    __syncthreads();
+
+    const int col = lane & 31, kk = lane >> 5;
+    const int dh = wave & 1, ah = wave >> 1;
+    qd_floatx16 acc0, acc1;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc0[r] = acc1[r] = 0.0f;
+#pragma unroll 8
+    for (int st = 0; st < ATOMS / 4; ++st) {
+        const int k = ah * (ATOMS / 2) + 2 * st + kk;
+        const float a = hist_t[k][col];
+        const __half2 d2 = *reinterpret_cast<const __half2 *>(&dv_s[k][64 * dh + 2 * col]);
+        const float2 df = __half22float2(d2);
+        acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, df.x, acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, df.y, acc1, 0, 0, 0);
+    }
+    __syncthreads();  // every wave is done with the slice: its space takes the second atom half's result
+    // accumulator r of a lane: pair 8 (r / 4) + 4 kk + r % 4, dimensions 64 dh + 2 col (acc0) and + 1 (acc1)
+    if (ah == 1) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int pr = 8 * (r >> 2) + 4 * kk + (r & 3);
+            *reinterpret_cast<float2 *>(&red_s[pr][64 * dh + 2 * col]) = make_float2(acc0[r], acc1[r]);
+        }
+    }
+    __syncthreads();
+    if (ah == 0) {
+        float *dst = part_out + (((int64_t)h * nslices + blockIdx.x) * BG + bg0) * 128;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int pr = 8 * (r >> 2) + 4 * kk + (r & 3);
+            if (pr < nbg) {
+                const float2 o = *reinterpret_cast<const float2 *>(&red_s[pr][64 * dh + 2 * col]);
+                *reinterpret_cast<float2 *>(dst + (int64_t)pr * 128 + 64 * dh + 2 * col) = make_float2(acc0[r] + o.x, acc1[r] + o.y);
+            }
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -928,7 +1083,15 @@ hipError_t launch_decode(const DecodeArgs &a, const DecodePlan &p)
 #define CSR_OUTR(NQ)                                                                                              \
     hipLaunchKernelGGL((out_rows_kernel<NQ>), grid, dim3(256), 0, a.stream, (const __half *)a.DV, hist, ml, acc, a.B, \
                        a.Hkv, a.G, p.GB, a.N, p.nchunks)
-        if (a.dict16 && a.snV == 1 && nq == 1) {   // measured faster for one pair per KV head only
+        if (a.dict16 && a.snV == 1 && BG >= 16 && a.N % 128 == 0) {   // many pairs per KV head: matrix cores
+            const dim3 mgrid((unsigned)nslices, (unsigned)a.Hkv, (unsigned)((BG + kOutMfmaPairs - 1) / kOutMfmaPairs));
+            if (p.nchunks <= 4)
+                hipLaunchKernelGGL(out_mfma_kernel<4>, mgrid, dim3(256), 0, a.stream, (const __half *)a.DV, hist, ml, acc,
+                                   a.B, a.Hkv, a.G, p.GB, a.N, p.nchunks);
+            else
+                hipLaunchKernelGGL(out_mfma_kernel<8>, mgrid, dim3(256), 0, a.stream, (const __half *)a.DV, hist, ml, acc,
+                                   a.B, a.Hkv, a.G, p.GB, a.N, p.nchunks);
+        } else if (a.dict16 && a.snV == 1 && nq == 1) {   // measured faster for one pair per KV head only
             CSR_OUTR(1);
         } else if (a.dict16) { CSR_OUT_NQ(__half, kOutAtomsF16) } else { CSR_OUT_NQ(float, kOutAtomsF32) }
 #undef CSR_OUTR
