@@ -42,7 +42,7 @@ using namespace dec;
 constexpr int kOutAtomsF16 = 128;     // atoms of D_V per out_kernel workgroup, fp16 dictionary
 constexpr int kOutAtomsF32 = 64;      // same, fp32 dictionary (the slice sits in LDS in its own type)
 constexpr int kQdAtoms = 64;          // atoms of D_K per qd_kernel workgroup
-constexpr int kQdTiles = 2;           // 32-atom tiles per wave of qd_mfma_kernel
+constexpr int kQdTiles = 2;           // 32-atom tiles per wave of qd_mfma_kernel (1 where that leaves CUs without a workgroup)
 constexpr int kQTile = 32;            // queries staged in LDS at a time by qd_kernel
 
 // ---------------------------------------------------------------------------------------------
@@ -123,6 +123,7 @@ __global__ __launch_bounds__(256) void qd_kernel(const TQ *__restrict__ q, const
 typedef _Float16 qd_half8 __attribute__((ext_vector_type(8)));
 typedef float qd_floatx16 __attribute__((ext_vector_type(16)));
 
+template <int TILES>
 __global__ __launch_bounds__(256) void qd_mfma_kernel(const __half *__restrict__ q, const __half *__restrict__ DK,
                                                       float *__restrict__ qd, int32_t B, int32_t Hq, int32_t Hkv,
                                                       int32_t G, int32_t GB, int32_t N, int32_t sn, float scale)
@@ -138,12 +139,12 @@ __global__ __launch_bounds__(256) void qd_mfma_kernel(const __half *__restrict__
     const int NT = sn * N;       // table entries
     const int dc = 128 / sn;     // dimensions per chunk
     const int nf = dc / 16;      // MFMA steps
-    // a wave owns kQdTiles consecutive 32-atom tiles; all their rows are requested before the first product
-    const int n_first = (blockIdx.x * 4 + wave) * 32 * kQdTiles;
+    // a wave owns TILES consecutive 32-atom tiles; all their rows are requested before the first product
+    const int n_first = (blockIdx.x * 4 + wave) * 32 * TILES;
     if (n_first >= NT) return;
-    qd_half8 bfrag[kQdTiles][8];
+    qd_half8 bfrag[TILES][8];
 #pragma unroll
-    for (int t = 0; t < kQdTiles; ++t) {
+    for (int t = 0; t < TILES; ++t) {
         const int v = min(n_first + t * 32 + col, NT - 1);  // row v of [Hkv][sn * N][dc]
         const __half *row = DK + ((int64_t)h * NT + v) * dc + hf * 8;
         const int j_first = (min(n_first + t * 32, NT - 1) / N) * nf;  // the tile's chunk (uniform over the wave)
@@ -168,7 +169,7 @@ __global__ __launch_bounds__(256) void qd_mfma_kernel(const __half *__restrict__
             afrag[j] = *reinterpret_cast<const qd_half8 *>(&raw);
         }
 #pragma unroll
-        for (int t = 0; t < kQdTiles; ++t) {
+        for (int t = 0; t < TILES; ++t) {
             const int v = n_first + t * 32 + col;
             qd_floatx16 acc;
 #pragma unroll
@@ -1044,9 +1045,16 @@ hipError_t launch_decode(const DecodeArgs &a, const DecodePlan &p)
             if (BG <= 1) CSR_QDR(1); else if (BG <= 2) CSR_QDR(2); else if (BG <= 4) CSR_QDR(4); else CSR_QDR(8);
 #undef CSR_QDR
         } else if (a.q16 && a.dict16) {
-            const dim3 mgrid((unsigned)((a.snK * a.N + 128 * kQdTiles - 1) / (128 * kQdTiles)), (unsigned)a.Hkv);
-            hipLaunchKernelGGL(qd_mfma_kernel, mgrid, dim3(256), 0, a.stream, (const __half *)a.q,
-                               (const __half *)a.DK, qd, a.B, a.Hq, a.Hkv, a.G, p.GB, a.N, a.snK, a.scale);
+            const int NT = a.snK * a.N;
+            if ((int64_t)((NT + 128 * kQdTiles - 1) / (128 * kQdTiles)) * a.Hkv >= 256) {
+                const dim3 mgrid((unsigned)((NT + 128 * kQdTiles - 1) / (128 * kQdTiles)), (unsigned)a.Hkv);
+                hipLaunchKernelGGL(qd_mfma_kernel<kQdTiles>, mgrid, dim3(256), 0, a.stream, (const __half *)a.q,
+                                   (const __half *)a.DK, qd, a.B, a.Hq, a.Hkv, a.G, p.GB, a.N, a.snK, a.scale);
+            } else {   // few KV heads: one tile per wave, twice the workgroups
+                const dim3 mgrid((unsigned)((NT + 127) / 128), (unsigned)a.Hkv);
+                hipLaunchKernelGGL(qd_mfma_kernel<1>, mgrid, dim3(256), 0, a.stream, (const __half *)a.q,
+                                   (const __half *)a.DK, qd, a.B, a.Hq, a.Hkv, a.G, p.GB, a.N, a.snK, a.scale);
+            }
         } else if (a.q16) CSR_QD(__half, float);
         else if (a.dict16) CSR_QD(float, __half);
         else CSR_QD(float, float);
