@@ -218,6 +218,25 @@ def test_four_query_heads_long_context_shape_ragged_lengths_and_a_hot_atom():
         _check(h_(out[b:b + 1, h * G:(h + 1) * G]), ref, TOL_F32_OUT, f"long four-head shape, sequence {b} KV head {h}")
 
 
+@pytest.mark.parametrize("B,Hq,Hkv,T,N", [
+    (4, 4, 1, 20000, 256),     # 16 pairs per KV head, 20 chunks: batches of 8 chunk histograms with a tail of 4
+    (17, 2, 2, 3000, 128),     # 17 pairs: one block of pairs with 15 empty rows, a single 128-atom slice
+    (33, 1, 1, 1500, 384),     # 33 pairs: a second block with one pair
+    (9, 8, 2, 2600, 1024),     # 36 pairs per KV head from groups of four query heads
+])
+def test_many_pairs_per_kv_head_take_the_matrix_core_product(B, Hq, Hkv, T, N):
+    # With 16 or more (sequence, query head) pairs per KV head the D_V product runs on the matrix cores in fp32;
+    # some sequences are empty or short (their chunks have weight zero and histograms that were never written).
+    args = _case(28, B, Hq, Hkv, T, N, 8, 8)
+    lens = np.full(B, T, dtype=np.int32)
+    lens[1] = 0
+    lens[2] = 1
+    lens[B - 1] = T // 2 + 3
+    out = _run(*args, seq_lens=lens, out_dtype=torch.float32)
+    assert np.all(out[1] == 0)
+    _check(out, oracle.decode_attn(*args, seq_lens=lens), TOL_F32_OUT, f"matrix-core D_V product, {B * Hq // Hkv} pairs per KV head")
+
+
 def test_decode_is_bit_reproducible():
     # Histogram sums are integer, partial outputs are added in a fixed order: same inputs, same bits.
     args = _case(22, 2, 8, 2, 5000, 4096, 8, 8)
