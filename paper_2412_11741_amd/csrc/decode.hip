@@ -281,8 +281,10 @@ __global__ __launch_bounds__(THREADS) void stream_kernel(
     float *red = reinterpret_cast<float *>(smem_raw + tab_bytes);
 
     const int tid = threadIdx.x;
-    const int c = blockIdx.x;
-    const int h = blockIdx.y / ngs, gs = blockIdx.y % ngs;
+    // (KV head, group slice) is the fastest grid dimension: workgroups are dealt to the 8 XCDs round-robin in that
+    // order, so the chunks of one (sequence, KV head) - which load the same score table - tend to share an L2
+    const int c = blockIdx.y;
+    const int h = blockIdx.x / ngs, gs = blockIdx.x % ngs;
     const int b = blockIdx.z;
 
     int64_t len = T;
@@ -917,7 +919,7 @@ hipError_t launch_stream_t(const DecodeArgs &a, const DecodePlan &p, float *qd, 
         if (e != hipSuccess) return e;
         attr_set[dev].store(true, std::memory_order_release);
     }
-    const dim3 grid((unsigned)p.nchunks, (unsigned)(a.Hkv * p.ngs), (unsigned)a.B);
+    const dim3 grid((unsigned)(a.Hkv * p.ngs), (unsigned)p.nchunks, (unsigned)a.B);
     hipLaunchKernelGGL(kern, grid, dim3(THREADS), p.lds_bytes, a.stream, qd, (const TI *)a.idxK,
                        (const TC *)a.coefK, (const TI *)a.idxV, (const TC *)a.coefV, a.seq_lens, hist, ml,
                        a.Hkv, p.ngs, a.T, a.N, a.sK, a.sV, a.snK, a.snV, p.chunk_tokens, p.nchunks,
