@@ -296,7 +296,13 @@ __device__ __forceinline__ void finish_chunk(unsigned char *smem_raw, float *red
     static_assert(WAVES <= 16 && GB <= 4, "layout of the reduction scratch");
     static_assert(VL == 0 || (sizeof(TI) == 2 && sizeof(TC) == 2 && PV == 8 && !CH), "16-byte code vectors");
     const int snV = CH ? snV_arg : 1;
-    uint32_t *h32 = reinterpret_cast<uint32_t *>(smem_raw);                  // [GB][NV][2]: |sum| of c > 0, of c < 0
+    // 32-bit form: |sum| of c > 0 and of c < 0 per (query head, atom).  [g][n][sign]; for an even number of heads
+    // [g / 2][n][sign][g % 2]: the bins of two heads side by side, so that ONE 64-bit add serves both (a loop of 16
+    // ds_add_u64 takes 8 % less LDS time than one of 32 ds_add_u32, and the second head needs no address).  A bin that
+    // wraps then carries into its neighbour's - which the check of the totals finds like any other wrap (the sum of
+    // all bins is off by 2^32 - 1).
+    constexpr bool PAIRED = GB % 2 == 0;
+    uint32_t *h32 = reinterpret_cast<uint32_t *>(smem_raw);
     unsigned long long *h64 = reinterpret_cast<unsigned long long *>(smem_raw);  // wide form: [GB][NV]
     uint32_t *redw = reinterpret_cast<uint32_t *>(red);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -441,10 +447,19 @@ __device__ __forceinline__ void finish_chunk(unsigned char *smem_raw, float *red
 #pragma unroll
                                     for (int g = 0; g < GB; ++g) atomicAdd(&h64[g * NV + base + id[j]], to_fixed(pp[g] * cf[j]));
                                 } else {
-                                    uint32_t *cell = h32 + 2 * (base + id[j]) + (__float_as_uint(cf[j]) >> 31);
+                                    const int cell = 2 * (base + id[j]) + (int)(__float_as_uint(cf[j]) >> 31);
+                                    if constexpr (PAIRED) {
 #pragma unroll
-                                    for (int g = 0; g < GB; ++g)
-                                        atomicAdd(cell + 2 * g * NV, __float2uint_rz(fmaf(pp[g], ac, 0.5f)));
+                                        for (int g = 0; g < GB; g += 2) {
+                                            const uint32_t a0 = __float2uint_rz(fmaf(pp[g], ac, 0.5f));
+                                            const uint32_t a1 = __float2uint_rz(fmaf(pp[g + 1], ac, 0.5f));
+                                            atomicAdd(h64 + cell + g * NV, ((unsigned long long)a1 << 32) | a0);
+                                        }
+                                    } else {
+#pragma unroll
+                                        for (int g = 0; g < GB; ++g)
+                                            atomicAdd(h32 + cell + 2 * g * NV, __float2uint_rz(fmaf(pp[g], ac, 0.5f)));
+                                    }
                                 }
                                 // one pair after the other (the next pair's products depend on this statement), so
                                 // that the values of all 8 x GB adds are not computed ahead and held in registers
@@ -510,7 +525,13 @@ __device__ __forceinline__ void finish_chunk(unsigned char *smem_raw, float *red
 #pragma unroll
                 for (int u = 0; u < U; ++u) {   // past the end: bin 0, ignored below (no load under a branch)
                     const int e = e0 + u * THREADS;
-                    pn[u] = *reinterpret_cast<const uint2 *>(h32 + 2 * (g * NV + (e < NV ? e : 0)));
+                    const int ec = e < NV ? e : 0;
+                    if constexpr (PAIRED) {
+                        const uint32_t *c2 = h32 + 4 * ((g >> 1) * NV + ec) + (g & 1);
+                        pn[u] = make_uint2(c2[0], c2[2]);
+                    } else {
+                        pn[u] = *reinterpret_cast<const uint2 *>(h32 + 2 * (g * NV + ec));
+                    }
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
