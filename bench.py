@@ -40,12 +40,12 @@ PEAK_HBM_GBS = 8000.0           # MI355X HBM3E peak
 # FETCH_SIZE / WRITE_SIZE runs (each scaled by what the counter reads for a 1 GiB copy): hardware counters cannot be
 # read from inside this process, so `traffic` in the JSON line is not a measurement of this run; `traffic_source`
 # names the summary under profiles/ that holds the commands and the raw counts.
-PMC_TRAFFIC_BYTES = {("llama7b_layer", "mfma"): (720.0e6 + 131.0e6, "profiles/encode_mfma_kernel_llama7b_layer.txt")}
+PMC_TRAFFIC_BYTES = {("llama7b_layer", "mfma"): (719.4e6 + 131.0e6, "profiles/encode_mfma_kernel_llama7b_layer.txt")}
 # The same for one csr_decode_attn call (its launches added up), per workload.
 PMC_DECODE_TRAFFIC_BYTES = {
     "llama7b_layer": (79.0e6 + 3.2e6, "profiles/decode_kernels_llama7b_layer.txt"),
     "long_context": (689.5e6 + 16.8e6, "profiles/decode_kernels_long_context_gqa.txt"),
-    "gqa_llama3_8b": (599.0e6 + 42.0e6, "profiles/decode_kernels_long_context_gqa.txt")}
+    "gqa_llama3_8b": (598.5e6 + 42.0e6, "profiles/decode_kernels_long_context_gqa.txt")}
 
 
 def recorded_traffic(table, key):
