@@ -142,3 +142,51 @@ def test_rotary_key_decode_on_random_shapes(seed):
         if lens[b] == 0:
             assert np.all(out[b] == 0)
     parity.assert_decode_close(out[lens > 0], ref[lens > 0], 2e-3, f"seed {seed}")
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_whole_vector_decode_on_random_large_shapes(seed):
+    # Batches, KV heads, query groups, context lengths (up to 66000 tokens), dictionary sizes, pairs per code, storage
+    # types and ragged lengths drawn at random: between them the cases reach every launch shape of the streaming
+    # kernel and every form of the D_V product.  Codes are drawn on the GPU; the oracle recomputes sampled
+    # (sequence, KV head) pairs from the bits copied back.
+    rng = np.random.default_rng(7000 + seed)
+    G = int(rng.choice([1, 1, 2, 4, 4, 8]))
+    Hkv = int(rng.choice([1, 2, 4, 8, 8, 16]))
+    B = int(rng.choice([1, 2, 4, 8, 8, 16, 33]))
+    s = int(rng.choice([8, 8, 16, 4, 3, 12]))
+    N = int(rng.choice([128, 256, 1024, 4096, 4096, 2048, 8192 if G == 1 else 4096, 96, 4000]))
+    T = int(rng.choice([40000, 66000, 33000, 20000])) if rng.random() < 0.4 else int(rng.choice([1, 17, 1024, 1025, 5000, 9000, 16385]))
+    while B * Hkv * T * s > 1.0e8:
+        B = max(1, B // 2)
+        if B == 1:
+            break
+    f32 = rng.random() < 0.15
+    cdt, idt = (torch.float32, torch.int32) if f32 else (torch.float16, torch.int16)
+    odt = torch.float32 if rng.random() < 0.5 else torch.float16
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(7000 + seed)
+    d = 128
+    unit = lambda *sh: (lambda a: (a / a.norm(dim=-1, keepdim=True)).to(cdt))(torch.randn(*sh, device=dev, generator=gen))
+    idx = lambda: torch.randint(0, N, (B, Hkv, T, s), device=dev, generator=gen, dtype=torch.int32).to(idt)
+    coef = lambda: (torch.randn(B, Hkv, T, s, device=dev, generator=gen) * 3).to(cdt)
+    q, DK, DV = torch.randn(B, Hkv * G, d, device=dev, generator=gen).to(cdt), unit(Hkv, N, d), unit(Hkv, N, d)
+    ik, ck, iv, cv = idx(), coef(), idx(), coef()
+    lens = None
+    if rng.random() < 0.6:
+        lens = rng.integers(0, T + 1, size=B).astype(np.int32)
+        lens[rng.integers(0, B)] = T
+    what = f"B {B} Hkv {Hkv} G {G} T {T} N {N} s {s} {'f32' if f32 else 'f16'} codes, {'f32' if odt == torch.float32 else 'f16'} out"
+    print("[random decode]", what, flush=True)
+    out = csr.csr_decode_attn(q, DK, ik, ck, DV, iv, cv, seq_lens=None if lens is None else torch.from_numpy(lens).to(dev),
+                              out_dtype=odt)
+    torch.cuda.synchronize()
+    h_ = lambda t: t.float().cpu().numpy() if t.dtype == torch.float16 else t.cpu().numpy()
+    picks = {(int(rng.integers(0, B)), int(rng.integers(0, Hkv))) for _ in range(3)} | {(0, 0), (B - 1, Hkv - 1)}
+    for b, h in sorted(picks):
+        ref = oracle.decode_attn(h_(q[b:b + 1, h * G:(h + 1) * G]), h_(DK[h:h + 1]), ik[b:b + 1, h:h + 1].cpu().numpy(),
+                                 h_(ck[b:b + 1, h:h + 1]), h_(DV[h:h + 1]), iv[b:b + 1, h:h + 1].cpu().numpy(),
+                                 h_(cv[b:b + 1, h:h + 1]), seq_lens=None if lens is None else lens[b:b + 1])
+        parity.assert_decode_close(h_(out[b:b + 1, h * G:(h + 1) * G]), ref, 1e-3 if odt == torch.float32 else 2e-3,
+                                   f"{what}, sequence {b} KV head {h}")
